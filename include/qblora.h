@@ -1,0 +1,198 @@
+/*
+ * qblora.h -- C ABI of the MI355X (gfx950) adapted quantized linear layer.
+ *
+ * The layer is the Q-BLoRA / QA-BLoRA one: a frozen 4-bit block-wise quantized
+ * base weight (the triplet (w^, alpha, beta) of Eq. 1) is dequantized and
+ * contracted with bf16 activations, and the balanced adapter of Sec. 3.2
+ * (AvgPool(lambda) on the input, a rank lambda*D_rank product A B,
+ * repeat_interleave(lambda) on the output, scaled by s) is added.
+ *
+ * General conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller unless stated
+ *     otherwise.  The library never allocates, frees or keeps a pointer after
+ *     the call returns; scratch memory is the caller's `workspace`.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream); no call synchronises the device.
+ *   - Storage layout of the base weight is [d_out, d_in] row-major (the paper
+ *     writes W as D_in x D_out with y = W^T x; Sec. 3.1), so Y = X W~^T.
+ *   - A quantization block is `block` contiguous input indices k inside one
+ *     output row n.  Block b of row n has index n*(d_in/block)+b.
+ *   - 4-bit codes are packed two per byte: element (n,k) is in byte
+ *     (n*d_in+k)/2, even k in the low nibble.
+ *   - bf16 tensors are raw 16-bit patterns (qblora_bf16).
+ *   - Return value: QBLORA_OK (0) or a negative QBLORA_ERR_* code.  Arguments
+ *     are validated on the host before anything is enqueued; an invalid call
+ *     enqueues nothing.  No entry point throws or aborts.
+ */
+#ifndef QBLORA_H
+#define QBLORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef uint16_t qblora_bf16;
+
+enum {
+    QBLORA_OK = 0,
+    QBLORA_ERR_NULL = -1,        /* a required pointer is NULL */
+    QBLORA_ERR_SHAPE = -2,       /* a size is non-positive or not divisible as the method requires */
+    QBLORA_ERR_UNSUPPORTED = -3, /* valid by the paper, not implemented by these kernels */
+    QBLORA_ERR_WORKSPACE = -4,   /* workspace missing or smaller than *_workspace_bytes() */
+    QBLORA_ERR_ALIGNMENT = -5,   /* beta-shift merge asked for tiles that do not cover whole blocks */
+    QBLORA_ERR_LAUNCH = -6       /* the HIP runtime refused a launch */
+};
+
+enum { QBLORA_QUANT_ABSMAX_CODEBOOK = 0, QBLORA_QUANT_MINMAX_INT4 = 1 };
+enum { QBLORA_SCALES_FP32 = 0, QBLORA_SCALES_E4M3_GROUPED = 1 };
+enum { QBLORA_MERGE_BETA_SHIFT = 0, QBLORA_MERGE_REQUANT_MINMAX = 1 };
+
+/*
+ * The quantized weight: the triplet (w^, alpha, beta) of Eq. 1, w~ = alpha*c[w^] + beta.
+ * The struct itself lives in host memory; the pointers in it are device pointers.
+ *   codebook   16 ascending code values c_j (host values, copied by value into launches).
+ *              Absmax/codebook quantizer (the NF4-style base of Sec. 3.2): any 16 ascending
+ *              values in [-1,1].  Min-max INT4: 0,1,...,15.
+ *   codes      [d_out*d_in/2] bytes.
+ *   scales     alpha, fp32 [d_out*d_in/block].
+ *   beta       beta,  fp32 [d_out*d_in/block], or NULL meaning beta = 0 (absmax quantizer).
+ *   scale_mode QBLORA_SCALES_FP32: `scales` is what consumers read.
+ *              QBLORA_SCALES_E4M3_GROUPED: consumers reconstruct the block scale i as
+ *              fma(e4m3(scale_codes[i]), scale_step[i/scale_group], scale_mid[i/scale_group]);
+ *              `scales` is then only written by the quantizer (the unquantized absmax values
+ *              the codes were chosen against) and may be NULL for consumers.
+ *   scale_codes [d_out*d_in/block] bytes, OCP E4M3 bit patterns.
+ *   scale_step, scale_mid  fp32 [ceil(nblocks/scale_group)].
+ */
+typedef struct qblora_qweight {
+    int32_t d_out;
+    int32_t d_in;
+    int32_t block;        /* 64 */
+    int32_t scale_mode;
+    int32_t scale_group;  /* 256 when scale_mode = E4M3_GROUPED, ignored otherwise */
+    float codebook[16];
+    uint8_t* codes;
+    float* scales;
+    float* beta;
+    uint8_t* scale_codes;
+    float* scale_step;
+    float* scale_mid;
+} qblora_qweight;
+
+/*
+ * The balanced adapter (Sec. 3.2): A is [d_in/lambda1, R], B is [R, d_out/lambda2], both bf16
+ * row-major; Q-BLoRA uses lambda1 = lambda2 = lambda and R = lambda*D_rank.  `s` is the
+ * non-learned scaling of Sec. 3.1 and multiplies the adapter term only.
+ * A = NULL, B = NULL or R = 0 means "no adapter" (base layer).
+ */
+typedef struct qblora_adapter {
+    int32_t lambda1;
+    int32_t lambda2;
+    int32_t R;
+    float s;
+    const qblora_bf16* A;
+    const qblora_bf16* B;
+} qblora_adapter;
+
+/*
+ * Block-wise quantization of an fp32 weight (Eq. 1; Sec. 3.1 for the min-max and absmax
+ * factors; Sec. 3.2 for the codebook base).
+ *   W         fp32 [d_out, d_in], device.
+ *   quantizer QBLORA_QUANT_ABSMAX_CODEBOOK: alpha = max|w| of the block, beta = 0,
+ *             code = #{ j : w > ((c_j + c_{j+1}) * 0.5) * alpha } (nearest codebook entry,
+ *             a value on a threshold takes the lower index).
+ *             QBLORA_QUANT_MINMAX_INT4: alpha = (max-min)/15, beta = min,
+ *             code = rint((w - min) * (15/(max-min))) (ties to even), all codes 0 when max = min;
+ *             `codebook` is ignored and out->codebook is set to 0..15; out->beta must be non-NULL.
+ *   scale_mode E4M3_GROUPED (absmax quantizer only): after the codes are chosen against the
+ *             fp32 absmax scales, groups of 256 consecutive scales are re-encoded as
+ *             mid = (min+max)*0.5, step = max|scale - mid|/448, code = E4M3 nearest-even of
+ *             (scale - mid)/step saturating at 448 (step = 0 and codes 0 when all equal).
+ *   out       host struct whose device pointers the caller has filled in (codes, scales, and
+ *             beta or scale_codes/scale_step/scale_mid as the mode needs); the call fills the
+ *             scalar fields and the codebook and overwrites the device buffers.
+ * All fp32 arithmetic is single IEEE operations in the order written above, so the outputs
+ * are reproducible bit for bit.  d_in must be a multiple of `block`; block must be 64.
+ */
+int qblora_quantize_blockwise(const float* W, int32_t d_out, int32_t d_in, int32_t block,
+                              int32_t quantizer, const float* codebook /* host, 16 values */,
+                              int32_t scale_mode, qblora_qweight* out, void* stream);
+
+/*
+ * Dequantize (Eq. 1) to the 16-bit compute weight: Wt[n,k] = bf16(c[code]*alpha) or
+ * bf16(fma(c[code], alpha, beta)), fp32 arithmetic then round-to-nearest-even.  This is the
+ * weight the forward/backward kernels build on the fly in LDS; the standalone call exists
+ * for inspection and tests.  Wt is bf16 [d_out, d_in], device.
+ */
+int qblora_dequantize_bf16(const qblora_qweight* qw, qblora_bf16* Wt, void* stream);
+
+/* Bytes of workspace the forward / backward calls need for T tokens (0 is possible). */
+size_t qblora_linear_fwd_workspace_bytes(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T);
+size_t qblora_linear_bwd_workspace_bytes(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T);
+
+/*
+ * Adapted forward (Sec. 3.2, Alg. 1 qblora_forward, scaling on the adapter term only):
+ *   Y[t,n] = sum_k X[t,k] * w~[n,k]  +  s * V[t, n / lambda2],
+ *   V = (AvgPool_lambda1(X) A) B.
+ *   X bf16 [T, d_in]; Y bf16 [T, d_out] (fully overwritten); accumulation in fp32.
+ *   workspace: device scratch of at least qblora_linear_fwd_workspace_bytes(), 256-byte aligned.
+ * Requires d_in % 64 == 0, d_out % 64 == 0, d_in % lambda1 == 0, d_out % lambda2 == 0,
+ * R % 8 == 0.  T = 0 is a no-op.
+ */
+int qblora_linear_fwd(const qblora_qweight* qw, const qblora_adapter* ad, const qblora_bf16* X, int64_t T,
+                      qblora_bf16* Y, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Backward of the forward above with respect to X, A and B (the base weight is frozen, Sec. 3.1):
+ *   dV[t,j] = s * sum_{i<lambda2} dY[t, lambda2*j+i];  dB = U^T dV;  dU = dV B^T;
+ *   dA = P^T dU;  dX[t,k] = sum_n dY[t,n] * w~[n,k] + (1/lambda1) * (dU A^T)[t, k / lambda1],
+ * with P = AvgPool_lambda1(X), U = P A recomputed from X.
+ *   dX bf16 [T, d_in]; dA fp32 [d_in/lambda1, R]; dB fp32 [R, d_out/lambda2]; all fully
+ *   overwritten (not accumulated).  dA/dB may be NULL together (then only dX is produced);
+ *   dX may be NULL (then only dA/dB).  Same shape requirements as the forward.
+ */
+int qblora_linear_bwd(const qblora_qweight* qw, const qblora_adapter* ad, const qblora_bf16* X,
+                      const qblora_bf16* dY, int64_t T, qblora_bf16* dX, float* dA, float* dB,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Tile matrix of a two-matrix adapter, H = A B, fp32 [d_in/lambda1, d_out/lambda2] (Alg. 1
+ * get_delta_weight before the expansion; the equivalent full-size delta weight is
+ * dW[k,n] = H[k/lambda1, n/lambda2]/lambda1, Sec. 3.2 "Merging Q-BLoRA").
+ * workspace: at least qblora_tile_product_workspace_bytes().
+ */
+size_t qblora_tile_product_workspace_bytes(const qblora_adapter* ad, int32_t d_in, int32_t d_out);
+int qblora_tile_product(const qblora_adapter* ad, int32_t d_in, int32_t d_out, float* H,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * QA-BLoRA merge (Sec. 3.3, Alg. 2 get_new_beta): fold the adapter, given as its tile matrix
+ * H fp32 [d_in/lambda1, d_out/lambda2] (a QA-BLoRA single-matrix adapter is already in this
+ * form; a Q-BLoRA adapter goes through qblora_tile_product), into block-wise INT4 parameters.
+ * The shift of element (n,k) is delta = (s * H[k/lambda1, n/lambda2]) / lambda1 in fp32.
+ *   QBLORA_MERGE_BETA_SHIFT      needs every quantization block inside one (lambda1 x lambda2)
+ *                                tile (lambda1 % block == 0), else QBLORA_ERR_ALIGNMENT.
+ *                                out->beta[b] = base beta[b] + delta (delta alone when the base
+ *                                has no beta); codes and alpha are copied to out unless out
+ *                                aliases base's buffers.  out keeps base's codebook; its scales
+ *                                are fp32 (reconstructed when the base has grouped scales).
+ *   QBLORA_MERGE_REQUANT_MINMAX  per block, w' = w~ + delta with w~ = c*alpha or fma(c,alpha,beta)
+ *                                in fp32, then the min-max INT4 quantizer of
+ *                                qblora_quantize_blockwise; out gets codes, alpha, beta and
+ *                                the codebook 0..15, scale_mode FP32.
+ * `out` is a host struct with caller-filled device pointers (codes, scales, beta), as for the
+ * quantizer.  Outputs are reproducible bit for bit given H.
+ */
+int qablora_merge_quantize(const qblora_qweight* base, const float* H, int32_t lambda1, int32_t lambda2,
+                           float s, int32_t mode, qblora_qweight* out, void* stream);
+
+/* Static description of an error code. */
+const char* qblora_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QBLORA_H */

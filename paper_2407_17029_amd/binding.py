@@ -1,0 +1,265 @@
+"""Thin ctypes binding over the C-ABI library (include/qblora.h), same entry-point names.
+
+Argument marshalling only: PyTorch allocates device buffers and supplies the stream; every step
+of the method runs inside libqblora.so.  There is no CPU fallback: if the library has not been
+built (python -m paper_2407_17029_amd.build) loading raises, and every call checks the returned
+status code and raises on error.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_DIR, "libqblora.so")
+
+OK = 0
+QUANT_ABSMAX_CODEBOOK, QUANT_MINMAX_INT4 = 0, 1
+SCALES_FP32, SCALES_E4M3_GROUPED = 0, 1
+MERGE_BETA_SHIFT, MERGE_REQUANT_MINMAX = 0, 1
+
+EXPORTS = ["qblora_quantize_blockwise", "qblora_dequantize_bf16", "qblora_linear_fwd_workspace_bytes",
+           "qblora_linear_bwd_workspace_bytes", "qblora_linear_fwd", "qblora_linear_bwd",
+           "qblora_tile_product_workspace_bytes", "qblora_tile_product", "qablora_merge_quantize",
+           "qblora_strerror"]
+
+
+class CQWeight(C.Structure):
+    _fields_ = [("d_out", C.c_int32), ("d_in", C.c_int32), ("block", C.c_int32), ("scale_mode", C.c_int32),
+                ("scale_group", C.c_int32), ("codebook", C.c_float * 16), ("codes", C.c_void_p),
+                ("scales", C.c_void_p), ("beta", C.c_void_p), ("scale_codes", C.c_void_p),
+                ("scale_step", C.c_void_p), ("scale_mid", C.c_void_p)]
+
+
+class CAdapter(C.Structure):
+    _fields_ = [("lambda1", C.c_int32), ("lambda2", C.c_int32), ("R", C.c_int32), ("s", C.c_float),
+                ("A", C.c_void_p), ("B", C.c_void_p)]
+
+
+class QBLoRAError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} (code {code})")
+
+
+_lib = None
+
+
+def lib():
+    """Load libqblora.so (raises if it was not built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2407_17029_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        L.qblora_strerror.restype = C.c_char_p
+        L.qblora_strerror.argtypes = [C.c_int]
+        for name in ("qblora_linear_fwd_workspace_bytes", "qblora_linear_bwd_workspace_bytes",
+                     "qblora_tile_product_workspace_bytes"):
+            getattr(L, name).restype = C.c_size_t
+        L.qblora_linear_fwd_workspace_bytes.argtypes = [C.c_void_p, C.c_void_p, C.c_int64]
+        L.qblora_linear_bwd_workspace_bytes.argtypes = [C.c_void_p, C.c_void_p, C.c_int64]
+        L.qblora_tile_product_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+        L.qblora_quantize_blockwise.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                                C.c_int32, C.c_void_p, C.c_void_p]
+        L.qblora_dequantize_bf16.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        L.qblora_linear_fwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                        C.c_size_t, C.c_void_p]
+        L.qblora_linear_bwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.qblora_tile_product.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
+                                          C.c_void_p]
+        L.qablora_merge_quantize.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_int32,
+                                             C.c_void_p, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().qblora_strerror(code).decode()
+
+
+def _check(code: int, where: str) -> None:
+    if code != OK:
+        raise QBLoRAError(code, where)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class QWeight:
+    """The triplet (codes, alpha, beta) of Eq. 1 on the device, plus the host-side C struct."""
+
+    def __init__(self, d_out, d_in, block, codebook, codes, scales, beta=None, scale_mode=SCALES_FP32,
+                 scale_codes=None, scale_step=None, scale_mid=None, scale_group=256):
+        self.d_out, self.d_in, self.block = d_out, d_in, block
+        self.codebook = np.asarray(codebook, np.float32)
+        self.codes, self.scales, self.beta = codes, scales, beta
+        self.scale_mode, self.scale_group = scale_mode, scale_group
+        self.scale_codes, self.scale_step, self.scale_mid = scale_codes, scale_step, scale_mid
+
+    def c_struct(self) -> CQWeight:
+        s = CQWeight()
+        s.d_out, s.d_in, s.block = self.d_out, self.d_in, self.block
+        s.scale_mode, s.scale_group = self.scale_mode, self.scale_group
+        for j in range(16):
+            s.codebook[j] = float(self.codebook[j])
+        for name in ("codes", "scales", "beta", "scale_codes", "scale_step", "scale_mid"):
+            t = getattr(self, name)
+            setattr(s, name, None if t is None else t.data_ptr())
+        return s
+
+    def absorb(self, s: CQWeight) -> None:
+        """Take back the scalar fields the library filled in."""
+        self.d_out, self.d_in, self.block = s.d_out, s.d_in, s.block
+        self.scale_mode, self.scale_group = s.scale_mode, s.scale_group
+        self.codebook = np.array([s.codebook[j] for j in range(16)], np.float32)
+        if not s.beta:
+            self.beta = None
+
+
+class Adapter:
+    """Balanced adapter of Sec. 3.2: A bf16 [d_in/lambda1, R], B bf16 [R, d_out/lambda2], scaling s."""
+
+    def __init__(self, A, B, lambda1, lambda2, s):
+        self.A, self.B, self.lambda1, self.lambda2, self.s = A, B, int(lambda1), int(lambda2), float(s)
+        self.R = 0 if A is None else int(A.shape[1])
+
+    def c_struct(self) -> CAdapter:
+        a = CAdapter()
+        a.lambda1, a.lambda2, a.R, a.s = self.lambda1, self.lambda2, self.R, self.s
+        a.A = None if self.A is None else self.A.data_ptr()
+        a.B = None if self.B is None else self.B.data_ptr()
+        return a
+
+
+def _adapter_ref(ad):
+    if ad is None:
+        return None, None
+    s = ad.c_struct()
+    return s, C.byref(s)
+
+
+def qblora_quantize_blockwise(W: torch.Tensor, block: int = 64, quantizer: int = QUANT_ABSMAX_CODEBOOK,
+                              codebook=None, scale_mode: int = SCALES_FP32) -> QWeight:
+    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and W.dim() == 2
+    d_out, d_in = W.shape
+    dev = W.device
+    nblk = d_out * (d_in // max(block, 1))
+    codes = torch.empty((d_out, d_in // 2), dtype=torch.uint8, device=dev)
+    scales = torch.empty((d_out, d_in // max(block, 1)), dtype=torch.float32, device=dev)
+    beta = torch.empty_like(scales) if quantizer == QUANT_MINMAX_INT4 else None
+    sc = st = mid = None
+    if scale_mode == SCALES_E4M3_GROUPED:
+        ng = (nblk + 255) // 256
+        sc = torch.empty(nblk, dtype=torch.uint8, device=dev)
+        st = torch.empty(ng, dtype=torch.float32, device=dev)
+        mid = torch.empty(ng, dtype=torch.float32, device=dev)
+    cb = np.zeros(16, np.float32) if codebook is None else np.ascontiguousarray(codebook, np.float32)
+    qw = QWeight(d_out, d_in, block, cb, codes, scales, beta, scale_mode, sc, st, mid)
+    s = qw.c_struct()
+    cb_ptr = None if codebook is None else cb.ctypes.data_as(C.c_void_p)
+    rc = lib().qblora_quantize_blockwise(_ptr(W), d_out, d_in, block, quantizer, cb_ptr, scale_mode, C.byref(s),
+                                         _stream())
+    _check(rc, "qblora_quantize_blockwise")
+    qw.absorb(s)
+    return qw
+
+
+def qblora_dequantize_bf16(qw: QWeight) -> torch.Tensor:
+    Wt = torch.empty((qw.d_out, qw.d_in), dtype=torch.bfloat16, device=qw.codes.device)
+    s = qw.c_struct()
+    _check(lib().qblora_dequantize_bf16(C.byref(s), _ptr(Wt), _stream()), "qblora_dequantize_bf16")
+    return Wt
+
+
+def qblora_linear_fwd_workspace_bytes(qw: QWeight, ad, T: int) -> int:
+    s = qw.c_struct()
+    a, aref = _adapter_ref(ad)
+    return int(lib().qblora_linear_fwd_workspace_bytes(C.byref(s), aref, T))
+
+
+def qblora_linear_bwd_workspace_bytes(qw: QWeight, ad, T: int) -> int:
+    s = qw.c_struct()
+    a, aref = _adapter_ref(ad)
+    return int(lib().qblora_linear_bwd_workspace_bytes(C.byref(s), aref, T))
+
+
+def _workspace(nbytes: int, device, workspace):
+    if workspace is not None:
+        return workspace
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def qblora_linear_fwd(qw: QWeight, ad, X: torch.Tensor, Y: torch.Tensor = None, workspace: torch.Tensor = None):
+    assert X.is_cuda and X.dtype == torch.bfloat16 and X.is_contiguous() and X.shape[1] == qw.d_in
+    T = X.shape[0]
+    if Y is None:
+        Y = torch.empty((T, qw.d_out), dtype=torch.bfloat16, device=X.device)
+    ws = _workspace(qblora_linear_fwd_workspace_bytes(qw, ad, T), X.device, workspace)
+    s = qw.c_struct()
+    a, aref = _adapter_ref(ad)
+    rc = lib().qblora_linear_fwd(C.byref(s), aref, _ptr(X), T, _ptr(Y), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "qblora_linear_fwd")
+    return Y
+
+
+def qblora_linear_bwd(qw: QWeight, ad, X: torch.Tensor, dY: torch.Tensor, need_dx: bool = True,
+                      need_grads: bool = True, dX=None, dA=None, dB=None, workspace: torch.Tensor = None):
+    assert dY.is_cuda and dY.dtype == torch.bfloat16 and dY.is_contiguous() and dY.shape[1] == qw.d_out
+    T = dY.shape[0]
+    dev = dY.device
+    if need_dx and dX is None:
+        dX = torch.empty((T, qw.d_in), dtype=torch.bfloat16, device=dev)
+    if need_grads and ad is not None and ad.R > 0:
+        if dA is None:
+            dA = torch.empty((qw.d_in // ad.lambda1, ad.R), dtype=torch.float32, device=dev)
+        if dB is None:
+            dB = torch.empty((ad.R, qw.d_out // ad.lambda2), dtype=torch.float32, device=dev)
+    ws = _workspace(qblora_linear_bwd_workspace_bytes(qw, ad, T), dev, workspace)
+    s = qw.c_struct()
+    a, aref = _adapter_ref(ad)
+    rc = lib().qblora_linear_bwd(C.byref(s), aref, _ptr(X), _ptr(dY), T, _ptr(dX), _ptr(dA), _ptr(dB), _ptr(ws),
+                                 ws.numel(), _stream())
+    _check(rc, "qblora_linear_bwd")
+    return dX, dA, dB
+
+
+def qblora_tile_product(ad: Adapter, d_in: int, d_out: int, H: torch.Tensor = None, workspace=None):
+    dev = ad.A.device
+    if H is None:
+        H = torch.empty((d_in // ad.lambda1, d_out // ad.lambda2), dtype=torch.float32, device=dev)
+    a = ad.c_struct()
+    need = int(lib().qblora_tile_product_workspace_bytes(C.byref(a), d_in, d_out))
+    ws = _workspace(need, dev, workspace)
+    rc = lib().qblora_tile_product(C.byref(a), d_in, d_out, _ptr(H), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "qblora_tile_product")
+    return H
+
+
+def qablora_merge_quantize(base: QWeight, H: torch.Tensor, lambda1: int, lambda2: int, s: float, mode: int,
+                           out: QWeight = None) -> QWeight:
+    assert H.is_cuda and H.dtype == torch.float32 and H.is_contiguous()
+    dev = H.device
+    if out is None:
+        out = QWeight(base.d_out, base.d_in, base.block, base.codebook,
+                      torch.empty_like(base.codes),
+                      torch.empty((base.d_out, base.d_in // base.block), dtype=torch.float32, device=dev),
+                      torch.empty((base.d_out, base.d_in // base.block), dtype=torch.float32, device=dev))
+    b = base.c_struct()
+    o = out.c_struct()
+    rc = lib().qablora_merge_quantize(C.byref(b), _ptr(H), lambda1, lambda2, s, mode, C.byref(o), _stream())
+    _check(rc, "qablora_merge_quantize")
+    beta_keep = out.beta
+    out.absorb(o)
+    out.beta = beta_keep
+    out.scale_codes = out.scale_step = out.scale_mid = None
+    return out

@@ -1,0 +1,368 @@
+// C-ABI entry points (include/qblora.h): host-side validation, workspace layout and kernel
+// sequencing.  Every step of the method runs in the kernels; nothing here touches tensor data.
+#include <cstring>
+
+#include "common.h"
+
+using namespace qblora;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Carver {
+    char* base;
+    size_t off = 0;
+    explicit Carver(void* p) : base(static_cast<char*>(p)) {}
+    template <typename T>
+    T* take(size_t count) {
+        T* r = base ? reinterpret_cast<T*>(base + off) : nullptr;
+        off += align_up(count * sizeof(T));
+        return r;
+    }
+};
+
+bool has_adapter(const qblora_adapter* ad) { return ad && ad->A && ad->B && ad->R > 0; }
+
+int check_qweight(const qblora_qweight* qw, bool need_codes) {
+    if (!qw) return QBLORA_ERR_NULL;
+    if (qw->d_out <= 0 || qw->d_in <= 0) return QBLORA_ERR_SHAPE;
+    if (qw->block != kBlock) return qw->block > 0 ? QBLORA_ERR_UNSUPPORTED : QBLORA_ERR_SHAPE;
+    if (qw->d_in % qw->block != 0 || qw->d_in % 2 != 0) return QBLORA_ERR_SHAPE;
+    if (need_codes) {
+        if (!qw->codes) return QBLORA_ERR_NULL;
+        if (qw->scale_mode == QBLORA_SCALES_FP32) {
+            if (!qw->scales) return QBLORA_ERR_NULL;
+        } else if (qw->scale_mode == QBLORA_SCALES_E4M3_GROUPED) {
+            if (!qw->scale_codes || !qw->scale_step || !qw->scale_mid) return QBLORA_ERR_NULL;
+            if (qw->scale_group <= 0) return QBLORA_ERR_SHAPE;
+        } else {
+            return QBLORA_ERR_UNSUPPORTED;
+        }
+    }
+    return QBLORA_OK;
+}
+
+int check_layer(const qblora_qweight* qw, const qblora_adapter* ad) {
+    int rc = check_qweight(qw, true);
+    if (rc) return rc;
+    if (qw->d_out % 64 != 0) return QBLORA_ERR_SHAPE;      // contraction step of the transposed use
+    if (ad && (ad->A || ad->B || ad->R)) {
+        if (ad->R < 0 || ad->lambda1 <= 0 || ad->lambda2 <= 0) return QBLORA_ERR_SHAPE;
+        if (has_adapter(ad)) {
+            if (qw->d_in % ad->lambda1 != 0 || qw->d_out % ad->lambda2 != 0) return QBLORA_ERR_SHAPE;
+            if (ad->R % 8 != 0) return QBLORA_ERR_SHAPE;
+        } else if (ad->R > 0) {
+            return QBLORA_ERR_NULL;                         // a rank was given but a matrix is missing
+        }
+    }
+    return QBLORA_OK;
+}
+
+Codebook codebook_of(const qblora_qweight* qw) {
+    Codebook cb;
+    for (int j = 0; j < 16; ++j) cb.c[j] = qw->codebook[j];
+    return cb;
+}
+
+int64_t n_blocks(const qblora_qweight* qw) { return (int64_t)qw->d_out * (qw->d_in / qw->block); }
+
+struct FwdSpace {
+    float* scales; qblora_bf16 *At_x, *Bt, *U;
+    size_t bytes;
+};
+FwdSpace carve_fwd(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T, void* ws) {
+    Carver c(ws);
+    FwdSpace s{};
+    if (qw->scale_mode == QBLORA_SCALES_E4M3_GROUPED) s.scales = c.take<float>(n_blocks(qw));
+    if (has_adapter(ad)) {
+        s.At_x = c.take<qblora_bf16>((size_t)ad->R * qw->d_in);
+        s.Bt = c.take<qblora_bf16>((size_t)(qw->d_out / ad->lambda2) * ad->R);
+        s.U = c.take<qblora_bf16>((size_t)T * ad->R);
+    }
+    s.bytes = c.off;
+    return s;
+}
+
+struct BwdSpace {
+    float* scales; qblora_bf16 *At_x, *Bx, *U, *dU, *dUs; float* part;
+    int splits_a, splits_b;
+    size_t bytes;
+};
+BwdSpace carve_bwd(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T, void* ws) {
+    Carver c(ws);
+    BwdSpace s{};
+    if (qw->scale_mode == QBLORA_SCALES_E4M3_GROUPED) s.scales = c.take<float>(n_blocks(qw));
+    if (has_adapter(ad)) {
+        s.At_x = c.take<qblora_bf16>((size_t)ad->R * qw->d_in);
+        s.Bx = c.take<qblora_bf16>((size_t)ad->R * qw->d_out);
+        s.U = c.take<qblora_bf16>((size_t)T * ad->R);
+        s.dU = c.take<qblora_bf16>((size_t)T * ad->R);
+        s.dUs = c.take<qblora_bf16>((size_t)T * ad->R);
+        s.splits_a = grad_splits(T, qw->d_in);
+        s.splits_b = grad_splits(T, qw->d_out);
+        size_t pa = (size_t)s.splits_a * qw->d_in * ad->R, pb = (size_t)s.splits_b * qw->d_out * ad->R;
+        s.part = c.take<float>(pa > pb ? pa : pb);
+    }
+    s.bytes = c.off;
+    return s;
+}
+
+__global__ void k_fill_zero(float* p, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0.0f;
+}
+
+// fp32 block scales the GEMM kernels read: the stored ones, or reconstructed into scratch.
+int resolve_scales(const qblora_qweight* qw, float* scratch, hipStream_t st, const float** out) {
+    if (qw->scale_mode == QBLORA_SCALES_FP32) { *out = qw->scales; return QBLORA_OK; }
+    *out = scratch;
+    return launch_scales_reconstruct(qw->scale_codes, qw->scale_step, qw->scale_mid, n_blocks(qw),
+                                     qw->scale_group, scratch, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* qblora_strerror(int code) {
+    switch (code) {
+        case QBLORA_OK: return "ok";
+        case QBLORA_ERR_NULL: return "a required pointer is NULL";
+        case QBLORA_ERR_SHAPE: return "a size is non-positive or not divisible as the method requires";
+        case QBLORA_ERR_UNSUPPORTED: return "configuration not implemented by these kernels";
+        case QBLORA_ERR_WORKSPACE: return "workspace missing or too small";
+        case QBLORA_ERR_ALIGNMENT: return "beta-shift merge needs every quantization block inside one adapter tile";
+        case QBLORA_ERR_LAUNCH: return "the HIP runtime refused a launch";
+        default: return "unknown error code";
+    }
+}
+
+int qblora_quantize_blockwise(const float* W, int32_t d_out, int32_t d_in, int32_t block, int32_t quantizer,
+                              const float* codebook, int32_t scale_mode, qblora_qweight* out, void* stream) {
+    if (!W || !out) return QBLORA_ERR_NULL;
+    if (d_out <= 0 || d_in <= 0 || block <= 0) return QBLORA_ERR_SHAPE;
+    if (block != kBlock) return QBLORA_ERR_UNSUPPORTED;
+    if (d_in % block != 0) return QBLORA_ERR_SHAPE;
+    if (quantizer != QBLORA_QUANT_ABSMAX_CODEBOOK && quantizer != QBLORA_QUANT_MINMAX_INT4)
+        return QBLORA_ERR_UNSUPPORTED;
+    if (scale_mode != QBLORA_SCALES_FP32 && scale_mode != QBLORA_SCALES_E4M3_GROUPED) return QBLORA_ERR_UNSUPPORTED;
+    if (!out->codes || !out->scales) return QBLORA_ERR_NULL;
+    hipStream_t st = as_stream(stream);
+    if (quantizer == QBLORA_QUANT_MINMAX_INT4) {
+        if (scale_mode != QBLORA_SCALES_FP32) return QBLORA_ERR_UNSUPPORTED;
+        if (!out->beta) return QBLORA_ERR_NULL;
+    } else {
+        if (!codebook) return QBLORA_ERR_NULL;
+        for (int j = 0; j < 15; ++j)
+            if (!(codebook[j] < codebook[j + 1])) return QBLORA_ERR_SHAPE;
+        if (scale_mode == QBLORA_SCALES_E4M3_GROUPED &&
+            (!out->scale_codes || !out->scale_step || !out->scale_mid))
+            return QBLORA_ERR_NULL;
+    }
+    out->d_out = d_out; out->d_in = d_in; out->block = block; out->scale_mode = scale_mode;
+    out->scale_group = 256;
+    if (quantizer == QBLORA_QUANT_MINMAX_INT4) {
+        for (int j = 0; j < 16; ++j) out->codebook[j] = (float)j;
+        return launch_quantize_minmax(W, d_out, d_in, out->codes, out->scales, out->beta, st);
+    }
+    Codebook cb;
+    for (int j = 0; j < 16; ++j) { cb.c[j] = codebook[j]; out->codebook[j] = codebook[j]; }
+    out->beta = nullptr;
+    int rc = launch_quantize_codebook(W, d_out, d_in, cb, out->codes, out->scales, st);
+    if (rc) return rc;
+    if (scale_mode == QBLORA_SCALES_E4M3_GROUPED)
+        rc = launch_scales_double_quantize(out->scales, n_blocks(out), out->scale_group, out->scale_codes,
+                                           out->scale_step, out->scale_mid, st);
+    return rc;
+}
+
+int qblora_dequantize_bf16(const qblora_qweight* qw, qblora_bf16* Wt, void* stream) {
+    int rc = check_qweight(qw, true);
+    if (rc) return rc;
+    if (!Wt) return QBLORA_ERR_NULL;
+    if (qw->scale_mode != QBLORA_SCALES_FP32) return QBLORA_ERR_UNSUPPORTED;   // reconstruct needs scratch
+    return launch_dequantize_bf16(*qw, qw->scales, Wt, as_stream(stream));
+}
+
+size_t qblora_linear_fwd_workspace_bytes(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T) {
+    if (check_layer(qw, ad) || T < 0) return 0;
+    return carve_fwd(qw, ad, T, nullptr).bytes;
+}
+
+size_t qblora_linear_bwd_workspace_bytes(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T) {
+    if (check_layer(qw, ad) || T < 0) return 0;
+    return carve_bwd(qw, ad, T, nullptr).bytes;
+}
+
+int qblora_linear_fwd(const qblora_qweight* qw, const qblora_adapter* ad, const qblora_bf16* X, int64_t T,
+                      qblora_bf16* Y, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_layer(qw, ad);
+    if (rc) return rc;
+    if (T < 0) return QBLORA_ERR_SHAPE;
+    if (T == 0) return QBLORA_OK;
+    if (!X || !Y) return QBLORA_ERR_NULL;
+    FwdSpace ws = carve_fwd(qw, ad, T, workspace);
+    if (ws.bytes > 0 && (!workspace || workspace_bytes < ws.bytes)) return QBLORA_ERR_WORKSPACE;
+    hipStream_t st = as_stream(stream);
+    const bool adapted = has_adapter(ad);
+
+    GemmDesc g{};
+    g.qmode = 1;
+    if ((rc = resolve_scales(qw, ws.scales, st, &g.scales))) return rc;
+    if (adapted) {
+        if ((rc = launch_adapter_prep(ad->A, ad->B, qw->d_in, qw->d_out, ad->R, ad->lambda1, ad->lambda2,
+                                      ws.At_x, ws.Bt, nullptr, st)))
+            return rc;
+        // s*U = (s/lambda1) * X * expand(A): average pool folded into the contraction
+        GemmDesc u{};
+        u.qmode = 0;
+        u.X2 = X; u.ldx2 = qw->d_in; u.W2 = ws.At_x; u.ldw2 = qw->d_in; u.K2 = qw->d_in; u.div2 = 1;
+        u.C = ws.U; u.ldc = ad->R; u.out_scale = ad->s / (float)ad->lambda1; u.M = T; u.N = ad->R;
+        if ((rc = launch_gemm(u, st))) return rc;
+        g.X2 = ws.U; g.ldx2 = ad->R; g.W2 = ws.Bt; g.ldw2 = ad->R; g.K2 = ad->R; g.div2 = ad->lambda2;
+    } else {
+        g.K2 = 0; g.div2 = 1;
+    }
+    g.X1 = X; g.ldx1 = qw->d_in;
+    g.codes = qw->codes; g.beta = qw->beta; g.d_out = qw->d_out; g.d_in = qw->d_in; g.cb = codebook_of(qw);
+    g.C = Y; g.ldc = qw->d_out; g.out_scale = 1.0f; g.M = T; g.N = qw->d_out;
+    return launch_gemm(g, st);
+}
+
+int qblora_linear_bwd(const qblora_qweight* qw, const qblora_adapter* ad, const qblora_bf16* X,
+                      const qblora_bf16* dY, int64_t T, qblora_bf16* dX, float* dA, float* dB,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_layer(qw, ad);
+    if (rc) return rc;
+    if (T < 0) return QBLORA_ERR_SHAPE;
+    const bool adapted = has_adapter(ad);
+    const bool want_grads = dA || dB;
+    if (want_grads && !(dA && dB)) return QBLORA_ERR_NULL;
+    if (want_grads && !adapted) return QBLORA_ERR_NULL;
+    if (!dX && !want_grads) return QBLORA_ERR_NULL;
+    hipStream_t st = as_stream(stream);
+    if (T == 0) {
+        if (want_grads) {
+            int64_t na = (int64_t)(qw->d_in / ad->lambda1) * ad->R, nb = (int64_t)ad->R * (qw->d_out / ad->lambda2);
+            hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((na + 255) / 256)), dim3(256), 0, st, dA, na);
+            hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, st, dB, nb);
+            return launch_status();
+        }
+        return QBLORA_OK;
+    }
+    if (!dY || (adapted && !X)) return QBLORA_ERR_NULL;
+    BwdSpace ws = carve_bwd(qw, ad, T, workspace);
+    if (ws.bytes > 0 && (!workspace || workspace_bytes < ws.bytes)) return QBLORA_ERR_WORKSPACE;
+
+    GemmDesc g{};
+    g.qmode = 2;
+    if (dX && (rc = resolve_scales(qw, ws.scales, st, &g.scales))) return rc;
+    if (adapted) {
+        const int R = ad->R;
+        if ((rc = launch_adapter_prep(ad->A, ad->B, qw->d_in, qw->d_out, R, ad->lambda1, ad->lambda2,
+                                      want_grads ? ws.At_x : nullptr, nullptr, ws.Bx, st)))
+            return rc;
+        // dU = s * dY * expand(B)^T (sum pool over lambda2 folded into the contraction); dUs = dU/lambda1
+        GemmDesc du{};
+        du.qmode = 0;
+        du.X2 = dY; du.ldx2 = qw->d_out; du.W2 = ws.Bx; du.ldw2 = qw->d_out; du.K2 = qw->d_out; du.div2 = 1;
+        du.C = ws.dU; du.ldc = R; du.out_scale = ad->s; du.C2 = ws.dUs; du.c2_scale = 1.0f / (float)ad->lambda1;
+        du.M = T; du.N = R;
+        if ((rc = launch_gemm(du, st))) return rc;
+        if (want_grads) {
+            GemmDesc u{};
+            u.qmode = 0;
+            u.X2 = X; u.ldx2 = qw->d_in; u.W2 = ws.At_x; u.ldw2 = qw->d_in; u.K2 = qw->d_in; u.div2 = 1;
+            u.C = ws.U; u.ldc = R; u.out_scale = ad->s / (float)ad->lambda1; u.M = T; u.N = R;
+            if ((rc = launch_gemm(u, st))) return rc;
+            GradDesc ga{};
+            ga.L = X; ga.ldl = qw->d_in; ga.I = qw->d_in; ga.S = ws.dU; ga.lds = R; ga.J = R; ga.T = T;
+            ga.part = ws.part; ga.splits = ws.splits_a; ga.out = dA; ga.pool = ad->lambda1;
+            ga.out_scale = 1.0f / (float)ad->lambda1; ga.transpose_out = 0;
+            if ((rc = launch_grad(ga, st))) return rc;
+            GradDesc gb{};
+            gb.L = dY; gb.ldl = qw->d_out; gb.I = qw->d_out; gb.S = ws.U; gb.lds = R; gb.J = R; gb.T = T;
+            gb.part = ws.part; gb.splits = ws.splits_b; gb.out = dB; gb.pool = ad->lambda2;
+            gb.out_scale = 1.0f; gb.transpose_out = 1;
+            if ((rc = launch_grad(gb, st))) return rc;
+        }
+        g.X2 = ws.dUs; g.ldx2 = R; g.W2 = ad->A; g.ldw2 = R; g.K2 = R; g.div2 = ad->lambda1;
+    } else {
+        g.K2 = 0; g.div2 = 1;
+    }
+    if (!dX) return QBLORA_OK;
+    g.X1 = dY; g.ldx1 = qw->d_out;
+    g.codes = qw->codes; g.beta = qw->beta; g.d_out = qw->d_out; g.d_in = qw->d_in; g.cb = codebook_of(qw);
+    g.C = dX; g.ldc = qw->d_in; g.out_scale = 1.0f; g.M = T; g.N = qw->d_in;
+    return launch_gemm(g, st);
+}
+
+size_t qblora_tile_product_workspace_bytes(const qblora_adapter* ad, int32_t d_in, int32_t d_out) {
+    if (!has_adapter(ad) || d_out <= 0 || ad->lambda2 <= 0 || d_out % ad->lambda2) return 0;
+    (void)d_in;
+    return align_up((size_t)(d_out / ad->lambda2) * ad->R * sizeof(qblora_bf16));
+}
+
+int qblora_tile_product(const qblora_adapter* ad, int32_t d_in, int32_t d_out, float* H, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+    if (!ad || !ad->A || !ad->B || !H) return QBLORA_ERR_NULL;
+    if (d_in <= 0 || d_out <= 0 || ad->R <= 0 || ad->lambda1 <= 0 || ad->lambda2 <= 0) return QBLORA_ERR_SHAPE;
+    if (d_in % ad->lambda1 || d_out % ad->lambda2 || ad->R % 8) return QBLORA_ERR_SHAPE;
+    const int rows = d_in / ad->lambda1, cols = d_out / ad->lambda2;
+    if (cols % 4) return QBLORA_ERR_UNSUPPORTED;
+    size_t need = qblora_tile_product_workspace_bytes(ad, d_in, d_out);
+    if (!workspace || workspace_bytes < need) return QBLORA_ERR_WORKSPACE;
+    hipStream_t st = as_stream(stream);
+    qblora_bf16* Bt = static_cast<qblora_bf16*>(workspace);
+    int rc = launch_adapter_prep(ad->A, ad->B, d_in, d_out, ad->R, ad->lambda1, ad->lambda2, nullptr, Bt, nullptr, st);
+    if (rc) return rc;
+    GemmDesc g{};
+    g.qmode = 0;
+    g.X2 = ad->A; g.ldx2 = ad->R; g.W2 = Bt; g.ldw2 = ad->R; g.K2 = ad->R; g.div2 = 1;
+    g.C = H; g.ldc = cols; g.out_f32 = 1; g.out_scale = 1.0f; g.M = rows; g.N = cols;
+    return launch_gemm(g, st);
+}
+
+int qablora_merge_quantize(const qblora_qweight* base, const float* H, int32_t lambda1, int32_t lambda2, float s,
+                           int32_t mode, qblora_qweight* out, void* stream) {
+    int rc = check_qweight(base, true);
+    if (rc) return rc;
+    if (!H || !out) return QBLORA_ERR_NULL;
+    if (lambda1 <= 0 || lambda2 <= 0) return QBLORA_ERR_SHAPE;
+    if (base->d_in % lambda1 || base->d_out % lambda2) return QBLORA_ERR_SHAPE;
+    if (mode != QBLORA_MERGE_BETA_SHIFT && mode != QBLORA_MERGE_REQUANT_MINMAX) return QBLORA_ERR_UNSUPPORTED;
+    if (!out->codes || !out->scales || !out->beta) return QBLORA_ERR_NULL;
+    hipStream_t st = as_stream(stream);
+    const bool grouped = base->scale_mode == QBLORA_SCALES_E4M3_GROUPED;
+    MergeDesc d{};
+    d.codes = base->codes; d.scales = base->scales; d.beta = base->beta;
+    if (grouped) {
+        d.scale_codes = base->scale_codes; d.scale_step = base->scale_step; d.scale_mid = base->scale_mid;
+        d.scale_group = base->scale_group;
+    }
+    d.cb = codebook_of(base); d.d_out = base->d_out; d.d_in = base->d_in;
+    d.H = H; d.lam1 = lambda1; d.lam2 = lambda2; d.s = s;
+    d.codes_out = out->codes; d.alpha_out = out->scales; d.beta_out = out->beta;
+    out->d_out = base->d_out; out->d_in = base->d_in; out->block = base->block;
+    out->scale_mode = QBLORA_SCALES_FP32; out->scale_group = 0;
+    out->scale_codes = nullptr; out->scale_step = nullptr; out->scale_mid = nullptr;
+    if (mode == QBLORA_MERGE_BETA_SHIFT) {
+        if (lambda1 % base->block != 0) return QBLORA_ERR_ALIGNMENT;
+        std::memcpy(out->codebook, base->codebook, sizeof(out->codebook));
+        if (out->codes != base->codes &&
+            hipMemcpyAsync(out->codes, base->codes, (size_t)base->d_out * base->d_in / 2, hipMemcpyDeviceToDevice,
+                           st) != hipSuccess)
+            return QBLORA_ERR_LAUNCH;
+        if (!grouped && out->scales != base->scales &&
+            hipMemcpyAsync(out->scales, base->scales, sizeof(float) * (size_t)n_blocks(base),
+                           hipMemcpyDeviceToDevice, st) != hipSuccess)
+            return QBLORA_ERR_LAUNCH;
+        return launch_merge_beta_shift(d, st);
+    }
+    for (int j = 0; j < 16; ++j) out->codebook[j] = (float)j;
+    return launch_merge_requant(d, st);
+}
+
+}  // extern "C"

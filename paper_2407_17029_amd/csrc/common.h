@@ -1,0 +1,110 @@
+// Shared device/host helpers of the gfx950 kernels (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/qblora.h"
+
+namespace qblora {
+
+constexpr int kBlock = 64;   // quantization block: 64 contiguous k of one output row
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+struct Codebook {
+    float c[16];
+};
+
+// Two fp32 -> one dword of two bf16 (round to nearest even); lo in bits 0..15.
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    bf16x2 p;
+    p[0] = (__bf16)lo;
+    p[1] = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, p);
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+
+// OCP E4M3 bit pattern -> fp32 (NaN patterns are never produced by the encoder).
+__device__ __forceinline__ float e4m3_to_float(uint32_t c) {
+    uint32_t e = (c >> 3) & 0xf, m = c & 7;
+    float v = e ? __uint_as_float(((e + 120u) << 23) | (m << 20)) : (float)m * 0x1p-9f;
+    return (c & 0x80) ? -v : v;
+}
+
+// Reconstructed block scale under the grouped E4M3 second-level quantization.
+__device__ __forceinline__ float grouped_scale(const uint8_t* __restrict__ scale_codes,
+                                               const float* __restrict__ step,
+                                               const float* __restrict__ mid, int64_t i, int group) {
+    int64_t g = i / group;
+    return __fmaf_rn(e4m3_to_float(scale_codes[i]), step[g], mid[g]);
+}
+
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? QBLORA_OK : QBLORA_ERR_LAUNCH; }
+
+// ---- kernels' host launchers (defined in the .hip files) -------------------------------------
+
+int launch_quantize_codebook(const float* W, int d_out, int d_in, const Codebook& cb, uint8_t* codes,
+                             float* absmax, hipStream_t st);
+int launch_quantize_minmax(const float* W, int d_out, int d_in, uint8_t* codes, float* alpha, float* beta,
+                           hipStream_t st);
+int launch_scales_double_quantize(const float* scales, int64_t n, int group, uint8_t* scale_codes,
+                                  float* step, float* mid, hipStream_t st);
+int launch_scales_reconstruct(const uint8_t* scale_codes, const float* step, const float* mid, int64_t n,
+                              int group, float* scales, hipStream_t st);
+int launch_dequantize_bf16(const qblora_qweight& qw, const float* scales, qblora_bf16* Wt, hipStream_t st);
+
+// Builds K-contiguous bf16 copies of the adapter matrices for the GEMM kernels:
+//   At_x [R, d_in]        At_x[j,k] = A[k/lam1, j]     (transpose, expand along k)
+//   Bt   [d_out/lam2, R]  Bt[q,j]   = B[j, q]          (transpose)
+//   Bx   [R, d_out]       Bx[j,n]   = B[j, n/lam2]     (expand along n)
+// Any output pointer may be NULL to skip it.
+int launch_adapter_prep(const qblora_bf16* A, const qblora_bf16* B, int d_in, int d_out, int R, int lam1,
+                        int lam2, qblora_bf16* At_x, qblora_bf16* Bt, qblora_bf16* Bx, hipStream_t st);
+
+// One GEMM launch description.  C[M,N] = out_scale1 * ( X1[M,K1] * Wq^T  +  X2[M,K2] * W2[N/div2, K2]^T )
+// "token" operands X1/X2 are bf16 row-major; the quantized segment is optional (qmode 0).
+struct GemmDesc {
+    int qmode;                 // 0: no quantized segment; 1: forward (N = d_out, K1 = d_in);
+                               // 2: transposed use (N = d_in, K1 = d_out)
+    const qblora_bf16* X1; int64_t ldx1;
+    const uint8_t* codes; const float* scales; const float* beta; int d_out, d_in;
+    Codebook cb;
+    const qblora_bf16* X2; int64_t ldx2;
+    const qblora_bf16* W2; int64_t ldw2; int K2; int div2;
+    void* C; int64_t ldc; int out_f32;     // bf16 or fp32 output
+    qblora_bf16* C2; float c2_scale;       // optional second bf16 output = bf16(c2_scale * acc), same shape
+    float out_scale;
+    int64_t M; int N;
+};
+int launch_gemm(const GemmDesc& d, hipStream_t st);
+
+// Token-contraction GEMM with split-T partials:  part[z][i][j] = sum_{t in slice z} L[t,i] * S[t,j]
+// followed by the reduction  out = sum_z part, pooled over `pool` adjacent i (scaled by out_scale),
+// written row-major [I/pool, J] or, when transpose_out, [J, I/pool].
+struct GradDesc {
+    const qblora_bf16* L; int64_t ldl; int I;
+    const qblora_bf16* S; int64_t lds; int J;
+    int64_t T;
+    float* part; int splits;
+    float* out; int pool; float out_scale; int transpose_out;
+};
+int grad_splits(int64_t T, int I);
+int launch_grad(const GradDesc& d, hipStream_t st);
+
+struct MergeDesc {
+    const uint8_t* codes; const float* scales; const float* beta;
+    const uint8_t* scale_codes; const float* scale_step; const float* scale_mid; int scale_group;
+    Codebook cb; int d_out, d_in;
+    const float* H; int lam1, lam2; float s;
+    uint8_t* codes_out; float* alpha_out; float* beta_out;
+};
+int launch_merge_requant(const MergeDesc& d, hipStream_t st);
+int launch_merge_beta_shift(const MergeDesc& d, hipStream_t st);
+
+}  // namespace qblora

@@ -1,0 +1,229 @@
+// Block-wise quantizers and the standalone dequantizer (Eq. 1, Sec. 3.1) for gfx950.
+//
+// Both quantizers are HBM-streaming kernels: a thread owns 4 consecutive fp32 weights (one
+// 16-byte load), 16 lanes own one 64-wide block and reduce its absmax / min / max with
+// cross-lane shuffles, every thread stores its 4 codes as one 16-bit word.  All decision
+// arithmetic is written with explicit single-rounding intrinsics so that no FMA contraction
+// can change a code.
+#include "common.h"
+
+namespace qblora {
+
+namespace {
+
+struct Midpoints {
+    float m[15];   // (c_j + c_{j+1}) * 0.5 in fp32, computed on the host
+};
+
+__device__ __forceinline__ float group16_max(float v) {
+    v = fmaxf(v, __shfl_xor(v, 8, 16));
+    v = fmaxf(v, __shfl_xor(v, 4, 16));
+    v = fmaxf(v, __shfl_xor(v, 2, 16));
+    v = fmaxf(v, __shfl_xor(v, 1, 16));
+    return v;
+}
+
+__device__ __forceinline__ float group16_min(float v) {
+    v = fminf(v, __shfl_xor(v, 8, 16));
+    v = fminf(v, __shfl_xor(v, 4, 16));
+    v = fminf(v, __shfl_xor(v, 2, 16));
+    v = fminf(v, __shfl_xor(v, 1, 16));
+    return v;
+}
+
+// Absmax / codebook quantizer.  n_vec = number of float4 groups = d_out*d_in/4 (a multiple of 16).
+__global__ __launch_bounds__(256) void k_quantize_codebook(const float4* __restrict__ W, int64_t n_vec,
+                                                           Midpoints mp, uint16_t* __restrict__ codes16,
+                                                           float* __restrict__ absmax) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n_vec) return;   // whole 16-lane groups leave together
+    float4 w = W[i];
+    float a = fmaxf(fmaxf(fabsf(w.x), fabsf(w.y)), fmaxf(fabsf(w.z), fabsf(w.w)));
+    a = group16_max(a);
+    uint32_t c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+#pragma unroll
+    for (int j = 0; j < 15; ++j) {
+        float t = __fmul_rn(mp.m[j], a);
+        c0 += (w.x > t) ? 1u : 0u;
+        c1 += (w.y > t) ? 1u : 0u;
+        c2 += (w.z > t) ? 1u : 0u;
+        c3 += (w.w > t) ? 1u : 0u;
+    }
+    codes16[i] = (uint16_t)(c0 | (c1 << 4) | (c2 << 8) | (c3 << 12));
+    if ((threadIdx.x & 15) == 0) absmax[i >> 4] = a;
+}
+
+// Min-max INT4 quantizer: alpha = (hi-lo)/15, beta = lo, code = rint((w-lo) * (15/(hi-lo))).
+__global__ __launch_bounds__(256) void k_quantize_minmax(const float4* __restrict__ W, int64_t n_vec,
+                                                         uint16_t* __restrict__ codes16,
+                                                         float* __restrict__ alpha, float* __restrict__ beta) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n_vec) return;
+    float4 w = W[i];
+    float lo = group16_min(fminf(fminf(w.x, w.y), fminf(w.z, w.w)));
+    float hi = group16_max(fmaxf(fmaxf(w.x, w.y), fmaxf(w.z, w.w)));
+    float range = __fsub_rn(hi, lo);
+    float al = __fdiv_rn(range, 15.0f);
+    uint32_t packed = 0;
+    if (al != 0.0f) {
+        float inv = __fdiv_rn(15.0f, range);
+        float q0 = rintf(__fmul_rn(__fsub_rn(w.x, lo), inv));
+        float q1 = rintf(__fmul_rn(__fsub_rn(w.y, lo), inv));
+        float q2 = rintf(__fmul_rn(__fsub_rn(w.z, lo), inv));
+        float q3 = rintf(__fmul_rn(__fsub_rn(w.w, lo), inv));
+        q0 = fminf(fmaxf(q0, 0.0f), 15.0f);
+        q1 = fminf(fmaxf(q1, 0.0f), 15.0f);
+        q2 = fminf(fmaxf(q2, 0.0f), 15.0f);
+        q3 = fminf(fmaxf(q3, 0.0f), 15.0f);
+        packed = (uint32_t)q0 | ((uint32_t)q1 << 4) | ((uint32_t)q2 << 8) | ((uint32_t)q3 << 12);
+    }
+    codes16[i] = (uint16_t)packed;
+    if ((threadIdx.x & 15) == 0) {
+        alpha[i >> 4] = al;
+        beta[i >> 4] = lo;
+    }
+}
+
+// fp32 magnitude -> E4M3 magnitude bits (7 bits), round to nearest even, saturating at 448.
+__device__ __forceinline__ uint32_t e4m3_encode_mag(float a) {
+    if (a < 0x1p-6f) return (uint32_t)rintf(a * 512.0f);          // subnormal grid 2^-9 (8 -> smallest normal)
+    uint32_t u = __float_as_uint(a);
+    u += 0x7ffffu + ((u >> 20) & 1u);                              // RNE to 3 mantissa bits, carry into exponent
+    uint32_t code = (u >> 20) - (120u << 3);
+    return code > 0x7eu ? 0x7eu : code;
+}
+
+// One workgroup of 256 threads per group of up to 256 consecutive scales.
+__global__ __launch_bounds__(256) void k_scales_double_quantize(const float* __restrict__ scales, int64_t n,
+                                                                int group, uint8_t* __restrict__ scale_codes,
+                                                                float* __restrict__ step,
+                                                                float* __restrict__ mid) {
+    __shared__ float s_lo[256], s_hi[256];
+    int64_t base = (int64_t)blockIdx.x * group;
+    int cnt = (int)((n - base) < group ? (n - base) : group);
+    int t = threadIdx.x;
+    float lo = INFINITY, hi = -INFINITY;
+    for (int i = t; i < cnt; i += 256) {
+        float v = scales[base + i];
+        lo = fminf(lo, v);
+        hi = fmaxf(hi, v);
+    }
+    s_lo[t] = lo; s_hi[t] = hi;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (t < o) { s_lo[t] = fminf(s_lo[t], s_lo[t + o]); s_hi[t] = fmaxf(s_hi[t], s_hi[t + o]); }
+        __syncthreads();
+    }
+    float m = __fmul_rn(__fadd_rn(s_lo[0], s_hi[0]), 0.5f);
+    __syncthreads();
+    float dmax = 0.0f;
+    for (int i = t; i < cnt; i += 256) dmax = fmaxf(dmax, fabsf(__fsub_rn(scales[base + i], m)));
+    s_hi[t] = dmax;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (t < o) s_hi[t] = fmaxf(s_hi[t], s_hi[t + o]);
+        __syncthreads();
+    }
+    dmax = s_hi[0];
+    float st = dmax == 0.0f ? 0.0f : __fdiv_rn(dmax, 448.0f);
+    if (t == 0) { step[blockIdx.x] = st; mid[blockIdx.x] = m; }
+    for (int i = t; i < cnt; i += 256) {
+        uint32_t code = 0;
+        if (dmax != 0.0f) {
+            float q = __fdiv_rn(__fsub_rn(scales[base + i], m), st);
+            code = e4m3_encode_mag(fabsf(q)) | (signbit(q) ? 0x80u : 0u);
+        }
+        scale_codes[base + i] = (uint8_t)code;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_scales_reconstruct(const uint8_t* __restrict__ scale_codes,
+                                                            const float* __restrict__ step,
+                                                            const float* __restrict__ mid, int64_t n, int group,
+                                                            float* __restrict__ scales) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) scales[i] = grouped_scale(scale_codes, step, mid, i, group);
+}
+
+// Standalone dequantize: thread = 8 consecutive k (one dword of codes) -> 8 bf16 (16 bytes).
+__global__ __launch_bounds__(256) void k_dequantize_bf16(const uint32_t* __restrict__ codes32,
+                                                         const float* __restrict__ scales,
+                                                         const float* __restrict__ beta, Codebook cb,
+                                                         int64_t n_words, uint4* __restrict__ out) {
+    __shared__ float lut[16];
+    if (threadIdx.x < 16) lut[threadIdx.x] = cb.c[threadIdx.x];
+    __syncthreads();
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n_words) return;
+    uint32_t w = codes32[i];
+    int64_t blk = i >> 3;    // 8 words of 8 codes per 64-block
+    float a = scales[blk];
+    float v[8];
+    if (beta) {
+        float b = beta[blk];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = __fmaf_rn(lut[(w >> (4 * j)) & 15], a, b);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = __fmul_rn(lut[(w >> (4 * j)) & 15], a);
+    }
+    uint4 o;
+    o.x = pack_bf16(v[0], v[1]); o.y = pack_bf16(v[2], v[3]);
+    o.z = pack_bf16(v[4], v[5]); o.w = pack_bf16(v[6], v[7]);
+    out[i] = o;
+}
+
+}  // namespace
+
+int launch_quantize_codebook(const float* W, int d_out, int d_in, const Codebook& cb, uint8_t* codes,
+                             float* absmax, hipStream_t st) {
+    Midpoints mp;
+    for (int j = 0; j < 15; ++j) {
+        volatile float sum = cb.c[j] + cb.c[j + 1];   // two separate fp32 roundings
+        volatile float m = sum * 0.5f;
+        mp.m[j] = m;
+    }
+    int64_t n_vec = (int64_t)d_out * d_in / 4;
+    unsigned grid = (unsigned)((n_vec + 255) / 256);
+    hipLaunchKernelGGL(k_quantize_codebook, dim3(grid), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
+                       n_vec, mp, reinterpret_cast<uint16_t*>(codes), absmax);
+    return launch_status();
+}
+
+int launch_quantize_minmax(const float* W, int d_out, int d_in, uint8_t* codes, float* alpha, float* beta,
+                           hipStream_t st) {
+    int64_t n_vec = (int64_t)d_out * d_in / 4;
+    unsigned grid = (unsigned)((n_vec + 255) / 256);
+    hipLaunchKernelGGL(k_quantize_minmax, dim3(grid), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
+                       n_vec, reinterpret_cast<uint16_t*>(codes), alpha, beta);
+    return launch_status();
+}
+
+int launch_scales_double_quantize(const float* scales, int64_t n, int group, uint8_t* scale_codes,
+                                  float* step, float* mid, hipStream_t st) {
+    unsigned grid = (unsigned)((n + group - 1) / group);
+    hipLaunchKernelGGL(k_scales_double_quantize, dim3(grid), dim3(256), 0, st, scales, n, group, scale_codes,
+                       step, mid);
+    return launch_status();
+}
+
+int launch_scales_reconstruct(const uint8_t* scale_codes, const float* step, const float* mid, int64_t n,
+                              int group, float* scales, hipStream_t st) {
+    unsigned grid = (unsigned)((n + 255) / 256);
+    hipLaunchKernelGGL(k_scales_reconstruct, dim3(grid), dim3(256), 0, st, scale_codes, step, mid, n, group,
+                       scales);
+    return launch_status();
+}
+
+int launch_dequantize_bf16(const qblora_qweight& qw, const float* scales, qblora_bf16* Wt, hipStream_t st) {
+    Codebook cb;
+    for (int j = 0; j < 16; ++j) cb.c[j] = qw.codebook[j];
+    int64_t n_words = (int64_t)qw.d_out * qw.d_in / 8;
+    unsigned grid = (unsigned)((n_words + 255) / 256);
+    hipLaunchKernelGGL(k_dequantize_bf16, dim3(grid), dim3(256), 0, st,
+                       reinterpret_cast<const uint32_t*>(qw.codes), scales, qw.beta, cb, n_words,
+                       reinterpret_cast<uint4*>(Wt));
+    return launch_status();
+}
+
+}  // namespace qblora

@@ -1,0 +1,85 @@
+"""The C-ABI library loads, exports every symbol include/qblora.h declares, and validates on the host.
+
+No compute is launched here: every call below is rejected by host-side argument checks before any
+HIP call, so the tests run without a GPU.
+"""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "qblora.h")
+
+
+@pytest.fixture(scope="module")
+def qb():
+    from paper_2407_17029_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2407_17029_amd import build
+        build.build_library()
+    binding.lib()
+    return binding
+
+
+def _declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(q[a]?blora_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(qb):
+    names = _declared_functions()
+    assert set(names) == set(qb.EXPORTS)
+    for n in names:
+        assert hasattr(qb.lib(), n), n
+
+
+def test_strerror(qb):
+    assert qb.strerror(0) == "ok"
+    for code in range(-6, 0):
+        assert qb.strerror(code) and "unknown" not in qb.strerror(code)
+    assert "unknown" in qb.strerror(-99)
+
+
+def test_host_validation_rejects_bad_arguments(qb):
+    L = qb.lib()
+    qw = qb.CQWeight()
+    dummy = C.c_void_p(0x1000)       # never dereferenced: the calls fail validation first
+    assert L.qblora_quantize_blockwise(None, 64, 64, 64, 0, None, 0, C.byref(qw), None) == -1
+    assert L.qblora_quantize_blockwise(dummy, 64, 100, 64, 0, None, 0, C.byref(qw), None) == -2
+    assert L.qblora_quantize_blockwise(dummy, 64, 64, 32, 0, None, 0, C.byref(qw), None) == -3
+    assert L.qblora_quantize_blockwise(dummy, 0, 64, 64, 0, None, 0, C.byref(qw), None) == -2
+    qw.d_out, qw.d_in, qw.block = 128, 128, 64
+    assert L.qblora_linear_fwd(C.byref(qw), None, dummy, 4, dummy, None, 0, None) == -1      # codes missing
+    qw.codes = 0x1000; qw.scales = 0x1000
+    ad = qb.CAdapter()
+    ad.lambda1, ad.lambda2, ad.R, ad.s, ad.A, ad.B = 3, 2, 16, 1.0, 0x1000, 0x1000
+    assert L.qblora_linear_fwd(C.byref(qw), C.byref(ad), dummy, 4, dummy, dummy, 1 << 30, None) == -2   # 128 % 3
+    ad.lambda1 = 2
+    assert L.qblora_linear_fwd(C.byref(qw), C.byref(ad), dummy, 4, dummy, None, 0, None) == -4           # workspace
+    assert L.qblora_linear_fwd(C.byref(qw), C.byref(ad), dummy, -1, dummy, dummy, 1 << 30, None) == -2
+    assert L.qblora_linear_fwd(C.byref(qw), C.byref(ad), dummy, 0, dummy, None, 0, None) == 0            # empty batch
+    assert L.qblora_linear_bwd(C.byref(qw), C.byref(ad), dummy, dummy, 4, None, None, None, dummy, 1 << 30, None) == -1
+    qw.d_out = 96
+    assert L.qblora_linear_fwd(C.byref(qw), None, dummy, 4, dummy, None, 0, None) == -2                  # d_out % 64
+    qw.d_out = 128
+    out = qb.CQWeight()
+    out.codes = out.scales = out.beta = 0x1000
+    assert L.qablora_merge_quantize(C.byref(qw), dummy, 2, 2, C.c_float(1.0), 0, C.byref(out), None) == -5
+    assert L.qablora_merge_quantize(C.byref(qw), dummy, 3, 2, C.c_float(1.0), 1, C.byref(out), None) == -2
+    assert L.qablora_merge_quantize(C.byref(qw), None, 2, 2, C.c_float(1.0), 1, C.byref(out), None) == -1
+
+
+def test_workspace_sizes(qb):
+    L = qb.lib()
+    qw = qb.CQWeight()
+    qw.d_out, qw.d_in, qw.block = 4096, 4096, 64
+    qw.codes = qw.scales = 0x1000
+    assert L.qblora_linear_fwd_workspace_bytes(C.byref(qw), None, 8192) == 0
+    ad = qb.CAdapter()
+    ad.lambda1, ad.lambda2, ad.R, ad.s, ad.A, ad.B = 2, 2, 128, 1.0, 0x1000, 0x1000
+    fwd = L.qblora_linear_fwd_workspace_bytes(C.byref(qw), C.byref(ad), 8192)
+    assert fwd == 2 * (128 * 4096 + 2048 * 128 + 8192 * 128)          # At_x, Bt, U in bf16
+    bwd = L.qblora_linear_bwd_workspace_bytes(C.byref(qw), C.byref(ad), 8192)
+    assert bwd > fwd and bwd % 256 == 0

@@ -1,0 +1,130 @@
+"""GPU parity: adapted forward / backward against the fp64 oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2407_17029_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def qb():
+    from paper_2407_17029_amd import binding
+    binding.lib()
+    return binding
+
+
+def _setup(qb, oracle, codebook, seed, T, d_out, d_in, R, lam1, lam2, s, minmax=False, grouped=False,
+           channel_outliers=False):
+    from gpu_util import f32_to_dev, to_np, bf16_to_dev, adapter_to_dev
+    L = synth.make_layer(seed, T, d_out, d_in, max(R, 8), lam1, lam2, channel_outliers=channel_outliers)
+    if minmax:
+        qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 64, qb.QUANT_MINMAX_INT4)
+        cb = synth.codebook_int4()
+    else:
+        qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 64, qb.QUANT_ABSMAX_CODEBOOK, codebook,
+                                          qb.SCALES_E4M3_GROUPED if grouped else qb.SCALES_FP32)
+        cb = codebook
+    torch.cuda.synchronize()
+    if grouped:
+        scales = oracle.scales_double_dequantize(to_np(qw.scale_codes), to_np(qw.scale_step), to_np(qw.scale_mid),
+                                                 256).reshape(d_out, d_in // 64)
+    else:
+        scales = to_np(qw.scales)
+    beta = None if qw.beta is None else to_np(qw.beta)
+    Wt = oracle.dequantize(to_np(qw.codes), scales, beta, cb, 64, 2)      # the bf16 compute weight
+    ad = adapter_to_dev(L, lam1, lam2, s) if R > 0 else None
+    return L, qw, Wt, ad, bf16_to_dev(L.X), bf16_to_dev(L.dY)
+
+
+CASES = [
+    # T, d_out, d_in, R, lam1, lam2, s
+    (256, 512, 512, 32, 2, 2, 1.0),          # the tiny configuration: rank 16, lambda 2
+    (300, 320, 192, 16, 2, 2, 0.25),         # ragged token count, partial tiles in every dimension
+    (77, 576, 832, 64, 4, 8, 2.0),           # lambda1 != lambda2 (the block-32 recommendation 4, 8)
+    (513, 512, 1024, 128, 8, 8, 1.0),        # lambda 8, inner rank 128 (two K-extension steps)
+    (130, 256, 256, 8, 1, 1, 1.0),           # lambda 1: plain LoRA, inner rank smaller than a K step
+]
+
+
+@pytest.mark.parametrize("T,d_out,d_in,R,lam1,lam2,s", CASES)
+def test_forward_parity(qb, oracle, codebook, T, d_out, d_in, R, lam1, lam2, s):
+    from gpu_util import assert_close_bf16
+    print(f"case fwd T={T} {d_out}x{d_in} R={R} lam=({lam1},{lam2})", flush=True)
+    L, qw, Wt, ad, X, dY = _setup(qb, oracle, codebook, 500 + T, T, d_out, d_in, R, lam1, lam2, s)
+    Y = qb.qblora_linear_fwd(qw, ad, X)
+    torch.cuda.synchronize()
+    ref = oracle.forward(Wt, L.X, L.A, L.B, lam1, lam2, s)
+    assert_close_bf16(Y, ref, "Y")
+
+
+@pytest.mark.parametrize("T,d_out,d_in,R,lam1,lam2,s", CASES)
+def test_backward_parity(qb, oracle, codebook, T, d_out, d_in, R, lam1, lam2, s):
+    from gpu_util import assert_close_bf16, assert_close_f32
+    print(f"case bwd T={T} {d_out}x{d_in} R={R} lam=({lam1},{lam2})", flush=True)
+    L, qw, Wt, ad, X, dY = _setup(qb, oracle, codebook, 600 + T, T, d_out, d_in, R, lam1, lam2, s)
+    dX, dA, dB = qb.qblora_linear_bwd(qw, ad, X, dY)
+    torch.cuda.synchronize()
+    rX, rA, rB = oracle.backward(Wt, L.X, L.dY, L.A, L.B, lam1, lam2, s)
+    assert_close_bf16(dX, rX, "dX")
+    assert_close_f32(dA, rA, "dA")
+    assert_close_f32(dB, rB, "dB")
+
+
+def test_base_layer_without_adapter_and_b_zero(qb, oracle, codebook):
+    from gpu_util import assert_close_bf16, bf16_to_dev
+    T, d_out, d_in = 200, 320, 448
+    L, qw, Wt, ad, X, dY = _setup(qb, oracle, codebook, 700, T, d_out, d_in, 16, 2, 2, 3.0)
+    Y0 = qb.qblora_linear_fwd(qw, None, X)
+    dX0, _, _ = qb.qblora_linear_bwd(qw, None, X, dY, need_grads=False)
+    torch.cuda.synchronize()
+    assert_close_bf16(Y0, oracle.forward(Wt, L.X, None, None, 1, 1, 0.0), "Y base")
+    assert_close_bf16(dX0, oracle.backward(Wt, L.X, L.dY, None, None, 1, 1, 0.0)[0], "dX base")
+    # B = 0: the adapter term vanishes and the scaling must not touch the base output
+    ad0 = qb.Adapter(ad.A, torch.zeros_like(ad.B), 2, 2, 3.0)
+    Yb = qb.qblora_linear_fwd(qw, ad0, X)
+    torch.cuda.synchronize()
+    assert torch.equal(Yb.view(torch.int16), Y0.view(torch.int16))
+
+
+def test_minmax_base_with_beta(qb, oracle, codebook):
+    from gpu_util import assert_close_bf16, assert_close_f32
+    T, d_out, d_in, R = 150, 256, 384, 32
+    L, qw, Wt, ad, X, dY = _setup(qb, oracle, codebook, 710, T, d_out, d_in, R, 2, 2, 1.0, minmax=True)
+    Y = qb.qblora_linear_fwd(qw, ad, X)
+    dX, dA, dB = qb.qblora_linear_bwd(qw, ad, X, dY)
+    torch.cuda.synchronize()
+    assert_close_bf16(Y, oracle.forward(Wt, L.X, L.A, L.B, 2, 2, 1.0), "Y")
+    rX, rA, rB = oracle.backward(Wt, L.X, L.dY, L.A, L.B, 2, 2, 1.0)
+    assert_close_bf16(dX, rX, "dX"); assert_close_f32(dA, rA, "dA"); assert_close_f32(dB, rB, "dB")
+
+
+def test_grouped_scales_and_channel_outliers(qb, oracle, codebook):
+    from gpu_util import assert_close_bf16, assert_close_f32
+    T, d_out, d_in, R = 160, 512, 512, 64
+    L, qw, Wt, ad, X, dY = _setup(qb, oracle, codebook, 720, T, d_out, d_in, R, 2, 2, 1.0, grouped=True,
+                                  channel_outliers=True)
+    Y = qb.qblora_linear_fwd(qw, ad, X)
+    dX, dA, dB = qb.qblora_linear_bwd(qw, ad, X, dY)
+    torch.cuda.synchronize()
+    assert_close_bf16(Y, oracle.forward(Wt, L.X, L.A, L.B, 2, 2, 1.0), "Y")
+    rX, rA, rB = oracle.backward(Wt, L.X, L.dY, L.A, L.B, 2, 2, 1.0)
+    assert_close_bf16(dX, rX, "dX"); assert_close_f32(dA, rA, "dA"); assert_close_f32(dB, rB, "dB")
+
+
+def test_empty_batch_and_errors(qb, oracle, codebook):
+    from gpu_util import f32_to_dev, bf16_to_dev, DEV
+    L, qw, Wt, ad, X, dY = _setup(qb, oracle, codebook, 730, 8, 128, 128, 16, 2, 2, 1.0)
+    Y = qb.qblora_linear_fwd(qw, ad, X[:0].contiguous())
+    assert Y.shape == (0, 128)
+    dX, dA, dB = qb.qblora_linear_bwd(qw, ad, X[:0].contiguous(), dY[:0].contiguous())
+    torch.cuda.synchronize()
+    assert float(dA.abs().max()) == 0.0 and float(dB.abs().max()) == 0.0
+    bad = qb.Adapter(ad.A, ad.B, 3, 2, 1.0)                      # 128 % 3 != 0
+    with pytest.raises(qb.QBLoRAError) as e:
+        qb.qblora_linear_fwd(qw, bad, X)
+    assert e.value.code == -2
+    with pytest.raises(qb.QBLoRAError) as e:
+        qb.qblora_linear_fwd(qw, ad, X, workspace=torch.empty(16, dtype=torch.uint8, device=DEV))
+    assert e.value.code == -4
