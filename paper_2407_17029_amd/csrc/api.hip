@@ -86,7 +86,7 @@ FwdSpace carve_fwd(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T
 }
 
 struct BwdSpace {
-    float* scales; qblora_bf16 *At_x, *Bx, *U, *dU, *dUs; float* part;
+    float* scales; qblora_bf16 *At_x, *Bx, *U, *U_lo, *dU, *dU_lo, *dUs; float* part;
     int splits_a, splits_b;
     size_t bytes;
 };
@@ -98,7 +98,9 @@ BwdSpace carve_bwd(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T
         s.At_x = c.take<qblora_bf16>((size_t)ad->R * qw->d_in);
         s.Bx = c.take<qblora_bf16>((size_t)ad->R * qw->d_out);
         s.U = c.take<qblora_bf16>((size_t)T * ad->R);
+        s.U_lo = c.take<qblora_bf16>((size_t)T * ad->R);
         s.dU = c.take<qblora_bf16>((size_t)T * ad->R);
+        s.dU_lo = c.take<qblora_bf16>((size_t)T * ad->R);
         s.dUs = c.take<qblora_bf16>((size_t)T * ad->R);
         s.splits_a = grad_splits(T, qw->d_in);
         s.splits_b = grad_splits(T, qw->d_out);
@@ -269,21 +271,22 @@ int qblora_linear_bwd(const qblora_qweight* qw, const qblora_adapter* ad, const 
         du.qmode = 0;
         du.X2 = dY; du.ldx2 = qw->d_out; du.W2 = ws.Bx; du.ldw2 = qw->d_out; du.K2 = qw->d_out; du.div2 = 1;
         du.C = ws.dU; du.ldc = R; du.out_scale = ad->s; du.C2 = ws.dUs; du.c2_scale = 1.0f / (float)ad->lambda1;
+        du.C_lo = want_grads ? ws.dU_lo : nullptr;
         du.M = T; du.N = R;
         if ((rc = launch_gemm(du, st))) return rc;
         if (want_grads) {
             GemmDesc u{};
             u.qmode = 0;
             u.X2 = X; u.ldx2 = qw->d_in; u.W2 = ws.At_x; u.ldw2 = qw->d_in; u.K2 = qw->d_in; u.div2 = 1;
-            u.C = ws.U; u.ldc = R; u.out_scale = ad->s / (float)ad->lambda1; u.M = T; u.N = R;
+            u.C = ws.U; u.ldc = R; u.out_scale = ad->s / (float)ad->lambda1; u.M = T; u.N = R; u.C_lo = ws.U_lo;
             if ((rc = launch_gemm(u, st))) return rc;
             GradDesc ga{};
-            ga.L = X; ga.ldl = qw->d_in; ga.I = qw->d_in; ga.S = ws.dU; ga.lds = R; ga.J = R; ga.T = T;
+            ga.L = X; ga.ldl = qw->d_in; ga.I = qw->d_in; ga.S = ws.dU; ga.S_lo = ws.dU_lo; ga.lds = R; ga.J = R; ga.T = T;
             ga.part = ws.part; ga.splits = ws.splits_a; ga.out = dA; ga.pool = ad->lambda1;
             ga.out_scale = 1.0f / (float)ad->lambda1; ga.transpose_out = 0;
             if ((rc = launch_grad(ga, st))) return rc;
             GradDesc gb{};
-            gb.L = dY; gb.ldl = qw->d_out; gb.I = qw->d_out; gb.S = ws.U; gb.lds = R; gb.J = R; gb.T = T;
+            gb.L = dY; gb.ldl = qw->d_out; gb.I = qw->d_out; gb.S = ws.U; gb.S_lo = ws.U_lo; gb.lds = R; gb.J = R; gb.T = T;
             gb.part = ws.part; gb.splits = ws.splits_b; gb.out = dB; gb.pool = ad->lambda2;
             gb.out_scale = 1.0f; gb.transpose_out = 1;
             if ((rc = launch_grad(gb, st))) return rc;

@@ -78,7 +78,8 @@ struct GemmDesc {
     const qblora_bf16* X2; int64_t ldx2;
     const qblora_bf16* W2; int64_t ldw2; int K2; int div2;
     void* C; int64_t ldc; int out_f32;     // bf16 or fp32 output
-    qblora_bf16* C2; float c2_scale;       // optional second bf16 output = bf16(c2_scale * acc), same shape
+    qblora_bf16* C2; float c2_scale;       // optional second bf16 output = bf16(c2_scale * value), same shape
+    qblora_bf16* C_lo;                     // optional bf16 residual: bf16(value - bf16(value)), same shape
     float out_scale;
     int64_t M; int N;
 };
@@ -90,6 +91,7 @@ int launch_gemm(const GemmDesc& d, hipStream_t st);
 struct GradDesc {
     const qblora_bf16* L; int64_t ldl; int I;
     const qblora_bf16* S; int64_t lds; int J;
+    const qblora_bf16* S_lo;               // optional low-order part of S (S = S + S_lo, both bf16), same layout
     int64_t T;
     float* part; int splits;
     float* out; int pool; float out_scale; int transpose_out;

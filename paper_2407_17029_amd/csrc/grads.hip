@@ -8,7 +8,9 @@
 // `splits` workgroup slices so the launch fills the chip; the partial sums are written to scratch
 // and a second kernel adds them in a fixed order (deterministic), pools adjacent rows and applies
 // the scale.  Operand tiles are transposed in registers on their way into LDS so that each MFMA
-// lane reads 8 consecutive tokens of one feature as a single 16-byte word.
+// lane reads 8 consecutive tokens of one feature as a single 16-byte word.  The narrow operand is
+// produced by this library in fp32 and handed over as a bf16 pair (high part + residual); both parts
+// are contracted, so the gradients carry fp32-accumulation error only.
 #include "common.h"
 
 namespace qblora {
@@ -23,8 +25,11 @@ __device__ __forceinline__ int swz(int row, int chunk) {
 }
 
 __global__ __launch_bounds__(kThreads) void k_grad_partial(GradDesc d, int64_t slice_len) {
-    __shared__ __align__(16) unsigned char sL[2][BI * 128];
-    __shared__ __align__(16) unsigned char sS[2][BJ * 128];
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char (*sL)[BI * 128] = reinterpret_cast<unsigned char (*)[BI * 128]>(smem);
+    unsigned char (*sS)[BJ * 128] = reinterpret_cast<unsigned char (*)[BJ * 128]>(smem + 2 * BI * 128);
+    unsigned char (*sSlo)[BJ * 128] = reinterpret_cast<unsigned char (*)[BJ * 128]>(smem + 2 * BI * 128 + 2 * BJ * 128);
+    const bool has_lo = d.S_lo != nullptr;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int i0 = blockIdx.x * BI, j0 = blockIdx.y * BJ, z = blockIdx.z;
     const int64_t t_begin = (int64_t)z * slice_len;
@@ -48,7 +53,7 @@ __global__ __launch_bounds__(kThreads) void k_grad_partial(GradDesc d, int64_t s
     const int width = isL ? d.I : d.J;
     int col = (isL ? i0 : j0) + 4 * cg;
     if (col > width - 4) col = width - 4;          // clamped columns are never stored
-    uint2 reg[8];
+    uint2 reg[8], reg_lo[8];
 
     auto load_global = [&](int step) {
         const int64_t tb = t_begin + (int64_t)step * BT + 8 * tg;
@@ -56,16 +61,17 @@ __global__ __launch_bounds__(kThreads) void k_grad_partial(GradDesc d, int64_t s
         for (int q = 0; q < 8; ++q) {
             int64_t tt = tb + q;
             reg[q] = (tt < t_end) ? *reinterpret_cast<const uint2*>(src + tt * ld + col) : make_uint2(0, 0);
+            if (!isL && has_lo)
+                reg_lo[q] = (tt < t_end) ? *reinterpret_cast<const uint2*>(d.S_lo + tt * ld + col) : make_uint2(0, 0);
         }
     };
-    auto store_lds = [&](int buf) {
-        unsigned char* base = isL ? sL[buf] : sS[buf];
+    auto transpose_store = [&](const uint2 (&rg)[8], unsigned char* base) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             uint32_t h[8];
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                uint32_t w = (c < 2) ? reg[q].x : reg[q].y;
+                uint32_t w = (c < 2) ? rg[q].x : rg[q].y;
                 h[q] = (c & 1) ? (w >> 16) : (w & 0xffffu);
             }
             uint4 o;
@@ -74,15 +80,22 @@ __global__ __launch_bounds__(kThreads) void k_grad_partial(GradDesc d, int64_t s
             *reinterpret_cast<uint4*>(base + swz(4 * cg + c, tg)) = o;
         }
     };
+    auto store_lds = [&](int buf) {
+        transpose_store(reg, isL ? sL[buf] : sS[buf]);
+        if (!isL && has_lo) transpose_store(reg_lo, sSlo[buf]);
+    };
     auto compute = [&](int buf) {
         const int r = lane & 31, hi = lane >> 5;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             bf16x8 sf = *reinterpret_cast<const bf16x8*>(sS[buf] + swz(wj0 + r, ks * 2 + hi));
+            bf16x8 sf_lo = sf;
+            if (has_lo) sf_lo = *reinterpret_cast<const bf16x8*>(sSlo[buf] + swz(wj0 + r, ks * 2 + hi));
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
                 bf16x8 lf = *reinterpret_cast<const bf16x8*>(sL[buf] + swz(wi0 + b * 32 + r, ks * 2 + hi));
                 acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf, lf, acc[b], 0, 0, 0);
+                if (has_lo) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf_lo, lf, acc[b], 0, 0, 0);
             }
         }
     };
@@ -150,15 +163,19 @@ int grad_splits(int64_t T, int I) {
 }
 
 int launch_grad(const GradDesc& d, hipStream_t st) {
-    if (d.T <= 0) {
-        if (hipMemsetAsync(d.out, 0, sizeof(float) * (size_t)(d.I / d.pool) * d.J, st) != hipSuccess)
-            return QBLORA_ERR_LAUNCH;
-        return QBLORA_OK;
-    }
+    if (d.T <= 0) return QBLORA_ERR_SHAPE;      // the entry point handles the empty batch itself
     int64_t slice_len = (d.T + d.splits - 1) / d.splits;
     slice_len = (slice_len + BT - 1) / BT * BT;
     dim3 grid((d.I + BI - 1) / BI, (d.J + BJ - 1) / BJ, d.splits);
-    hipLaunchKernelGGL(k_grad_partial, grid, dim3(kThreads), 0, st, d, slice_len);
+    constexpr size_t smem = 2 * BI * 128 + 4 * BJ * 128;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_grad_partial),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+            return QBLORA_ERR_LAUNCH;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(k_grad_partial, grid, dim3(kThreads), smem, st, d, slice_len);
     int64_t total = (int64_t)(d.I / d.pool) * d.J;
     hipLaunchKernelGGL(k_grad_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, d);
     return launch_status();

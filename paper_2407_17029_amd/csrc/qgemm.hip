@@ -266,6 +266,14 @@ __global__ __launch_bounds__(kThreads) void k_qgemm(GemmDesc d) {
                     o.x = pack_bf16(v0, v1); o.y = pack_bf16(v2, v3);
                     *reinterpret_cast<uint2*>(reinterpret_cast<qblora_bf16*>(d.C) + m * d.ldc + n) = o;
                 }
+                if (d.C_lo) {
+                    uint2 h;
+                    h.x = pack_bf16(v0, v1); h.y = pack_bf16(v2, v3);
+                    uint2 o;
+                    o.x = pack_bf16(v0 - bf16_bits_to_float(h.x & 0xffffu), v1 - bf16_bits_to_float(h.x >> 16));
+                    o.y = pack_bf16(v2 - bf16_bits_to_float(h.y & 0xffffu), v3 - bf16_bits_to_float(h.y >> 16));
+                    *reinterpret_cast<uint2*>(d.C_lo + m * d.ldc + n) = o;
+                }
                 if (d.C2) {
                     uint2 o;
                     o.x = pack_bf16(v0 * d.c2_scale, v1 * d.c2_scale);
