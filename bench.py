@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the adapted quantized linear layer hot path on one MI355X.
+
+One step = one pass of the whole path over one synthetic batch of the LLaMA-7B attention
+projection workload (T = 8192 tokens, W 4096x4096, 4-bit block 64, adapter rank 64, lambda 2):
+block-wise quantize -> adapted forward -> backward (dX, dA, dB) -> tile product -> INT4 merge.
+All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+value      = algorithmic fwd+bwd flops (4*T*D_in*D_out + 6*T*r*(D_in+D_out)) / wall time of the
+             whole step, in TFLOP/s.
+roofline   = the forward dequantize-and-contract kernel alone, timed with HIP events recorded by
+             the library around that one launch, against the dense bf16 MFMA peak.
+cpu_baseline = the fp64 CPU oracle timed on a bounded token sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the forward GEMM from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see the
+# profiles/ summaries); None until measured for the workload.
+MEASURED_TRAFFIC_BYTES = {"llama7b_attn": None}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llama7b_attn")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (no collectives are part of it); run with --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2407_17029_amd import binding as qb
+    from paper_2407_17029_amd import synth
+
+    wl = synth.WORKLOADS[args.workload]
+    if len(wl.projections) != 1:
+        print("bench.py: the timed workload is a single projection", file=sys.stderr)
+        return 2
+    proj = wl.projections[0]
+    T, d_out, d_in, lam, r = wl.tokens, proj.d_out, proj.d_in, wl.lam, wl.rank
+    R = lam * r
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    qb.lib()
+
+    L = synth.make_layer(wl.seed, T, d_out, d_in, R, lam, lam)
+    cb = synth.codebook_nf4_style()
+
+    def bf16_dev(bits):
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
+
+    W = torch.from_numpy(L.W).to(dev)
+    X, dY = bf16_dev(L.X), bf16_dev(L.dY)
+    ad = qb.Adapter(bf16_dev(L.A), bf16_dev(L.B), lam, lam, wl.s)
+    scale_mode = qb.SCALES_E4M3_GROUPED if wl.scale_mode else qb.SCALES_FP32
+    qw = qb.qblora_quantize_blockwise(W, wl.block, qb.QUANT_ABSMAX_CODEBOOK, cb, scale_mode)
+    Y = torch.empty((T, d_out), dtype=torch.bfloat16, device=dev)
+    dX = torch.empty((T, d_in), dtype=torch.bfloat16, device=dev)
+    dA = torch.empty((d_in // lam, R), dtype=torch.float32, device=dev)
+    dB = torch.empty((R, d_out // lam), dtype=torch.float32, device=dev)
+    H = torch.empty((d_in // lam, d_out // lam), dtype=torch.float32, device=dev)
+    nbytes = max(qb.qblora_linear_fwd_workspace_bytes(qw, ad, T), qb.qblora_linear_bwd_workspace_bytes(qw, ad, T))
+    ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+    merged = qb.qablora_merge_quantize(qw, qb.qblora_tile_product(ad, d_in, d_out, H, ws), lam, lam, wl.s,
+                                       qb.MERGE_REQUANT_MINMAX)
+
+    def step():
+        qb.qblora_quantize_blockwise(W, wl.block, qb.QUANT_ABSMAX_CODEBOOK, cb, scale_mode, out=qw)
+        qb.qblora_linear_fwd(qw, ad, X, Y, ws)
+        qb.qblora_linear_bwd(qw, ad, X, dY, True, True, dX, dA, dB, ws)
+        qb.qblora_tile_product(ad, d_in, d_out, H, ws)
+        qb.qablora_merge_quantize(qw, H, lam, lam, wl.s, qb.MERGE_REQUANT_MINMAX, out=merged)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # per-kernel HIP events, recorded by the library on the launch stream around one kernel each
+    kinds = {"fwd_gemm": qb.PROFILE_FWD_GEMM, "bwd_gemm": qb.PROFILE_BWD_GEMM, "merge": qb.PROFILE_MERGE,
+             "quantize": qb.PROFILE_QUANTIZE}
+    events = {k: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                  for _ in range(args.steps)] for k in kinds}
+    for pairs in events.values():
+        for a, b in pairs:
+            a.record(); b.record()          # creates the native handles
+    torch.cuda.synchronize()
+
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        for k, which in kinds.items():
+            qb.qblora_profile_events(which, *events[k][i])
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    for which in kinds.values():
+        qb.qblora_profile_events(which, None, None)
+
+    kernel_ms = {k: float(np.mean([a.elapsed_time(b) for a, b in pairs])) for k, pairs in events.items()}
+    ms_per_step = elapsed * 1e3 / args.steps
+    flops_step = 4.0 * T * d_in * d_out + 6.0 * T * r * (d_in + d_out)
+    value = flops_step / (ms_per_step * 1e-3) / 1e12
+
+    n_w = d_in * d_out
+    fwd_kernel_flops = 2.0 * T * d_in * d_out + 2.0 * T * R * d_out / lam
+    bwd_kernel_flops = 2.0 * T * d_in * d_out + 2.0 * T * R * d_in / lam
+    merge_bytes = n_w * (0.5 + (1 / 64 + 4 / (64 * 256) if wl.scale_mode else 4 / 64) + 4.0 / (lam * lam) + 0.5 + 8 / 64)
+    quant_bytes = n_w * (4 + 0.5 + 4 / 64)
+    achieved = fwd_kernel_flops / (kernel_ms["fwd_gemm"] * 1e-3) / 1e12
+    traffic = MEASURED_TRAFFIC_BYTES.get(wl.name)
+    out = {
+        "metric": "fused quantized-linear+BLoRA fwd+bwd TFLOP/s",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: T={T} tokens, W {d_out}x{d_in} 4-bit block {wl.block}, adapter rank {r}, "
+                               f"lambda {lam} (inner rank {R}), s={wl.s}",
+                   "step": "quantize + forward + backward(dX,dA,dB) + tile product + INT4 requantizing merge"},
+        "tokens_per_s": round(T / (ms_per_step * 1e-3), 1),
+        "pct_of_bf16_mfma_peak": round(100.0 * value / MFMA_BF16_PEAK_TFLOPS, 2),
+        "roofline": {"kernel": "k_qgemm (forward dequantize-and-contract)", "bound": "mfma",
+                     "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic,
+                     "avg_kernel_ms": round(kernel_ms["fwd_gemm"], 4)},
+        "kernels": {
+            "bwd_gemm": {"bound": "mfma", "avg_kernel_ms": round(kernel_ms["bwd_gemm"], 4),
+                         "achieved": round(bwd_kernel_flops / (kernel_ms["bwd_gemm"] * 1e-3) / 1e12, 2),
+                         "unit": "TFLOP/s",
+                         "frac": round(bwd_kernel_flops / (kernel_ms["bwd_gemm"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)},
+            "merge_requant": {"bound": "hbm", "avg_kernel_ms": round(kernel_ms["merge"], 4),
+                              "achieved": round(merge_bytes / (kernel_ms["merge"] * 1e-3) / 1e9, 1), "unit": "GB/s",
+                              "frac": round(merge_bytes / (kernel_ms["merge"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+            "quantize": {"bound": "hbm", "avg_kernel_ms": round(kernel_ms["quantize"], 4),
+                         "achieved": round(quant_bytes / (kernel_ms["quantize"] * 1e-3) / 1e9, 1), "unit": "GB/s",
+                         "frac": round(quant_bytes / (kernel_ms["quantize"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        ts = min(args.cpu_sample_tokens, T)
+        rows = synth.sample_rows(T, ts, wl.seed)
+        Xs, dYs = np.ascontiguousarray(L.X[rows]), np.ascontiguousarray(L.dY[rows])
+        c0 = time.perf_counter()
+        codes, absmax = oracle.quantize_codebook(L.W, wl.block, cb)
+        scales = absmax
+        if wl.scale_mode:
+            sc, stp, mid = oracle.scales_double_quantize(absmax.reshape(-1), 256)
+            scales = oracle.scales_double_dequantize(sc, stp, mid, 256).reshape(absmax.shape)
+        Wt = oracle.dequantize(codes, scales, None, cb, wl.block, 2)
+        c1 = time.perf_counter()
+        oracle.forward(Wt, Xs, L.A, L.B, lam, lam, wl.s)
+        oracle.backward(Wt, Xs, dYs, L.A, L.B, lam, lam, wl.s)
+        c2 = time.perf_counter()
+        Ho = oracle.tile_product(L.A, L.B).astype(np.float32)
+        oracle.merge_requant(codes, scales, None, cb, Ho, wl.block, lam, lam, wl.s)
+        c3 = time.perf_counter()
+        one_off = (c1 - c0) + (c3 - c2)
+        est_full = one_off + (c2 - c1) * (T / ts)
+        out["cpu_baseline"] = {
+            "value": round(flops_step / est_full / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.get_threads(),
+            "kind": "oracle",
+            "sample": f"fp64 oracle: quantize+dequantize+tile product+merge in full ({one_off:.2f} s), forward+backward "
+                      f"on {ts} of {T} token rows ({c2 - c1:.2f} s), token-proportional part scaled by {T / ts:.0f}x "
+                      f"(extrapolated full step {est_full:.1f} s)"}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -113,7 +113,8 @@ typedef struct qblora_adapter {
  *             (scale - mid)/step saturating at 448 (step = 0 and codes 0 when all equal).
  *   out       host struct whose device pointers the caller has filled in (codes, scales, and
  *             beta or scale_codes/scale_step/scale_mid as the mode needs); the call fills the
- *             scalar fields and the codebook and overwrites the device buffers.
+ *             scalar fields and the codebook and overwrites the device buffers.  The absmax
+ *             quantizer sets out->beta to NULL (beta = 0).
  * All fp32 arithmetic is single IEEE operations in the order written above, so the outputs
  * are reproducible bit for bit.  d_in must be a multiple of `block`; block must be 64.
  */
@@ -188,6 +189,21 @@ int qblora_tile_product(const qblora_adapter* ad, int32_t d_in, int32_t d_out, f
  */
 int qablora_merge_quantize(const qblora_qweight* base, const float* H, int32_t lambda1, int32_t lambda2,
                            float s, int32_t mode, qblora_qweight* out, void* stream);
+
+/*
+ * Measurement hook.  Registers a pair of caller-created hipEvent_t (passed as void*) that the next
+ * calls record on their stream immediately before and after ONE kernel launch, so that a
+ * benchmark can time that kernel alone while running the whole path:
+ *   QBLORA_PROFILE_FWD_GEMM   the dequantize-and-contract kernel of qblora_linear_fwd
+ *   QBLORA_PROFILE_BWD_GEMM   the transposed dequantize-and-contract kernel of qblora_linear_bwd
+ *   QBLORA_PROFILE_MERGE      the requantizing (or beta-shift) kernel of qablora_merge_quantize
+ *   QBLORA_PROFILE_QUANTIZE   the code-selection kernel of qblora_quantize_blockwise
+ * Passing NULL for both events unregisters the slot.  Process-wide state, not thread safe; has no
+ * effect on results.
+ */
+enum { QBLORA_PROFILE_FWD_GEMM = 0, QBLORA_PROFILE_BWD_GEMM = 1, QBLORA_PROFILE_MERGE = 2,
+       QBLORA_PROFILE_QUANTIZE = 3 };
+int qblora_profile_events(int32_t which, void* start_event, void* stop_event);
 
 /* Static description of an error code. */
 const char* qblora_strerror(int code);

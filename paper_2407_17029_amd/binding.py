@@ -24,7 +24,9 @@ MERGE_BETA_SHIFT, MERGE_REQUANT_MINMAX = 0, 1
 EXPORTS = ["qblora_quantize_blockwise", "qblora_dequantize_bf16", "qblora_linear_fwd_workspace_bytes",
            "qblora_linear_bwd_workspace_bytes", "qblora_linear_fwd", "qblora_linear_bwd",
            "qblora_tile_product_workspace_bytes", "qblora_tile_product", "qablora_merge_quantize",
-           "qblora_strerror"]
+           "qblora_strerror", "qblora_profile_events"]
+
+PROFILE_FWD_GEMM, PROFILE_BWD_GEMM, PROFILE_MERGE, PROFILE_QUANTIZE = 0, 1, 2, 3
 
 
 class CQWeight(C.Structure):
@@ -74,8 +76,20 @@ def lib():
                                           C.c_void_p]
         L.qablora_merge_quantize.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_int32,
                                              C.c_void_p, C.c_void_p]
+        L.qblora_profile_events.argtypes = [C.c_int32, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
+
+
+def qblora_profile_events(which: int, start: "torch.cuda.Event" = None, stop: "torch.cuda.Event" = None) -> None:
+    """Register (or with None, unregister) a pair of timing events recorded around one kernel.
+
+    The events must have been created with enable_timing=True and recorded once already so that
+    their native handles exist.
+    """
+    a = None if start is None else C.c_void_p(start.cuda_event)
+    b = None if stop is None else C.c_void_p(stop.cuda_event)
+    _check(lib().qblora_profile_events(which, a, b), "qblora_profile_events")
 
 
 def strerror(code: int) -> str:
@@ -149,10 +163,19 @@ def _adapter_ref(ad):
 
 
 def qblora_quantize_blockwise(W: torch.Tensor, block: int = 64, quantizer: int = QUANT_ABSMAX_CODEBOOK,
-                              codebook=None, scale_mode: int = SCALES_FP32) -> QWeight:
+                              codebook=None, scale_mode: int = SCALES_FP32, out: QWeight = None) -> QWeight:
     assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and W.dim() == 2
     d_out, d_in = W.shape
     dev = W.device
+    if out is not None:                      # reuse the caller's buffers
+        cb = np.zeros(16, np.float32) if codebook is None else np.ascontiguousarray(codebook, np.float32)
+        s = out.c_struct()
+        cb_ptr = None if codebook is None else cb.ctypes.data_as(C.c_void_p)
+        rc = lib().qblora_quantize_blockwise(_ptr(W), d_out, d_in, block, quantizer, cb_ptr, scale_mode,
+                                             C.byref(s), _stream())
+        _check(rc, "qblora_quantize_blockwise")
+        out.absorb(s)
+        return out
     nblk = d_out * (d_in // max(block, 1))
     codes = torch.empty((d_out, d_in // 2), dtype=torch.uint8, device=dev)
     scales = torch.empty((d_out, d_in // max(block, 1)), dtype=torch.float32, device=dev)

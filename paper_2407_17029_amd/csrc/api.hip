@@ -111,6 +111,18 @@ BwdSpace carve_bwd(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T
     return s;
 }
 
+hipEvent_t g_events[4][2] = {};
+
+struct ScopedEvents {
+    int which; hipStream_t st;
+    ScopedEvents(int w, hipStream_t s) : which(w), st(s) {
+        if (g_events[which][0]) (void)hipEventRecord(g_events[which][0], st);
+    }
+    ~ScopedEvents() {
+        if (g_events[which][1]) (void)hipEventRecord(g_events[which][1], st);
+    }
+};
+
 __global__ void k_fill_zero(float* p, int64_t n) {
     int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i < n) p[i] = 0.0f;
@@ -141,6 +153,14 @@ const char* qblora_strerror(int code) {
     }
 }
 
+int qblora_profile_events(int32_t which, void* start_event, void* stop_event) {
+    if (which < 0 || which > 3) return QBLORA_ERR_SHAPE;
+    if ((start_event == nullptr) != (stop_event == nullptr)) return QBLORA_ERR_NULL;
+    g_events[which][0] = static_cast<hipEvent_t>(start_event);
+    g_events[which][1] = static_cast<hipEvent_t>(stop_event);
+    return QBLORA_OK;
+}
+
 int qblora_quantize_blockwise(const float* W, int32_t d_out, int32_t d_in, int32_t block, int32_t quantizer,
                               const float* codebook, int32_t scale_mode, qblora_qweight* out, void* stream) {
     if (!W || !out) return QBLORA_ERR_NULL;
@@ -167,12 +187,17 @@ int qblora_quantize_blockwise(const float* W, int32_t d_out, int32_t d_in, int32
     out->scale_group = 256;
     if (quantizer == QBLORA_QUANT_MINMAX_INT4) {
         for (int j = 0; j < 16; ++j) out->codebook[j] = (float)j;
+        ScopedEvents ev(QBLORA_PROFILE_QUANTIZE, st);
         return launch_quantize_minmax(W, d_out, d_in, out->codes, out->scales, out->beta, st);
     }
     Codebook cb;
     for (int j = 0; j < 16; ++j) { cb.c[j] = codebook[j]; out->codebook[j] = codebook[j]; }
     out->beta = nullptr;
-    int rc = launch_quantize_codebook(W, d_out, d_in, cb, out->codes, out->scales, st);
+    int rc;
+    {
+        ScopedEvents ev(QBLORA_PROFILE_QUANTIZE, st);
+        rc = launch_quantize_codebook(W, d_out, d_in, cb, out->codes, out->scales, st);
+    }
     if (rc) return rc;
     if (scale_mode == QBLORA_SCALES_E4M3_GROUPED)
         rc = launch_scales_double_quantize(out->scales, n_blocks(out), out->scale_group, out->scale_codes,
@@ -230,6 +255,7 @@ int qblora_linear_fwd(const qblora_qweight* qw, const qblora_adapter* ad, const 
     g.X1 = X; g.ldx1 = qw->d_in;
     g.codes = qw->codes; g.beta = qw->beta; g.d_out = qw->d_out; g.d_in = qw->d_in; g.cb = codebook_of(qw);
     g.C = Y; g.ldc = qw->d_out; g.out_scale = 1.0f; g.M = T; g.N = qw->d_out;
+    ScopedEvents ev(QBLORA_PROFILE_FWD_GEMM, st);
     return launch_gemm(g, st);
 }
 
@@ -299,6 +325,7 @@ int qblora_linear_bwd(const qblora_qweight* qw, const qblora_adapter* ad, const 
     g.X1 = dY; g.ldx1 = qw->d_out;
     g.codes = qw->codes; g.beta = qw->beta; g.d_out = qw->d_out; g.d_in = qw->d_in; g.cb = codebook_of(qw);
     g.C = dX; g.ldc = qw->d_in; g.out_scale = 1.0f; g.M = T; g.N = qw->d_in;
+    ScopedEvents ev(QBLORA_PROFILE_BWD_GEMM, st);
     return launch_gemm(g, st);
 }
 
@@ -362,9 +389,11 @@ int qablora_merge_quantize(const qblora_qweight* base, const float* H, int32_t l
             hipMemcpyAsync(out->scales, base->scales, sizeof(float) * (size_t)n_blocks(base),
                            hipMemcpyDeviceToDevice, st) != hipSuccess)
             return QBLORA_ERR_LAUNCH;
+        ScopedEvents ev(QBLORA_PROFILE_MERGE, st);
         return launch_merge_beta_shift(d, st);
     }
     for (int j = 0; j < 16; ++j) out->codebook[j] = (float)j;
+    ScopedEvents ev(QBLORA_PROFILE_MERGE, st);
     return launch_merge_requant(d, st);
 }
 
