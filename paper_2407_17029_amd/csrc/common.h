@@ -84,6 +84,8 @@ struct GemmDesc {
     int64_t M; int N;
 };
 int launch_gemm(const GemmDesc& d, hipStream_t st);
+// the quantized segments (qmode 1, 2) with a 4-wave 256x256 tile; called by launch_gemm
+int launch_qlinear(const GemmDesc& d, hipStream_t st);
 
 // Token-contraction GEMM with split-T partials:  part[z][i][j] = sum_{t in slice z} L[t,i] * S[t,j]
 // followed by the reduction  out = sum_z part, pooled over `pool` adjacent i (scaled by out_scale),

@@ -1,0 +1,415 @@
+// Dequantize-and-contract kernel of the adapted layer for gfx950 (Alg. 1 qblora_forward:
+// W_tilde = dequantize(...), x @ W_tilde, plus the adapter term; and its transpose for the
+// backward pass with respect to the activations).
+//
+//   C[M,N] = X1[M,K1] * Wq^T  +  X2[M,K2] * W2[N/div2, K2]^T
+//
+// Segment 1 reads the 4-bit codes and block scales of the frozen base weight from HBM, rebuilds
+// bf16 weights (Eq. 1: c[code]*alpha (+beta), fp32 then round-to-nearest-even) straight into an
+// LDS tile and feeds them to v_mfma_f32_32x32x16_bf16 with fp32 accumulation; the dequantized
+// weight never exists in HBM.  QMODE 1 contracts along d_in (forward); QMODE 2 uses the same
+// stored tile transposed and contracts along d_out (backward w.r.t. activations) -- there the
+// scale varies along the contraction index, which is why it is applied while building the tile
+// and not to the accumulator.  Segment 2 is a plain bf16 K-extension: the adapter's rank-R product
+// rides in the same accumulators as R extra contraction steps (forward: X2 = s*U, W2 = B^T with
+// output row n using row n/lambda2, i.e. repeat_interleave; backward: X2 = dU/lambda1, W2 = A with
+// row k/lambda1).
+//
+// Shape of the computation on a CU: one workgroup of 256 threads (4 wave64, one per SIMD) owns a
+// 256 x 256 output tile; every wave owns a 128 x 128 quadrant, i.e. 16 MFMA accumulators of
+// 32 x 32 (256 registers), so one k-step of 64 issues 64 MFMAs against 32 16-byte LDS fragment
+// reads per wave.  Both operand tiles live in LDS as [row][64 k] bf16 (128 bytes per row) with the
+// 16-byte chunks of a row XOR-swizzled by (row ^ row>>3) & 7, double buffered, one barrier per
+// k-step.  Activation tiles (and the bf16 tiles of segment 2) go from global memory directly into
+// LDS (global_load_lds, 16 bytes per lane; the swizzle is applied by choosing which global chunk a
+// lane fetches).  Codes and scales are fetched two k-steps ahead into registers and dequantized
+// between the MFMAs of the step before they are needed.
+// The weight tile is the MFMA A operand and the token tile the B operand, so a lane ends up with 4
+// consecutive output features of one token and stores them as one 8-byte word.
+#include "common.h"
+
+namespace qblora {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int BM = 256, BN = 256, kBK = 64;
+constexpr int kTileBytes = 256 * 128;                       // one operand tile: 256 rows x 128 bytes
+
+__device__ __align__(16) const uint32_t g_zero_chunk[4] = {0u, 0u, 0u, 0u};
+
+__device__ __forceinline__ int swz(int row, int chunk) {
+    return row * 128 + (((chunk ^ row ^ (row >> 3)) & 7) << 4);
+}
+
+// One wave-wide global -> LDS copy: lane i fetches the 16 bytes at base + offset_i and they land at
+// lds_base + 16*i (M0 carries the wave-uniform LDS byte address).  Written as assembly so that the
+// compiler's wait-count bookkeeping does not tie later LDS accesses to these copies; every copy is
+// completed by the explicit vmcnt(0) in front of the barrier that publishes the tile.
+__device__ __forceinline__ void copy16_to_lds(const void* src, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(lds_base), "v"(src) : "memory");
+}
+__device__ __forceinline__ void copy16_to_lds(const void* uniform_base, uint32_t lane_offset, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_base), "v"(lane_offset), "s"(uniform_base) : "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
+}
+
+// codes / scales of one k-step held in registers
+template <int QMODE>
+struct Staged {
+    uint32_t cw[8];          // QMODE 1: the 64 codes of this thread's row; QMODE 2: 8 codes of each of 8 rows
+    float sc[QMODE == 2 ? 8 : 1];
+    float be[QMODE == 2 ? 8 : 1];
+};
+
+template <int QMODE, bool BETA>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_qlinear(GemmDesc d) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ float lut[16];                                   // code values: a distinct LDS object, so the
+                                                                // compiler may move table reads across tile stores
+    unsigned char* sX = smem;                                   // 2 tiles
+    unsigned char* sW = sX + 2 * kTileBytes;                    // 2 tiles
+
+    // Every field of the descriptor the loop touches is copied into a local first: the copies in
+    // the loop are assembly statements that clobber memory, and values must not be re-read around them.
+    const int64_t M = d.M;
+    const int N = d.N, d_in = d.d_in, d_out = d.d_out, K2 = d.K2, div2 = d.div2;
+    const qblora_bf16* const X1 = d.X1; const int64_t ldx1 = d.ldx1;
+    const qblora_bf16* const X2 = d.X2; const int64_t ldx2 = d.ldx2;
+    const qblora_bf16* const W2 = d.W2; const int64_t ldw2 = d.ldw2;
+    const uint8_t* const codes = d.codes;
+    const float* const scales = d.scales;
+    const float* const beta = d.beta;
+    qblora_bf16* const C = reinterpret_cast<qblora_bf16*>(d.C);
+    const int64_t ldc = d.ldc;
+    const float out_scale = d.out_scale;
+
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm0 = (wave & 1) * 128, wn0 = (wave >> 1) * 128;
+
+    // ---- tile assignment: XCD-contiguous, grouped along tokens ---------------------------------
+    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (N + BN - 1) / BN;
+    const int ntiles = tiles_m * tiles_n;
+    int L = blockIdx.x;
+    if ((ntiles & 7) == 0) L = (blockIdx.x & 7) * (ntiles >> 3) + (blockIdx.x >> 3);
+    constexpr int GM = 4;
+    const int in_group = GM * tiles_n;
+    const int first_m = (L / in_group) * GM;
+    const int gsize = min(tiles_m - first_m, GM);
+    const int mt = first_m + (L % in_group) % gsize, nt = (L % in_group) / gsize;
+    const int64_t m0 = (int64_t)mt * BM;
+    const int n0 = nt * BN;
+
+    if (t < 16) lut[t] = d.cb.c[t];
+
+    const int K1 = QMODE == 1 ? d_in : d_out;
+    const int steps1 = K1 / kBK, steps2 = (K2 + kBK - 1) / kBK;
+    const int nsteps = steps1 + steps2;
+    const int bpr = d_in / kBlock;                // blocks per stored weight row
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
+
+    // ---- direct global -> LDS copies -------------------------------------------------------------
+    // Wave w fills rows 64w .. 64w+63 of a tile with 8 copies of 8 rows each.  In copy i, lane l
+    // lands on row 64w + 8i + (l>>3), physical chunk l&7, which must hold logical chunk
+    // (l&7) ^ swizzle(row); with row&7 = l>>3 and (row>>3)&7 = i that is (l&7) ^ (l>>3) ^ i.
+    const int crow = lane >> 3;
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem) + wave * 64 * 128);
+    // CHECK_K: chunks at or beyond K are fetched from a zero constant instead (K-extension only)
+    auto copy_tile = [&](const bool check_k, const qblora_bf16* src, int64_t ld, int64_t row_base, int64_t row_max,
+                         int div, int K, int k0, uint32_t tile_off) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            int64_t row = row_base + wave * 64 + i * 8 + crow;
+            row = row > row_max ? row_max : row;
+            if (div != 1) row = (int64_t)((uint32_t)row / (uint32_t)div);      // only weight rows (< 2^31) are divided
+            const int k = k0 + (((lane & 7) ^ crow ^ i) << 3);
+            const qblora_bf16* p = src + row * ld + k;
+            if (check_k)
+                p = (k < K) ? p : reinterpret_cast<const qblora_bf16*>(g_zero_chunk);
+            copy16_to_lds(p, lds0 + tile_off + i * 8 * 128);
+        }
+    };
+
+    // ---- codes / scales -> registers -------------------------------------------------------------
+    int qrow = 0, qcol = 0;
+    if constexpr (QMODE == 1) {
+        qrow = n0 + t;                               // this thread's stored weight row
+        if (qrow > N - 1) qrow = N - 1;
+    } else {
+        qcol = n0 + 8 * (t & 31);                    // this thread's 8 stored columns (k of the layer)
+        if (qcol > N - 8) qcol = N - 8;
+    }
+    auto load_staged = [&](Staged<QMODE>& s, int step) __attribute__((always_inline)) {
+        const int k0 = step * kBK;
+        if constexpr (QMODE == 1) {
+            const uint4* p = reinterpret_cast<const uint4*>(codes + (int64_t)qrow * (d_in / 2) + k0 / 2);
+            uint4 v0 = p[0], v1 = p[1];
+            s.cw[0] = v0.x; s.cw[1] = v0.y; s.cw[2] = v0.z; s.cw[3] = v0.w;
+            s.cw[4] = v1.x; s.cw[5] = v1.y; s.cw[6] = v1.z; s.cw[7] = v1.w;
+            const int64_t blk = (int64_t)qrow * bpr + step;
+            s.sc[0] = scales[blk];
+            if constexpr (BETA) s.be[0] = beta[blk];
+        } else {
+            const int nb = k0 + 8 * (t >> 5);        // 8 stored rows (contraction index)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int64_t n = nb + i;
+                s.cw[i] = *reinterpret_cast<const uint32_t*>(codes + n * (d_in / 2) + qcol / 2);
+                const int64_t blk = n * bpr + qcol / kBlock;
+                s.sc[i] = scales[blk];
+                if constexpr (BETA) s.be[i] = beta[blk];
+            }
+        }
+    };
+
+    // ---- dequantize one staged k-step into a weight tile ------------------------------------------
+    // Piece p (0..7) of a k-step is 8 elements per thread and ends in one 16-byte LDS store:
+    // QMODE 1: the 8 codes of dword p of this thread's row -> chunk p of LDS row t;
+    // QMODE 2: column p of this thread's 8x8 patch (8 contraction rows) -> LDS row 8*kg+p, chunk ng.
+    auto dequant_piece = [&](const Staged<QMODE>& s, unsigned char* tile, int p) __attribute__((always_inline)) {
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if constexpr (QMODE == 1) {
+                const float c = lut[(s.cw[p] >> (4 * j)) & 15];
+                v[j] = BETA ? __fmaf_rn(c, s.sc[0], s.be[0]) : __fmul_rn(c, s.sc[0]);
+            } else {
+                const float c = lut[(s.cw[j] >> (4 * p)) & 15];
+                v[j] = BETA ? __fmaf_rn(c, s.sc[j], s.be[j]) : __fmul_rn(c, s.sc[j]);
+            }
+        }
+        uint4 o;
+        o.x = pack_bf16(v[0], v[1]); o.y = pack_bf16(v[2], v[3]);
+        o.z = pack_bf16(v[4], v[5]); o.w = pack_bf16(v[6], v[7]);
+        if constexpr (QMODE == 1) *reinterpret_cast<uint4*>(tile + swz(t, p)) = o;
+        else *reinterpret_cast<uint4*>(tile + swz(8 * (t & 31) + p, t >> 5)) = o;
+    };
+    auto dequant_store = [&](const Staged<QMODE>& s, unsigned char* tile) __attribute__((always_inline)) {
+#pragma unroll
+        for (int p = 0; p < 8; ++p) dequant_piece(s, tile, p);
+    };
+
+    // ---- 64 MFMAs of one k-step --------------------------------------------------------------------
+    const int r = lane & 31, hi = lane >> 5;
+    auto compute = [&](const unsigned char* bx, const unsigned char* bw) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8 wf[4], xf[4];
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+                wf[a] = *reinterpret_cast<const bf16x8*>(bw + swz(wn0 + a * 32 + r, ks * 2 + hi));
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                xf[b] = *reinterpret_cast<const bf16x8*>(bx + swz(wm0 + b * 32 + r, ks * 2 + hi));
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[a], xf[b], acc[a][b], 0, 0, 0);
+        }
+    };
+    // Steady-state step: the 64 MFMAs on (bx, bw) with the dequantization of the next weight tile
+    // (st -> bw_next) software-pipelined between them.  A wave runs alone on its SIMD, so nothing hides
+    // an LDS round trip but its own MFMAs: the step is cut into 8 slices of 8 MFMAs (about 256 cycles),
+    // and every LDS read is issued one slice before its result is used.  Slice h: finish piece h-1
+    // (scale, pack, store), issue the table reads of piece h, extract the table offsets of piece h+1,
+    // issue half of the fragment reads of the next quarter, 8 MFMAs.  Scheduling barriers keep work
+    // from leaving its slice; group barriers inside a slice spread it between the MFMAs.
+    auto table_offsets = [&](const Staged<QMODE>& s, int p, uint32_t (&li)[8]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t w = QMODE == 1 ? s.cw[p] : s.cw[j];
+            const int nib = QMODE == 1 ? j : p;
+            li[j] = nib == 0 ? ((w << 2) & 0x3cu) : ((w >> (4 * nib - 2)) & 0x3cu);
+        }
+    };
+    auto finish_piece = [&](const Staged<QMODE>& s, int p, const float (&lv)[8], unsigned char* tile)
+        __attribute__((always_inline)) {
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int si = QMODE == 1 ? 0 : j;
+            v[j] = BETA ? __fmaf_rn(lv[j], s.sc[si], s.be[si]) : __fmul_rn(lv[j], s.sc[si]);
+        }
+        uint4 o;
+        o.x = pack_bf16(v[0], v[1]); o.y = pack_bf16(v[2], v[3]);
+        o.z = pack_bf16(v[4], v[5]); o.w = pack_bf16(v[6], v[7]);
+        if constexpr (QMODE == 1) *reinterpret_cast<uint4*>(tile + swz(t, p)) = o;
+        else *reinterpret_cast<uint4*>(tile + swz(8 * (t & 31) + p, t >> 5)) = o;
+    };
+    auto compute_dequant = [&](const unsigned char* bx, const unsigned char* bw, const Staged<QMODE>& s,
+                               unsigned char* bw_next) __attribute__((always_inline)) {
+        bf16x8 wf[2][4], xf[2][4];
+        float lv[2][8];
+        uint32_t li[2][8];
+#pragma unroll
+        for (int a = 0; a < 4; ++a) wf[0][a] = *reinterpret_cast<const bf16x8*>(bw + swz(wn0 + a * 32 + r, hi));
+#pragma unroll
+        for (int b = 0; b < 4; ++b) xf[0][b] = *reinterpret_cast<const bf16x8*>(bx + swz(wm0 + b * 32 + r, hi));
+        table_offsets(s, 0, li[0]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int h = 0; h < 8; ++h) {
+            const int ks = h >> 1, half = h & 1, cur = ks & 1, nxt = cur ^ 1;
+            if (h >= 1) finish_piece(s, h - 1, lv[(h - 1) & 1], bw_next);
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                lv[h & 1][j] = *reinterpret_cast<const float*>(reinterpret_cast<const unsigned char*>(lut) + li[h & 1][j]);
+            if (h < 7) table_offsets(s, h + 1, li[(h + 1) & 1]);
+            if (ks < 3) {
+                if (half == 0) {
+#pragma unroll
+                    for (int a = 0; a < 4; ++a)
+                        wf[nxt][a] = *reinterpret_cast<const bf16x8*>(bw + swz(wn0 + a * 32 + r, (ks + 1) * 2 + hi));
+                } else {
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        xf[nxt][b] = *reinterpret_cast<const bf16x8*>(bx + swz(wm0 + b * 32 + r, (ks + 1) * 2 + hi));
+                }
+            }
+#pragma unroll
+            for (int a = 2 * half; a < 2 * half + 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][a], xf[cur][b], acc[a][b], 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);       // vector ALU
+                if (i < 4) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);   // LDS reads
+                if (i == 3) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // the LDS store of the finished piece
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        finish_piece(s, 7, lv[1], bw_next);
+    };
+
+    // Segment-1 activation tiles: per-lane byte offsets relative to the tile's first row are fixed for
+    // the whole kernel, the uniform base walks along k.
+    uint32_t xoff[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        int64_t lrow = wave * 64 + i * 8 + crow;
+        if (m0 + lrow > M - 1) lrow = M - 1 - m0;
+        xoff[i] = (uint32_t)(lrow * ldx1 * 2) + ((((lane & 7) ^ crow ^ i)) << 4);
+    }
+    const qblora_bf16* const x1_tile = X1 + m0 * ldx1;
+    auto issue_x1 = [&](int step, int buf) __attribute__((always_inline)) {
+        const qblora_bf16* base = x1_tile + step * kBK;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) copy16_to_lds(base, xoff[i], lds0 + buf * kTileBytes + i * 8 * 128);
+    };
+    auto issue_copies = [&](int step, int buf) __attribute__((always_inline)) {
+        if (step < steps1) {
+            issue_x1(step, buf);
+        } else {
+            const int k0 = (step - steps1) * kBK;
+            copy_tile(true, X2, ldx2, m0, M - 1, 1, K2, k0, buf * kTileBytes);
+            copy_tile(true, W2, ldw2, n0, N - 1, div2, K2, k0, (2 + buf) * kTileBytes);
+        }
+    };
+    auto copies_landed = [&]() __attribute__((always_inline)) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0): direct copies and staged codes
+        __syncthreads();
+    };
+
+    // ---- main loop ---------------------------------------------------------------------------------
+    // Invariant at the top of step s: tile buffers s&1 hold step s; st[(s+1)&1] holds the codes of
+    // step s+1 (if it is a quantized step).
+    Staged<QMODE> st[2];
+    if (nsteps > 0) {
+        issue_copies(0, 0);
+        if (steps1 > 0) load_staged(st[0], 0);
+        if (steps1 > 1) load_staged(st[1], 1);
+        __syncthreads();                                   // lut visible
+        if (steps1 > 0) dequant_store(st[0], sW);
+        copies_landed();
+        int s = 0;
+        // steady state over quantized steps that still have two quantized successors, unrolled by
+        // two so that the staging registers have fixed names
+        for (; s + 3 < steps1; s += 2) {
+            issue_x1(s + 1, 1);
+            load_staged(st[0], s + 2);
+            compute_dequant(sX, sW, st[1], sW + kTileBytes);
+            copies_landed();
+            issue_x1(s + 2, 0);
+            load_staged(st[1], s + 3);
+            compute_dequant(sX + kTileBytes, sW + kTileBytes, st[0], sW);
+            copies_landed();
+        }
+        // remaining steps (the last quantized ones and the K-extension), same order of work with
+        // every part guarded; still unrolled by two for the staging registers
+        auto one_step = [&](int step, int buf, Staged<QMODE>& load_into, const Staged<QMODE>& dequant_from) __attribute__((always_inline)) {
+            if (step + 1 < nsteps) issue_copies(step + 1, buf ^ 1);
+            if (step + 2 < steps1) load_staged(load_into, step + 2);
+            compute(sX + buf * kTileBytes, sW + buf * kTileBytes);
+            if (step + 1 < steps1) dequant_store(dequant_from, sW + (buf ^ 1) * kTileBytes);
+            copies_landed();
+        };
+        for (; s < nsteps; s += 2) {
+            one_step(s, 0, st[0], st[1]);
+            if (s + 1 < nsteps) one_step(s + 1, 1, st[1], st[0]);
+        }
+    }
+
+    __builtin_amdgcn_s_waitcnt(0x0F70);                    // nothing may still be writing this workgroup's LDS
+
+    // ---- epilogue: lane holds features n..n+3 of one token per accumulator quad -----------------------
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int64_t m = m0 + wm0 + b * 32 + r;
+            if (m >= M) continue;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wn0 + a * 32 + q * 8 + hi * 4;
+                if (n >= N) continue;
+                uint2 o;
+                o.x = pack_bf16(acc[a][b][q * 4 + 0] * out_scale, acc[a][b][q * 4 + 1] * out_scale);
+                o.y = pack_bf16(acc[a][b][q * 4 + 2] * out_scale, acc[a][b][q * 4 + 3] * out_scale);
+                *reinterpret_cast<uint2*>(C + m * ldc + n) = o;
+            }
+        }
+}
+
+template <int QMODE, bool BETA>
+int launch_cfg(const GemmDesc& d, hipStream_t st) {
+    constexpr size_t smem = 4 * kTileBytes;
+    auto kern = k_qlinear<QMODE, BETA>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)smem) != hipSuccess)
+            return QBLORA_ERR_LAUNCH;
+        attr_set = true;
+    }
+    int64_t tiles = ((d.M + BM - 1) / BM) * ((d.N + BN - 1) / BN);
+    hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(kThreads), smem, st, d);
+    return launch_status();
+}
+
+}  // namespace
+
+// The quantized GEMMs of the layer (qmode 1 or 2, bf16 output, no auxiliary outputs).
+int launch_qlinear(const GemmDesc& d, hipStream_t st) {
+    if (d.M <= 0 || d.N <= 0) return QBLORA_OK;
+    if (d.out_f32 || d.C2 || d.C_lo) return QBLORA_ERR_UNSUPPORTED;
+    if (d.qmode == 1) return d.beta ? launch_cfg<1, true>(d, st) : launch_cfg<1, false>(d, st);
+    if (d.qmode == 2) return d.beta ? launch_cfg<2, true>(d, st) : launch_cfg<2, false>(d, st);
+    return QBLORA_ERR_UNSUPPORTED;
+}
+
+}  // namespace qblora
