@@ -86,6 +86,9 @@ struct GemmDesc {
 int launch_gemm(const GemmDesc& d, hipStream_t st);
 // the quantized segments (qmode 1, 2) with a 4-wave 256x256 tile; called by launch_gemm
 int launch_qlinear(const GemmDesc& d, hipStream_t st);
+// narrow-output plain bf16 GEMM (qmode 0, N = inner rank); called by launch_gemm when it applies
+bool skinny_applies(const GemmDesc& d);
+int launch_skinny(const GemmDesc& d, hipStream_t st);
 
 // Token-contraction GEMM with split-T partials:  part[z][i][j] = sum_{t in slice z} L[t,i] * S[t,j]
 // followed by the reduction  out = sum_z part, pooled over `pool` adjacent i (scaled by out_scale),

@@ -201,32 +201,28 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         for (int p = 0; p < 8; ++p) dequant_piece(s, tile, p);
     };
 
-    // ---- 64 MFMAs of one k-step --------------------------------------------------------------------
+    // ---- one k-step ----------------------------------------------------------------------------------
+    // A wave runs alone on its SIMD, so nothing hides an LDS round trip or a barrier but its own
+    // MFMAs.  The 64 MFMAs of a step are cut into 8 slices of 8 (about 256 cycles each) and all other
+    // work is pinned to slices, every LDS read one slice before its result is used:
+    //   fragments   quarter q+1 is read during quarter q (weight half in the even slice, token half in
+    //               the odd one); quarter 0 of the NEXT step is read right after the barrier that
+    //               publishes its tiles, and the last four MFMAs of this step are issued after that
+    //               barrier, so the matrix pipe stays busy across it.
+    //   dequantize  (next weight tile, 8 pieces of 8 elements) table offsets of piece p in slice p-1,
+    //               table reads in slice p (pieces 6 and 7 both in slice 6), scale/pack/store in slice
+    //               p+1 (both in slice 7, before the barrier).
+    // Scheduling barriers keep work inside its slice; group barriers spread it between the MFMAs.
     const int r = lane & 31, hi = lane >> 5;
-    auto compute = [&](const unsigned char* bx, const unsigned char* bw) __attribute__((always_inline)) {
+    bf16x8 wf[2][4], xf[2][4];      // two fragment sets; set 0 holds quarter 0 when a step starts
+    auto read_wf = [&](const unsigned char* bw, int ks, bf16x8 (&f)[4]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 wf[4], xf[4];
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-                wf[a] = *reinterpret_cast<const bf16x8*>(bw + swz(wn0 + a * 32 + r, ks * 2 + hi));
-#pragma unroll
-            for (int b = 0; b < 4; ++b)
-                xf[b] = *reinterpret_cast<const bf16x8*>(bx + swz(wm0 + b * 32 + r, ks * 2 + hi));
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int b = 0; b < 4; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[a], xf[b], acc[a][b], 0, 0, 0);
-        }
+        for (int a = 0; a < 4; ++a) f[a] = *reinterpret_cast<const bf16x8*>(bw + swz(wn0 + a * 32 + r, ks * 2 + hi));
     };
-    // Steady-state step: the 64 MFMAs on (bx, bw) with the dequantization of the next weight tile
-    // (st -> bw_next) software-pipelined between them.  A wave runs alone on its SIMD, so nothing hides
-    // an LDS round trip but its own MFMAs: the step is cut into 8 slices of 8 MFMAs (about 256 cycles),
-    // and every LDS read is issued one slice before its result is used.  Slice h: finish piece h-1
-    // (scale, pack, store), issue the table reads of piece h, extract the table offsets of piece h+1,
-    // issue half of the fragment reads of the next quarter, 8 MFMAs.  Scheduling barriers keep work
-    // from leaving its slice; group barriers inside a slice spread it between the MFMAs.
+    auto read_xf = [&](const unsigned char* bx, int ks, bf16x8 (&f)[4]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) f[b] = *reinterpret_cast<const bf16x8*>(bx + swz(wm0 + b * 32 + r, ks * 2 + hi));
+    };
     auto table_offsets = [&](const Staged<QMODE>& s, int p, uint32_t (&li)[8]) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -234,6 +230,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             const int nib = QMODE == 1 ? j : p;
             li[j] = nib == 0 ? ((w << 2) & 0x3cu) : ((w >> (4 * nib - 2)) & 0x3cu);
         }
+    };
+    auto table_reads = [&](const uint32_t (&li)[8], float (&lv)[8]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            lv[j] = *reinterpret_cast<const float*>(reinterpret_cast<const unsigned char*>(lut) + li[j]);
     };
     auto finish_piece = [&](const Staged<QMODE>& s, int p, const float (&lv)[8], unsigned char* tile)
         __attribute__((always_inline)) {
@@ -249,51 +250,70 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         if constexpr (QMODE == 1) *reinterpret_cast<uint4*>(tile + swz(t, p)) = o;
         else *reinterpret_cast<uint4*>(tile + swz(8 * (t & 31) + p, t >> 5)) = o;
     };
-    auto compute_dequant = [&](const unsigned char* bx, const unsigned char* bw, const Staged<QMODE>& s,
-                               unsigned char* bw_next) __attribute__((always_inline)) {
-        bf16x8 wf[2][4], xf[2][4];
-        float lv[2][8];
-        uint32_t li[2][8];
+    auto mfma_row = [&](int a, const bf16x8 (&fw)[4], const bf16x8 (&fx)[4]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int a = 0; a < 4; ++a) wf[0][a] = *reinterpret_cast<const bf16x8*>(bw + swz(wn0 + a * 32 + r, hi));
-#pragma unroll
-        for (int b = 0; b < 4; ++b) xf[0][b] = *reinterpret_cast<const bf16x8*>(bx + swz(wm0 + b * 32 + r, hi));
-        table_offsets(s, 0, li[0]);
-        __builtin_amdgcn_sched_barrier(0);
+        for (int b = 0; b < 4; ++b)
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[a], fx[b], acc[a][b], 0, 0, 0);
+    };
+    // dq: dequantize `sdq` into bw_next during this step; has_next: a step follows (its tiles are in
+    // bx_next / bw_next once the barrier is passed).  Both are literal `true` in the steady state.
+    auto run_step = [&](const unsigned char* bx, const unsigned char* bw, const unsigned char* bx_next,
+                        unsigned char* bw_next, const bool dq, const Staged<QMODE>& sdq, const bool has_next)
+        __attribute__((always_inline)) {
+        float lv[3][8];
+        uint32_t li[3][8];
+        if (dq) table_offsets(sdq, 0, li[0]);
 #pragma unroll
         for (int h = 0; h < 8; ++h) {
             const int ks = h >> 1, half = h & 1, cur = ks & 1, nxt = cur ^ 1;
-            if (h >= 1) finish_piece(s, h - 1, lv[(h - 1) & 1], bw_next);
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                lv[h & 1][j] = *reinterpret_cast<const float*>(reinterpret_cast<const unsigned char*>(lut) + li[h & 1][j]);
-            if (h < 7) table_offsets(s, h + 1, li[(h + 1) & 1]);
-            if (ks < 3) {
-                if (half == 0) {
-#pragma unroll
-                    for (int a = 0; a < 4; ++a)
-                        wf[nxt][a] = *reinterpret_cast<const bf16x8*>(bw + swz(wn0 + a * 32 + r, (ks + 1) * 2 + hi));
-                } else {
-#pragma unroll
-                    for (int b = 0; b < 4; ++b)
-                        xf[nxt][b] = *reinterpret_cast<const bf16x8*>(bx + swz(wm0 + b * 32 + r, (ks + 1) * 2 + hi));
+            if (dq) {
+                if (h >= 1 && h <= 6) finish_piece(sdq, h - 1, lv[(h - 1) % 3], bw_next);
+                if (h <= 6) table_reads(li[h % 3], lv[h % 3]);
+                if (h <= 5) table_offsets(sdq, h + 1, li[(h + 1) % 3]);
+                if (h == 6) {
+                    table_offsets(sdq, 7, li[7 % 3]);
+                    table_reads(li[7 % 3], lv[7 % 3]);
                 }
             }
-#pragma unroll
-            for (int a = 2 * half; a < 2 * half + 2; ++a)
-#pragma unroll
-                for (int b = 0; b < 4; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][a], xf[cur][b], acc[a][b], 0, 0, 0);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);       // vector ALU
-                if (i < 4) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);   // LDS reads
-                if (i == 3) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // the LDS store of the finished piece
+            if (ks < 3) {
+                if (half == 0) read_wf(bw, ks + 1, wf[nxt]);
+                else read_xf(bx, ks + 1, xf[nxt]);
             }
-            __builtin_amdgcn_sched_barrier(0);
+            if (h < 7) {
+                mfma_row(2 * half, wf[cur], xf[cur]);
+                mfma_row(2 * half + 1, wf[cur], xf[cur]);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);       // vector ALU
+                    if (i < 4) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);   // LDS reads
+                    if (i == 3) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // LDS store of the finished piece
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            } else {
+                mfma_row(2, wf[cur], xf[cur]);
+                if (dq) {
+                    finish_piece(sdq, 6, lv[6 % 3], bw_next);
+                    finish_piece(sdq, 7, lv[7 % 3], bw_next);
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+                    if (i & 1) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (has_next) {
+                    __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): direct copies and staged codes
+                    __syncthreads();                           // next tiles published; this step's tiles free
+                    read_wf(bw_next, 0, wf[0]);
+                    read_xf(bx_next, 0, xf[0]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_row(3, wf[cur], xf[cur]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-        finish_piece(s, 7, lv[1], bw_next);
     };
 
     // Segment-1 activation tiles: per-lane byte offsets relative to the tile's first row are fixed for
@@ -320,14 +340,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             copy_tile(true, W2, ldw2, n0, N - 1, div2, K2, k0, (2 + buf) * kTileBytes);
         }
     };
-    auto copies_landed = [&]() __attribute__((always_inline)) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0): direct copies and staged codes
-        __syncthreads();
-    };
-
     // ---- main loop ---------------------------------------------------------------------------------
-    // Invariant at the top of step s: tile buffers s&1 hold step s; st[(s+1)&1] holds the codes of
-    // step s+1 (if it is a quantized step).
+    // Invariant at the top of step s: tile buffers s&1 hold step s and fragment set 0 holds its first
+    // quarter; st[(s+1)&1] holds the codes of step s+1 (if that is a quantized step).
     Staged<QMODE> st[2];
     if (nsteps > 0) {
         issue_copies(0, 0);
@@ -335,32 +350,32 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         if (steps1 > 1) load_staged(st[1], 1);
         __syncthreads();                                   // lut visible
         if (steps1 > 0) dequant_store(st[0], sW);
-        copies_landed();
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        read_wf(sW, 0, wf[0]);
+        read_xf(sX, 0, xf[0]);
         int s = 0;
         // steady state over quantized steps that still have two quantized successors, unrolled by
-        // two so that the staging registers have fixed names
+        // two so that the staging registers and the tile buffers have fixed names
         for (; s + 3 < steps1; s += 2) {
             issue_x1(s + 1, 1);
             load_staged(st[0], s + 2);
-            compute_dequant(sX, sW, st[1], sW + kTileBytes);
-            copies_landed();
+            run_step(sX, sW, sX + kTileBytes, sW + kTileBytes, true, st[1], true);
             issue_x1(s + 2, 0);
             load_staged(st[1], s + 3);
-            compute_dequant(sX + kTileBytes, sW + kTileBytes, st[0], sW);
-            copies_landed();
+            run_step(sX + kTileBytes, sW + kTileBytes, sX, sW, true, st[0], true);
         }
-        // remaining steps (the last quantized ones and the K-extension), same order of work with
-        // every part guarded; still unrolled by two for the staging registers
-        auto one_step = [&](int step, int buf, Staged<QMODE>& load_into, const Staged<QMODE>& dequant_from) __attribute__((always_inline)) {
+        // remaining steps (the last quantized ones and the K-extension): same step with its parts guarded
+        auto tail_step = [&](int step, int buf, Staged<QMODE>& load_into, const Staged<QMODE>& dequant_from)
+            __attribute__((always_inline)) {
             if (step + 1 < nsteps) issue_copies(step + 1, buf ^ 1);
             if (step + 2 < steps1) load_staged(load_into, step + 2);
-            compute(sX + buf * kTileBytes, sW + buf * kTileBytes);
-            if (step + 1 < steps1) dequant_store(dequant_from, sW + (buf ^ 1) * kTileBytes);
-            copies_landed();
+            run_step(sX + buf * kTileBytes, sW + buf * kTileBytes, sX + (buf ^ 1) * kTileBytes,
+                     sW + (buf ^ 1) * kTileBytes, step + 1 < steps1, dequant_from, step + 1 < nsteps);
         };
         for (; s < nsteps; s += 2) {
-            one_step(s, 0, st[0], st[1]);
-            if (s + 1 < nsteps) one_step(s + 1, 1, st[1], st[0]);
+            tail_step(s, 0, st[0], st[1]);
+            if (s + 1 < nsteps) tail_step(s + 1, 1, st[1], st[0]);
         }
     }
 
