@@ -27,7 +27,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the forward GEMM from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see the
 # profiles/ summaries); None until measured for the workload.
-MEASURED_TRAFFIC_BYTES = {"llama7b_attn": None}
+MEASURED_TRAFFIC_BYTES = {"llama7b_attn": int((208.5 + 66.1) * 2**20)}   # profiles/bench_llama7b_attn.md
 
 
 def main() -> int:
@@ -38,6 +38,9 @@ def main() -> int:
     ap.add_argument("--workload", default="llama7b_attn")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain device copy of 256 MiB before the timed steps, so that a counter "
+                         "profile of this command holds a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (no collectives are part of it); run with --gpus 1",
@@ -88,6 +91,14 @@ def main() -> int:
         qb.qblora_tile_product(ad, d_in, d_out, H, ws)
         qb.qablora_merge_quantize(qw, H, lam, lam, wl.s, qb.MERGE_REQUANT_MINMAX, out=merged)
 
+    if args.calibration_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        src.zero_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -134,7 +145,7 @@ def main() -> int:
                    "step": "quantize + forward + backward(dX,dA,dB) + tile product + INT4 requantizing merge"},
         "tokens_per_s": round(T / (ms_per_step * 1e-3), 1),
         "pct_of_bf16_mfma_peak": round(100.0 * value / MFMA_BF16_PEAK_TFLOPS, 2),
-        "roofline": {"kernel": "k_qgemm (forward dequantize-and-contract)", "bound": "mfma",
+        "roofline": {"kernel": "k_qlinear<1> (forward dequantize-and-contract)", "bound": "mfma",
                      "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic,
                      "avg_kernel_ms": round(kernel_ms["fwd_gemm"], 4)},

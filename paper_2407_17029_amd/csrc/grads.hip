@@ -154,7 +154,7 @@ __global__ __launch_bounds__(256) void k_grad_reduce(GradDesc d) {
 
 int grad_splits(int64_t T, int I) {
     int tiles_i = (I + BI - 1) / BI;
-    int want = (512 + tiles_i - 1) / tiles_i;
+    int want = (256 + tiles_i - 1) / tiles_i;          // one workgroup per CU
     int64_t max_splits = (T + BT - 1) / BT;
     if (want > max_splits) want = (int)max_splits;
     if (want > 32) want = 32;

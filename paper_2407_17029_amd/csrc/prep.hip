@@ -10,58 +10,81 @@ namespace qblora {
 namespace {
 
 // out[b][a*e + i] = in[a][b]  for i < e;  in is [na, nb] row-major, out is [nb, na*e] row-major.
-__global__ __launch_bounds__(256) void k_transpose_expand(const uint16_t* __restrict__ in, int na, int nb, int e,
-                                                          uint16_t* __restrict__ out) {
-    __shared__ uint16_t tile[64][66];
-    int a0 = blockIdx.x * 64, b0 = blockIdx.y * 64;
-    int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;   // 64 x 4
+// One call handles the 64 x 64 input tile (ta, tb).
+__device__ __forceinline__ void transpose_expand_tile(const uint16_t* __restrict__ in, int na, int nb, int e,
+                                                      uint16_t* __restrict__ out, int ta, int tb,
+                                                      uint16_t (*tile)[66]) {
+    const int a0 = ta * 64, b0 = tb * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;   // 64 x 4
     for (int r = ty; r < 64; r += 4) {
-        int a = a0 + r, b = b0 + tx;
+        const int a = a0 + r, b = b0 + tx;
         tile[r][tx] = (a < na && b < nb) ? in[(int64_t)a * nb + b] : (uint16_t)0;
     }
     __syncthreads();
-    int64_t ld = (int64_t)na * e;
-    int width = 64 * e;                                  // output columns covered by this tile
+    const int64_t ld = (int64_t)na * e;
+    const int width = 64 * e;                                  // output columns covered by this tile
     for (int r = ty; r < 64; r += 4) {
-        int b = b0 + r;
+        const int b = b0 + r;
         if (b >= nb) continue;
         for (int c = tx; c < width; c += 64) {
-            int a = a0 + c / e;
+            const int a = a0 + c / e;
             if (a < na) out[(int64_t)b * ld + (int64_t)a0 * e + c] = tile[c / e][r];
         }
     }
 }
 
-// out[j][n] = in[j][n / e];  in is [rows, cols], out is [rows, cols*e].
-__global__ __launch_bounds__(256) void k_expand_cols(const uint16_t* __restrict__ in, int rows, int cols, int e,
-                                                     uint16_t* __restrict__ out) {
-    int64_t total = (int64_t)rows * cols * e;
-    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= total) return;
-    int64_t ld = (int64_t)cols * e;
-    int64_t j = i / ld, n = i - j * ld;
-    out[i] = in[j * cols + n / e];
+struct PrepDesc {
+    const uint16_t* A; const uint16_t* B;
+    int na_A, R, lam1;          // A is [na_A, R]
+    int cols_B, lam2;           // B is [R, cols_B]
+    uint16_t* At_x; uint16_t* Bt; uint16_t* Bx;
+    int tilesA_a, tilesA_b, nA;     // tile grid of the A job and its block count (0 when skipped)
+    int tilesB_a, tilesB_b, nB;     // tile grid of the B-transpose job
+    int nX;                         // blocks of the column-expansion job (2048 outputs each)
+};
+
+// All re-layouts of one call in a single launch: blocks [0,nA) transpose-expand A, the next nB
+// transpose B, the last nX expand B along its columns.
+__global__ __launch_bounds__(256) void k_adapter_prep(PrepDesc d) {
+    __shared__ uint16_t tile[64][66];
+    int b = blockIdx.x;
+    if (b < d.nA) {
+        transpose_expand_tile(d.A, d.na_A, d.R, d.lam1, d.At_x, b % d.tilesA_a, b / d.tilesA_a, tile);
+        return;
+    }
+    b -= d.nA;
+    if (b < d.nB) {
+        transpose_expand_tile(d.B, d.R, d.cols_B, 1, d.Bt, b % d.tilesB_a, b / d.tilesB_a, tile);
+        return;
+    }
+    b -= d.nB;
+    // Bx[j][n] = B[j][n / lam2]
+    const int64_t ld = (int64_t)d.cols_B * d.lam2;
+    const int64_t total = (int64_t)d.R * ld;
+    const int64_t base = (int64_t)b * 2048;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int64_t i = base + u * 256 + threadIdx.x;
+        if (i < total) {
+            const int64_t j = i / ld, n = i - j * ld;
+            d.Bx[i] = d.B[j * d.cols_B + n / d.lam2];
+        }
+    }
 }
 
 }  // namespace
 
 int launch_adapter_prep(const qblora_bf16* A, const qblora_bf16* B, int d_in, int d_out, int R, int lam1,
                         int lam2, qblora_bf16* At_x, qblora_bf16* Bt, qblora_bf16* Bx, hipStream_t st) {
-    if (At_x) {
-        int na = d_in / lam1, nb = R;
-        hipLaunchKernelGGL(k_transpose_expand, dim3((na + 63) / 64, (nb + 63) / 64), dim3(256), 0, st, A, na, nb,
-                           lam1, At_x);
-    }
-    if (Bt) {
-        int na = R, nb = d_out / lam2;
-        hipLaunchKernelGGL(k_transpose_expand, dim3((na + 63) / 64, (nb + 63) / 64), dim3(256), 0, st, B, na, nb,
-                           1, Bt);
-    }
-    if (Bx) {
-        int64_t total = (int64_t)R * d_out;
-        hipLaunchKernelGGL(k_expand_cols, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, B, R,
-                           d_out / lam2, lam2, Bx);
-    }
+    PrepDesc d{};
+    d.A = A; d.B = B; d.na_A = d_in / lam1; d.R = R; d.lam1 = lam1; d.cols_B = d_out / lam2; d.lam2 = lam2;
+    d.At_x = At_x; d.Bt = Bt; d.Bx = Bx;
+    if (At_x) { d.tilesA_a = (d.na_A + 63) / 64; d.tilesA_b = (R + 63) / 64; d.nA = d.tilesA_a * d.tilesA_b; }
+    if (Bt) { d.tilesB_a = (R + 63) / 64; d.tilesB_b = (d.cols_B + 63) / 64; d.nB = d.tilesB_a * d.tilesB_b; }
+    if (Bx) d.nX = (int)(((int64_t)R * d_out + 2047) / 2048);
+    const int blocks = d.nA + d.nB + d.nX;
+    if (blocks == 0) return QBLORA_OK;
+    hipLaunchKernelGGL(k_adapter_prep, dim3(blocks), dim3(256), 0, st, d);
     return launch_status();
 }
 
