@@ -355,27 +355,31 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         read_wf(sW, 0, wf[0]);
         read_xf(sX, 0, xf[0]);
         int s = 0;
-        // steady state over quantized steps that still have two quantized successors, unrolled by
-        // two so that the staging registers and the tile buffers have fixed names
-        for (; s + 3 < steps1; s += 2) {
+        // Quantized steps whose successor is quantized too (the successor's tile is dequantized during
+        // the step), unrolled by two so that the staging registers and the tile buffers have fixed
+        // names.  Codes are fetched two steps ahead; past the end the last quantized step is fetched
+        // again (in bounds, unused) so that the body has no conditions.
+        const int last_q = steps1 - 1;
+        for (; s + 2 < steps1; s += 2) {
             issue_x1(s + 1, 1);
-            load_staged(st[0], s + 2);
+            load_staged(st[0], min(s + 2, last_q));
             run_step(sX, sW, sX + kTileBytes, sW + kTileBytes, true, st[1], true);
             issue_x1(s + 2, 0);
-            load_staged(st[1], s + 3);
+            load_staged(st[1], min(s + 3, last_q));
             run_step(sX + kTileBytes, sW + kTileBytes, sX, sW, true, st[0], true);
         }
-        // remaining steps (the last quantized ones and the K-extension): same step with its parts guarded
-        auto tail_step = [&](int step, int buf, Staged<QMODE>& load_into, const Staged<QMODE>& dequant_from)
-            __attribute__((always_inline)) {
-            if (step + 1 < nsteps) issue_copies(step + 1, buf ^ 1);
-            if (step + 2 < steps1) load_staged(load_into, step + 2);
+        if (s + 1 < steps1) {
+            issue_x1(s + 1, 1);
+            run_step(sX, sW, sX + kTileBytes, sW + kTileBytes, true, st[1], true);
+            ++s;
+        }
+        // the last quantized step and the K-extension steps: nothing to dequantize
+        for (; s < nsteps; ++s) {
+            const int buf = s & 1;
+            const bool has_next = s + 1 < nsteps;
+            if (has_next) issue_copies(s + 1, buf ^ 1);
             run_step(sX + buf * kTileBytes, sW + buf * kTileBytes, sX + (buf ^ 1) * kTileBytes,
-                     sW + (buf ^ 1) * kTileBytes, step + 1 < steps1, dequant_from, step + 1 < nsteps);
-        };
-        for (; s < nsteps; s += 2) {
-            tail_step(s, 0, st[0], st[1]);
-            if (s + 1 < nsteps) tail_step(s + 1, 1, st[1], st[0]);
+                     sW + (buf ^ 1) * kTileBytes, false, st[0], has_next);
         }
     }
 

@@ -11,23 +11,33 @@ namespace qblora {
 
 namespace {
 
+constexpr int kUnroll = 4;      // float4 loads per thread of the quantizers
+
 struct Midpoints {
     float m[15];   // (c_j + c_{j+1}) * 0.5 in fp32, computed on the host
 };
 
+// All-reduce over the 16 lanes of a DPP row (= one 64-wide block held as 16 float4): rotating the row by
+// 8, 4, 2, 1 lanes and combining leaves the result in every lane.  DPP keeps this in the vector ALU; the
+// generic lane shuffle would go through the LDS crossbar four times per block.
+template <int ROT>
+__device__ __forceinline__ float row_rotate(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + ROT, 0xf, 0xf, false));
+}
+
 __device__ __forceinline__ float group16_max(float v) {
-    v = fmaxf(v, __shfl_xor(v, 8, 16));
-    v = fmaxf(v, __shfl_xor(v, 4, 16));
-    v = fmaxf(v, __shfl_xor(v, 2, 16));
-    v = fmaxf(v, __shfl_xor(v, 1, 16));
+    v = fmaxf(v, row_rotate<8>(v));
+    v = fmaxf(v, row_rotate<4>(v));
+    v = fmaxf(v, row_rotate<2>(v));
+    v = fmaxf(v, row_rotate<1>(v));
     return v;
 }
 
 __device__ __forceinline__ float group16_min(float v) {
-    v = fminf(v, __shfl_xor(v, 8, 16));
-    v = fminf(v, __shfl_xor(v, 4, 16));
-    v = fminf(v, __shfl_xor(v, 2, 16));
-    v = fminf(v, __shfl_xor(v, 1, 16));
+    v = fminf(v, row_rotate<8>(v));
+    v = fminf(v, row_rotate<4>(v));
+    v = fminf(v, row_rotate<2>(v));
+    v = fminf(v, row_rotate<1>(v));
     return v;
 }
 
@@ -35,52 +45,84 @@ __device__ __forceinline__ float group16_min(float v) {
 __global__ __launch_bounds__(256) void k_quantize_codebook(const float4* __restrict__ W, int64_t n_vec,
                                                            Midpoints mp, uint16_t* __restrict__ codes16,
                                                            float* __restrict__ absmax) {
-    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n_vec) return;   // whole 16-lane groups leave together
-    float4 w = W[i];
-    float a = fmaxf(fmaxf(fabsf(w.x), fabsf(w.y)), fmaxf(fabsf(w.z), fabsf(w.w)));
-    a = group16_max(a);
-    uint32_t c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+    // four independent 16-byte loads per thread are issued before any arithmetic (bytes in flight)
+    int64_t idx[kUnroll];
+    float4 wv[kUnroll];
 #pragma unroll
-    for (int j = 0; j < 15; ++j) {
-        float t = __fmul_rn(mp.m[j], a);
-        c0 += (w.x > t) ? 1u : 0u;
-        c1 += (w.y > t) ? 1u : 0u;
-        c2 += (w.z > t) ? 1u : 0u;
-        c3 += (w.w > t) ? 1u : 0u;
+    for (int u = 0; u < kUnroll; ++u) {
+        idx[u] = ((int64_t)blockIdx.x * kUnroll + u) * 256 + threadIdx.x;
+        wv[u] = idx[u] < n_vec ? W[idx[u]] : make_float4(0.f, 0.f, 0.f, 0.f);   // whole 16-lane groups are in or out
     }
-    codes16[i] = (uint16_t)(c0 | (c1 << 4) | (c2 << 8) | (c3 << 12));
-    if ((threadIdx.x & 15) == 0) absmax[i >> 4] = a;
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        const float4 w = wv[u];
+        float a = fmaxf(fmaxf(fabsf(w.x), fabsf(w.y)), fmaxf(fabsf(w.z), fabsf(w.w)));
+        a = group16_max(a);
+        // code = #{ j : w > t_j } with t_j = m_j * a.  Rounding is monotone, so the t_j ascend (weakly)
+        // and the count is found by bisection: four comparisons per weight against thresholds selected
+        // by the earlier outcomes, instead of fifteen.
+        const float t0 = __fmul_rn(mp.m[0], a), t1 = __fmul_rn(mp.m[1], a), t2 = __fmul_rn(mp.m[2], a),
+                    t3 = __fmul_rn(mp.m[3], a), t4 = __fmul_rn(mp.m[4], a), t5 = __fmul_rn(mp.m[5], a),
+                    t6 = __fmul_rn(mp.m[6], a), t7 = __fmul_rn(mp.m[7], a), t8 = __fmul_rn(mp.m[8], a),
+                    t9 = __fmul_rn(mp.m[9], a), t10 = __fmul_rn(mp.m[10], a), t11 = __fmul_rn(mp.m[11], a),
+                    t12 = __fmul_rn(mp.m[12], a), t13 = __fmul_rn(mp.m[13], a), t14 = __fmul_rn(mp.m[14], a);
+        auto code_of = [&](float x) -> uint32_t {
+            const bool b3 = x > t7;
+            const float u2 = b3 ? t11 : t3;
+            const bool b2 = x > u2;
+            const float u1lo = b2 ? t5 : t1, u1hi = b2 ? t13 : t9;
+            const bool b1 = x > (b3 ? u1hi : u1lo);
+            const float q0 = b1 ? t2 : t0, q1 = b1 ? t6 : t4, q2 = b1 ? t10 : t8, q3 = b1 ? t14 : t12;
+            const float u0lo = b2 ? q1 : q0, u0hi = b2 ? q3 : q2;
+            const bool b0 = x > (b3 ? u0hi : u0lo);
+            return (b3 ? 8u : 0u) + (b2 ? 4u : 0u) + (b1 ? 2u : 0u) + (b0 ? 1u : 0u);
+        };
+        const uint32_t c0 = code_of(w.x), c1 = code_of(w.y), c2 = code_of(w.z), c3 = code_of(w.w);
+        if (idx[u] < n_vec) {
+            codes16[idx[u]] = (uint16_t)(c0 | (c1 << 4) | (c2 << 8) | (c3 << 12));
+            if ((threadIdx.x & 15) == 0) absmax[idx[u] >> 4] = a;
+        }
+    }
 }
 
 // Min-max INT4 quantizer: alpha = (hi-lo)/15, beta = lo, code = rint((w-lo) * (15/(hi-lo))).
 __global__ __launch_bounds__(256) void k_quantize_minmax(const float4* __restrict__ W, int64_t n_vec,
                                                          uint16_t* __restrict__ codes16,
                                                          float* __restrict__ alpha, float* __restrict__ beta) {
-    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n_vec) return;
-    float4 w = W[i];
-    float lo = group16_min(fminf(fminf(w.x, w.y), fminf(w.z, w.w)));
-    float hi = group16_max(fmaxf(fmaxf(w.x, w.y), fmaxf(w.z, w.w)));
-    float range = __fsub_rn(hi, lo);
-    float al = __fdiv_rn(range, 15.0f);
-    uint32_t packed = 0;
-    if (al != 0.0f) {
-        float inv = __fdiv_rn(15.0f, range);
-        float q0 = rintf(__fmul_rn(__fsub_rn(w.x, lo), inv));
-        float q1 = rintf(__fmul_rn(__fsub_rn(w.y, lo), inv));
-        float q2 = rintf(__fmul_rn(__fsub_rn(w.z, lo), inv));
-        float q3 = rintf(__fmul_rn(__fsub_rn(w.w, lo), inv));
-        q0 = fminf(fmaxf(q0, 0.0f), 15.0f);
-        q1 = fminf(fmaxf(q1, 0.0f), 15.0f);
-        q2 = fminf(fmaxf(q2, 0.0f), 15.0f);
-        q3 = fminf(fmaxf(q3, 0.0f), 15.0f);
-        packed = (uint32_t)q0 | ((uint32_t)q1 << 4) | ((uint32_t)q2 << 8) | ((uint32_t)q3 << 12);
+    int64_t idx[kUnroll];
+    float4 wv[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        idx[u] = ((int64_t)blockIdx.x * kUnroll + u) * 256 + threadIdx.x;
+        wv[u] = idx[u] < n_vec ? W[idx[u]] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    codes16[i] = (uint16_t)packed;
-    if ((threadIdx.x & 15) == 0) {
-        alpha[i >> 4] = al;
-        beta[i >> 4] = lo;
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        const float4 w = wv[u];
+        const float lo = group16_min(fminf(fminf(w.x, w.y), fminf(w.z, w.w)));
+        const float hi = group16_max(fmaxf(fmaxf(w.x, w.y), fmaxf(w.z, w.w)));
+        const float range = __fsub_rn(hi, lo);
+        const float al = __fdiv_rn(range, 15.0f);
+        uint32_t packed = 0;
+        if (al != 0.0f) {
+            const float inv = __fdiv_rn(15.0f, range);
+            float q0 = rintf(__fmul_rn(__fsub_rn(w.x, lo), inv));
+            float q1 = rintf(__fmul_rn(__fsub_rn(w.y, lo), inv));
+            float q2 = rintf(__fmul_rn(__fsub_rn(w.z, lo), inv));
+            float q3 = rintf(__fmul_rn(__fsub_rn(w.w, lo), inv));
+            q0 = fminf(fmaxf(q0, 0.0f), 15.0f);
+            q1 = fminf(fmaxf(q1, 0.0f), 15.0f);
+            q2 = fminf(fmaxf(q2, 0.0f), 15.0f);
+            q3 = fminf(fmaxf(q3, 0.0f), 15.0f);
+            packed = (uint32_t)q0 | ((uint32_t)q1 << 4) | ((uint32_t)q2 << 8) | ((uint32_t)q3 << 12);
+        }
+        if (idx[u] < n_vec) {
+            codes16[idx[u]] = (uint16_t)packed;
+            if ((threadIdx.x & 15) == 0) {
+                alpha[idx[u] >> 4] = al;
+                beta[idx[u] >> 4] = lo;
+            }
+        }
     }
 }
 
@@ -184,7 +226,7 @@ int launch_quantize_codebook(const float* W, int d_out, int d_in, const Codebook
         mp.m[j] = m;
     }
     int64_t n_vec = (int64_t)d_out * d_in / 4;
-    unsigned grid = (unsigned)((n_vec + 255) / 256);
+    unsigned grid = (unsigned)((n_vec + 256 * kUnroll - 1) / (256 * kUnroll));
     hipLaunchKernelGGL(k_quantize_codebook, dim3(grid), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
                        n_vec, mp, reinterpret_cast<uint16_t*>(codes), absmax);
     return launch_status();
@@ -193,7 +235,7 @@ int launch_quantize_codebook(const float* W, int d_out, int d_in, const Codebook
 int launch_quantize_minmax(const float* W, int d_out, int d_in, uint8_t* codes, float* alpha, float* beta,
                            hipStream_t st) {
     int64_t n_vec = (int64_t)d_out * d_in / 4;
-    unsigned grid = (unsigned)((n_vec + 255) / 256);
+    unsigned grid = (unsigned)((n_vec + 256 * kUnroll - 1) / (256 * kUnroll));
     hipLaunchKernelGGL(k_quantize_minmax, dim3(grid), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
                        n_vec, reinterpret_cast<uint16_t*>(codes), alpha, beta);
     return launch_status();
