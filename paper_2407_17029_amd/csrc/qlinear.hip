@@ -35,6 +35,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int BM = 256, BN = 256, kBK = 64;
 constexpr int kTileBytes = 256 * 128;                       // one operand tile: 256 rows x 128 bytes
+constexpr int kTableBytes = 256 * 128;                      // byte-indexed pair table, 16 replicas
 
 __device__ __align__(16) const uint32_t g_zero_chunk[4] = {0u, 0u, 0u, 0u};
 
@@ -70,10 +71,9 @@ struct Staged {
 template <int QMODE, bool BETA>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_qlinear(GemmDesc d) {
     extern __shared__ __align__(16) unsigned char smem[];
-    __shared__ float lut[16];                                   // code values: a distinct LDS object, so the
-                                                                // compiler may move table reads across tile stores
     unsigned char* sX = smem;                                   // 2 tiles
     unsigned char* sW = sX + 2 * kTileBytes;                    // 2 tiles
+    unsigned char* sT = smem + 4 * kTileBytes;                  // pair table, see below
 
     // Every field of the descriptor the loop touches is copied into a local first: the copies in
     // the loop are assembly statements that clobber memory, and values must not be re-read around them.
@@ -105,7 +105,19 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     const int64_t m0 = (int64_t)mt * BM;
     const int n0 = nt * BN;
 
-    if (t < 16) lut[t] = d.cb.c[t];
+    // Pair table: a byte of codes (two adjacent k, low nibble first) selects the 8-byte entry
+    // (c[lo], c[hi]) -- one LDS read dequantizes two weights.  The 256 entries are replicated 16 times,
+    // entry b of replica q at b*128 + q*8, and lane l reads replica l & 15: whatever the bytes are, the
+    // 16 lanes the LDS serves together touch 16 different bank pairs.
+    if (t < 16) reinterpret_cast<float*>(sT)[t] = d.cb.c[t];
+    __syncthreads();
+    {
+        const float c_lo = reinterpret_cast<const float*>(sT)[t & 15], c_hi = reinterpret_cast<const float*>(sT)[t >> 4];
+        __syncthreads();
+        const float4 e = make_float4(c_lo, c_hi, c_lo, c_hi);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) *reinterpret_cast<float4*>(sT + t * 128 + q * 16) = e;
+    }
 
     const int K1 = QMODE == 1 ? d_in : d_out;
     const int steps1 = K1 / kBK, steps2 = (K2 + kBK - 1) / kBK;
@@ -174,44 +186,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         }
     };
 
-    // ---- dequantize one staged k-step into a weight tile ------------------------------------------
-    // Piece p (0..7) of a k-step is 8 elements per thread and ends in one 16-byte LDS store:
-    // QMODE 1: the 8 codes of dword p of this thread's row -> chunk p of LDS row t;
-    // QMODE 2: column p of this thread's 8x8 patch (8 contraction rows) -> LDS row 8*kg+p, chunk ng.
-    auto dequant_piece = [&](const Staged<QMODE>& s, unsigned char* tile, int p) __attribute__((always_inline)) {
-        float v[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            if constexpr (QMODE == 1) {
-                const float c = lut[(s.cw[p] >> (4 * j)) & 15];
-                v[j] = BETA ? __fmaf_rn(c, s.sc[0], s.be[0]) : __fmul_rn(c, s.sc[0]);
-            } else {
-                const float c = lut[(s.cw[j] >> (4 * p)) & 15];
-                v[j] = BETA ? __fmaf_rn(c, s.sc[j], s.be[j]) : __fmul_rn(c, s.sc[j]);
-            }
-        }
-        uint4 o;
-        o.x = pack_bf16(v[0], v[1]); o.y = pack_bf16(v[2], v[3]);
-        o.z = pack_bf16(v[4], v[5]); o.w = pack_bf16(v[6], v[7]);
-        if constexpr (QMODE == 1) *reinterpret_cast<uint4*>(tile + swz(t, p)) = o;
-        else *reinterpret_cast<uint4*>(tile + swz(8 * (t & 31) + p, t >> 5)) = o;
-    };
-    auto dequant_store = [&](const Staged<QMODE>& s, unsigned char* tile) __attribute__((always_inline)) {
-#pragma unroll
-        for (int p = 0; p < 8; ++p) dequant_piece(s, tile, p);
-    };
-
     // ---- one k-step ----------------------------------------------------------------------------------
     // A wave runs alone on its SIMD, so nothing hides an LDS round trip or a barrier but its own
     // MFMAs.  The 64 MFMAs of a step are cut into 8 slices of 8 (about 256 cycles each) and all other
-    // work is pinned to slices, every LDS read one slice before its result is used:
-    //   fragments   quarter q+1 is read during quarter q (weight half in the even slice, token half in
-    //               the odd one); quarter 0 of the NEXT step is read right after the barrier that
-    //               publishes its tiles, and the last four MFMAs of this step are issued after that
-    //               barrier, so the matrix pipe stays busy across it.
-    //   dequantize  (next weight tile, 8 pieces of 8 elements) table offsets of piece p in slice p-1,
-    //               table reads in slice p (pieces 6 and 7 both in slice 6), scale/pack/store in slice
-    //               p+1 (both in slice 7, before the barrier).
+    // work is pinned to slices (plan at run_step): fragments and table values are read two slices
+    // before their use; the barrier that publishes the next tiles sits in front of slice 6, so the
+    // last 16 MFMAs of a step cover it and the first fragment reads of the next step.
     // Scheduling barriers keep work inside its slice; group barriers spread it between the MFMAs.
     const int r = lane & 31, hi = lane >> 5;
     bf16x8 wf[2][4], xf[2][4];      // two fragment sets; set 0 holds quarter 0 when a step starts
@@ -223,32 +203,62 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
         for (int b = 0; b < 4; ++b) f[b] = *reinterpret_cast<const bf16x8*>(bx + swz(wm0 + b * 32 + r, ks * 2 + hi));
     };
-    auto table_offsets = [&](const Staged<QMODE>& s, int p, uint32_t (&li)[8]) __attribute__((always_inline)) {
+    // Dequantization of a staged k-step in 4 pieces of 16 elements (two 16-byte LDS stores each):
+    //   QMODE 1: piece q = dwords 2q, 2q+1 of this thread's row (8 bytes of codes) -> chunks 2q, 2q+1 of LDS row t;
+    //   QMODE 2: piece q = byte q (columns 2q, 2q+1) of each of the 8 stored rows of this thread's 8x8
+    //            patch -> LDS rows 8*kg+2q and 8*kg+2q+1, chunk ng (packing down the columns transposes).
+    const uint32_t table_lane = lds_address(sT) - lds_address(smem) + ((lane & 15) << 3);
+    auto table_offsets = [&](const Staged<QMODE>& s, int q, uint32_t (&li)[8]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t w = QMODE == 1 ? s.cw[p] : s.cw[j];
-            const int nib = QMODE == 1 ? j : p;
-            li[j] = nib == 0 ? ((w << 2) & 0x3cu) : ((w >> (4 * nib - 2)) & 0x3cu);
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t w = QMODE == 1 ? s.cw[2 * q + (i >> 2)] : s.cw[i];
+            const int byte = QMODE == 1 ? (i & 3) : q;
+            const uint32_t sh = byte == 0 ? (w << 7) : (w >> (8 * byte - 7));
+            li[i] = (sh & 0x7f80u) | table_lane;
         }
     };
-    auto table_reads = [&](const uint32_t (&li)[8], float (&lv)[8]) __attribute__((always_inline)) {
+    auto table_reads = [&](const uint32_t (&li)[8], float2 (&lv)[8]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            lv[j] = *reinterpret_cast<const float*>(reinterpret_cast<const unsigned char*>(lut) + li[j]);
+        for (int i = 0; i < 8; ++i) lv[i] = *reinterpret_cast<const float2*>(smem + li[i]);
     };
-    auto finish_piece = [&](const Staged<QMODE>& s, int p, const float (&lv)[8], unsigned char* tile)
+    auto finish_piece = [&](const Staged<QMODE>& s, int q, const float2 (&lv)[8], unsigned char* tile)
         __attribute__((always_inline)) {
-        float v[8];
+        float lo[8], hi[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int si = QMODE == 1 ? 0 : j;
-            v[j] = BETA ? __fmaf_rn(lv[j], s.sc[si], s.be[si]) : __fmul_rn(lv[j], s.sc[si]);
+        for (int i = 0; i < 8; ++i) {
+            const int si = QMODE == 1 ? 0 : i;
+            lo[i] = BETA ? __fmaf_rn(lv[i].x, s.sc[si], s.be[si]) : __fmul_rn(lv[i].x, s.sc[si]);
+            hi[i] = BETA ? __fmaf_rn(lv[i].y, s.sc[si], s.be[si]) : __fmul_rn(lv[i].y, s.sc[si]);
         }
-        uint4 o;
-        o.x = pack_bf16(v[0], v[1]); o.y = pack_bf16(v[2], v[3]);
-        o.z = pack_bf16(v[4], v[5]); o.w = pack_bf16(v[6], v[7]);
-        if constexpr (QMODE == 1) *reinterpret_cast<uint4*>(tile + swz(t, p)) = o;
-        else *reinterpret_cast<uint4*>(tile + swz(8 * (t & 31) + p, t >> 5)) = o;
+        if constexpr (QMODE == 1) {
+            // byte i holds elements 2i, 2i+1 of the 16: adjacent k, packed as they come
+            uint4 o0, o1;
+            o0.x = pack_bf16(lo[0], hi[0]); o0.y = pack_bf16(lo[1], hi[1]);
+            o0.z = pack_bf16(lo[2], hi[2]); o0.w = pack_bf16(lo[3], hi[3]);
+            o1.x = pack_bf16(lo[4], hi[4]); o1.y = pack_bf16(lo[5], hi[5]);
+            o1.z = pack_bf16(lo[6], hi[6]); o1.w = pack_bf16(lo[7], hi[7]);
+            *reinterpret_cast<uint4*>(tile + swz(t, 2 * q)) = o0;
+            *reinterpret_cast<uint4*>(tile + swz(t, 2 * q + 1)) = o1;
+        } else {
+            // lo[i] / hi[i] are columns 2q / 2q+1 of stored row i: pack down each column
+            uint4 o0, o1;
+            o0.x = pack_bf16(lo[0], lo[1]); o0.y = pack_bf16(lo[2], lo[3]);
+            o0.z = pack_bf16(lo[4], lo[5]); o0.w = pack_bf16(lo[6], lo[7]);
+            o1.x = pack_bf16(hi[0], hi[1]); o1.y = pack_bf16(hi[2], hi[3]);
+            o1.z = pack_bf16(hi[4], hi[5]); o1.w = pack_bf16(hi[6], hi[7]);
+            *reinterpret_cast<uint4*>(tile + swz(8 * (t & 31) + 2 * q, t >> 5)) = o0;
+            *reinterpret_cast<uint4*>(tile + swz(8 * (t & 31) + 2 * q + 1, t >> 5)) = o1;
+        }
+    };
+    auto dequant_store = [&](const Staged<QMODE>& s, unsigned char* tile) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            uint32_t li[8];
+            float2 lv[8];
+            table_offsets(s, q, li);
+            table_reads(li, lv);
+            finish_piece(s, q, lv, tile);
+        }
     };
     auto mfma_row = [&](int a, const bf16x8 (&fw)[4], const bf16x8 (&fx)[4]) __attribute__((always_inline)) {
 #pragma unroll
@@ -257,62 +267,51 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     };
     // dq: dequantize `sdq` into bw_next during this step; has_next: a step follows (its tiles are in
     // bx_next / bw_next once the barrier is passed).  Both are literal `true` in the steady state.
+    //
+    // Slice plan (8 MFMAs per slice; fragment set = quarter & 1; every LDS read two slices before use):
+    //   0: table reads of piece 0, fragments of quarter 1, offsets of piece 1
+    //   1: table reads of piece 1, offsets of piece 2
+    //   2: table reads of piece 2, fragments of quarter 2, finish piece 0, offsets of piece 3
+    //   3: table reads of piece 3, finish piece 1
+    //   4: fragments of quarter 3, finish piece 2
+    //   5: finish piece 3
+    //   6: wait for the copies, barrier, fragments of quarter 0 of the next step
+    //   7: -
     auto run_step = [&](const unsigned char* bx, const unsigned char* bw, const unsigned char* bx_next,
                         unsigned char* bw_next, const bool dq, const Staged<QMODE>& sdq, const bool has_next)
         __attribute__((always_inline)) {
-        float lv[3][8];
-        uint32_t li[3][8];
+        float2 lv[3][8];
+        uint32_t li[2][8];
         if (dq) table_offsets(sdq, 0, li[0]);
 #pragma unroll
         for (int h = 0; h < 8; ++h) {
             const int ks = h >> 1, half = h & 1, cur = ks & 1, nxt = cur ^ 1;
+            if (h == 6 && has_next) {
+                __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): direct copies and staged codes
+                __syncthreads();                           // next tiles published; this step's tiles free
+                read_wf(bw_next, 0, wf[0]);
+                read_xf(bx_next, 0, xf[0]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
             if (dq) {
-                if (h >= 1 && h <= 6) finish_piece(sdq, h - 1, lv[(h - 1) % 3], bw_next);
-                if (h <= 6) table_reads(li[h % 3], lv[h % 3]);
-                if (h <= 5) table_offsets(sdq, h + 1, li[(h + 1) % 3]);
-                if (h == 6) {
-                    table_offsets(sdq, 7, li[7 % 3]);
-                    table_reads(li[7 % 3], lv[7 % 3]);
-                }
+                if (h >= 2 && h <= 5) finish_piece(sdq, h - 2, lv[(h - 2) % 3], bw_next);
+                if (h <= 3) table_reads(li[h & 1], lv[h % 3]);
+                if (h <= 2) table_offsets(sdq, h + 1, li[(h + 1) & 1]);
             }
-            if (ks < 3) {
-                if (half == 0) read_wf(bw, ks + 1, wf[nxt]);
-                else read_xf(bx, ks + 1, xf[nxt]);
+            if (half == 0 && ks < 3) {
+                read_wf(bw, ks + 1, wf[nxt]);
+                read_xf(bx, ks + 1, xf[nxt]);
             }
-            if (h < 7) {
-                mfma_row(2 * half, wf[cur], xf[cur]);
-                mfma_row(2 * half + 1, wf[cur], xf[cur]);
+            mfma_row(2 * half, wf[cur], xf[cur]);
+            mfma_row(2 * half + 1, wf[cur], xf[cur]);
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);       // vector ALU
-                    if (i < 4) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);   // LDS reads
-                    if (i == 3) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // LDS store of the finished piece
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            } else {
-                mfma_row(2, wf[cur], xf[cur]);
-                if (dq) {
-                    finish_piece(sdq, 6, lv[6 % 3], bw_next);
-                    finish_piece(sdq, 7, lv[7 % 3], bw_next);
-                }
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
-                    if (i & 1) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                if (has_next) {
-                    __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): direct copies and staged codes
-                    __syncthreads();                           // next tiles published; this step's tiles free
-                    read_wf(bw_next, 0, wf[0]);
-                    read_xf(bx_next, 0, xf[0]);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                mfma_row(3, wf[cur], xf[cur]);
-                __builtin_amdgcn_sched_barrier(0);
+            for (int i = 0; i < 8; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                   // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                   // LDS reads
+                __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);                   // vector ALU
+                if (i == 3 || i == 7) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // a piece's LDS stores
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
@@ -348,7 +347,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         issue_copies(0, 0);
         if (steps1 > 0) load_staged(st[0], 0);
         if (steps1 > 1) load_staged(st[1], 1);
-        __syncthreads();                                   // lut visible
+        __syncthreads();                                   // pair table visible
         if (steps1 > 0) dequant_store(st[0], sW);
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
@@ -406,7 +405,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 
 template <int QMODE, bool BETA>
 int launch_cfg(const GemmDesc& d, hipStream_t st) {
-    constexpr size_t smem = 4 * kTileBytes;
+    constexpr size_t smem = 4 * kTileBytes + kTableBytes;
     auto kern = k_qlinear<QMODE, BETA>;
     static bool attr_set = false;
     if (!attr_set) {
