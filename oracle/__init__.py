@@ -141,9 +141,14 @@ def forward(Wt, X, A, B, lam1, lam2, s, want_intermediates=False):
     return (Y, P, U, V) if want_intermediates else Y
 
 
-def backward(Wt, X, dY, A, B, lam1, lam2, s, compute_dx=True, compute_dab=True):
-    Wt = _c(Wt, np.float64); X = _c(X, np.uint16); dY = _c(dY, np.uint16)
-    d_out, d_in = Wt.shape
+def backward(Wt, X, dY, A, B, lam1, lam2, s, compute_dx=True, compute_dab=True, d_out=None, d_in=None):
+    """Wt may be None (with d_out, d_in given) when compute_dx is False: dA, dB do not involve the base weight."""
+    X = _c(X, np.uint16); dY = _c(dY, np.uint16)
+    if Wt is None:
+        assert not compute_dx and d_out is not None and d_in is not None
+    else:
+        Wt = _c(Wt, np.float64)
+        d_out, d_in = Wt.shape
     T = X.shape[0]
     assert X.shape == (T, d_in) and dY.shape == (T, d_out)
     dX = np.zeros((T, d_in), np.float64) if compute_dx else None

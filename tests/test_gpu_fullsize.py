@@ -1,0 +1,93 @@
+"""GPU parity at the full layer shapes of the workloads, in the launch configuration bench.py times.
+
+The benchmark workload (LLaMA-7B attention projection, T = 8192, 4096 x 4096, rank 64, lambda 2) is
+checked end to end: integer outputs bit for bit in full, forward / backward-dX on a seeded sample of
+token rows (each output row depends on its own input row only, so the oracle evaluates exactly those
+rows), the parameter gradients in full (they need every token).  The larger layer shapes (7B MLP,
+65B with double-quantized scales) run with the real weight shape and a reduced token count so that
+the fp64 oracle stays within seconds; they cover the non-power-of-two widths 11008 and 22016.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2407_17029_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def qb():
+    from paper_2407_17029_amd import binding
+    binding.lib()
+    return binding
+
+
+def _run_layer(qb, oracle, codebook, seed, T, d_out, d_in, rank, lam, s, grouped, sample, full_grads):
+    from gpu_util import (f32_to_dev, to_np, bf16_to_dev, adapter_to_dev, assert_close_bf16, assert_close_f32,
+                          bf16_to_f64)
+    R = lam * rank
+    print(f"full-size case T={T} {d_out}x{d_in} R={R} grouped={grouped}", flush=True)
+    L = synth.make_layer(seed, T, d_out, d_in, R, lam, lam)
+    qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 64, qb.QUANT_ABSMAX_CODEBOOK, codebook,
+                                      qb.SCALES_E4M3_GROUPED if grouped else qb.SCALES_FP32)
+    ad = adapter_to_dev(L, lam, lam, s)
+    X, dY = bf16_to_dev(L.X), bf16_to_dev(L.dY)
+    Y = qb.qblora_linear_fwd(qw, ad, X)
+    dX, dA, dB = qb.qblora_linear_bwd(qw, ad, X, dY)
+    H = qb.qblora_tile_product(ad, d_in, d_out)
+    merged = qb.qablora_merge_quantize(qw, H, lam, lam, s, qb.MERGE_REQUANT_MINMAX)
+    torch.cuda.synchronize()
+
+    # integer paths, in full
+    codes, absmax = oracle.quantize_codebook(L.W, 64, codebook)
+    assert np.array_equal(to_np(qw.codes), codes)
+    assert np.array_equal(to_np(qw.scales).view(np.uint32), absmax.view(np.uint32))
+    scales = absmax
+    if grouped:
+        sc, stp, mid = oracle.scales_double_quantize(absmax.reshape(-1), 256)
+        assert np.array_equal(to_np(qw.scale_codes), sc)
+        assert np.array_equal(to_np(qw.scale_step).view(np.uint32), stp.view(np.uint32))
+        assert np.array_equal(to_np(qw.scale_mid).view(np.uint32), mid.view(np.uint32))
+        scales = oracle.scales_double_dequantize(sc, stp, mid, 256).reshape(absmax.shape)
+    Hh = to_np(H)
+    co, ao, bo = oracle.merge_requant(codes, scales, None, codebook, Hh, 64, lam, lam, s)
+    assert np.array_equal(to_np(merged.codes), co)
+    assert np.array_equal(to_np(merged.scales).view(np.uint32), ao.view(np.uint32))
+    assert np.array_equal(to_np(merged.beta).view(np.uint32), bo.view(np.uint32))
+    assert_close_f32(H, oracle.tile_product(L.A, L.B), "H")
+
+    # forward / backward-dX on sampled token rows
+    Wt = oracle.dequantize(codes, scales, None, codebook, 64, 2)
+    rows = synth.sample_rows(T, sample, seed)
+    Xs, dYs = np.ascontiguousarray(L.X[rows]), np.ascontiguousarray(L.dY[rows])
+    ridx = torch.from_numpy(rows).to(Y.device)
+    assert_close_bf16(Y[ridx], oracle.forward(Wt, Xs, L.A, L.B, lam, lam, s), "Y (sampled rows)")
+    rX, _, _ = oracle.backward(Wt, Xs, dYs, L.A, L.B, lam, lam, s, compute_dx=True, compute_dab=False)
+    assert_close_bf16(dX[ridx], rX, "dX (sampled rows)")
+    del Wt
+
+    # parameter gradients need every token
+    if full_grads:
+        _, rA, rB = oracle.backward(None, L.X, L.dY, L.A, L.B, lam, lam, s, compute_dx=False, compute_dab=True,
+                                    d_out=d_out, d_in=d_in)
+        assert_close_f32(dA, rA, "dA")
+        assert_close_f32(dB, rB, "dB")
+
+
+def test_benchmark_workload_llama7b_attn(qb, oracle, codebook):
+    wl = synth.WORKLOADS["llama7b_attn"]
+    p = wl.projections[0]
+    _run_layer(qb, oracle, codebook, wl.seed, wl.tokens, p.d_out, p.d_in, wl.rank, wl.lam, wl.s, False, 160, True)
+
+
+def test_llama7b_mlp_shapes_reduced_tokens(qb, oracle, codebook):
+    wl = synth.WORKLOADS["llama7b_mlp"]
+    for i, p in enumerate((wl.projections[0], wl.projections[2])):      # up [11008x4096] and down [4096x11008]
+        _run_layer(qb, oracle, codebook, wl.seed + 1 + i, 768, p.d_out, p.d_in, wl.rank, wl.lam, wl.s, False, 96, True)
+
+
+def test_llama65b_down_proj_grouped_scales_reduced_tokens(qb, oracle, codebook):
+    wl = synth.WORKLOADS["llama65b_layer"]
+    p = wl.projections[6]                                                # down_proj [8192 x 22016]
+    _run_layer(qb, oracle, codebook, wl.seed + 7, 320, p.d_out, p.d_in, wl.rank, wl.lam, wl.s, True, 64, True)
