@@ -384,23 +384,36 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 
     __builtin_amdgcn_s_waitcnt(0x0F70);                    // nothing may still be writing this workgroup's LDS
 
-    // ---- epilogue: lane holds features n..n+3 of one token per accumulator quad -----------------------
+    // ---- epilogue ---------------------------------------------------------------------------------------
+    // A lane holds features n..n+3 of one token per accumulator quad, i.e. 8 bytes of an output row.
+    // The wave first lays its 128 x 128 quadrant out in LDS (the tiles are dead by now) as bf16 rows of
+    // 256 bytes (pitch 272), then reads it back 16 bytes per lane so that every global store
+    // instruction writes four complete 256-byte row segments.
+    __syncthreads();                                       // every wave is done reading the tiles
+    {
+        constexpr int kPitch = 272;
+        unsigned char* eb = smem + wave * (128 * kPitch);
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+        for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int64_t m = m0 + wm0 + b * 32 + r;
-            if (m >= M) continue;
+            for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn0 + a * 32 + q * 8 + hi * 4;
-                if (n >= N) continue;
-                uint2 o;
-                o.x = pack_bf16(acc[a][b][q * 4 + 0] * out_scale, acc[a][b][q * 4 + 1] * out_scale);
-                o.y = pack_bf16(acc[a][b][q * 4 + 2] * out_scale, acc[a][b][q * 4 + 3] * out_scale);
-                *reinterpret_cast<uint2*>(C + m * ldc + n) = o;
-            }
+                for (int q = 0; q < 4; ++q) {
+                    uint2 o;
+                    o.x = pack_bf16(acc[a][b][q * 4 + 0] * out_scale, acc[a][b][q * 4 + 1] * out_scale);
+                    o.y = pack_bf16(acc[a][b][q * 4 + 2] * out_scale, acc[a][b][q * 4 + 3] * out_scale);
+                    *reinterpret_cast<uint2*>(eb + (b * 32 + r) * kPitch + (a * 32 + q * 8 + hi * 4) * 2) = o;
+                }
+        const int erow = lane >> 4, echunk = lane & 15;
+        const int n = n0 + wn0 + echunk * 8;
+#pragma unroll 8
+        for (int i = 0; i < 32; ++i) {
+            const int row = i * 4 + erow;
+            const uint4 v = *reinterpret_cast<const uint4*>(eb + row * kPitch + echunk * 16);
+            const int64_t m = m0 + wm0 + row;
+            if (m < M && n < N) *reinterpret_cast<uint4*>(C + m * ldc + n) = v;
         }
+    }
 }
 
 template <int QMODE, bool BETA>
