@@ -66,6 +66,14 @@ enum { QBLORA_MERGE_BETA_SHIFT = 0, QBLORA_MERGE_REQUANT_MINMAX = 1 };
  *              the codes were chosen against) and may be NULL for consumers.
  *   scale_codes [d_out*d_in/block] bytes, OCP E4M3 bit patterns.
  *   scale_step, scale_mid  fp32 [ceil(nblocks/scale_group)].
+ *   codes_tiled optional second copy of the codes (NULL = absent) in the order the forward kernel
+ *              streams them, qblora_codes_tiled_bytes() bytes: output rows in tiles of 256, and for
+ *              tile i and 64-wide input step j one contiguous 8 KiB block at ((i*(d_in/64) + j)*256 + r)*32
+ *              holding the 32 code bytes of row 256*i + r, inputs [64j, 64j+64) (runs of rows past d_out
+ *              are never used for a result; qblora_prepack_codes zeroes them).  The base weight is frozen (Sec. 3.1), so this is a one-off re-layout: written by
+ *              qblora_quantize_blockwise when the pointer is set, or by qblora_prepack_codes.  `codes`
+ *              stays the reference layout; qblora_linear_fwd reads `codes_tiled` when it is present and
+ *              `codes` otherwise, with identical results.
  */
 typedef struct qblora_qweight {
     int32_t d_out;
@@ -80,6 +88,7 @@ typedef struct qblora_qweight {
     uint8_t* scale_codes;
     float* scale_step;
     float* scale_mid;
+    uint8_t* codes_tiled;
 } qblora_qweight;
 
 /*
@@ -112,15 +121,22 @@ typedef struct qblora_adapter {
  *             mid = (min+max)*0.5, step = max|scale - mid|/448, code = E4M3 nearest-even of
  *             (scale - mid)/step saturating at 448 (step = 0 and codes 0 when all equal).
  *   out       host struct whose device pointers the caller has filled in (codes, scales, and
- *             beta or scale_codes/scale_step/scale_mid as the mode needs); the call fills the
- *             scalar fields and the codebook and overwrites the device buffers.  The absmax
- *             quantizer sets out->beta to NULL (beta = 0).
+ *             beta or scale_codes/scale_step/scale_mid as the mode needs, codes_tiled or NULL); the
+ *             call fills the scalar fields and the codebook and overwrites the device buffers.  The
+ *             absmax quantizer sets out->beta to NULL (beta = 0).
  * All fp32 arithmetic is single IEEE operations in the order written above, so the outputs
  * are reproducible bit for bit.  d_in must be a multiple of `block`; block must be 64.
  */
 int qblora_quantize_blockwise(const float* W, int32_t d_out, int32_t d_in, int32_t block,
                               int32_t quantizer, const float* codebook /* host, 16 values */,
                               int32_t scale_mode, qblora_qweight* out, void* stream);
+
+/*
+ * Size of the tiled code copy of a [d_out, d_in] weight, and the one-off re-layout itself
+ * (qw->codes -> qw->codes_tiled, both device buffers of the caller).
+ */
+size_t qblora_codes_tiled_bytes(int32_t d_out, int32_t d_in);
+int qblora_prepack_codes(const qblora_qweight* qw, void* stream);
 
 /*
  * Dequantize (Eq. 1) to the 16-bit compute weight: Wt[n,k] = bf16(c[code]*alpha) or
@@ -185,7 +201,7 @@ int qblora_tile_product(const qblora_adapter* ad, int32_t d_in, int32_t d_out, f
  *                                qblora_quantize_blockwise; out gets codes, alpha, beta and
  *                                the codebook 0..15, scale_mode FP32.
  * `out` is a host struct with caller-filled device pointers (codes, scales, beta), as for the
- * quantizer.  Outputs are reproducible bit for bit given H.
+ * quantizer; the merge does not write a tiled code copy and sets out->codes_tiled to NULL.  Outputs are reproducible bit for bit given H.
  */
 int qablora_merge_quantize(const qblora_qweight* base, const float* H, int32_t lambda1, int32_t lambda2,
                            float s, int32_t mode, qblora_qweight* out, void* stream);

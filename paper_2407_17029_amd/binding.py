@@ -24,7 +24,7 @@ MERGE_BETA_SHIFT, MERGE_REQUANT_MINMAX = 0, 1
 EXPORTS = ["qblora_quantize_blockwise", "qblora_dequantize_bf16", "qblora_linear_fwd_workspace_bytes",
            "qblora_linear_bwd_workspace_bytes", "qblora_linear_fwd", "qblora_linear_bwd",
            "qblora_tile_product_workspace_bytes", "qblora_tile_product", "qablora_merge_quantize",
-           "qblora_strerror", "qblora_profile_events"]
+           "qblora_strerror", "qblora_profile_events", "qblora_codes_tiled_bytes", "qblora_prepack_codes"]
 
 PROFILE_FWD_GEMM, PROFILE_BWD_GEMM, PROFILE_MERGE, PROFILE_QUANTIZE = 0, 1, 2, 3
 
@@ -33,7 +33,7 @@ class CQWeight(C.Structure):
     _fields_ = [("d_out", C.c_int32), ("d_in", C.c_int32), ("block", C.c_int32), ("scale_mode", C.c_int32),
                 ("scale_group", C.c_int32), ("codebook", C.c_float * 16), ("codes", C.c_void_p),
                 ("scales", C.c_void_p), ("beta", C.c_void_p), ("scale_codes", C.c_void_p),
-                ("scale_step", C.c_void_p), ("scale_mid", C.c_void_p)]
+                ("scale_step", C.c_void_p), ("scale_mid", C.c_void_p), ("codes_tiled", C.c_void_p)]
 
 
 class CAdapter(C.Structure):
@@ -77,6 +77,9 @@ def lib():
         L.qablora_merge_quantize.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_int32,
                                              C.c_void_p, C.c_void_p]
         L.qblora_profile_events.argtypes = [C.c_int32, C.c_void_p, C.c_void_p]
+        L.qblora_codes_tiled_bytes.restype = C.c_size_t
+        L.qblora_codes_tiled_bytes.argtypes = [C.c_int32, C.c_int32]
+        L.qblora_prepack_codes.argtypes = [C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -113,12 +116,13 @@ class QWeight:
     """The triplet (codes, alpha, beta) of Eq. 1 on the device, plus the host-side C struct."""
 
     def __init__(self, d_out, d_in, block, codebook, codes, scales, beta=None, scale_mode=SCALES_FP32,
-                 scale_codes=None, scale_step=None, scale_mid=None, scale_group=256):
+                 scale_codes=None, scale_step=None, scale_mid=None, scale_group=256, codes_tiled=None):
         self.d_out, self.d_in, self.block = d_out, d_in, block
         self.codebook = np.asarray(codebook, np.float32)
         self.codes, self.scales, self.beta = codes, scales, beta
         self.scale_mode, self.scale_group = scale_mode, scale_group
         self.scale_codes, self.scale_step, self.scale_mid = scale_codes, scale_step, scale_mid
+        self.codes_tiled = codes_tiled          # optional tile-ordered copy of the codes (forward fast path)
 
     def c_struct(self) -> CQWeight:
         s = CQWeight()
@@ -126,7 +130,7 @@ class QWeight:
         s.scale_mode, s.scale_group = self.scale_mode, self.scale_group
         for j in range(16):
             s.codebook[j] = float(self.codebook[j])
-        for name in ("codes", "scales", "beta", "scale_codes", "scale_step", "scale_mid"):
+        for name in ("codes", "scales", "beta", "scale_codes", "scale_step", "scale_mid", "codes_tiled"):
             t = getattr(self, name)
             setattr(s, name, None if t is None else t.data_ptr())
         return s
@@ -162,8 +166,23 @@ def _adapter_ref(ad):
     return s, C.byref(s)
 
 
+def qblora_codes_tiled_bytes(d_out: int, d_in: int) -> int:
+    return int(lib().qblora_codes_tiled_bytes(d_out, d_in))
+
+
+def qblora_prepack_codes(qw: QWeight) -> QWeight:
+    """Fill (allocating if needed) the tile-ordered copy of the codes from the reference layout."""
+    if qw.codes_tiled is None:
+        qw.codes_tiled = torch.empty(qblora_codes_tiled_bytes(qw.d_out, qw.d_in), dtype=torch.uint8,
+                                     device=qw.codes.device)
+    s = qw.c_struct()
+    _check(lib().qblora_prepack_codes(C.byref(s), _stream()), "qblora_prepack_codes")
+    return qw
+
+
 def qblora_quantize_blockwise(W: torch.Tensor, block: int = 64, quantizer: int = QUANT_ABSMAX_CODEBOOK,
-                              codebook=None, scale_mode: int = SCALES_FP32, out: QWeight = None) -> QWeight:
+                              codebook=None, scale_mode: int = SCALES_FP32, out: QWeight = None,
+                              tiled: bool = True) -> QWeight:
     assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and W.dim() == 2
     d_out, d_in = W.shape
     dev = W.device
@@ -187,7 +206,10 @@ def qblora_quantize_blockwise(W: torch.Tensor, block: int = 64, quantizer: int =
         st = torch.empty(ng, dtype=torch.float32, device=dev)
         mid = torch.empty(ng, dtype=torch.float32, device=dev)
     cb = np.zeros(16, np.float32) if codebook is None else np.ascontiguousarray(codebook, np.float32)
-    qw = QWeight(d_out, d_in, block, cb, codes, scales, beta, scale_mode, sc, st, mid)
+    ct = None
+    if tiled and block == 64 and d_in % 64 == 0:
+        ct = torch.empty(qblora_codes_tiled_bytes(d_out, d_in), dtype=torch.uint8, device=dev)
+    qw = QWeight(d_out, d_in, block, cb, codes, scales, beta, scale_mode, sc, st, mid, codes_tiled=ct)
     s = qw.c_struct()
     cb_ptr = None if codebook is None else cb.ctypes.data_as(C.c_void_p)
     rc = lib().qblora_quantize_blockwise(_ptr(W), d_out, d_in, block, quantizer, cb_ptr, scale_mode, C.byref(s),
@@ -285,4 +307,5 @@ def qablora_merge_quantize(base: QWeight, H: torch.Tensor, lambda1: int, lambda2
     out.absorb(o)
     out.beta = beta_keep
     out.scale_codes = out.scale_step = out.scale_mid = None
+    out.codes_tiled = None
     return out

@@ -75,7 +75,7 @@ struct FwdSpace {
 FwdSpace carve_fwd(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T, void* ws) {
     Carver c(ws);
     FwdSpace s{};
-    if (qw->scale_mode == QBLORA_SCALES_E4M3_GROUPED) s.scales = c.take<float>(n_blocks(qw));
+    s.scales = c.take<float>((size_t)((qw->d_out + 255) / 256) * 256 * (qw->d_in / qw->block));   // tile-ordered
     if (has_adapter(ad)) {
         s.At_x = c.take<qblora_bf16>((size_t)ad->R * qw->d_in);
         s.Bt = c.take<qblora_bf16>((size_t)(qw->d_out / ad->lambda2) * ad->R);
@@ -188,7 +188,7 @@ int qblora_quantize_blockwise(const float* W, int32_t d_out, int32_t d_in, int32
     if (quantizer == QBLORA_QUANT_MINMAX_INT4) {
         for (int j = 0; j < 16; ++j) out->codebook[j] = (float)j;
         ScopedEvents ev(QBLORA_PROFILE_QUANTIZE, st);
-        return launch_quantize_minmax(W, d_out, d_in, out->codes, out->scales, out->beta, st);
+        return launch_quantize_minmax(W, d_out, d_in, out->codes, out->codes_tiled, out->scales, out->beta, st);
     }
     Codebook cb;
     for (int j = 0; j < 16; ++j) { cb.c[j] = codebook[j]; out->codebook[j] = codebook[j]; }
@@ -196,13 +196,25 @@ int qblora_quantize_blockwise(const float* W, int32_t d_out, int32_t d_in, int32
     int rc;
     {
         ScopedEvents ev(QBLORA_PROFILE_QUANTIZE, st);
-        rc = launch_quantize_codebook(W, d_out, d_in, cb, out->codes, out->scales, st);
+        rc = launch_quantize_codebook(W, d_out, d_in, cb, out->codes, out->codes_tiled, out->scales, st);
     }
     if (rc) return rc;
     if (scale_mode == QBLORA_SCALES_E4M3_GROUPED)
         rc = launch_scales_double_quantize(out->scales, n_blocks(out), out->scale_group, out->scale_codes,
                                            out->scale_step, out->scale_mid, st);
     return rc;
+}
+
+size_t qblora_codes_tiled_bytes(int32_t d_out, int32_t d_in) {
+    if (d_out <= 0 || d_in <= 0 || d_in % kBlock != 0) return 0;
+    return (size_t)((d_out + 255) / 256) * 256 * (size_t)(d_in / 2);
+}
+
+int qblora_prepack_codes(const qblora_qweight* qw, void* stream) {
+    int rc = check_qweight(qw, false);
+    if (rc) return rc;
+    if (!qw->codes || !qw->codes_tiled) return QBLORA_ERR_NULL;
+    return launch_prepack_codes(qw->codes, qw->d_out, qw->d_in, qw->codes_tiled, as_stream(stream));
 }
 
 int qblora_dequantize_bf16(const qblora_qweight* qw, qblora_bf16* Wt, void* stream) {
@@ -237,11 +249,19 @@ int qblora_linear_fwd(const qblora_qweight* qw, const qblora_adapter* ad, const 
 
     GemmDesc g{};
     g.qmode = 1;
-    if ((rc = resolve_scales(qw, ws.scales, st, &g.scales))) return rc;
+    // one launch re-orders the block scales for the forward kernel (reconstructing grouped ones) and,
+    // with an adapter, builds its K-contiguous operands
+    ScaleTiling sct{};
+    const bool grouped = qw->scale_mode == QBLORA_SCALES_E4M3_GROUPED;
+    sct.scales = grouped ? nullptr : qw->scales;
+    if (grouped) { sct.scale_codes = qw->scale_codes; sct.scale_step = qw->scale_step; sct.scale_mid = qw->scale_mid; }
+    sct.scale_group = qw->scale_group; sct.d_out = qw->d_out; sct.d_in = qw->d_in; sct.out = ws.scales;
+    g.scales = nullptr; g.scales_tiled = ws.scales;
+    if ((rc = launch_adapter_prep(adapted ? ad->A : nullptr, adapted ? ad->B : nullptr, qw->d_in, qw->d_out,
+                                  adapted ? ad->R : 0, adapted ? ad->lambda1 : 1, adapted ? ad->lambda2 : 1,
+                                  ws.At_x, ws.Bt, nullptr, st, &sct)))
+        return rc;
     if (adapted) {
-        if ((rc = launch_adapter_prep(ad->A, ad->B, qw->d_in, qw->d_out, ad->R, ad->lambda1, ad->lambda2,
-                                      ws.At_x, ws.Bt, nullptr, st)))
-            return rc;
         // s*U = (s/lambda1) * X * expand(A): average pool folded into the contraction
         GemmDesc u{};
         u.qmode = 0;
@@ -254,6 +274,7 @@ int qblora_linear_fwd(const qblora_qweight* qw, const qblora_adapter* ad, const 
     }
     g.X1 = X; g.ldx1 = qw->d_in;
     g.codes = qw->codes; g.beta = qw->beta; g.d_out = qw->d_out; g.d_in = qw->d_in; g.cb = codebook_of(qw);
+    g.codes_tiled = qw->codes_tiled;
     g.C = Y; g.ldc = qw->d_out; g.out_scale = 1.0f; g.M = T; g.N = qw->d_out;
     ScopedEvents ev(QBLORA_PROFILE_FWD_GEMM, st);
     return launch_gemm(g, st);
@@ -377,7 +398,7 @@ int qablora_merge_quantize(const qblora_qweight* base, const float* H, int32_t l
     d.codes_out = out->codes; d.alpha_out = out->scales; d.beta_out = out->beta;
     out->d_out = base->d_out; out->d_in = base->d_in; out->block = base->block;
     out->scale_mode = QBLORA_SCALES_FP32; out->scale_group = 0;
-    out->scale_codes = nullptr; out->scale_step = nullptr; out->scale_mid = nullptr;
+    out->scale_codes = nullptr; out->scale_step = nullptr; out->scale_mid = nullptr; out->codes_tiled = nullptr;
     if (mode == QBLORA_MERGE_BETA_SHIFT) {
         if (lambda1 % base->block != 0) return QBLORA_ERR_ALIGNMENT;
         std::memcpy(out->codebook, base->codebook, sizeof(out->codebook));

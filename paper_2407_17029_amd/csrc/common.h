@@ -49,10 +49,17 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? QBLORA_OK 
 
 // ---- kernels' host launchers (defined in the .hip files) -------------------------------------
 
+// `tiled` (may be NULL) receives the second, tile-ordered copy of the codes described in qblora.h
 int launch_quantize_codebook(const float* W, int d_out, int d_in, const Codebook& cb, uint8_t* codes,
-                             float* absmax, hipStream_t st);
-int launch_quantize_minmax(const float* W, int d_out, int d_in, uint8_t* codes, float* alpha, float* beta,
-                           hipStream_t st);
+                             uint8_t* tiled, float* absmax, hipStream_t st);
+int launch_quantize_minmax(const float* W, int d_out, int d_in, uint8_t* codes, uint8_t* tiled, float* alpha,
+                           float* beta, hipStream_t st);
+int launch_prepack_codes(const uint8_t* codes, int d_out, int d_in, uint8_t* tiled, hipStream_t st);
+
+// byte offset of the 32-byte run of (row n, 64-block b) in the tiled code copy
+__host__ __device__ inline int64_t tiled_run_offset(int64_t n, int64_t b, int64_t blocks_per_row) {
+    return (((n >> 8) * blocks_per_row + b) * 256 + (n & 255)) * 32;
+}
 int launch_scales_double_quantize(const float* scales, int64_t n, int group, uint8_t* scale_codes,
                                   float* step, float* mid, hipStream_t st);
 int launch_scales_reconstruct(const uint8_t* scale_codes, const float* step, const float* mid, int64_t n,
@@ -64,8 +71,16 @@ int launch_dequantize_bf16(const qblora_qweight& qw, const float* scales, qblora
 //   Bt   [d_out/lam2, R]  Bt[q,j]   = B[j, q]          (transpose)
 //   Bx   [R, d_out]       Bx[j,n]   = B[j, n/lam2]     (expand along n)
 // Any output pointer may be NULL to skip it.
+// Optional extra job of the same launch: the block scales (fp32, or reconstructed from the grouped E4M3
+// form when scale_codes is set) re-ordered to [row tile of 256][64-block][row in tile] for the forward kernel.
+struct ScaleTiling {
+    const float* scales; const uint8_t* scale_codes; const float* scale_step; const float* scale_mid;
+    int scale_group, d_out, d_in;
+    float* out;
+};
 int launch_adapter_prep(const qblora_bf16* A, const qblora_bf16* B, int d_in, int d_out, int R, int lam1,
-                        int lam2, qblora_bf16* At_x, qblora_bf16* Bt, qblora_bf16* Bx, hipStream_t st);
+                        int lam2, qblora_bf16* At_x, qblora_bf16* Bt, qblora_bf16* Bx, hipStream_t st,
+                        const ScaleTiling* sc = nullptr);
 
 // One GEMM launch description.  C[M,N] = out_scale1 * ( X1[M,K1] * Wq^T  +  X2[M,K2] * W2[N/div2, K2]^T )
 // "token" operands X1/X2 are bf16 row-major; the quantized segment is optional (qmode 0).
@@ -74,6 +89,8 @@ struct GemmDesc {
                                // 2: transposed use (N = d_in, K1 = d_out)
     const qblora_bf16* X1; int64_t ldx1;
     const uint8_t* codes; const float* scales; const float* beta; int d_out, d_in;
+    const uint8_t* codes_tiled;            // optional tile-ordered copy (forward only)
+    const float* scales_tiled;             // optional tile-ordered scales (forward only)
     Codebook cb;
     const qblora_bf16* X2; int64_t ldx2;
     const qblora_bf16* W2; int64_t ldw2; int K2; int div2;

@@ -41,6 +41,10 @@ struct PrepDesc {
     int tilesA_a, tilesA_b, nA;     // tile grid of the A job and its block count (0 when skipped)
     int tilesB_a, tilesB_b, nB;     // tile grid of the B-transpose job
     int nX;                         // blocks of the column-expansion job (2048 outputs each)
+    // block scales in the order the forward kernel streams them: [row tile of 256][64-block][row in tile]
+    const float* scales; const uint8_t* scale_codes; const float* scale_step; const float* scale_mid;
+    int scale_group, d_out, bpr;
+    float* scales_tiled; int nS;    // blocks of this job (256 outputs each)
 };
 
 // All re-layouts of one call in a single launch: blocks [0,nA) transpose-expand A, the next nB
@@ -58,6 +62,21 @@ __global__ __launch_bounds__(256) void k_adapter_prep(PrepDesc d) {
         return;
     }
     b -= d.nB;
+    if (b < d.nS) {
+        const int64_t o = (int64_t)b * 256 + threadIdx.x;             // ((tile*bpr + blk)*256 + r)
+        const int r = threadIdx.x;
+        const int64_t tb = b;
+        const int64_t tile = tb / d.bpr, blk = tb - tile * d.bpr;
+        const int64_t n = tile * 256 + r;
+        float v = 0.0f;
+        if (n < d.d_out) {
+            const int64_t i = n * d.bpr + blk;
+            v = d.scale_codes ? grouped_scale(d.scale_codes, d.scale_step, d.scale_mid, i, d.scale_group) : d.scales[i];
+        }
+        d.scales_tiled[o] = v;
+        return;
+    }
+    b -= d.nS;
     // Bx[j][n] = B[j][n / lam2]
     const int64_t ld = (int64_t)d.cols_B * d.lam2;
     const int64_t total = (int64_t)d.R * ld;
@@ -75,14 +94,21 @@ __global__ __launch_bounds__(256) void k_adapter_prep(PrepDesc d) {
 }  // namespace
 
 int launch_adapter_prep(const qblora_bf16* A, const qblora_bf16* B, int d_in, int d_out, int R, int lam1,
-                        int lam2, qblora_bf16* At_x, qblora_bf16* Bt, qblora_bf16* Bx, hipStream_t st) {
+                        int lam2, qblora_bf16* At_x, qblora_bf16* Bt, qblora_bf16* Bx, hipStream_t st,
+                        const ScaleTiling* sc) {
     PrepDesc d{};
+    if (sc && sc->out) {
+        d.scales = sc->scales; d.scale_codes = sc->scale_codes; d.scale_step = sc->scale_step; d.scale_mid = sc->scale_mid;
+        d.scale_group = sc->scale_group; d.d_out = sc->d_out; d.bpr = sc->d_in / kBlock; d.scales_tiled = sc->out;
+        d.nS = ((sc->d_out + 255) / 256) * d.bpr;
+    }
+    if (!A || !B) At_x = Bt = Bx = nullptr;
     d.A = A; d.B = B; d.na_A = d_in / lam1; d.R = R; d.lam1 = lam1; d.cols_B = d_out / lam2; d.lam2 = lam2;
     d.At_x = At_x; d.Bt = Bt; d.Bx = Bx;
     if (At_x) { d.tilesA_a = (d.na_A + 63) / 64; d.tilesA_b = (R + 63) / 64; d.nA = d.tilesA_a * d.tilesA_b; }
     if (Bt) { d.tilesB_a = (R + 63) / 64; d.tilesB_b = (d.cols_B + 63) / 64; d.nB = d.tilesB_a * d.tilesB_b; }
     if (Bx) d.nX = (int)(((int64_t)R * d_out + 2047) / 2048);
-    const int blocks = d.nA + d.nB + d.nX;
+    const int blocks = d.nA + d.nB + d.nS + d.nX;
     if (blocks == 0) return QBLORA_OK;
     hipLaunchKernelGGL(k_adapter_prep, dim3(blocks), dim3(256), 0, st, d);
     return launch_status();

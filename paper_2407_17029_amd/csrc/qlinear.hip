@@ -156,9 +156,25 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 
     // ---- codes / scales -> registers -------------------------------------------------------------
     int qrow = 0, qcol = 0;
+    const uint8_t* fwd_codes = nullptr;              // QMODE 1: this thread's 32 bytes of step 0 ...
+    int fwd_stride = 32;                             // ... and the distance to the next step's
+    const float* fwd_scales = nullptr;               // likewise for its block scale
+    int fwd_scale_stride = 1;
     if constexpr (QMODE == 1) {
         qrow = n0 + t;                               // this thread's stored weight row
         if (qrow > N - 1) qrow = N - 1;
+        if (d.codes_tiled) {                         // tile-ordered copy: the workgroup's step is one 8 KiB block
+            fwd_codes = d.codes_tiled + tiled_run_offset(n0 + t, 0, bpr);
+            fwd_stride = 256 * 32;
+        } else {
+            fwd_codes = codes + (int64_t)qrow * (d_in / 2);
+        }
+        if (d.scales_tiled) {
+            fwd_scales = d.scales_tiled + tiled_run_offset(n0 + t, 0, bpr) / 32;
+            fwd_scale_stride = 256;
+        } else {
+            fwd_scales = scales + (int64_t)qrow * bpr;
+        }
     } else {
         qcol = n0 + 8 * (t & 31);                    // this thread's 8 stored columns (k of the layer)
         if (qcol > N - 8) qcol = N - 8;
@@ -166,13 +182,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     auto load_staged = [&](Staged<QMODE>& s, int step) __attribute__((always_inline)) {
         const int k0 = step * kBK;
         if constexpr (QMODE == 1) {
-            const uint4* p = reinterpret_cast<const uint4*>(codes + (int64_t)qrow * (d_in / 2) + k0 / 2);
+            const uint4* p = reinterpret_cast<const uint4*>(fwd_codes + (int64_t)step * fwd_stride);
             uint4 v0 = p[0], v1 = p[1];
             s.cw[0] = v0.x; s.cw[1] = v0.y; s.cw[2] = v0.z; s.cw[3] = v0.w;
             s.cw[4] = v1.x; s.cw[5] = v1.y; s.cw[6] = v1.z; s.cw[7] = v1.w;
-            const int64_t blk = (int64_t)qrow * bpr + step;
-            s.sc[0] = scales[blk];
-            if constexpr (BETA) s.be[0] = beta[blk];
+            s.sc[0] = fwd_scales[(int64_t)step * fwd_scale_stride];
+            if constexpr (BETA) s.be[0] = beta[(int64_t)qrow * bpr + step];
         } else {
             const int nb = k0 + 8 * (t >> 5);        // 8 stored rows (contraction index)
 #pragma unroll

@@ -42,8 +42,16 @@ __device__ __forceinline__ float group16_min(float v) {
 }
 
 // Absmax / codebook quantizer.  n_vec = number of float4 groups = d_out*d_in/4 (a multiple of 16).
+// byte offset, in the tiled code copy, of the two code bytes of float4 group `idx`
+__device__ __forceinline__ int64_t tiled_pair_offset(int64_t idx, int bpr) {
+    const int64_t blk = idx >> 4;                         // 16 groups per 64-block
+    const int64_t n = blk / bpr, b = blk - n * bpr;
+    return tiled_run_offset(n, b, bpr) + 2 * (idx & 15);
+}
+
 __global__ __launch_bounds__(256) void k_quantize_codebook(const float4* __restrict__ W, int64_t n_vec,
                                                            Midpoints mp, uint16_t* __restrict__ codes16,
+                                                           uint8_t* __restrict__ tiled, int bpr,
                                                            float* __restrict__ absmax) {
     // four independent 16-byte loads per thread are issued before any arithmetic (bytes in flight)
     int64_t idx[kUnroll];
@@ -79,7 +87,9 @@ __global__ __launch_bounds__(256) void k_quantize_codebook(const float4* __restr
         };
         const uint32_t c0 = code_of(w.x), c1 = code_of(w.y), c2 = code_of(w.z), c3 = code_of(w.w);
         if (idx[u] < n_vec) {
-            codes16[idx[u]] = (uint16_t)(c0 | (c1 << 4) | (c2 << 8) | (c3 << 12));
+            const uint16_t packed = (uint16_t)(c0 | (c1 << 4) | (c2 << 8) | (c3 << 12));
+            codes16[idx[u]] = packed;
+            if (tiled) *reinterpret_cast<uint16_t*>(tiled + tiled_pair_offset(idx[u], bpr)) = packed;
             if ((threadIdx.x & 15) == 0) absmax[idx[u] >> 4] = a;
         }
     }
@@ -88,6 +98,7 @@ __global__ __launch_bounds__(256) void k_quantize_codebook(const float4* __restr
 // Min-max INT4 quantizer: alpha = (hi-lo)/15, beta = lo, code = rint((w-lo) * (15/(hi-lo))).
 __global__ __launch_bounds__(256) void k_quantize_minmax(const float4* __restrict__ W, int64_t n_vec,
                                                          uint16_t* __restrict__ codes16,
+                                                         uint8_t* __restrict__ tiled, int bpr,
                                                          float* __restrict__ alpha, float* __restrict__ beta) {
     int64_t idx[kUnroll];
     float4 wv[kUnroll];
@@ -118,6 +129,7 @@ __global__ __launch_bounds__(256) void k_quantize_minmax(const float4* __restric
         }
         if (idx[u] < n_vec) {
             codes16[idx[u]] = (uint16_t)packed;
+            if (tiled) *reinterpret_cast<uint16_t*>(tiled + tiled_pair_offset(idx[u], bpr)) = (uint16_t)packed;
             if ((threadIdx.x & 15) == 0) {
                 alpha[idx[u] >> 4] = al;
                 beta[idx[u] >> 4] = lo;
@@ -215,10 +227,35 @@ __global__ __launch_bounds__(256) void k_dequantize_bf16(const uint32_t* __restr
     out[i] = o;
 }
 
+// Tile-ordered copy of the codes: one thread moves one 16-byte half of a (row, 64-block) run; rows past
+// d_out inside the last tile are written as zeros.
+__global__ __launch_bounds__(256) void k_prepack_codes(const uint8_t* __restrict__ codes, int d_out, int bpr,
+                                                       int64_t n_halves, uint8_t* __restrict__ tiled) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;        // index of a 16-byte piece of the tiled copy
+    if (i >= n_halves) return;
+    const int half = (int)(i & 1);
+    const int64_t run = i >> 1;                                       // (tile, block, row-in-tile)
+    const int r = (int)(run & 255);
+    const int64_t tb = run >> 8;
+    const int64_t tile = tb / bpr, b = tb - tile * bpr;
+    const int64_t n = tile * 256 + r;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (n < d_out) v = *reinterpret_cast<const uint4*>(codes + (n * bpr + b) * 32 + half * 16);
+    *reinterpret_cast<uint4*>(tiled + i * 16) = v;
+}
+
 }  // namespace
 
+int launch_prepack_codes(const uint8_t* codes, int d_out, int d_in, uint8_t* tiled, hipStream_t st) {
+    const int bpr = d_in / kBlock;
+    const int64_t n_halves = (int64_t)((d_out + 255) / 256) * 256 * bpr * 2;
+    hipLaunchKernelGGL(k_prepack_codes, dim3((unsigned)((n_halves + 255) / 256)), dim3(256), 0, st, codes, d_out, bpr,
+                       n_halves, tiled);
+    return launch_status();
+}
+
 int launch_quantize_codebook(const float* W, int d_out, int d_in, const Codebook& cb, uint8_t* codes,
-                             float* absmax, hipStream_t st) {
+                             uint8_t* tiled, float* absmax, hipStream_t st) {
     Midpoints mp;
     for (int j = 0; j < 15; ++j) {
         volatile float sum = cb.c[j] + cb.c[j + 1];   // two separate fp32 roundings
@@ -228,16 +265,16 @@ int launch_quantize_codebook(const float* W, int d_out, int d_in, const Codebook
     int64_t n_vec = (int64_t)d_out * d_in / 4;
     unsigned grid = (unsigned)((n_vec + 256 * kUnroll - 1) / (256 * kUnroll));
     hipLaunchKernelGGL(k_quantize_codebook, dim3(grid), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
-                       n_vec, mp, reinterpret_cast<uint16_t*>(codes), absmax);
+                       n_vec, mp, reinterpret_cast<uint16_t*>(codes), tiled, d_in / kBlock, absmax);
     return launch_status();
 }
 
-int launch_quantize_minmax(const float* W, int d_out, int d_in, uint8_t* codes, float* alpha, float* beta,
-                           hipStream_t st) {
+int launch_quantize_minmax(const float* W, int d_out, int d_in, uint8_t* codes, uint8_t* tiled, float* alpha,
+                           float* beta, hipStream_t st) {
     int64_t n_vec = (int64_t)d_out * d_in / 4;
     unsigned grid = (unsigned)((n_vec + 256 * kUnroll - 1) / (256 * kUnroll));
     hipLaunchKernelGGL(k_quantize_minmax, dim3(grid), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
-                       n_vec, reinterpret_cast<uint16_t*>(codes), alpha, beta);
+                       n_vec, reinterpret_cast<uint16_t*>(codes), tiled, d_in / kBlock, alpha, beta);
     return launch_status();
 }
 

@@ -76,10 +76,11 @@ def test_workspace_sizes(qb):
     qw = qb.CQWeight()
     qw.d_out, qw.d_in, qw.block = 4096, 4096, 64
     qw.codes = qw.scales = 0x1000
-    assert L.qblora_linear_fwd_workspace_bytes(C.byref(qw), None, 8192) == 0
+    scales_t = 4 * 4096 * 64                                            # tile-ordered fp32 block scales
+    assert L.qblora_linear_fwd_workspace_bytes(C.byref(qw), None, 8192) == scales_t
     ad = qb.CAdapter()
     ad.lambda1, ad.lambda2, ad.R, ad.s, ad.A, ad.B = 2, 2, 128, 1.0, 0x1000, 0x1000
     fwd = L.qblora_linear_fwd_workspace_bytes(C.byref(qw), C.byref(ad), 8192)
-    assert fwd == 2 * (128 * 4096 + 2048 * 128 + 8192 * 128)          # At_x, Bt, U in bf16
+    assert fwd == scales_t + 2 * (128 * 4096 + 2048 * 128 + 8192 * 128)   # + At_x, Bt, U in bf16
     bwd = L.qblora_linear_bwd_workspace_bytes(C.byref(qw), C.byref(ad), 8192)
     assert bwd > fwd and bwd % 256 == 0

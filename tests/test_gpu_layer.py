@@ -88,6 +88,18 @@ def test_base_layer_without_adapter_and_b_zero(qb, oracle, codebook):
     assert torch.equal(Yb.view(torch.int16), Y0.view(torch.int16))
 
 
+def test_forward_same_bits_with_and_without_tiled_codes(qb, oracle, codebook):
+    T, d_out, d_in, R = 300, 576, 448, 32
+    L, qw, Wt, ad, X, dY = _setup(qb, oracle, codebook, 740, T, d_out, d_in, R, 2, 2, 1.0)
+    assert qw.codes_tiled is not None
+    Y_tiled = qb.qblora_linear_fwd(qw, ad, X)
+    tiled, qw.codes_tiled = qw.codes_tiled, None
+    Y_ref = qb.qblora_linear_fwd(qw, ad, X)
+    qw.codes_tiled = tiled
+    torch.cuda.synchronize()
+    assert torch.equal(Y_tiled.view(torch.int16), Y_ref.view(torch.int16))
+
+
 def test_minmax_base_with_beta(qb, oracle, codebook):
     from gpu_util import assert_close_bf16, assert_close_f32
     T, d_out, d_in, R = 150, 256, 384, 32

@@ -77,3 +77,30 @@ def test_dequantize_bf16_bit_exact(qb, oracle, codebook):
     torch.cuda.synchronize()
     want = oracle.dequantize(to_np(qm.codes), to_np(qm.scales), to_np(qm.beta), synth.codebook_int4(), 64, 2)
     assert np.array_equal(bf16_to_f64(Wm), want)
+
+
+@pytest.mark.parametrize("d_out,d_in", [(512, 512), (320, 192), (256, 1088)])
+def test_tiled_code_copy(qb, oracle, codebook, d_out, d_in):
+    """The tile-ordered copy holds the same code bytes as the reference layout, from either producer."""
+    from gpu_util import f32_to_dev, to_np
+    W = synth.base_weight(900 + d_in, 0, d_out, d_in)
+    qw = qb.qblora_quantize_blockwise(f32_to_dev(W), 64, qb.QUANT_ABSMAX_CODEBOOK, codebook)
+    assert qw.codes_tiled is not None and qw.codes_tiled.numel() == qb.qblora_codes_tiled_bytes(d_out, d_in)
+    from_quantizer = to_np(qw.codes_tiled).copy()
+    qw.codes_tiled = None
+    qb.qblora_prepack_codes(qw)
+    torch.cuda.synchronize()
+    from_prepack = to_np(qw.codes_tiled)
+    codes = to_np(qw.codes)                                   # [d_out, d_in/2]
+    bpr = d_in // 64
+    tiles = (d_out + 255) // 256
+    want = np.zeros((tiles, bpr, 256, 32), np.uint8)          # rows past d_out stay zero
+    for n in range(d_out):
+        want[n // 256, :, n % 256, :] = codes[n].reshape(bpr, 32)
+    got_p = from_prepack.reshape(tiles, bpr, 256, 32)
+    got_q = from_quantizer.reshape(tiles, bpr, 256, 32)
+    assert np.array_equal(got_p, want)
+    valid = np.zeros((tiles, 1, 256, 1), bool)
+    for n in range(d_out):
+        valid[n // 256, 0, n % 256, 0] = True
+    assert np.array_equal(np.where(valid, got_q, 0), want)
