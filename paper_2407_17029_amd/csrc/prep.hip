@@ -16,14 +16,21 @@ __device__ __forceinline__ void transpose_expand_tile(const uint16_t* __restrict
                                                       uint16_t (*tile)[66]) {
     const int a0 = ta * 64, b0 = tb * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;   // 64 x 4
-    for (int r = ty; r < 64; r += 4) {
-        const int a = a0 + r, b = b0 + tx;
-        tile[r][tx] = (a < na && b < nb) ? in[(int64_t)a * nb + b] : (uint16_t)0;
+    // all 16 loads of a thread are independent and issued together
+    uint16_t v[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int a = a0 + ty + 4 * i, b = b0 + tx;
+        v[i] = (a < na && b < nb) ? in[(int64_t)a * nb + b] : (uint16_t)0;
     }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) tile[ty + 4 * i][tx] = v[i];
     __syncthreads();
     const int64_t ld = (int64_t)na * e;
     const int width = 64 * e;                                  // output columns covered by this tile
-    for (int r = ty; r < 64; r += 4) {
+#pragma unroll 4
+    for (int i = 0; i < 16; ++i) {
+        const int r = ty + 4 * i;
         const int b = b0 + r;
         if (b >= nb) continue;
         for (int c = tx; c < width; c += 64) {

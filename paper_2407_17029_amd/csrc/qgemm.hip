@@ -306,8 +306,10 @@ int launch_gemm(const GemmDesc& d, hipStream_t st) {
     if (d.M <= 0 || d.N <= 0) return QBLORA_OK;
     if (d.qmode == 1 || d.qmode == 2) return launch_qlinear(d, st);
     if (skinny_applies(d)) return launch_skinny(d, st);
-    // plain bf16 GEMMs of the adapter path: narrow N (the inner rank) or small problems
-    if (d.N <= 128) return launch_cfg<128, 128, 2, 4, 0>(d, st);
+    // plain bf16 GEMMs of the adapter path that are not narrow (the tile product): 128 x 128 tiles unless
+    // 256 x 256 tiles alone give every CU at least two workgroups
+    const int64_t big_tiles = ((d.M + 255) / 256) * ((d.N + 255) / 256);
+    if (d.N <= 128 || big_tiles < 512) return launch_cfg<128, 128, 2, 4, 0>(d, st);
     return launch_cfg<256, 256, 2, 4, 0>(d, st);
 }
 

@@ -7,10 +7,12 @@
 // folded the same way).  M is the token count and K the layer width, so the kernel reads X once
 // from HBM and is bound by that stream, not by the MFMAs: the design goal is bytes in flight.
 //
-// One workgroup of 4 wave64 owns 64 tokens x 128 output columns and walks K in steps of 64 through
-// a ring of 4 LDS stages.  Both operand tiles of a stage arrive by direct global -> LDS copies
-// issued three steps ahead (6 copies per wave and stage), so up to 72 KB per workgroup are in
-// flight; one barrier per step.  Tiles are [row][64 k] bf16 with the 16-byte chunks XOR-swizzled by
+// One workgroup of 4 wave64 owns BM (32 or 64) tokens x 128 output columns and walks K in steps of 64
+// through a ring of LDS stages (6 for BM = 32, 4 for BM = 64).  Both operand tiles of a stage arrive
+// by direct global -> LDS copies issued STAGES-1 steps ahead, so 70 to 100 KB per workgroup are in
+// flight; one barrier per step.  BM = 32 doubles the number of workgroups (the token count of the
+// workloads gives only 128 workgroups of 64 tokens, half the CUs) at the price of re-reading W from L2
+// twice as often.  Tiles are [row][64 k] bf16 with the 16-byte chunks XOR-swizzled by
 // (row ^ row>>3) & 7, applied by choosing which global chunk a lane fetches.  Wave w owns output
 // columns 32w..32w+31 (MFMA A operand) for both 32-token halves (B operand).
 #include "common.h"
@@ -20,8 +22,11 @@ namespace qblora {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int BM = 64, BN = 128, kBK = 64, kStages = 4;
-constexpr int kXBytes = BM * 128, kWBytes = BN * 128, kStageBytes = kXBytes + kWBytes;
+constexpr int BN = 128, kBK = 64;
+constexpr int kWBytes = BN * 128;
+
+// s_waitcnt immediate that waits until at most n vector-memory operations are outstanding
+constexpr int vmcnt_imm(int n) { return (n & 15) | 0x0F70 | ((n >> 4) << 14); }
 
 __device__ __forceinline__ int swz(int row, int chunk) {
     return row * 128 + (((chunk ^ row ^ (row >> 3)) & 7) << 4);
@@ -36,7 +41,11 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
     return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
 }
 
+template <int BM, int kStages>
 __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
+    constexpr int kXBytes = BM * 128, kStageBytes = kXBytes + kWBytes;
+    constexpr int XC = BM / 32;                   // activation copies per wave and stage
+    constexpr int MF = BM / 32;                   // 32-token blocks per wave
     extern __shared__ __align__(16) unsigned char smem[];
     const int64_t M = d.M;
     const int N = d.N, K = d.K2;
@@ -55,12 +64,12 @@ __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
 
     // per-lane byte offsets of the copies, relative to the first row of the tile
     const int crow = lane >> 3;
-    uint32_t xoff[2], woff[4];
+    uint32_t xoff[XC], woff[4];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        int64_t lrow = wave * 16 + i * 8 + crow;
+    for (int i = 0; i < XC; ++i) {
+        int64_t lrow = wave * (8 * XC) + i * 8 + crow;
         if (m0 + lrow > M - 1) lrow = M - 1 - m0;
-        xoff[i] = (uint32_t)(lrow * ldx * 2) + (((lane & 7) ^ crow ^ ((2 * wave + i) & 7)) << 4);
+        xoff[i] = (uint32_t)(lrow * ldx * 2) + (((lane & 7) ^ crow ^ ((XC * wave + i) & 7)) << 4);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -70,47 +79,48 @@ __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
     }
     const qblora_bf16* const x_tile = X + m0 * ldx;
     const qblora_bf16* const w_tile = W + (int64_t)n0 * ldw;
-    const uint32_t lds_x = __builtin_amdgcn_readfirstlane(lds_address(smem) + wave * 16 * 128);
+    const uint32_t lds_x = __builtin_amdgcn_readfirstlane(lds_address(smem) + wave * (8 * XC) * 128);
     const uint32_t lds_w = __builtin_amdgcn_readfirstlane(lds_address(smem) + kXBytes + wave * 32 * 128);
     auto issue = [&](int step) __attribute__((always_inline)) {
-        const uint32_t stage = (step & (kStages - 1)) * kStageBytes;
+        const uint32_t stage = (step % kStages) * kStageBytes;
         const qblora_bf16* xb = x_tile + step * kBK;
         const qblora_bf16* wb = w_tile + step * kBK;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) copy16_to_lds(xb, xoff[i], lds_x + stage + i * 8 * 128);
+        for (int i = 0; i < XC; ++i) copy16_to_lds(xb, xoff[i], lds_x + stage + i * 8 * 128);
 #pragma unroll
         for (int i = 0; i < 4; ++i) copy16_to_lds(wb, woff[i], lds_w + stage + i * 8 * 128);
     };
 
-    f32x16 acc[2];
+    f32x16 acc[MF];
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < MF; ++b)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[b][i] = 0.0f;
 
     const int r = lane & 31, hi = lane >> 5;
     auto compute = [&](int step) __attribute__((always_inline)) {
-        const unsigned char* bx = smem + (step & (kStages - 1)) * kStageBytes;
+        const unsigned char* bx = smem + (step % kStages) * kStageBytes;
         const unsigned char* bw = bx + kXBytes;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             const bf16x8 wf = *reinterpret_cast<const bf16x8*>(bw + swz(wave * 32 + r, ks * 2 + hi));
 #pragma unroll
-            for (int b = 0; b < 2; ++b) {
+            for (int b = 0; b < MF; ++b) {
                 const bf16x8 xf = *reinterpret_cast<const bf16x8*>(bx + swz(b * 32 + r, ks * 2 + hi));
                 acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[b], 0, 0, 0);
             }
         }
     };
 
-    if (nsteps > 0) issue(0);
-    if (nsteps > 1) issue(1);
-    if (nsteps > 2) issue(2);
+    constexpr int kAhead = kStages - 1;           // stages in flight
+#pragma unroll
+    for (int i = 0; i < kAhead; ++i)
+        if (i < nsteps) issue(i);
     int s = 0;
-    for (; s + 3 < nsteps; ++s) {
-        __builtin_amdgcn_s_waitcnt(0x0F7C);       // vmcnt(12): the two younger stages may be in flight
+    for (; s + kAhead < nsteps; ++s) {
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm((kAhead - 1) * (XC + 4)));   // the younger stages may be in flight
         __syncthreads();                          // stage s landed for all; everyone is done with step s-1
-        issue(s + 3);                             // into the buffer step s-1 used
+        issue(s + kAhead);                        // into the buffer step s-1 used
         compute(s);
     }
     for (; s < nsteps; ++s) {
@@ -121,7 +131,7 @@ __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
 
     // lane holds columns n..n+3 of one token per accumulator quad
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < MF; ++b) {
         const int64_t m = m0 + b * 32 + r;
         if (m >= M) continue;
 #pragma unroll
@@ -155,21 +165,30 @@ __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
 bool skinny_applies(const GemmDesc& d) {
     return d.qmode == 0 && !d.out_f32 && d.div2 == 1 && d.N % 4 == 0 && d.N <= 512 && d.K2 > 0 &&
            d.K2 % kBK == 0 && d.M >= 1 && (int64_t)BN * d.ldw2 * 2 < (int64_t)1 << 31 &&
-           (int64_t)BM * d.ldx2 * 2 < (int64_t)1 << 31;
+           (int64_t)64 * d.ldx2 * 2 < (int64_t)1 << 31;
 }
 
-int launch_skinny(const GemmDesc& d, hipStream_t st) {
-    constexpr size_t smem = kStages * kStageBytes;
+template <int BM, int kStages>
+int launch_skinny_cfg(const GemmDesc& d, hipStream_t st) {
+    constexpr size_t smem = kStages * (BM * 128 + kWBytes);
+    auto kern = k_skinny<BM, kStages>;
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_skinny), hipFuncAttributeMaxDynamicSharedMemorySize,
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)smem) != hipSuccess)
             return QBLORA_ERR_LAUNCH;
         attr_set = true;
     }
     dim3 grid((unsigned)((d.M + BM - 1) / BM), (unsigned)((d.N + BN - 1) / BN));
-    hipLaunchKernelGGL(k_skinny, grid, dim3(kThreads), smem, st, d);
+    hipLaunchKernelGGL(kern, grid, dim3(kThreads), smem, st, d);
     return launch_status();
+}
+
+int launch_skinny(const GemmDesc& d, hipStream_t st) {
+    // 64-token tiles once they alone fill the chip twice over, 32-token tiles below that
+    const int64_t wgs64 = ((d.M + 63) / 64) * ((d.N + BN - 1) / BN);
+    if (wgs64 >= 512) return launch_skinny_cfg<64, 4>(d, st);
+    return launch_skinny_cfg<32, 6>(d, st);
 }
 
 }  // namespace qblora
