@@ -103,11 +103,14 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
 
-    # per-kernel HIP events, recorded by the library on the launch stream around one kernel each
+    # Per-kernel HIP events, recorded by the library on the launch stream around one kernel each.  An
+    # event record costs about 5.6 us of idle stream on this machine, so only the dominant kernel is
+    # bracketed inside the timed region; the other kernels are timed in a pass of their own afterwards.
     kinds = {"fwd_gemm": qb.PROFILE_FWD_GEMM, "bwd_gemm": qb.PROFILE_BWD_GEMM, "merge": qb.PROFILE_MERGE,
              "quantize": qb.PROFILE_QUANTIZE}
+    side_steps = min(args.steps, 10)
     events = {k: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                  for _ in range(args.steps)] for k in kinds}
+                  for _ in range(args.steps if k == "fwd_gemm" else side_steps)] for k in kinds}
     for pairs in events.values():
         for a, b in pairs:
             a.record(); b.record()          # creates the native handles
@@ -115,11 +118,18 @@ def main() -> int:
 
     t0 = time.perf_counter()
     for i in range(args.steps):
-        for k, which in kinds.items():
-            qb.qblora_profile_events(which, *events[k][i])
+        qb.qblora_profile_events(kinds["fwd_gemm"], *events["fwd_gemm"][i])
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    qb.qblora_profile_events(kinds["fwd_gemm"], None, None)
+
+    for i in range(side_steps):             # untimed: the kernels the extra "kernels" object reports
+        for k, which in kinds.items():
+            if k != "fwd_gemm":
+                qb.qblora_profile_events(which, *events[k][i])
+        step()
+    torch.cuda.synchronize()
     for which in kinds.values():
         qb.qblora_profile_events(which, None, None)
 

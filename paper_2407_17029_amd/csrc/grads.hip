@@ -7,10 +7,14 @@
 // wide L (X or dY) and a narrow S (dU or s*U, inner rank columns).  The token range is split over
 // `splits` workgroup slices so the launch fills the chip; the partial sums are written to scratch
 // and a second kernel adds them in a fixed order (deterministic), pools adjacent rows and applies
-// the scale.  Operand tiles are transposed in registers on their way into LDS so that each MFMA
-// lane reads 8 consecutive tokens of one feature as a single 16-byte word.  The narrow operand is
-// produced by this library in fp32 and handed over as a bf16 pair (high part + residual); both parts
-// are contracted, so the gradients carry fp32-accumulation error only.
+// the scale.  The narrow operand is produced by this library in fp32 and handed over as a bf16 pair
+// (high part + residual); both parts are contracted, so the gradients carry fp32-accumulation error
+// only.
+//
+// Both operands are token-major in memory while an MFMA lane needs consecutive tokens of one
+// feature.  k_grad_tr (the fast path) copies token-major tiles straight into an LDS ring and lets
+// the transposing LDS read (ds_read_b64_tr_b16) deliver the operand layout; k_grad_partial (any
+// shape and alignment) transposes in registers on the way into LDS.
 #include "common.h"
 
 namespace qblora {
@@ -130,6 +134,157 @@ __global__ __launch_bounds__(kThreads) void k_grad_partial(GradDesc d, int64_t s
     }
 }
 
+// ---- fast path: direct copies + transposing LDS reads -------------------------------------------
+//
+// A stage holds 32 tokens of three token-major tiles (L, S, S_lo), each 32 rows x 128 features of
+// bf16 = 256-byte rows of sixteen 16-byte chunks.  Logical chunk c of row t sits at chunk position
+// c ^ ((t & 3) << 2): a direct copy instruction fills four whole rows (lane l: row l>>4, position
+// l&15, so it fetches chunk (l&15) ^ ((l>>4)<<2)), and the transposing read below touches every
+// bank exactly once.
+//
+// ds_read_b64_tr_b16 works on groups of 16 lanes: if lane s of a group points at four consecutive
+// features of token row s>>2, starting at feature 4*(s&3) of a 16-feature block, lane i of the
+// group receives feature i of the block for the group's four token rows, in row order.  Two such
+// reads (rows +0..3 and +4..7) give a lane the 8 consecutive tokens of one feature that
+// v_mfma_f32_32x32x16_bf16 wants: lane groups 0/1 serve features 0-15 / 16-31 of a 32-feature block
+// for tokens 0-7 of a 16-token slice, groups 2/3 the same features for tokens 8-15.
+constexpr int kTrBT = 32, kTrStages = 6, kTrAhead = kTrStages - 1;
+constexpr int kTrTile = kTrBT * 256, kTrStage = 3 * kTrTile;
+constexpr int kTrThreads = 256;
+
+__device__ __align__(16) const uint32_t g_zero16[4] = {0u, 0u, 0u, 0u};
+
+constexpr int vmcnt_imm(int n) { return (n & 15) | 0x0F70 | ((n >> 4) << 14); }
+
+__device__ __forceinline__ void copy16_to_lds(const void* p, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(lds_base), "v"(p) : "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
+}
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+
+// 8 consecutive tokens of this lane's feature: rows +0..3 and +4..7 of the 16-token slice half
+__device__ __forceinline__ bf16x8 tr_fragment(const unsigned char* p) {
+    const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
+    const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + 4 * 256));
+    const s16x8 v = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+template <bool HAS_LO>
+__global__ __launch_bounds__(kTrThreads) void k_grad_tr(GradDesc d, int64_t slice_len) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int kPer = HAS_LO ? 6 : 4;             // copy instructions per wave and stage
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int i0 = blockIdx.x * BI, j0 = blockIdx.y * BJ, z = blockIdx.z;
+    const int64_t t_begin = (int64_t)z * slice_len;
+    int64_t t_end = t_begin + slice_len;
+    if (t_end > d.T) t_end = d.T;
+    const int nsteps = t_begin < t_end ? (int)((t_end - t_begin + kTrBT - 1) / kTrBT) : 0;
+
+    const qblora_bf16* const Lp = d.L; const int64_t ldl = d.ldl;
+    const qblora_bf16* const Sp = d.S; const qblora_bf16* const Slo = d.S_lo; const int64_t lds = d.lds;
+
+    // copies: wave w fills rows 8w .. 8w+7 of each tile with two instructions of four rows
+    const int drow = lane >> 4;
+    const int dchunk = (lane & 15) ^ (drow << 2);
+    const int lcol = i0 + 8 * dchunk, scol = j0 + 8 * dchunk;
+    const bool lcol_ok = lcol < d.I, scol_ok = scol < d.J;      // widths are multiples of 8: a chunk is in or out
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem) + wave * 8 * 256);
+    const void* const zero = g_zero16;
+    auto issue = [&](int step) __attribute__((always_inline)) {
+        const uint32_t stage = lds0 + (uint32_t)(step % kTrStages) * kTrStage;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int64_t tt = t_begin + (int64_t)step * kTrBT + wave * 8 + i * 4 + drow;
+            const bool ok = tt < t_end;                         // rows past the slice contribute zeros
+            copy16_to_lds((ok && lcol_ok) ? (const void*)(Lp + tt * ldl + lcol) : zero, stage + i * 1024);
+            copy16_to_lds((ok && scol_ok) ? (const void*)(Sp + tt * lds + scol) : zero, stage + kTrTile + i * 1024);
+            if constexpr (HAS_LO)
+                copy16_to_lds((ok && scol_ok) ? (const void*)(Slo + tt * lds + scol) : zero,
+                              stage + 2 * kTrTile + i * 1024);
+        }
+    };
+
+    // wave tile: 64 j (MFMA rows, two blocks) x 64 i (MFMA columns, two blocks)
+    const int wj0 = (wave & 1) * 64, wi0 = (wave >> 1) * 64;
+    const int g = lane >> 4, sl = lane & 15;
+    const int frow = 8 * (g >> 1) + (sl >> 2);                  // token row inside a 16-token slice
+    uint32_t soff[2], loff[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const int cs = wj0 + b * 32 + 16 * (g & 1) + 4 * (sl & 3);
+        const int cl = wi0 + b * 32 + 16 * (g & 1) + 4 * (sl & 3);
+        soff[b] = frow * 256 + ((((cs >> 3) ^ ((frow & 3) << 2)) & 15) << 4) + ((cs >> 2) & 1) * 8;
+        loff[b] = frow * 256 + ((((cl >> 3) ^ ((frow & 3) << 2)) & 15) << 4) + ((cl >> 2) & 1) * 8;
+    }
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
+
+    auto compute = [&](int step) __attribute__((always_inline)) {
+        const unsigned char* base = smem + (step % kTrStages) * kTrStage;
+#pragma unroll
+        for (int kk = 0; kk < kTrBT / 16; ++kk) {
+            bf16x8 sf[2], sflo[2], lf[2];
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                sf[b] = tr_fragment(base + kTrTile + soff[b] + kk * 16 * 256);
+                if constexpr (HAS_LO) sflo[b] = tr_fragment(base + 2 * kTrTile + soff[b] + kk * 16 * 256);
+                lf[b] = tr_fragment(base + loff[b] + kk * 16 * 256);
+            }
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf[a], lf[b], acc[a][b], 0, 0, 0);
+                    if constexpr (HAS_LO)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sflo[a], lf[b], acc[a][b], 0, 0, 0);
+                }
+        }
+    };
+
+    for (int s = 0; s < kTrAhead && s < nsteps; ++s) issue(s);
+    int s = 0;
+    for (; s + kTrAhead < nsteps; ++s) {
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm((kTrAhead - 1) * kPer));   // the younger stages may be in flight
+        __syncthreads();                             // stage s landed for all; everyone is done with step s-1
+        issue(s + kTrAhead);                         // into the buffer step s-1 used
+        compute(s);
+    }
+    for (; s < nsteps; ++s) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
+        __syncthreads();
+        compute(s);
+    }
+
+    // accumulator rows are j (4 consecutive per lane), columns are i
+    float* part = d.part + (int64_t)z * d.I * d.J;
+    const int r = lane & 31, hi = lane >> 5;
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const int i = i0 + wi0 + b * 32 + r;
+        if (i >= d.I) continue;
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int j = j0 + wj0 + a * 32 + q * 8 + hi * 4;
+                if (j >= d.J) continue;
+                *reinterpret_cast<float4*>(part + (int64_t)i * d.J + j) =
+                    make_float4(acc[a][b][q * 4 + 0], acc[a][b][q * 4 + 1], acc[a][b][q * 4 + 2], acc[a][b][q * 4 + 3]);
+            }
+    }
+}
+
 // out[i', j] (or out[j, i'] when transposed) = out_scale * sum_{p < pool} sum_z part[z][i'*pool+p][j],
 // summed in ascending (p, z) order.
 __global__ __launch_bounds__(256) void k_grad_reduce(GradDesc d) {
@@ -162,20 +317,49 @@ int grad_splits(int64_t T, int I) {
     return want;
 }
 
+namespace {
+
+// The fast path fetches 16-byte chunks: rows and widths must keep every chunk whole and aligned.
+bool tr_applies(const GradDesc& d) {
+    auto aligned16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+    return d.I % 8 == 0 && d.J % 8 == 0 && d.ldl % 8 == 0 && d.lds % 8 == 0 && aligned16(d.L) && aligned16(d.S) &&
+           (d.S_lo == nullptr || aligned16(d.S_lo));
+}
+
+template <typename K>
+int set_lds_once(K kernel, size_t smem, bool& done) {
+    if (done) return QBLORA_OK;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)smem) != hipSuccess)
+        return QBLORA_ERR_LAUNCH;
+    done = true;
+    return QBLORA_OK;
+}
+
+}  // namespace
+
 int launch_grad(const GradDesc& d, hipStream_t st) {
     if (d.T <= 0) return QBLORA_ERR_SHAPE;      // the entry point handles the empty batch itself
     int64_t slice_len = (d.T + d.splits - 1) / d.splits;
     slice_len = (slice_len + BT - 1) / BT * BT;
     dim3 grid((d.I + BI - 1) / BI, (d.J + BJ - 1) / BJ, d.splits);
-    constexpr size_t smem = 2 * BI * 128 + 4 * BJ * 128;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_grad_partial),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return QBLORA_ERR_LAUNCH;
-        attr_set = true;
+    int rc;
+    if (tr_applies(d)) {
+        constexpr size_t smem = (size_t)kTrStages * kTrStage;
+        static bool set_lo = false, set_nolo = false;
+        if (d.S_lo) {
+            if ((rc = set_lds_once(k_grad_tr<true>, smem, set_lo))) return rc;
+            hipLaunchKernelGGL(k_grad_tr<true>, grid, dim3(kTrThreads), smem, st, d, slice_len);
+        } else {
+            if ((rc = set_lds_once(k_grad_tr<false>, smem, set_nolo))) return rc;
+            hipLaunchKernelGGL(k_grad_tr<false>, grid, dim3(kTrThreads), smem, st, d, slice_len);
+        }
+    } else {
+        constexpr size_t smem = 2 * BI * 128 + 4 * BJ * 128;
+        static bool set_general = false;
+        if ((rc = set_lds_once(k_grad_partial, smem, set_general))) return rc;
+        hipLaunchKernelGGL(k_grad_partial, grid, dim3(kThreads), smem, st, d, slice_len);
     }
-    hipLaunchKernelGGL(k_grad_partial, grid, dim3(kThreads), smem, st, d, slice_len);
     int64_t total = (int64_t)(d.I / d.pool) * d.J;
     hipLaunchKernelGGL(k_grad_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, d);
     return launch_status();
