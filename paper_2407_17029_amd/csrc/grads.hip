@@ -148,9 +148,9 @@ __global__ __launch_bounds__(kThreads) void k_grad_partial(GradDesc d, int64_t s
 // reads (rows +0..3 and +4..7) give a lane the 8 consecutive tokens of one feature that
 // v_mfma_f32_32x32x16_bf16 wants: lane groups 0/1 serve features 0-15 / 16-31 of a 32-feature block
 // for tokens 0-7 of a 16-token slice, groups 2/3 the same features for tokens 8-15.
-constexpr int kTrBT = 32, kTrStages = 6, kTrAhead = kTrStages - 1;
+constexpr int kTrBT = 32, kTrStages = 6;
 constexpr int kTrTile = kTrBT * 256, kTrStage = 3 * kTrTile;
-constexpr int kTrThreads = 256;
+constexpr int kTrThreads = 512;
 
 __device__ __align__(16) const uint32_t g_zero16[4] = {0u, 0u, 0u, 0u};
 
@@ -178,9 +178,13 @@ __device__ __forceinline__ bf16x8 tr_fragment(const unsigned char* p) {
 template <bool HAS_LO>
 __global__ __launch_bounds__(kTrThreads) void k_grad_tr(GradDesc d, int64_t slice_len) {
     extern __shared__ __align__(16) unsigned char smem[];
-    constexpr int kPer = HAS_LO ? 6 : 4;             // copy instructions per wave and stage
+    constexpr int kPer = HAS_LO ? 3 : 2;             // copy instructions per wave and stage
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int i0 = blockIdx.x * BI, j0 = blockIdx.y * BJ, z = blockIdx.z;
+    // Consecutive workgroups go to different XCDs; the token slice varies fastest so that (with 8
+    // slices) all workgroups that stream one slice of S share one XCD's L2.
+    const int tiles_i = (d.I + BI - 1) / BI;
+    const int z = blockIdx.x % d.splits, rest = blockIdx.x / d.splits;
+    const int i0 = (rest % tiles_i) * BI, j0 = (rest / tiles_i) * BJ;
     const int64_t t_begin = (int64_t)z * slice_len;
     int64_t t_end = t_begin + slice_len;
     if (t_end > d.T) t_end = d.T;
@@ -189,18 +193,42 @@ __global__ __launch_bounds__(kTrThreads) void k_grad_tr(GradDesc d, int64_t slic
     const qblora_bf16* const Lp = d.L; const int64_t ldl = d.ldl;
     const qblora_bf16* const Sp = d.S; const qblora_bf16* const Slo = d.S_lo; const int64_t lds = d.lds;
 
-    // copies: wave w fills rows 8w .. 8w+7 of each tile with two instructions of four rows
+    // copies: wave w fills rows 4w .. 4w+3 of each tile with one instruction
     const int drow = lane >> 4;
     const int dchunk = (lane & 15) ^ (drow << 2);
     const int lcol = i0 + 8 * dchunk, scol = j0 + 8 * dchunk;
     const bool lcol_ok = lcol < d.I, scol_ok = scol < d.J;      // widths are multiples of 8: a chunk is in or out
-    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem) + wave * 8 * 256);
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem) + wave * 4 * 256);
     const void* const zero = g_zero16;
+    // Whole steps (every token row inside the slice) walk per-lane pointers: a lane whose chunk lies
+    // beyond the operand's width keeps fetching the zero chunk (increment 0).  Steps are issued in
+    // ascending order, so the pointers simply advance by 32 rows per call.
+    const unsigned char* pl[1]; const unsigned char* ps[1]; const unsigned char* pslo[1];
+#pragma unroll
+    for (int i = 0; i < 1; ++i) {
+        const int64_t tt = t_begin + wave * 4 + drow;
+        pl[i] = lcol_ok ? reinterpret_cast<const unsigned char*>(Lp + tt * ldl + lcol) : static_cast<const unsigned char*>(zero);
+        ps[i] = scol_ok ? reinterpret_cast<const unsigned char*>(Sp + tt * lds + scol) : static_cast<const unsigned char*>(zero);
+        pslo[i] = (HAS_LO && scol_ok) ? reinterpret_cast<const unsigned char*>(Slo + tt * lds + scol)
+                                      : static_cast<const unsigned char*>(zero);
+    }
+    const int64_t inc_l = lcol_ok ? kTrBT * ldl * 2 : 0, inc_s = scol_ok ? kTrBT * lds * 2 : 0;
     auto issue = [&](int step) __attribute__((always_inline)) {
         const uint32_t stage = lds0 + (uint32_t)(step % kTrStages) * kTrStage;
+        if (t_begin + (int64_t)(step + 1) * kTrBT <= t_end) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int64_t tt = t_begin + (int64_t)step * kTrBT + wave * 8 + i * 4 + drow;
+            for (int i = 0; i < 1; ++i) {
+                copy16_to_lds(pl[i], stage + i * 1024);
+                copy16_to_lds(ps[i], stage + kTrTile + i * 1024);
+                if constexpr (HAS_LO) copy16_to_lds(pslo[i], stage + 2 * kTrTile + i * 1024);
+                pl[i] += inc_l; ps[i] += inc_s;
+                if constexpr (HAS_LO) pslo[i] += inc_s;
+            }
+            return;
+        }
+#pragma unroll
+        for (int i = 0; i < 1; ++i) {                           // the ragged last step of the last slice
+            const int64_t tt = t_begin + (int64_t)step * kTrBT + wave * 4 + drow;
             const bool ok = tt < t_end;                         // rows past the slice contribute zeros
             copy16_to_lds((ok && lcol_ok) ? (const void*)(Lp + tt * ldl + lcol) : zero, stage + i * 1024);
             copy16_to_lds((ok && scol_ok) ? (const void*)(Sp + tt * lds + scol) : zero, stage + kTrTile + i * 1024);
@@ -210,67 +238,103 @@ __global__ __launch_bounds__(kTrThreads) void k_grad_tr(GradDesc d, int64_t slic
         }
     };
 
-    // wave tile: 64 j (MFMA rows, two blocks) x 64 i (MFMA columns, two blocks)
-    const int wj0 = (wave & 1) * 64, wi0 = (wave >> 1) * 64;
+    // wave tile: 64 j (MFMA rows, two blocks) x 32 i (MFMA columns); two waves share a SIMD
+    const int wj0 = (wave & 1) * 64, wi0 = (wave >> 1) * 32;
     const int g = lane >> 4, sl = lane & 15;
     const int frow = 8 * (g >> 1) + (sl >> 2);                  // token row inside a 16-token slice
     uint32_t soff[2], loff[2];
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
         const int cs = wj0 + b * 32 + 16 * (g & 1) + 4 * (sl & 3);
-        const int cl = wi0 + b * 32 + 16 * (g & 1) + 4 * (sl & 3);
+        const int cl = wi0 + 16 * (g & 1) + 4 * (sl & 3);
         soff[b] = frow * 256 + ((((cs >> 3) ^ ((frow & 3) << 2)) & 15) << 4) + ((cs >> 2) & 1) * 8;
         loff[b] = frow * 256 + ((((cl >> 3) ^ ((frow & 3) << 2)) & 15) << 4) + ((cl >> 2) & 1) * 8;
     }
-    f32x16 acc[2][2];
+    f32x16 acc[2][1];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
+        for (int i = 0; i < 16; ++i) acc[a][0][i] = 0.0f;
 
-    auto compute = [&](int step) __attribute__((always_inline)) {
-        const unsigned char* base = smem + (step % kTrStages) * kTrStage;
+    // A wave is alone on its SIMD, so LDS latency is hidden by hand: the fragments of the next
+    // 16-token slice are read while the MFMAs of the current one issue (two fragment sets with fixed
+    // names), and the barrier that publishes the next stage sits between the two slices of a step.
+    struct Frags { bf16x8 sf[2], sflo[2], lf[1]; };
+    auto read_frags = [&](Frags& f, int buf, int kk) __attribute__((always_inline)) {
+        const unsigned char* base = smem + buf * kTrStage + kk * 16 * 256;
 #pragma unroll
-        for (int kk = 0; kk < kTrBT / 16; ++kk) {
-            bf16x8 sf[2], sflo[2], lf[2];
-#pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                sf[b] = tr_fragment(base + kTrTile + soff[b] + kk * 16 * 256);
-                if constexpr (HAS_LO) sflo[b] = tr_fragment(base + 2 * kTrTile + soff[b] + kk * 16 * 256);
-                lf[b] = tr_fragment(base + loff[b] + kk * 16 * 256);
-            }
-#pragma unroll
-            for (int a = 0; a < 2; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b) {
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf[a], lf[b], acc[a][b], 0, 0, 0);
-                    if constexpr (HAS_LO)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sflo[a], lf[b], acc[a][b], 0, 0, 0);
-                }
+        for (int b = 0; b < 2; ++b) {
+            f.sf[b] = tr_fragment(base + kTrTile + soff[b]);
+            if constexpr (HAS_LO) f.sflo[b] = tr_fragment(base + 2 * kTrTile + soff[b]);
+            if (b == 0) f.lf[0] = tr_fragment(base + loff[0]);
         }
     };
+    auto mfmas = [&](const Frags& f) __attribute__((always_inline)) {
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 1; ++b) {
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.sf[a], f.lf[b], acc[a][b], 0, 0, 0);
+                if constexpr (HAS_LO)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.sflo[a], f.lf[b], acc[a][b], 0, 0, 0);
+            }
+    };
+    auto interleave = [&]() __attribute__((always_inline)) {        // one MFMA, then two of the pending LDS reads
+#pragma unroll
+        for (int m = 0; m < (HAS_LO ? 4 : 2); ++m) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
 
-    for (int s = 0; s < kTrAhead && s < nsteps; ++s) issue(s);
-    int s = 0;
-    for (; s + kTrAhead < nsteps; ++s) {
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm((kTrAhead - 1) * kPer));   // the younger stages may be in flight
-        __syncthreads();                             // stage s landed for all; everyone is done with step s-1
-        issue(s + kTrAhead);                         // into the buffer step s-1 used
-        compute(s);
-    }
-    for (; s < nsteps; ++s) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
+    // Ring: every buffer is filled up front; step s hands its buffer to step s + kTrStages as soon as
+    // all waves have read it (the barrier in the middle of the step).
+    static_assert(kTrBT == 32, "a step is two 16-token slices");
+    if (nsteps > 0) {
+        for (int q = 0; q < kTrStages && q < nsteps; ++q) issue(q);
+        if (nsteps >= kTrStages) __builtin_amdgcn_s_waitcnt(vmcnt_imm((kTrStages - 1) * kPer));
+        else __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
-        compute(s);
+        Frags f0, f1;
+        read_frags(f0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        int s = 0, buf = 0;
+        for (; s + kTrStages < nsteps; ++s) {
+            const int nxt = buf + 1 == kTrStages ? 0 : buf + 1;
+            read_frags(f1, buf, 1);
+            mfmas(f0);
+            interleave();
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm((kTrStages - 2) * kPer));   // stage s+1 is in; younger ones may fly
+            __syncthreads();                         // ... for every wave, and all reads of this buffer are done
+            issue(s + kTrStages);                    // refill this buffer
+            read_frags(f0, nxt, 0);
+            mfmas(f1);
+            interleave();
+            buf = nxt;
+        }
+        for (; s < nsteps; ++s) {
+            const int nxt = buf + 1 == kTrStages ? 0 : buf + 1;
+            const bool more = s + 1 < nsteps;
+            read_frags(f1, buf, 1);
+            mfmas(f0);
+            interleave();
+            if (more) {
+                __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+                __syncthreads();
+                read_frags(f0, nxt, 0);
+            }
+            mfmas(f1);
+            interleave();
+            buf = nxt;
+        }
     }
 
     // accumulator rows are j (4 consecutive per lane), columns are i
     float* part = d.part + (int64_t)z * d.I * d.J;
     const int r = lane & 31, hi = lane >> 5;
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < 1; ++b) {
         const int i = i0 + wi0 + b * 32 + r;
         if (i >= d.I) continue;
 #pragma unroll
@@ -346,13 +410,14 @@ int launch_grad(const GradDesc& d, hipStream_t st) {
     int rc;
     if (tr_applies(d)) {
         constexpr size_t smem = (size_t)kTrStages * kTrStage;
+        const dim3 flat(grid.x * grid.y * grid.z);
         static bool set_lo = false, set_nolo = false;
         if (d.S_lo) {
             if ((rc = set_lds_once(k_grad_tr<true>, smem, set_lo))) return rc;
-            hipLaunchKernelGGL(k_grad_tr<true>, grid, dim3(kTrThreads), smem, st, d, slice_len);
+            hipLaunchKernelGGL(k_grad_tr<true>, flat, dim3(kTrThreads), smem, st, d, slice_len);
         } else {
             if ((rc = set_lds_once(k_grad_tr<false>, smem, set_nolo))) return rc;
-            hipLaunchKernelGGL(k_grad_tr<false>, grid, dim3(kTrThreads), smem, st, d, slice_len);
+            hipLaunchKernelGGL(k_grad_tr<false>, flat, dim3(kTrThreads), smem, st, d, slice_len);
         }
     } else {
         constexpr size_t smem = 2 * BI * 128 + 4 * BJ * 128;
