@@ -7,14 +7,15 @@
 // folded the same way).  M is the token count and K the layer width, so the kernel reads X once
 // from HBM and is bound by that stream, not by the MFMAs: the design goal is bytes in flight.
 //
-// One workgroup of 4 wave64 owns BM (32 or 64) tokens x 128 output columns and walks K in steps of 64
-// through a ring of LDS stages (6 for BM = 32, 4 for BM = 64).  Both operand tiles of a stage arrive
-// by direct global -> LDS copies issued STAGES-1 steps ahead, so 70 to 100 KB per workgroup are in
-// flight; one barrier per step.  BM = 32 doubles the number of workgroups (the token count of the
-// workloads gives only 128 workgroups of 64 tokens, half the CUs) at the price of re-reading W from L2
-// twice as often.  Tiles are [row][64 k] bf16 with the 16-byte chunks XOR-swizzled by
-// (row ^ row>>3) & 7, applied by choosing which global chunk a lane fetches.  Wave w owns output
-// columns 32w..32w+31 (MFMA A operand) for both 32-token halves (B operand).
+// One workgroup of 4 wave64 owns BM tokens x BN output columns and walks K through a ring of LDS
+// stages (one or two 64-wide k-steps per stage and barrier).  Both operand tiles of a stage arrive by
+// direct global -> LDS copies issued STAGES-1 stages ahead.  X comes from HBM once; W (1 MB for rank
+// 128 at K = 4096) is re-read from L2 by every token tile, so the traffic through the CUs is a few
+// times the X stream and that, not HBM latency, sets the pace: measured times do not change between
+// 3 and 9 stages.  With a token count that gives only 128 tiles of 64 tokens, 64 x 64 tiles put a
+// workgroup on every CU; the two workgroups that share a token tile sit on the same XCD and the second
+// finds X in L2.  Tiles are [row][64 k] bf16 with the 16-byte chunks XOR-swizzled by
+// (row ^ row>>3) & 7, applied by choosing which global chunk a lane fetches.
 #include "common.h"
 
 namespace qblora {
@@ -22,8 +23,7 @@ namespace qblora {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int BN = 128, kBK = 64;
-constexpr int kWBytes = BN * 128;
+constexpr int kBK = 64;
 
 // s_waitcnt immediate that waits until at most n vector-memory operations are outstanding
 constexpr int vmcnt_imm(int n) { return (n & 15) | 0x0F70 | ((n >> 4) << 14); }
@@ -41,11 +41,15 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
     return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
 }
 
-template <int BM, int kStages>
+template <int BM, int BN, int kStages, int kSub, bool kSplitK>
 __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
-    constexpr int kXBytes = BM * 128, kStageBytes = kXBytes + kWBytes;
-    constexpr int XC = BM / 32;                   // activation copies per wave and stage
-    constexpr int MF = BM / 32;                   // 32-token blocks per wave
+    static_assert(!kSplitK || (BM == 64 && BN == 64), "the k-split form is written for 64 x 64 tiles");
+    // a stage holds kSub consecutive k-steps (sub-tiles of 64 k each): one barrier per kSub * 64 k
+    constexpr int kXBytes = BM * 128, kWBytes = BN * 128, kSubBytes = kXBytes + kWBytes, kStageBytes = kSub * kSubBytes;
+    constexpr int XC = BM / 32, WC = BN / 32;     // copies per wave and stage
+    constexpr int WN = BN / 32, WM = 4 / WN;      // waves along the columns / along the tokens
+    constexpr int MF = BM / (32 * WM);            // 32-token blocks per wave
+    static_assert(MF >= 1 && WN * WM == 4, "tile shape");
     extern __shared__ __align__(16) unsigned char smem[];
     const int64_t M = d.M;
     const int N = d.N, K = d.K2;
@@ -58,13 +62,18 @@ __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
     const float out_scale = d.out_scale, c2_scale = d.c2_scale;
 
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int64_t m0 = (int64_t)blockIdx.x * BM;
-    const int n0 = blockIdx.y * BN;
-    const int nsteps = K / kBK;
+    // blockIdx.x % 8 is the XCD: the column tiles of one token tile are 8 apart
+    const int tiles_n = (N + BN - 1) / BN;
+    const int grp = blockIdx.x / (8 * tiles_n), within = blockIdx.x % (8 * tiles_n);
+    const int64_t m0 = ((int64_t)grp * 8 + (within & 7)) * BM;
+    const int n0 = (within >> 3) * BN;
+    if (m0 >= M) return;                          // the grid is rounded up to whole groups of 8 token tiles
+    const int wave_n = wave % WN, wave_m = wave / WN;
+    const int nsteps = K / (kBK * kSub);
 
     // per-lane byte offsets of the copies, relative to the first row of the tile
     const int crow = lane >> 3;
-    uint32_t xoff[XC], woff[4];
+    uint32_t xoff[XC], woff[WC];
 #pragma unroll
     for (int i = 0; i < XC; ++i) {
         int64_t lrow = wave * (8 * XC) + i * 8 + crow;
@@ -72,44 +81,76 @@ __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
         xoff[i] = (uint32_t)(lrow * ldx * 2) + (((lane & 7) ^ crow ^ ((XC * wave + i) & 7)) << 4);
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int lrow = wave * 32 + i * 8 + crow;
+    for (int i = 0; i < WC; ++i) {
+        int lrow = wave * (8 * WC) + i * 8 + crow;
         if (n0 + lrow > N - 1) lrow = N - 1 - n0;
-        woff[i] = (uint32_t)((int64_t)lrow * ldw * 2) + (((lane & 7) ^ crow ^ ((4 * wave + i) & 7)) << 4);
+        woff[i] = (uint32_t)((int64_t)lrow * ldw * 2) + (((lane & 7) ^ crow ^ ((WC * wave + i) & 7)) << 4);
     }
     const qblora_bf16* const x_tile = X + m0 * ldx;
     const qblora_bf16* const w_tile = W + (int64_t)n0 * ldw;
     const uint32_t lds_x = __builtin_amdgcn_readfirstlane(lds_address(smem) + wave * (8 * XC) * 128);
-    const uint32_t lds_w = __builtin_amdgcn_readfirstlane(lds_address(smem) + kXBytes + wave * 32 * 128);
+    const uint32_t lds_w = __builtin_amdgcn_readfirstlane(lds_address(smem) + kXBytes + wave * (8 * WC) * 128);
     auto issue = [&](int step) __attribute__((always_inline)) {
         const uint32_t stage = (step % kStages) * kStageBytes;
-        const qblora_bf16* xb = x_tile + step * kBK;
-        const qblora_bf16* wb = w_tile + step * kBK;
 #pragma unroll
-        for (int i = 0; i < XC; ++i) copy16_to_lds(xb, xoff[i], lds_x + stage + i * 8 * 128);
+        for (int u = 0; u < kSub; ++u) {
+            const qblora_bf16* xb = x_tile + (step * kSub + u) * kBK;
+            const qblora_bf16* wb = w_tile + (step * kSub + u) * kBK;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) copy16_to_lds(wb, woff[i], lds_w + stage + i * 8 * 128);
+            for (int i = 0; i < XC; ++i) copy16_to_lds(xb, xoff[i], lds_x + stage + u * kSubBytes + i * 8 * 128);
+#pragma unroll
+            for (int i = 0; i < WC; ++i) copy16_to_lds(wb, woff[i], lds_w + stage + u * kSubBytes + i * 8 * 128);
+        }
     };
 
-    f32x16 acc[MF];
+    // Plain form: a wave owns 32 columns x MF token blocks and keeps one accumulator chain per
+    // sub-tile (added at the end).  k-split form (64 x 64 tiles): a 32 x 32 wave tile would read two
+    // fragments per MFMA, which is all the LDS can deliver; instead every wave computes the whole
+    // 64 x 64 tile (acc[column block][token block]) for one quarter of each sub-tile's k (slice ks ==
+    // wave), one fragment read per MFMA, and the four partial tiles are added through LDS at the end.
+    constexpr int NA = kSplitK ? 2 : kSub, NB = kSplitK ? 2 : MF;
+    f32x16 acc[NA][NB];
 #pragma unroll
-    for (int b = 0; b < MF; ++b)
+    for (int u = 0; u < NA; ++u)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[b][i] = 0.0f;
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[u][b][i] = 0.0f;
 
     const int r = lane & 31, hi = lane >> 5;
     auto compute = [&](int step) __attribute__((always_inline)) {
-        const unsigned char* bx = smem + (step % kStages) * kStageBytes;
-        const unsigned char* bw = bx + kXBytes;
+        if constexpr (kSplitK) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const bf16x8 wf = *reinterpret_cast<const bf16x8*>(bw + swz(wave * 32 + r, ks * 2 + hi));
+            for (int u = 0; u < kSub; ++u) {
+                const unsigned char* bx = smem + (step % kStages) * kStageBytes + u * kSubBytes;
+                const unsigned char* bw = bx + kXBytes;
+                bf16x8 wf[2], xf[2];
 #pragma unroll
-            for (int b = 0; b < MF; ++b) {
-                const bf16x8 xf = *reinterpret_cast<const bf16x8*>(bx + swz(b * 32 + r, ks * 2 + hi));
-                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[b], 0, 0, 0);
+                for (int a = 0; a < 2; ++a) {
+                    wf[a] = *reinterpret_cast<const bf16x8*>(bw + swz(a * 32 + r, wave * 2 + hi));
+                    xf[a] = *reinterpret_cast<const bf16x8*>(bx + swz(a * 32 + r, wave * 2 + hi));
+                }
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+#pragma unroll
+                    for (int b = 0; b < 2; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[a], xf[b], acc[a][b], 0, 0, 0);
             }
+            return;
         }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int u = 0; u < kSub; ++u) {
+                const unsigned char* bx = smem + (step % kStages) * kStageBytes + u * kSubBytes;
+                const unsigned char* bw = bx + kXBytes;
+                const bf16x8 wf = *reinterpret_cast<const bf16x8*>(bw + swz(wave_n * 32 + r, ks * 2 + hi));
+#pragma unroll
+                for (int b = 0; b < MF; ++b) {
+                    const bf16x8 xf = *reinterpret_cast<const bf16x8*>(bx + swz((wave_m * MF + b) * 32 + r, ks * 2 + hi));
+                    acc[u][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[u][b], 0, 0, 0);
+                }
+            }
     };
 
     constexpr int kAhead = kStages - 1;           // stages in flight
@@ -118,7 +159,7 @@ __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
         if (i < nsteps) issue(i);
     int s = 0;
     for (; s + kAhead < nsteps; ++s) {
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm((kAhead - 1) * (XC + 4)));   // the younger stages may be in flight
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm((kAhead - 1) * (XC + WC) * kSub));   // the younger stages may be in flight
         __syncthreads();                          // stage s landed for all; everyone is done with step s-1
         issue(s + kAhead);                        // into the buffer step s-1 used
         compute(s);
@@ -129,17 +170,47 @@ __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
         compute(s);
     }
 
+    int out_n = wave_n * 32, out_m = wave_m * MF * 32;      // first column / token of this wave's output
+    if constexpr (kSplitK) {
+        // partial tiles -> LDS (the ring is idle: the last step's data has been read by everyone after
+        // this barrier), register i of block (a, b) of wave w at float [((w*4 + a*2+b)*16 + i)*64 + lane];
+        // wave w then adds the four partials of block (a, b) = (w >> 1, w & 1) in wave order.
+        __syncthreads();
+        float* red = reinterpret_cast<float*>(smem);
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) red[((wave * 4 + a * 2 + b) * 16 + i) * 64 + lane] = acc[a][b][i];
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            float v = red[((0 * 4 + wave) * 16 + i) * 64 + lane];
+#pragma unroll
+            for (int w = 1; w < 4; ++w) v += red[((w * 4 + wave) * 16 + i) * 64 + lane];
+            acc[0][0][i] = v;
+        }
+        out_n = (wave >> 1) * 32; out_m = (wave & 1) * 32;
+    } else {
+#pragma unroll
+        for (int u = 1; u < kSub; ++u)
+#pragma unroll
+            for (int b = 0; b < MF; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[0][b][i] += acc[u][b][i];
+    }
     // lane holds columns n..n+3 of one token per accumulator quad
 #pragma unroll
-    for (int b = 0; b < MF; ++b) {
-        const int64_t m = m0 + b * 32 + r;
+    for (int b = 0; b < (kSplitK ? 1 : MF); ++b) {
+        const int64_t m = m0 + out_m + b * 32 + r;
         if (m >= M) continue;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const int n = n0 + wave * 32 + q * 8 + hi * 4;
+            const int n = n0 + out_n + q * 8 + hi * 4;
             if (n >= N) continue;
-            const float v0 = acc[b][q * 4 + 0] * out_scale, v1 = acc[b][q * 4 + 1] * out_scale;
-            const float v2 = acc[b][q * 4 + 2] * out_scale, v3 = acc[b][q * 4 + 3] * out_scale;
+            const float v0 = acc[0][b][q * 4 + 0] * out_scale, v1 = acc[0][b][q * 4 + 1] * out_scale;
+            const float v2 = acc[0][b][q * 4 + 2] * out_scale, v3 = acc[0][b][q * 4 + 3] * out_scale;
             uint2 h;
             h.x = pack_bf16(v0, v1); h.y = pack_bf16(v2, v3);
             *reinterpret_cast<uint2*>(C + m * ldc + n) = h;
@@ -164,14 +235,14 @@ __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
 // Whether launch_skinny can take this problem (otherwise the general tile kernel does).
 bool skinny_applies(const GemmDesc& d) {
     return d.qmode == 0 && !d.out_f32 && d.div2 == 1 && d.N % 4 == 0 && d.N <= 512 && d.K2 > 0 &&
-           d.K2 % kBK == 0 && d.M >= 1 && (int64_t)BN * d.ldw2 * 2 < (int64_t)1 << 31 &&
+           d.K2 % kBK == 0 && d.M >= 1 && (int64_t)128 * d.ldw2 * 2 < (int64_t)1 << 31 &&
            (int64_t)64 * d.ldx2 * 2 < (int64_t)1 << 31;
 }
 
-template <int BM, int kStages>
+template <int BM, int BN, int kStages, int kSub, bool kSplitK>
 int launch_skinny_cfg(const GemmDesc& d, hipStream_t st) {
-    constexpr size_t smem = kStages * (BM * 128 + kWBytes);
-    auto kern = k_skinny<BM, kStages>;
+    constexpr size_t smem = kStages * kSub * (BM * 128 + BN * 128);
+    auto kern = k_skinny<BM, BN, kStages, kSub, kSplitK>;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -179,16 +250,22 @@ int launch_skinny_cfg(const GemmDesc& d, hipStream_t st) {
             return QBLORA_ERR_LAUNCH;
         attr_set = true;
     }
-    dim3 grid((unsigned)((d.M + BM - 1) / BM), (unsigned)((d.N + BN - 1) / BN));
+    const int64_t tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
+    dim3 grid((unsigned)((tiles_m + 7) / 8 * 8 * tiles_n));
     hipLaunchKernelGGL(kern, grid, dim3(kThreads), smem, st, d);
     return launch_status();
 }
 
 int launch_skinny(const GemmDesc& d, hipStream_t st) {
-    // 64-token tiles once they alone fill the chip twice over, 32-token tiles below that
-    const int64_t wgs64 = ((d.M + 63) / 64) * ((d.N + BN - 1) / BN);
-    if (wgs64 >= 512) return launch_skinny_cfg<64, 4>(d, st);
-    return launch_skinny_cfg<32, 6>(d, st);
+    // 64 x 128 tiles once they alone fill the chip twice over; below that 64 x 64 tiles with a deep
+    // ring (a narrower output has nothing to split: 32-token tiles, 128 columns)
+    const int64_t wgs = ((d.M + 63) / 64) * ((d.N + 127) / 128);
+    if (wgs >= 512) return launch_skinny_cfg<64, 128, 4, 1, false>(d, st);
+    if (d.N > 64) {
+        if (d.K2 % (2 * kBK) == 0) return launch_skinny_cfg<64, 64, 5, 2, true>(d, st);
+        return launch_skinny_cfg<64, 64, 9, 1, true>(d, st);
+    }
+    return launch_skinny_cfg<32, 128, 6, 1, false>(d, st);
 }
 
 }  // namespace qblora
