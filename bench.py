@@ -84,10 +84,12 @@ def main() -> int:
     merged = qb.qablora_merge_quantize(qw, qb.qblora_tile_product(ad, d_in, d_out, H, ws), lam, lam, wl.s,
                                        qb.MERGE_REQUANT_MINMAX)
 
+    saved = torch.empty(qb.qblora_saved_bytes(ad, T), dtype=torch.uint8, device=dev)   # s*U kept from forward to backward
+
     def step():
         qb.qblora_quantize_blockwise(W, wl.block, qb.QUANT_ABSMAX_CODEBOOK, cb, scale_mode, out=qw)
-        qb.qblora_linear_fwd(qw, ad, X, Y, ws)
-        qb.qblora_linear_bwd(qw, ad, X, dY, True, True, dX, dA, dB, ws)
+        qb.qblora_linear_fwd(qw, ad, X, Y, ws, saved=saved)
+        qb.qblora_linear_bwd(qw, ad, X, dY, True, True, dX, dA, dB, ws, saved=saved)
         qb.qblora_tile_product(ad, d_in, d_out, H, ws)
         qb.qablora_merge_quantize(qw, H, lam, lam, wl.s, qb.MERGE_REQUANT_MINMAX, out=merged)
 

@@ -176,6 +176,25 @@ int qblora_linear_bwd(const qblora_qweight* qw, const qblora_adapter* ad, const 
                       void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same forward and backward with the adapter's inner activation kept in between, as a training
+ * step does (the forward of Sec. 3.2 computes s*U = s * AvgPool_lambda1(X) A anyway; dB = U^T dV of
+ * the backward needs it again).  `saved` is a device buffer of qblora_saved_bytes() bytes, 16-byte
+ * aligned, owned by the caller: qblora_linear_fwd_save fills it (bf16 [T, R] high part of s*U
+ * followed by bf16 [T, R] residual), qblora_linear_bwd_saved reads it instead of recomputing s*U from
+ * X and must be given the buffer a forward call filled for the same X, adapter and T.  Results are
+ * those of qblora_linear_fwd / qblora_linear_bwd bit for bit; everything else (arguments, workspace
+ * sizes, errors) is as for those calls.  Without an adapter `saved` is ignored and may be NULL;
+ * with one, NULL is QBLORA_ERR_NULL (the backward only needs it when dA/dB are asked for).
+ */
+size_t qblora_saved_bytes(const qblora_adapter* ad, int64_t T);
+int qblora_linear_fwd_save(const qblora_qweight* qw, const qblora_adapter* ad, const qblora_bf16* X, int64_t T,
+                           qblora_bf16* Y, qblora_bf16* saved, void* workspace, size_t workspace_bytes,
+                           void* stream);
+int qblora_linear_bwd_saved(const qblora_qweight* qw, const qblora_adapter* ad, const qblora_bf16* X,
+                            const qblora_bf16* dY, int64_t T, const qblora_bf16* saved, qblora_bf16* dX,
+                            float* dA, float* dB, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Tile matrix of a two-matrix adapter, H = A B, fp32 [d_in/lambda1, d_out/lambda2] (Alg. 1
  * get_delta_weight before the expansion; the equivalent full-size delta weight is
  * dW[k,n] = H[k/lambda1, n/lambda2]/lambda1, Sec. 3.2 "Merging Q-BLoRA").

@@ -24,7 +24,8 @@ MERGE_BETA_SHIFT, MERGE_REQUANT_MINMAX = 0, 1
 EXPORTS = ["qblora_quantize_blockwise", "qblora_dequantize_bf16", "qblora_linear_fwd_workspace_bytes",
            "qblora_linear_bwd_workspace_bytes", "qblora_linear_fwd", "qblora_linear_bwd",
            "qblora_tile_product_workspace_bytes", "qblora_tile_product", "qablora_merge_quantize",
-           "qblora_strerror", "qblora_profile_events", "qblora_codes_tiled_bytes", "qblora_prepack_codes"]
+           "qblora_strerror", "qblora_profile_events", "qblora_codes_tiled_bytes", "qblora_prepack_codes",
+           "qblora_saved_bytes", "qblora_linear_fwd_save", "qblora_linear_bwd_saved"]
 
 PROFILE_FWD_GEMM, PROFILE_BWD_GEMM, PROFILE_MERGE, PROFILE_QUANTIZE = 0, 1, 2, 3
 
@@ -80,6 +81,12 @@ def lib():
         L.qblora_codes_tiled_bytes.restype = C.c_size_t
         L.qblora_codes_tiled_bytes.argtypes = [C.c_int32, C.c_int32]
         L.qblora_prepack_codes.argtypes = [C.c_void_p, C.c_void_p]
+        L.qblora_saved_bytes.restype = C.c_size_t
+        L.qblora_saved_bytes.argtypes = [C.c_void_p, C.c_int64]
+        L.qblora_linear_fwd_save.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                             C.c_void_p, C.c_size_t, C.c_void_p]
+        L.qblora_linear_bwd_saved.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         _lib = L
     return _lib
 
@@ -244,7 +251,14 @@ def _workspace(nbytes: int, device, workspace):
     return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
 
 
-def qblora_linear_fwd(qw: QWeight, ad, X: torch.Tensor, Y: torch.Tensor = None, workspace: torch.Tensor = None):
+def qblora_saved_bytes(ad, T: int) -> int:
+    a, aref = _adapter_ref(ad)
+    return int(lib().qblora_saved_bytes(aref, T))
+
+
+def qblora_linear_fwd(qw: QWeight, ad, X: torch.Tensor, Y: torch.Tensor = None, workspace: torch.Tensor = None,
+                      saved: torch.Tensor = None):
+    """`saved` (uint8 tensor of qblora_saved_bytes()) selects qblora_linear_fwd_save."""
     assert X.is_cuda and X.dtype == torch.bfloat16 and X.is_contiguous() and X.shape[1] == qw.d_in
     T = X.shape[0]
     if Y is None:
@@ -252,13 +266,21 @@ def qblora_linear_fwd(qw: QWeight, ad, X: torch.Tensor, Y: torch.Tensor = None, 
     ws = _workspace(qblora_linear_fwd_workspace_bytes(qw, ad, T), X.device, workspace)
     s = qw.c_struct()
     a, aref = _adapter_ref(ad)
-    rc = lib().qblora_linear_fwd(C.byref(s), aref, _ptr(X), T, _ptr(Y), _ptr(ws), ws.numel(), _stream())
-    _check(rc, "qblora_linear_fwd")
+    if saved is None:
+        rc = lib().qblora_linear_fwd(C.byref(s), aref, _ptr(X), T, _ptr(Y), _ptr(ws), ws.numel(), _stream())
+        _check(rc, "qblora_linear_fwd")
+    else:
+        assert saved.is_cuda and saved.numel() * saved.element_size() >= qblora_saved_bytes(ad, T)
+        rc = lib().qblora_linear_fwd_save(C.byref(s), aref, _ptr(X), T, _ptr(Y), _ptr(saved), _ptr(ws), ws.numel(),
+                                          _stream())
+        _check(rc, "qblora_linear_fwd_save")
     return Y
 
 
 def qblora_linear_bwd(qw: QWeight, ad, X: torch.Tensor, dY: torch.Tensor, need_dx: bool = True,
-                      need_grads: bool = True, dX=None, dA=None, dB=None, workspace: torch.Tensor = None):
+                      need_grads: bool = True, dX=None, dA=None, dB=None, workspace: torch.Tensor = None,
+                      saved: torch.Tensor = None):
+    """`saved` (the buffer a forward call filled) selects qblora_linear_bwd_saved."""
     assert dY.is_cuda and dY.dtype == torch.bfloat16 and dY.is_contiguous() and dY.shape[1] == qw.d_out
     T = dY.shape[0]
     dev = dY.device
@@ -272,9 +294,14 @@ def qblora_linear_bwd(qw: QWeight, ad, X: torch.Tensor, dY: torch.Tensor, need_d
     ws = _workspace(qblora_linear_bwd_workspace_bytes(qw, ad, T), dev, workspace)
     s = qw.c_struct()
     a, aref = _adapter_ref(ad)
-    rc = lib().qblora_linear_bwd(C.byref(s), aref, _ptr(X), _ptr(dY), T, _ptr(dX), _ptr(dA), _ptr(dB), _ptr(ws),
-                                 ws.numel(), _stream())
-    _check(rc, "qblora_linear_bwd")
+    if saved is None:
+        rc = lib().qblora_linear_bwd(C.byref(s), aref, _ptr(X), _ptr(dY), T, _ptr(dX), _ptr(dA), _ptr(dB), _ptr(ws),
+                                     ws.numel(), _stream())
+        _check(rc, "qblora_linear_bwd")
+    else:
+        rc = lib().qblora_linear_bwd_saved(C.byref(s), aref, _ptr(X), _ptr(dY), T, _ptr(saved), _ptr(dX), _ptr(dA),
+                                           _ptr(dB), _ptr(ws), ws.numel(), _stream())
+        _check(rc, "qblora_linear_bwd_saved")
     return dX, dA, dB
 
 

@@ -235,8 +235,15 @@ size_t qblora_linear_bwd_workspace_bytes(const qblora_qweight* qw, const qblora_
     return carve_bwd(qw, ad, T, nullptr).bytes;
 }
 
-int qblora_linear_fwd(const qblora_qweight* qw, const qblora_adapter* ad, const qblora_bf16* X, int64_t T,
-                      qblora_bf16* Y, void* workspace, size_t workspace_bytes, void* stream) {
+size_t qblora_saved_bytes(const qblora_adapter* ad, int64_t T) {
+    if (!has_adapter(ad) || T <= 0) return 0;
+    return (size_t)2 * (size_t)T * (size_t)ad->R * sizeof(qblora_bf16);
+}
+
+namespace {
+
+int linear_fwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qblora_bf16* X, int64_t T,
+                    qblora_bf16* Y, qblora_bf16* saved, void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_layer(qw, ad);
     if (rc) return rc;
     if (T < 0) return QBLORA_ERR_SHAPE;
@@ -266,9 +273,11 @@ int qblora_linear_fwd(const qblora_qweight* qw, const qblora_adapter* ad, const 
         GemmDesc u{};
         u.qmode = 0;
         u.X2 = X; u.ldx2 = qw->d_in; u.W2 = ws.At_x; u.ldw2 = qw->d_in; u.K2 = qw->d_in; u.div2 = 1;
-        u.C = ws.U; u.ldc = ad->R; u.out_scale = ad->s / (float)ad->lambda1; u.M = T; u.N = ad->R;
+        qblora_bf16* su = saved ? saved : ws.U;               // kept for the backward: high part, then residual
+        u.C = su; u.C_lo = saved ? saved + T * ad->R : nullptr;
+        u.ldc = ad->R; u.out_scale = ad->s / (float)ad->lambda1; u.M = T; u.N = ad->R;
         if ((rc = launch_gemm(u, st))) return rc;
-        g.X2 = ws.U; g.ldx2 = ad->R; g.W2 = ws.Bt; g.ldw2 = ad->R; g.K2 = ad->R; g.div2 = ad->lambda2;
+        g.X2 = su; g.ldx2 = ad->R; g.W2 = ws.Bt; g.ldw2 = ad->R; g.K2 = ad->R; g.div2 = ad->lambda2;
     } else {
         g.K2 = 0; g.div2 = 1;
     }
@@ -280,9 +289,9 @@ int qblora_linear_fwd(const qblora_qweight* qw, const qblora_adapter* ad, const 
     return launch_gemm(g, st);
 }
 
-int qblora_linear_bwd(const qblora_qweight* qw, const qblora_adapter* ad, const qblora_bf16* X,
-                      const qblora_bf16* dY, int64_t T, qblora_bf16* dX, float* dA, float* dB,
-                      void* workspace, size_t workspace_bytes, void* stream) {
+int linear_bwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qblora_bf16* X,
+                    const qblora_bf16* dY, int64_t T, const qblora_bf16* saved, qblora_bf16* dX, float* dA,
+                    float* dB, void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_layer(qw, ad);
     if (rc) return rc;
     if (T < 0) return QBLORA_ERR_SHAPE;
@@ -311,7 +320,7 @@ int qblora_linear_bwd(const qblora_qweight* qw, const qblora_adapter* ad, const 
     if (adapted) {
         const int R = ad->R;
         if ((rc = launch_adapter_prep(ad->A, ad->B, qw->d_in, qw->d_out, R, ad->lambda1, ad->lambda2,
-                                      want_grads ? ws.At_x : nullptr, nullptr, ws.Bx, st)))
+                                      (want_grads && !saved) ? ws.At_x : nullptr, nullptr, ws.Bx, st)))
             return rc;
         // dU = s * dY * expand(B)^T (sum pool over lambda2 folded into the contraction); dUs = dU/lambda1
         GemmDesc du{};
@@ -322,18 +331,22 @@ int qblora_linear_bwd(const qblora_qweight* qw, const qblora_adapter* ad, const 
         du.M = T; du.N = R;
         if ((rc = launch_gemm(du, st))) return rc;
         if (want_grads) {
-            GemmDesc u{};
-            u.qmode = 0;
-            u.X2 = X; u.ldx2 = qw->d_in; u.W2 = ws.At_x; u.ldw2 = qw->d_in; u.K2 = qw->d_in; u.div2 = 1;
-            u.C = ws.U; u.ldc = R; u.out_scale = ad->s / (float)ad->lambda1; u.M = T; u.N = R; u.C_lo = ws.U_lo;
-            if ((rc = launch_gemm(u, st))) return rc;
+            const qblora_bf16* su = saved; const qblora_bf16* su_lo = saved ? saved + T * R : nullptr;
+            if (!saved) {                                     // s*U again from X, as the forward computed it
+                GemmDesc u{};
+                u.qmode = 0;
+                u.X2 = X; u.ldx2 = qw->d_in; u.W2 = ws.At_x; u.ldw2 = qw->d_in; u.K2 = qw->d_in; u.div2 = 1;
+                u.C = ws.U; u.ldc = R; u.out_scale = ad->s / (float)ad->lambda1; u.M = T; u.N = R; u.C_lo = ws.U_lo;
+                if ((rc = launch_gemm(u, st))) return rc;
+                su = ws.U; su_lo = ws.U_lo;
+            }
             GradDesc ga{};
             ga.L = X; ga.ldl = qw->d_in; ga.I = qw->d_in; ga.S = ws.dU; ga.S_lo = ws.dU_lo; ga.lds = R; ga.J = R; ga.T = T;
             ga.part = ws.part; ga.splits = ws.splits_a; ga.out = dA; ga.pool = ad->lambda1;
             ga.out_scale = 1.0f / (float)ad->lambda1; ga.transpose_out = 0;
             if ((rc = launch_grad(ga, st))) return rc;
             GradDesc gb{};
-            gb.L = dY; gb.ldl = qw->d_out; gb.I = qw->d_out; gb.S = ws.U; gb.S_lo = ws.U_lo; gb.lds = R; gb.J = R; gb.T = T;
+            gb.L = dY; gb.ldl = qw->d_out; gb.I = qw->d_out; gb.S = su; gb.S_lo = su_lo; gb.lds = R; gb.J = R; gb.T = T;
             gb.part = ws.part; gb.splits = ws.splits_b; gb.out = dB; gb.pool = ad->lambda2;
             gb.out_scale = 1.0f; gb.transpose_out = 1;
             if ((rc = launch_grad(gb, st))) return rc;
@@ -348,6 +361,34 @@ int qblora_linear_bwd(const qblora_qweight* qw, const qblora_adapter* ad, const 
     g.C = dX; g.ldc = qw->d_in; g.out_scale = 1.0f; g.M = T; g.N = qw->d_in;
     ScopedEvents ev(QBLORA_PROFILE_BWD_GEMM, st);
     return launch_gemm(g, st);
+}
+
+}  // namespace
+
+int qblora_linear_fwd(const qblora_qweight* qw, const qblora_adapter* ad, const qblora_bf16* X, int64_t T,
+                      qblora_bf16* Y, void* workspace, size_t workspace_bytes, void* stream) {
+    return linear_fwd_impl(qw, ad, X, T, Y, nullptr, workspace, workspace_bytes, stream);
+}
+
+int qblora_linear_fwd_save(const qblora_qweight* qw, const qblora_adapter* ad, const qblora_bf16* X, int64_t T,
+                           qblora_bf16* Y, qblora_bf16* saved, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+    if (has_adapter(ad) && T > 0 && !saved) return QBLORA_ERR_NULL;
+    return linear_fwd_impl(qw, ad, X, T, Y, has_adapter(ad) ? saved : nullptr, workspace, workspace_bytes, stream);
+}
+
+int qblora_linear_bwd(const qblora_qweight* qw, const qblora_adapter* ad, const qblora_bf16* X,
+                      const qblora_bf16* dY, int64_t T, qblora_bf16* dX, float* dA, float* dB,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+    return linear_bwd_impl(qw, ad, X, dY, T, nullptr, dX, dA, dB, workspace, workspace_bytes, stream);
+}
+
+int qblora_linear_bwd_saved(const qblora_qweight* qw, const qblora_adapter* ad, const qblora_bf16* X,
+                            const qblora_bf16* dY, int64_t T, const qblora_bf16* saved, qblora_bf16* dX,
+                            float* dA, float* dB, void* workspace, size_t workspace_bytes, void* stream) {
+    if (has_adapter(ad) && T > 0 && (dA || dB) && !saved) return QBLORA_ERR_NULL;
+    return linear_bwd_impl(qw, ad, X, dY, T, has_adapter(ad) ? saved : nullptr, dX, dA, dB, workspace,
+                           workspace_bytes, stream);
 }
 
 size_t qblora_tile_product_workspace_bytes(const qblora_adapter* ad, int32_t d_in, int32_t d_out) {

@@ -23,7 +23,8 @@ def qb():
     return binding
 
 
-def _run_layer(qb, oracle, codebook, seed, T, d_out, d_in, rank, lam, s, grouped, sample, full_grads):
+def _run_layer(qb, oracle, codebook, seed, T, d_out, d_in, rank, lam, s, grouped, sample, full_grads,
+               use_saved=False):
     from gpu_util import (f32_to_dev, to_np, bf16_to_dev, adapter_to_dev, assert_close_bf16, assert_close_f32,
                           bf16_to_f64)
     R = lam * rank
@@ -33,8 +34,9 @@ def _run_layer(qb, oracle, codebook, seed, T, d_out, d_in, rank, lam, s, grouped
                                       qb.SCALES_E4M3_GROUPED if grouped else qb.SCALES_FP32)
     ad = adapter_to_dev(L, lam, lam, s)
     X, dY = bf16_to_dev(L.X), bf16_to_dev(L.dY)
-    Y = qb.qblora_linear_fwd(qw, ad, X)
-    dX, dA, dB = qb.qblora_linear_bwd(qw, ad, X, dY)
+    saved = torch.empty(qb.qblora_saved_bytes(ad, T), dtype=torch.uint8, device=X.device) if use_saved else None
+    Y = qb.qblora_linear_fwd(qw, ad, X, saved=saved)                 # as bench.py calls them
+    dX, dA, dB = qb.qblora_linear_bwd(qw, ad, X, dY, saved=saved)
     H = qb.qblora_tile_product(ad, d_in, d_out)
     merged = qb.qablora_merge_quantize(qw, H, lam, lam, s, qb.MERGE_REQUANT_MINMAX)
     torch.cuda.synchronize()
@@ -78,7 +80,7 @@ def _run_layer(qb, oracle, codebook, seed, T, d_out, d_in, rank, lam, s, grouped
 def test_benchmark_workload_llama7b_attn(qb, oracle, codebook):
     wl = synth.WORKLOADS["llama7b_attn"]
     p = wl.projections[0]
-    _run_layer(qb, oracle, codebook, wl.seed, wl.tokens, p.d_out, p.d_in, wl.rank, wl.lam, wl.s, False, 160, True)
+    _run_layer(qb, oracle, codebook, wl.seed, wl.tokens, p.d_out, p.d_in, wl.rank, wl.lam, wl.s, False, 160, True, use_saved=True)
 
 
 def test_llama7b_mlp_shapes_reduced_tokens(qb, oracle, codebook):

@@ -100,6 +100,35 @@ def test_forward_same_bits_with_and_without_tiled_codes(qb, oracle, codebook):
     assert torch.equal(Y_tiled.view(torch.int16), Y_ref.view(torch.int16))
 
 
+@pytest.mark.parametrize("T,d_out,d_in,R,lam1,lam2,s", [CASES[1], CASES[3]])
+def test_saved_activation_calls_match_the_plain_calls(qb, oracle, codebook, T, d_out, d_in, R, lam1, lam2, s):
+    """Forward that keeps s*U + backward that reuses it: same bits as the recomputing calls, and
+    parity with the oracle."""
+    from gpu_util import assert_close_bf16, assert_close_f32
+    print(f"case saved T={T} {d_out}x{d_in} R={R} lam=({lam1},{lam2})", flush=True)
+    L, qw, Wt, ad, X, dY = _setup(qb, oracle, codebook, 900 + T, T, d_out, d_in, R, lam1, lam2, s)
+    assert qb.qblora_saved_bytes(ad, T) == 2 * T * R * 2
+    saved = torch.empty(qb.qblora_saved_bytes(ad, T), dtype=torch.uint8, device=X.device)
+    Y_s = qb.qblora_linear_fwd(qw, ad, X, saved=saved)
+    dX_s, dA_s, dB_s = qb.qblora_linear_bwd(qw, ad, X, dY, saved=saved)
+    Y = qb.qblora_linear_fwd(qw, ad, X)
+    dX, dA, dB = qb.qblora_linear_bwd(qw, ad, X, dY)
+    torch.cuda.synchronize()
+    assert torch.equal(Y_s.view(torch.int16), Y.view(torch.int16))
+    assert torch.equal(dX_s.view(torch.int16), dX.view(torch.int16))
+    assert torch.equal(dA_s, dA) and torch.equal(dB_s, dB)
+    rX, rA, rB = oracle.backward(Wt, L.X, L.dY, L.A, L.B, lam1, lam2, s)
+    assert_close_bf16(Y_s, oracle.forward(Wt, L.X, L.A, L.B, lam1, lam2, s), "Y")
+    assert_close_bf16(dX_s, rX, "dX")
+    assert_close_f32(dA_s, rA, "dA")
+    assert_close_f32(dB_s, rB, "dB")
+    # without an adapter the buffer is ignored; with one it is required
+    assert qb.qblora_saved_bytes(None, T) == 0
+    Y0 = qb.qblora_linear_fwd(qw, None, X, saved=saved)
+    torch.cuda.synchronize()
+    assert torch.equal(Y0.view(torch.int16), qb.qblora_linear_fwd(qw, None, X).view(torch.int16))
+
+
 def test_minmax_base_with_beta(qb, oracle, codebook):
     from gpu_util import assert_close_bf16, assert_close_f32
     T, d_out, d_in, R = 150, 256, 384, 32
