@@ -5,14 +5,17 @@
 //   beta-shift : blocks lie inside tiles, so delta is constant per block and only beta changes.
 //   requantize : w' = w~ + delta per element, then the min-max quantizer of Eq. 1 per block.
 //
-// Requantize tiling: a workgroup of 256 threads owns 64 output rows x 256 input columns and every
-// thread owns one whole 64-block of one row, so the block minimum and maximum are thread-local
-// (no shuffles) and all of a thread's global loads (32 bytes of codes, scale, beta) are issued
+// Requantize tiling: a workgroup of 1024 threads owns 64 output rows x 256 input columns and every
+// thread owns a quarter (16 elements) of one 64-block; the block minimum and maximum are combined
+// over the four lanes with DPP.  Short threads mean many waves (16 per SIMD over a 4096 x 4096
+// weight, about half of them resident), so loads, arithmetic and stores of different waves overlap;
+// with one thread per block the whole grid was resident at once and went through load, compute and
+// store phases in lockstep.  A thread's global loads (8 bytes of codes, scale, beta) are issued
 // before anything else.  Meanwhile the workgroup stages the deltas of its tile in LDS, transposed
 // to [n/lambda2][k/lambda1] so that a thread's deltas are contiguous (H itself is stored with
 // k/lambda1 as the slow index, so the global reads run along n).  When lambda1 divides 64 the run
-// of 64/lambda1 deltas of a block is read with 16-byte LDS loads; runs are padded by 4 floats so the
-// four blocks of a row hit different banks.
+// of 16/lambda1 deltas of a quarter is read with 8- or 16-byte LDS loads; the runs of a block are
+// padded by 4 floats so the four blocks of a row start in different banks.
 #include "common.h"
 
 namespace qblora {
@@ -20,6 +23,7 @@ namespace qblora {
 namespace {
 
 constexpr int NT = 64, KT = 256;
+constexpr int kMergeThreads = 1024;           // 64 rows x 16 quarter blocks
 
 struct TileGeom {
     int hrow0, hrows, hcol0, hcols;
@@ -48,96 +52,129 @@ __host__ __device__ inline int delta_stride(int lam1) {
     else return KT / lam1 + 3;
 }
 
+// lanes of a quad (4 consecutive lanes) exchange values: minimum / maximum over the quad
+__device__ __forceinline__ float quad_min(float v) {
+    v = fminf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, false)));
+    return fminf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xf, 0xf, false)));
+}
+__device__ __forceinline__ float quad_max(float v) {
+    v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, false)));
+    return fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xf, 0xf, false)));
+}
+
 template <bool GROUPED, bool BETA, int L1>
-__global__ __launch_bounds__(256) void k_merge_requant(MergeDesc d) {
+__global__ __launch_bounds__(kMergeThreads) void k_merge_requant(MergeDesc d) {
     __shared__ float lut[16];
     extern __shared__ __align__(16) float dl[];          // deltas, [hcols][stride]
     const int t = threadIdx.x;
     const int k0 = blockIdx.x * KT, n0 = blockIdx.y * NT;
-    const int row = t >> 2, bk = t & 3;
-    const int n = n0 + row, k = k0 + kBlock * bk;
-    const bool live = n < d.d_out && k < d.d_in;
+    const int row = t >> 4, bk = (t >> 2) & 3, sub = t & 3;
+    const int n = n0 + row, k = k0 + kBlock * bk + 16 * sub;
+    const bool live = n < d.d_out && k < d.d_in;         // the same for the four lanes of a block
     const int bpr = d.d_in / kBlock;
 
-    // this thread's block: all global loads first
-    uint4 c0 = make_uint4(0, 0, 0, 0), c1 = c0;
+    // this thread's quarter block: all global loads first
+    uint2 cq = make_uint2(0, 0);
     float a = 0.f, b = 0.f;
     int64_t blk = 0;
     if (live) {
         blk = (int64_t)n * bpr + k / kBlock;
-        const uint4* cp = reinterpret_cast<const uint4*>(d.codes + ((int64_t)n * d.d_in + k) / 2);
-        c0 = cp[0]; c1 = cp[1];
+        cq = *reinterpret_cast<const uint2*>(d.codes + ((int64_t)n * d.d_in + k) / 2);
         if constexpr (GROUPED) a = grouped_scale(d.scale_codes, d.scale_step, d.scale_mid, blk, d.scale_group);
         else a = d.scales[blk];
         if constexpr (BETA) b = d.beta[blk];
     }
 
-    // stage the deltas of the tile
+    // stage the deltas of the tile: delta = (s*H)/lambda1, a division unless lambda1 is one of the
+    // powers of two with a code path of their own, where multiplying by the (exact) reciprocal gives
+    // the same bits
     const TileGeom g = tile_geom(d, n0, k0);
     const int ldH = d.d_out / d.lam2, stride = delta_stride<L1>(d.lam1);
     if (t < 16) lut[t] = d.cb.c[t];
     const float lam1f = (float)d.lam1;
-    for (int idx = t; idx < g.hrows * g.hcols; idx += 256) {
-        const int r = idx / g.hcols, c = idx - r * g.hcols;
-        const float h = d.H[(int64_t)(g.hrow0 + r) * ldH + g.hcol0 + c];
-        dl[delta_pos<L1>(c, r, stride)] = __fdiv_rn(__fmul_rn(d.s, h), lam1f);
+    auto delta_of = [&](float h) __attribute__((always_inline)) {
+        const float sh = __fmul_rn(d.s, h);
+        if constexpr (L1 > 0) return __fmul_rn(sh, 1.0f / (float)L1);
+        else return __fdiv_rn(sh, lam1f);
+    };
+    const int hc4 = g.hcols >> 2;
+    if ((g.hcols & 3) == 0 && (hc4 & (hc4 - 1)) == 0 && (ldH & 3) == 0 && (g.hcol0 & 3) == 0 &&
+        (reinterpret_cast<uintptr_t>(d.H) & 15) == 0) {
+        // whole tiles of power-of-two lambdas: 16-byte loads along n, no division in the index
+        const int sh = 31 - __builtin_clz(hc4);
+        for (int idx = t; idx < g.hrows * hc4; idx += kMergeThreads) {
+            const int r = idx >> sh, c = (idx & (hc4 - 1)) << 2;
+            const float4 h = *reinterpret_cast<const float4*>(d.H + (int64_t)(g.hrow0 + r) * ldH + g.hcol0 + c);
+            dl[delta_pos<L1>(c, r, stride)] = delta_of(h.x);
+            dl[delta_pos<L1>(c + 1, r, stride)] = delta_of(h.y);
+            dl[delta_pos<L1>(c + 2, r, stride)] = delta_of(h.z);
+            dl[delta_pos<L1>(c + 3, r, stride)] = delta_of(h.w);
+        }
+    } else {
+        for (int idx = t; idx < g.hrows * g.hcols; idx += kMergeThreads) {
+            const int r = idx / g.hcols, c = idx - r * g.hcols;
+            dl[delta_pos<L1>(c, r, stride)] = delta_of(d.H[(int64_t)(g.hrow0 + r) * ldH + g.hcol0 + c]);
+        }
     }
     __syncthreads();
     if (!live) return;
 
-    // w' = w~ + delta for the 64 elements of the block
-    const uint32_t cw[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
-    float w[64];
+    // w' = w~ + delta for the 16 elements of the quarter
+    float w[16];
     const int c = n / d.lam2 - g.hcol0;
+    auto element = [&](int j, float de) __attribute__((always_inline)) {
+        const float cv = lut[((j < 8 ? cq.x : cq.y) >> (4 * (j & 7))) & 15];
+        const float wt = BETA ? __fmaf_rn(cv, a, b) : __fmul_rn(cv, a);
+        w[j] = __fadd_rn(wt, de);
+    };
     if constexpr (L1 > 0) {
-        constexpr int RUN = 64 / L1;
-        const float* drow = dl + c * stride + bk * (RUN + 4);
+        constexpr int RUN = 64 / L1, QR = 16 / L1;       // deltas per block / per quarter
+        const float* dq = dl + c * stride + bk * (RUN + 4) + sub * QR;
+        float de[QR];
+        if constexpr (QR % 4 == 0) {
 #pragma unroll
-        for (int q = 0; q < RUN / 4; ++q) {
-            const float4 dv = *reinterpret_cast<const float4*>(drow + 4 * q);
-            const float de[4] = {dv.x, dv.y, dv.z, dv.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-#pragma unroll
-                for (int u = 0; u < L1; ++u) {
-                    const int j = (4 * q + e) * L1 + u;
-                    const float cv = lut[(cw[j >> 3] >> (4 * (j & 7))) & 15];
-                    const float wt = BETA ? __fmaf_rn(cv, a, b) : __fmul_rn(cv, a);
-                    w[j] = __fadd_rn(wt, de[e]);
-                }
+            for (int v = 0; v < QR / 4; ++v) {
+                const float4 x = *reinterpret_cast<const float4*>(dq + 4 * v);
+                de[4 * v] = x.x; de[4 * v + 1] = x.y; de[4 * v + 2] = x.z; de[4 * v + 3] = x.w;
+            }
+        } else {
+            const float2 x = *reinterpret_cast<const float2*>(dq);
+            de[0] = x.x; de[1] = x.y;
         }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) element(j, de[j / L1]);
     } else {
         const float* drow = dl + c * stride - g.hrow0;
 #pragma unroll
-        for (int j = 0; j < 64; ++j) {
-            const float cv = lut[(cw[j >> 3] >> (4 * (j & 7))) & 15];
-            const float wt = BETA ? __fmaf_rn(cv, a, b) : __fmul_rn(cv, a);
-            w[j] = __fadd_rn(wt, drow[(k + j) / d.lam1]);
-        }
+        for (int j = 0; j < 16; ++j) element(j, drow[(k + j) / d.lam1]);
     }
     float lo = w[0], hi = w[0];
 #pragma unroll
-    for (int j = 1; j < 64; ++j) { lo = fminf(lo, w[j]); hi = fmaxf(hi, w[j]); }
+    for (int j = 1; j < 16; ++j) { lo = fminf(lo, w[j]); hi = fmaxf(hi, w[j]); }
+    lo = quad_min(lo); hi = quad_max(hi);                // minimum and maximum are exact: any order
 
     // min-max INT4 of the block: one division for the scale, one for its reciprocal
     const float range = __fsub_rn(hi, lo);
     const float al = __fdiv_rn(range, 15.0f);
-    uint32_t packed[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (al != 0.0f) {
-        const float inv = __fdiv_rn(15.0f, range);
+    const float inv = al != 0.0f ? __fdiv_rn(15.0f, range) : 0.0f;     // a flat block gets codes 0
+    // (w-lo)*inv lies in [0, 15*(1+2^-23)], so rint() of it already lies in 0..15: adding 1.5*2^23
+    // rounds to the nearest integer (ties to even) and leaves it in the low mantissa bits, above the
+    // constant 0x4B400000.  Eight such words are summed with their nibble shifts (mod 2^32) and the
+    // constants' sum, 0x4B400000 * 0x11111111 mod 2^32, is taken off once.
+    constexpr uint32_t kMagicSum = (uint32_t)(0x4B400000ull * 0x11111111ull);
+    uint32_t p0 = 0, p1 = 0;
 #pragma unroll
-        for (int j = 0; j < 64; ++j) {
-            // (w-lo)*inv lies in [0, 15*(1+2^-23)], so rint() of it already lies in 0..15: adding
-            // 1.5*2^23 rounds to the nearest integer (ties to even) and leaves it in the low mantissa bits
-            const float q = __fadd_rn(__fmul_rn(__fsub_rn(w[j], lo), inv), 12582912.0f);
-            packed[j >> 3] |= (__float_as_uint(q) - 0x4B400000u) << (4 * (j & 7));
-        }
+    for (int j = 0; j < 8; ++j) {
+        const float q0 = __fadd_rn(__fmul_rn(__fsub_rn(w[j], lo), inv), 12582912.0f);
+        const float q1 = __fadd_rn(__fmul_rn(__fsub_rn(w[8 + j], lo), inv), 12582912.0f);
+        p0 += __float_as_uint(q0) << (4 * j);
+        p1 += __float_as_uint(q1) << (4 * j);
     }
-    uint4* op = reinterpret_cast<uint4*>(d.codes_out + ((int64_t)n * d.d_in + k) / 2);
-    op[0] = make_uint4(packed[0], packed[1], packed[2], packed[3]);
-    op[1] = make_uint4(packed[4], packed[5], packed[6], packed[7]);
-    d.alpha_out[blk] = al;
-    d.beta_out[blk] = lo;
+    *reinterpret_cast<uint2*>(d.codes_out + ((int64_t)n * d.d_in + k) / 2) = make_uint2(p0 - kMagicSum, p1 - kMagicSum);
+    if (sub == 0) {
+        d.alpha_out[blk] = al;
+        d.beta_out[blk] = lo;
+    }
 }
 
 // beta'[n,b] = beta[n,b] + delta(n, k = b*64); also emits fp32 alpha when the base scales are grouped.
@@ -168,7 +205,7 @@ int launch_requant_l1(const MergeDesc& d, hipStream_t st) {
             hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)smem) != hipSuccess)
             return QBLORA_ERR_LAUNCH;
-        hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, d);
+        hipLaunchKernelGGL(kern, grid, dim3(kMergeThreads), smem, st, d);
         return launch_status();
     };
     if (d.scale_codes) return d.beta ? launch(k_merge_requant<true, true, L1>) : launch(k_merge_requant<true, false, L1>);
