@@ -10,32 +10,71 @@ namespace qblora {
 namespace {
 
 // out[b][a*e + i] = in[a][b]  for i < e;  in is [na, nb] row-major, out is [nb, na*e] row-major.
-// One call handles the 64 x 64 input tile (ta, tb).
+// One call handles the 64 x 64 input tile (ta, tb).  When rows are whole 16-byte chunks on both sides
+// (nb % 8 == 0 and 16-byte aligned bases) the tile is moved with 16-byte loads and stores.
 __device__ __forceinline__ void transpose_expand_tile(const uint16_t* __restrict__ in, int na, int nb, int e,
                                                       uint16_t* __restrict__ out, int ta, int tb,
                                                       uint16_t (*tile)[66]) {
     const int a0 = ta * 64, b0 = tb * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;   // 64 x 4
-    // all 16 loads of a thread are independent and issued together
-    uint16_t v[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int a = a0 + ty + 4 * i, b = b0 + tx;
-        v[i] = (a < na && b < nb) ? in[(int64_t)a * nb + b] : (uint16_t)0;
-    }
-#pragma unroll
-    for (int i = 0; i < 16; ++i) tile[ty + 4 * i][tx] = v[i];
-    __syncthreads();
     const int64_t ld = (int64_t)na * e;
+    const bool wide = (nb & 7) == 0 && (ld & 7) == 0 && ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
+    if (wide) {
+        // 64 rows x 8 chunks of 8 elements: two chunks per thread
+        uint4 v[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int a = a0 + (threadIdx.x >> 3) + 32 * i, bb = b0 + 8 * (threadIdx.x & 7);
+            v[i] = (a < na && bb < nb) ? *reinterpret_cast<const uint4*>(in + (int64_t)a * nb + bb) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int ar = (threadIdx.x >> 3) + 32 * i, bc = 8 * (threadIdx.x & 7);
+            const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                tile[ar][bc + 2 * q] = (uint16_t)(w[q] & 0xffffu);
+                tile[ar][bc + 2 * q + 1] = (uint16_t)(w[q] >> 16);
+            }
+        }
+        __syncthreads();
+        // output row b0 + r holds 64*e elements of this tile = 8*e chunks; only whole tiles take this
+        // path, the ragged edge falls through to the loop below
+        if (a0 + 64 <= na && b0 + 64 <= nb) {
+            const int chunks = 8 * e;                              // per output row
+            for (int idx = threadIdx.x; idx < 64 * chunks; idx += 256) {
+                const int r = idx / chunks, c = (idx - r * chunks) * 8;
+                uint32_t w[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t lo = tile[(c + 2 * q) / e][r], hi = tile[(c + 2 * q + 1) / e][r];
+                    w[q] = lo | (hi << 16);
+                }
+                *reinterpret_cast<uint4*>(out + (int64_t)(b0 + r) * ld + (int64_t)a0 * e + c) = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+            return;
+        }
+    } else {
+        const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;   // 64 x 4
+        uint16_t v[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int a = a0 + ty + 4 * i, bb = b0 + tx;
+            v[i] = (a < na && bb < nb) ? in[(int64_t)a * nb + bb] : (uint16_t)0;
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) tile[ty + 4 * i][tx] = v[i];
+        __syncthreads();
+    }
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     const int width = 64 * e;                                  // output columns covered by this tile
 #pragma unroll 4
     for (int i = 0; i < 16; ++i) {
         const int r = ty + 4 * i;
-        const int b = b0 + r;
-        if (b >= nb) continue;
+        const int bb = b0 + r;
+        if (bb >= nb) continue;
         for (int c = tx; c < width; c += 64) {
             const int a = a0 + c / e;
-            if (a < na) out[(int64_t)b * ld + (int64_t)a0 * e + c] = tile[c / e][r];
+            if (a < na) out[(int64_t)bb * ld + (int64_t)a0 * e + c] = tile[c / e][r];
         }
     }
 }
@@ -51,7 +90,7 @@ struct PrepDesc {
     // block scales in the order the forward kernel streams them: [row tile of 256][64-block][row in tile]
     const float* scales; const uint8_t* scale_codes; const float* scale_step; const float* scale_mid;
     int scale_group, d_out, bpr;
-    float* scales_tiled; int nS;    // blocks of this job (256 outputs each)
+    float* scales_tiled; int nS;    // blocks of this job (256 rows x 16 blocks each)
 };
 
 // All re-layouts of one call in a single launch: blocks [0,nA) transpose-expand A, the next nB
@@ -70,23 +109,51 @@ __global__ __launch_bounds__(256) void k_adapter_prep(PrepDesc d) {
     }
     b -= d.nB;
     if (b < d.nS) {
-        const int64_t o = (int64_t)b * 256 + threadIdx.x;             // ((tile*bpr + blk)*256 + r)
-        const int r = threadIdx.x;
-        const int64_t tb = b;
-        const int64_t tile = tb / d.bpr, blk = tb - tile * d.bpr;
-        const int64_t n = tile * 256 + r;
-        float v = 0.0f;
-        if (n < d.d_out) {
-            const int64_t i = n * d.bpr + blk;
-            v = d.scale_codes ? grouped_scale(d.scale_codes, d.scale_step, d.scale_mid, i, d.scale_group) : d.scales[i];
+        // 256 rows x 16 blocks per workgroup: rows are read along their (contiguous) blocks, written
+        // per block along the 256 rows of the tile, through LDS
+        __shared__ float st[16][257];
+        const int groups = (d.bpr + 15) / 16;
+        const int rt = b / groups, blk0 = (b - rt * groups) * 16;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int idx = i * 256 + threadIdx.x;
+            const int r = idx >> 4, q = idx & 15;
+            const int64_t n = (int64_t)rt * 256 + r;
+            float v = 0.0f;
+            if (n < d.d_out && blk0 + q < d.bpr) {
+                const int64_t i0 = n * d.bpr + blk0 + q;
+                v = d.scale_codes ? grouped_scale(d.scale_codes, d.scale_step, d.scale_mid, i0, d.scale_group) : d.scales[i0];
+            }
+            st[q][r] = v;
         }
-        d.scales_tiled[o] = v;
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 16; ++q)
+            if (blk0 + q < d.bpr)
+                d.scales_tiled[((int64_t)rt * d.bpr + blk0 + q) * 256 + threadIdx.x] = st[q][threadIdx.x];
         return;
     }
     b -= d.nS;
-    // Bx[j][n] = B[j][n / lam2]
+    // Bx[j][n] = B[j][n / lam2]: 8 consecutive n (16 bytes) per store when rows are whole chunks
     const int64_t ld = (int64_t)d.cols_B * d.lam2;
     const int64_t total = (int64_t)d.R * ld;
+    if ((ld & 7) == 0 && (reinterpret_cast<uintptr_t>(d.Bx) & 15) == 0) {
+        const int64_t base = (int64_t)b * 2048;
+        const int64_t i = base + 8 * (int64_t)threadIdx.x;
+        if (i < total) {
+            const int64_t j = i / ld;
+            const int n = (int)(i - j * ld);
+            const uint16_t* src = d.B + j * d.cols_B;
+            uint32_t w[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t lo = src[(n + 2 * q) / d.lam2], hi = src[(n + 2 * q + 1) / d.lam2];
+                w[q] = lo | (hi << 16);
+            }
+            *reinterpret_cast<uint4*>(d.Bx + i) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+        return;
+    }
     const int64_t base = (int64_t)b * 2048;
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
@@ -107,7 +174,7 @@ int launch_adapter_prep(const qblora_bf16* A, const qblora_bf16* B, int d_in, in
     if (sc && sc->out) {
         d.scales = sc->scales; d.scale_codes = sc->scale_codes; d.scale_step = sc->scale_step; d.scale_mid = sc->scale_mid;
         d.scale_group = sc->scale_group; d.d_out = sc->d_out; d.bpr = sc->d_in / kBlock; d.scales_tiled = sc->out;
-        d.nS = ((sc->d_out + 255) / 256) * d.bpr;
+        d.nS = ((sc->d_out + 255) / 256) * ((d.bpr + 15) / 16);
     }
     if (!A || !B) At_x = Bt = Bx = nullptr;
     d.A = A; d.B = B; d.na_A = d_in / lam1; d.R = R; d.lam1 = lam1; d.cols_B = d_out / lam2; d.lam2 = lam2;
