@@ -201,6 +201,34 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         }
     };
 
+    // Segment-1 activation tiles: per-lane byte offsets relative to the tile's first row are fixed for
+    // the whole kernel, the uniform base walks along k.
+    uint32_t xoff[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        int64_t lrow = wave * 64 + i * 8 + crow;
+        if (m0 + lrow > M - 1) lrow = M - 1 - m0;
+        xoff[i] = (uint32_t)(lrow * ldx1 * 2) + ((((lane & 7) ^ crow ^ i)) << 4);
+    }
+    const qblora_bf16* const x1_tile = X1 + m0 * ldx1;
+    // Copies of a quantized step's token tile in two halves of 4, and all copies of any step.
+    auto issue_x1_half = [&](int step, int buf, int half) __attribute__((always_inline)) {
+        const qblora_bf16* base = x1_tile + step * kBK;
+#pragma unroll
+        for (int i = 4 * half; i < 4 * half + 4; ++i)
+            copy16_to_lds(base, xoff[i], lds0 + buf * kTileBytes + i * 8 * 128);
+    };
+    auto issue_copies = [&](int step, int buf) __attribute__((always_inline)) {
+        if (step < steps1) {
+            issue_x1_half(step, buf, 0);
+            issue_x1_half(step, buf, 1);
+        } else {
+            const int k0 = (step - steps1) * kBK;
+            copy_tile(true, X2, ldx2, m0, M - 1, 1, K2, k0, buf * kTileBytes);
+            copy_tile(true, W2, ldw2, n0, N - 1, div2, K2, k0, (2 + buf) * kTileBytes);
+        }
+    };
+
     // ---- one k-step ----------------------------------------------------------------------------------
     // A wave runs alone on its SIMD, so nothing hides an LDS round trip or a barrier but its own
     // MFMAs.  The 64 MFMAs of a step are cut into 8 slices of 8 (about 256 cycles each) and all other
@@ -290,11 +318,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     //   3: table reads of piece 3, finish piece 1
     //   4: fragments of quarter 3, finish piece 2
     //   5: finish piece 3
-    //   6: wait for the copies, barrier, fragments of quarter 0 of the next step
-    //   7: -
+    //   6: wait for the copies, barrier, fragments of quarter 0 of the next step; with `refill`, first
+    //      half of the token-tile copies of quantized step `step2` (the step after next) into the
+    //      buffer this step has just finished reading
+    //   7: second half of those copies
     auto run_step = [&](const unsigned char* bx, const unsigned char* bw, const unsigned char* bx_next,
-                        unsigned char* bw_next, const bool dq, const Staged<QMODE>& sdq, const bool has_next)
-        __attribute__((always_inline)) {
+                        unsigned char* bw_next, const bool dq, const Staged<QMODE>& sdq, const bool has_next,
+                        const bool refill, const int step2, const int buf2) __attribute__((always_inline)) {
         float2 lv[3][8];
         uint32_t li[2][8];
         if (dq) table_offsets(sdq, 0, li[0]);
@@ -306,8 +336,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
                 __syncthreads();                           // next tiles published; this step's tiles free
                 read_wf(bw_next, 0, wf[0]);
                 read_xf(bx_next, 0, xf[0]);
+                if (refill) issue_x1_half(step2, buf2, 0);  // this step's token buffer is free: refill it
                 __builtin_amdgcn_sched_barrier(0);
             }
+            if (h == 7 && has_next && refill) issue_x1_half(step2, buf2, 1);
             if (dq) {
                 if (h >= 2 && h <= 5) finish_piece(sdq, h - 2, lv[(h - 2) % 3], bw_next);
                 if (h <= 3) table_reads(li[h & 1], lv[h % 3]);
@@ -330,36 +362,14 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         }
     };
 
-    // Segment-1 activation tiles: per-lane byte offsets relative to the tile's first row are fixed for
-    // the whole kernel, the uniform base walks along k.
-    uint32_t xoff[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        int64_t lrow = wave * 64 + i * 8 + crow;
-        if (m0 + lrow > M - 1) lrow = M - 1 - m0;
-        xoff[i] = (uint32_t)(lrow * ldx1 * 2) + ((((lane & 7) ^ crow ^ i)) << 4);
-    }
-    const qblora_bf16* const x1_tile = X1 + m0 * ldx1;
-    auto issue_x1 = [&](int step, int buf) __attribute__((always_inline)) {
-        const qblora_bf16* base = x1_tile + step * kBK;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) copy16_to_lds(base, xoff[i], lds0 + buf * kTileBytes + i * 8 * 128);
-    };
-    auto issue_copies = [&](int step, int buf) __attribute__((always_inline)) {
-        if (step < steps1) {
-            issue_x1(step, buf);
-        } else {
-            const int k0 = (step - steps1) * kBK;
-            copy_tile(true, X2, ldx2, m0, M - 1, 1, K2, k0, buf * kTileBytes);
-            copy_tile(true, W2, ldw2, n0, N - 1, div2, K2, k0, (2 + buf) * kTileBytes);
-        }
-    };
     // ---- main loop ---------------------------------------------------------------------------------
     // Invariant at the top of step s: tile buffers s&1 hold step s and fragment set 0 holds its first
     // quarter; st[(s+1)&1] holds the codes of step s+1 (if that is a quantized step).
     Staged<QMODE> st[2];
     if (nsteps > 0) {
         issue_copies(0, 0);
+        int issued = 0;                                    // copies are in flight or done for steps <= issued
+        if (steps1 > 1) { issue_copies(1, 1); issued = 1; }
         if (steps1 > 0) load_staged(st[0], 0);
         if (steps1 > 1) load_staged(st[1], 1);
         __syncthreads();                                   // pair table visible
@@ -372,28 +382,30 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         // Quantized steps whose successor is quantized too (the successor's tile is dequantized during
         // the step), unrolled by two so that the staging registers and the tile buffers have fixed
         // names.  Codes are fetched two steps ahead; past the end the last quantized step is fetched
-        // again (in bounds, unused) so that the body has no conditions.
+        // again (in bounds, unused) so that the body has no conditions.  A step refills its own token
+        // buffer with the copies of the step after next (when that is a quantized step) behind its
+        // barrier, under its last 16 MFMAs.
         const int last_q = steps1 - 1;
         for (; s + 2 < steps1; s += 2) {
-            issue_x1(s + 1, 1);
             load_staged(st[0], min(s + 2, last_q));
-            run_step(sX, sW, sX + kTileBytes, sW + kTileBytes, true, st[1], true);
-            issue_x1(s + 2, 0);
+            run_step(sX, sW, sX + kTileBytes, sW + kTileBytes, true, st[1], true, true, s + 2, 0);
             load_staged(st[1], min(s + 3, last_q));
-            run_step(sX + kTileBytes, sW + kTileBytes, sX, sW, true, st[0], true);
+            const bool more = s + 3 < steps1;
+            run_step(sX + kTileBytes, sW + kTileBytes, sX, sW, true, st[0], true, more, s + 3, 1);
+            issued = more ? s + 3 : s + 2;
         }
         if (s + 1 < steps1) {
-            issue_x1(s + 1, 1);
-            run_step(sX, sW, sX + kTileBytes, sW + kTileBytes, true, st[1], true);
+            run_step(sX, sW, sX + kTileBytes, sW + kTileBytes, true, st[1], true, false, 0, 0);
             ++s;
         }
-        // the last quantized step and the K-extension steps: nothing to dequantize
+        // the last quantized step and the K-extension steps: nothing to dequantize; copies of the next
+        // step are issued at the top of a step when no earlier step has done it
         for (; s < nsteps; ++s) {
             const int buf = s & 1;
             const bool has_next = s + 1 < nsteps;
-            if (has_next) issue_copies(s + 1, buf ^ 1);
+            if (has_next && issued < s + 1) { issue_copies(s + 1, buf ^ 1); issued = s + 1; }
             run_step(sX + buf * kTileBytes, sW + buf * kTileBytes, sX + (buf ^ 1) * kTileBytes,
-                     sW + (buf ^ 1) * kTileBytes, false, st[0], has_next);
+                     sW + (buf ^ 1) * kTileBytes, false, st[0], has_next, false, 0, 0);
         }
     }
 
