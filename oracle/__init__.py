@@ -167,6 +167,35 @@ def backward(Wt, X, dY, A, B, lam1, lam2, s, compute_dx=True, compute_dab=True, 
     return dX, dA, dB
 
 
+def qa_forward(Wt, X, H, lam1, lam2, s):
+    """Single-matrix adapter (QA-BLoRA): H is bf16 bits [d_in/lam1, d_out/lam2]."""
+    Wt = _c(Wt, np.float64); X = _c(X, np.uint16); H = _c(H, np.uint16)
+    d_out, d_in = Wt.shape
+    T = X.shape[0]
+    assert X.shape == (T, d_in) and H.shape == (d_in // lam1, d_out // lam2)
+    Y = np.zeros((T, d_out), np.float64)
+    lib().oracle_qa_forward(_p(Wt), i64(d_out), i64(d_in), _p(X), i64(T), _p(H), C.c_int(lam1), C.c_int(lam2),
+                            C.c_double(s), _p(Y))
+    return Y
+
+
+def qa_backward(Wt, X, dY, H, lam1, lam2, s, compute_dx=True, compute_dh=True, d_out=None, d_in=None):
+    """Wt may be None (with d_out, d_in given) when compute_dx is False."""
+    X = _c(X, np.uint16); dY = _c(dY, np.uint16); H = _c(H, np.uint16)
+    if Wt is None:
+        assert not compute_dx and d_out is not None and d_in is not None
+    else:
+        Wt = _c(Wt, np.float64)
+        d_out, d_in = Wt.shape
+    T = X.shape[0]
+    assert X.shape == (T, d_in) and dY.shape == (T, d_out) and H.shape == (d_in // lam1, d_out // lam2)
+    dX = np.zeros((T, d_in), np.float64) if compute_dx else None
+    dH = np.zeros(H.shape, np.float64) if compute_dh else None
+    lib().oracle_qa_backward(_p(Wt), i64(d_out), i64(d_in), _p(X), _p(dY), i64(T), _p(H), C.c_int(lam1),
+                             C.c_int(lam2), C.c_double(s), C.c_int(int(compute_dx)), _p(dX), _p(dH))
+    return dX, dH
+
+
 def tile_product(A, B):
     A = _c(A, np.uint16); B = _c(B, np.uint16)
     rows, R = A.shape

@@ -28,7 +28,9 @@
 // forms and error bounds of Eq. 1, dense-matmul equivalence with the full-size
 // delta weight (Sec. 3.2 "Merging Q-BLoRA", Eq. 2), B = 0 and lambda = 1
 // special cases, central finite differences, adjoint identity, merge
-// invariants, E4M3 round trips.  No function here is unpinned.
+// invariants, E4M3 round trips; the single-matrix (QA-BLoRA) layer against the
+// dense delta weight, against the two-matrix layer with A = identity and by
+// finite differences.  No function here is unpinned.
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
@@ -396,6 +398,92 @@ void oracle_backward(const double* Wt, int64_t d_out, int64_t d_in, const uint16
                 }
                 for (int64_t k = 0; k < d_in; ++k) dx[k] += dP[k / lam1] / (double)lam1;
             }
+        }
+    });
+}
+
+// ---------------------------------------------------------------------------
+// QA-BLoRA single-matrix adapter (Sec. 3.3, Alg. 2 qablora_forward, scaling on
+// the adapter term only): the adapter is one matrix H [d_in/lam1, d_out/lam2],
+//   P[t,m] = (1/lam1) sum_{i<lam1} X[t, lam1*m+i]
+//   V = P H
+//   Y[t,n] = sum_k X[t,k] Wt[n,k] + s * V[t, n / lam2]
+// and its backward with respect to X and H (the base weight is frozen):
+//   dV[t,j] = s * sum_{i<lam2} G[t, lam2*j+i],  dH = P^T dV,  dP = dV H^T,
+//   dX[t,k] = sum_n G[t,n] Wt[n,k] + (1/lam1) dP[t, k / lam1].
+// H is bf16 (bit patterns), like the other trainable operands.
+// ---------------------------------------------------------------------------
+void oracle_qa_forward(const double* Wt, int64_t d_out, int64_t d_in, const uint16_t* X, int64_t T,
+                       const uint16_t* H, int lam1, int lam2, double s, double* Y) {
+    int64_t dp = d_in / lam1, dq = d_out / lam2;
+    parallel_rows(T, [&](int64_t t0, int64_t t1) {
+        std::vector<double> x(d_in), P(dp), V(dq);
+        for (int64_t t = t0; t < t1; ++t) {
+            for (int64_t k = 0; k < d_in; ++k) x[k] = bf16_to_f64(X[t * d_in + k]);
+            for (int64_t m = 0; m < dp; ++m) {
+                double acc = 0.0;
+                for (int i = 0; i < lam1; ++i) acc += x[lam1 * m + i];
+                P[m] = acc / (double)lam1;
+            }
+            for (int64_t j = 0; j < dq; ++j) V[j] = 0.0;
+            for (int64_t m = 0; m < dp; ++m)
+                for (int64_t j = 0; j < dq; ++j) V[j] += P[m] * bf16_to_f64(H[m * dq + j]);
+            for (int64_t n = 0; n < d_out; ++n) {
+                const double* w = Wt + n * d_in;
+                double acc = 0.0;
+                for (int64_t k = 0; k < d_in; ++k) acc += x[k] * w[k];
+                Y[t * d_out + n] = acc + s * V[n / lam2];
+            }
+        }
+    });
+}
+
+void oracle_qa_backward(const double* Wt, int64_t d_out, int64_t d_in, const uint16_t* X,
+                        const uint16_t* dY, int64_t T, const uint16_t* H, int lam1, int lam2, double s,
+                        int compute_dx, double* dX, double* dH) {
+    int64_t dp = d_in / lam1, dq = d_out / lam2;
+    std::vector<double> P(T * dp), dV(T * dq);
+    parallel_rows(T, [&](int64_t t0, int64_t t1) {
+        for (int64_t t = t0; t < t1; ++t) {
+            for (int64_t m = 0; m < dp; ++m) {
+                double acc = 0.0;
+                for (int i = 0; i < lam1; ++i) acc += bf16_to_f64(X[t * d_in + lam1 * m + i]);
+                P[t * dp + m] = acc / (double)lam1;
+            }
+            for (int64_t j = 0; j < dq; ++j) {
+                double acc = 0.0;
+                for (int i = 0; i < lam2; ++i) acc += bf16_to_f64(dY[t * d_out + lam2 * j + i]);
+                dV[t * dq + j] = s * acc;
+            }
+        }
+    });
+    if (dH) {
+        parallel_rows(dp, [&](int64_t m0, int64_t m1) {
+            for (int64_t m = m0; m < m1; ++m)
+                for (int64_t j = 0; j < dq; ++j) {
+                    double acc = 0.0;
+                    for (int64_t t = 0; t < T; ++t) acc += P[t * dp + m] * dV[t * dq + j];
+                    dH[m * dq + j] = acc;
+                }
+        });
+    }
+    if (!compute_dx) return;
+    parallel_rows(T, [&](int64_t t0, int64_t t1) {
+        std::vector<double> dP(dp);
+        for (int64_t t = t0; t < t1; ++t) {
+            double* dx = dX + t * d_in;
+            for (int64_t k = 0; k < d_in; ++k) dx[k] = 0.0;
+            for (int64_t n = 0; n < d_out; ++n) {
+                double g = bf16_to_f64(dY[t * d_out + n]);
+                const double* w = Wt + n * d_in;
+                for (int64_t k = 0; k < d_in; ++k) dx[k] += g * w[k];
+            }
+            for (int64_t m = 0; m < dp; ++m) {
+                double acc = 0.0;
+                for (int64_t j = 0; j < dq; ++j) acc += dV[t * dq + j] * bf16_to_f64(H[m * dq + j]);
+                dP[m] = acc;
+            }
+            for (int64_t k = 0; k < d_in; ++k) dx[k] += dP[k / lam1] / (double)lam1;
         }
     });
 }

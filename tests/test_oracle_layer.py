@@ -184,3 +184,84 @@ def test_thread_count_does_not_change_results(oracle):
     b = oracle.forward(Wt, L.X, L.A, L.B, 2, 2, 1.0), oracle.backward(Wt, L.X, L.dY, L.A, L.B, 2, 2, 1.0)
     oracle.set_threads(0)
     assert np.array_equal(a[0], b[0]) and all(np.array_equal(x, y) for x, y in zip(a[1], b[1]))
+
+
+# ---- single-matrix adapter (QA-BLoRA, Sec. 3.3, Alg. 2) ------------------------------------------------
+
+def _qa_case(seed, T, d_out, d_in, lam1, lam2):
+    rng = np.random.default_rng(seed)
+    L = synth.make_layer(seed, T, d_out, d_in, 8, lam1, lam2)
+    Wt = rng.standard_normal((d_out, d_in)) * 0.05
+    H = _bits(rng.standard_normal((d_in // lam1, d_out // lam2)) * 0.1)
+    return L, Wt, H
+
+
+@pytest.mark.parametrize("lam1,lam2", [(2, 2), (4, 8), (8, 8), (1, 1)])
+def test_qa_forward_equals_dense_delta_weight(oracle, lam1, lam2):
+    """The paper's merging argument: the layer equals a dense layer with W~ + s*dW, dW tiled from H."""
+    T, d_out, d_in = 5, 48, 64
+    L, Wt, H = _qa_case(21, T, d_out, d_in, lam1, lam2)
+    s = 0.75
+    Y = oracle.qa_forward(Wt, L.X, H, lam1, lam2, s)
+    X = bf16_exact(L.X); Hf = bf16_exact(H)
+    dW = np.repeat(np.repeat(Hf, lam1, axis=0), lam2, axis=1) / lam1        # [d_in, d_out], numpy only
+    dense = X @ (Wt + s * dW.T).T
+    assert np.allclose(Y, dense, rtol=0, atol=1e-12 * np.abs(dense).max())
+    assert np.array_equal(oracle.delta_weight(Hf, lam1, lam2), dW)
+    # pool -> H -> repeat written out with numpy
+    P = X.reshape(T, d_in // lam1, lam1).mean(-1)
+    assert np.allclose(Y, X @ Wt.T + s * np.repeat(P @ Hf, lam2, axis=1), atol=1e-12)
+
+
+def test_qa_layer_is_the_two_matrix_layer_with_identity_a(oracle):
+    """A = I (inner rank d_in/lam1), B = H turns the two-matrix adapter into the single-matrix one."""
+    T, d_out, d_in, lam1, lam2 = 4, 32, 64, 4, 2
+    L, Wt, H = _qa_case(22, T, d_out, d_in, lam1, lam2)
+    eye = _bits(np.eye(d_in // lam1))
+    s = 1.5
+    assert np.allclose(oracle.qa_forward(Wt, L.X, H, lam1, lam2, s),
+                       oracle.forward(Wt, L.X, eye, H, lam1, lam2, s), atol=1e-13)
+    dX, dH = oracle.qa_backward(Wt, L.X, L.dY, H, lam1, lam2, s)
+    rX, _, rB = oracle.backward(Wt, L.X, L.dY, eye, H, lam1, lam2, s)
+    assert np.allclose(dX, rX, atol=1e-12) and np.allclose(dH, rB, atol=1e-12)
+
+
+def test_qa_h_zero_is_base_layer(oracle):
+    L, Wt, H = _qa_case(23, 3, 32, 64, 2, 2)
+    Y = oracle.qa_forward(Wt, L.X, np.zeros_like(H), 2, 2, 3.0)
+    assert np.allclose(Y, bf16_exact(L.X) @ Wt.T, atol=1e-13)
+
+
+@pytest.mark.parametrize("lam1,lam2", [(2, 2), (4, 8)])
+def test_qa_backward_adjoint_and_finite_differences(oracle, lam1, lam2):
+    T, d_out, d_in = 6, 48, 64
+    L, Wt, H = _qa_case(24, T, d_out, d_in, lam1, lam2)
+    s = 0.5
+    dX, dH = oracle.qa_backward(Wt, L.X, L.dY, H, lam1, lam2, s)
+    G = bf16_exact(L.dY); X = bf16_exact(L.X); Hf = bf16_exact(H)
+
+    def fwd(Wm, Xm, Hm):                                                    # numpy only
+        P = Xm.reshape(T, d_in // lam1, lam1).mean(-1)
+        return Xm @ Wm.T + s * np.repeat(P @ Hm, lam2, axis=1)
+
+    rng = np.random.default_rng(1)
+    vX = rng.standard_normal(X.shape); vH = rng.standard_normal(Hf.shape)
+    zero = np.zeros_like(Wt)
+    assert np.isclose((G * fwd(Wt, vX, Hf)).sum(), (dX * vX).sum(), rtol=1e-11)      # linear in X
+    assert np.isclose((G * fwd(zero, X, vH)).sum(), (dH * vH).sum(), rtol=1e-11)     # linear in H
+    # central differences of the scalar <dY, Y> on single entries
+    eps = 1e-3
+    for (m, j) in [(0, 0), (3, 5), (d_in // lam1 - 1, d_out // lam2 - 1)]:
+        Hp = Hf.copy(); Hp[m, j] += eps
+        Hm = Hf.copy(); Hm[m, j] -= eps
+        fd = ((G * fwd(Wt, X, Hp)).sum() - (G * fwd(Wt, X, Hm)).sum()) / (2 * eps)
+        assert np.isclose(fd, dH[m, j], rtol=1e-8, atol=1e-10)
+    # dH straight from its definition, dX from the dense equivalent weight
+    P = X.reshape(T, d_in // lam1, lam1).mean(-1)
+    dV = s * G.reshape(T, d_out // lam2, lam2).sum(-1)
+    assert np.allclose(dH, P.T @ dV, atol=1e-12)
+    dW = np.repeat(np.repeat(Hf, lam1, axis=0), lam2, axis=1) / lam1
+    assert np.allclose(dX, G @ (Wt + s * dW.T), atol=1e-12 * np.abs(dX).max())
+    # dH only, without the base weight
+    _, dH2 = oracle.qa_backward(None, L.X, L.dY, H, lam1, lam2, s, compute_dx=False, d_out=d_out, d_in=d_in)
+    assert np.array_equal(dH, dH2)

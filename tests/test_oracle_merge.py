@@ -61,6 +61,23 @@ def test_beta_shift_merged_layer_equals_adapted_layer(oracle):
     assert np.allclose(Y_merged, Y_adapted, rtol=0, atol=1e-5 * np.abs(Y_adapted).max())
 
 
+def test_beta_shift_merged_layer_equals_single_matrix_adapted_layer(oracle):
+    """Quantization-aware training form (Sec. 3.3): a layer trained with the single-matrix adapter H and
+    aligned tiles is reproduced by the INT4 layer whose beta absorbed H."""
+    d_out, d_in, lam1, lam2, s = 16, 256, 64, 8, 0.75
+    L = synth.make_layer(54, 6, d_out, d_in, 8, lam1, lam2)
+    codes, alpha, beta = oracle.quantize_minmax(L.W, 64)
+    cb = synth.codebook_int4()
+    Hb = synth.f32_to_bf16_bits((np.random.default_rng(54).standard_normal((d_in // lam1, d_out // lam2)) * 0.05)
+                                .astype(np.float32))
+    beta2 = oracle.merge_beta_shift(beta, bf16_exact(Hb).astype(np.float32), d_out, d_in, 64, lam1, lam2, s)
+    Wt = oracle.dequantize(codes, alpha, beta, cb, 64, 0)
+    Wm = oracle.dequantize(codes, alpha, beta2, cb, 64, 0)
+    Y_adapted = oracle.qa_forward(Wt, L.X, Hb, lam1, lam2, s)
+    Y_merged = oracle.forward(Wm, L.X, None, None, 1, 1, 0.0)
+    assert np.allclose(Y_merged, Y_adapted, rtol=0, atol=1e-5 * np.abs(Y_adapted).max())
+
+
 @pytest.mark.parametrize("lam1,lam2", [(2, 2), (4, 8), (8, 8)])
 def test_requant_error_bound(oracle, codebook, lam1, lam2):
     d_out, d_in, s = 16, 256, 1.0
