@@ -195,6 +195,30 @@ int qblora_linear_bwd_saved(const qblora_qweight* qw, const qblora_adapter* ad, 
                             float* dA, float* dB, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Single-matrix adapter (QA-BLoRA, Sec. 3.3, Alg. 2 qablora_forward with the scaling on the adapter
+ * term only): the trainable adapter is one matrix H, bf16 [d_in/lambda1, d_out/lambda2] row-major,
+ * device memory, whose tiles can later be folded into the block offsets (qablora_merge_quantize).
+ *   forward   Y[t,n] = sum_k X[t,k] * w~[n,k] + s * (AvgPool_lambda1(X) H)[t, n / lambda2]
+ *   backward  dV[t,j] = s * sum_{i<lambda2} dY[t, lambda2*j+i];  dH = AvgPool_lambda1(X)^T dV;
+ *             dX[t,k] = sum_n dY[t,n] * w~[n,k] + (1/lambda1) * (dV H^T)[t, k / lambda1]
+ *   X bf16 [T, d_in]; Y, dY bf16 [T, d_out]; dX bf16 [T, d_in]; dH fp32 [d_in/lambda1, d_out/lambda2];
+ *   outputs fully overwritten.  dX or dH may be NULL (not both); X may be NULL when dH is.
+ *   The pooled input and the pooled output gradient are rounded to bf16 where they feed the MFMA
+ *   kernels; accumulation is fp32.
+ * Requires d_in % 64 == 0, d_out % 64 == 0, d_in % lambda1 == 0, d_out % lambda2 == 0 and
+ * (d_in/lambda1) % 8 == 0, (d_out/lambda2) % 8 == 0.  workspace: device scratch of at least
+ * qablora_linear_*_workspace_bytes(), 256-byte aligned.  T = 0: no-op (dH zeroed).
+ */
+size_t qablora_linear_fwd_workspace_bytes(const qblora_qweight* qw, int32_t lambda1, int32_t lambda2, int64_t T);
+size_t qablora_linear_bwd_workspace_bytes(const qblora_qweight* qw, int32_t lambda1, int32_t lambda2, int64_t T);
+int qablora_linear_fwd(const qblora_qweight* qw, const qblora_bf16* H, int32_t lambda1, int32_t lambda2, float s,
+                       const qblora_bf16* X, int64_t T, qblora_bf16* Y, void* workspace, size_t workspace_bytes,
+                       void* stream);
+int qablora_linear_bwd(const qblora_qweight* qw, const qblora_bf16* H, int32_t lambda1, int32_t lambda2, float s,
+                       const qblora_bf16* X, const qblora_bf16* dY, int64_t T, qblora_bf16* dX, float* dH,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Tile matrix of a two-matrix adapter, H = A B, fp32 [d_in/lambda1, d_out/lambda2] (Alg. 1
  * get_delta_weight before the expansion; the equivalent full-size delta weight is
  * dW[k,n] = H[k/lambda1, n/lambda2]/lambda1, Sec. 3.2 "Merging Q-BLoRA").

@@ -25,7 +25,9 @@ EXPORTS = ["qblora_quantize_blockwise", "qblora_dequantize_bf16", "qblora_linear
            "qblora_linear_bwd_workspace_bytes", "qblora_linear_fwd", "qblora_linear_bwd",
            "qblora_tile_product_workspace_bytes", "qblora_tile_product", "qablora_merge_quantize",
            "qblora_strerror", "qblora_profile_events", "qblora_codes_tiled_bytes", "qblora_prepack_codes",
-           "qblora_saved_bytes", "qblora_linear_fwd_save", "qblora_linear_bwd_saved"]
+           "qblora_saved_bytes", "qblora_linear_fwd_save", "qblora_linear_bwd_saved",
+           "qablora_linear_fwd_workspace_bytes", "qablora_linear_bwd_workspace_bytes", "qablora_linear_fwd",
+           "qablora_linear_bwd"]
 
 PROFILE_FWD_GEMM, PROFILE_BWD_GEMM, PROFILE_MERGE, PROFILE_QUANTIZE = 0, 1, 2, 3
 
@@ -81,6 +83,13 @@ def lib():
         L.qblora_codes_tiled_bytes.restype = C.c_size_t
         L.qblora_codes_tiled_bytes.argtypes = [C.c_int32, C.c_int32]
         L.qblora_prepack_codes.argtypes = [C.c_void_p, C.c_void_p]
+        for name in ("qablora_linear_fwd_workspace_bytes", "qablora_linear_bwd_workspace_bytes"):
+            getattr(L, name).restype = C.c_size_t
+            getattr(L, name).argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64]
+        L.qablora_linear_fwd.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_int64,
+                                         C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.qablora_linear_bwd.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p,
+                                         C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.qblora_saved_bytes.restype = C.c_size_t
         L.qblora_saved_bytes.argtypes = [C.c_void_p, C.c_int64]
         L.qblora_linear_fwd_save.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
@@ -303,6 +312,43 @@ def qblora_linear_bwd(qw: QWeight, ad, X: torch.Tensor, dY: torch.Tensor, need_d
                                            _ptr(dB), _ptr(ws), ws.numel(), _stream())
         _check(rc, "qblora_linear_bwd_saved")
     return dX, dA, dB
+
+
+def qablora_linear_fwd(qw: QWeight, H: torch.Tensor, lambda1: int, lambda2: int, s: float, X: torch.Tensor,
+                       Y: torch.Tensor = None, workspace: torch.Tensor = None):
+    """Single-matrix adapter forward; H is bf16 [d_in/lambda1, d_out/lambda2]."""
+    assert X.is_cuda and X.dtype == torch.bfloat16 and X.is_contiguous() and X.shape[1] == qw.d_in
+    assert H.is_cuda and H.dtype == torch.bfloat16 and H.is_contiguous()
+    assert tuple(H.shape) == (qw.d_in // lambda1, qw.d_out // lambda2)
+    T = X.shape[0]
+    if Y is None:
+        Y = torch.empty((T, qw.d_out), dtype=torch.bfloat16, device=X.device)
+    q = qw.c_struct()
+    ws = _workspace(int(lib().qablora_linear_fwd_workspace_bytes(C.byref(q), lambda1, lambda2, T)), X.device, workspace)
+    rc = lib().qablora_linear_fwd(C.byref(q), _ptr(H), lambda1, lambda2, s, _ptr(X), T, _ptr(Y), _ptr(ws), ws.numel(),
+                                  _stream())
+    _check(rc, "qablora_linear_fwd")
+    return Y
+
+
+def qablora_linear_bwd(qw: QWeight, H: torch.Tensor, lambda1: int, lambda2: int, s: float, X: torch.Tensor,
+                       dY: torch.Tensor, need_dx: bool = True, need_dh: bool = True, dX=None, dH=None,
+                       workspace: torch.Tensor = None):
+    assert dY.is_cuda and dY.dtype == torch.bfloat16 and dY.is_contiguous() and dY.shape[1] == qw.d_out
+    assert H.is_cuda and H.dtype == torch.bfloat16 and H.is_contiguous()
+    T = dY.shape[0]
+    dev = dY.device
+    if need_dx and dX is None:
+        dX = torch.empty((T, qw.d_in), dtype=torch.bfloat16, device=dev)
+    if need_dh and dH is None:
+        dH = torch.empty((qw.d_in // lambda1, qw.d_out // lambda2), dtype=torch.float32, device=dev)
+    q = qw.c_struct()
+    ws = _workspace(int(lib().qablora_linear_bwd_workspace_bytes(C.byref(q), lambda1, lambda2, T)), dev, workspace)
+    rc = lib().qablora_linear_bwd(C.byref(q), _ptr(H), lambda1, lambda2, s, _ptr(X), _ptr(dY), T,
+                                  _ptr(dX if need_dx else None), _ptr(dH if need_dh else None), _ptr(ws), ws.numel(),
+                                  _stream())
+    _check(rc, "qablora_linear_bwd")
+    return (dX if need_dx else None), (dH if need_dh else None)
 
 
 def qblora_tile_product(ad: Adapter, d_in: int, d_out: int, H: torch.Tensor = None, workspace=None):

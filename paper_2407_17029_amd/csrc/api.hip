@@ -391,6 +391,137 @@ int qblora_linear_bwd_saved(const qblora_qweight* qw, const qblora_adapter* ad, 
                            workspace_bytes, stream);
 }
 
+// ---- single-matrix adapter (QA-BLoRA) ------------------------------------------------------------
+
+namespace {
+
+int check_qa(const qblora_qweight* qw, const qblora_bf16* H, int32_t lam1, int32_t lam2) {
+    int rc = check_qweight(qw, true);
+    if (rc) return rc;
+    if (qw->d_out % 64 != 0) return QBLORA_ERR_SHAPE;
+    if (!H) return QBLORA_ERR_NULL;
+    if (lam1 <= 0 || lam2 <= 0 || qw->d_in % lam1 != 0 || qw->d_out % lam2 != 0) return QBLORA_ERR_SHAPE;
+    // the pooled widths are contraction lengths of 16-byte chunk copies
+    if ((qw->d_in / lam1) % 8 != 0 || (qw->d_out / lam2) % 8 != 0) return QBLORA_ERR_SHAPE;
+    return QBLORA_OK;
+}
+
+struct QaFwdSpace { float* scales; qblora_bf16 *Ht, *P; size_t bytes; };
+QaFwdSpace carve_qa_fwd(const qblora_qweight* qw, int lam1, int lam2, int64_t T, void* ws) {
+    Carver c(ws);
+    QaFwdSpace s{};
+    s.scales = c.take<float>((size_t)((qw->d_out + 255) / 256) * 256 * (qw->d_in / qw->block));
+    s.Ht = c.take<qblora_bf16>((size_t)(qw->d_out / lam2) * (qw->d_in / lam1));
+    s.P = c.take<qblora_bf16>((size_t)T * (qw->d_in / lam1));
+    s.bytes = c.off;
+    return s;
+}
+
+struct QaBwdSpace { float* scales; qblora_bf16 *P, *dVs, *dVs_lo; float* part; int splits; size_t bytes; };
+QaBwdSpace carve_qa_bwd(const qblora_qweight* qw, int lam1, int lam2, int64_t T, void* ws) {
+    Carver c(ws);
+    QaBwdSpace s{};
+    const int I = qw->d_in / lam1, J = qw->d_out / lam2;
+    if (qw->scale_mode == QBLORA_SCALES_E4M3_GROUPED) s.scales = c.take<float>(n_blocks(qw));
+    s.P = c.take<qblora_bf16>((size_t)T * I);
+    s.dVs = c.take<qblora_bf16>((size_t)T * J);
+    s.dVs_lo = c.take<qblora_bf16>((size_t)T * J);
+    s.splits = grad_splits(T, I, J);
+    s.part = c.take<float>((size_t)s.splits * I * J);
+    s.bytes = c.off;
+    return s;
+}
+
+}  // namespace
+
+size_t qablora_linear_fwd_workspace_bytes(const qblora_qweight* qw, int32_t lambda1, int32_t lambda2, int64_t T) {
+    if (check_qweight(qw, false) || lambda1 <= 0 || lambda2 <= 0 || T < 0) return 0;
+    return carve_qa_fwd(qw, lambda1, lambda2, T, nullptr).bytes;
+}
+
+size_t qablora_linear_bwd_workspace_bytes(const qblora_qweight* qw, int32_t lambda1, int32_t lambda2, int64_t T) {
+    if (check_qweight(qw, false) || lambda1 <= 0 || lambda2 <= 0 || T < 0) return 0;
+    return carve_qa_bwd(qw, lambda1, lambda2, T, nullptr).bytes;
+}
+
+int qablora_linear_fwd(const qblora_qweight* qw, const qblora_bf16* H, int32_t lambda1, int32_t lambda2, float s,
+                       const qblora_bf16* X, int64_t T, qblora_bf16* Y, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+    int rc = check_qa(qw, H, lambda1, lambda2);
+    if (rc) return rc;
+    if (T < 0) return QBLORA_ERR_SHAPE;
+    if (T == 0) return QBLORA_OK;
+    if (!X || !Y) return QBLORA_ERR_NULL;
+    QaFwdSpace ws = carve_qa_fwd(qw, lambda1, lambda2, T, workspace);
+    if (!workspace || workspace_bytes < ws.bytes) return QBLORA_ERR_WORKSPACE;
+    hipStream_t st = as_stream(stream);
+    const int I = qw->d_in / lambda1, J = qw->d_out / lambda2;
+
+    // block scales in tile order and H^T (the K-contiguous weight operand of the K-extension), one launch
+    ScaleTiling sct{};
+    const bool grouped = qw->scale_mode == QBLORA_SCALES_E4M3_GROUPED;
+    sct.scales = grouped ? nullptr : qw->scales;
+    if (grouped) { sct.scale_codes = qw->scale_codes; sct.scale_step = qw->scale_step; sct.scale_mid = qw->scale_mid; }
+    sct.scale_group = qw->scale_group; sct.d_out = qw->d_out; sct.d_in = qw->d_in; sct.out = ws.scales;
+    if ((rc = launch_adapter_prep(H, H, I, J, J, 1, 1, ws.Ht, nullptr, nullptr, st, &sct))) return rc;
+    // s * AvgPool_lambda1(X)
+    if ((rc = launch_pool_rows(X, T, qw->d_in, lambda1, s / (float)lambda1, ws.P, nullptr, st))) return rc;
+
+    GemmDesc g{};
+    g.qmode = 1;
+    g.scales = nullptr; g.scales_tiled = ws.scales;
+    g.X2 = ws.P; g.ldx2 = I; g.W2 = ws.Ht; g.ldw2 = I; g.K2 = I; g.div2 = lambda2;
+    g.X1 = X; g.ldx1 = qw->d_in;
+    g.codes = qw->codes; g.beta = qw->beta; g.d_out = qw->d_out; g.d_in = qw->d_in; g.cb = codebook_of(qw);
+    g.codes_tiled = qw->codes_tiled;
+    g.C = Y; g.ldc = qw->d_out; g.out_scale = 1.0f; g.M = T; g.N = qw->d_out;
+    return launch_gemm(g, st);
+}
+
+int qablora_linear_bwd(const qblora_qweight* qw, const qblora_bf16* H, int32_t lambda1, int32_t lambda2, float s,
+                       const qblora_bf16* X, const qblora_bf16* dY, int64_t T, qblora_bf16* dX, float* dH,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_qa(qw, H, lambda1, lambda2);
+    if (rc) return rc;
+    if (T < 0) return QBLORA_ERR_SHAPE;
+    if (!dX && !dH) return QBLORA_ERR_NULL;
+    hipStream_t st = as_stream(stream);
+    const int I = qw->d_in / lambda1, J = qw->d_out / lambda2;
+    if (T == 0) {
+        if (dH) {
+            const int64_t nh = (int64_t)I * J;
+            hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((nh + 255) / 256)), dim3(256), 0, st, dH, nh);
+            return launch_status();
+        }
+        return QBLORA_OK;
+    }
+    if (!dY || (dH && !X)) return QBLORA_ERR_NULL;
+    QaBwdSpace ws = carve_qa_bwd(qw, lambda1, lambda2, T, workspace);
+    if (!workspace || workspace_bytes < ws.bytes) return QBLORA_ERR_WORKSPACE;
+
+    // (s/lambda1) * sum_lambda2(dY): operand of the dX K-extension and, rescaled by lambda1 at the end, of dH
+    // (there with its bf16 residual, so that only the pooled input carries a bf16 rounding)
+    if ((rc = launch_pool_rows(dY, T, qw->d_out, lambda2, s / (float)lambda1, ws.dVs, dH ? ws.dVs_lo : nullptr, st)))
+        return rc;
+    if (dH) {
+        if ((rc = launch_pool_rows(X, T, qw->d_in, lambda1, 1.0f / (float)lambda1, ws.P, nullptr, st))) return rc;
+        GradDesc gh{};
+        gh.L = ws.P; gh.ldl = I; gh.I = I; gh.S = ws.dVs; gh.S_lo = ws.dVs_lo; gh.lds = J; gh.J = J; gh.T = T;
+        gh.part = ws.part; gh.splits = ws.splits; gh.out = dH; gh.pool = 1;
+        gh.out_scale = (float)lambda1; gh.transpose_out = 0;
+        if ((rc = launch_grad(gh, st))) return rc;
+    }
+    if (!dX) return QBLORA_OK;
+    GemmDesc g{};
+    g.qmode = 2;
+    if ((rc = resolve_scales(qw, ws.scales, st, &g.scales))) return rc;
+    g.X2 = ws.dVs; g.ldx2 = J; g.W2 = H; g.ldw2 = J; g.K2 = J; g.div2 = lambda1;
+    g.X1 = dY; g.ldx1 = qw->d_out;
+    g.codes = qw->codes; g.beta = qw->beta; g.d_out = qw->d_out; g.d_in = qw->d_in; g.cb = codebook_of(qw);
+    g.C = dX; g.ldc = qw->d_in; g.out_scale = 1.0f; g.M = T; g.N = qw->d_in;
+    return launch_gemm(g, st);
+}
+
 size_t qblora_tile_product_workspace_bytes(const qblora_adapter* ad, int32_t d_in, int32_t d_out) {
     if (!has_adapter(ad) || d_out <= 0 || ad->lambda2 <= 0 || d_out % ad->lambda2) return 0;
     (void)d_in;

@@ -118,7 +118,9 @@ struct GradDesc {
     float* part; int splits;
     float* out; int pool; float out_scale; int transpose_out;
 };
-int grad_splits(int64_t T, int I);
+int grad_splits(int64_t T, int I, int J = 1);    // slices of the token range for an [I, J] gradient
+int launch_pool_rows(const qblora_bf16* in, int64_t T, int d, int lam, float scale, qblora_bf16* out,
+                     qblora_bf16* out_lo, hipStream_t st);
 int launch_grad(const GradDesc& d, hipStream_t st);
 
 struct MergeDesc {

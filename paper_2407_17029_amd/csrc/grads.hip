@@ -371,9 +371,9 @@ __global__ __launch_bounds__(256) void k_grad_reduce(GradDesc d) {
 
 }  // namespace
 
-int grad_splits(int64_t T, int I) {
-    int tiles_i = (I + BI - 1) / BI;
-    int want = (256 + tiles_i - 1) / tiles_i;          // one workgroup per CU
+int grad_splits(int64_t T, int I, int J) {
+    int tiles = ((I + BI - 1) / BI) * ((J + BJ - 1) / BJ);
+    int want = (256 + tiles - 1) / tiles;              // one workgroup per CU
     int64_t max_splits = (T + BT - 1) / BT;
     if (want > max_splits) want = (int)max_splits;
     if (want > 32) want = 32;

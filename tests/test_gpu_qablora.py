@@ -1,0 +1,124 @@
+"""GPU parity: single-matrix (QA-BLoRA) adapted forward / backward against the fp64 oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2407_17029_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def qb():
+    from paper_2407_17029_amd import binding
+    binding.lib()
+    return binding
+
+
+def _h_bits(seed, rows, cols, std=0.02):
+    rng = np.random.default_rng(seed)
+    return synth.f32_to_bf16_bits((rng.standard_normal((rows, cols)) * std).astype(np.float32))
+
+
+def _setup(qb, oracle, codebook, seed, T, d_out, d_in, lam1, lam2, minmax=False, grouped=False):
+    from gpu_util import f32_to_dev, to_np, bf16_to_dev
+    L = synth.make_layer(seed, T, d_out, d_in, 8, lam1, lam2)
+    if minmax:
+        qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 64, qb.QUANT_MINMAX_INT4)
+        cb = synth.codebook_int4()
+    else:
+        qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 64, qb.QUANT_ABSMAX_CODEBOOK, codebook,
+                                          qb.SCALES_E4M3_GROUPED if grouped else qb.SCALES_FP32)
+        cb = codebook
+    torch.cuda.synchronize()
+    if grouped:
+        scales = oracle.scales_double_dequantize(to_np(qw.scale_codes), to_np(qw.scale_step), to_np(qw.scale_mid),
+                                                 256).reshape(d_out, d_in // 64)
+    else:
+        scales = to_np(qw.scales)
+    beta = None if qw.beta is None else to_np(qw.beta)
+    Wt = oracle.dequantize(to_np(qw.codes), scales, beta, cb, 64, 2)      # the bf16 compute weight
+    Hb = _h_bits(seed + 1, d_in // lam1, d_out // lam2)
+    return L, qw, Wt, Hb, bf16_to_dev(Hb), bf16_to_dev(L.X), bf16_to_dev(L.dY)
+
+
+CASES = [
+    # T, d_out, d_in, lam1, lam2, s
+    (256, 512, 512, 2, 2, 1.0),              # the recommended lambda of the two-matrix form
+    (300, 320, 192, 4, 8, 0.25),             # the block-32 recommendation (4, 8); ragged tokens, partial tiles
+    (77, 576, 832, 8, 8, 2.0),               # the block-64 recommendation (8, 8)
+    (130, 256, 512, 64, 8, 1.0),             # tiles that cover whole quantization blocks (beta-shift mergeable)
+    (513, 512, 1024, 1, 1, 1.0),             # lambda 1: a full-size dense adapter
+]
+
+
+@pytest.mark.parametrize("T,d_out,d_in,lam1,lam2,s", CASES)
+def test_forward_parity(qb, oracle, codebook, T, d_out, d_in, lam1, lam2, s):
+    from gpu_util import assert_close_bf16
+    print(f"case qa fwd T={T} {d_out}x{d_in} lam=({lam1},{lam2})", flush=True)
+    L, qw, Wt, Hb, H, X, dY = _setup(qb, oracle, codebook, 1500 + T, T, d_out, d_in, lam1, lam2)
+    Y = qb.qablora_linear_fwd(qw, H, lam1, lam2, s, X)
+    torch.cuda.synchronize()
+    assert_close_bf16(Y, oracle.qa_forward(Wt, L.X, Hb, lam1, lam2, s), "Y")
+
+
+@pytest.mark.parametrize("T,d_out,d_in,lam1,lam2,s", CASES)
+def test_backward_parity(qb, oracle, codebook, T, d_out, d_in, lam1, lam2, s):
+    from gpu_util import assert_close_bf16, assert_close_f32
+    print(f"case qa bwd T={T} {d_out}x{d_in} lam=({lam1},{lam2})", flush=True)
+    L, qw, Wt, Hb, H, X, dY = _setup(qb, oracle, codebook, 1600 + T, T, d_out, d_in, lam1, lam2)
+    dX, dH = qb.qablora_linear_bwd(qw, H, lam1, lam2, s, X, dY)
+    torch.cuda.synchronize()
+    rX, rH = oracle.qa_backward(Wt, L.X, L.dY, Hb, lam1, lam2, s)
+    assert_close_bf16(dX, rX, "dX")
+    assert_close_f32(dH, rH, "dH")                    # operands of the dH contraction are bf16-rounded pools
+    # each output alone
+    dX2, none = qb.qablora_linear_bwd(qw, H, lam1, lam2, s, X, dY, need_dh=False)
+    none2, dH2 = qb.qablora_linear_bwd(qw, H, lam1, lam2, s, X, dY, need_dx=False)
+    torch.cuda.synchronize()
+    assert none is None and none2 is None
+    assert torch.equal(dX2.view(torch.int16), dX.view(torch.int16)) and torch.equal(dH2, dH)
+
+
+def test_minmax_base_grouped_scales_and_zero_adapter(qb, oracle, codebook):
+    from gpu_util import assert_close_bf16
+    T, d_out, d_in, lam1, lam2 = 200, 384, 512, 4, 8
+    for kw in (dict(minmax=True), dict(grouped=True)):
+        L, qw, Wt, Hb, H, X, dY = _setup(qb, oracle, codebook, 1700, T, d_out, d_in, lam1, lam2, **kw)
+        Y = qb.qablora_linear_fwd(qw, H, lam1, lam2, 0.5, X)
+        dX, dH = qb.qablora_linear_bwd(qw, H, lam1, lam2, 0.5, X, dY)
+        torch.cuda.synchronize()
+        assert_close_bf16(Y, oracle.qa_forward(Wt, L.X, Hb, lam1, lam2, 0.5), "Y")
+        assert_close_bf16(dX, oracle.qa_backward(Wt, L.X, L.dY, Hb, lam1, lam2, 0.5, compute_dh=False)[0], "dX")
+    # H = 0: exactly the base layer
+    H0 = torch.zeros_like(H)
+    Y0 = qb.qablora_linear_fwd(qw, H0, lam1, lam2, 3.0, X)
+    Yb = qb.qblora_linear_fwd(qw, None, X)
+    torch.cuda.synchronize()
+    assert torch.equal(Y0.view(torch.int16), Yb.view(torch.int16))
+
+
+def test_empty_batch_and_errors(qb, oracle, codebook):
+    L, qw, Wt, Hb, H, X, dY = _setup(qb, oracle, codebook, 1800, 64, 256, 256, 2, 2)
+    E = torch.empty((0, 256), dtype=torch.bfloat16, device=X.device)
+    assert qb.qablora_linear_fwd(qw, H, 2, 2, 1.0, E).shape == (0, 256)
+    dX, dH = qb.qablora_linear_bwd(qw, H, 2, 2, 1.0, E, E)
+    torch.cuda.synchronize()
+    assert dX.shape == (0, 256) and torch.count_nonzero(dH).item() == 0
+    H4 = torch.zeros((4, 128), dtype=torch.bfloat16, device=X.device)
+    with pytest.raises(RuntimeError):
+        qb.qablora_linear_fwd(qw, H4, 64, 2, 1.0, X)                     # pooled width 4 is not a multiple of 8
+
+
+def test_merged_int4_layer_reproduces_the_trained_layer(qb, oracle, codebook):
+    """Sec. 3.3 end to end on the GPU: train-time layer with aligned tiles == INT4 layer after the beta-shift."""
+    from gpu_util import assert_close_bf16, to_np
+    T, d_out, d_in, lam1, lam2, s = 192, 256, 512, 64, 8, 0.75
+    L, qw, Wt, Hb, H, X, dY = _setup(qb, oracle, codebook, 1900, T, d_out, d_in, lam1, lam2, minmax=True)
+    Y = qb.qablora_linear_fwd(qw, H, lam1, lam2, s, X)
+    merged = qb.qablora_merge_quantize(qw, H.float(), lam1, lam2, s, qb.MERGE_BETA_SHIFT)
+    Ym = qb.qblora_linear_fwd(merged, None, X)
+    torch.cuda.synchronize()
+    ref = oracle.qa_forward(Wt, L.X, Hb, lam1, lam2, s)
+    assert_close_bf16(Y, ref, "Y (adapter)")
+    assert_close_bf16(Ym, ref, "Y (merged INT4)")
