@@ -93,3 +93,30 @@ def test_llama65b_down_proj_grouped_scales_reduced_tokens(qb, oracle, codebook):
     wl = synth.WORKLOADS["llama65b_layer"]
     p = wl.projections[6]                                                # down_proj [8192 x 22016]
     _run_layer(qb, oracle, codebook, wl.seed + 7, 320, p.d_out, p.d_in, wl.rank, wl.lam, wl.s, True, 64, True)
+
+
+def test_single_matrix_adapter_benchmark_shape(qb, oracle, codebook):
+    """QA-BLoRA at the benchmark layer shape with the block-64 recommendation lambda = (8, 8)."""
+    from gpu_util import f32_to_dev, to_np, bf16_to_dev, assert_close_bf16, assert_close_f32
+    wl = synth.WORKLOADS["llama7b_attn"]
+    p = wl.projections[0]
+    T, d_out, d_in, lam1, lam2, s = wl.tokens, p.d_out, p.d_in, 8, 8, 1.0
+    print(f"full-size single-matrix case T={T} {d_out}x{d_in} lam=({lam1},{lam2})", flush=True)
+    L = synth.make_layer(wl.seed + 20, T, d_out, d_in, 8, lam1, lam2)
+    Hb = synth.f32_to_bf16_bits((np.random.default_rng(wl.seed + 21).standard_normal((d_in // lam1, d_out // lam2)) * 0.02)
+                                .astype(np.float32))
+    qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 64, qb.QUANT_ABSMAX_CODEBOOK, codebook)
+    H, X, dY = bf16_to_dev(Hb), bf16_to_dev(L.X), bf16_to_dev(L.dY)
+    Y = qb.qablora_linear_fwd(qw, H, lam1, lam2, s, X)
+    dX, dH = qb.qablora_linear_bwd(qw, H, lam1, lam2, s, X, dY)
+    torch.cuda.synchronize()
+    Wt = oracle.dequantize(to_np(qw.codes), to_np(qw.scales), None, codebook, 64, 2)
+    rows = synth.sample_rows(T, 128, wl.seed + 22)
+    Xs, dYs = np.ascontiguousarray(L.X[rows]), np.ascontiguousarray(L.dY[rows])
+    ridx = torch.from_numpy(rows).to(Y.device)
+    assert_close_bf16(Y[ridx], oracle.qa_forward(Wt, Xs, Hb, lam1, lam2, s), "Y (sampled rows)")
+    rX, _ = oracle.qa_backward(Wt, Xs, dYs, Hb, lam1, lam2, s, compute_dh=False)
+    assert_close_bf16(dX[ridx], rX, "dX (sampled rows)")
+    del Wt
+    _, rH = oracle.qa_backward(None, L.X, L.dY, Hb, lam1, lam2, s, compute_dx=False, d_out=d_out, d_in=d_in)
+    assert_close_f32(dH, rH, "dH")
