@@ -39,6 +39,7 @@ def main() -> int:
     ap.add_argument("--workload", default="llama7b_attn")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-next-rows", action="store_true", help="skip the untimed side measurement of the single-matrix adapter")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device copy of 256 MiB before the timed steps, so that a counter "
                          "profile of this command holds a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
@@ -182,32 +183,33 @@ def main() -> int:
         },
     }
 
-    # Untimed side measurement of the next row of the scope: the single-matrix (QA-BLoRA) training form at
-    # the same layer shape with the block-64 recommendation lambda = (8, 8), forward + backward (dX, dH).
-    qa_l1 = qa_l2 = 8
-    Hq = (torch.randn((d_in // qa_l1, d_out // qa_l2), device=dev) * 0.02).to(torch.bfloat16)
-    dH = torch.empty((d_in // qa_l1, d_out // qa_l2), dtype=torch.float32, device=dev)
-    qa_bytes = max(qb.lib().qablora_linear_fwd_workspace_bytes(C.byref(qw.c_struct()), qa_l1, qa_l2, T),
-                   qb.lib().qablora_linear_bwd_workspace_bytes(C.byref(qw.c_struct()), qa_l1, qa_l2, T))
-    ws_qa = torch.empty(int(qa_bytes) + 256, dtype=torch.uint8, device=dev)
+    if not args.no_next_rows:
+        # Untimed side measurement of the next row of the scope: the single-matrix (QA-BLoRA) training form at
+        # the same layer shape with the block-64 recommendation lambda = (8, 8), forward + backward (dX, dH).
+        qa_l1 = qa_l2 = 8
+        Hq = (torch.randn((d_in // qa_l1, d_out // qa_l2), device=dev) * 0.02).to(torch.bfloat16)
+        dH = torch.empty((d_in // qa_l1, d_out // qa_l2), dtype=torch.float32, device=dev)
+        qa_bytes = max(qb.lib().qablora_linear_fwd_workspace_bytes(C.byref(qw.c_struct()), qa_l1, qa_l2, T),
+                       qb.lib().qablora_linear_bwd_workspace_bytes(C.byref(qw.c_struct()), qa_l1, qa_l2, T))
+        ws_qa = torch.empty(int(qa_bytes) + 256, dtype=torch.uint8, device=dev)
 
-    def qa_step():
-        qb.qablora_linear_fwd(qw, Hq, qa_l1, qa_l2, wl.s, X, Y, ws_qa)
-        qb.qablora_linear_bwd(qw, Hq, qa_l1, qa_l2, wl.s, X, dY, True, True, dX, dH, ws_qa)
+        def qa_step():
+            qb.qablora_linear_fwd(qw, Hq, qa_l1, qa_l2, wl.s, X, Y, ws_qa)
+            qb.qablora_linear_bwd(qw, Hq, qa_l1, qa_l2, wl.s, X, dY, True, True, dX, dH, ws_qa)
 
-    for _ in range(3):
-        qa_step()
-    torch.cuda.synchronize()
-    q0 = time.perf_counter()
-    for _ in range(side_steps):
-        qa_step()
-    torch.cuda.synchronize()
-    qa_ms = (time.perf_counter() - q0) * 1e3 / side_steps
-    qa_flops = 4.0 * T * d_in * d_out + 6.0 * T * (d_in // qa_l1) * (d_out // qa_l2)
-    out["next_rows"] = {"qablora_single_matrix_fwd_bwd": {
-        "lambda": [qa_l1, qa_l2], "ms_per_step": round(qa_ms, 4), "unit": "TFLOP/s",
-        "achieved": round(qa_flops / (qa_ms * 1e-3) / 1e12, 2),
-        "frac_of_bf16_mfma_peak": round(qa_flops / (qa_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}}
+        for _ in range(3):
+            qa_step()
+        torch.cuda.synchronize()
+        q0 = time.perf_counter()
+        for _ in range(side_steps):
+            qa_step()
+        torch.cuda.synchronize()
+        qa_ms = (time.perf_counter() - q0) * 1e3 / side_steps
+        qa_flops = 4.0 * T * d_in * d_out + 6.0 * T * (d_in // qa_l1) * (d_out // qa_l2)
+        out["next_rows"] = {"qablora_single_matrix_fwd_bwd": {
+            "lambda": [qa_l1, qa_l2], "ms_per_step": round(qa_ms, 4), "unit": "TFLOP/s",
+            "achieved": round(qa_flops / (qa_ms * 1e-3) / 1e12, 2),
+            "frac_of_bf16_mfma_peak": round(qa_flops / (qa_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}}
 
     if not args.no_cpu_baseline:
         import oracle

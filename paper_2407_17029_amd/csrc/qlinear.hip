@@ -326,7 +326,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
                         unsigned char* bw_next, const bool dq, const Staged<QMODE>& sdq, const bool has_next,
                         const bool refill, const int step2, const int buf2) __attribute__((always_inline)) {
         float2 lv[3][8];
-        uint32_t li[2][8];
+        uint32_t li[3][8];
         if (dq) table_offsets(sdq, 0, li[0]);
 #pragma unroll
         for (int h = 0; h < 8; ++h) {
@@ -342,8 +342,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             if (h == 7 && has_next && refill) issue_x1_half(step2, buf2, 1);
             if (dq) {
                 if (h >= 2 && h <= 5) finish_piece(sdq, h - 2, lv[(h - 2) % 3], bw_next);
-                if (h <= 3) table_reads(li[h & 1], lv[h % 3]);
-                if (h <= 2) table_offsets(sdq, h + 1, li[(h + 1) & 1]);
+                if (h <= 3) table_reads(li[h % 3], lv[h % 3]);
+                if (h == 0) table_offsets(sdq, 1, li[1]);
+                if (h == 1) { table_offsets(sdq, 2, li[2]); table_offsets(sdq, 3, li[0]); }
             }
             if (half == 0 && ks < 3) {
                 read_wf(bw, ks + 1, wf[nxt]);
@@ -354,8 +355,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                   // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);                   // vector ALU
                 __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                   // LDS reads
-                __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);                   // vector ALU
+                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);                   // vector ALU
                 if (i == 3 || i == 7) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // a piece's LDS stores
             }
             __builtin_amdgcn_sched_barrier(0);
