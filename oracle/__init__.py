@@ -237,3 +237,16 @@ def merge_requant(codes, alpha, beta, codebook, H, block, lam1, lam2, s):
     lib().oracle_merge_requant(_p(codes), _p(alpha), _p(beta), _p(cb), _p(H), i64(d_out), i64(d_in),
                                C.c_int(block), C.c_int(lam1), C.c_int(lam2), C.c_float(s), _p(co), _p(ao), _p(bo))
     return co, ao, bo
+
+
+def merge_bf16(codes, alpha, beta, codebook, H, block, lam1, lam2, s):
+    """16-bit merge: bf16 bit patterns of w~ + s*dW, [d_out, d_in]."""
+    codes = _c(codes, np.uint8); alpha = _c(alpha, np.float32); cb = _c(codebook, np.float32)
+    beta = None if beta is None else _c(beta, np.float32)
+    H = _c(H, np.float32)
+    d_out, d_in = codes.shape[0], codes.shape[1] * 2
+    assert H.shape == (d_in // lam1, d_out // lam2)
+    W16 = np.zeros((d_out, d_in), np.uint16)
+    lib().oracle_merge_bf16(_p(codes), _p(alpha), _p(beta), _p(cb), _p(H), i64(d_out), i64(d_in), C.c_int(block),
+                            C.c_int(lam1), C.c_int(lam2), C.c_float(s), _p(W16))
+    return W16

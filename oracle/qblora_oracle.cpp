@@ -565,4 +565,30 @@ void oracle_merge_requant(const uint8_t* codes, const float* alpha, const float*
     });
 }
 
+// ---------------------------------------------------------------------------
+// Merge into a 16-bit weight (Sec. 3.2 "Merging Q-BLoRA", Alg. 1 get_delta_weight): W'[n,k] = w~[n,k] +
+// delta(n,k), delta = (s*H[k/lam1, n/lam2]) / lam1, with w~ and the sum in fp32 exactly as in the
+// requantizing merge above, then one rounding to bf16 (ties to even).  Returns bf16 bit patterns
+// [d_out, d_in].
+// ---------------------------------------------------------------------------
+void oracle_merge_bf16(const uint8_t* codes, const float* alpha, const float* beta, const float* codebook,
+                       const float* H, int64_t d_out, int64_t d_in, int block, int lam1, int lam2, float s,
+                       uint16_t* W16) {
+    int64_t bpr = d_in / block, cols = d_out / lam2;
+    parallel_rows(d_out, [&](int64_t n0, int64_t n1) {
+        for (int64_t n = n0; n < n1; ++n)
+            for (int64_t k = 0; k < d_in; ++k) {
+                int64_t blk = n * bpr + k / block;
+                float cv = codebook[get_code(codes, n * d_in + k)];
+                float wt = beta ? std::fmaf(cv, alpha[blk], beta[blk]) : f32_mul(cv, alpha[blk]);
+                float delta = f32_div(f32_mul(s, H[(k / lam1) * cols + n / lam2]), (float)lam1);
+                float w = f32_add(wt, delta);
+                uint32_t bits;
+                float r = round_to_bf16(w);
+                std::memcpy(&bits, &r, 4);
+                W16[n * d_in + k] = (uint16_t)(bits >> 16);
+            }
+    });
+}
+
 }  // extern "C"

@@ -129,3 +129,25 @@ def test_requant_merged_layer_close_to_adapted_layer(oracle, codebook):
     Y_merged = oracle.forward(Wm, L.X, None, None, 1, 1, 0.0)
     x_l1 = np.abs(bf16_exact(L.X)).sum(1, keepdims=True)
     assert np.all(np.abs(Y_merged - Y_adapted) <= x_l1 * ao.max() * 0.5 * (1 + 1e-4) + 1e-9)
+
+
+@pytest.mark.parametrize("lam1,lam2", [(2, 2), (4, 8), (64, 8)])
+@pytest.mark.parametrize("minmax_base", [False, True])
+def test_bf16_merge_is_the_rounded_dense_sum_and_reproduces_the_adapted_layer(oracle, codebook, lam1, lam2, minmax_base):
+    """16-bit merge (Alg. 1 get_delta_weight): W' = bf16(w~ + s*dW); the merged dense layer equals the adapted
+    layer up to that one rounding."""
+    d_out, d_in, s = 32, 256, 0.75
+    L, codes, alpha, beta, cb, H = _setup(oracle, codebook, 60 + lam1, d_out, d_in, lam1, lam2, R=8,
+                                          minmax_base=minmax_base, b_std=0.05)
+    W16 = oracle.merge_bf16(codes, alpha, beta, cb, H, 64, lam1, lam2, s)
+    # the same sum written with numpy in fp32, then rounded with the input generator's bf16 rounding
+    Wt32 = oracle.dequantize(codes, alpha, beta, cb, 64, 1).astype(np.float32)
+    delta = ((np.float32(s) * _expand(H, lam1, lam2).astype(np.float32)) / np.float32(lam1)).astype(np.float32)
+    assert np.array_equal(W16, synth.f32_to_bf16_bits(Wt32 + delta))
+    # merged dense layer vs adapted layer (fp64 forward on the fp32-dequantized base)
+    Wt = oracle.dequantize(codes, alpha, beta, cb, 64, 1)
+    Y_adapted = oracle.forward(Wt, L.X, L.A, L.B, lam1, lam2, s)
+    Y_merged = oracle.forward(bf16_exact(W16), L.X, None, None, 1, 1, 0.0)
+    rms = np.sqrt(np.mean(Y_adapted ** 2))
+    assert np.abs(Y_merged - Y_adapted).max() <= 2.0 ** -8 * np.abs(bf16_exact(L.X)).sum(1).max() * np.abs(Wt).max() + 1e-6 * rms
+    assert np.sqrt(np.mean((Y_merged - Y_adapted) ** 2)) <= 4e-3 * rms
