@@ -250,6 +250,17 @@ int qablora_merge_quantize(const qblora_qweight* base, const float* H, int32_t l
                            float s, int32_t mode, qblora_qweight* out, void* stream);
 
 /*
+ * Merge into a 16-bit weight (Sec. 3.2 "Merging Q-BLoRA", Alg. 1 get_delta_weight):
+ *   W16[n,k] = bf16( w~[n,k] + (s * H[k/lambda1, n/lambda2]) / lambda1 ),
+ * w~ = c*alpha or fma(c, alpha, beta) and the sum in fp32 (the arithmetic of the requantizing merge), one
+ * rounding to bf16 (ties to even); reproducible bit for bit.  H fp32 [d_in/lambda1, d_out/lambda2] as for
+ * qablora_merge_quantize (qblora_tile_product for a two-matrix adapter); W16 bf16 [d_out, d_in], device,
+ * 16-byte aligned, fully overwritten.  X * W16^T then equals the adapted layer up to that one rounding.
+ */
+int qblora_merge_bf16(const qblora_qweight* base, const float* H, int32_t lambda1, int32_t lambda2, float s,
+                      qblora_bf16* W16, void* stream);
+
+/*
  * Measurement hook.  Registers a pair of caller-created hipEvent_t (passed as void*) that the next
  * calls record on their stream immediately before and after ONE kernel launch, so that a
  * benchmark can time that kernel alone while running the whole path:

@@ -27,7 +27,7 @@ EXPORTS = ["qblora_quantize_blockwise", "qblora_dequantize_bf16", "qblora_linear
            "qblora_strerror", "qblora_profile_events", "qblora_codes_tiled_bytes", "qblora_prepack_codes",
            "qblora_saved_bytes", "qblora_linear_fwd_save", "qblora_linear_bwd_saved",
            "qablora_linear_fwd_workspace_bytes", "qablora_linear_bwd_workspace_bytes", "qablora_linear_fwd",
-           "qablora_linear_bwd"]
+           "qablora_linear_bwd", "qblora_merge_bf16"]
 
 PROFILE_FWD_GEMM, PROFILE_BWD_GEMM, PROFILE_MERGE, PROFILE_QUANTIZE = 0, 1, 2, 3
 
@@ -90,6 +90,7 @@ def lib():
                                          C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.qablora_linear_bwd.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p,
                                          C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.qblora_merge_bf16.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p]
         L.qblora_saved_bytes.restype = C.c_size_t
         L.qblora_saved_bytes.argtypes = [C.c_void_p, C.c_int64]
         L.qblora_linear_fwd_save.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
@@ -382,3 +383,15 @@ def qablora_merge_quantize(base: QWeight, H: torch.Tensor, lambda1: int, lambda2
     out.scale_codes = out.scale_step = out.scale_mid = None
     out.codes_tiled = None
     return out
+
+
+def qblora_merge_bf16(base: QWeight, H: torch.Tensor, lambda1: int, lambda2: int, s: float,
+                      W16: torch.Tensor = None) -> torch.Tensor:
+    """16-bit merge: bf16 [d_out, d_in] = w~ + s*dW."""
+    assert H.is_cuda and H.dtype == torch.float32 and H.is_contiguous()
+    if W16 is None:
+        W16 = torch.empty((base.d_out, base.d_in), dtype=torch.bfloat16, device=H.device)
+    b = base.c_struct()
+    rc = lib().qblora_merge_bf16(C.byref(b), _ptr(H), lambda1, lambda2, s, _ptr(W16), _stream())
+    _check(rc, "qblora_merge_bf16")
+    return W16

@@ -590,4 +590,24 @@ int qablora_merge_quantize(const qblora_qweight* base, const float* H, int32_t l
     return launch_merge_requant(d, st);
 }
 
+int qblora_merge_bf16(const qblora_qweight* base, const float* H, int32_t lambda1, int32_t lambda2, float s,
+                      qblora_bf16* W16, void* stream) {
+    int rc = check_qweight(base, true);
+    if (rc) return rc;
+    if (!H || !W16) return QBLORA_ERR_NULL;
+    if (lambda1 <= 0 || lambda2 <= 0) return QBLORA_ERR_SHAPE;
+    if (base->d_in % lambda1 || base->d_out % lambda2) return QBLORA_ERR_SHAPE;
+    const bool grouped = base->scale_mode == QBLORA_SCALES_E4M3_GROUPED;
+    MergeDesc d{};
+    d.codes = base->codes; d.scales = base->scales; d.beta = base->beta;
+    if (grouped) {
+        d.scale_codes = base->scale_codes; d.scale_step = base->scale_step; d.scale_mid = base->scale_mid;
+        d.scale_group = base->scale_group;
+    }
+    d.cb = codebook_of(base); d.d_out = base->d_out; d.d_in = base->d_in;
+    d.H = H; d.lam1 = lambda1; d.lam2 = lambda2; d.s = s;
+    d.w16_out = W16;
+    return launch_merge_bf16(d, as_stream(stream));
+}
+
 }  // extern "C"

@@ -129,8 +129,10 @@ struct MergeDesc {
     Codebook cb; int d_out, d_in;
     const float* H; int lam1, lam2; float s;
     uint8_t* codes_out; float* alpha_out; float* beta_out;
+    qblora_bf16* w16_out;                  // 16-bit merge only
 };
 int launch_merge_requant(const MergeDesc& d, hipStream_t st);
+int launch_merge_bf16(const MergeDesc& d, hipStream_t st);
 int launch_merge_beta_shift(const MergeDesc& d, hipStream_t st);
 
 }  // namespace qblora

@@ -62,7 +62,8 @@ __device__ __forceinline__ float quad_max(float v) {
     return fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xf, 0xf, false)));
 }
 
-template <bool GROUPED, bool BETA, int L1>
+// OUT16: write the shifted weights themselves as bf16 (the 16-bit merge) instead of requantizing them.
+template <bool GROUPED, bool BETA, int L1, bool OUT16>
 __global__ __launch_bounds__(kMergeThreads) void k_merge_requant(MergeDesc d) {
     __shared__ float lut[16];
     extern __shared__ __align__(16) float dl[];          // deltas, [hcols][stride]
@@ -148,6 +149,12 @@ __global__ __launch_bounds__(kMergeThreads) void k_merge_requant(MergeDesc d) {
 #pragma unroll
         for (int j = 0; j < 16; ++j) element(j, drow[(k + j) / d.lam1]);
     }
+    if constexpr (OUT16) {
+        uint4* wp = reinterpret_cast<uint4*>(d.w16_out + (int64_t)n * d.d_in + k);
+        wp[0] = make_uint4(pack_bf16(w[0], w[1]), pack_bf16(w[2], w[3]), pack_bf16(w[4], w[5]), pack_bf16(w[6], w[7]));
+        wp[1] = make_uint4(pack_bf16(w[8], w[9]), pack_bf16(w[10], w[11]), pack_bf16(w[12], w[13]), pack_bf16(w[14], w[15]));
+        return;
+    }
     float lo = w[0], hi = w[0];
 #pragma unroll
     for (int j = 1; j < 16; ++j) { lo = fminf(lo, w[j]); hi = fmaxf(hi, w[j]); }
@@ -195,7 +202,7 @@ __global__ __launch_bounds__(256) void k_merge_beta_shift(MergeDesc d) {
 
 }  // namespace
 
-template <int L1>
+template <int L1, bool OUT16>
 int launch_requant_l1(const MergeDesc& d, hipStream_t st) {
     const int hcols = NT / d.lam2 + 2;
     const size_t smem = sizeof(float) * (size_t)delta_stride<L1>(d.lam1) * hcols;
@@ -208,19 +215,24 @@ int launch_requant_l1(const MergeDesc& d, hipStream_t st) {
         hipLaunchKernelGGL(kern, grid, dim3(kMergeThreads), smem, st, d);
         return launch_status();
     };
-    if (d.scale_codes) return d.beta ? launch(k_merge_requant<true, true, L1>) : launch(k_merge_requant<true, false, L1>);
-    return d.beta ? launch(k_merge_requant<false, true, L1>) : launch(k_merge_requant<false, false, L1>);
+    if (d.scale_codes)
+        return d.beta ? launch(k_merge_requant<true, true, L1, OUT16>) : launch(k_merge_requant<true, false, L1, OUT16>);
+    return d.beta ? launch(k_merge_requant<false, true, L1, OUT16>) : launch(k_merge_requant<false, false, L1, OUT16>);
 }
 
-int launch_merge_requant(const MergeDesc& d, hipStream_t st) {
+template <bool OUT16>
+int launch_merge_elementwise(const MergeDesc& d, hipStream_t st) {
     switch (d.lam1) {
-        case 1: return launch_requant_l1<1>(d, st);
-        case 2: return launch_requant_l1<2>(d, st);
-        case 4: return launch_requant_l1<4>(d, st);
-        case 8: return launch_requant_l1<8>(d, st);
-        default: return launch_requant_l1<0>(d, st);
+        case 1: return launch_requant_l1<1, OUT16>(d, st);
+        case 2: return launch_requant_l1<2, OUT16>(d, st);
+        case 4: return launch_requant_l1<4, OUT16>(d, st);
+        case 8: return launch_requant_l1<8, OUT16>(d, st);
+        default: return launch_requant_l1<0, OUT16>(d, st);
     }
 }
+
+int launch_merge_requant(const MergeDesc& d, hipStream_t st) { return launch_merge_elementwise<false>(d, st); }
+int launch_merge_bf16(const MergeDesc& d, hipStream_t st) { return launch_merge_elementwise<true>(d, st); }
 
 int launch_merge_beta_shift(const MergeDesc& d, hipStream_t st) {
     int64_t total = (int64_t)d.d_out * (d.d_in / kBlock);

@@ -96,3 +96,59 @@ def test_merge_beta_shift_rejects_misaligned(qb, codebook):
     with pytest.raises(qb.QBLoRAError) as e:
         qb.qablora_merge_quantize(qw, H, 2, 2, 1.0, qb.MERGE_BETA_SHIFT)
     assert e.value.code == -5
+
+
+@pytest.mark.parametrize("base", ["codebook", "grouped", "minmax"])
+@pytest.mark.parametrize("d_out,d_in,lam1,lam2,s", [(512, 512, 2, 2, 1.0), (192, 320, 4, 8, 0.25),
+                                                     (128, 1088, 8, 8, 1.0), (100, 192, 1, 1, 1.5),
+                                                     (64, 768, 64, 2, 1.0), (96, 192, 3, 2, 1.0)])
+def test_merge_bf16_bit_exact(qb, oracle, codebook, d_out, d_in, lam1, lam2, s, base):
+    """16-bit merge: the bf16 weight w~ + s*dW, bit for bit."""
+    from gpu_util import f32_to_dev, to_np
+    print(f"case merge16 {d_out}x{d_in} lam=({lam1},{lam2}) base={base}", flush=True)
+    W = synth.base_weight(830 + d_in, 0, d_out, d_in)
+    H = synth.normal_f32(831, 1, (d_in // lam1, d_out // lam2), 0.01)
+    if base == "minmax":
+        qw = qb.qblora_quantize_blockwise(f32_to_dev(W), 64, qb.QUANT_MINMAX_INT4)
+        cb = synth.codebook_int4()
+    else:
+        qw = qb.qblora_quantize_blockwise(f32_to_dev(W), 64, qb.QUANT_ABSMAX_CODEBOOK, codebook,
+                                          qb.SCALES_E4M3_GROUPED if base == "grouped" else qb.SCALES_FP32)
+        cb = codebook
+    W16 = qb.qblora_merge_bf16(qw, f32_to_dev(H), lam1, lam2, s)
+    torch.cuda.synchronize()
+    scales = to_np(qw.scales)
+    if base == "grouped":
+        scales = oracle.scales_double_dequantize(to_np(qw.scale_codes), to_np(qw.scale_step), to_np(qw.scale_mid),
+                                                 256).reshape(scales.shape)
+    beta = None if qw.beta is None else to_np(qw.beta)
+    ref = oracle.merge_bf16(to_np(qw.codes), scales, beta, cb, H, 64, lam1, lam2, s)
+    assert np.array_equal(W16.view(torch.int16).cpu().numpy().view(np.uint16), ref)
+
+
+def test_merged_bf16_layer_reproduces_the_adapted_layer(qb, oracle, codebook):
+    """X * W16^T (a plain bf16 matmul) against the adapted forward of this library and the oracle."""
+    from gpu_util import f32_to_dev, bf16_to_dev, adapter_to_dev, to_np, assert_close_bf16
+    T, d_out, d_in, R, lam, s = 256, 512, 768, 32, 2, 1.0
+    L = synth.make_layer(840, T, d_out, d_in, R, lam, lam)
+    qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 64, qb.QUANT_ABSMAX_CODEBOOK, codebook)
+    ad = adapter_to_dev(L, lam, lam, s)
+    X = bf16_to_dev(L.X)
+    H = qb.qblora_tile_product(ad, d_in, d_out)
+    W16 = qb.qblora_merge_bf16(qw, H, lam, lam, s)
+    Y16 = torch.matmul(X.float(), W16.float().t()).to(torch.bfloat16)
+    torch.cuda.synchronize()
+    # the merged dense layer itself, from the oracle's merged weight
+    H32 = oracle.tile_product(L.A, L.B).astype(np.float32)
+    assert np.array_equal(to_np(H).view(np.uint32), H32.view(np.uint32)) or np.allclose(to_np(H), H32, rtol=1e-6, atol=1e-9)
+    W16_ref = oracle.merge_bf16(to_np(qw.codes), to_np(qw.scales), None, codebook, to_np(H), 64, lam, lam, s)
+    from helpers import bf16_exact
+    assert_close_bf16(Y16, oracle.forward(bf16_exact(W16_ref), L.X, None, None, 1, 1, 0.0), "Y (16-bit merged)")
+    # ... and the adapted layer it replaces: every merged weight carries one more bf16 rounding (2^-9
+    # relative), which shows as ~3e-3 rms and a few 1e-2 at the worst of 131072 outputs
+    from gpu_util import bf16_to_f64
+    Wt = oracle.dequantize(to_np(qw.codes), to_np(qw.scales), None, codebook, 64, 2)
+    ref = oracle.forward(Wt, L.X, L.A, L.B, lam, lam, s)
+    err = bf16_to_f64(Y16) - ref
+    rms = np.sqrt(np.mean(ref ** 2))
+    assert np.sqrt(np.mean(err ** 2)) <= 5e-3 * rms and np.abs(err).max() <= 4e-2 * rms
