@@ -261,6 +261,21 @@ int qblora_merge_bf16(const qblora_qweight* base, const float* H, int32_t lambda
                       qblora_bf16* W16, void* stream);
 
 /*
+ * Small-batch forward of a quantized layer without adapter -- inference on the INT4 model that
+ * qablora_merge_quantize produces (Sec. 3.3: the fine-tuned model is deployed in 4 bits), or on any
+ * other qblora_qweight:  Y[t,n] = sum_k X[t,k] * w~[n,k] with w~ the bf16 compute weight of
+ * qblora_dequantize_bf16, fp32 accumulation, for 1 <= T <= 16 tokens (decode batches).  Same result as
+ * qblora_linear_fwd without adapter up to the summation order; a kernel that streams the codes once
+ * instead of tiling 256 tokens.
+ *   X bf16 [T, d_in], 16-byte aligned; Y bf16 [T, d_out], fully overwritten.
+ *   workspace: qblora_linear_decode_workspace_bytes() bytes (non-zero only for grouped scales).
+ * T = 0 is a no-op; T > 16 is QBLORA_ERR_SHAPE (use qblora_linear_fwd).
+ */
+size_t qblora_linear_decode_workspace_bytes(const qblora_qweight* qw);
+int qblora_linear_decode(const qblora_qweight* qw, const qblora_bf16* X, int32_t T, qblora_bf16* Y, void* workspace,
+                         size_t workspace_bytes, void* stream);
+
+/*
  * Measurement hook.  Registers a pair of caller-created hipEvent_t (passed as void*) that the next
  * calls record on their stream immediately before and after ONE kernel launch, so that a
  * benchmark can time that kernel alone while running the whole path:

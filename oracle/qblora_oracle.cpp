@@ -243,6 +243,8 @@ void oracle_scales_double_dequantize(const uint8_t* scale_codes, int64_t n, int 
 // Dequantize (Eq. 1): w~ = alpha * c[code] + beta, beta = 0 when absent.
 //   mode 0: the real-number formula evaluated in fp64
 //   mode 1: fp32 arithmetic, c*alpha (one multiply) or fma(c, alpha, beta)
+//   mode 3: the small-batch inference weight: the code value is rounded to bf16 (exact for the integer
+//           codebook 0..15 of merged INT4 models), scale and offset are applied unrounded -- evaluated in fp64
 //   mode 2: mode 1 followed by rounding to bf16 -- the 16-bit compute weight
 //           the paper contracts activations with (Sec. 3.1: the dequantized
 //           base is held in BF16/FP16)
@@ -259,6 +261,8 @@ void oracle_dequantize(const uint8_t* codes, const float* alpha, const float* be
                 double v;
                 if (mode == 0) {
                     v = (double)alpha[blk] * (double)c + (beta ? (double)beta[blk] : 0.0);
+                } else if (mode == 3) {
+                    v = (double)alpha[blk] * (double)round_to_bf16(c) + (beta ? (double)beta[blk] : 0.0);
                 } else {
                     float f = beta ? std::fmaf(c, alpha[blk], beta[blk]) : f32_mul(c, alpha[blk]);
                     v = (double)(mode == 2 ? round_to_bf16(f) : f);

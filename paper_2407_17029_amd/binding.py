@@ -27,7 +27,8 @@ EXPORTS = ["qblora_quantize_blockwise", "qblora_dequantize_bf16", "qblora_linear
            "qblora_strerror", "qblora_profile_events", "qblora_codes_tiled_bytes", "qblora_prepack_codes",
            "qblora_saved_bytes", "qblora_linear_fwd_save", "qblora_linear_bwd_saved",
            "qablora_linear_fwd_workspace_bytes", "qablora_linear_bwd_workspace_bytes", "qablora_linear_fwd",
-           "qablora_linear_bwd", "qblora_merge_bf16"]
+           "qablora_linear_bwd", "qblora_merge_bf16",
+           "qblora_linear_decode_workspace_bytes", "qblora_linear_decode"]
 
 PROFILE_FWD_GEMM, PROFILE_BWD_GEMM, PROFILE_MERGE, PROFILE_QUANTIZE = 0, 1, 2, 3
 
@@ -91,6 +92,9 @@ def lib():
         L.qablora_linear_bwd.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p,
                                          C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.qblora_merge_bf16.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p]
+        L.qblora_linear_decode_workspace_bytes.restype = C.c_size_t
+        L.qblora_linear_decode_workspace_bytes.argtypes = [C.c_void_p]
+        L.qblora_linear_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.qblora_saved_bytes.restype = C.c_size_t
         L.qblora_saved_bytes.argtypes = [C.c_void_p, C.c_int64]
         L.qblora_linear_fwd_save.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
@@ -395,3 +399,16 @@ def qblora_merge_bf16(base: QWeight, H: torch.Tensor, lambda1: int, lambda2: int
     rc = lib().qblora_merge_bf16(C.byref(b), _ptr(H), lambda1, lambda2, s, _ptr(W16), _stream())
     _check(rc, "qblora_merge_bf16")
     return W16
+
+
+def qblora_linear_decode(qw: QWeight, X: torch.Tensor, Y: torch.Tensor = None, workspace: torch.Tensor = None):
+    """Small-batch (T <= 16) forward of a quantized layer without adapter."""
+    assert X.is_cuda and X.dtype == torch.bfloat16 and X.is_contiguous() and X.shape[1] == qw.d_in
+    T = X.shape[0]
+    if Y is None:
+        Y = torch.empty((T, qw.d_out), dtype=torch.bfloat16, device=X.device)
+    q = qw.c_struct()
+    ws = _workspace(int(lib().qblora_linear_decode_workspace_bytes(C.byref(q))), X.device, workspace)
+    rc = lib().qblora_linear_decode(C.byref(q), _ptr(X), T, _ptr(Y), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "qblora_linear_decode")
+    return Y

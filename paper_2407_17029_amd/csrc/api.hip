@@ -610,4 +610,26 @@ int qblora_merge_bf16(const qblora_qweight* base, const float* H, int32_t lambda
     return launch_merge_bf16(d, as_stream(stream));
 }
 
+size_t qblora_linear_decode_workspace_bytes(const qblora_qweight* qw) {
+    if (check_qweight(qw, false)) return 0;
+    return qw->scale_mode == QBLORA_SCALES_E4M3_GROUPED ? align_up(sizeof(float) * (size_t)n_blocks(qw)) : 0;
+}
+
+int qblora_linear_decode(const qblora_qweight* qw, const qblora_bf16* X, int32_t T, qblora_bf16* Y, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+    int rc = check_qweight(qw, true);
+    if (rc) return rc;
+    if (T < 0 || T > 16) return QBLORA_ERR_SHAPE;
+    if (T == 0) return QBLORA_OK;
+    if (!X || !Y) return QBLORA_ERR_NULL;
+    if (qw->d_in % 8 != 0 || (reinterpret_cast<uintptr_t>(X) & 15) || (reinterpret_cast<uintptr_t>(qw->codes) & 15))
+        return QBLORA_ERR_SHAPE;
+    hipStream_t st = as_stream(stream);
+    const float* scales = nullptr;
+    const size_t need = qblora_linear_decode_workspace_bytes(qw);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return QBLORA_ERR_WORKSPACE;
+    if ((rc = resolve_scales(qw, static_cast<float*>(workspace), st, &scales))) return rc;
+    return launch_w4_decode(qw->codes, scales, qw->beta, codebook_of(qw), qw->d_out, qw->d_in, X, T, Y, st);
+}
+
 }  // extern "C"

@@ -1,0 +1,79 @@
+"""GPU parity: small-batch forward of a quantized layer (merged-model inference) against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2407_17029_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def qb():
+    from paper_2407_17029_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.mark.parametrize("base", ["codebook", "minmax", "grouped"])
+@pytest.mark.parametrize("T,d_out,d_in", [(1, 512, 512), (3, 320, 192), (8, 1000, 1088), (16, 256, 2048), (5, 40, 64)])
+def test_decode_parity(qb, oracle, codebook, T, d_out, d_in, base):
+    from gpu_util import f32_to_dev, to_np, bf16_to_dev, assert_close_bf16
+    print(f"case decode T={T} {d_out}x{d_in} base={base}", flush=True)
+    L = synth.make_layer(2000 + T, T, d_out, d_in, 8, 1, 1)
+    if base == "minmax":
+        qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 64, qb.QUANT_MINMAX_INT4)
+        cb = synth.codebook_int4()
+    else:
+        qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 64, qb.QUANT_ABSMAX_CODEBOOK, codebook,
+                                          qb.SCALES_E4M3_GROUPED if base == "grouped" else qb.SCALES_FP32)
+        cb = codebook
+    X = bf16_to_dev(L.X)
+    Y = qb.qblora_linear_decode(qw, X)
+    torch.cuda.synchronize()
+    scales = to_np(qw.scales)
+    if base == "grouped":
+        scales = oracle.scales_double_dequantize(to_np(qw.scale_codes), to_np(qw.scale_step), to_np(qw.scale_mid),
+                                                 256).reshape(scales.shape)
+    beta = None if qw.beta is None else to_np(qw.beta)
+    Wt = oracle.dequantize(to_np(qw.codes), scales, beta, cb, 64, 2)
+    assert_close_bf16(Y, oracle.forward(Wt, L.X, None, None, 1, 1, 0.0), "Y")
+
+
+def test_decode_of_the_merged_int4_model(qb, oracle, codebook):
+    """Sec. 3.3 deployment path: train-time layer with aligned tiles -> beta-shift merge -> 4-bit inference."""
+    from gpu_util import f32_to_dev, to_np, bf16_to_dev, assert_close_bf16
+    T, d_out, d_in, lam1, lam2, s = 4, 512, 1024, 64, 8, 0.75
+    L = synth.make_layer(2100, T, d_out, d_in, 8, lam1, lam2)
+    Hb = synth.f32_to_bf16_bits((np.random.default_rng(2101).standard_normal((d_in // lam1, d_out // lam2)) * 0.05)
+                                .astype(np.float32))
+    qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 64, qb.QUANT_MINMAX_INT4)
+    H = bf16_to_dev(Hb)
+    merged = qb.qablora_merge_quantize(qw, H.float(), lam1, lam2, s, qb.MERGE_BETA_SHIFT)
+    X = bf16_to_dev(L.X)
+    Y = qb.qblora_linear_decode(merged, X)
+    torch.cuda.synchronize()
+    # the merged model itself: beta' from the oracle's merge, the bf16 compute weight, a plain forward
+    from helpers import bf16_exact
+    from gpu_util import bf16_to_f64
+    cb = synth.codebook_int4()
+    beta2 = oracle.merge_beta_shift(to_np(qw.beta), bf16_exact(Hb).astype(np.float32), d_out, d_in, 64, lam1, lam2, s)
+    assert np.array_equal(to_np(merged.beta).view(np.uint32), beta2.view(np.uint32))
+    Wm = oracle.dequantize(to_np(qw.codes), to_np(qw.scales), beta2, cb, 64, 2)
+    assert_close_bf16(Y, oracle.forward(Wm, L.X, None, None, 1, 1, 0.0), "Y (merged INT4, decode)")
+    # ... and the train-time layer it replaces, up to the bf16 rounding of the merged weights
+    Wt = oracle.dequantize(to_np(qw.codes), to_np(qw.scales), to_np(qw.beta), cb, 64, 2)
+    ref = oracle.qa_forward(Wt, L.X, Hb, lam1, lam2, s)
+    err = bf16_to_f64(Y) - ref
+    rms = np.sqrt(np.mean(ref ** 2))
+    assert np.sqrt(np.mean(err ** 2)) <= 5e-3 * rms and np.abs(err).max() <= 4e-2 * rms
+
+
+def test_decode_errors(qb, oracle, codebook):
+    from gpu_util import f32_to_dev
+    W = synth.base_weight(2200, 0, 128, 128)
+    qw = qb.qblora_quantize_blockwise(f32_to_dev(W), 64, qb.QUANT_ABSMAX_CODEBOOK, codebook)
+    X = torch.zeros((17, 128), dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(RuntimeError):
+        qb.qblora_linear_decode(qw, X)                                   # more than 16 tokens
+    assert qb.qblora_linear_decode(qw, X[:0]).shape == (0, 128)

@@ -220,3 +220,17 @@ def test_double_quant_equal_scales_and_ragged_group(oracle):
     assert sc.shape == (300,) and step.shape == (2,)
     assert np.all(sc == 0) and np.all(step == 0) and np.all(mid == np.float32(0.7))
     assert np.array_equal(oracle.scales_double_dequantize(sc, step, mid, 256), s)
+
+
+def test_dequantize_inference_mode_is_scale_times_bf16_code_plus_offset(oracle, codebook):
+    """Mode 3 (small-batch inference weight): alpha * bf16(c) + beta without further rounding; for the integer
+    codebook of INT4 models it is the real-number formula of Eq. 1 itself."""
+    from helpers import unpack_codes, bf16_exact
+    W = synth.base_weight(77, 0, 8, 128)
+    codes, alpha, beta = oracle.quantize_minmax(W, 64)
+    cb = synth.codebook_int4()
+    assert np.array_equal(oracle.dequantize(codes, alpha, beta, cb, 64, 3), oracle.dequantize(codes, alpha, beta, cb, 64, 0))
+    codes, alpha = oracle.quantize_codebook(W, 64, codebook)
+    cbr = bf16_exact(synth.f32_to_bf16_bits(np.asarray(codebook, np.float32)))
+    want = np.repeat(alpha.astype(np.float64), 64, axis=1) * cbr[unpack_codes(codes)]
+    assert np.array_equal(oracle.dequantize(codes, alpha, None, codebook, 64, 3), want)
