@@ -263,17 +263,30 @@ int qblora_merge_bf16(const qblora_qweight* base, const float* H, int32_t lambda
 /*
  * Small-batch forward of a quantized layer without adapter -- inference on the INT4 model that
  * qablora_merge_quantize produces (Sec. 3.3: the fine-tuned model is deployed in 4 bits), or on any
- * other qblora_qweight:  Y[t,n] = sum_k X[t,k] * w~[n,k] with w~ the bf16 compute weight of
- * qblora_dequantize_bf16, fp32 accumulation, for 1 <= T <= 16 tokens (decode batches).  Same result as
- * qblora_linear_fwd without adapter up to the summation order; a kernel that streams the codes once
- * instead of tiling 256 tokens.
+ * other qblora_qweight, for 1 <= T <= 16 tokens (decode batches):
+ *   Y[t,n] = sum_b ( alpha[n,b] * sum_{k in block b} X[t,k] * bf16(c[code[n,k]]) + beta[n,b] * sum_{k in b} X[t,k] ),
+ * fp32 accumulation.  Scale and offset act on the block sums, so the weight itself is never rounded to
+ * 16 bits; for the integer codebook of INT4 models bf16(c) = c and the result is Eq. 1 contracted in
+ * fp32.  It differs from qblora_linear_fwd without adapter (which contracts the bf16-rounded weight)
+ * by that rounding only.
  *   X bf16 [T, d_in], 16-byte aligned; Y bf16 [T, d_out], fully overwritten.
  *   workspace: qblora_linear_decode_workspace_bytes() bytes (non-zero only for grouped scales).
  * T = 0 is a no-op; T > 16 is QBLORA_ERR_SHAPE (use qblora_linear_fwd).
  */
 size_t qblora_linear_decode_workspace_bytes(const qblora_qweight* qw);
-int qblora_linear_decode(const qblora_qweight* qw, const qblora_bf16* X, int32_t T, qblora_bf16* Y, void* workspace,
-                         size_t workspace_bytes, void* stream);
+int qblora_linear_decode(const qblora_qweight* qw, const void* pack, const qblora_bf16* X, int32_t T, qblora_bf16* Y,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * One-off re-layout of a (frozen) quantized weight for qblora_linear_decode: `pack` is a device buffer of
+ * qblora_decode_pack_bytes() bytes, 256-byte aligned, owned by the caller, that receives the codes, the
+ * fp32 block scales (grouped scales are reconstructed) and the offsets in tile order (rows in tiles of
+ * 256; the values of one block for the rows of a tile are adjacent), so that a wave's load of one block
+ * for 16 rows touches 5 cache lines instead of 32.  qblora_linear_decode with pack = NULL reads the
+ * row-major arrays of `qw` (same result, about half the speed); with a pack it needs no workspace.
+ */
+size_t qblora_decode_pack_bytes(const qblora_qweight* qw);
+int qblora_decode_pack(const qblora_qweight* qw, void* pack, void* stream);
 
 /*
  * Measurement hook.  Registers a pair of caller-created hipEvent_t (passed as void*) that the next

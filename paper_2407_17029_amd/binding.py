@@ -28,7 +28,8 @@ EXPORTS = ["qblora_quantize_blockwise", "qblora_dequantize_bf16", "qblora_linear
            "qblora_saved_bytes", "qblora_linear_fwd_save", "qblora_linear_bwd_saved",
            "qablora_linear_fwd_workspace_bytes", "qablora_linear_bwd_workspace_bytes", "qablora_linear_fwd",
            "qablora_linear_bwd", "qblora_merge_bf16",
-           "qblora_linear_decode_workspace_bytes", "qblora_linear_decode"]
+           "qblora_linear_decode_workspace_bytes", "qblora_linear_decode",
+           "qblora_decode_pack_bytes", "qblora_decode_pack"]
 
 PROFILE_FWD_GEMM, PROFILE_BWD_GEMM, PROFILE_MERGE, PROFILE_QUANTIZE = 0, 1, 2, 3
 
@@ -94,7 +95,11 @@ def lib():
         L.qblora_merge_bf16.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p]
         L.qblora_linear_decode_workspace_bytes.restype = C.c_size_t
         L.qblora_linear_decode_workspace_bytes.argtypes = [C.c_void_p]
-        L.qblora_linear_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.qblora_linear_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
+                                           C.c_void_p]
+        L.qblora_decode_pack_bytes.restype = C.c_size_t
+        L.qblora_decode_pack_bytes.argtypes = [C.c_void_p]
+        L.qblora_decode_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.qblora_saved_bytes.restype = C.c_size_t
         L.qblora_saved_bytes.argtypes = [C.c_void_p, C.c_int64]
         L.qblora_linear_fwd_save.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
@@ -401,7 +406,16 @@ def qblora_merge_bf16(base: QWeight, H: torch.Tensor, lambda1: int, lambda2: int
     return W16
 
 
-def qblora_linear_decode(qw: QWeight, X: torch.Tensor, Y: torch.Tensor = None, workspace: torch.Tensor = None):
+def qblora_decode_pack(qw: QWeight) -> torch.Tensor:
+    """One-off tile-ordered copy of codes / scales / offsets for qblora_linear_decode."""
+    q = qw.c_struct()
+    pack = torch.empty(int(lib().qblora_decode_pack_bytes(C.byref(q))), dtype=torch.uint8, device=qw.codes.device)
+    _check(lib().qblora_decode_pack(C.byref(q), _ptr(pack), _stream()), "qblora_decode_pack")
+    return pack
+
+
+def qblora_linear_decode(qw: QWeight, X: torch.Tensor, Y: torch.Tensor = None, workspace: torch.Tensor = None,
+                         pack: torch.Tensor = None):
     """Small-batch (T <= 16) forward of a quantized layer without adapter."""
     assert X.is_cuda and X.dtype == torch.bfloat16 and X.is_contiguous() and X.shape[1] == qw.d_in
     T = X.shape[0]
@@ -409,6 +423,6 @@ def qblora_linear_decode(qw: QWeight, X: torch.Tensor, Y: torch.Tensor = None, w
         Y = torch.empty((T, qw.d_out), dtype=torch.bfloat16, device=X.device)
     q = qw.c_struct()
     ws = _workspace(int(lib().qblora_linear_decode_workspace_bytes(C.byref(q))), X.device, workspace)
-    rc = lib().qblora_linear_decode(C.byref(q), _ptr(X), T, _ptr(Y), _ptr(ws), ws.numel(), _stream())
+    rc = lib().qblora_linear_decode(C.byref(q), _ptr(pack), _ptr(X), T, _ptr(Y), _ptr(ws), ws.numel(), _stream())
     _check(rc, "qblora_linear_decode")
     return Y

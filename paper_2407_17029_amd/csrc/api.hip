@@ -610,26 +610,75 @@ int qblora_merge_bf16(const qblora_qweight* base, const float* H, int32_t lambda
     return launch_merge_bf16(d, as_stream(stream));
 }
 
+namespace {
+
+struct DecodePack { uint8_t* codes; float* scales; float* beta; size_t bytes; };
+DecodePack carve_pack(const qblora_qweight* qw, void* base) {
+    Carver c(base);
+    DecodePack p{};
+    const size_t rows = (size_t)((qw->d_out + 255) / 256) * 256, bpr = (size_t)(qw->d_in / qw->block);
+    p.codes = c.take<uint8_t>(rows * bpr * 32);
+    p.scales = c.take<float>(rows * bpr);
+    if (qw->beta) p.beta = c.take<float>(rows * bpr);
+    p.bytes = c.off;
+    return p;
+}
+
+}  // namespace
+
+size_t qblora_decode_pack_bytes(const qblora_qweight* qw) {
+    if (check_qweight(qw, false)) return 0;
+    return carve_pack(qw, nullptr).bytes;
+}
+
+int qblora_decode_pack(const qblora_qweight* qw, void* pack, void* stream) {
+    int rc = check_qweight(qw, true);
+    if (rc) return rc;
+    if (!pack) return QBLORA_ERR_NULL;
+    hipStream_t st = as_stream(stream);
+    DecodePack p = carve_pack(qw, pack);
+    if ((rc = launch_prepack_codes(qw->codes, qw->d_out, qw->d_in, p.codes, st))) return rc;
+    ScaleTiling sct{};
+    const bool grouped = qw->scale_mode == QBLORA_SCALES_E4M3_GROUPED;
+    sct.scales = grouped ? nullptr : qw->scales;
+    if (grouped) { sct.scale_codes = qw->scale_codes; sct.scale_step = qw->scale_step; sct.scale_mid = qw->scale_mid; }
+    sct.scale_group = qw->scale_group; sct.d_out = qw->d_out; sct.d_in = qw->d_in; sct.out = p.scales;
+    if ((rc = launch_adapter_prep(nullptr, nullptr, qw->d_in, qw->d_out, 0, 1, 1, nullptr, nullptr, nullptr, st, &sct)))
+        return rc;
+    if (qw->beta) {
+        ScaleTiling bt{};
+        bt.scales = qw->beta; bt.d_out = qw->d_out; bt.d_in = qw->d_in; bt.out = p.beta;
+        if ((rc = launch_adapter_prep(nullptr, nullptr, qw->d_in, qw->d_out, 0, 1, 1, nullptr, nullptr, nullptr, st, &bt)))
+            return rc;
+    }
+    return QBLORA_OK;
+}
+
 size_t qblora_linear_decode_workspace_bytes(const qblora_qweight* qw) {
     if (check_qweight(qw, false)) return 0;
     return qw->scale_mode == QBLORA_SCALES_E4M3_GROUPED ? align_up(sizeof(float) * (size_t)n_blocks(qw)) : 0;
 }
 
-int qblora_linear_decode(const qblora_qweight* qw, const qblora_bf16* X, int32_t T, qblora_bf16* Y, void* workspace,
-                         size_t workspace_bytes, void* stream) {
+int qblora_linear_decode(const qblora_qweight* qw, const void* pack, const qblora_bf16* X, int32_t T, qblora_bf16* Y,
+                         void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_qweight(qw, true);
     if (rc) return rc;
     if (T < 0 || T > 16) return QBLORA_ERR_SHAPE;
     if (T == 0) return QBLORA_OK;
     if (!X || !Y) return QBLORA_ERR_NULL;
-    if (qw->d_in % 8 != 0 || (reinterpret_cast<uintptr_t>(X) & 15) || (reinterpret_cast<uintptr_t>(qw->codes) & 15))
+    if (qw->d_in % 8 != 0 || (reinterpret_cast<uintptr_t>(X) & 15) || (reinterpret_cast<uintptr_t>(qw->codes) & 15) ||
+        (reinterpret_cast<uintptr_t>(pack) & 255))
         return QBLORA_ERR_SHAPE;
     hipStream_t st = as_stream(stream);
+    if (pack) {
+        DecodePack p = carve_pack(qw, const_cast<void*>(pack));
+        return launch_w4_decode(p.codes, p.scales, p.beta, codebook_of(qw), 1, qw->d_out, qw->d_in, X, T, Y, st);
+    }
     const float* scales = nullptr;
     const size_t need = qblora_linear_decode_workspace_bytes(qw);
     if (need > 0 && (!workspace || workspace_bytes < need)) return QBLORA_ERR_WORKSPACE;
     if ((rc = resolve_scales(qw, static_cast<float*>(workspace), st, &scales))) return rc;
-    return launch_w4_decode(qw->codes, scales, qw->beta, codebook_of(qw), qw->d_out, qw->d_in, X, T, Y, st);
+    return launch_w4_decode(qw->codes, scales, qw->beta, codebook_of(qw), 0, qw->d_out, qw->d_in, X, T, Y, st);
 }
 
 }  // extern "C"

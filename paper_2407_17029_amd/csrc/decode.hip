@@ -1,20 +1,22 @@
 // Small-batch forward of a 4-bit block-quantized layer (merged-model inference: the INT4 weights
 // (codes, alpha, beta) that the QA-BLoRA merge of Sec. 3.3 produces, or any other quantized base):
 //
-//   Y[t, n] = sum_k X[t, k] * w~[n, k],   w~ = bf16(c[code] * alpha) or bf16(fma(c[code], alpha, beta)),
+//   Y[t, n] = sum_b ( alpha[n,b] * sum_{k in b} X[t,k] * c^[n,k]  +  beta[n,b] * sum_{k in b} X[t,k] ),
 //
-// for T <= 16 tokens.  Every weight is used once per token, so the kernel is bound by streaming the
-// codes and block parameters from HBM (0.5 + 4/64 (+ 4/64) bytes per weight); the dequantize-and-
-// contract kernel for training batches would spend its time filling 256-token tiles with padding.
+// c^ = bf16(c[code]) (exact for the codebook 0..15 of INT4 models), for T <= 16 tokens.  Every weight is
+// used once per token, so the job is to stream the codes and block parameters from HBM (0.5 + 4/64
+// (+ 4/64) bytes per weight) with as little vector arithmetic per weight as possible: scale and offset
+// are constant inside a 64-block, so they are applied to the block's partial sums, not to the weights,
+// and a code byte becomes two bf16 operand values with one LDS read.
 //
 // A workgroup of 4 waves owns 16 output rows; the waves split the input dimension (wave w takes the
-// groups of 4 blocks j = w, w+4, ...) and add their partial tiles through LDS at the end.  Inside a
-// wave, lane l works on row (l & 15) and on block 4j + (l >> 4) of the group: it loads that block's 32
-// code bytes and parameters, dequantizes 8 weights at a time into the A operand of
-// v_mfma_f32_16x16x32_bf16 and contracts them with the 8 matching activations of token (l & 15) (B
-// operand, zero for tokens >= T), so one MFMA retires 16 rows x 16 tokens x 32 inputs and the vector
-// ALU only dequantizes.  The contraction order inside a group is this lane assignment (any order is
-// valid as long as both operands agree); accumulation is fp32.
+// groups of 4 consecutive blocks j = w, w+4, ...) and add their partial tiles through LDS at the end.
+// Inside a wave, lane l works on row (l & 15): for block b it loads 8 of the block's 32 code bytes
+// (quarter l >> 4), turns them into the B operand of two v_mfma_f32_16x16x32_bf16 whose A operand is the
+// matching 8 activations of token (l & 15) (zero for tokens >= T): the two MFMAs give the lane the
+// block's sums for its row and tokens 4*(l>>4) .. +3.  A third and fourth MFMA against a B operand of
+// ones give sum_k X[t,k] of the block when there are offsets.  Then one FMA per token applies alpha
+// (and one beta).  Any assignment of k to lanes is valid as long as both operands agree.
 #include "common.h"
 
 namespace qblora {
@@ -25,20 +27,23 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 struct DecodeDesc {
     const uint8_t* codes; const float* scales; const float* beta; Codebook cb;
+    int tiled;                 // the three arrays are in tile order (256-row tiles, rows of a block adjacent)
     int d_out, d_in;
     const qblora_bf16* X; int T;
     qblora_bf16* Y;
 };
 
-struct DecodeRegs {
-    uint4 c0, c1;          // the lane's block: 64 codes
-    float a, b;            // its scale and offset
-    uint4 x[8];            // activations of the lane's token for the block, 8 per MFMA
+constexpr int kReplicas = 16;               // copies of the byte -> (bf16 c[lo], bf16 c[hi]) table
+
+struct DecodeRegs {                         // one group = 4 consecutive blocks of the lane's row
+    uint2 c[4];                             // the lane's quarter of each block's codes: 16 codes
+    float a[4], b[4];                       // scale and offset of each block
+    uint4 x[4][2];                          // activations of the lane's token, 8 per MFMA
 };
 
 template <bool BETA>
 __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
-    __shared__ float lut[16];
+    __shared__ uint32_t pair[256 * kReplicas];          // entry e of replica q at e*kReplicas + q
     __shared__ float red[4][4][64];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int nl = lane & 15, kg = lane >> 4;
@@ -46,46 +51,71 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
     const int n = min(n0 + nl, d.d_out - 1);                  // rows past the end are computed, not stored
     const int bpr = d.d_in / kBlock;
     const int groups = (bpr + 3) / 4;
-    if (t < 16) lut[t] = d.cb.c[t];
-    __syncthreads();
-
-    const uint8_t* crow = d.codes + (int64_t)n * (d.d_in / 2);
-    const float* srow = d.scales + (int64_t)n * bpr;
-    const float* brow = BETA ? d.beta + (int64_t)n * bpr : nullptr;
-    const qblora_bf16* xrow = d.X + (int64_t)min(nl, d.T - 1) * d.d_in;
-    const bool token = nl < d.T;
-
-    auto load = [&](DecodeRegs& r, int j) __attribute__((always_inline)) {
-        const int b = 4 * j + kg;
-        if (b < bpr) {
-            const uint4* cp = reinterpret_cast<const uint4*>(crow + b * 32);
-            r.c0 = cp[0]; r.c1 = cp[1];
-            r.a = srow[b];
-            r.b = BETA ? brow[b] : 0.0f;
-        } else {
-            r.c0 = r.c1 = make_uint4(0, 0, 0, 0); r.a = 0.0f; r.b = 0.0f;
-        }
+    {
+        const uint32_t e = pack_bf16(d.cb.c[t & 15], d.cb.c[t >> 4]);
 #pragma unroll
-        for (int m = 0; m < 8; ++m)
-            r.x[m] = (token && b < bpr) ? *reinterpret_cast<const uint4*>(xrow + b * kBlock + 8 * m) : make_uint4(0, 0, 0, 0);
+        for (int q = 0; q < kReplicas; ++q) pair[t * kReplicas + q] = e;
+    }
+    __syncthreads();
+    const uint32_t* my_pair = pair + (lane & (kReplicas - 1));
+
+    // Row-major arrays: a wave's load of one block touches 16 rows, i.e. 16 cache lines.  In tile order
+    // (the layout of the forward kernel's code copy) the 16 rows of a block are adjacent: 4 lines of codes
+    // and one of scales per load, which is what keeps the address path from being the bottleneck.
+    const int64_t run = d.tiled ? ((int64_t)(n >> 8) * bpr * 256 + (n & 255)) : (int64_t)n * bpr;   // block 0 of row n
+    const int bstep = d.tiled ? 256 : 1;                                                            // next block
+    const uint8_t* crow = d.codes + run * 32 + 8 * kg;
+    const float* srow = d.scales + run;
+    const float* brow = BETA ? d.beta + run : nullptr;
+    const int cstep = bstep * 32;
+    const qblora_bf16* xrow = d.X + (int64_t)min(nl, d.T - 1) * d.d_in + 16 * kg;
+
+    // Every load is unconditional: a block past the end of the row is redirected to the last block and
+    // given scale = offset = 0; lanes whose token does not exist read the last token's row and produce
+    // output rows that are never stored.
+    auto load = [&](DecodeRegs& r, int j) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int b = 4 * j + q;
+            const bool in = b < bpr;
+            const int bc = in ? b : bpr - 1;
+            r.c[q] = *reinterpret_cast<const uint2*>(crow + (int64_t)bc * cstep);
+            const float a = srow[(int64_t)bc * bstep];
+            r.a[q] = in ? a : 0.0f;
+            if constexpr (BETA) {
+                const float bt = brow[(int64_t)bc * bstep];
+                r.b[q] = in ? bt : 0.0f;
+            } else {
+                r.b[q] = 0.0f;
+            }
+#pragma unroll
+            for (int m = 0; m < 2; ++m) r.x[q][m] = *reinterpret_cast<const uint4*>(xrow + bc * kBlock + 8 * m);
+        }
     };
 
     f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    const f32x4_t zero = {0.0f, 0.0f, 0.0f, 0.0f};
+    const uint4 ones4 = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, ones4);
+    auto operand = [&](uint32_t w) __attribute__((always_inline)) {
+        const uint4 v = make_uint4(my_pair[(w & 0xffu) * kReplicas], my_pair[((w >> 8) & 0xffu) * kReplicas],
+                                   my_pair[((w >> 16) & 0xffu) * kReplicas], my_pair[(w >> 24) * kReplicas]);
+        return __builtin_bit_cast(bf16x8, v);
+    };
     auto compute = [&](const DecodeRegs& r) __attribute__((always_inline)) {
-        const uint32_t cw[8] = {r.c0.x, r.c0.y, r.c0.z, r.c0.w, r.c1.x, r.c1.y, r.c1.z, r.c1.w};
 #pragma unroll
-        for (int m = 0; m < 8; ++m) {
-            uint32_t p[4];
+        for (int q = 0; q < 4; ++q) {
+            const bf16x8 x0 = __builtin_bit_cast(bf16x8, r.x[q][0]), x1 = __builtin_bit_cast(bf16x8, r.x[q][1]);
+            f32x4_t blk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x0, operand(r.c[q].x), zero, 0, 0, 0);
+            blk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x1, operand(r.c[q].y), blk, 0, 0, 0);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float c_lo = lut[(cw[m] >> (8 * q)) & 15], c_hi = lut[(cw[m] >> (8 * q + 4)) & 15];
-                const float w_lo = BETA ? __fmaf_rn(c_lo, r.a, r.b) : __fmul_rn(c_lo, r.a);
-                const float w_hi = BETA ? __fmaf_rn(c_hi, r.a, r.b) : __fmul_rn(c_hi, r.a);
-                p[q] = pack_bf16(w_lo, w_hi);
+            for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(r.a[q], blk[e], acc[e]);
+            if constexpr (BETA) {
+                f32x4_t sx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x0, ones, zero, 0, 0, 0);
+                sx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x1, ones, sx, 0, 0, 0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(r.b[q], sx[e], acc[e]);
             }
-            const uint4 wv = make_uint4(p[0], p[1], p[2], p[3]);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv), __builtin_bit_cast(bf16x8, r.x[m]),
-                                                          acc, 0, 0, 0);
         }
     };
 
@@ -102,32 +132,36 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
         }
     }
 
-    // partial tiles of the four waves -> LDS, added in wave order by wave 0
+    // The lane holds row nl, tokens 4*kg .. 4*kg+3.  Partial tiles of the four waves -> LDS; wave 0 adds
+    // them in wave order, lane l taking token l >> 2 and rows 4*(l & 3) .. +3 so that stores run along n.
 #pragma unroll
     for (int e = 0; e < 4; ++e) red[wave][e][lane] = acc[e];
     __syncthreads();
-    if (wave == 0 && token) {
-        // the lane holds token nl, rows 4*kg .. 4*kg+3
+    const int tok = lane >> 2, nq = 4 * (lane & 3);
+    if (wave == 0 && tok < d.T) {
         float v[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = ((red[0][e][lane] + red[1][e][lane]) + red[2][e][lane]) + red[3][e][lane];
-        const int nb = n0 + 4 * kg;
-        qblora_bf16* yp = d.Y + (int64_t)nl * d.d_out + nb;
+        for (int i = 0; i < 4; ++i) {
+            const int src = (nq + i) + 16 * (tok >> 2), e = tok & 3;
+            v[i] = ((red[0][e][src] + red[1][e][src]) + red[2][e][src]) + red[3][e][src];
+        }
+        const int nb = n0 + nq;
+        qblora_bf16* yp = d.Y + (int64_t)tok * d.d_out + nb;
         if (nb + 3 < d.d_out && (d.d_out & 3) == 0) {
             *reinterpret_cast<uint2*>(yp) = make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]));
         } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (nb + e < d.d_out) reinterpret_cast<uint16_t*>(yp)[e] = (uint16_t)(pack_bf16(v[e], 0.0f) & 0xffffu);
+            for (int i = 0; i < 4; ++i)
+                if (nb + i < d.d_out) reinterpret_cast<uint16_t*>(yp)[i] = (uint16_t)(pack_bf16(v[i], 0.0f) & 0xffffu);
         }
     }
 }
 
 }  // namespace
 
-int launch_w4_decode(const uint8_t* codes, const float* scales, const float* beta, const Codebook& cb, int d_out,
-                     int d_in, const qblora_bf16* X, int T, qblora_bf16* Y, hipStream_t st) {
-    DecodeDesc d{codes, scales, beta, cb, d_out, d_in, X, T, Y};
+int launch_w4_decode(const uint8_t* codes, const float* scales, const float* beta, const Codebook& cb, int tiled,
+                     int d_out, int d_in, const qblora_bf16* X, int T, qblora_bf16* Y, hipStream_t st) {
+    DecodeDesc d{codes, scales, beta, cb, tiled, d_out, d_in, X, T, Y};
     const dim3 grid((unsigned)((d_out + 15) / 16));
     if (beta) hipLaunchKernelGGL(k_w4_decode<true>, grid, dim3(256), 0, st, d);
     else hipLaunchKernelGGL(k_w4_decode<false>, grid, dim3(256), 0, st, d);

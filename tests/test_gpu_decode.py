@@ -30,13 +30,15 @@ def test_decode_parity(qb, oracle, codebook, T, d_out, d_in, base):
         cb = codebook
     X = bf16_to_dev(L.X)
     Y = qb.qblora_linear_decode(qw, X)
+    Yp = qb.qblora_linear_decode(qw, X, pack=qb.qblora_decode_pack(qw))
     torch.cuda.synchronize()
+    assert torch.equal(Y.view(torch.int16), Yp.view(torch.int16))       # tile-ordered pack: same bits
     scales = to_np(qw.scales)
     if base == "grouped":
         scales = oracle.scales_double_dequantize(to_np(qw.scale_codes), to_np(qw.scale_step), to_np(qw.scale_mid),
                                                  256).reshape(scales.shape)
     beta = None if qw.beta is None else to_np(qw.beta)
-    Wt = oracle.dequantize(to_np(qw.codes), scales, beta, cb, 64, 2)
+    Wt = oracle.dequantize(to_np(qw.codes), scales, beta, cb, 64, 3)     # the inference weight: alpha*bf16(c)+beta
     assert_close_bf16(Y, oracle.forward(Wt, L.X, None, None, 1, 1, 0.0), "Y")
 
 
@@ -51,7 +53,7 @@ def test_decode_of_the_merged_int4_model(qb, oracle, codebook):
     H = bf16_to_dev(Hb)
     merged = qb.qablora_merge_quantize(qw, H.float(), lam1, lam2, s, qb.MERGE_BETA_SHIFT)
     X = bf16_to_dev(L.X)
-    Y = qb.qblora_linear_decode(merged, X)
+    Y = qb.qblora_linear_decode(merged, X, pack=qb.qblora_decode_pack(merged))
     torch.cuda.synchronize()
     # the merged model itself: beta' from the oracle's merge, the bf16 compute weight, a plain forward
     from helpers import bf16_exact
@@ -59,9 +61,9 @@ def test_decode_of_the_merged_int4_model(qb, oracle, codebook):
     cb = synth.codebook_int4()
     beta2 = oracle.merge_beta_shift(to_np(qw.beta), bf16_exact(Hb).astype(np.float32), d_out, d_in, 64, lam1, lam2, s)
     assert np.array_equal(to_np(merged.beta).view(np.uint32), beta2.view(np.uint32))
-    Wm = oracle.dequantize(to_np(qw.codes), to_np(qw.scales), beta2, cb, 64, 2)
+    Wm = oracle.dequantize(to_np(qw.codes), to_np(qw.scales), beta2, cb, 64, 3)
     assert_close_bf16(Y, oracle.forward(Wm, L.X, None, None, 1, 1, 0.0), "Y (merged INT4, decode)")
-    # ... and the train-time layer it replaces, up to the bf16 rounding of the merged weights
+    # ... and the train-time layer it replaces (whose base weight is rounded to bf16)
     Wt = oracle.dequantize(to_np(qw.codes), to_np(qw.scales), to_np(qw.beta), cb, 64, 2)
     ref = oracle.qa_forward(Wt, L.X, Hb, lam1, lam2, s)
     err = bf16_to_f64(Y) - ref
