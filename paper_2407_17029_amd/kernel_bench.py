@@ -1,0 +1,127 @@
+#!/usr/bin/env python3
+"""Per-kernel timings of the library beyond the benchmark step: the streaming kernels on the large layer
+shapes (where launch overhead no longer dominates) and the rows built next to the hot path.
+
+    python -m paper_2407_17029_amd.kernel_bench [merge] [quantize] [decode] [qablora]
+
+Each measurement is one JSON line: back-to-back launches between two HIP events on the current stream
+(warm caches; the 256 MB last-level cache holds the smaller shapes), algorithmic bytes or flops as defined
+in the design notes, and the fraction of the MI355X peak (HBM 8000 GB/s, bf16 MFMA 2500 TFLOP/s).  The
+short kernels are launched through the C ABI with arguments marshalled once, so that the host keeps ahead
+of the GPU (the Python wrappers cost ~25 us a call).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import json
+import sys
+
+import numpy as np
+import torch
+
+from . import binding as qb
+from . import synth
+
+HBM_GBS, MFMA_TFLOPS = 8000.0, 2500.0
+SHAPES = [(4096, 4096), (11008, 4096), (22016, 8192)]          # 7B attention, 7B MLP up, 65B MLP up
+DEV = "cuda:0"
+
+
+def timed(fn, iters=20, warm=3):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(iters):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / iters * 1e-3                      # seconds per launch
+
+
+def emit(**kw):
+    print(json.dumps(kw), flush=True)
+
+
+def bench_quantize():
+    cb = synth.codebook_nf4_style()
+    for d_out, d_in in SHAPES:
+        W = torch.randn(d_out, d_in, device=DEV) * 0.02
+        qw = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_ABSMAX_CODEBOOK, cb, tiled=False)
+        q, cbp = qw.c_struct(), np.ascontiguousarray(cb, np.float32)
+        args = (qb._ptr(W), d_out, d_in, 64, qb.QUANT_ABSMAX_CODEBOOK, cbp.ctypes.data_as(C.c_void_p), qb.SCALES_FP32,
+                C.byref(q), qb._stream())
+        s = timed(lambda: qb.lib().qblora_quantize_blockwise(*args))
+        nbytes = d_out * d_in * (4 + 0.5 + 4 / 64)
+        emit(kernel="quantize_codebook", shape=[d_out, d_in], us=round(s * 1e6, 1), GBps=round(nbytes / s / 1e9, 1),
+             frac_hbm=round(nbytes / s / 1e9 / HBM_GBS, 3))
+        del W, qw
+
+
+def bench_merge():
+    cb = synth.codebook_nf4_style()
+    for d_out, d_in in SHAPES:
+        for lam in (2, 8):
+            W = torch.randn(d_out, d_in, device=DEV) * 0.02
+            qw = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_ABSMAX_CODEBOOK, cb, tiled=False)
+            H = torch.randn(d_in // lam, d_out // lam, device=DEV) * 0.01
+            out = qb.qablora_merge_quantize(qw, H, lam, lam, 1.0, qb.MERGE_REQUANT_MINMAX)
+            b, o = qw.c_struct(), out.c_struct()
+            args = (C.byref(b), qb._ptr(H), lam, lam, C.c_float(1.0), qb.MERGE_REQUANT_MINMAX, C.byref(o), qb._stream())
+            s = timed(lambda: qb.lib().qablora_merge_quantize(*args))
+            nbytes = d_out * d_in * (0.5 + 4 / 64 + 4.0 / (lam * lam) + 0.5 + 8 / 64)
+            emit(kernel="merge_requant", shape=[d_out, d_in], lam=lam, us=round(s * 1e6, 1),
+                 GBps=round(nbytes / s / 1e9, 1), frac_hbm=round(nbytes / s / 1e9 / HBM_GBS, 3))
+            del W, qw, H, out
+
+
+def bench_decode():
+    for d_out, d_in in SHAPES:
+        W = torch.randn(d_out, d_in, device=DEV) * 0.02
+        qw = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_MINMAX_INT4, tiled=False)
+        pack = qb.qblora_decode_pack(qw)
+        for T in (1, 4, 16):
+            X = torch.randn(T, d_in, device=DEV).to(torch.bfloat16)
+            Y = torch.empty(T, d_out, dtype=torch.bfloat16, device=DEV)
+            q = qw.c_struct()
+            for name, pk in (("packed", pack), ("row-major", None)):
+                args = (C.byref(q), qb._ptr(pk), qb._ptr(X), T, qb._ptr(Y), None, 0, qb._stream())
+                s = timed(lambda: qb.lib().qblora_linear_decode(*args), iters=50)
+                nbytes = d_out * d_in * (0.5 + 8 / 64) + 2 * T * (d_in + d_out)
+                emit(kernel="w4_decode", layout=name, shape=[d_out, d_in], T=T, us=round(s * 1e6, 1),
+                     GBps=round(nbytes / s / 1e9, 1), frac_hbm=round(nbytes / s / 1e9 / HBM_GBS, 3))
+        del W, qw, pack
+
+
+def bench_qablora():
+    cb = synth.codebook_nf4_style()
+    T, d_out, d_in = 8192, 4096, 4096
+    W = torch.randn(d_out, d_in, device=DEV) * 0.02
+    qw = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_ABSMAX_CODEBOOK, cb)
+    X = torch.randn(T, d_in, device=DEV).to(torch.bfloat16)
+    dY = torch.randn(T, d_out, device=DEV).to(torch.bfloat16)
+    Y = torch.empty_like(dY)
+    dX = torch.empty_like(X)
+    for l1, l2 in ((8, 8), (4, 8), (2, 2)):
+        H = (torch.randn(d_in // l1, d_out // l2, device=DEV) * 0.02).to(torch.bfloat16)
+        dH = torch.empty(d_in // l1, d_out // l2, device=DEV)
+        f = timed(lambda: qb.qablora_linear_fwd(qw, H, l1, l2, 1.0, X, Y), iters=10)
+        b = timed(lambda: qb.qablora_linear_bwd(qw, H, l1, l2, 1.0, X, dY, True, True, dX, dH), iters=10)
+        flops = 4.0 * T * d_in * d_out + 6.0 * T * (d_in // l1) * (d_out // l2)
+        emit(kernel="qablora_fwd+bwd", shape=[d_out, d_in], T=T, lam=[l1, l2], fwd_us=round(f * 1e6, 1),
+             bwd_us=round(b * 1e6, 1), TFLOPs=round(flops / (f + b) / 1e12, 1),
+             frac_mfma=round(flops / (f + b) / 1e12 / MFMA_TFLOPS, 3))
+
+
+def main(argv):
+    qb.lib()
+    torch.cuda.set_device(0)
+    what = argv or ["quantize", "merge", "decode", "qablora"]
+    for w in what:
+        {"quantize": bench_quantize, "merge": bench_merge, "decode": bench_decode, "qablora": bench_qablora}[w]()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main(sys.argv[1:]))
