@@ -5,16 +5,17 @@
 //   beta-shift : blocks lie inside tiles, so delta is constant per block and only beta changes.
 //   requantize : w' = w~ + delta per element, then the min-max quantizer of Eq. 1 per block.
 //
-// Requantize tiling: a workgroup of 1024 threads owns 64 output rows x 256 input columns and every
-// thread owns a quarter (16 elements) of one 64-block; the block minimum and maximum are combined
-// over the four lanes with DPP.  Short threads mean many waves (16 per SIMD over a 4096 x 4096
-// weight, about half of them resident), so loads, arithmetic and stores of different waves overlap;
-// with one thread per block the whole grid was resident at once and went through load, compute and
-// store phases in lockstep.  A thread's global loads (8 bytes of codes, scale, beta) are issued
+// Requantize tiling: a workgroup of 512 threads owns 64 output rows x 256 input columns and every
+// thread owns half (32 elements) of one 64-block; the block minimum and maximum are combined over
+// the two lanes with DPP.  The kernel is bound by vector instructions as much as by HBM: one thread
+// per block (64 elements) keeps the per-thread overhead (addresses, the two divisions of a block)
+// lowest but gives only 4 waves per SIMD over a 4096 x 4096 weight, all resident at once and moving
+// through load, compute and store phases in lockstep; a quarter block per thread overlaps those
+// phases but doubles the overhead per element.  A thread's global loads (16 bytes of codes, scale, beta) are issued
 // before anything else.  Meanwhile the workgroup stages the deltas of its tile in LDS, transposed
 // to [n/lambda2][k/lambda1] so that a thread's deltas are contiguous (H itself is stored with
 // k/lambda1 as the slow index, so the global reads run along n).  When lambda1 divides 64 the run
-// of 16/lambda1 deltas of a quarter is read with 8- or 16-byte LDS loads; the runs of a block are
+// of 32/lambda1 deltas of a half is read with 16-byte LDS loads; the runs of a block are
 // padded by 4 floats so the four blocks of a row start in different banks.
 #include "common.h"
 
@@ -23,7 +24,7 @@ namespace qblora {
 namespace {
 
 constexpr int NT = 64, KT = 256;
-constexpr int kMergeThreads = 1024;           // 64 rows x 16 quarter blocks
+constexpr int kMergeThreads = 512;            // 64 rows x 8 half blocks
 
 struct TileGeom {
     int hrow0, hrows, hcol0, hcols;
@@ -52,14 +53,12 @@ __host__ __device__ inline int delta_stride(int lam1) {
     else return KT / lam1 + 3;
 }
 
-// lanes of a quad (4 consecutive lanes) exchange values: minimum / maximum over the quad
-__device__ __forceinline__ float quad_min(float v) {
-    v = fminf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, false)));
-    return fminf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xf, 0xf, false)));
+// the two lanes of a block (lanes 2i, 2i+1) exchange values: minimum / maximum over the pair
+__device__ __forceinline__ float pair_min(float v) {
+    return fminf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, false)));
 }
-__device__ __forceinline__ float quad_max(float v) {
-    v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, false)));
-    return fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xf, 0xf, false)));
+__device__ __forceinline__ float pair_max(float v) {
+    return fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, false)));
 }
 
 // OUT16: write the shifted weights themselves as bf16 (the 16-bit merge) instead of requantizing them.
@@ -69,18 +68,18 @@ __global__ __launch_bounds__(kMergeThreads) void k_merge_requant(MergeDesc d) {
     extern __shared__ __align__(16) float dl[];          // deltas, [hcols][stride]
     const int t = threadIdx.x;
     const int k0 = blockIdx.x * KT, n0 = blockIdx.y * NT;
-    const int row = t >> 4, bk = (t >> 2) & 3, sub = t & 3;
-    const int n = n0 + row, k = k0 + kBlock * bk + 16 * sub;
-    const bool live = n < d.d_out && k < d.d_in;         // the same for the four lanes of a block
+    const int row = t >> 3, bk = (t >> 1) & 3, sub = t & 1;
+    const int n = n0 + row, k = k0 + kBlock * bk + 32 * sub;
+    const bool live = n < d.d_out && k < d.d_in;         // the same for the two lanes of a block
     const int bpr = d.d_in / kBlock;
 
-    // this thread's quarter block: all global loads first
-    uint2 cq = make_uint2(0, 0);
+    // this thread's half block: all global loads first
+    uint4 cq = make_uint4(0, 0, 0, 0);
     float a = 0.f, b = 0.f;
     int64_t blk = 0;
     if (live) {
         blk = (int64_t)n * bpr + k / kBlock;
-        cq = *reinterpret_cast<const uint2*>(d.codes + ((int64_t)n * d.d_in + k) / 2);
+        cq = *reinterpret_cast<const uint4*>(d.codes + ((int64_t)n * d.d_in + k) / 2);
         if constexpr (GROUPED) a = grouped_scale(d.scale_codes, d.scale_step, d.scale_mid, blk, d.scale_group);
         else a = d.scales[blk];
         if constexpr (BETA) b = d.beta[blk];
@@ -120,45 +119,43 @@ __global__ __launch_bounds__(kMergeThreads) void k_merge_requant(MergeDesc d) {
     __syncthreads();
     if (!live) return;
 
-    // w' = w~ + delta for the 16 elements of the quarter
-    float w[16];
+    // w' = w~ + delta for the 32 elements of the half
+    float w[32];
+    const uint32_t cw[4] = {cq.x, cq.y, cq.z, cq.w};
     const int c = n / d.lam2 - g.hcol0;
     auto element = [&](int j, float de) __attribute__((always_inline)) {
-        const float cv = lut[((j < 8 ? cq.x : cq.y) >> (4 * (j & 7))) & 15];
+        const float cv = lut[(cw[j >> 3] >> (4 * (j & 7))) & 15];
         const float wt = BETA ? __fmaf_rn(cv, a, b) : __fmul_rn(cv, a);
         w[j] = __fadd_rn(wt, de);
     };
     if constexpr (L1 > 0) {
-        constexpr int RUN = 64 / L1, QR = 16 / L1;       // deltas per block / per quarter
+        constexpr int RUN = 64 / L1, QR = 32 / L1;       // deltas per block / per half
         const float* dq = dl + c * stride + bk * (RUN + 4) + sub * QR;
         float de[QR];
-        if constexpr (QR % 4 == 0) {
 #pragma unroll
-            for (int v = 0; v < QR / 4; ++v) {
-                const float4 x = *reinterpret_cast<const float4*>(dq + 4 * v);
-                de[4 * v] = x.x; de[4 * v + 1] = x.y; de[4 * v + 2] = x.z; de[4 * v + 3] = x.w;
-            }
-        } else {
-            const float2 x = *reinterpret_cast<const float2*>(dq);
-            de[0] = x.x; de[1] = x.y;
+        for (int v = 0; v < QR / 4; ++v) {
+            const float4 x = *reinterpret_cast<const float4*>(dq + 4 * v);
+            de[4 * v] = x.x; de[4 * v + 1] = x.y; de[4 * v + 2] = x.z; de[4 * v + 3] = x.w;
         }
 #pragma unroll
-        for (int j = 0; j < 16; ++j) element(j, de[j / L1]);
+        for (int j = 0; j < 32; ++j) element(j, de[j / L1]);
     } else {
         const float* drow = dl + c * stride - g.hrow0;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) element(j, drow[(k + j) / d.lam1]);
+        for (int j = 0; j < 32; ++j) element(j, drow[(k + j) / d.lam1]);
     }
     if constexpr (OUT16) {
         uint4* wp = reinterpret_cast<uint4*>(d.w16_out + (int64_t)n * d.d_in + k);
-        wp[0] = make_uint4(pack_bf16(w[0], w[1]), pack_bf16(w[2], w[3]), pack_bf16(w[4], w[5]), pack_bf16(w[6], w[7]));
-        wp[1] = make_uint4(pack_bf16(w[8], w[9]), pack_bf16(w[10], w[11]), pack_bf16(w[12], w[13]), pack_bf16(w[14], w[15]));
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            wp[v] = make_uint4(pack_bf16(w[8 * v], w[8 * v + 1]), pack_bf16(w[8 * v + 2], w[8 * v + 3]),
+                               pack_bf16(w[8 * v + 4], w[8 * v + 5]), pack_bf16(w[8 * v + 6], w[8 * v + 7]));
         return;
     }
     float lo = w[0], hi = w[0];
 #pragma unroll
-    for (int j = 1; j < 16; ++j) { lo = fminf(lo, w[j]); hi = fmaxf(hi, w[j]); }
-    lo = quad_min(lo); hi = quad_max(hi);                // minimum and maximum are exact: any order
+    for (int j = 1; j < 32; ++j) { lo = fminf(lo, w[j]); hi = fmaxf(hi, w[j]); }
+    lo = pair_min(lo); hi = pair_max(hi);                // minimum and maximum are exact: any order
 
     // min-max INT4 of the block: one division for the scale, one for its reciprocal
     const float range = __fsub_rn(hi, lo);
@@ -169,15 +166,14 @@ __global__ __launch_bounds__(kMergeThreads) void k_merge_requant(MergeDesc d) {
     // constant 0x4B400000.  Eight such words are summed with their nibble shifts (mod 2^32) and the
     // constants' sum, 0x4B400000 * 0x11111111 mod 2^32, is taken off once.
     constexpr uint32_t kMagicSum = (uint32_t)(0x4B400000ull * 0x11111111ull);
-    uint32_t p0 = 0, p1 = 0;
+    uint32_t p[4] = {0, 0, 0, 0};
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const float q0 = __fadd_rn(__fmul_rn(__fsub_rn(w[j], lo), inv), 12582912.0f);
-        const float q1 = __fadd_rn(__fmul_rn(__fsub_rn(w[8 + j], lo), inv), 12582912.0f);
-        p0 += __float_as_uint(q0) << (4 * j);
-        p1 += __float_as_uint(q1) << (4 * j);
+    for (int j = 0; j < 32; ++j) {
+        const float q = __fadd_rn(__fmul_rn(__fsub_rn(w[j], lo), inv), 12582912.0f);
+        p[j >> 3] += __float_as_uint(q) << (4 * (j & 7));
     }
-    *reinterpret_cast<uint2*>(d.codes_out + ((int64_t)n * d.d_in + k) / 2) = make_uint2(p0 - kMagicSum, p1 - kMagicSum);
+    *reinterpret_cast<uint4*>(d.codes_out + ((int64_t)n * d.d_in + k) / 2) =
+        make_uint4(p[0] - kMagicSum, p[1] - kMagicSum, p[2] - kMagicSum, p[3] - kMagicSum);
     if (sub == 0) {
         d.alpha_out[blk] = al;
         d.beta_out[blk] = lo;
