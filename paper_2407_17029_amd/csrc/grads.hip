@@ -362,7 +362,16 @@ __global__ __launch_bounds__(256) void k_grad_reduce(GradDesc d) {
     float sum = 0.0f;
     for (int p = 0; p < d.pool; ++p) {
         const float* src = d.part + (int64_t)(ip * d.pool + p) * d.J + j;
-        for (int z = 0; z < d.splits; ++z) sum += src[z * plane];
+        // eight slices at a time: the loads are independent and issued together, the additions keep
+        // their order
+        for (int z0 = 0; z0 < d.splits; z0 += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = (z0 + u < d.splits) ? src[(int64_t)(z0 + u) * plane] : 0.0f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (z0 + u < d.splits) sum += v[u];
+        }
     }
     sum *= d.out_scale;
     if (d.transpose_out) d.out[(int64_t)j * Ip + ip] = sum;
