@@ -71,6 +71,50 @@ def test_host_validation_rejects_bad_arguments(qb):
     assert L.qablora_merge_quantize(C.byref(qw), None, 2, 2, C.c_float(1.0), 1, C.byref(out), None) == -1
 
 
+def test_host_validation_of_the_later_entry_points(qb):
+    """Single-matrix adapter, 16-bit merge, small-batch inference, saved activations: bad arguments are turned
+    into error codes on the host, before any launch."""
+    L = qb.lib()
+    qw = qb.CQWeight()
+    dummy = C.c_void_p(0x1000)       # never dereferenced
+    qw.d_out, qw.d_in, qw.block = 128, 256, 64
+    qw.codes = qw.scales = 0x1000
+    f = C.c_float(1.0)
+    big = 1 << 30
+    # single-matrix adapter
+    assert L.qablora_linear_fwd(C.byref(qw), None, 2, 2, f, dummy, 4, dummy, dummy, big, None) == -1       # H missing
+    assert L.qablora_linear_fwd(C.byref(qw), dummy, 3, 2, f, dummy, 4, dummy, dummy, big, None) == -2      # 256 % 3
+    assert L.qablora_linear_fwd(C.byref(qw), dummy, 64, 2, f, dummy, 4, dummy, dummy, big, None) == -2     # pooled width 4
+    assert L.qablora_linear_fwd(C.byref(qw), dummy, 2, 2, f, dummy, 4, dummy, None, 0, None) == -4         # workspace
+    assert L.qablora_linear_fwd(C.byref(qw), dummy, 2, 2, f, dummy, 0, dummy, None, 0, None) == 0          # empty batch
+    assert L.qablora_linear_bwd(C.byref(qw), dummy, 2, 2, f, dummy, dummy, 4, None, None, dummy, big, None) == -1
+    assert L.qablora_linear_fwd_workspace_bytes(C.byref(qw), 2, 2, 64) % 256 == 0
+    assert L.qablora_linear_bwd_workspace_bytes(C.byref(qw), 2, 2, 64) > 0
+    # 16-bit merge
+    assert L.qblora_merge_bf16(C.byref(qw), None, 2, 2, f, dummy, None) == -1
+    assert L.qblora_merge_bf16(C.byref(qw), dummy, 2, 2, f, None, None) == -1
+    assert L.qblora_merge_bf16(C.byref(qw), dummy, 5, 2, f, dummy, None) == -2
+    # small-batch inference
+    assert L.qblora_linear_decode(C.byref(qw), None, dummy, 17, dummy, None, 0, None) == -2               # T > 16
+    assert L.qblora_linear_decode(C.byref(qw), None, None, 4, dummy, None, 0, None) == -1
+    assert L.qblora_linear_decode(C.byref(qw), None, dummy, 0, dummy, None, 0, None) == 0
+    assert L.qblora_linear_decode(C.byref(qw), C.c_void_p(0x1010), dummy, 4, dummy, None, 0, None) == -2   # pack alignment
+    assert L.qblora_decode_pack(C.byref(qw), None, None) == -1
+    rows, bpr = 256, 4
+    assert L.qblora_decode_pack_bytes(C.byref(qw)) == rows * bpr * 32 + rows * bpr * 4                    # codes + scales
+    qw.beta = 0x1000
+    assert L.qblora_decode_pack_bytes(C.byref(qw)) == rows * bpr * 32 + 2 * rows * bpr * 4
+    qw.beta = None
+    # saved activations
+    ad = qb.CAdapter()
+    ad.lambda1, ad.lambda2, ad.R, ad.s, ad.A, ad.B = 2, 2, 16, 1.0, 0x1000, 0x1000
+    assert L.qblora_saved_bytes(C.byref(ad), 100) == 2 * 100 * 16 * 2
+    assert L.qblora_saved_bytes(None, 100) == 0
+    assert L.qblora_linear_fwd_save(C.byref(qw), C.byref(ad), dummy, 4, dummy, None, dummy, big, None) == -1
+    assert L.qblora_linear_bwd_saved(C.byref(qw), C.byref(ad), dummy, dummy, 4, None, dummy, dummy, dummy, dummy, big,
+                                     None) == -1
+
+
 def test_workspace_sizes(qb):
     L = qb.lib()
     qw = qb.CQWeight()

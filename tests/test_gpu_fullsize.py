@@ -89,6 +89,12 @@ def test_llama7b_mlp_shapes_reduced_tokens(qb, oracle, codebook):
         _run_layer(qb, oracle, codebook, wl.seed + 1 + i, 768, p.d_out, p.d_in, wl.rank, wl.lam, wl.s, False, 96, True)
 
 
+def test_llama13b_shapes_reduced_tokens(qb, oracle, codebook):
+    wl = synth.WORKLOADS["llama13b_layer"]
+    for i, p in enumerate((wl.projections[0], wl.projections[4])):      # attention [5120x5120] and up [13824x5120]
+        _run_layer(qb, oracle, codebook, wl.seed + 1 + i, 512, p.d_out, p.d_in, wl.rank, wl.lam, wl.s, False, 64, True)
+
+
 def test_llama65b_down_proj_grouped_scales_reduced_tokens(qb, oracle, codebook):
     wl = synth.WORKLOADS["llama65b_layer"]
     p = wl.projections[6]                                                # down_proj [8192 x 22016]
