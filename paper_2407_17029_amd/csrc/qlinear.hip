@@ -15,15 +15,17 @@
 // output row n using row n/lambda2, i.e. repeat_interleave; backward: X2 = dU/lambda1, W2 = A with
 // row k/lambda1).
 //
-// Shape of the computation on a CU: one workgroup of 256 threads (4 wave64, one per SIMD) owns a
-// 256 x 256 output tile; every wave owns a 128 x 128 quadrant, i.e. 16 MFMA accumulators of
-// 32 x 32 (256 registers), so one k-step of 64 issues 64 MFMAs against 32 16-byte LDS fragment
-// reads per wave.  Both operand tiles live in LDS as [row][64 k] bf16 (128 bytes per row) with the
-// 16-byte chunks of a row XOR-swizzled by (row ^ row>>3) & 7, double buffered, one barrier per
-// k-step.  Activation tiles (and the bf16 tiles of segment 2) go from global memory directly into
-// LDS (global_load_lds, 16 bytes per lane; the swizzle is applied by choosing which global chunk a
-// lane fetches).  Codes and scales are fetched two k-steps ahead into registers and dequantized
-// between the MFMAs of the step before they are needed.
+// Shape of the computation on a CU: one workgroup of 512 threads (8 wave64, two per SIMD) owns a
+// 256 x 256 output tile; a wave owns 128 tokens x 64 features = 8 MFMA accumulators of 32 x 32
+// (128 registers).  Two waves per SIMD matter: a single wave cannot issue MFMAs back to back at the
+// full rate of the matrix pipe, and the dequantization arithmetic of one wave issues in the shadow
+// of the other wave's MFMAs.  Both operand tiles live in LDS as [row][64 k] bf16 (128 bytes per
+// row) with the 16-byte chunks of a row XOR-swizzled by (row ^ row>>3) & 7, double buffered, one
+// barrier per k-step.  Activation tiles (and both bf16 tiles of segment 2) go from global memory
+// directly into LDS (global_load_lds, 16 bytes per lane; the swizzle is applied by choosing which
+// global chunk a lane fetches).  Codes and scales are fetched two k-steps ahead into registers and
+// dequantized between the MFMAs of the step before they are needed, through a byte-indexed table
+// in LDS that turns one byte of codes into two fp32 code values.
 // The weight tile is the MFMA A operand and the token tile the B operand, so a lane ends up with 4
 // consecutive output features of one token and stores them as one 8-byte word.
 #include "common.h"
@@ -32,7 +34,7 @@ namespace qblora {
 
 namespace {
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 512;
 constexpr int BM = 256, BN = 256, kBK = 64;
 constexpr int kTileBytes = 256 * 128;                       // one operand tile: 256 rows x 128 bytes
 constexpr int kTableBytes = 256 * 128;                      // byte-indexed pair table, 16 replicas
@@ -43,10 +45,10 @@ __device__ __forceinline__ int swz(int row, int chunk) {
     return row * 128 + (((chunk ^ row ^ (row >> 3)) & 7) << 4);
 }
 
-// One wave-wide global -> LDS copy: lane i fetches the 16 bytes at base + offset_i and they land at
-// lds_base + 16*i (M0 carries the wave-uniform LDS byte address).  Written as assembly so that the
-// compiler's wait-count bookkeeping does not tie later LDS accesses to these copies; every copy is
-// completed by the explicit vmcnt(0) in front of the barrier that publishes the tile.
+// One wave-wide global -> LDS copy: lane i fetches 16 bytes and they land at lds_base + 16*i (M0
+// carries the wave-uniform LDS byte address).  Written as assembly so that the compiler's wait-count
+// bookkeeping does not tie later LDS accesses to these copies; every copy is completed by the
+// explicit vmcnt(0) in front of the barrier that publishes the tile.
 __device__ __forceinline__ void copy16_to_lds(const void* src, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                  :: "s"(lds_base), "v"(src) : "memory");
@@ -60,16 +62,18 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
     return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
 }
 
-// codes / scales of one k-step held in registers
+// codes / scales of one k-step held in registers: 32 weights per thread
+//   QMODE 1: half a stored row (16 bytes of codes), one scale
+//   QMODE 2: a patch of 4 stored rows x 8 columns (one dword per row), a scale per row
 template <int QMODE>
 struct Staged {
-    uint32_t cw[8];          // QMODE 1: the 64 codes of this thread's row; QMODE 2: 8 codes of each of 8 rows
-    float sc[QMODE == 2 ? 8 : 1];
-    float be[QMODE == 2 ? 8 : 1];
+    uint32_t cw[4];
+    float sc[QMODE == 2 ? 4 : 1];
+    float be[QMODE == 2 ? 4 : 1];
 };
 
 template <int QMODE, bool BETA>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_qlinear(GemmDesc d) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_qlinear(GemmDesc d) {
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* sX = smem;                                   // 2 tiles
     unsigned char* sW = sX + 2 * kTileBytes;                    // 2 tiles
@@ -90,7 +94,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     const float out_scale = d.out_scale;
 
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int wm0 = (wave & 1) * 128, wn0 = (wave >> 1) * 128;
+    const int wm0 = (wave & 1) * 128, wn0 = (wave >> 1) * 64;
 
     // ---- tile assignment: XCD-contiguous, grouped along tokens ---------------------------------
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (N + BN - 1) / BN;
@@ -107,16 +111,17 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 
     // Pair table: a byte of codes (two adjacent k, low nibble first) selects the 8-byte entry
     // (c[lo], c[hi]) -- one LDS read dequantizes two weights.  The 256 entries are replicated 16 times,
-    // entry b of replica q at b*128 + q*8, and lane l reads replica l & 15: whatever the bytes are, the
-    // 16 lanes the LDS serves together touch 16 different bank pairs.
+    // entry b of replica q at b*128 + q*8, and lane l reads replica l & 15, so that lanes of one
+    // 16-lane group never collide whatever their bytes are.
     if (t < 16) reinterpret_cast<float*>(sT)[t] = d.cb.c[t];
     __syncthreads();
     {
-        const float c_lo = reinterpret_cast<const float*>(sT)[t & 15], c_hi = reinterpret_cast<const float*>(sT)[t >> 4];
+        const int b = t & 255;
+        const float c_lo = reinterpret_cast<const float*>(sT)[b & 15], c_hi = reinterpret_cast<const float*>(sT)[b >> 4];
         __syncthreads();
         const float4 e = make_float4(c_lo, c_hi, c_lo, c_hi);
 #pragma unroll
-        for (int q = 0; q < 8; ++q) *reinterpret_cast<float4*>(sT + t * 128 + q * 16) = e;
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<float4*>(sT + b * 128 + (t >> 8) * 64 + q * 16) = e;
     }
 
     const int K1 = QMODE == 1 ? d_in : d_out;
@@ -124,57 +129,71 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     const int nsteps = steps1 + steps2;
     const int bpr = d_in / kBlock;                // blocks per stored weight row
 
-    f32x16 acc[4][4];
+    f32x16 acc[2][4];                             // [feature block][token block]
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
 
     // ---- direct global -> LDS copies -------------------------------------------------------------
-    // Wave w fills rows 64w .. 64w+63 of a tile with 8 copies of 8 rows each.  In copy i, lane l
-    // lands on row 64w + 8i + (l>>3), physical chunk l&7, which must hold logical chunk
-    // (l&7) ^ swizzle(row); with row&7 = l>>3 and (row>>3)&7 = i that is (l&7) ^ (l>>3) ^ i.
+    // Wave w fills rows 32w .. 32w+31 of a tile with 4 copies of 8 rows each.  In copy i, lane l
+    // lands on row 32w + 8i + (l>>3), physical chunk l&7, which must hold logical chunk
+    // (l&7) ^ swizzle(row); with row&7 = l>>3 and (row>>3)&7 = (4w+i)&7 that is (l&7) ^ (l>>3) ^ (4w+i).
     const int crow = lane >> 3;
-    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem) + wave * 64 * 128);
-    // CHECK_K: chunks at or beyond K are fetched from a zero constant instead (K-extension only)
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem) + wave * 32 * 128);
+    // check_k: chunks at or beyond K are fetched from a zero constant instead (K-extension only)
     auto copy_tile = [&](const bool check_k, const qblora_bf16* src, int64_t ld, int64_t row_base, int64_t row_max,
                          int div, int K, int k0, uint32_t tile_off) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            int64_t row = row_base + wave * 64 + i * 8 + crow;
+        for (int i = 0; i < 4; ++i) {
+            int64_t row = row_base + wave * 32 + i * 8 + crow;
             row = row > row_max ? row_max : row;
             if (div != 1) row = (int64_t)((uint32_t)row / (uint32_t)div);      // only weight rows (< 2^31) are divided
-            const int k = k0 + (((lane & 7) ^ crow ^ i) << 3);
+            const int k = k0 + (((lane & 7) ^ crow ^ ((4 * wave + i) & 7)) << 3);
             const qblora_bf16* p = src + row * ld + k;
             if (check_k)
                 p = (k < K) ? p : reinterpret_cast<const qblora_bf16*>(g_zero_chunk);
             copy16_to_lds(p, lds0 + tile_off + i * 8 * 128);
         }
     };
+    // Segment-1 activation tiles: per-lane byte offsets relative to the tile's first row are fixed for
+    // the whole kernel, the uniform base walks along k.
+    uint32_t xoff[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int64_t lrow = wave * 32 + i * 8 + crow;
+        if (m0 + lrow > M - 1) lrow = M - 1 - m0;
+        xoff[i] = (uint32_t)(lrow * ldx1 * 2) + (((lane & 7) ^ crow ^ ((4 * wave + i) & 7)) << 4);
+    }
+    const qblora_bf16* const x1_tile = X1 + m0 * ldx1;
+    auto issue_x1 = [&](int step, int buf) __attribute__((always_inline)) {
+        const qblora_bf16* base = x1_tile + step * kBK;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) copy16_to_lds(base, xoff[i], lds0 + buf * kTileBytes + i * 8 * 128);
+    };
+    auto issue_copies = [&](int step, int buf) __attribute__((always_inline)) {
+        if (step < steps1) {
+            issue_x1(step, buf);
+        } else {
+            const int k0 = (step - steps1) * kBK;
+            copy_tile(true, X2, ldx2, m0, M - 1, 1, K2, k0, buf * kTileBytes);
+            copy_tile(true, W2, ldw2, n0, N - 1, div2, K2, k0, (2 + buf) * kTileBytes);
+        }
+    };
 
     // ---- codes / scales -> registers -------------------------------------------------------------
     int qrow = 0, qcol = 0;
-    const uint8_t* fwd_codes = nullptr;              // QMODE 1: this thread's 32 bytes of step 0 ...
-    int fwd_stride = 32;                             // ... and the distance to the next step's
-    const float* fwd_scales = nullptr;               // likewise for its block scale
-    int fwd_scale_stride = 1;
+    const uint8_t* fwd_codes = nullptr; int fwd_stride = 32;
+    const float* fwd_scales = nullptr; int fwd_scale_stride = 1;
     if constexpr (QMODE == 1) {
-        qrow = n0 + t;                               // this thread's stored weight row
+        qrow = n0 + (t >> 1);                        // this thread's stored weight row (it owns half of it)
         if (qrow > N - 1) qrow = N - 1;
-        if (d.codes_tiled) {                         // tile-ordered copy: the workgroup's step is one 8 KiB block
-            fwd_codes = d.codes_tiled + tiled_run_offset(n0 + t, 0, bpr);
-            fwd_stride = 256 * 32;
-        } else {
-            fwd_codes = codes + (int64_t)qrow * (d_in / 2);
-        }
-        if (d.scales_tiled) {
-            fwd_scales = d.scales_tiled + tiled_run_offset(n0 + t, 0, bpr) / 32;
-            fwd_scale_stride = 256;
-        } else {
-            fwd_scales = scales + (int64_t)qrow * bpr;
-        }
+        if (d.codes_tiled) { fwd_codes = d.codes_tiled + tiled_run_offset(n0 + (t >> 1), 0, bpr) + (t & 1) * 16; fwd_stride = 256 * 32; }
+        else fwd_codes = codes + (int64_t)qrow * (d_in / 2) + (t & 1) * 16;
+        if (d.scales_tiled) { fwd_scales = d.scales_tiled + tiled_run_offset(n0 + (t >> 1), 0, bpr) / 32; fwd_scale_stride = 256; }
+        else fwd_scales = scales + (int64_t)qrow * bpr;
     } else {
         qcol = n0 + 8 * (t & 31);                    // this thread's 8 stored columns (k of the layer)
         if (qcol > N - 8) qcol = N - 8;
@@ -182,16 +201,14 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     auto load_staged = [&](Staged<QMODE>& s, int step) __attribute__((always_inline)) {
         const int k0 = step * kBK;
         if constexpr (QMODE == 1) {
-            const uint4* p = reinterpret_cast<const uint4*>(fwd_codes + (int64_t)step * fwd_stride);
-            uint4 v0 = p[0], v1 = p[1];
-            s.cw[0] = v0.x; s.cw[1] = v0.y; s.cw[2] = v0.z; s.cw[3] = v0.w;
-            s.cw[4] = v1.x; s.cw[5] = v1.y; s.cw[6] = v1.z; s.cw[7] = v1.w;
+            const uint4 v = *reinterpret_cast<const uint4*>(fwd_codes + (int64_t)step * fwd_stride);
+            s.cw[0] = v.x; s.cw[1] = v.y; s.cw[2] = v.z; s.cw[3] = v.w;
             s.sc[0] = fwd_scales[(int64_t)step * fwd_scale_stride];
             if constexpr (BETA) s.be[0] = beta[(int64_t)qrow * bpr + step];
         } else {
-            const int nb = k0 + 8 * (t >> 5);        // 8 stored rows (contraction index)
+            const int nb = k0 + 4 * (t >> 5);        // 4 stored rows (contraction index)
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < 4; ++i) {
                 const int64_t n = nb + i;
                 s.cw[i] = *reinterpret_cast<const uint32_t*>(codes + n * (d_in / 2) + qcol / 2);
                 const int64_t blk = n * bpr + qcol / kBlock;
@@ -201,61 +218,17 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         }
     };
 
-    // Segment-1 activation tiles: per-lane byte offsets relative to the tile's first row are fixed for
-    // the whole kernel, the uniform base walks along k.
-    uint32_t xoff[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        int64_t lrow = wave * 64 + i * 8 + crow;
-        if (m0 + lrow > M - 1) lrow = M - 1 - m0;
-        xoff[i] = (uint32_t)(lrow * ldx1 * 2) + ((((lane & 7) ^ crow ^ i)) << 4);
-    }
-    const qblora_bf16* const x1_tile = X1 + m0 * ldx1;
-    // Copies of a quantized step's token tile in two halves of 4, and all copies of any step.
-    auto issue_x1_half = [&](int step, int buf, int half) __attribute__((always_inline)) {
-        const qblora_bf16* base = x1_tile + step * kBK;
-#pragma unroll
-        for (int i = 4 * half; i < 4 * half + 4; ++i)
-            copy16_to_lds(base, xoff[i], lds0 + buf * kTileBytes + i * 8 * 128);
-    };
-    auto issue_copies = [&](int step, int buf) __attribute__((always_inline)) {
-        if (step < steps1) {
-            issue_x1_half(step, buf, 0);
-            issue_x1_half(step, buf, 1);
-        } else {
-            const int k0 = (step - steps1) * kBK;
-            copy_tile(true, X2, ldx2, m0, M - 1, 1, K2, k0, buf * kTileBytes);
-            copy_tile(true, W2, ldw2, n0, N - 1, div2, K2, k0, (2 + buf) * kTileBytes);
-        }
-    };
-
-    // ---- one k-step ----------------------------------------------------------------------------------
-    // A wave runs alone on its SIMD, so nothing hides an LDS round trip or a barrier but its own
-    // MFMAs.  The 64 MFMAs of a step are cut into 8 slices of 8 (about 256 cycles each) and all other
-    // work is pinned to slices (plan at run_step): fragments and table values are read two slices
-    // before their use; the barrier that publishes the next tiles sits in front of slice 6, so the
-    // last 16 MFMAs of a step cover it and the first fragment reads of the next step.
-    // Scheduling barriers keep work inside its slice; group barriers spread it between the MFMAs.
-    const int r = lane & 31, hi = lane >> 5;
-    bf16x8 wf[2][4], xf[2][4];      // two fragment sets; set 0 holds quarter 0 when a step starts
-    auto read_wf = [&](const unsigned char* bw, int ks, bf16x8 (&f)[4]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int a = 0; a < 4; ++a) f[a] = *reinterpret_cast<const bf16x8*>(bw + swz(wn0 + a * 32 + r, ks * 2 + hi));
-    };
-    auto read_xf = [&](const unsigned char* bx, int ks, bf16x8 (&f)[4]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int b = 0; b < 4; ++b) f[b] = *reinterpret_cast<const bf16x8*>(bx + swz(wm0 + b * 32 + r, ks * 2 + hi));
-    };
-    // Dequantization of a staged k-step in 4 pieces of 16 elements (two 16-byte LDS stores each):
-    //   QMODE 1: piece q = dwords 2q, 2q+1 of this thread's row (8 bytes of codes) -> chunks 2q, 2q+1 of LDS row t;
-    //   QMODE 2: piece q = byte q (columns 2q, 2q+1) of each of the 8 stored rows of this thread's 8x8
-    //            patch -> LDS rows 8*kg+2q and 8*kg+2q+1, chunk ng (packing down the columns transposes).
+    // ---- dequantization of a staged k-step: 2 pieces of 16 weights (8 table reads) per thread -------
+    //   QMODE 1: piece p = dwords 2p, 2p+1 of this thread's half row -> chunks 4*half+2p, +1 of LDS row t>>1;
+    //   QMODE 2: piece p = bytes 2p, 2p+1 (columns 4p..4p+3) of each of the 4 stored rows of the patch
+    //            -> 8-byte halves of LDS rows 8*kg+4p .. +3 (packing down the columns transposes).
     const uint32_t table_lane = lds_address(sT) - lds_address(smem) + ((lane & 15) << 3);
-    auto table_offsets = [&](const Staged<QMODE>& s, int q, uint32_t (&li)[8]) __attribute__((always_inline)) {
+    auto table_offsets = [&](const Staged<QMODE>& s, int p, uint32_t (&li)[8]) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const uint32_t w = QMODE == 1 ? s.cw[2 * q + (i >> 2)] : s.cw[i];
-            const int byte = QMODE == 1 ? (i & 3) : q;
+            // QMODE 1: i = 4*(dword in piece) + byte;  QMODE 2: i = 4*(byte in piece) + row
+            const uint32_t w = QMODE == 1 ? s.cw[2 * p + (i >> 2)] : s.cw[i & 3];
+            const int byte = QMODE == 1 ? (i & 3) : (2 * p + (i >> 2));
             const uint32_t sh = byte == 0 ? (w << 7) : (w >> (8 * byte - 7));
             li[i] = (sh & 0x7f80u) | table_lane;
         }
@@ -264,12 +237,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
         for (int i = 0; i < 8; ++i) lv[i] = *reinterpret_cast<const float2*>(smem + li[i]);
     };
-    auto finish_piece = [&](const Staged<QMODE>& s, int q, const float2 (&lv)[8], unsigned char* tile)
+    auto finish_piece = [&](const Staged<QMODE>& s, int p, const float2 (&lv)[8], unsigned char* tile)
         __attribute__((always_inline)) {
         float lo[8], hi[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int si = QMODE == 1 ? 0 : i;
+            const int si = QMODE == 1 ? 0 : (i & 3);
             lo[i] = BETA ? __fmaf_rn(lv[i].x, s.sc[si], s.be[si]) : __fmul_rn(lv[i].x, s.sc[si]);
             hi[i] = BETA ? __fmaf_rn(lv[i].y, s.sc[si], s.be[si]) : __fmul_rn(lv[i].y, s.sc[si]);
         }
@@ -280,87 +253,90 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             o0.z = pack_bf16(lo[2], hi[2]); o0.w = pack_bf16(lo[3], hi[3]);
             o1.x = pack_bf16(lo[4], hi[4]); o1.y = pack_bf16(lo[5], hi[5]);
             o1.z = pack_bf16(lo[6], hi[6]); o1.w = pack_bf16(lo[7], hi[7]);
-            *reinterpret_cast<uint4*>(tile + swz(t, 2 * q)) = o0;
-            *reinterpret_cast<uint4*>(tile + swz(t, 2 * q + 1)) = o1;
+            const int chunk = 4 * (t & 1) + 2 * p;
+            *reinterpret_cast<uint4*>(tile + swz(t >> 1, chunk)) = o0;
+            *reinterpret_cast<uint4*>(tile + swz(t >> 1, chunk + 1)) = o1;
         } else {
-            // lo[i] / hi[i] are columns 2q / 2q+1 of stored row i: pack down each column
-            uint4 o0, o1;
-            o0.x = pack_bf16(lo[0], lo[1]); o0.y = pack_bf16(lo[2], lo[3]);
-            o0.z = pack_bf16(lo[4], lo[5]); o0.w = pack_bf16(lo[6], lo[7]);
-            o1.x = pack_bf16(hi[0], hi[1]); o1.y = pack_bf16(hi[2], hi[3]);
-            o1.z = pack_bf16(hi[4], hi[5]); o1.w = pack_bf16(hi[6], hi[7]);
-            *reinterpret_cast<uint4*>(tile + swz(8 * (t & 31) + 2 * q, t >> 5)) = o0;
-            *reinterpret_cast<uint4*>(tile + swz(8 * (t & 31) + 2 * q + 1, t >> 5)) = o1;
+            // lv[4*j + i] is (column 4p+2j, column 4p+2j+1) of stored row i: pack down each column
+            const int kg = t & 31, ng = t >> 5;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                uint2 c0, c1;
+                c0.x = pack_bf16(lo[4 * j + 0], lo[4 * j + 1]); c0.y = pack_bf16(lo[4 * j + 2], lo[4 * j + 3]);
+                c1.x = pack_bf16(hi[4 * j + 0], hi[4 * j + 1]); c1.y = pack_bf16(hi[4 * j + 2], hi[4 * j + 3]);
+                const int row = 8 * kg + 4 * p + 2 * j;
+                *reinterpret_cast<uint2*>(tile + swz(row, ng >> 1) + 8 * (ng & 1)) = c0;
+                *reinterpret_cast<uint2*>(tile + swz(row + 1, ng >> 1) + 8 * (ng & 1)) = c1;
+            }
         }
     };
     auto dequant_store = [&](const Staged<QMODE>& s, unsigned char* tile) __attribute__((always_inline)) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int p = 0; p < 2; ++p) {
             uint32_t li[8];
             float2 lv[8];
-            table_offsets(s, q, li);
+            table_offsets(s, p, li);
             table_reads(li, lv);
-            finish_piece(s, q, lv, tile);
+            finish_piece(s, p, lv, tile);
         }
     };
-    auto mfma_row = [&](int a, const bf16x8 (&fw)[4], const bf16x8 (&fx)[4]) __attribute__((always_inline)) {
+
+    // ---- one k-step ----------------------------------------------------------------------------------
+    // Four quarters of 8 MFMAs (one 16-wide slice of k each).  Fragments of quarter q+1 are read during
+    // quarter q (two fragment sets); the dequantization of the next weight tile is spread over the
+    // first three quarters (table reads one quarter before the values are scaled and stored); the
+    // barrier that publishes the next tiles sits in front of the last quarter, whose MFMAs cover it and
+    // the first fragment reads of the next step.
+    const int r = lane & 31, hi = lane >> 5;
+    bf16x8 wf[2][2], xf[2][4];      // two fragment sets; set 0 holds quarter 0 when a step starts
+    // Fragment addresses: row base + 32a + r, chunk 2ks + hi sits at (base + r)*128 + 4096a +
+    // 16*[(hi ^ r ^ r>>3) & 7 ^ (2ks ^ 4(a&1))] -- one per-lane value XOR a constant plus an immediate;
+    // the empty asm in run_step keeps the variants from being hoisted and held in registers.
+    uint32_t frag_w = (uint32_t)(sW - smem) + (uint32_t)((wn0 + r) * 128 + (((hi ^ r ^ (r >> 3)) & 7) << 4));
+    uint32_t frag_x = (uint32_t)(sX - smem) + (uint32_t)((wm0 + r) * 128 + (((hi ^ r ^ (r >> 3)) & 7) << 4));
+    auto read_frags = [&](const unsigned char* bx, const unsigned char* bw, int ks, bf16x8 (&fw)[2], bf16x8 (&fx)[4])
+        __attribute__((always_inline)) {
+        const uint32_t wo = (uint32_t)(bw - sW), xo = (uint32_t)(bx - sX);
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+            fw[a] = *reinterpret_cast<const bf16x8*>(smem + (((frag_w + wo) ^ (uint32_t)(((2 * ks) ^ (4 * (a & 1))) << 4)) + a * 4096));
 #pragma unroll
         for (int b = 0; b < 4; ++b)
-            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[a], fx[b], acc[a][b], 0, 0, 0);
+            fx[b] = *reinterpret_cast<const bf16x8*>(smem + (((frag_x + xo) ^ (uint32_t)(((2 * ks) ^ (4 * (b & 1))) << 4)) + b * 4096));
     };
     // dq: dequantize `sdq` into bw_next during this step; has_next: a step follows (its tiles are in
     // bx_next / bw_next once the barrier is passed).  Both are literal `true` in the steady state.
-    //
-    // Slice plan (8 MFMAs per slice; fragment set = quarter & 1; every LDS read two slices before use):
-    //   0: table reads of piece 0, fragments of quarter 1, offsets of piece 1
-    //   1: table reads of piece 1, offsets of piece 2
-    //   2: table reads of piece 2, fragments of quarter 2, finish piece 0, offsets of piece 3
-    //   3: table reads of piece 3, finish piece 1
-    //   4: fragments of quarter 3, finish piece 2
-    //   5: finish piece 3
-    //   6: wait for the copies, barrier, fragments of quarter 0 of the next step; with `refill`, first
-    //      half of the token-tile copies of quantized step `step2` (the step after next) into the
-    //      buffer this step has just finished reading
-    //   7: second half of those copies
     auto run_step = [&](const unsigned char* bx, const unsigned char* bw, const unsigned char* bx_next,
                         unsigned char* bw_next, const bool dq, const Staged<QMODE>& sdq, const bool has_next,
                         const bool refill, const int step2, const int buf2) __attribute__((always_inline)) {
-        float2 lv[3][8];
-        uint32_t li[3][8];
-        if (dq) table_offsets(sdq, 0, li[0]);
+        float2 lv[2][8];
+        uint32_t li[8];
+        asm volatile("" : "+v"(frag_w), "+v"(frag_x));
+        if (dq) {
+            table_offsets(sdq, 0, li);
+            table_reads(li, lv[0]);
+            table_offsets(sdq, 1, li);
+        }
 #pragma unroll
-        for (int h = 0; h < 8; ++h) {
-            const int ks = h >> 1, half = h & 1, cur = ks & 1, nxt = cur ^ 1;
-            if (h == 6 && has_next) {
+        for (int ks = 0; ks < 4; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks == 3 && has_next) {
                 __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): direct copies and staged codes
                 __syncthreads();                           // next tiles published; this step's tiles free
-                read_wf(bw_next, 0, wf[0]);
-                read_xf(bx_next, 0, xf[0]);
-                if (refill) issue_x1_half(step2, buf2, 0);  // this step's token buffer is free: refill it
-                __builtin_amdgcn_sched_barrier(0);
+                read_frags(bx_next, bw_next, 0, wf[0], xf[0]);
+                if (refill) issue_x1(step2, buf2);         // this step's token buffer is free: refill it
             }
-            if (h == 7 && has_next && refill) issue_x1_half(step2, buf2, 1);
+            if (ks < 3) read_frags(bx, bw, ks + 1, wf[nxt], xf[nxt]);
             if (dq) {
-                if (h >= 2 && h <= 5) finish_piece(sdq, h - 2, lv[(h - 2) % 3], bw_next);
-                if (h <= 3) table_reads(li[h % 3], lv[h % 3]);
-                if (h == 0) table_offsets(sdq, 1, li[1]);
-                if (h == 1) { table_offsets(sdq, 2, li[2]); table_offsets(sdq, 3, li[0]); }
+                if (ks == 0) table_reads(li, lv[1]);
+                if (ks == 1) finish_piece(sdq, 0, lv[0], bw_next);
+                if (ks == 2) finish_piece(sdq, 1, lv[1], bw_next);
             }
-            if (half == 0 && ks < 3) {
-                read_wf(bw, ks + 1, wf[nxt]);
-                read_xf(bx, ks + 1, xf[nxt]);
-            }
-            mfma_row(2 * half, wf[cur], xf[cur]);
-            mfma_row(2 * half + 1, wf[cur], xf[cur]);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                   // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);                   // vector ALU
-                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                   // LDS reads
-                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);                   // vector ALU
-                if (i == 3 || i == 7) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // a piece's LDS stores
-            }
-            __builtin_amdgcn_sched_barrier(0);
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][a], xf[cur][b], acc[a][b], 0, 0, 0);
         }
     };
 
@@ -378,15 +354,14 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         if (steps1 > 0) dequant_store(st[0], sW);
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
-        read_wf(sW, 0, wf[0]);
-        read_xf(sX, 0, xf[0]);
+        read_frags(sX, sW, 0, wf[0], xf[0]);
         int s = 0;
         // Quantized steps whose successor is quantized too (the successor's tile is dequantized during
         // the step), unrolled by two so that the staging registers and the tile buffers have fixed
         // names.  Codes are fetched two steps ahead; past the end the last quantized step is fetched
         // again (in bounds, unused) so that the body has no conditions.  A step refills its own token
         // buffer with the copies of the step after next (when that is a quantized step) behind its
-        // barrier, under its last 16 MFMAs.
+        // barrier, under its last 8 MFMAs.
         const int last_q = steps1 - 1;
         for (; s + 2 < steps1; s += 2) {
             load_staged(st[0], min(s + 2, last_q));
@@ -415,15 +390,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 
     // ---- epilogue ---------------------------------------------------------------------------------------
     // A lane holds features n..n+3 of one token per accumulator quad, i.e. 8 bytes of an output row.
-    // The wave first lays its 128 x 128 quadrant out in LDS (the tiles are dead by now) as bf16 rows of
-    // 256 bytes (pitch 272), then reads it back 16 bytes per lane so that every global store
-    // instruction writes four complete 256-byte row segments.
+    // The wave first lays its 128 x 64 quadrant out in LDS (the tiles are dead by now) as bf16 rows of
+    // 128 bytes (pitch 144), then reads it back 16 bytes per lane so that every global store
+    // instruction writes eight complete 128-byte row segments.
     __syncthreads();                                       // every wave is done reading the tiles
     {
-        constexpr int kPitch = 272;
+        constexpr int kPitch = 144;
         unsigned char* eb = smem + wave * (128 * kPitch);
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
+        for (int a = 0; a < 2; ++a)
 #pragma unroll
             for (int b = 0; b < 4; ++b)
 #pragma unroll
@@ -433,11 +408,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
                     o.y = pack_bf16(acc[a][b][q * 4 + 2] * out_scale, acc[a][b][q * 4 + 3] * out_scale);
                     *reinterpret_cast<uint2*>(eb + (b * 32 + r) * kPitch + (a * 32 + q * 8 + hi * 4) * 2) = o;
                 }
-        const int erow = lane >> 4, echunk = lane & 15;
+        const int erow = lane >> 3, echunk = lane & 7;
         const int n = n0 + wn0 + echunk * 8;
 #pragma unroll 8
-        for (int i = 0; i < 32; ++i) {
-            const int row = i * 4 + erow;
+        for (int i = 0; i < 16; ++i) {
+            const int row = i * 8 + erow;
             const uint4 v = *reinterpret_cast<const uint4*>(eb + row * kPitch + echunk * 16);
             const int64_t m = m0 + wm0 + row;
             if (m < M && n < N) *reinterpret_cast<uint4*>(C + m * ldc + n) = v;
