@@ -2,7 +2,8 @@
 //
 // Both quantizers are HBM-streaming kernels: a thread owns 4 consecutive fp32 weights (one
 // 16-byte load), 16 lanes own one 64-wide block and reduce its absmax / min / max with
-// cross-lane shuffles, every thread stores its 4 codes as one 16-bit word.  All decision
+// cross-lane shuffles; the codes of a workgroup are gathered in LDS and stored 16 bytes per
+// thread.  All decision
 // arithmetic is written with explicit single-rounding intrinsics so that no FMA contraction
 // can change a code.
 #include "common.h"
@@ -10,8 +11,6 @@
 namespace qblora {
 
 namespace {
-
-constexpr int kUnroll = 4;      // float4 loads per thread of the quantizers
 
 struct Midpoints {
     float m[15];   // (c_j + c_{j+1}) * 0.5 in fp32, computed on the host
@@ -41,28 +40,64 @@ __device__ __forceinline__ float group16_min(float v) {
     return v;
 }
 
-// Absmax / codebook quantizer.  n_vec = number of float4 groups = d_out*d_in/4 (a multiple of 16).
-// byte offset, in the tiled code copy, of the two code bytes of float4 group `idx`
-__device__ __forceinline__ int64_t tiled_pair_offset(int64_t idx, int bpr) {
-    const int64_t blk = idx >> 4;                         // 16 groups per 64-block
-    const int64_t n = blk / bpr, b = blk - n * bpr;
-    return tiled_run_offset(n, b, bpr) + 2 * (idx & 15);
+// Work split of both quantizers: a workgroup owns 4 consecutive weight rows x 16 consecutive 64-blocks
+// (4 x 4 KB of contiguous fp32 input).  Pass u of a thread takes float4 group t of row u, so 16 lanes
+// hold one block.  Codes (2 bytes per thread and pass) and block scales are collected in LDS and leave
+// as 16-byte stores: 512 contiguous bytes per row in the canonical layout, and -- because the 4 rows
+// are neighbours inside one 256-row tile -- 128 contiguous bytes per block column in the tile-ordered
+// copy.
+constexpr int kQRows = 4, kQBlocks = 16;
+
+struct QuantTile {
+    int row0, blk0, jt;
+};
+
+__device__ __forceinline__ QuantTile quant_tile(int bpr) {
+    const int ntj = (bpr + kQBlocks - 1) / kQBlocks;
+    QuantTile q;
+    q.jt = blockIdx.x % ntj;
+    q.row0 = (blockIdx.x / ntj) * kQRows;
+    q.blk0 = q.jt * kQBlocks;
+    return q;
 }
 
-__global__ __launch_bounds__(256) void k_quantize_codebook(const float4* __restrict__ W, int64_t n_vec,
-                                                           Midpoints mp, uint16_t* __restrict__ codes16,
-                                                           uint8_t* __restrict__ tiled, int bpr,
-                                                           float* __restrict__ absmax) {
+// codes of the tile from LDS (cs[u][t] = 4 codes of float4 group t of row u) to both global layouts
+__device__ __forceinline__ void store_tile_codes(const uint16_t (&cs)[kQRows][256], const QuantTile& q, int d_out, int bpr,
+                                                 uint8_t* __restrict__ codes, uint8_t* __restrict__ tiled) {
+    const int t = threadIdx.x;
+    if (t < 128) {
+        const int u = t >> 5, piece = t & 31;                 // 16-byte piece of the row's 512 bytes
+        const int row = q.row0 + u, blk = q.blk0 + (piece >> 1);
+        if (row < d_out && blk < bpr)
+            *reinterpret_cast<uint4*>(codes + ((int64_t)row * bpr + blk) * 32 + (piece & 1) * 16) =
+                *reinterpret_cast<const uint4*>(&cs[u][piece * 8]);
+    } else if (tiled) {
+        const int tt = t - 128, b = tt >> 3, u = (tt >> 1) & 3, half = tt & 1;
+        const int row = q.row0 + u, blk = q.blk0 + b;
+        if (row < d_out && blk < bpr)
+            *reinterpret_cast<uint4*>(tiled + tiled_run_offset(row, blk, bpr) + half * 16) =
+                *reinterpret_cast<const uint4*>(&cs[u][b * 16 + half * 8]);
+    }
+}
+
+// Absmax / codebook quantizer.
+__global__ __launch_bounds__(256) void k_quantize_codebook(const float4* __restrict__ W, int d_out, int bpr,
+                                                           Midpoints mp, uint8_t* __restrict__ codes,
+                                                           uint8_t* __restrict__ tiled, float* __restrict__ absmax) {
+    __shared__ __align__(16) uint16_t cs[kQRows][256];
+    __shared__ float as[kQRows][kQBlocks];
+    const QuantTile q = quant_tile(bpr);
+    const int t = threadIdx.x;
+    const bool col_ok = q.blk0 + (t >> 4) < bpr;
     // four independent 16-byte loads per thread are issued before any arithmetic (bytes in flight)
-    int64_t idx[kUnroll];
-    float4 wv[kUnroll];
+    float4 wv[kQRows];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-        idx[u] = ((int64_t)blockIdx.x * kUnroll + u) * 256 + threadIdx.x;
-        wv[u] = idx[u] < n_vec ? W[idx[u]] : make_float4(0.f, 0.f, 0.f, 0.f);   // whole 16-lane groups are in or out
+    for (int u = 0; u < kQRows; ++u) {
+        const int row = q.row0 + u;
+        wv[u] = (col_ok && row < d_out) ? W[((int64_t)row * bpr + q.blk0) * 16 + t] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
+    for (int u = 0; u < kQRows; ++u) {
         const float4 w = wv[u];
         float a = fmaxf(fmaxf(fabsf(w.x), fabsf(w.y)), fmaxf(fabsf(w.z), fabsf(w.w)));
         a = group16_max(a);
@@ -86,29 +121,34 @@ __global__ __launch_bounds__(256) void k_quantize_codebook(const float4* __restr
             return (b3 ? 8u : 0u) + (b2 ? 4u : 0u) + (b1 ? 2u : 0u) + (b0 ? 1u : 0u);
         };
         const uint32_t c0 = code_of(w.x), c1 = code_of(w.y), c2 = code_of(w.z), c3 = code_of(w.w);
-        if (idx[u] < n_vec) {
-            const uint16_t packed = (uint16_t)(c0 | (c1 << 4) | (c2 << 8) | (c3 << 12));
-            codes16[idx[u]] = packed;
-            if (tiled) *reinterpret_cast<uint16_t*>(tiled + tiled_pair_offset(idx[u], bpr)) = packed;
-            if ((threadIdx.x & 15) == 0) absmax[idx[u] >> 4] = a;
-        }
+        cs[u][t] = (uint16_t)(c0 | (c1 << 4) | (c2 << 8) | (c3 << 12));
+        if ((t & 15) == 0) as[u][t >> 4] = a;
+    }
+    __syncthreads();
+    store_tile_codes(cs, q, d_out, bpr, codes, tiled);
+    if (t < kQRows * kQBlocks) {
+        const int row = q.row0 + (t >> 4), blk = q.blk0 + (t & 15);
+        if (row < d_out && blk < bpr) absmax[(int64_t)row * bpr + blk] = as[t >> 4][t & 15];
     }
 }
 
 // Min-max INT4 quantizer: alpha = (hi-lo)/15, beta = lo, code = rint((w-lo) * (15/(hi-lo))).
-__global__ __launch_bounds__(256) void k_quantize_minmax(const float4* __restrict__ W, int64_t n_vec,
-                                                         uint16_t* __restrict__ codes16,
-                                                         uint8_t* __restrict__ tiled, int bpr,
+__global__ __launch_bounds__(256) void k_quantize_minmax(const float4* __restrict__ W, int d_out, int bpr,
+                                                         uint8_t* __restrict__ codes, uint8_t* __restrict__ tiled,
                                                          float* __restrict__ alpha, float* __restrict__ beta) {
-    int64_t idx[kUnroll];
-    float4 wv[kUnroll];
+    __shared__ __align__(16) uint16_t cs[kQRows][256];
+    __shared__ float as[kQRows][kQBlocks], bs[kQRows][kQBlocks];
+    const QuantTile q = quant_tile(bpr);
+    const int t = threadIdx.x;
+    const bool col_ok = q.blk0 + (t >> 4) < bpr;
+    float4 wv[kQRows];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-        idx[u] = ((int64_t)blockIdx.x * kUnroll + u) * 256 + threadIdx.x;
-        wv[u] = idx[u] < n_vec ? W[idx[u]] : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int u = 0; u < kQRows; ++u) {
+        const int row = q.row0 + u;
+        wv[u] = (col_ok && row < d_out) ? W[((int64_t)row * bpr + q.blk0) * 16 + t] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
+    for (int u = 0; u < kQRows; ++u) {
         const float4 w = wv[u];
         const float lo = group16_min(fminf(fminf(w.x, w.y), fminf(w.z, w.w)));
         const float hi = group16_max(fmaxf(fmaxf(w.x, w.y), fmaxf(w.z, w.w)));
@@ -127,13 +167,16 @@ __global__ __launch_bounds__(256) void k_quantize_minmax(const float4* __restric
             q3 = fminf(fmaxf(q3, 0.0f), 15.0f);
             packed = (uint32_t)q0 | ((uint32_t)q1 << 4) | ((uint32_t)q2 << 8) | ((uint32_t)q3 << 12);
         }
-        if (idx[u] < n_vec) {
-            codes16[idx[u]] = (uint16_t)packed;
-            if (tiled) *reinterpret_cast<uint16_t*>(tiled + tiled_pair_offset(idx[u], bpr)) = (uint16_t)packed;
-            if ((threadIdx.x & 15) == 0) {
-                alpha[idx[u] >> 4] = al;
-                beta[idx[u] >> 4] = lo;
-            }
+        cs[u][t] = (uint16_t)packed;
+        if ((t & 15) == 0) { as[u][t >> 4] = al; bs[u][t >> 4] = lo; }
+    }
+    __syncthreads();
+    store_tile_codes(cs, q, d_out, bpr, codes, tiled);
+    if (t < kQRows * kQBlocks) {
+        const int row = q.row0 + (t >> 4), blk = q.blk0 + (t & 15);
+        if (row < d_out && blk < bpr) {
+            alpha[(int64_t)row * bpr + blk] = as[t >> 4][t & 15];
+            beta[(int64_t)row * bpr + blk] = bs[t >> 4][t & 15];
         }
     }
 }
@@ -262,19 +305,19 @@ int launch_quantize_codebook(const float* W, int d_out, int d_in, const Codebook
         volatile float m = sum * 0.5f;
         mp.m[j] = m;
     }
-    int64_t n_vec = (int64_t)d_out * d_in / 4;
-    unsigned grid = (unsigned)((n_vec + 256 * kUnroll - 1) / (256 * kUnroll));
+    const int bpr = d_in / kBlock;
+    const unsigned grid = (unsigned)(((bpr + kQBlocks - 1) / kQBlocks) * ((d_out + kQRows - 1) / kQRows));
     hipLaunchKernelGGL(k_quantize_codebook, dim3(grid), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
-                       n_vec, mp, reinterpret_cast<uint16_t*>(codes), tiled, d_in / kBlock, absmax);
+                       d_out, bpr, mp, codes, tiled, absmax);
     return launch_status();
 }
 
 int launch_quantize_minmax(const float* W, int d_out, int d_in, uint8_t* codes, uint8_t* tiled, float* alpha,
                            float* beta, hipStream_t st) {
-    int64_t n_vec = (int64_t)d_out * d_in / 4;
-    unsigned grid = (unsigned)((n_vec + 256 * kUnroll - 1) / (256 * kUnroll));
+    const int bpr = d_in / kBlock;
+    const unsigned grid = (unsigned)(((bpr + kQBlocks - 1) / kQBlocks) * ((d_out + kQRows - 1) / kQRows));
     hipLaunchKernelGGL(k_quantize_minmax, dim3(grid), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
-                       n_vec, reinterpret_cast<uint16_t*>(codes), tiled, d_in / kBlock, alpha, beta);
+                       d_out, bpr, codes, tiled, alpha, beta);
     return launch_status();
 }
 
