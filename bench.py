@@ -28,7 +28,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the forward GEMM from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see the
 # profiles/ summaries); None until measured for the workload.
-MEASURED_TRAFFIC_BYTES = {"llama7b_attn": int((208.9 + 64.0) * 2**20)}   # profiles/bench_llama7b_attn.md
+MEASURED_TRAFFIC_BYTES = {"llama7b_attn": int((209.3 + 65.0) * 2**20)}   # profiles/bench_llama7b_attn.md
 
 
 def main() -> int:
