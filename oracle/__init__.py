@@ -167,6 +167,41 @@ def backward(Wt, X, dY, A, B, lam1, lam2, s, compute_dx=True, compute_dab=True, 
     return dX, dA, dB
 
 
+OP_AVGPOOL_REPEAT, OP_TRUNCATE_PAD0, OP_SAMPLE_ZEROFILL = 0, 1, 2
+
+
+def forward_op(Wt, X, A, B, lam1, lam2, s, op):
+    """Adapted forward with one of the scale-operator pairs of the ablation (op 0 is the default pair)."""
+    Wt = _c(Wt, np.float64); X = _c(X, np.uint16); A = _c(A, np.uint16); B = _c(B, np.uint16)
+    d_out, d_in = Wt.shape
+    T, R = X.shape[0], A.shape[1]
+    assert X.shape[1] == d_in and d_in % lam1 == 0 and d_out % lam2 == 0 and op in (0, 1, 2)
+    assert A.shape == (d_in // lam1, R) and B.shape == (R, d_out // lam2)
+    Y = np.zeros((T, d_out), np.float64)
+    lib().oracle_forward_op(_p(Wt), i64(d_out), i64(d_in), _p(X), i64(T), _p(A), _p(B), i64(R), C.c_int(lam1),
+                            C.c_int(lam2), C.c_int(op), C.c_double(s), _p(Y))
+    return Y
+
+
+def backward_op(Wt, X, dY, A, B, lam1, lam2, s, op, compute_dx=True, compute_dab=True, d_out=None, d_in=None):
+    X = _c(X, np.uint16); dY = _c(dY, np.uint16); A = _c(A, np.uint16); B = _c(B, np.uint16)
+    if Wt is None:
+        assert not compute_dx and d_out is not None and d_in is not None
+    else:
+        Wt = _c(Wt, np.float64)
+        d_out, d_in = Wt.shape
+    T, R = X.shape[0], A.shape[1]
+    assert X.shape == (T, d_in) and dY.shape == (T, d_out) and op in (0, 1, 2)
+    assert A.shape == (d_in // lam1, R) and B.shape == (R, d_out // lam2)
+    dX = np.zeros((T, d_in), np.float64) if compute_dx else None
+    dA = np.zeros(A.shape, np.float64) if compute_dab else None
+    dB = np.zeros(B.shape, np.float64) if compute_dab else None
+    lib().oracle_backward_op(_p(Wt), i64(d_out), i64(d_in), _p(X), _p(dY), i64(T), _p(A), _p(B), i64(R),
+                             C.c_int(lam1), C.c_int(lam2), C.c_int(op), C.c_double(s), C.c_int(int(compute_dx)),
+                             _p(dX), _p(dA), _p(dB))
+    return dX, dA, dB
+
+
 def qa_forward(Wt, X, H, lam1, lam2, s):
     """Single-matrix adapter (QA-BLoRA): H is bf16 bits [d_in/lam1, d_out/lam2]."""
     Wt = _c(Wt, np.float64); X = _c(X, np.uint16); H = _c(H, np.uint16)

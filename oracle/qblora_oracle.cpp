@@ -30,7 +30,9 @@
 // special cases, central finite differences, adjoint identity, merge
 // invariants, E4M3 round trips; the single-matrix (QA-BLoRA) layer against the
 // dense delta weight, against the two-matrix layer with A = identity and by
-// finite differences.  No function here is unpinned.
+// finite differences; the alternative scale operators against dense operator
+// matrices, against the default layer (op 0, lambda = 1) and by finite
+// differences.  No function here is unpinned.
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
@@ -402,6 +404,163 @@ void oracle_backward(const double* Wt, int64_t d_out, int64_t d_in, const uint16
                 }
                 for (int64_t k = 0; k < d_in; ++k) dx[k] += dP[k / lam1] / (double)lam1;
             }
+        }
+    });
+}
+
+// ---------------------------------------------------------------------------
+// The adapted layer with the alternative non-parametric scale operators of the
+// ablation (Sec. 4.3 "The scale operators", Table 6).  The compress operator C
+// maps the d_in input features to d_in/lam1, the expand operator E maps the
+// d_out/lam2 adapter outputs to d_out features:
+//   op 0  AvgPool & repeat_interleave (Sec. 3.2):  P[m] = mean_i x[lam1*m+i];
+//         the expanded output at n is V[n / lam2]
+//   op 1  truncation & supplement_0:  P[m] = x[m] (the front part is kept);
+//         the expanded output at n is V[n] for n < d_out/lam2 and 0 behind it
+//   op 2  interval_sampling & interpolation with zeros:  P[m] = x[lam1*m];
+//         the expanded output at n is V[n / lam2] where lam2 divides n, else 0
+//   Y[t,n] = sum_k X[t,k] Wt[n,k] + s * E(C(x) A B)[n]
+// The backward applies the transposed operators: dV = s * E^T(G),
+// dB = U^T dV, dU = dV B^T, dA = P^T dU, dX = G Wt + C^T(dU A^T).
+// ---------------------------------------------------------------------------
+static void compress_row(const double* x, int64_t dp, int lam1, int op, double* P) {
+    for (int64_t m = 0; m < dp; ++m) {
+        if (op == 0) {
+            double acc = 0.0;
+            for (int i = 0; i < lam1; ++i) acc += x[lam1 * m + i];
+            P[m] = acc / (double)lam1;
+        } else if (op == 1) {
+            P[m] = x[m];
+        } else {
+            P[m] = x[(int64_t)lam1 * m];
+        }
+    }
+}
+
+// y[n] += scale * E(V)[n]
+static void expand_add_row(const double* V, int64_t dq, int64_t d_out, int lam2, int op, double scale, double* y) {
+    for (int64_t n = 0; n < d_out; ++n) {
+        if (op == 0) y[n] += scale * V[n / lam2];
+        else if (op == 1) { if (n < dq) y[n] += scale * V[n]; }
+        else { if (n % lam2 == 0) y[n] += scale * V[n / lam2]; }
+    }
+}
+
+// dV[j] = scale * E^T(g)[j]
+static void expand_transposed_row(const double* g, int64_t dq, int lam2, int op, double scale, double* dV) {
+    for (int64_t j = 0; j < dq; ++j) {
+        if (op == 0) {
+            double acc = 0.0;
+            for (int i = 0; i < lam2; ++i) acc += g[lam2 * j + i];
+            dV[j] = scale * acc;
+        } else if (op == 1) {
+            dV[j] = scale * g[j];
+        } else {
+            dV[j] = scale * g[(int64_t)lam2 * j];
+        }
+    }
+}
+
+// dx[k] += C^T(dP)[k]
+static void compress_transposed_add_row(const double* dP, int64_t dp, int64_t d_in, int lam1, int op, double* dx) {
+    for (int64_t k = 0; k < d_in; ++k) {
+        if (op == 0) dx[k] += dP[k / lam1] / (double)lam1;
+        else if (op == 1) { if (k < dp) dx[k] += dP[k]; }
+        else { if (k % lam1 == 0) dx[k] += dP[k / lam1]; }
+    }
+}
+
+void oracle_forward_op(const double* Wt, int64_t d_out, int64_t d_in, const uint16_t* X, int64_t T,
+                       const uint16_t* A, const uint16_t* B, int64_t R, int lam1, int lam2, int op, double s,
+                       double* Y) {
+    const int64_t dp = d_in / lam1, dq = d_out / lam2;
+    parallel_rows(T, [&](int64_t t0, int64_t t1) {
+        std::vector<double> x(d_in), P(dp), U(R), V(dq);
+        for (int64_t t = t0; t < t1; ++t) {
+            for (int64_t k = 0; k < d_in; ++k) x[k] = bf16_to_f64(X[t * d_in + k]);
+            compress_row(x.data(), dp, lam1, op, P.data());
+            for (int64_t r = 0; r < R; ++r) {
+                double acc = 0.0;
+                for (int64_t m = 0; m < dp; ++m) acc += P[m] * bf16_to_f64(A[m * R + r]);
+                U[r] = acc;
+            }
+            for (int64_t j = 0; j < dq; ++j) {
+                double acc = 0.0;
+                for (int64_t r = 0; r < R; ++r) acc += U[r] * bf16_to_f64(B[r * dq + j]);
+                V[j] = acc;
+            }
+            double* y = Y + t * d_out;
+            for (int64_t n = 0; n < d_out; ++n) {
+                const double* w = Wt + n * d_in;
+                double acc = 0.0;
+                for (int64_t k = 0; k < d_in; ++k) acc += x[k] * w[k];
+                y[n] = acc;
+            }
+            expand_add_row(V.data(), dq, d_out, lam2, op, s, y);
+        }
+    });
+}
+
+// Wt may be NULL when compute_dx == 0; dA/dB are skipped when dA == NULL.
+void oracle_backward_op(const double* Wt, int64_t d_out, int64_t d_in, const uint16_t* X, const uint16_t* dY,
+                        int64_t T, const uint16_t* A, const uint16_t* B, int64_t R, int lam1, int lam2, int op,
+                        double s, int compute_dx, double* dX, double* dA, double* dB) {
+    const int64_t dp = d_in / lam1, dq = d_out / lam2;
+    std::vector<double> P(T * dp), U(T * R), dV(T * dq), dU(T * R);
+    parallel_rows(T, [&](int64_t t0, int64_t t1) {
+        std::vector<double> x(d_in), g(d_out);
+        for (int64_t t = t0; t < t1; ++t) {
+            for (int64_t k = 0; k < d_in; ++k) x[k] = bf16_to_f64(X[t * d_in + k]);
+            for (int64_t n = 0; n < d_out; ++n) g[n] = bf16_to_f64(dY[t * d_out + n]);
+            compress_row(x.data(), dp, lam1, op, &P[t * dp]);
+            for (int64_t r = 0; r < R; ++r) {
+                double acc = 0.0;
+                for (int64_t m = 0; m < dp; ++m) acc += P[t * dp + m] * bf16_to_f64(A[m * R + r]);
+                U[t * R + r] = acc;
+            }
+            expand_transposed_row(g.data(), dq, lam2, op, s, &dV[t * dq]);
+            for (int64_t r = 0; r < R; ++r) {
+                double acc = 0.0;
+                for (int64_t j = 0; j < dq; ++j) acc += dV[t * dq + j] * bf16_to_f64(B[r * dq + j]);
+                dU[t * R + r] = acc;
+            }
+        }
+    });
+    if (dA) {
+        parallel_rows(dp, [&](int64_t m0, int64_t m1) {
+            for (int64_t m = m0; m < m1; ++m)
+                for (int64_t r = 0; r < R; ++r) {
+                    double acc = 0.0;
+                    for (int64_t t = 0; t < T; ++t) acc += P[t * dp + m] * dU[t * R + r];
+                    dA[m * R + r] = acc;
+                }
+        });
+        parallel_rows(R, [&](int64_t r0, int64_t r1) {
+            for (int64_t r = r0; r < r1; ++r)
+                for (int64_t j = 0; j < dq; ++j) {
+                    double acc = 0.0;
+                    for (int64_t t = 0; t < T; ++t) acc += U[t * R + r] * dV[t * dq + j];
+                    dB[r * dq + j] = acc;
+                }
+        });
+    }
+    if (!compute_dx) return;
+    parallel_rows(T, [&](int64_t t0, int64_t t1) {
+        std::vector<double> dP(dp);
+        for (int64_t t = t0; t < t1; ++t) {
+            double* dx = dX + t * d_in;
+            for (int64_t k = 0; k < d_in; ++k) dx[k] = 0.0;
+            for (int64_t n = 0; n < d_out; ++n) {
+                const double gn = bf16_to_f64(dY[t * d_out + n]);
+                const double* w = Wt + n * d_in;
+                for (int64_t k = 0; k < d_in; ++k) dx[k] += gn * w[k];
+            }
+            for (int64_t m = 0; m < dp; ++m) {
+                double acc = 0.0;
+                for (int64_t r = 0; r < R; ++r) acc += dU[t * R + r] * bf16_to_f64(A[m * R + r]);
+                dP[m] = acc;
+            }
+            compress_transposed_add_row(dP.data(), dp, d_in, lam1, op, dx);
         }
     });
 }

@@ -265,3 +265,105 @@ def test_qa_backward_adjoint_and_finite_differences(oracle, lam1, lam2):
     # dH only, without the base weight
     _, dH2 = oracle.qa_backward(None, L.X, L.dY, H, lam1, lam2, s, compute_dx=False, d_out=d_out, d_in=d_in)
     assert np.array_equal(dH, dH2)
+
+
+# ---- alternative scale operators (ablation "The scale operators", Table 6) ---------------------------
+
+def _operator_matrices(d_in, d_out, lam1, lam2, op):
+    """Dense compress matrix C [d_in/lam1, d_in] and expand matrix E [d_out, d_out/lam2], written from the
+    operators' descriptions: 0 average pool / repeat, 1 keep the front part / pad zeros behind,
+    2 every lam-th value / zeros in between."""
+    dp, dq = d_in // lam1, d_out // lam2
+    C = np.zeros((dp, d_in)); E = np.zeros((d_out, dq))
+    if op == 0:
+        for m in range(dp): C[m, lam1 * m:lam1 * (m + 1)] = 1.0 / lam1
+        for n in range(d_out): E[n, n // lam2] = 1.0
+    elif op == 1:
+        for m in range(dp): C[m, m] = 1.0
+        for j in range(dq): E[j, j] = 1.0
+    else:
+        for m in range(dp): C[m, lam1 * m] = 1.0
+        for j in range(dq): E[lam2 * j, j] = 1.0
+    return C, E
+
+
+def _dense_forward_op(Wt, X, A, B, C, E, s):
+    return X @ Wt.T + s * (X @ C.T @ A @ B @ E.T)
+
+
+@pytest.mark.parametrize("op", [0, 1, 2])
+@pytest.mark.parametrize("lam1,lam2", [(2, 2), (4, 8)])
+def test_scale_operators_equal_dense_operator_matrices(oracle, op, lam1, lam2):
+    T, d_out, d_in, R = 5, 48, 64, 6
+    L, Wt = _case(31 + op, T, d_out, d_in, R, lam1, lam2)
+    s = 0.75
+    X = bf16_exact(L.X); A = bf16_exact(L.A); B = bf16_exact(L.B); G = bf16_exact(L.dY)
+    C, E = _operator_matrices(d_in, d_out, lam1, lam2, op)
+    Y = oracle.forward_op(Wt, L.X, L.A, L.B, lam1, lam2, s, op)
+    assert np.allclose(Y, _dense_forward_op(Wt, X, A, B, C, E, s), atol=1e-12 * np.abs(Y).max())
+    dX, dA, dB = oracle.backward_op(Wt, L.X, L.dY, L.A, L.B, lam1, lam2, s, op)
+    # matrix calculus on the dense form
+    P = X @ C.T; U = P @ A; dV = s * (G @ E); dU = dV @ B.T
+    assert np.allclose(dX, G @ Wt + dU @ A.T @ C, atol=1e-12 * np.abs(dX).max())
+    assert np.allclose(dA, P.T @ dU, atol=1e-12 * np.abs(dA).max())
+    assert np.allclose(dB, U.T @ dV, atol=1e-12 * np.abs(dB).max())
+
+
+def test_scale_operator_zero_is_the_default_layer(oracle):
+    lam1, lam2, s = 2, 4, 1.5
+    L, Wt = _case(35, 4, 32, 48, 6, lam1, lam2)
+    assert np.array_equal(oracle.forward_op(Wt, L.X, L.A, L.B, lam1, lam2, s, 0),
+                          oracle.forward(Wt, L.X, L.A, L.B, lam1, lam2, s))
+    for got, want in zip(oracle.backward_op(Wt, L.X, L.dY, L.A, L.B, lam1, lam2, s, 0),
+                         oracle.backward(Wt, L.X, L.dY, L.A, L.B, lam1, lam2, s)):
+        assert np.allclose(got, want, rtol=1e-13, atol=1e-15)
+
+
+def test_scale_operators_coincide_at_lambda_one(oracle):
+    L, Wt = _case(36, 3, 16, 24, 4, 1, 1)
+    ref = oracle.forward(Wt, L.X, L.A, L.B, 1, 1, 0.5)
+    for op in (1, 2):
+        assert np.allclose(oracle.forward_op(Wt, L.X, L.A, L.B, 1, 1, 0.5, op), ref, rtol=1e-14, atol=1e-16)
+
+
+def test_scale_operators_discard_what_the_descriptions_say(oracle):
+    """Truncation ignores every input feature behind the front part and writes nothing behind the front part
+    of the output; sampling ignores the features between the samples and writes zeros between them."""
+    lam1, lam2, s = 4, 2, 1.0
+    T, d_out, d_in, R = 3, 16, 32, 4
+    L, _ = _case(37, T, d_out, d_in, R, lam1, lam2, b_std=0.5)
+    Wt = np.zeros((d_out, d_in))
+    X2 = L.X.copy()
+    for op, kept_in, written_out in ((1, np.arange(d_in) < d_in // lam1, np.arange(d_out) < d_out // lam2),
+                                     (2, np.arange(d_in) % lam1 == 0, np.arange(d_out) % lam2 == 0)):
+        Y = oracle.forward_op(Wt, L.X, L.A, L.B, lam1, lam2, s, op)
+        assert np.all(Y[:, ~written_out] == 0.0) and np.any(Y[:, written_out] != 0.0)
+        X2[:] = L.X
+        X2[:, ~kept_in] = synth.f32_to_bf16_bits(np.full((T, int((~kept_in).sum())), 3.0, np.float32))
+        assert np.array_equal(oracle.forward_op(Wt, X2, L.A, L.B, lam1, lam2, s, op), Y)
+
+
+@pytest.mark.parametrize("op", [1, 2])
+def test_scale_operator_backward_finite_differences(oracle, op):
+    lam1, lam2, s = 2, 4, 1.25
+    T, d_out, d_in, R = 3, 16, 16, 4
+    L, Wt = _case(38 + op, T, d_out, d_in, R, lam1, lam2, b_std=0.5)
+    dX, dA, dB = oracle.backward_op(Wt, L.X, L.dY, L.A, L.B, lam1, lam2, s, op)
+    G = bf16_exact(L.dY); X = bf16_exact(L.X); A = bf16_exact(L.A); B = bf16_exact(L.B)
+    C, E = _operator_matrices(d_in, d_out, lam1, lam2, op)
+    loss = lambda x, a, b: float((G * _dense_forward_op(Wt, x, a, b, C, E, s)).sum())
+    h = 1e-6
+
+    def fd(arr, which):
+        g = np.zeros_like(arr)
+        for idx in np.ndindex(arr.shape):
+            p = arr.copy(); m = arr.copy()
+            p[idx] += h; m[idx] -= h
+            args_p = {"x": X, "a": A, "b": B}; args_m = dict(args_p)
+            args_p[which] = p; args_m[which] = m
+            g[idx] = (loss(**args_p) - loss(**args_m)) / (2 * h)
+        return g
+
+    assert np.allclose(dX, fd(X, "x"), rtol=1e-6, atol=1e-7)
+    assert np.allclose(dA, fd(A, "a"), rtol=1e-6, atol=1e-7)
+    assert np.allclose(dB, fd(B, "b"), rtol=1e-6, atol=1e-7)
