@@ -211,6 +211,34 @@ def main() -> int:
             "achieved": round(qa_flops / (qa_ms * 1e-3) / 1e12, 2),
             "frac_of_bf16_mfma_peak": round(qa_flops / (qa_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}}
 
+    if not args.no_next_rows:
+        # The ablation's alternative scale operators on the same layer: forward + backward (dX, dA, dB) with the
+        # activation kept in between, as in the timed step (no merge: their delta weight is not tile-constant).
+        op_rows = {}
+        for name, op in (("truncate_pad0", qb.OP_TRUNCATE_PAD0), ("sample_zerofill", qb.OP_SAMPLE_ZEROFILL)):
+            ad_op = qb.Adapter(ad.A, ad.B, lam, lam, wl.s, scale_op=op)
+            nb_op = max(qb.qblora_linear_fwd_workspace_bytes(qw, ad_op, T), qb.qblora_linear_bwd_workspace_bytes(qw, ad_op, T))
+            ws_op = torch.empty(int(nb_op) + 256, dtype=torch.uint8, device=dev)
+
+            def op_step():
+                qb.qblora_linear_fwd(qw, ad_op, X, Y, ws_op, saved=saved)
+                qb.qblora_linear_bwd(qw, ad_op, X, dY, True, True, dX, dA, dB, ws_op, saved=saved)
+
+            for _ in range(3):
+                op_step()
+            torch.cuda.synchronize()
+            q0 = time.perf_counter()
+            for _ in range(side_steps):
+                op_step()
+            torch.cuda.synchronize()
+            op_ms = (time.perf_counter() - q0) * 1e3 / side_steps
+            op_flops = 4.0 * T * d_in * d_out + 6.0 * T * wl.rank * (d_in + d_out)
+            op_rows[name] = {"ms_per_step": round(op_ms, 4), "unit": "TFLOP/s",
+                             "achieved": round(op_flops / (op_ms * 1e-3) / 1e12, 2),
+                             "frac_of_bf16_mfma_peak": round(op_flops / (op_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+            del ws_op
+        out["next_rows"]["scale_operators_fwd_bwd"] = op_rows
+
     if not args.no_cpu_baseline:
         import oracle
         ts = min(args.cpu_sample_tokens, T)

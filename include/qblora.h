@@ -104,7 +104,26 @@ typedef struct qblora_adapter {
     float s;
     const qblora_bf16* A;
     const qblora_bf16* B;
+    int32_t scale_op;     /* QBLORA_OP_*; 0 = the method's AvgPool & repeat_interleave */
 } qblora_adapter;
+
+/*
+ * Non-parametric scale operators around the adapter (Sec. 4.3 "The scale operators", Table 6).
+ * With C the compress operator on the d_in input features and E the expand operator on the
+ * d_out/lambda2 adapter outputs, the adapter term is s * E((C(x) A) B):
+ *   QBLORA_OP_AVGPOOL_REPEAT   C(x)[m] = mean_i x[lambda1*m+i];  E(v)[n] = v[n / lambda2]   (Sec. 3.2)
+ *   QBLORA_OP_TRUNCATE_PAD0    C(x)[m] = x[m] (front part kept); E(v)[n] = v[n] for n < d_out/lambda2, else 0
+ *   QBLORA_OP_SAMPLE_ZEROFILL  C(x)[m] = x[lambda1*m];           E(v)[n] = v[n / lambda2] where lambda2 | n, else 0
+ * The backward applies the transposed operators.  The two alternatives are the ablation's variants:
+ * qblora_linear_fwd / _bwd (and their _save / _saved forms) take them; they additionally need
+ * (d_in/lambda1) % 8 == 0 and (d_out/lambda2) % 8 == 0.  Their delta weight is not constant on
+ * (lambda1 x lambda2) tiles, so qblora_tile_product and the merges refuse them (QBLORA_ERR_UNSUPPORTED).
+ */
+enum {
+    QBLORA_OP_AVGPOOL_REPEAT = 0,
+    QBLORA_OP_TRUNCATE_PAD0 = 1,
+    QBLORA_OP_SAMPLE_ZEROFILL = 2
+};
 
 /*
  * Block-wise quantization of an fp32 weight (Eq. 1; Sec. 3.1 for the min-max and absmax

@@ -20,6 +20,7 @@ OK = 0
 QUANT_ABSMAX_CODEBOOK, QUANT_MINMAX_INT4 = 0, 1
 SCALES_FP32, SCALES_E4M3_GROUPED = 0, 1
 MERGE_BETA_SHIFT, MERGE_REQUANT_MINMAX = 0, 1
+OP_AVGPOOL_REPEAT, OP_TRUNCATE_PAD0, OP_SAMPLE_ZEROFILL = 0, 1, 2
 
 EXPORTS = ["qblora_quantize_blockwise", "qblora_dequantize_bf16", "qblora_linear_fwd_workspace_bytes",
            "qblora_linear_bwd_workspace_bytes", "qblora_linear_fwd", "qblora_linear_bwd",
@@ -43,7 +44,7 @@ class CQWeight(C.Structure):
 
 class CAdapter(C.Structure):
     _fields_ = [("lambda1", C.c_int32), ("lambda2", C.c_int32), ("R", C.c_int32), ("s", C.c_float),
-                ("A", C.c_void_p), ("B", C.c_void_p)]
+                ("A", C.c_void_p), ("B", C.c_void_p), ("scale_op", C.c_int32)]
 
 
 class QBLoRAError(RuntimeError):
@@ -173,13 +174,15 @@ class QWeight:
 class Adapter:
     """Balanced adapter of Sec. 3.2: A bf16 [d_in/lambda1, R], B bf16 [R, d_out/lambda2], scaling s."""
 
-    def __init__(self, A, B, lambda1, lambda2, s):
+    def __init__(self, A, B, lambda1, lambda2, s, scale_op=0):
         self.A, self.B, self.lambda1, self.lambda2, self.s = A, B, int(lambda1), int(lambda2), float(s)
         self.R = 0 if A is None else int(A.shape[1])
+        self.scale_op = int(scale_op)        # OP_*: the scale operators of the ablation (Sec. 4.3)
 
     def c_struct(self) -> CAdapter:
         a = CAdapter()
         a.lambda1, a.lambda2, a.R, a.s = self.lambda1, self.lambda2, self.R, self.s
+        a.scale_op = self.scale_op
         a.A = None if self.A is None else self.A.data_ptr()
         a.B = None if self.B is None else self.B.data_ptr()
         return a

@@ -24,6 +24,9 @@ struct Carver {
 };
 
 bool has_adapter(const qblora_adapter* ad) { return ad && ad->A && ad->B && ad->R > 0; }
+int scale_op_of(const qblora_adapter* ad) { return has_adapter(ad) ? ad->scale_op : QBLORA_OP_AVGPOOL_REPEAT; }
+// index map of an expanded operand for the compress / expand operator `op`
+int op_map(int op) { return op == QBLORA_OP_TRUNCATE_PAD0 ? MAP_FRONT : op == QBLORA_OP_SAMPLE_ZEROFILL ? MAP_STRIDE : MAP_DIV; }
 
 int check_qweight(const qblora_qweight* qw, bool need_codes) {
     if (!qw) return QBLORA_ERR_NULL;
@@ -53,6 +56,11 @@ int check_layer(const qblora_qweight* qw, const qblora_adapter* ad) {
         if (has_adapter(ad)) {
             if (qw->d_in % ad->lambda1 != 0 || qw->d_out % ad->lambda2 != 0) return QBLORA_ERR_SHAPE;
             if (ad->R % 8 != 0) return QBLORA_ERR_SHAPE;
+            if (ad->scale_op < QBLORA_OP_AVGPOOL_REPEAT || ad->scale_op > QBLORA_OP_SAMPLE_ZEROFILL)
+                return QBLORA_ERR_UNSUPPORTED;
+            if (ad->scale_op != QBLORA_OP_AVGPOOL_REPEAT &&
+                ((qw->d_in / ad->lambda1) % 8 != 0 || (qw->d_out / ad->lambda2) % 8 != 0))
+                return QBLORA_ERR_SHAPE;
         } else if (ad->R > 0) {
             return QBLORA_ERR_NULL;                         // a rank was given but a matrix is missing
         }
@@ -78,7 +86,9 @@ FwdSpace carve_fwd(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T
     s.scales = c.take<float>((size_t)((qw->d_out + 255) / 256) * 256 * (qw->d_in / qw->block));   // tile-ordered
     if (has_adapter(ad)) {
         s.At_x = c.take<qblora_bf16>((size_t)ad->R * qw->d_in);
-        s.Bt = c.take<qblora_bf16>((size_t)(qw->d_out / ad->lambda2) * ad->R);
+        // the alternative scale operators use a full [d_out, R] expansion (zero rows included)
+        const size_t bt_rows = scale_op_of(ad) ? (size_t)qw->d_out : (size_t)(qw->d_out / ad->lambda2);
+        s.Bt = c.take<qblora_bf16>(bt_rows * ad->R);
         s.U = c.take<qblora_bf16>((size_t)T * ad->R);
     }
     s.bytes = c.off;
@@ -86,7 +96,7 @@ FwdSpace carve_fwd(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T
 }
 
 struct BwdSpace {
-    float* scales; qblora_bf16 *At_x, *Bx, *U, *U_lo, *dU, *dU_lo, *dUs; float* part;
+    float* scales; qblora_bf16 *At_x, *Bx, *U, *U_lo, *dU, *dU_lo, *dUs, *A_op, *Xs, *dYs; float* part;
     int splits_a, splits_b;
     size_t bytes;
 };
@@ -106,6 +116,11 @@ BwdSpace carve_bwd(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T
         s.splits_b = grad_splits(T, qw->d_out);
         size_t pa = (size_t)s.splits_a * qw->d_in * ad->R, pb = (size_t)s.splits_b * qw->d_out * ad->R;
         s.part = c.take<float>(pa > pb ? pa : pb);
+        if (scale_op_of(ad)) s.A_op = c.take<qblora_bf16>((size_t)qw->d_in * ad->R);
+        if (scale_op_of(ad) == QBLORA_OP_SAMPLE_ZEROFILL) {
+            s.Xs = c.take<qblora_bf16>((size_t)T * (qw->d_in / ad->lambda1));
+            s.dYs = c.take<qblora_bf16>((size_t)T * (qw->d_out / ad->lambda2));
+        }
     }
     s.bytes = c.off;
     return s;
@@ -264,10 +279,20 @@ int linear_fwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
     if (grouped) { sct.scale_codes = qw->scale_codes; sct.scale_step = qw->scale_step; sct.scale_mid = qw->scale_mid; }
     sct.scale_group = qw->scale_group; sct.d_out = qw->d_out; sct.d_in = qw->d_in; sct.out = ws.scales;
     g.scales = nullptr; g.scales_tiled = ws.scales;
-    if ((rc = launch_adapter_prep(adapted ? ad->A : nullptr, adapted ? ad->B : nullptr, qw->d_in, qw->d_out,
+    const int op = scale_op_of(ad);
+    const bool prep_adapter = adapted && op == QBLORA_OP_AVGPOOL_REPEAT;
+    if ((rc = launch_adapter_prep(prep_adapter ? ad->A : nullptr, prep_adapter ? ad->B : nullptr, qw->d_in, qw->d_out,
                                   adapted ? ad->R : 0, adapted ? ad->lambda1 : 1, adapted ? ad->lambda2 : 1,
                                   ws.At_x, ws.Bt, nullptr, st, &sct)))
         return rc;
+    if (adapted && op != QBLORA_OP_AVGPOOL_REPEAT) {
+        // At_x[j][k] = A[C-map(k)][j] and Bt[n][j] = B[j][E-map(n)], zero where the operator drops the index
+        const int na = qw->d_in / ad->lambda1, nb = qw->d_out / ad->lambda2;
+        if ((rc = launch_expand_op(ad->A, ad->R, na, 1, ad->R, qw->d_in, MAP_ID, 1, op_map(op), ad->lambda1, ws.At_x, st)))
+            return rc;
+        if ((rc = launch_expand_op(ad->B, nb, ad->R, 1, qw->d_out, ad->R, op_map(op), ad->lambda2, MAP_ID, 1, ws.Bt, st)))
+            return rc;
+    }
     if (adapted) {
         // s*U = (s/lambda1) * X * expand(A): average pool folded into the contraction
         GemmDesc u{};
@@ -275,9 +300,9 @@ int linear_fwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
         u.X2 = X; u.ldx2 = qw->d_in; u.W2 = ws.At_x; u.ldw2 = qw->d_in; u.K2 = qw->d_in; u.div2 = 1;
         qblora_bf16* su = saved ? saved : ws.U;               // kept for the backward: high part, then residual
         u.C = su; u.C_lo = saved ? saved + T * ad->R : nullptr;
-        u.ldc = ad->R; u.out_scale = ad->s / (float)ad->lambda1; u.M = T; u.N = ad->R;
+        u.ldc = ad->R; u.out_scale = op ? ad->s : ad->s / (float)ad->lambda1; u.M = T; u.N = ad->R;
         if ((rc = launch_gemm(u, st))) return rc;
-        g.X2 = su; g.ldx2 = ad->R; g.W2 = ws.Bt; g.ldw2 = ad->R; g.K2 = ad->R; g.div2 = ad->lambda2;
+        g.X2 = su; g.ldx2 = ad->R; g.W2 = ws.Bt; g.ldw2 = ad->R; g.K2 = ad->R; g.div2 = op ? 1 : ad->lambda2;
     } else {
         g.K2 = 0; g.div2 = 1;
     }
@@ -319,14 +344,27 @@ int linear_bwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
     if (dX && (rc = resolve_scales(qw, ws.scales, st, &g.scales))) return rc;
     if (adapted) {
         const int R = ad->R;
-        if ((rc = launch_adapter_prep(ad->A, ad->B, qw->d_in, qw->d_out, R, ad->lambda1, ad->lambda2,
-                                      (want_grads && !saved) ? ws.At_x : nullptr, nullptr, ws.Bx, st)))
-            return rc;
+        const int op = scale_op_of(ad);
+        const int na = qw->d_in / ad->lambda1, nb = qw->d_out / ad->lambda2;
+        if (op == QBLORA_OP_AVGPOOL_REPEAT) {
+            if ((rc = launch_adapter_prep(ad->A, ad->B, qw->d_in, qw->d_out, R, ad->lambda1, ad->lambda2,
+                                          (want_grads && !saved) ? ws.At_x : nullptr, nullptr, ws.Bx, st)))
+                return rc;
+        } else {
+            // Bx[j][n] = B[j][E-map(n)], A_op[k][j] = A[C-map(k)][j] (and At_x as in the forward), zeros elsewhere
+            if ((rc = launch_expand_op(ad->B, R, nb, 0, R, qw->d_out, MAP_ID, 1, op_map(op), ad->lambda2, ws.Bx, st)))
+                return rc;
+            if (dX && (rc = launch_expand_op(ad->A, na, R, 0, qw->d_in, R, op_map(op), ad->lambda1, MAP_ID, 1, ws.A_op, st)))
+                return rc;
+            if (want_grads && !saved &&
+                (rc = launch_expand_op(ad->A, R, na, 1, R, qw->d_in, MAP_ID, 1, op_map(op), ad->lambda1, ws.At_x, st)))
+                return rc;
+        }
         // dU = s * dY * expand(B)^T (sum pool over lambda2 folded into the contraction); dUs = dU/lambda1
         GemmDesc du{};
         du.qmode = 0;
         du.X2 = dY; du.ldx2 = qw->d_out; du.W2 = ws.Bx; du.ldw2 = qw->d_out; du.K2 = qw->d_out; du.div2 = 1;
-        du.C = ws.dU; du.ldc = R; du.out_scale = ad->s; du.C2 = ws.dUs; du.c2_scale = 1.0f / (float)ad->lambda1;
+        du.C = ws.dU; du.ldc = R; du.out_scale = ad->s; du.C2 = ws.dUs; du.c2_scale = op ? 1.0f : 1.0f / (float)ad->lambda1;
         du.C_lo = want_grads ? ws.dU_lo : nullptr;
         du.M = T; du.N = R;
         if ((rc = launch_gemm(du, st))) return rc;
@@ -336,7 +374,7 @@ int linear_bwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
                 GemmDesc u{};
                 u.qmode = 0;
                 u.X2 = X; u.ldx2 = qw->d_in; u.W2 = ws.At_x; u.ldw2 = qw->d_in; u.K2 = qw->d_in; u.div2 = 1;
-                u.C = ws.U; u.ldc = R; u.out_scale = ad->s / (float)ad->lambda1; u.M = T; u.N = R; u.C_lo = ws.U_lo;
+                u.C = ws.U; u.ldc = R; u.out_scale = op ? ad->s : ad->s / (float)ad->lambda1; u.M = T; u.N = R; u.C_lo = ws.U_lo;
                 if ((rc = launch_gemm(u, st))) return rc;
                 su = ws.U; su_lo = ws.U_lo;
             }
@@ -344,14 +382,27 @@ int linear_bwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
             ga.L = X; ga.ldl = qw->d_in; ga.I = qw->d_in; ga.S = ws.dU; ga.S_lo = ws.dU_lo; ga.lds = R; ga.J = R; ga.T = T;
             ga.part = ws.part; ga.splits = ws.splits_a; ga.out = dA; ga.pool = ad->lambda1;
             ga.out_scale = 1.0f / (float)ad->lambda1; ga.transpose_out = 0;
-            if ((rc = launch_grad(ga, st))) return rc;
             GradDesc gb{};
             gb.L = dY; gb.ldl = qw->d_out; gb.I = qw->d_out; gb.S = su; gb.S_lo = su_lo; gb.lds = R; gb.J = R; gb.T = T;
             gb.part = ws.part; gb.splits = ws.splits_b; gb.out = dB; gb.pool = ad->lambda2;
             gb.out_scale = 1.0f; gb.transpose_out = 1;
+            if (op != QBLORA_OP_AVGPOOL_REPEAT) {
+                // dA = C(X)^T dU and dB = (sU)^T E^T(dY): the kept features are the first ones of each
+                // row (truncation) or are gathered into a dense copy first (interval sampling)
+                ga.I = na; ga.pool = 1; ga.out_scale = 1.0f;
+                gb.I = nb; gb.pool = 1;
+                if (op == QBLORA_OP_SAMPLE_ZEROFILL) {
+                    if ((rc = launch_sample_rows(X, T, qw->d_in, ad->lambda1, ws.Xs, st))) return rc;
+                    if ((rc = launch_sample_rows(dY, T, qw->d_out, ad->lambda2, ws.dYs, st))) return rc;
+                    ga.L = ws.Xs; ga.ldl = na; gb.L = ws.dYs; gb.ldl = nb;
+                }
+            }
+            if ((rc = launch_grad(ga, st))) return rc;
             if ((rc = launch_grad(gb, st))) return rc;
         }
-        g.X2 = ws.dUs; g.ldx2 = R; g.W2 = ad->A; g.ldw2 = R; g.K2 = R; g.div2 = ad->lambda1;
+        g.X2 = ws.dUs; g.ldx2 = R; g.K2 = R;
+        if (op == QBLORA_OP_AVGPOOL_REPEAT) { g.W2 = ad->A; g.ldw2 = R; g.div2 = ad->lambda1; }
+        else { g.W2 = ws.A_op; g.ldw2 = R; g.div2 = 1; }
     } else {
         g.K2 = 0; g.div2 = 1;
     }
@@ -533,6 +584,7 @@ int qblora_tile_product(const qblora_adapter* ad, int32_t d_in, int32_t d_out, f
     if (!ad || !ad->A || !ad->B || !H) return QBLORA_ERR_NULL;
     if (d_in <= 0 || d_out <= 0 || ad->R <= 0 || ad->lambda1 <= 0 || ad->lambda2 <= 0) return QBLORA_ERR_SHAPE;
     if (d_in % ad->lambda1 || d_out % ad->lambda2 || ad->R % 8) return QBLORA_ERR_SHAPE;
+    if (ad->scale_op != QBLORA_OP_AVGPOOL_REPEAT) return QBLORA_ERR_UNSUPPORTED;   // no tile-constant delta weight
     const int rows = d_in / ad->lambda1, cols = d_out / ad->lambda2;
     if (cols % 4) return QBLORA_ERR_UNSUPPORTED;
     size_t need = qblora_tile_product_workspace_bytes(ad, d_in, d_out);

@@ -122,6 +122,15 @@ int grad_splits(int64_t T, int I, int J = 1);    // slices of the token range fo
 int launch_pool_rows(const qblora_bf16* in, int64_t T, int d, int lam, float scale, qblora_bf16* out,
                      qblora_bf16* out_lo, hipStream_t st);
 int launch_grad(const GradDesc& d, hipStream_t st);
+// out[t, c] = in[t, lam*c] for c < d/lam (every lam-th feature of each row), bf16
+int launch_sample_rows(const qblora_bf16* in, int64_t T, int d, int lam, qblora_bf16* out, hipStream_t st);
+
+// Index maps of the expanded adapter operands: output index -> source index, or "zero".
+enum { MAP_ID = 0, MAP_DIV = 1, MAP_FRONT = 2, MAP_STRIDE = 3 };
+// out[r][c] (bf16 [out_rows, out_cols]) = src(map_row(r), map_col(c)), 0 where a map says zero.  The source
+// has src_rows x src_cols elements, stored row-major [src_rows, src_cols], or [src_cols, src_rows] when `transpose`.
+int launch_expand_op(const qblora_bf16* in, int src_rows, int src_cols, int transpose, int out_rows, int out_cols,
+                     int row_map, int row_lam, int col_map, int col_lam, qblora_bf16* out, hipStream_t st);
 
 struct MergeDesc {
     const uint8_t* codes; const float* scales; const float* beta;

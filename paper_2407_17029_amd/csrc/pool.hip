@@ -66,6 +66,30 @@ __global__ __launch_bounds__(256) void k_pool_rows1(const uint16_t* __restrict__
     if (out_lo) out_lo[o] = (uint16_t)(pack_bf16(v - bf16_bits_to_float(h), 0.0f) & 0xffffu);
 }
 
+// Interval sampling (the "interval_sampling" compress operator of the ablation, Sec. 4.3):
+// out[t, c] = in[t, lam*c]; 8 outputs (one 16-byte store) per thread when rows are whole chunks.
+__global__ __launch_bounds__(256) void k_sample_rows(const uint16_t* __restrict__ in, int64_t T, int d, int lam,
+                                                     uint16_t* __restrict__ out) {
+    const int dq = d / lam;
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;   // first of 8 consecutive outputs
+    const int64_t total = T * dq;
+    if (i >= total) return;
+    if ((dq & 7) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0) {
+        const int64_t t = i / dq;
+        const int c = (int)(i - t * dq);
+        const uint16_t* src = in + t * d + (int64_t)c * lam;
+        uint32_t w[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) w[q] = (uint32_t)src[(2 * q) * lam] | ((uint32_t)src[(2 * q + 1) * lam] << 16);
+        *reinterpret_cast<uint4*>(out + i) = make_uint4(w[0], w[1], w[2], w[3]);
+        return;
+    }
+    for (int64_t j = i; j < i + 8 && j < total; ++j) {
+        const int64_t t = j / dq;
+        out[j] = in[t * d + (j - t * dq) * lam];
+    }
+}
+
 }  // namespace
 
 // in: bf16 [T, d] with d % lam == 0 (rows are contiguous, so the whole matrix is one run of groups of
@@ -93,6 +117,14 @@ int launch_pool_rows(const qblora_bf16* in, int64_t T, int d, int lam, float sca
                            reinterpret_cast<const uint16_t*>(in), n_out, lam, scale, reinterpret_cast<uint16_t*>(out),
                            reinterpret_cast<uint16_t*>(out_lo));
     }
+    return launch_status();
+}
+
+int launch_sample_rows(const qblora_bf16* in, int64_t T, int d, int lam, qblora_bf16* out, hipStream_t st) {
+    if (T <= 0 || d <= 0 || lam <= 0 || d % lam != 0) return QBLORA_ERR_SHAPE;
+    const int64_t total = T * (d / lam);
+    hipLaunchKernelGGL(k_sample_rows, dim3((unsigned)((total + 2047) / 2048)), dim3(256), 0, st,
+                       reinterpret_cast<const uint16_t*>(in), T, d, lam, reinterpret_cast<uint16_t*>(out));
     return launch_status();
 }
 

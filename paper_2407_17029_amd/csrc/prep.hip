@@ -165,6 +165,36 @@ __global__ __launch_bounds__(256) void k_adapter_prep(PrepDesc d) {
     }
 }
 
+// Expanded adapter operand for the alternative scale operators (Sec. 4.3 "The scale operators"):
+// every output element copies one source element or is zero.  Small (at most d x R elements), so one
+// element per thread is enough.
+struct ExpandDesc {
+    const uint16_t* in; int src_rows, src_cols, transpose;
+    int out_rows, out_cols, row_map, row_lam, col_map, col_lam;
+    uint16_t* out;
+};
+
+__device__ __forceinline__ int map_index(int idx, int map, int lam, int n_src) {
+    switch (map) {
+        case MAP_DIV: return idx / lam;
+        case MAP_FRONT: return idx < n_src ? idx : -1;
+        case MAP_STRIDE: return idx % lam == 0 ? idx / lam : -1;
+        default: return idx;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_expand_op(ExpandDesc d) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (int64_t)d.out_rows * d.out_cols) return;
+    const int r = (int)(i / d.out_cols), c = (int)(i - (int64_t)r * d.out_cols);
+    const int sr = map_index(r, d.row_map, d.row_lam, d.src_rows);
+    const int sc = map_index(c, d.col_map, d.col_lam, d.src_cols);
+    uint16_t v = 0;
+    if (sr >= 0 && sc >= 0 && sr < d.src_rows && sc < d.src_cols)
+        v = d.transpose ? d.in[(int64_t)sc * d.src_rows + sr] : d.in[(int64_t)sr * d.src_cols + sc];
+    d.out[i] = v;
+}
+
 }  // namespace
 
 int launch_adapter_prep(const qblora_bf16* A, const qblora_bf16* B, int d_in, int d_out, int R, int lam1,
@@ -185,6 +215,17 @@ int launch_adapter_prep(const qblora_bf16* A, const qblora_bf16* B, int d_in, in
     const int blocks = d.nA + d.nB + d.nS + d.nX;
     if (blocks == 0) return QBLORA_OK;
     hipLaunchKernelGGL(k_adapter_prep, dim3(blocks), dim3(256), 0, st, d);
+    return launch_status();
+}
+
+int launch_expand_op(const qblora_bf16* in, int src_rows, int src_cols, int transpose, int out_rows, int out_cols,
+                     int row_map, int row_lam, int col_map, int col_lam, qblora_bf16* out, hipStream_t st) {
+    if (!in || !out || src_rows <= 0 || src_cols <= 0 || out_rows <= 0 || out_cols <= 0 || row_lam <= 0 || col_lam <= 0)
+        return QBLORA_ERR_SHAPE;
+    ExpandDesc d{reinterpret_cast<const uint16_t*>(in), src_rows, src_cols, transpose, out_rows, out_cols,
+                 row_map, row_lam, col_map, col_lam, reinterpret_cast<uint16_t*>(out)};
+    const int64_t total = (int64_t)out_rows * out_cols;
+    hipLaunchKernelGGL(k_expand_op, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, d);
     return launch_status();
 }
 

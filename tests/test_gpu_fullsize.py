@@ -126,3 +126,33 @@ def test_single_matrix_adapter_benchmark_shape(qb, oracle, codebook):
     del Wt
     _, rH = oracle.qa_backward(None, L.X, L.dY, Hb, lam1, lam2, s, compute_dx=False, d_out=d_out, d_in=d_in)
     assert_close_f32(dH, rH, "dH")
+
+
+@pytest.mark.parametrize("op", [1, 2])
+def test_scale_operators_benchmark_shape(qb, oracle, codebook, op):
+    """The ablation's alternative scale operators at the benchmark layer shape, as bench.py calls them."""
+    from gpu_util import f32_to_dev, to_np, bf16_to_dev, assert_close_bf16, assert_close_f32
+    wl = synth.WORKLOADS["llama7b_attn"]
+    p = wl.projections[0]
+    T, d_out, d_in, lam, s = wl.tokens, p.d_out, p.d_in, wl.lam, wl.s
+    R = lam * wl.rank
+    print(f"full-size scale-operator case op={op} T={T} {d_out}x{d_in} R={R}", flush=True)
+    L = synth.make_layer(wl.seed + 30 + op, T, d_out, d_in, R, lam, lam)
+    qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 64, qb.QUANT_ABSMAX_CODEBOOK, codebook)
+    ad = qb.Adapter(bf16_to_dev(L.A), bf16_to_dev(L.B), lam, lam, s, scale_op=op)
+    X, dY = bf16_to_dev(L.X), bf16_to_dev(L.dY)
+    saved = torch.empty(qb.qblora_saved_bytes(ad, T), dtype=torch.uint8, device=X.device)
+    Y = qb.qblora_linear_fwd(qw, ad, X, saved=saved)
+    dX, dA, dB = qb.qblora_linear_bwd(qw, ad, X, dY, saved=saved)
+    torch.cuda.synchronize()
+    Wt = oracle.dequantize(to_np(qw.codes), to_np(qw.scales), None, codebook, 64, 2)
+    rows = synth.sample_rows(T, 128, wl.seed + 40 + op)
+    Xs, dYs = np.ascontiguousarray(L.X[rows]), np.ascontiguousarray(L.dY[rows])
+    ridx = torch.from_numpy(rows).to(Y.device)
+    assert_close_bf16(Y[ridx], oracle.forward_op(Wt, Xs, L.A, L.B, lam, lam, s, op), "Y (sampled rows)")
+    rX, _, _ = oracle.backward_op(Wt, Xs, dYs, L.A, L.B, lam, lam, s, op, compute_dab=False)
+    assert_close_bf16(dX[ridx], rX, "dX (sampled rows)")
+    del Wt
+    _, rA, rB = oracle.backward_op(None, L.X, L.dY, L.A, L.B, lam, lam, s, op, compute_dx=False, d_out=d_out, d_in=d_in)
+    assert_close_f32(dA, rA, "dA")
+    assert_close_f32(dB, rB, "dB")
