@@ -262,6 +262,54 @@ def merge_beta_shift(beta, H, d_out, d_in, block, lam1, lam2, s):
     return out
 
 
+def quantize_codebook_tile(W, br, bc, codebook):
+    """Codebook quantizer on blocks of br output rows x bc inputs; absmax is [d_out/br, d_in/bc]."""
+    W = _c(W, np.float32); cb = _c(codebook, np.float32)
+    d_out, d_in = W.shape
+    assert d_out % br == 0 and d_in % bc == 0 and d_in % 2 == 0
+    codes = np.zeros((d_out, d_in // 2), np.uint8)
+    absmax = np.zeros((d_out // br, d_in // bc), np.float32)
+    lib().oracle_quantize_codebook_tile(_p(W), i64(d_out), i64(d_in), C.c_int(br), C.c_int(bc), _p(cb), _p(codes),
+                                        _p(absmax))
+    return codes, absmax
+
+
+def quantize_minmax_tile(W, br, bc):
+    W = _c(W, np.float32)
+    d_out, d_in = W.shape
+    assert d_out % br == 0 and d_in % bc == 0 and d_in % 2 == 0
+    codes = np.zeros((d_out, d_in // 2), np.uint8)
+    alpha = np.zeros((d_out // br, d_in // bc), np.float32)
+    beta = np.zeros((d_out // br, d_in // bc), np.float32)
+    lib().oracle_quantize_minmax_tile(_p(W), i64(d_out), i64(d_in), C.c_int(br), C.c_int(bc), _p(codes), _p(alpha),
+                                      _p(beta))
+    return codes, alpha, beta
+
+
+def dequantize_tile(codes, alpha, beta, codebook, br, bc, mode):
+    codes = _c(codes, np.uint8); alpha = _c(alpha, np.float32); cb = _c(codebook, np.float32)
+    beta = None if beta is None else _c(beta, np.float32)
+    d_out, d_in = codes.shape[0], codes.shape[1] * 2
+    assert alpha.size == (d_out // br) * (d_in // bc)
+    Wt = np.zeros((d_out, d_in), np.float64)
+    lib().oracle_dequantize_tile(_p(codes), _p(alpha), _p(beta), _p(cb), i64(d_out), i64(d_in), C.c_int(br),
+                                 C.c_int(bc), C.c_int(mode), _p(Wt))
+    return Wt
+
+
+def merge_beta_shift_tile(beta, H, d_out, d_in, br, bc, lam1, lam2, s):
+    H = _c(H, np.float32)
+    assert H.shape == (d_in // lam1, d_out // lam2)
+    beta = None if beta is None else _c(beta, np.float32)
+    out = np.zeros((d_out // br, d_in // bc), np.float32)
+    lib().oracle_merge_beta_shift_tile.restype = C.c_int
+    rc = lib().oracle_merge_beta_shift_tile(_p(beta), _p(H), i64(d_out), i64(d_in), C.c_int(br), C.c_int(bc),
+                                            C.c_int(lam1), C.c_int(lam2), C.c_float(s), _p(out))
+    if rc != 0:
+        raise ValueError("offset-shift merge needs every quantization block inside one (lam1 x lam2) tile")
+    return out
+
+
 def merge_requant(codes, alpha, beta, codebook, H, block, lam1, lam2, s):
     codes = _c(codes, np.uint8); alpha = _c(alpha, np.float32); cb = _c(codebook, np.float32)
     beta = None if beta is None else _c(beta, np.float32)

@@ -32,7 +32,9 @@
 // dense delta weight, against the two-matrix layer with A = identity and by
 // finite differences; the alternative scale operators against dense operator
 // matrices, against the default layer (op 0, lambda = 1) and by finite
-// differences.  No function here is unpinned.
+// differences; the two-dimensional block variants against the row-segment
+// functions (br = 1), brute force, and the exactness of the offset-shift merge.
+// No function here is unpinned.
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
@@ -696,6 +698,96 @@ int oracle_merge_beta_shift(const float* beta, const float* H, int64_t d_out, in
             int64_t k = b * block;
             float delta = f32_div(f32_mul(s, H[(k / lam1) * cols + n / lam2]), (float)lam1);
             beta_out[n * bpr + b] = beta ? f32_add(beta[n * bpr + b], delta) : delta;
+        }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------
+// Two-dimensional quantization blocks (Sec. 3.3: block quantization "with
+// sizes of 4 x 8 or 8 x 8"): a block is br consecutive output rows x bc
+// consecutive inputs; its scale / offset live at [(n/br) * (d_in/bc) + k/bc].
+// With lam1 % bc == 0 and lam2 % br == 0 every block lies inside one
+// (lam1 x lam2) tile of the adapter, so get_new_beta (Alg. 2) is exact: the
+// merge is the offset shift alone.  Codes keep the [d_out, d_in/2] packing.
+// Elements of a block are visited row by row; br = 1 gives the row-segment
+// blocks of the functions above.
+// ---------------------------------------------------------------------------
+void oracle_quantize_codebook_tile(const float* W, int64_t d_out, int64_t d_in, int br, int bc,
+                                   const float* codebook, uint8_t* codes, float* absmax) {
+    const int64_t nbr = d_out / br, nbc = d_in / bc;
+    std::memset(codes, 0, (size_t)(d_out * d_in / 2));
+    parallel_rows(nbr, [&](int64_t r0, int64_t r1) {
+        for (int64_t rb = r0; rb < r1; ++rb)
+            for (int64_t cbk = 0; cbk < nbc; ++cbk) {
+                float a = 0.0f;
+                for (int i = 0; i < br; ++i)
+                    for (int j = 0; j < bc; ++j) a = std::max(a, std::fabs(W[(rb * br + i) * d_in + cbk * bc + j]));
+                absmax[rb * nbc + cbk] = a;
+                float t[15];
+                for (int j = 0; j < 15; ++j) t[j] = f32_mul(f32_mul(f32_add(codebook[j], codebook[j + 1]), 0.5f), a);
+                for (int i = 0; i < br; ++i)
+                    for (int j = 0; j < bc; ++j) {
+                        const int64_t idx = (rb * br + i) * d_in + cbk * bc + j;
+                        int c = 0;
+                        for (int q = 0; q < 15; ++q) c += (W[idx] > t[q]) ? 1 : 0;
+                        put_code(codes, idx, c);
+                    }
+            }
+    });
+}
+
+void oracle_quantize_minmax_tile(const float* W, int64_t d_out, int64_t d_in, int br, int bc,
+                                 uint8_t* codes, float* alpha, float* beta) {
+    const int64_t nbr = d_out / br, nbc = d_in / bc;
+    std::memset(codes, 0, (size_t)(d_out * d_in / 2));
+    parallel_rows(nbr, [&](int64_t r0, int64_t r1) {
+        std::vector<float> w(br * bc);
+        std::vector<int> c(br * bc);
+        for (int64_t rb = r0; rb < r1; ++rb)
+            for (int64_t cbk = 0; cbk < nbc; ++cbk) {
+                for (int i = 0; i < br; ++i)
+                    for (int j = 0; j < bc; ++j) w[i * bc + j] = W[(rb * br + i) * d_in + cbk * bc + j];
+                minmax_encode_block(w.data(), br * bc, c.data(), &alpha[rb * nbc + cbk], &beta[rb * nbc + cbk]);
+                for (int i = 0; i < br; ++i)
+                    for (int j = 0; j < bc; ++j) put_code(codes, (rb * br + i) * d_in + cbk * bc + j, c[i * bc + j]);
+            }
+    });
+}
+
+// modes as in oracle_dequantize
+void oracle_dequantize_tile(const uint8_t* codes, const float* alpha, const float* beta, const float* codebook,
+                            int64_t d_out, int64_t d_in, int br, int bc, int mode, double* Wt) {
+    const int64_t nbc = d_in / bc;
+    parallel_rows(d_out, [&](int64_t n0, int64_t n1) {
+        for (int64_t n = n0; n < n1; ++n)
+            for (int64_t k = 0; k < d_in; ++k) {
+                const int64_t blk = (n / br) * nbc + k / bc;
+                const float c = codebook[get_code(codes, n * d_in + k)];
+                double v;
+                if (mode == 0) {
+                    v = (double)alpha[blk] * (double)c + (beta ? (double)beta[blk] : 0.0);
+                } else if (mode == 3) {
+                    v = (double)alpha[blk] * (double)round_to_bf16(c) + (beta ? (double)beta[blk] : 0.0);
+                } else {
+                    float f = beta ? std::fmaf(c, alpha[blk], beta[blk]) : f32_mul(c, alpha[blk]);
+                    v = (double)(mode == 2 ? round_to_bf16(f) : f);
+                }
+                Wt[n * d_in + k] = v;
+            }
+    });
+}
+
+// Alg. 2 get_new_beta on two-dimensional blocks: beta' = beta + (s * H[k/lam1, n/lam2]) / lam1 for the
+// block at rows n.., inputs k..; -1 when a block would straddle two tiles.
+int oracle_merge_beta_shift_tile(const float* beta, const float* H, int64_t d_out, int64_t d_in, int br, int bc,
+                                 int lam1, int lam2, float s, float* beta_out) {
+    if (lam1 % bc != 0 || lam2 % br != 0) return -1;
+    const int64_t nbr = d_out / br, nbc = d_in / bc, cols = d_out / lam2;
+    for (int64_t rb = 0; rb < nbr; ++rb)
+        for (int64_t cbk = 0; cbk < nbc; ++cbk) {
+            const int64_t n = rb * br, k = cbk * bc;
+            const float delta = f32_div(f32_mul(s, H[(k / lam1) * cols + n / lam2]), (float)lam1);
+            beta_out[rb * nbc + cbk] = beta ? f32_add(beta[rb * nbc + cbk], delta) : delta;
         }
     return 0;
 }
