@@ -66,6 +66,14 @@ enum { QBLORA_MERGE_BETA_SHIFT = 0, QBLORA_MERGE_REQUANT_MINMAX = 1 };
  *              the codes were chosen against) and may be NULL for consumers.
  *   scale_codes [d_out*d_in/block] bytes, OCP E4M3 bit patterns.
  *   scale_step, scale_mid  fp32 [ceil(nblocks/scale_group)].
+ *   block_rows 8 selects two-dimensional quantization blocks (Sec. 3.3: pre-trained models "use block
+ *              quantization with sizes of 4 x 8 or 8 x 8"; Sec. 4.3: block 64 goes with lambda1 = lambda2 = 8):
+ *              block (i, j) covers output rows [8i, 8i+8) and inputs [8j, 8j+8), its scale / offset has
+ *              index i*(d_in/8) + j; `codes` keeps the [d_out, d_in/2] packing.  Then every block lies in
+ *              one (lambda1 x lambda2) adapter tile when 8 | lambda1 and 8 | lambda2, and the offset-shift
+ *              merge (Alg. 2 get_new_beta) is exact.  Needs d_out % 8 == 0 and fp32 scales.  The caller sets
+ *              the field before qblora_quantize_blockwise; entry points that do not take such weights
+ *              return QBLORA_ERR_UNSUPPORTED.
  *   codes_tiled optional second copy of the codes (NULL = absent) in the order the forward kernel
  *              streams them, qblora_codes_tiled_bytes() bytes: output rows in tiles of 256, and for
  *              tile i and 64-wide input step j one contiguous 8 KiB block at ((i*(d_in/64) + j)*256 + r)*32
@@ -89,6 +97,8 @@ typedef struct qblora_qweight {
     float* scale_step;
     float* scale_mid;
     uint8_t* codes_tiled;
+    int32_t block_rows;   /* 1 (or 0): a block is `block` consecutive inputs of one output row;
+                             8: a block is 8 output rows x 8 inputs (see below) */
 } qblora_qweight;
 
 /*

@@ -39,7 +39,8 @@ class CQWeight(C.Structure):
     _fields_ = [("d_out", C.c_int32), ("d_in", C.c_int32), ("block", C.c_int32), ("scale_mode", C.c_int32),
                 ("scale_group", C.c_int32), ("codebook", C.c_float * 16), ("codes", C.c_void_p),
                 ("scales", C.c_void_p), ("beta", C.c_void_p), ("scale_codes", C.c_void_p),
-                ("scale_step", C.c_void_p), ("scale_mid", C.c_void_p), ("codes_tiled", C.c_void_p)]
+                ("scale_step", C.c_void_p), ("scale_mid", C.c_void_p), ("codes_tiled", C.c_void_p),
+                ("block_rows", C.c_int32)]
 
 
 class CAdapter(C.Structure):
@@ -143,8 +144,9 @@ class QWeight:
     """The triplet (codes, alpha, beta) of Eq. 1 on the device, plus the host-side C struct."""
 
     def __init__(self, d_out, d_in, block, codebook, codes, scales, beta=None, scale_mode=SCALES_FP32,
-                 scale_codes=None, scale_step=None, scale_mid=None, scale_group=256, codes_tiled=None):
+                 scale_codes=None, scale_step=None, scale_mid=None, scale_group=256, codes_tiled=None, block_rows=1):
         self.d_out, self.d_in, self.block = d_out, d_in, block
+        self.block_rows = int(block_rows)       # 1: blocks of 64 inputs in a row; 8: blocks of 8 rows x 8 inputs
         self.codebook = np.asarray(codebook, np.float32)
         self.codes, self.scales, self.beta = codes, scales, beta
         self.scale_mode, self.scale_group = scale_mode, scale_group
@@ -155,6 +157,7 @@ class QWeight:
         s = CQWeight()
         s.d_out, s.d_in, s.block = self.d_out, self.d_in, self.block
         s.scale_mode, s.scale_group = self.scale_mode, self.scale_group
+        s.block_rows = self.block_rows
         for j in range(16):
             s.codebook[j] = float(self.codebook[j])
         for name in ("codes", "scales", "beta", "scale_codes", "scale_step", "scale_mid", "codes_tiled"):
@@ -211,7 +214,7 @@ def qblora_prepack_codes(qw: QWeight) -> QWeight:
 
 def qblora_quantize_blockwise(W: torch.Tensor, block: int = 64, quantizer: int = QUANT_ABSMAX_CODEBOOK,
                               codebook=None, scale_mode: int = SCALES_FP32, out: QWeight = None,
-                              tiled: bool = True) -> QWeight:
+                              tiled: bool = True, block_rows: int = 1) -> QWeight:
     assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and W.dim() == 2
     d_out, d_in = W.shape
     dev = W.device
@@ -226,7 +229,10 @@ def qblora_quantize_blockwise(W: torch.Tensor, block: int = 64, quantizer: int =
         return out
     nblk = d_out * (d_in // max(block, 1))
     codes = torch.empty((d_out, d_in // 2), dtype=torch.uint8, device=dev)
-    scales = torch.empty((d_out, d_in // max(block, 1)), dtype=torch.float32, device=dev)
+    if block_rows == 8:
+        scales = torch.empty((d_out // 8, d_in // 8), dtype=torch.float32, device=dev)
+    else:
+        scales = torch.empty((d_out, d_in // max(block, 1)), dtype=torch.float32, device=dev)
     beta = torch.empty_like(scales) if quantizer == QUANT_MINMAX_INT4 else None
     sc = st = mid = None
     if scale_mode == SCALES_E4M3_GROUPED:
@@ -238,7 +244,8 @@ def qblora_quantize_blockwise(W: torch.Tensor, block: int = 64, quantizer: int =
     ct = None
     if tiled and block == 64 and d_in % 64 == 0:
         ct = torch.empty(qblora_codes_tiled_bytes(d_out, d_in), dtype=torch.uint8, device=dev)
-    qw = QWeight(d_out, d_in, block, cb, codes, scales, beta, scale_mode, sc, st, mid, codes_tiled=ct)
+    qw = QWeight(d_out, d_in, block, cb, codes, scales, beta, scale_mode, sc, st, mid, codes_tiled=ct,
+                 block_rows=block_rows)
     s = qw.c_struct()
     cb_ptr = None if codebook is None else cb.ctypes.data_as(C.c_void_p)
     rc = lib().qblora_quantize_blockwise(_ptr(W), d_out, d_in, block, quantizer, cb_ptr, scale_mode, C.byref(s),
@@ -383,8 +390,9 @@ def qablora_merge_quantize(base: QWeight, H: torch.Tensor, lambda1: int, lambda2
     if out is None:
         out = QWeight(base.d_out, base.d_in, base.block, base.codebook,
                       torch.empty_like(base.codes),
-                      torch.empty((base.d_out, base.d_in // base.block), dtype=torch.float32, device=dev),
-                      torch.empty((base.d_out, base.d_in // base.block), dtype=torch.float32, device=dev))
+                      torch.empty(tuple(base.scales.shape), dtype=torch.float32, device=dev),
+                      torch.empty(tuple(base.scales.shape), dtype=torch.float32, device=dev),
+                      block_rows=base.block_rows)
     b = base.c_struct()
     o = out.c_struct()
     rc = lib().qablora_merge_quantize(C.byref(b), _ptr(H), lambda1, lambda2, s, mode, C.byref(o), _stream())

@@ -28,11 +28,19 @@ int scale_op_of(const qblora_adapter* ad) { return has_adapter(ad) ? ad->scale_o
 // index map of an expanded operand for the compress / expand operator `op`
 int op_map(int op) { return op == QBLORA_OP_TRUNCATE_PAD0 ? MAP_FRONT : op == QBLORA_OP_SAMPLE_ZEROFILL ? MAP_STRIDE : MAP_DIV; }
 
-int check_qweight(const qblora_qweight* qw, bool need_codes) {
+// rows of a quantization block: 1 (row segments of 64 inputs) or 8 (8 x 8 blocks)
+int block_rows_of(const qblora_qweight* qw) { return qw->block_rows == 8 ? 8 : 1; }
+
+int check_qweight(const qblora_qweight* qw, bool need_codes, bool allow_tile8 = false) {
     if (!qw) return QBLORA_ERR_NULL;
     if (qw->d_out <= 0 || qw->d_in <= 0) return QBLORA_ERR_SHAPE;
     if (qw->block != kBlock) return qw->block > 0 ? QBLORA_ERR_UNSUPPORTED : QBLORA_ERR_SHAPE;
     if (qw->d_in % qw->block != 0 || qw->d_in % 2 != 0) return QBLORA_ERR_SHAPE;
+    if (qw->block_rows != 0 && qw->block_rows != 1 && qw->block_rows != 8) return QBLORA_ERR_UNSUPPORTED;
+    if (qw->block_rows == 8) {
+        if (!allow_tile8 || qw->scale_mode != QBLORA_SCALES_FP32) return QBLORA_ERR_UNSUPPORTED;
+        if (qw->d_out % 8 != 0) return QBLORA_ERR_SHAPE;
+    }
     if (need_codes) {
         if (!qw->codes) return QBLORA_ERR_NULL;
         if (qw->scale_mode == QBLORA_SCALES_FP32) {
@@ -186,6 +194,10 @@ int qblora_quantize_blockwise(const float* W, int32_t d_out, int32_t d_in, int32
         return QBLORA_ERR_UNSUPPORTED;
     if (scale_mode != QBLORA_SCALES_FP32 && scale_mode != QBLORA_SCALES_E4M3_GROUPED) return QBLORA_ERR_UNSUPPORTED;
     if (!out->codes || !out->scales) return QBLORA_ERR_NULL;
+    if (out->block_rows != 0 && out->block_rows != 1 && out->block_rows != 8) return QBLORA_ERR_UNSUPPORTED;
+    const int block_rows = out->block_rows == 8 ? 8 : 1;
+    if (block_rows == 8 && scale_mode != QBLORA_SCALES_FP32) return QBLORA_ERR_UNSUPPORTED;
+    if (block_rows == 8 && d_out % 8 != 0) return QBLORA_ERR_SHAPE;
     hipStream_t st = as_stream(stream);
     if (quantizer == QBLORA_QUANT_MINMAX_INT4) {
         if (scale_mode != QBLORA_SCALES_FP32) return QBLORA_ERR_UNSUPPORTED;
@@ -203,7 +215,7 @@ int qblora_quantize_blockwise(const float* W, int32_t d_out, int32_t d_in, int32
     if (quantizer == QBLORA_QUANT_MINMAX_INT4) {
         for (int j = 0; j < 16; ++j) out->codebook[j] = (float)j;
         ScopedEvents ev(QBLORA_PROFILE_QUANTIZE, st);
-        return launch_quantize_minmax(W, d_out, d_in, out->codes, out->codes_tiled, out->scales, out->beta, st);
+        return launch_quantize_minmax(W, d_out, d_in, out->codes, out->codes_tiled, out->scales, out->beta, st, block_rows);
     }
     Codebook cb;
     for (int j = 0; j < 16; ++j) { cb.c[j] = codebook[j]; out->codebook[j] = codebook[j]; }
@@ -211,7 +223,7 @@ int qblora_quantize_blockwise(const float* W, int32_t d_out, int32_t d_in, int32
     int rc;
     {
         ScopedEvents ev(QBLORA_PROFILE_QUANTIZE, st);
-        rc = launch_quantize_codebook(W, d_out, d_in, cb, out->codes, out->codes_tiled, out->scales, st);
+        rc = launch_quantize_codebook(W, d_out, d_in, cb, out->codes, out->codes_tiled, out->scales, st, block_rows);
     }
     if (rc) return rc;
     if (scale_mode == QBLORA_SCALES_E4M3_GROUPED)
@@ -226,14 +238,14 @@ size_t qblora_codes_tiled_bytes(int32_t d_out, int32_t d_in) {
 }
 
 int qblora_prepack_codes(const qblora_qweight* qw, void* stream) {
-    int rc = check_qweight(qw, false);
+    int rc = check_qweight(qw, false, true);                 // the code packing does not depend on the block shape
     if (rc) return rc;
     if (!qw->codes || !qw->codes_tiled) return QBLORA_ERR_NULL;
     return launch_prepack_codes(qw->codes, qw->d_out, qw->d_in, qw->codes_tiled, as_stream(stream));
 }
 
 int qblora_dequantize_bf16(const qblora_qweight* qw, qblora_bf16* Wt, void* stream) {
-    int rc = check_qweight(qw, true);
+    int rc = check_qweight(qw, true, true);
     if (rc) return rc;
     if (!Wt) return QBLORA_ERR_NULL;
     if (qw->scale_mode != QBLORA_SCALES_FP32) return QBLORA_ERR_UNSUPPORTED;   // reconstruct needs scratch
@@ -602,7 +614,7 @@ int qblora_tile_product(const qblora_adapter* ad, int32_t d_in, int32_t d_out, f
 
 int qablora_merge_quantize(const qblora_qweight* base, const float* H, int32_t lambda1, int32_t lambda2, float s,
                            int32_t mode, qblora_qweight* out, void* stream) {
-    int rc = check_qweight(base, true);
+    int rc = check_qweight(base, true, mode == QBLORA_MERGE_BETA_SHIFT);     // 8 x 8 blocks: offset shift only
     if (rc) return rc;
     if (!H || !out) return QBLORA_ERR_NULL;
     if (lambda1 <= 0 || lambda2 <= 0) return QBLORA_ERR_SHAPE;
@@ -620,11 +632,13 @@ int qablora_merge_quantize(const qblora_qweight* base, const float* H, int32_t l
     d.cb = codebook_of(base); d.d_out = base->d_out; d.d_in = base->d_in;
     d.H = H; d.lam1 = lambda1; d.lam2 = lambda2; d.s = s;
     d.codes_out = out->codes; d.alpha_out = out->scales; d.beta_out = out->beta;
-    out->d_out = base->d_out; out->d_in = base->d_in; out->block = base->block;
+    out->d_out = base->d_out; out->d_in = base->d_in; out->block = base->block; out->block_rows = base->block_rows;
+    d.block_rows = block_rows_of(base);
     out->scale_mode = QBLORA_SCALES_FP32; out->scale_group = 0;
     out->scale_codes = nullptr; out->scale_step = nullptr; out->scale_mid = nullptr; out->codes_tiled = nullptr;
     if (mode == QBLORA_MERGE_BETA_SHIFT) {
-        if (lambda1 % base->block != 0) return QBLORA_ERR_ALIGNMENT;
+        if (d.block_rows == 8 ? (lambda1 % 8 != 0 || lambda2 % 8 != 0) : (lambda1 % base->block != 0))
+            return QBLORA_ERR_ALIGNMENT;
         std::memcpy(out->codebook, base->codebook, sizeof(out->codebook));
         if (out->codes != base->codes &&
             hipMemcpyAsync(out->codes, base->codes, (size_t)base->d_out * base->d_in / 2, hipMemcpyDeviceToDevice,

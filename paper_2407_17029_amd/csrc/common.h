@@ -51,9 +51,9 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? QBLORA_OK 
 
 // `tiled` (may be NULL) receives the second, tile-ordered copy of the codes described in qblora.h
 int launch_quantize_codebook(const float* W, int d_out, int d_in, const Codebook& cb, uint8_t* codes,
-                             uint8_t* tiled, float* absmax, hipStream_t st);
+                             uint8_t* tiled, float* absmax, hipStream_t st, int block_rows = 1);
 int launch_quantize_minmax(const float* W, int d_out, int d_in, uint8_t* codes, uint8_t* tiled, float* alpha,
-                           float* beta, hipStream_t st);
+                           float* beta, hipStream_t st, int block_rows = 1);
 int launch_prepack_codes(const uint8_t* codes, int d_out, int d_in, uint8_t* tiled, hipStream_t st);
 
 // byte offset of the 32-byte run of (row n, 64-block b) in the tiled code copy
@@ -139,6 +139,7 @@ struct MergeDesc {
     const float* H; int lam1, lam2; float s;
     uint8_t* codes_out; float* alpha_out; float* beta_out;
     qblora_bf16* w16_out;                  // 16-bit merge only
+    int block_rows;                        // 1 or 8 (offset-shift merge only)
 };
 int launch_merge_requant(const MergeDesc& d, hipStream_t st);
 int launch_merge_bf16(const MergeDesc& d, hipStream_t st);

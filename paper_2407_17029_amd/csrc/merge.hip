@@ -196,6 +196,19 @@ __global__ __launch_bounds__(256) void k_merge_beta_shift(MergeDesc d) {
         d.alpha_out[blk] = grouped_scale(d.scale_codes, d.scale_step, d.scale_mid, blk, d.scale_group);
 }
 
+// The same shift on 8 x 8 blocks (block (i, j): rows 8i.., inputs 8j.., index i*(d_in/8) + j); with 8 | lambda1
+// and 8 | lambda2 the whole block sees one element of H, so the merged weight is exact (Alg. 2 get_new_beta).
+__global__ __launch_bounds__(256) void k_merge_beta_shift_tile8(MergeDesc d) {
+    const int nbc = d.d_in / 8;
+    const int64_t total = (int64_t)(d.d_out / 8) * nbc;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int i = (int)(idx / nbc), j = (int)(idx - (int64_t)i * nbc);
+    const float h = d.H[(int64_t)((8 * j) / d.lam1) * (d.d_out / d.lam2) + (8 * i) / d.lam2];
+    const float delta = __fdiv_rn(__fmul_rn(d.s, h), (float)d.lam1);
+    d.beta_out[idx] = d.beta ? __fadd_rn(d.beta[idx], delta) : delta;
+}
+
 }  // namespace
 
 template <int L1, bool OUT16>
@@ -233,6 +246,10 @@ int launch_merge_bf16(const MergeDesc& d, hipStream_t st) { return launch_merge_
 int launch_merge_beta_shift(const MergeDesc& d, hipStream_t st) {
     int64_t total = (int64_t)d.d_out * (d.d_in / kBlock);
     unsigned grid = (unsigned)((total + 255) / 256);
+    if (d.block_rows == 8) {
+        hipLaunchKernelGGL(k_merge_beta_shift_tile8, dim3(grid), dim3(256), 0, st, d);
+        return launch_status();
+    }
     if (d.scale_codes) hipLaunchKernelGGL(k_merge_beta_shift<true>, dim3(grid), dim3(256), 0, st, d);
     else hipLaunchKernelGGL(k_merge_beta_shift<false>, dim3(grid), dim3(256), 0, st, d);
     return launch_status();

@@ -40,6 +40,50 @@ __device__ __forceinline__ float group16_min(float v) {
     return v;
 }
 
+// Four codes of one float4 against the block's absmax a: code = #{ j : w > t_j } with t_j = m_j * a.
+// Rounding is monotone, so the t_j ascend (weakly) and the count is found by bisection: four comparisons
+// per weight against thresholds selected by the earlier outcomes, instead of fifteen.
+__device__ __forceinline__ uint32_t codes4_codebook(const float4& w, float a, const Midpoints& mp) {
+    const float t0 = __fmul_rn(mp.m[0], a), t1 = __fmul_rn(mp.m[1], a), t2 = __fmul_rn(mp.m[2], a),
+                t3 = __fmul_rn(mp.m[3], a), t4 = __fmul_rn(mp.m[4], a), t5 = __fmul_rn(mp.m[5], a),
+                t6 = __fmul_rn(mp.m[6], a), t7 = __fmul_rn(mp.m[7], a), t8 = __fmul_rn(mp.m[8], a),
+                t9 = __fmul_rn(mp.m[9], a), t10 = __fmul_rn(mp.m[10], a), t11 = __fmul_rn(mp.m[11], a),
+                t12 = __fmul_rn(mp.m[12], a), t13 = __fmul_rn(mp.m[13], a), t14 = __fmul_rn(mp.m[14], a);
+    auto code_of = [&](float x) -> uint32_t {
+        const bool b3 = x > t7;
+        const float u2 = b3 ? t11 : t3;
+        const bool b2 = x > u2;
+        const float u1lo = b2 ? t5 : t1, u1hi = b2 ? t13 : t9;
+        const bool b1 = x > (b3 ? u1hi : u1lo);
+        const float q0 = b1 ? t2 : t0, q1 = b1 ? t6 : t4, q2 = b1 ? t10 : t8, q3 = b1 ? t14 : t12;
+        const float u0lo = b2 ? q1 : q0, u0hi = b2 ? q3 : q2;
+        const bool b0 = x > (b3 ? u0hi : u0lo);
+        return (b3 ? 8u : 0u) + (b2 ? 4u : 0u) + (b1 ? 2u : 0u) + (b0 ? 1u : 0u);
+    };
+    const uint32_t c0 = code_of(w.x), c1 = code_of(w.y), c2 = code_of(w.z), c3 = code_of(w.w);
+    return c0 | (c1 << 4) | (c2 << 8) | (c3 << 12);
+}
+
+// Four min-max codes of one float4 given the block's extremes; also returns alpha = (hi-lo)/15.
+__device__ __forceinline__ uint32_t codes4_minmax(const float4& w, float lo, float hi, float& al) {
+    const float range = __fsub_rn(hi, lo);
+    al = __fdiv_rn(range, 15.0f);
+    uint32_t packed = 0;
+    if (al != 0.0f) {
+        const float inv = __fdiv_rn(15.0f, range);
+        float q0 = rintf(__fmul_rn(__fsub_rn(w.x, lo), inv));
+        float q1 = rintf(__fmul_rn(__fsub_rn(w.y, lo), inv));
+        float q2 = rintf(__fmul_rn(__fsub_rn(w.z, lo), inv));
+        float q3 = rintf(__fmul_rn(__fsub_rn(w.w, lo), inv));
+        q0 = fminf(fmaxf(q0, 0.0f), 15.0f);
+        q1 = fminf(fmaxf(q1, 0.0f), 15.0f);
+        q2 = fminf(fmaxf(q2, 0.0f), 15.0f);
+        q3 = fminf(fmaxf(q3, 0.0f), 15.0f);
+        packed = (uint32_t)q0 | ((uint32_t)q1 << 4) | ((uint32_t)q2 << 8) | ((uint32_t)q3 << 12);
+    }
+    return packed;
+}
+
 // Work split of both quantizers: a workgroup owns 4 consecutive weight rows x 16 consecutive 64-blocks
 // (4 x 4 KB of contiguous fp32 input).  Pass u of a thread takes float4 group t of row u, so 16 lanes
 // hold one block.  Codes (2 bytes per thread and pass) and block scales are collected in LDS and leave
@@ -101,27 +145,7 @@ __global__ __launch_bounds__(256) void k_quantize_codebook(const float4* __restr
         const float4 w = wv[u];
         float a = fmaxf(fmaxf(fabsf(w.x), fabsf(w.y)), fmaxf(fabsf(w.z), fabsf(w.w)));
         a = group16_max(a);
-        // code = #{ j : w > t_j } with t_j = m_j * a.  Rounding is monotone, so the t_j ascend (weakly)
-        // and the count is found by bisection: four comparisons per weight against thresholds selected
-        // by the earlier outcomes, instead of fifteen.
-        const float t0 = __fmul_rn(mp.m[0], a), t1 = __fmul_rn(mp.m[1], a), t2 = __fmul_rn(mp.m[2], a),
-                    t3 = __fmul_rn(mp.m[3], a), t4 = __fmul_rn(mp.m[4], a), t5 = __fmul_rn(mp.m[5], a),
-                    t6 = __fmul_rn(mp.m[6], a), t7 = __fmul_rn(mp.m[7], a), t8 = __fmul_rn(mp.m[8], a),
-                    t9 = __fmul_rn(mp.m[9], a), t10 = __fmul_rn(mp.m[10], a), t11 = __fmul_rn(mp.m[11], a),
-                    t12 = __fmul_rn(mp.m[12], a), t13 = __fmul_rn(mp.m[13], a), t14 = __fmul_rn(mp.m[14], a);
-        auto code_of = [&](float x) -> uint32_t {
-            const bool b3 = x > t7;
-            const float u2 = b3 ? t11 : t3;
-            const bool b2 = x > u2;
-            const float u1lo = b2 ? t5 : t1, u1hi = b2 ? t13 : t9;
-            const bool b1 = x > (b3 ? u1hi : u1lo);
-            const float q0 = b1 ? t2 : t0, q1 = b1 ? t6 : t4, q2 = b1 ? t10 : t8, q3 = b1 ? t14 : t12;
-            const float u0lo = b2 ? q1 : q0, u0hi = b2 ? q3 : q2;
-            const bool b0 = x > (b3 ? u0hi : u0lo);
-            return (b3 ? 8u : 0u) + (b2 ? 4u : 0u) + (b1 ? 2u : 0u) + (b0 ? 1u : 0u);
-        };
-        const uint32_t c0 = code_of(w.x), c1 = code_of(w.y), c2 = code_of(w.z), c3 = code_of(w.w);
-        cs[u][t] = (uint16_t)(c0 | (c1 << 4) | (c2 << 8) | (c3 << 12));
+        cs[u][t] = (uint16_t)codes4_codebook(w, a, mp);
         if ((t & 15) == 0) as[u][t >> 4] = a;
     }
     __syncthreads();
@@ -152,21 +176,8 @@ __global__ __launch_bounds__(256) void k_quantize_minmax(const float4* __restric
         const float4 w = wv[u];
         const float lo = group16_min(fminf(fminf(w.x, w.y), fminf(w.z, w.w)));
         const float hi = group16_max(fmaxf(fmaxf(w.x, w.y), fmaxf(w.z, w.w)));
-        const float range = __fsub_rn(hi, lo);
-        const float al = __fdiv_rn(range, 15.0f);
-        uint32_t packed = 0;
-        if (al != 0.0f) {
-            const float inv = __fdiv_rn(15.0f, range);
-            float q0 = rintf(__fmul_rn(__fsub_rn(w.x, lo), inv));
-            float q1 = rintf(__fmul_rn(__fsub_rn(w.y, lo), inv));
-            float q2 = rintf(__fmul_rn(__fsub_rn(w.z, lo), inv));
-            float q3 = rintf(__fmul_rn(__fsub_rn(w.w, lo), inv));
-            q0 = fminf(fmaxf(q0, 0.0f), 15.0f);
-            q1 = fminf(fmaxf(q1, 0.0f), 15.0f);
-            q2 = fminf(fmaxf(q2, 0.0f), 15.0f);
-            q3 = fminf(fmaxf(q3, 0.0f), 15.0f);
-            packed = (uint32_t)q0 | ((uint32_t)q1 << 4) | ((uint32_t)q2 << 8) | ((uint32_t)q3 << 12);
-        }
+        float al;
+        const uint32_t packed = codes4_minmax(w, lo, hi, al);
         cs[u][t] = (uint16_t)packed;
         if ((t & 15) == 0) { as[u][t >> 4] = al; bs[u][t >> 4] = lo; }
     }
@@ -178,6 +189,65 @@ __global__ __launch_bounds__(256) void k_quantize_minmax(const float4* __restric
             alpha[(int64_t)row * bpr + blk] = as[t >> 4][t & 15];
             beta[(int64_t)row * bpr + blk] = bs[t >> 4][t & 15];
         }
+    }
+}
+
+// Both quantizers on 8 x 8 blocks (Sec. 3.3: block quantization "of 4 x 8 or 8 x 8"): a block is 8 output
+// rows x 8 inputs, scale index (n/8)*(d_in/8) + k/8.  A workgroup owns 8 rows x 512 inputs = 64 blocks; in
+// pass u the 16 lanes of a DPP row hold block 16u + t/16 (lane q: row q/2, inputs 4*(q&1) .. +3), so a wave
+// reads 128 contiguous bytes of each of the 8 rows and the block reductions are the same row rotations.
+// Codes go through LDS as [row][256 bytes] and leave 16 bytes per thread in both layouts.
+template <bool MINMAX>
+__global__ __launch_bounds__(256) void k_quantize_tile8(const float4* __restrict__ W, int d_out, int d_in, Midpoints mp,
+                                                        uint8_t* __restrict__ codes, uint8_t* __restrict__ tiled,
+                                                        float* __restrict__ alpha, float* __restrict__ beta) {
+    __shared__ __align__(16) uint8_t cs[8][256];
+    __shared__ float as[64], bs[64];
+    const int ntj = (d_in + 511) / 512;
+    const int jt = blockIdx.x % ntj, row0 = (blockIdx.x / ntj) * 8, col0 = jt * 512;
+    const int t = threadIdx.x, q = t & 15, row = q >> 1, c4 = q & 1;
+    float4 wv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int col = col0 + (16 * u + (t >> 4)) * 8 + 4 * c4;
+        wv[u] = (col < d_in && row0 + row < d_out) ? W[((int64_t)(row0 + row) * d_in + col) >> 2] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const float4 w = wv[u];
+        const int j = 16 * u + (t >> 4);                    // block of the workgroup
+        uint32_t packed;
+        if constexpr (MINMAX) {
+            const float lo = group16_min(fminf(fminf(w.x, w.y), fminf(w.z, w.w)));
+            const float hi = group16_max(fmaxf(fmaxf(w.x, w.y), fmaxf(w.z, w.w)));
+            float al;
+            packed = codes4_minmax(w, lo, hi, al);
+            if (q == 0) { as[j] = al; bs[j] = lo; }
+        } else {
+            float a = fmaxf(fmaxf(fabsf(w.x), fabsf(w.y)), fmaxf(fabsf(w.z), fabsf(w.w)));
+            a = group16_max(a);
+            packed = codes4_codebook(w, a, mp);
+            if (q == 0) as[j] = a;
+        }
+        *reinterpret_cast<uint16_t*>(&cs[row][4 * j + 2 * c4]) = (uint16_t)packed;
+    }
+    __syncthreads();
+    const int bpr64 = d_in / kBlock;
+    if (t < 128) {
+        const int r = t >> 4, piece = t & 15;                // 16-byte piece of the row's 256 bytes (32 inputs)
+        if (row0 + r < d_out && col0 + 32 * piece < d_in)
+            *reinterpret_cast<uint4*>(codes + ((int64_t)(row0 + r) * d_in + col0) / 2 + 16 * piece) =
+                *reinterpret_cast<const uint4*>(&cs[r][16 * piece]);
+    } else if (tiled) {
+        const int tt = t - 128, ks = tt >> 4, r = (tt >> 1) & 7, half = tt & 1;   // 64-wide input step of the tile copy
+        if (row0 + r < d_out && col0 + 64 * ks < d_in)
+            *reinterpret_cast<uint4*>(tiled + tiled_run_offset(row0 + r, col0 / 64 + ks, bpr64) + half * 16) =
+                *reinterpret_cast<const uint4*>(&cs[r][32 * ks + 16 * half]);
+    }
+    if (t < 64 && col0 + 8 * t < d_in && row0 < d_out) {
+        const int64_t blk = (int64_t)(row0 / 8) * (d_in / 8) + col0 / 8 + t;
+        alpha[blk] = as[t];
+        if constexpr (MINMAX) beta[blk] = bs[t];
     }
 }
 
@@ -246,7 +316,8 @@ __global__ __launch_bounds__(256) void k_scales_reconstruct(const uint8_t* __res
 __global__ __launch_bounds__(256) void k_dequantize_bf16(const uint32_t* __restrict__ codes32,
                                                          const float* __restrict__ scales,
                                                          const float* __restrict__ beta, Codebook cb,
-                                                         int64_t n_words, uint4* __restrict__ out) {
+                                                         int64_t n_words, int words_per_row,
+                                                         uint4* __restrict__ out) {
     __shared__ float lut[16];
     if (threadIdx.x < 16) lut[threadIdx.x] = cb.c[threadIdx.x];
     __syncthreads();
@@ -254,6 +325,10 @@ __global__ __launch_bounds__(256) void k_dequantize_bf16(const uint32_t* __restr
     if (i >= n_words) return;
     uint32_t w = codes32[i];
     int64_t blk = i >> 3;    // 8 words of 8 codes per 64-block
+    if (words_per_row > 0) { // 8 x 8 blocks: a word is one row of block (n/8, word in row)
+        const int64_t n = i / words_per_row;
+        blk = (n >> 3) * words_per_row + (i - n * words_per_row);
+    }
     float a = scales[blk];
     float v[8];
     if (beta) {
@@ -298,12 +373,18 @@ int launch_prepack_codes(const uint8_t* codes, int d_out, int d_in, uint8_t* til
 }
 
 int launch_quantize_codebook(const float* W, int d_out, int d_in, const Codebook& cb, uint8_t* codes,
-                             uint8_t* tiled, float* absmax, hipStream_t st) {
+                             uint8_t* tiled, float* absmax, hipStream_t st, int block_rows) {
     Midpoints mp;
     for (int j = 0; j < 15; ++j) {
         volatile float sum = cb.c[j] + cb.c[j + 1];   // two separate fp32 roundings
         volatile float m = sum * 0.5f;
         mp.m[j] = m;
+    }
+    if (block_rows == 8) {
+        const unsigned grid8 = (unsigned)(((d_in + 511) / 512) * (d_out / 8));
+        hipLaunchKernelGGL(k_quantize_tile8<false>, dim3(grid8), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
+                           d_out, d_in, mp, codes, tiled, absmax, static_cast<float*>(nullptr));
+        return launch_status();
     }
     const int bpr = d_in / kBlock;
     const unsigned grid = (unsigned)(((bpr + kQBlocks - 1) / kQBlocks) * ((d_out + kQRows - 1) / kQRows));
@@ -313,7 +394,13 @@ int launch_quantize_codebook(const float* W, int d_out, int d_in, const Codebook
 }
 
 int launch_quantize_minmax(const float* W, int d_out, int d_in, uint8_t* codes, uint8_t* tiled, float* alpha,
-                           float* beta, hipStream_t st) {
+                           float* beta, hipStream_t st, int block_rows) {
+    if (block_rows == 8) {
+        const unsigned grid8 = (unsigned)(((d_in + 511) / 512) * (d_out / 8));
+        hipLaunchKernelGGL(k_quantize_tile8<true>, dim3(grid8), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
+                           d_out, d_in, Midpoints{}, codes, tiled, alpha, beta);
+        return launch_status();
+    }
     const int bpr = d_in / kBlock;
     const unsigned grid = (unsigned)(((bpr + kQBlocks - 1) / kQBlocks) * ((d_out + kQRows - 1) / kQRows));
     hipLaunchKernelGGL(k_quantize_minmax, dim3(grid), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
@@ -344,7 +431,7 @@ int launch_dequantize_bf16(const qblora_qweight& qw, const float* scales, qblora
     unsigned grid = (unsigned)((n_words + 255) / 256);
     hipLaunchKernelGGL(k_dequantize_bf16, dim3(grid), dim3(256), 0, st,
                        reinterpret_cast<const uint32_t*>(qw.codes), scales, qw.beta, cb, n_words,
-                       reinterpret_cast<uint4*>(Wt));
+                       qw.block_rows == 8 ? qw.d_in / 8 : 0, reinterpret_cast<uint4*>(Wt));
     return launch_status();
 }
 
