@@ -56,7 +56,7 @@ int check_qweight(const qblora_qweight* qw, bool need_codes, bool allow_tile8 = 
 }
 
 int check_layer(const qblora_qweight* qw, const qblora_adapter* ad) {
-    int rc = check_qweight(qw, true);
+    int rc = check_qweight(qw, true, true);
     if (rc) return rc;
     if (qw->d_out % 64 != 0) return QBLORA_ERR_SHAPE;      // contraction step of the transposed use
     if (ad && (ad->A || ad->B || ad->R)) {
@@ -291,6 +291,8 @@ int linear_fwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
     if (grouped) { sct.scale_codes = qw->scale_codes; sct.scale_step = qw->scale_step; sct.scale_mid = qw->scale_mid; }
     sct.scale_group = qw->scale_group; sct.d_out = qw->d_out; sct.d_in = qw->d_in; sct.out = ws.scales;
     g.scales = nullptr; g.scales_tiled = ws.scales;
+    g.block_rows = block_rows_of(qw);
+    if (g.block_rows == 8) { sct.out = nullptr; g.scales = qw->scales; g.scales_tiled = nullptr; }   // read in place
     const int op = scale_op_of(ad);
     const bool prep_adapter = adapted && op == QBLORA_OP_AVGPOOL_REPEAT;
     if ((rc = launch_adapter_prep(prep_adapter ? ad->A : nullptr, prep_adapter ? ad->B : nullptr, qw->d_in, qw->d_out,
@@ -353,6 +355,7 @@ int linear_bwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
 
     GemmDesc g{};
     g.qmode = 2;
+    g.block_rows = block_rows_of(qw);
     if (dX && (rc = resolve_scales(qw, ws.scales, st, &g.scales))) return rc;
     if (adapted) {
         const int R = ad->R;
@@ -459,7 +462,7 @@ int qblora_linear_bwd_saved(const qblora_qweight* qw, const qblora_adapter* ad, 
 namespace {
 
 int check_qa(const qblora_qweight* qw, const qblora_bf16* H, int32_t lam1, int32_t lam2) {
-    int rc = check_qweight(qw, true);
+    int rc = check_qweight(qw, true, true);
     if (rc) return rc;
     if (qw->d_out % 64 != 0) return QBLORA_ERR_SHAPE;
     if (!H) return QBLORA_ERR_NULL;
@@ -498,12 +501,12 @@ QaBwdSpace carve_qa_bwd(const qblora_qweight* qw, int lam1, int lam2, int64_t T,
 }  // namespace
 
 size_t qablora_linear_fwd_workspace_bytes(const qblora_qweight* qw, int32_t lambda1, int32_t lambda2, int64_t T) {
-    if (check_qweight(qw, false) || lambda1 <= 0 || lambda2 <= 0 || T < 0) return 0;
+    if (check_qweight(qw, false, true) || lambda1 <= 0 || lambda2 <= 0 || T < 0) return 0;
     return carve_qa_fwd(qw, lambda1, lambda2, T, nullptr).bytes;
 }
 
 size_t qablora_linear_bwd_workspace_bytes(const qblora_qweight* qw, int32_t lambda1, int32_t lambda2, int64_t T) {
-    if (check_qweight(qw, false) || lambda1 <= 0 || lambda2 <= 0 || T < 0) return 0;
+    if (check_qweight(qw, false, true) || lambda1 <= 0 || lambda2 <= 0 || T < 0) return 0;
     return carve_qa_bwd(qw, lambda1, lambda2, T, nullptr).bytes;
 }
 
@@ -526,6 +529,8 @@ int qablora_linear_fwd(const qblora_qweight* qw, const qblora_bf16* H, int32_t l
     sct.scales = grouped ? nullptr : qw->scales;
     if (grouped) { sct.scale_codes = qw->scale_codes; sct.scale_step = qw->scale_step; sct.scale_mid = qw->scale_mid; }
     sct.scale_group = qw->scale_group; sct.d_out = qw->d_out; sct.d_in = qw->d_in; sct.out = ws.scales;
+    const bool tile8 = block_rows_of(qw) == 8;               // 8 x 8 blocks: scales are read in place
+    if (tile8) sct.out = nullptr;
     if ((rc = launch_adapter_prep(H, H, I, J, J, 1, 1, ws.Ht, nullptr, nullptr, st, &sct))) return rc;
     // s * AvgPool_lambda1(X)
     if ((rc = launch_pool_rows(X, T, qw->d_in, lambda1, s / (float)lambda1, ws.P, nullptr, st))) return rc;
@@ -533,6 +538,7 @@ int qablora_linear_fwd(const qblora_qweight* qw, const qblora_bf16* H, int32_t l
     GemmDesc g{};
     g.qmode = 1;
     g.scales = nullptr; g.scales_tiled = ws.scales;
+    if (tile8) { g.scales = qw->scales; g.scales_tiled = nullptr; g.block_rows = 8; }
     g.X2 = ws.P; g.ldx2 = I; g.W2 = ws.Ht; g.ldw2 = I; g.K2 = I; g.div2 = lambda2;
     g.X1 = X; g.ldx1 = qw->d_in;
     g.codes = qw->codes; g.beta = qw->beta; g.d_out = qw->d_out; g.d_in = qw->d_in; g.cb = codebook_of(qw);
@@ -577,6 +583,7 @@ int qablora_linear_bwd(const qblora_qweight* qw, const qblora_bf16* H, int32_t l
     if (!dX) return QBLORA_OK;
     GemmDesc g{};
     g.qmode = 2;
+    g.block_rows = block_rows_of(qw);
     if ((rc = resolve_scales(qw, ws.scales, st, &g.scales))) return rc;
     g.X2 = ws.dVs; g.ldx2 = J; g.W2 = H; g.ldw2 = J; g.K2 = J; g.div2 = lambda1;
     g.X1 = dY; g.ldx1 = qw->d_out;

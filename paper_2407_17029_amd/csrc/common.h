@@ -99,9 +99,10 @@ struct GemmDesc {
     qblora_bf16* C_lo;                     // optional bf16 residual: bf16(value - bf16(value)), same shape
     float out_scale;
     int64_t M; int N;
+    int block_rows;            // rows of a quantization block: 0/1 = 64 inputs of one row, 8 = 8 rows x 8 inputs
 };
 int launch_gemm(const GemmDesc& d, hipStream_t st);
-// the quantized segments (qmode 1, 2) with a 4-wave 256x256 tile; called by launch_gemm
+// the quantized segments (qmode 1, 2) with an 8-wave 256x256 tile; called by launch_gemm
 int launch_qlinear(const GemmDesc& d, hipStream_t st);
 // narrow-output plain bf16 GEMM (qmode 0, N = inner rank); called by launch_gemm when it applies
 bool skinny_applies(const GemmDesc& d);

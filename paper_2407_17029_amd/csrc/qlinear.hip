@@ -63,16 +63,18 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
 }
 
 // codes / scales of one k-step held in registers: 32 weights per thread
-//   QMODE 1: half a stored row (16 bytes of codes), one scale
-//   QMODE 2: a patch of 4 stored rows x 8 columns (one dword per row), a scale per row
-template <int QMODE>
+//   QMODE 1: half a stored row (16 bytes of codes), one scale -- or, with 8 x 8 quantization blocks
+//            (BR = 8), one scale per code dword (8 inputs = one block column)
+//   QMODE 2: a patch of 4 stored rows x 8 columns (one dword per row), a scale per row (with BR = 8 the
+//            patch lies in one block and the four are equal)
+template <int QMODE, int BR>
 struct Staged {
     uint32_t cw[4];
-    float sc[QMODE == 2 ? 4 : 1];
-    float be[QMODE == 2 ? 4 : 1];
+    float sc[(QMODE == 2 || BR == 8) ? 4 : 1];
+    float be[(QMODE == 2 || BR == 8) ? 4 : 1];
 };
 
-template <int QMODE, bool BETA>
+template <int QMODE, bool BETA, int BR>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_qlinear(GemmDesc d) {
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* sX = smem;                                   // 2 tiles
@@ -198,20 +200,31 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
         qcol = n0 + 8 * (t & 31);                    // this thread's 8 stored columns (k of the layer)
         if (qcol > N - 8) qcol = N - 8;
     }
-    auto load_staged = [&](Staged<QMODE>& s, int step) __attribute__((always_inline)) {
+    auto load_staged = [&](Staged<QMODE, BR>& s, int step) __attribute__((always_inline)) {
         const int k0 = step * kBK;
         if constexpr (QMODE == 1) {
             const uint4 v = *reinterpret_cast<const uint4*>(fwd_codes + (int64_t)step * fwd_stride);
             s.cw[0] = v.x; s.cw[1] = v.y; s.cw[2] = v.z; s.cw[3] = v.w;
-            s.sc[0] = fwd_scales[(int64_t)step * fwd_scale_stride];
-            if constexpr (BETA) s.be[0] = beta[(int64_t)qrow * bpr + step];
+            if constexpr (BR == 8) {
+                // block columns 8*step + 4*half .. +3 of block row qrow/8: one scale per code dword
+                const int64_t b0 = (int64_t)(qrow >> 3) * (d_in >> 3) + 8 * step + 4 * (t & 1);
+                const float4 a4 = *reinterpret_cast<const float4*>(scales + b0);
+                s.sc[0] = a4.x; s.sc[1] = a4.y; s.sc[2] = a4.z; s.sc[3] = a4.w;
+                if constexpr (BETA) {
+                    const float4 b4 = *reinterpret_cast<const float4*>(beta + b0);
+                    s.be[0] = b4.x; s.be[1] = b4.y; s.be[2] = b4.z; s.be[3] = b4.w;
+                }
+            } else {
+                s.sc[0] = fwd_scales[(int64_t)step * fwd_scale_stride];
+                if constexpr (BETA) s.be[0] = beta[(int64_t)qrow * bpr + step];
+            }
         } else {
             const int nb = k0 + 4 * (t >> 5);        // 4 stored rows (contraction index)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int64_t n = nb + i;
                 s.cw[i] = *reinterpret_cast<const uint32_t*>(codes + n * (d_in / 2) + qcol / 2);
-                const int64_t blk = n * bpr + qcol / kBlock;
+                const int64_t blk = BR == 8 ? (n >> 3) * (d_in >> 3) + (qcol >> 3) : n * bpr + qcol / kBlock;
                 s.sc[i] = scales[blk];
                 if constexpr (BETA) s.be[i] = beta[blk];
             }
@@ -223,7 +236,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     //   QMODE 2: piece p = bytes 2p, 2p+1 (columns 4p..4p+3) of each of the 4 stored rows of the patch
     //            -> 8-byte halves of LDS rows 8*kg+4p .. +3 (packing down the columns transposes).
     const uint32_t table_lane = lds_address(sT) - lds_address(smem) + ((lane & 15) << 3);
-    auto table_offsets = [&](const Staged<QMODE>& s, int p, uint32_t (&li)[8]) __attribute__((always_inline)) {
+    auto table_offsets = [&](const Staged<QMODE, BR>& s, int p, uint32_t (&li)[8]) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             // QMODE 1: i = 4*(dword in piece) + byte;  QMODE 2: i = 4*(byte in piece) + row
@@ -237,12 +250,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
         for (int i = 0; i < 8; ++i) lv[i] = *reinterpret_cast<const float2*>(smem + li[i]);
     };
-    auto finish_piece = [&](const Staged<QMODE>& s, int p, const float2 (&lv)[8], unsigned char* tile)
+    auto finish_piece = [&](const Staged<QMODE, BR>& s, int p, const float2 (&lv)[8], unsigned char* tile)
         __attribute__((always_inline)) {
         float lo[8], hi[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int si = QMODE == 1 ? 0 : (i & 3);
+            const int si = QMODE == 2 ? (i & 3) : (BR == 8 ? 2 * p + (i >> 2) : 0);
             lo[i] = BETA ? __fmaf_rn(lv[i].x, s.sc[si], s.be[si]) : __fmul_rn(lv[i].x, s.sc[si]);
             hi[i] = BETA ? __fmaf_rn(lv[i].y, s.sc[si], s.be[si]) : __fmul_rn(lv[i].y, s.sc[si]);
         }
@@ -270,7 +283,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
             }
         }
     };
-    auto dequant_store = [&](const Staged<QMODE>& s, unsigned char* tile) __attribute__((always_inline)) {
+    auto dequant_store = [&](const Staged<QMODE, BR>& s, unsigned char* tile) __attribute__((always_inline)) {
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
             uint32_t li[8];
@@ -307,7 +320,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     // dq: dequantize `sdq` into bw_next during this step; has_next: a step follows (its tiles are in
     // bx_next / bw_next once the barrier is passed).  Both are literal `true` in the steady state.
     auto run_step = [&](const unsigned char* bx, const unsigned char* bw, const unsigned char* bx_next,
-                        unsigned char* bw_next, const bool dq, const Staged<QMODE>& sdq, const bool has_next,
+                        unsigned char* bw_next, const bool dq, const Staged<QMODE, BR>& sdq, const bool has_next,
                         const bool refill, const int step2, const int buf2) __attribute__((always_inline)) {
         float2 lv[2][8];
         uint32_t li[8];
@@ -343,7 +356,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     // ---- main loop ---------------------------------------------------------------------------------
     // Invariant at the top of step s: tile buffers s&1 hold step s and fragment set 0 holds its first
     // quarter; st[(s+1)&1] holds the codes of step s+1 (if that is a quantized step).
-    Staged<QMODE> st[2];
+    Staged<QMODE, BR> st[2];
     if (nsteps > 0) {
         issue_copies(0, 0);
         int issued = 0;                                    // copies are in flight or done for steps <= issued
@@ -420,10 +433,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     }
 }
 
-template <int QMODE, bool BETA>
+template <int QMODE, bool BETA, int BR>
 int launch_cfg(const GemmDesc& d, hipStream_t st) {
     constexpr size_t smem = 4 * kTileBytes + kTableBytes;
-    auto kern = k_qlinear<QMODE, BETA>;
+    auto kern = k_qlinear<QMODE, BETA, BR>;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -442,8 +455,17 @@ int launch_cfg(const GemmDesc& d, hipStream_t st) {
 int launch_qlinear(const GemmDesc& d, hipStream_t st) {
     if (d.M <= 0 || d.N <= 0) return QBLORA_OK;
     if (d.out_f32 || d.C2 || d.C_lo) return QBLORA_ERR_UNSUPPORTED;
-    if (d.qmode == 1) return d.beta ? launch_cfg<1, true>(d, st) : launch_cfg<1, false>(d, st);
-    if (d.qmode == 2) return d.beta ? launch_cfg<2, true>(d, st) : launch_cfg<2, false>(d, st);
+    if (d.block_rows == 8) {
+        // scales / offsets are read as 16-byte groups of 4 block columns; tile-ordered scales do not exist
+        if (d.scales_tiled || !d.scales || d.d_out % 8 != 0 || (reinterpret_cast<uintptr_t>(d.scales) & 15) ||
+            (reinterpret_cast<uintptr_t>(d.beta) & 15))
+            return QBLORA_ERR_UNSUPPORTED;
+        if (d.qmode == 1) return d.beta ? launch_cfg<1, true, 8>(d, st) : launch_cfg<1, false, 8>(d, st);
+        if (d.qmode == 2) return d.beta ? launch_cfg<2, true, 8>(d, st) : launch_cfg<2, false, 8>(d, st);
+        return QBLORA_ERR_UNSUPPORTED;
+    }
+    if (d.qmode == 1) return d.beta ? launch_cfg<1, true, 1>(d, st) : launch_cfg<1, false, 1>(d, st);
+    if (d.qmode == 2) return d.beta ? launch_cfg<2, true, 1>(d, st) : launch_cfg<2, false, 1>(d, st);
     return QBLORA_ERR_UNSUPPORTED;
 }
 

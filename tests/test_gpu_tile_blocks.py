@@ -81,3 +81,76 @@ def test_errors(qb, oracle, codebook):
         qb.qblora_quantize_blockwise(W[:60].contiguous(), 64, qb.QUANT_MINMAX_INT4, block_rows=8)
     with pytest.raises(qb.QBLoRAError):
         qb.qblora_quantize_blockwise(W, 64, qb.QUANT_ABSMAX_CODEBOOK, codebook, qb.SCALES_E4M3_GROUPED, block_rows=8)
+
+
+def _layer(qb, oracle, codebook, seed, T, d_out, d_in, R, lam1, lam2, minmax):
+    from gpu_util import f32_to_dev, to_np, bf16_to_dev
+    L = synth.make_layer(seed, T, d_out, d_in, max(R, 8), lam1, lam2)
+    if minmax:
+        qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 64, qb.QUANT_MINMAX_INT4, block_rows=8)
+        cb = synth.codebook_int4()
+    else:
+        qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 64, qb.QUANT_ABSMAX_CODEBOOK, codebook, block_rows=8)
+        cb = codebook
+    torch.cuda.synchronize()
+    beta = None if qw.beta is None else to_np(qw.beta)
+    Wt = oracle.dequantize_tile(to_np(qw.codes), to_np(qw.scales), beta, cb, 8, 8, 2)      # the bf16 compute weight
+    return L, qw, Wt, bf16_to_dev(L.X), bf16_to_dev(L.dY)
+
+
+LAYER_CASES = [
+    # T, d_out, d_in, R, lam1, lam2, s, minmax
+    (256, 512, 512, 32, 2, 2, 1.0, False),
+    (300, 320, 192, 16, 2, 2, 0.25, True),          # ragged token count, partial tiles in every dimension
+    (77, 576, 832, 64, 4, 8, 2.0, False),
+    (513, 512, 1024, 128, 8, 8, 1.0, True),
+]
+
+
+@pytest.mark.parametrize("T,d_out,d_in,R,lam1,lam2,s,minmax", LAYER_CASES)
+def test_two_matrix_layer_on_8x8_blocks(qb, oracle, codebook, T, d_out, d_in, R, lam1, lam2, s, minmax):
+    from gpu_util import assert_close_bf16, assert_close_f32, adapter_to_dev
+    print(f"case 8x8 layer T={T} {d_out}x{d_in} R={R} lam=({lam1},{lam2}) minmax={minmax}", flush=True)
+    L, qw, Wt, X, dY = _layer(qb, oracle, codebook, 1500 + T, T, d_out, d_in, R, lam1, lam2, minmax)
+    ad = adapter_to_dev(L, lam1, lam2, s)
+    Y = qb.qblora_linear_fwd(qw, ad, X)
+    dX, dA, dB = qb.qblora_linear_bwd(qw, ad, X, dY)
+    Y0 = qb.qblora_linear_fwd(qw, None, X)
+    torch.cuda.synchronize()
+    assert_close_bf16(Y, oracle.forward(Wt, L.X, L.A, L.B, lam1, lam2, s), "Y")
+    assert_close_bf16(Y0, oracle.forward(Wt, L.X, None, None, 1, 1, 0.0), "Y base")
+    rX, rA, rB = oracle.backward(Wt, L.X, L.dY, L.A, L.B, lam1, lam2, s)
+    assert_close_bf16(dX, rX, "dX")
+    assert_close_f32(dA, rA, "dA")
+    assert_close_f32(dB, rB, "dB")
+
+
+@pytest.mark.parametrize("T,d_out,d_in,lam1,lam2", [(200, 512, 512, 8, 8), (77, 320, 896, 16, 8)])
+def test_quantization_aware_loop_on_8x8_blocks(qb, oracle, T, d_out, d_in, lam1, lam2):
+    """Sec. 3.3 end to end: single-matrix adapter on an INT4 base with 8 x 8 blocks (forward and backward
+    against the oracle), offset-shift merge, and the merged INT4 layer reproduces the adapted layer."""
+    from gpu_util import bf16_to_dev, f32_to_dev, to_np, assert_close_bf16, assert_close_f32, bf16_to_f64
+    s = 0.75
+    L, qw, Wt, X, dY = _layer(qb, oracle, None, 1600 + T, T, d_out, d_in, 8, lam1, lam2, True)
+    Hb = synth.f32_to_bf16_bits((np.random.default_rng(1600 + T).standard_normal((d_in // lam1, d_out // lam2)) * 0.02)
+                                .astype(np.float32))
+    H = bf16_to_dev(Hb)
+    Y = qb.qablora_linear_fwd(qw, H, lam1, lam2, s, X)
+    dX, dH = qb.qablora_linear_bwd(qw, H, lam1, lam2, s, X, dY)
+    torch.cuda.synchronize()
+    assert_close_bf16(Y, oracle.qa_forward(Wt, L.X, Hb, lam1, lam2, s), "Y")
+    rX, rH = oracle.qa_backward(Wt, L.X, L.dY, Hb, lam1, lam2, s)
+    assert_close_bf16(dX, rX, "dX")
+    assert_close_f32(dH, rH, "dH")
+    # merge: beta' = beta + s*H/lambda1, codes and alpha untouched; then plain INT4 forward
+    merged = qb.qablora_merge_quantize(qw, H.float().contiguous(), lam1, lam2, s, qb.MERGE_BETA_SHIFT)
+    Ym = qb.qblora_linear_fwd(merged, None, X)
+    torch.cuda.synchronize()
+    Wm = oracle.dequantize_tile(to_np(merged.codes), to_np(merged.scales), to_np(merged.beta), synth.codebook_int4(), 8, 8, 2)
+    assert_close_bf16(Ym, oracle.forward(Wm, L.X, None, None, 1, 1, 0.0), "Y merged")
+    # the merged layer against the adapted layer: they differ by the bf16 rounding of the merged weight only
+    ref = oracle.qa_forward(oracle.dequantize_tile(to_np(qw.codes), to_np(qw.scales), to_np(qw.beta), synth.codebook_int4(), 8, 8, 0),
+                            L.X, Hb, lam1, lam2, s)
+    err = np.abs(bf16_to_f64(Ym) - ref)
+    rms = np.sqrt((ref ** 2).mean())
+    assert np.sqrt((err ** 2).mean()) <= 5e-3 * rms and err.max() <= 4e-2 * rms
