@@ -691,8 +691,12 @@ DecodePack carve_pack(const qblora_qweight* qw, void* base) {
     DecodePack p{};
     const size_t rows = (size_t)((qw->d_out + 255) / 256) * 256, bpr = (size_t)(qw->d_in / qw->block);
     p.codes = c.take<uint8_t>(rows * bpr * 32);
-    p.scales = c.take<float>(rows * bpr);
-    if (qw->beta) p.beta = c.take<float>(rows * bpr);
+    if (block_rows_of(qw) == 8) {            // scales and offsets of 8 x 8 blocks are read where they are
+        p.scales = qw->scales; p.beta = qw->beta;
+    } else {
+        p.scales = c.take<float>(rows * bpr);
+        if (qw->beta) p.beta = c.take<float>(rows * bpr);
+    }
     p.bytes = c.off;
     return p;
 }
@@ -700,17 +704,18 @@ DecodePack carve_pack(const qblora_qweight* qw, void* base) {
 }  // namespace
 
 size_t qblora_decode_pack_bytes(const qblora_qweight* qw) {
-    if (check_qweight(qw, false)) return 0;
+    if (check_qweight(qw, false, true)) return 0;
     return carve_pack(qw, nullptr).bytes;
 }
 
 int qblora_decode_pack(const qblora_qweight* qw, void* pack, void* stream) {
-    int rc = check_qweight(qw, true);
+    int rc = check_qweight(qw, true, true);
     if (rc) return rc;
     if (!pack) return QBLORA_ERR_NULL;
     hipStream_t st = as_stream(stream);
     DecodePack p = carve_pack(qw, pack);
     if ((rc = launch_prepack_codes(qw->codes, qw->d_out, qw->d_in, p.codes, st))) return rc;
+    if (block_rows_of(qw) == 8) return QBLORA_OK;
     ScaleTiling sct{};
     const bool grouped = qw->scale_mode == QBLORA_SCALES_E4M3_GROUPED;
     sct.scales = grouped ? nullptr : qw->scales;
@@ -728,13 +733,13 @@ int qblora_decode_pack(const qblora_qweight* qw, void* pack, void* stream) {
 }
 
 size_t qblora_linear_decode_workspace_bytes(const qblora_qweight* qw) {
-    if (check_qweight(qw, false)) return 0;
+    if (check_qweight(qw, false, true)) return 0;
     return qw->scale_mode == QBLORA_SCALES_E4M3_GROUPED ? align_up(sizeof(float) * (size_t)n_blocks(qw)) : 0;
 }
 
 int qblora_linear_decode(const qblora_qweight* qw, const void* pack, const qblora_bf16* X, int32_t T, qblora_bf16* Y,
                          void* workspace, size_t workspace_bytes, void* stream) {
-    int rc = check_qweight(qw, true);
+    int rc = check_qweight(qw, true, true);
     if (rc) return rc;
     if (T < 0 || T > 16) return QBLORA_ERR_SHAPE;
     if (T == 0) return QBLORA_OK;
@@ -745,13 +750,15 @@ int qblora_linear_decode(const qblora_qweight* qw, const void* pack, const qblor
     hipStream_t st = as_stream(stream);
     if (pack) {
         DecodePack p = carve_pack(qw, const_cast<void*>(pack));
-        return launch_w4_decode(p.codes, p.scales, p.beta, codebook_of(qw), 1, qw->d_out, qw->d_in, X, T, Y, st);
+        return launch_w4_decode(p.codes, p.scales, p.beta, codebook_of(qw), 1, qw->d_out, qw->d_in, X, T, Y, st,
+                                block_rows_of(qw));
     }
     const float* scales = nullptr;
     const size_t need = qblora_linear_decode_workspace_bytes(qw);
     if (need > 0 && (!workspace || workspace_bytes < need)) return QBLORA_ERR_WORKSPACE;
     if ((rc = resolve_scales(qw, static_cast<float*>(workspace), st, &scales))) return rc;
-    return launch_w4_decode(qw->codes, scales, qw->beta, codebook_of(qw), 0, qw->d_out, qw->d_in, X, T, Y, st);
+    return launch_w4_decode(qw->codes, scales, qw->beta, codebook_of(qw), 0, qw->d_out, qw->d_in, X, T, Y, st,
+                            block_rows_of(qw));
 }
 
 }  // extern "C"

@@ -145,7 +145,7 @@ struct MergeDesc {
 int launch_merge_requant(const MergeDesc& d, hipStream_t st);
 int launch_merge_bf16(const MergeDesc& d, hipStream_t st);
 int launch_w4_decode(const uint8_t* codes, const float* scales, const float* beta, const Codebook& cb, int tiled,
-                     int d_out, int d_in, const qblora_bf16* X, int T, qblora_bf16* Y, hipStream_t st);
+                     int d_out, int d_in, const qblora_bf16* X, int T, qblora_bf16* Y, hipStream_t st, int block_rows = 1);
 int launch_merge_beta_shift(const MergeDesc& d, hipStream_t st);
 
 }  // namespace qblora

@@ -17,6 +17,11 @@
 // block's sums for its row and tokens 4*(l>>4) .. +3.  A third and fourth MFMA against a B operand of
 // ones give sum_k X[t,k] of the block when there are offsets.  Then one FMA per token applies alpha
 // (and one beta).  Any assignment of k to lanes is valid as long as both operands agree.
+//
+// With 8 x 8 quantization blocks (BR = 8) the scale changes every 8 inputs, inside the contraction of one
+// MFMA, so it cannot act on partial sums: there the lane builds the bf16 compute weight
+// bf16(fma(c, alpha, beta)) of its 16 inputs (two block columns; the byte table then holds fp32 pairs) and
+// the MFMAs accumulate directly -- the arithmetic of the training forward.
 #include "common.h"
 
 namespace qblora {
@@ -27,7 +32,9 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 struct DecodeDesc {
     const uint8_t* codes; const float* scales; const float* beta; Codebook cb;
-    int tiled;                 // the three arrays are in tile order (256-row tiles, rows of a block adjacent)
+    int tiled;                 // the three arrays are in tile order (256-row tiles, rows of a block adjacent);
+                               // with 8 x 8 blocks only the codes are, scales and offsets stay [d_out/8, d_in/8]
+    int block_rows;            // 1 or 8
     int d_out, d_in;
     const qblora_bf16* X; int T;
     qblora_bf16* Y;
@@ -38,12 +45,14 @@ constexpr int kReplicas = 16;               // copies of the byte -> (bf16 c[lo]
 struct DecodeRegs {                         // one group = 4 consecutive blocks of the lane's row
     uint2 c[4];                             // the lane's quarter of each block's codes: 16 codes
     float a[4], b[4];                       // scale and offset of each block
+    float2 a2[4], b2[4];                    // BR = 8: scales and offsets of the lane's two block columns
     uint4 x[4][2];                          // activations of the lane's token, 8 per MFMA
 };
 
-template <bool BETA>
+template <bool BETA, int BR>
 __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
-    __shared__ uint32_t pair[256 * kReplicas];          // entry e of replica q at e*kReplicas + q
+    // entry e of replica q at e*kReplicas + q: bf16 pairs (4 bytes), or fp32 pairs (8 bytes) for BR = 8
+    __shared__ __align__(8) uint32_t pair[256 * kReplicas * (BR == 8 ? 2 : 1)];
     __shared__ float red[4][4][64];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int nl = lane & 15, kg = lane >> 4;
@@ -51,13 +60,18 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
     const int n = min(n0 + nl, d.d_out - 1);                  // rows past the end are computed, not stored
     const int bpr = d.d_in / kBlock;
     const int groups = (bpr + 3) / 4;
-    {
+    if constexpr (BR == 8) {
+        const float2 e = make_float2(d.cb.c[t & 15], d.cb.c[t >> 4]);
+#pragma unroll
+        for (int q = 0; q < kReplicas; ++q) reinterpret_cast<float2*>(pair)[t * kReplicas + q] = e;
+    } else {
         const uint32_t e = pack_bf16(d.cb.c[t & 15], d.cb.c[t >> 4]);
 #pragma unroll
         for (int q = 0; q < kReplicas; ++q) pair[t * kReplicas + q] = e;
     }
     __syncthreads();
     const uint32_t* my_pair = pair + (lane & (kReplicas - 1));
+    const float2* my_pairf = reinterpret_cast<const float2*>(pair) + (lane & (kReplicas - 1));
 
     // Row-major arrays: a wave's load of one block touches 16 rows, i.e. 16 cache lines.  In tile order
     // (the layout of the forward kernel's code copy) the 16 rows of a block are adjacent: 4 lines of codes
@@ -67,6 +81,8 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
     const uint8_t* crow = d.codes + run * 32 + 8 * kg;
     const float* srow = d.scales + run;
     const float* brow = BETA ? d.beta + run : nullptr;
+    // BR = 8: block row n/8, block columns 8*b + 2*kg, +1 of 64-input step b
+    const int64_t run8 = (int64_t)(n >> 3) * (d.d_in >> 3) + 2 * kg;
     const int cstep = bstep * 32;
     const qblora_bf16* xrow = d.X + (int64_t)min(nl, d.T - 1) * d.d_in + 16 * kg;
 
@@ -80,13 +96,23 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
             const bool in = b < bpr;
             const int bc = in ? b : bpr - 1;
             r.c[q] = *reinterpret_cast<const uint2*>(crow + (int64_t)bc * cstep);
-            const float a = srow[(int64_t)bc * bstep];
-            r.a[q] = in ? a : 0.0f;
-            if constexpr (BETA) {
-                const float bt = brow[(int64_t)bc * bstep];
-                r.b[q] = in ? bt : 0.0f;
+            if constexpr (BR == 8) {
+                const float2 a = *reinterpret_cast<const float2*>(d.scales + run8 + 8 * bc);
+                r.a2[q] = in ? a : make_float2(0.0f, 0.0f);
+                r.b2[q] = make_float2(0.0f, 0.0f);
+                if constexpr (BETA) {
+                    const float2 bt = *reinterpret_cast<const float2*>(d.beta + run8 + 8 * bc);
+                    if (in) r.b2[q] = bt;
+                }
             } else {
-                r.b[q] = 0.0f;
+                const float a = srow[(int64_t)bc * bstep];
+                r.a[q] = in ? a : 0.0f;
+                if constexpr (BETA) {
+                    const float bt = brow[(int64_t)bc * bstep];
+                    r.b[q] = in ? bt : 0.0f;
+                } else {
+                    r.b[q] = 0.0f;
+                }
             }
 #pragma unroll
             for (int m = 0; m < 2; ++m) r.x[q][m] = *reinterpret_cast<const uint4*>(xrow + bc * kBlock + 8 * m);
@@ -102,10 +128,25 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
                                    my_pair[((w >> 16) & 0xffu) * kReplicas], my_pair[(w >> 24) * kReplicas]);
         return __builtin_bit_cast(bf16x8, v);
     };
+    // BR = 8: the 8 weights of one code dword (one block column) as bf16(fma(c, alpha, beta))
+    auto weights8 = [&](uint32_t w, float a, float b) __attribute__((always_inline)) {
+        uint32_t o[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float2 c = my_pairf[((w >> (8 * i)) & 0xffu) * kReplicas];
+            o[i] = BETA ? pack_bf16(__fmaf_rn(c.x, a, b), __fmaf_rn(c.y, a, b)) : pack_bf16(__fmul_rn(c.x, a), __fmul_rn(c.y, a));
+        }
+        return __builtin_bit_cast(bf16x8, make_uint4(o[0], o[1], o[2], o[3]));
+    };
     auto compute = [&](const DecodeRegs& r) __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const bf16x8 x0 = __builtin_bit_cast(bf16x8, r.x[q][0]), x1 = __builtin_bit_cast(bf16x8, r.x[q][1]);
+            if constexpr (BR == 8) {
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x0, weights8(r.c[q].x, r.a2[q].x, r.b2[q].x), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x1, weights8(r.c[q].y, r.a2[q].y, r.b2[q].y), acc, 0, 0, 0);
+                continue;
+            }
             f32x4_t blk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x0, operand(r.c[q].x), zero, 0, 0, 0);
             blk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x1, operand(r.c[q].y), blk, 0, 0, 0);
 #pragma unroll
@@ -160,11 +201,16 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
 }  // namespace
 
 int launch_w4_decode(const uint8_t* codes, const float* scales, const float* beta, const Codebook& cb, int tiled,
-                     int d_out, int d_in, const qblora_bf16* X, int T, qblora_bf16* Y, hipStream_t st) {
-    DecodeDesc d{codes, scales, beta, cb, tiled, d_out, d_in, X, T, Y};
+                     int d_out, int d_in, const qblora_bf16* X, int T, qblora_bf16* Y, hipStream_t st, int block_rows) {
+    DecodeDesc d{codes, scales, beta, cb, tiled, block_rows, d_out, d_in, X, T, Y};
     const dim3 grid((unsigned)((d_out + 15) / 16));
-    if (beta) hipLaunchKernelGGL(k_w4_decode<true>, grid, dim3(256), 0, st, d);
-    else hipLaunchKernelGGL(k_w4_decode<false>, grid, dim3(256), 0, st, d);
+    if (block_rows == 8) {
+        if (beta) hipLaunchKernelGGL((k_w4_decode<true, 8>), grid, dim3(256), 0, st, d);
+        else hipLaunchKernelGGL((k_w4_decode<false, 8>), grid, dim3(256), 0, st, d);
+        return launch_status();
+    }
+    if (beta) hipLaunchKernelGGL((k_w4_decode<true, 1>), grid, dim3(256), 0, st, d);
+    else hipLaunchKernelGGL((k_w4_decode<false, 1>), grid, dim3(256), 0, st, d);
     return launch_status();
 }
 

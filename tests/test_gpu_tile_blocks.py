@@ -154,3 +154,20 @@ def test_quantization_aware_loop_on_8x8_blocks(qb, oracle, T, d_out, d_in, lam1,
     err = np.abs(bf16_to_f64(Ym) - ref)
     rms = np.sqrt((ref ** 2).mean())
     assert np.sqrt((err ** 2).mean()) <= 5e-3 * rms and err.max() <= 4e-2 * rms
+
+
+@pytest.mark.parametrize("T", [1, 5, 16])
+@pytest.mark.parametrize("d_out,d_in,minmax", [(512, 1024, True), (328, 832, True), (256, 512, False)])
+def test_small_batch_inference_on_8x8_blocks(qb, oracle, codebook, T, d_out, d_in, minmax):
+    """Merged-model inference (Sec. 3.3) on 8 x 8 blocks: the small-batch kernel contracts the bf16 compute
+    weight bf16(fma(c, alpha, beta)), like the training forward; with and without the tile-ordered code copy."""
+    from gpu_util import assert_close_bf16, to_np
+    print(f"case 8x8 decode T={T} {d_out}x{d_in} minmax={minmax}", flush=True)
+    L, qw, Wt, X, dY = _layer(qb, oracle, codebook, 1700 + T + d_out, T, d_out, d_in, 8, 1, 1, minmax)
+    Y = qb.qblora_linear_decode(qw, X)
+    pack = qb.qblora_decode_pack(qw)
+    Yp = qb.qblora_linear_decode(qw, X, pack=pack)
+    torch.cuda.synchronize()
+    ref = oracle.forward(Wt, L.X, None, None, 1, 1, 0.0)
+    assert_close_bf16(Y, ref, "Y")
+    assert torch.equal(Y, Yp)
