@@ -2,7 +2,7 @@
 """Per-kernel timings of the library beyond the benchmark step: the streaming kernels on the large layer
 shapes (where launch overhead no longer dominates) and the rows built next to the hot path.
 
-    python -m paper_2407_17029_amd.kernel_bench [merge] [quantize] [decode] [qablora]
+    python -m paper_2407_17029_amd.kernel_bench [merge] [quantize] [decode] [qablora] [tile8]
 
 Each measurement is one JSON line: back-to-back launches between two HIP events on the current stream
 (warm caches; the 256 MB last-level cache holds the smaller shapes), algorithmic bytes or flops as defined
@@ -114,12 +114,62 @@ def bench_qablora():
              frac_mfma=round(flops / (f + b) / 1e12 / MFMA_TFLOPS, 3))
 
 
+def bench_tile8():
+    """The quantization-aware loop on 8 x 8 quantization blocks (block 64 with lambda1 = lambda2 = 8): min-max INT4
+    quantizer, single-matrix forward / backward, the exact offset-shift merge, small-batch inference."""
+    T, d_out, d_in, l1, l2 = 8192, 4096, 4096, 8, 8
+    W = torch.randn(d_out, d_in, device=DEV) * 0.02
+    qw = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_MINMAX_INT4, block_rows=8, tiled=True)
+    q = qw.c_struct()
+    args = (qb._ptr(W), d_out, d_in, 64, qb.QUANT_MINMAX_INT4, None, qb.SCALES_FP32, C.byref(q), qb._stream())
+    s = timed(lambda: qb.lib().qblora_quantize_blockwise(*args))
+    nbytes = d_out * d_in * (4 + 0.5 + 8 / 64)
+    emit(kernel="quantize_minmax 8x8 blocks (+ tile-ordered code copy)", shape=[d_out, d_in], us=round(s * 1e6, 1),
+         GBps=round(nbytes / s / 1e9, 1), frac_hbm=round(nbytes / s / 1e9 / HBM_GBS, 3))
+    X = torch.randn(T, d_in, device=DEV).to(torch.bfloat16)
+    dY = torch.randn(T, d_out, device=DEV).to(torch.bfloat16)
+    Y = torch.empty_like(dY)
+    dX = torch.empty_like(X)
+    H = (torch.randn(d_in // l1, d_out // l2, device=DEV) * 0.02).to(torch.bfloat16)
+    dH = torch.empty(d_in // l1, d_out // l2, device=DEV)
+    f = timed(lambda: qb.qablora_linear_fwd(qw, H, l1, l2, 1.0, X, Y), iters=10)
+    b = timed(lambda: qb.qablora_linear_bwd(qw, H, l1, l2, 1.0, X, dY, True, True, dX, dH), iters=10)
+    flops = 4.0 * T * d_in * d_out + 6.0 * T * (d_in // l1) * (d_out // l2)
+    emit(kernel="qablora_fwd+bwd 8x8 blocks", shape=[d_out, d_in], T=T, lam=[l1, l2], fwd_us=round(f * 1e6, 1),
+         bwd_us=round(b * 1e6, 1), TFLOPs=round(flops / (f + b) / 1e12, 1),
+         frac_mfma=round(flops / (f + b) / 1e12 / MFMA_TFLOPS, 3))
+    Hf = H.float().contiguous()
+    merged = qb.qablora_merge_quantize(qw, Hf, l1, l2, 1.0, qb.MERGE_BETA_SHIFT)
+    bq, o = qw.c_struct(), merged.c_struct()
+    margs = (C.byref(bq), qb._ptr(Hf), l1, l2, C.c_float(1.0), qb.MERGE_BETA_SHIFT, C.byref(o), qb._stream())
+    s = timed(lambda: qb.lib().qablora_merge_quantize(*margs))
+    nb = d_out * d_in // 64
+    nbytes = d_out * d_in * 0.5 * 2 + nb * 4 * 4 + Hf.numel() * 4           # codes and alpha copied, beta shifted
+    emit(kernel="merge_beta_shift 8x8 blocks (codes + alpha copied)", shape=[d_out, d_in], us=round(s * 1e6, 1),
+         GBps=round(nbytes / s / 1e9, 1), frac_hbm=round(nbytes / s / 1e9 / HBM_GBS, 3))
+    for d_out2, d_in2 in ((4096, 4096), (22016, 8192)):
+        W2 = torch.randn(d_out2, d_in2, device=DEV) * 0.02
+        q2 = qb.qblora_quantize_blockwise(W2, 64, qb.QUANT_MINMAX_INT4, block_rows=8, tiled=False)
+        pack = qb.qblora_decode_pack(q2)
+        for Tn in (1, 16):
+            Xs = torch.randn(Tn, d_in2, device=DEV).to(torch.bfloat16)
+            Ys = torch.empty(Tn, d_out2, dtype=torch.bfloat16, device=DEV)
+            qs = q2.c_struct()
+            dargs = (C.byref(qs), qb._ptr(pack), qb._ptr(Xs), Tn, qb._ptr(Ys), None, 0, qb._stream())
+            s = timed(lambda: qb.lib().qblora_linear_decode(*dargs), iters=50)
+            nbytes = d_out2 * d_in2 * (0.5 + 8 / 64) + 2 * Tn * (d_in2 + d_out2)
+            emit(kernel="w4_decode 8x8 blocks", layout="packed", shape=[d_out2, d_in2], T=Tn, us=round(s * 1e6, 1),
+                 GBps=round(nbytes / s / 1e9, 1), frac_hbm=round(nbytes / s / 1e9 / HBM_GBS, 3))
+        del W2, q2, pack
+
+
 def main(argv):
     qb.lib()
     torch.cuda.set_device(0)
-    what = argv or ["quantize", "merge", "decode", "qablora"]
+    what = argv or ["quantize", "merge", "decode", "qablora", "tile8"]
     for w in what:
-        {"quantize": bench_quantize, "merge": bench_merge, "decode": bench_decode, "qablora": bench_qablora}[w]()
+        {"quantize": bench_quantize, "merge": bench_merge, "decode": bench_decode, "qablora": bench_qablora,
+         "tile8": bench_tile8}[w]()
     return 0
 
 
