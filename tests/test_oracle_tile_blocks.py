@@ -1,6 +1,7 @@
 """Pins for the oracle's two-dimensional quantization blocks (Sec. 3.3: blocks "of 4 x 8 or 8 x 8") and the
 exact offset-shift merge they allow at lambda1 = lambda2 = 8 (Alg. 2 get_new_beta; ablation "The balancing
-factor of QA-BLoRA")."""
+factor of QA-BLoRA").  A block of lambda1 inputs x lambda2 outputs is br = lambda2 rows x bc = lambda1 columns
+of the stored [d_out, d_in] weight: block size 32 with (lambda1, lambda2) = (4, 8) is br = 8, bc = 4."""
 import numpy as np
 import pytest
 
@@ -27,7 +28,7 @@ def test_one_row_blocks_are_the_row_segment_functions(oracle, codebook):
                               oracle.dequantize_tile(m0[0], m0[1], m0[2], synth.codebook_int4(), 1, 64, mode))
 
 
-@pytest.mark.parametrize("br,bc", [(8, 8), (4, 8)])
+@pytest.mark.parametrize("br,bc", [(8, 8), (4, 8), (8, 4)])
 def test_tile_quantizers_against_numpy_on_gathered_blocks(oracle, codebook, br, bc):
     """Scales are the per-block reductions; codes are the brute-force nearest entry (codebook) and the Eq. 1
     rounding (min-max) evaluated on the gathered block with its own scale."""
@@ -70,7 +71,7 @@ def test_tile_dequantize_closed_form(oracle):
         np.abs(W1 - Wd).max() <= 1e-7                      # fused multiply-add: within one fp32 rounding
 
 
-@pytest.mark.parametrize("lam1,lam2,br,bc", [(8, 8, 8, 8), (8, 8, 4, 8), (16, 8, 8, 8)])
+@pytest.mark.parametrize("lam1,lam2,br,bc", [(8, 8, 8, 8), (8, 8, 4, 8), (16, 8, 8, 8), (4, 8, 8, 4)])
 def test_offset_shift_merge_is_exact_on_aligned_tiles(oracle, lam1, lam2, br, bc):
     """get_new_beta: every block sits in one adapter tile, so the merged INT4 weight is w~ + s*dW exactly (up
     to the fp32 rounding of beta + delta), with the codes and alpha untouched."""
