@@ -1,8 +1,8 @@
 // Block-wise quantizers and the standalone dequantizer (Eq. 1, Sec. 3.1) for gfx950.
 //
-// Both quantizers are HBM-streaming kernels: a thread owns 4 consecutive fp32 weights (one
-// 16-byte load), 16 lanes own one 64-wide block and reduce its absmax / min / max with
-// cross-lane shuffles; the codes of a workgroup are gathered in LDS and stored 16 bytes per
+// Both quantizers are HBM-streaming kernels: a thread owns 16 consecutive fp32 weights (four
+// 16-byte loads), 4 lanes own one 64-wide block and reduce its absmax / min / max with
+// cross-lane swaps; the codes of a workgroup are gathered in LDS and stored 16 bytes per
 // thread.  All decision
 // arithmetic is written with explicit single-rounding intrinsics so that no FMA contraction
 // can change a code.
@@ -16,28 +16,20 @@ struct Midpoints {
     float m[15];   // (c_j + c_{j+1}) * 0.5 in fp32, computed on the host
 };
 
-// All-reduce over the 16 lanes of a DPP row (= one 64-wide block held as 16 float4): rotating the row by
-// 8, 4, 2, 1 lanes and combining leaves the result in every lane.  DPP keeps this in the vector ALU; the
-// generic lane shuffle would go through the LDS crossbar four times per block.
-template <int ROT>
-__device__ __forceinline__ float row_rotate(float v) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + ROT, 0xf, 0xf, false));
+// All-reduce over the 4 lanes of a quad (one block held as 4 x 16 weights): two DPP quad permutations and
+// combines leave the result in every lane; DPP keeps this in the vector ALU (the generic lane shuffle would go
+// through the LDS crossbar).
+template <int PERM>
+__device__ __forceinline__ float quad_swap(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), PERM, 0xf, 0xf, false));
 }
-
-__device__ __forceinline__ float group16_max(float v) {
-    v = fmaxf(v, row_rotate<8>(v));
-    v = fmaxf(v, row_rotate<4>(v));
-    v = fmaxf(v, row_rotate<2>(v));
-    v = fmaxf(v, row_rotate<1>(v));
-    return v;
+__device__ __forceinline__ float quad_max(float v) {
+    v = fmaxf(v, quad_swap<0xB1>(v));
+    return fmaxf(v, quad_swap<0x4E>(v));
 }
-
-__device__ __forceinline__ float group16_min(float v) {
-    v = fminf(v, row_rotate<8>(v));
-    v = fminf(v, row_rotate<4>(v));
-    v = fminf(v, row_rotate<2>(v));
-    v = fminf(v, row_rotate<1>(v));
-    return v;
+__device__ __forceinline__ float quad_min(float v) {
+    v = fminf(v, quad_swap<0xB1>(v));
+    return fminf(v, quad_swap<0x4E>(v));
 }
 
 // Four codes of one float4 against the block's absmax a: code = #{ j : w > t_j } with t_j = m_j * a.
@@ -85,11 +77,11 @@ __device__ __forceinline__ uint32_t codes4_minmax(const float4& w, float lo, flo
 }
 
 // Work split of both quantizers: a workgroup owns 4 consecutive weight rows x 16 consecutive 64-blocks
-// (4 x 4 KB of contiguous fp32 input).  Pass u of a thread takes float4 group t of row u, so 16 lanes
-// hold one block.  Codes (2 bytes per thread and pass) and block scales are collected in LDS and leave
-// as 16-byte stores: 512 contiguous bytes per row in the canonical layout, and -- because the 4 rows
-// are neighbours inside one 256-row tile -- 128 contiguous bytes per block column in the tile-ordered
-// copy.
+// (4 x 4 KB of contiguous fp32 input), wave u row u; a thread owns a quarter block (16 consecutive
+// weights), so the four lanes of a quad hold one block.  Codes (8 bytes per thread) and block scales are
+// collected in LDS and leave as 16-byte stores: 512 contiguous bytes per row in the canonical layout,
+// and -- because the 4 rows are neighbours inside one 256-row tile -- 128 contiguous bytes per block
+// column in the tile-ordered copy.
 constexpr int kQRows = 4, kQBlocks = 16;
 
 struct QuantTile {
@@ -105,7 +97,7 @@ __device__ __forceinline__ QuantTile quant_tile(int bpr) {
     return q;
 }
 
-// codes of the tile from LDS (cs[u][t] = 4 codes of float4 group t of row u) to both global layouts
+// codes of the tile from LDS (cs[u][g] = 4 codes of float4 group g of row u) to both global layouts
 __device__ __forceinline__ void store_tile_codes(const uint16_t (&cs)[kQRows][256], const QuantTile& q, int d_out, int bpr,
                                                  uint8_t* __restrict__ codes, uint8_t* __restrict__ tiled) {
     const int t = threadIdx.x;
@@ -124,78 +116,84 @@ __device__ __forceinline__ void store_tile_codes(const uint16_t (&cs)[kQRows][25
     }
 }
 
-// Absmax / codebook quantizer.
+// Absmax / codebook quantizer.  Wave u of the workgroup takes row u of the tile; a thread owns 16
+// consecutive weights (a quarter block, four 16-byte loads), so the 15 thresholds of its block are
+// computed once per thread and the block reduction is two quad swaps.
 __global__ __launch_bounds__(256) void k_quantize_codebook(const float4* __restrict__ W, int d_out, int bpr,
                                                            Midpoints mp, uint8_t* __restrict__ codes,
                                                            uint8_t* __restrict__ tiled, float* __restrict__ absmax) {
     __shared__ __align__(16) uint16_t cs[kQRows][256];
     __shared__ float as[kQRows][kQBlocks];
     const QuantTile q = quant_tile(bpr);
-    const int t = threadIdx.x;
-    const bool col_ok = q.blk0 + (t >> 4) < bpr;
-    // four independent 16-byte loads per thread are issued before any arithmetic (bytes in flight)
-    float4 wv[kQRows];
+    const int t = threadIdx.x, u = t >> 6, lane = t & 63, j = lane >> 2;
+    const int row = q.row0 + u;
+    const bool ok = row < d_out && q.blk0 + j < bpr;
+    const float4* src = W + ((int64_t)row * bpr + q.blk0) * 16 + lane * 4;
+    float4 wv[4];
 #pragma unroll
-    for (int u = 0; u < kQRows; ++u) {
-        const int row = q.row0 + u;
-        wv[u] = (col_ok && row < d_out) ? W[((int64_t)row * bpr + q.blk0) * 16 + t] : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
+    for (int i = 0; i < 4; ++i) wv[i] = ok ? src[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    float a = 0.0f;
 #pragma unroll
-    for (int u = 0; u < kQRows; ++u) {
-        const float4 w = wv[u];
-        float a = fmaxf(fmaxf(fabsf(w.x), fabsf(w.y)), fmaxf(fabsf(w.z), fabsf(w.w)));
-        a = group16_max(a);
-        cs[u][t] = (uint16_t)codes4_codebook(w, a, mp);
-        if ((t & 15) == 0) as[u][t >> 4] = a;
-    }
+    for (int i = 0; i < 4; ++i)
+        a = fmaxf(a, fmaxf(fmaxf(fabsf(wv[i].x), fabsf(wv[i].y)), fmaxf(fabsf(wv[i].z), fabsf(wv[i].w))));
+    a = quad_max(a);
+    uint32_t c[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) c[i] = codes4_codebook(wv[i], a, mp);
+    *reinterpret_cast<uint2*>(&cs[u][lane * 4]) = make_uint2(c[0] | (c[1] << 16), c[2] | (c[3] << 16));
+    if ((lane & 3) == 0) as[u][j] = a;
     __syncthreads();
     store_tile_codes(cs, q, d_out, bpr, codes, tiled);
     if (t < kQRows * kQBlocks) {
-        const int row = q.row0 + (t >> 4), blk = q.blk0 + (t & 15);
-        if (row < d_out && blk < bpr) absmax[(int64_t)row * bpr + blk] = as[t >> 4][t & 15];
+        const int r = q.row0 + (t >> 4), blk = q.blk0 + (t & 15);
+        if (r < d_out && blk < bpr) absmax[(int64_t)r * bpr + blk] = as[t >> 4][t & 15];
     }
 }
 
-// Min-max INT4 quantizer: alpha = (hi-lo)/15, beta = lo, code = rint((w-lo) * (15/(hi-lo))).
+// Min-max INT4 quantizer: alpha = (hi-lo)/15, beta = lo, code = rint((w-lo) * (15/(hi-lo))).  Same work
+// split as the codebook quantizer.
 __global__ __launch_bounds__(256) void k_quantize_minmax(const float4* __restrict__ W, int d_out, int bpr,
                                                          uint8_t* __restrict__ codes, uint8_t* __restrict__ tiled,
                                                          float* __restrict__ alpha, float* __restrict__ beta) {
     __shared__ __align__(16) uint16_t cs[kQRows][256];
     __shared__ float as[kQRows][kQBlocks], bs[kQRows][kQBlocks];
     const QuantTile q = quant_tile(bpr);
-    const int t = threadIdx.x;
-    const bool col_ok = q.blk0 + (t >> 4) < bpr;
-    float4 wv[kQRows];
+    const int t = threadIdx.x, u = t >> 6, lane = t & 63, j = lane >> 2;
+    const int row = q.row0 + u;
+    const bool ok = row < d_out && q.blk0 + j < bpr;
+    const float4* src = W + ((int64_t)row * bpr + q.blk0) * 16 + lane * 4;
+    float4 wv[4];
 #pragma unroll
-    for (int u = 0; u < kQRows; ++u) {
-        const int row = q.row0 + u;
-        wv[u] = (col_ok && row < d_out) ? W[((int64_t)row * bpr + q.blk0) * 16 + t] : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
+    for (int i = 0; i < 4; ++i) wv[i] = ok ? src[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    float lo = wv[0].x, hi = wv[0].x;
 #pragma unroll
-    for (int u = 0; u < kQRows; ++u) {
-        const float4 w = wv[u];
-        const float lo = group16_min(fminf(fminf(w.x, w.y), fminf(w.z, w.w)));
-        const float hi = group16_max(fmaxf(fmaxf(w.x, w.y), fmaxf(w.z, w.w)));
-        float al;
-        const uint32_t packed = codes4_minmax(w, lo, hi, al);
-        cs[u][t] = (uint16_t)packed;
-        if ((t & 15) == 0) { as[u][t >> 4] = al; bs[u][t >> 4] = lo; }
+    for (int i = 0; i < 4; ++i) {
+        lo = fminf(lo, fminf(fminf(wv[i].x, wv[i].y), fminf(wv[i].z, wv[i].w)));
+        hi = fmaxf(hi, fmaxf(fmaxf(wv[i].x, wv[i].y), fmaxf(wv[i].z, wv[i].w)));
     }
+    lo = quad_min(lo);
+    hi = quad_max(hi);
+    float al = 0.0f;
+    uint32_t c[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) c[i] = codes4_minmax(wv[i], lo, hi, al);
+    *reinterpret_cast<uint2*>(&cs[u][lane * 4]) = make_uint2(c[0] | (c[1] << 16), c[2] | (c[3] << 16));
+    if ((lane & 3) == 0) { as[u][j] = al; bs[u][j] = lo; }
     __syncthreads();
     store_tile_codes(cs, q, d_out, bpr, codes, tiled);
     if (t < kQRows * kQBlocks) {
-        const int row = q.row0 + (t >> 4), blk = q.blk0 + (t & 15);
-        if (row < d_out && blk < bpr) {
-            alpha[(int64_t)row * bpr + blk] = as[t >> 4][t & 15];
-            beta[(int64_t)row * bpr + blk] = bs[t >> 4][t & 15];
+        const int r = q.row0 + (t >> 4), blk = q.blk0 + (t & 15);
+        if (r < d_out && blk < bpr) {
+            alpha[(int64_t)r * bpr + blk] = as[t >> 4][t & 15];
+            beta[(int64_t)r * bpr + blk] = bs[t >> 4][t & 15];
         }
     }
 }
 
 // Both quantizers on 8 x 8 blocks (Sec. 3.3: block quantization "of 4 x 8 or 8 x 8"): a block is 8 output
-// rows x 8 inputs, scale index (n/8)*(d_in/8) + k/8.  A workgroup owns 8 rows x 512 inputs = 64 blocks; in
-// pass u the 16 lanes of a DPP row hold block 16u + t/16 (lane q: row q/2, inputs 4*(q&1) .. +3), so a wave
-// reads 128 contiguous bytes of each of the 8 rows and the block reductions are the same row rotations.
+// rows x 8 inputs, scale index (n/8)*(d_in/8) + k/8.  A workgroup owns 8 rows x 512 inputs = 64 blocks; the
+// four lanes of a quad hold block t/4, lane q of the quad its rows 2q and 2q+1 (two 16-byte loads each), so
+// a wave reads 512 contiguous bytes of each of the 8 rows and the block reduction is two quad swaps.
 // Codes go through LDS as [row][256 bytes] and leave 16 bytes per thread in both layouts.
 template <bool MINMAX>
 __global__ __launch_bounds__(256) void k_quantize_tile8(const float4* __restrict__ W, int d_out, int d_in, Midpoints mp,
@@ -205,32 +203,39 @@ __global__ __launch_bounds__(256) void k_quantize_tile8(const float4* __restrict
     __shared__ float as[64], bs[64];
     const int ntj = (d_in + 511) / 512;
     const int jt = blockIdx.x % ntj, row0 = (blockIdx.x / ntj) * 8, col0 = jt * 512;
-    const int t = threadIdx.x, q = t & 15, row = q >> 1, c4 = q & 1;
-    float4 wv[4];
+    const int t = threadIdx.x, j = t >> 2, q = t & 3;              // block of the workgroup, lane of its quad
+    const int col = col0 + 8 * j;
+    const bool ok = col < d_in && row0 < d_out;                    // d_out % 8 == 0: whole blocks are in or out
+    float4 wv[4];                                                  // [2*rr + c]: row 2q+rr, inputs 4c .. 4c+3
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int col = col0 + (16 * u + (t >> 4)) * 8 + 4 * c4;
-        wv[u] = (col < d_in && row0 + row < d_out) ? W[((int64_t)(row0 + row) * d_in + col) >> 2] : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
+    for (int i = 0; i < 4; ++i)
+        wv[i] = ok ? W[((int64_t)(row0 + 2 * q + (i >> 1)) * d_in + col + 4 * (i & 1)) >> 2] : make_float4(0.f, 0.f, 0.f, 0.f);
+    uint32_t c[4];
+    if constexpr (MINMAX) {
+        float lo = wv[0].x, hi = wv[0].x;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const float4 w = wv[u];
-        const int j = 16 * u + (t >> 4);                    // block of the workgroup
-        uint32_t packed;
-        if constexpr (MINMAX) {
-            const float lo = group16_min(fminf(fminf(w.x, w.y), fminf(w.z, w.w)));
-            const float hi = group16_max(fmaxf(fmaxf(w.x, w.y), fmaxf(w.z, w.w)));
-            float al;
-            packed = codes4_minmax(w, lo, hi, al);
-            if (q == 0) { as[j] = al; bs[j] = lo; }
-        } else {
-            float a = fmaxf(fmaxf(fabsf(w.x), fabsf(w.y)), fmaxf(fabsf(w.z), fabsf(w.w)));
-            a = group16_max(a);
-            packed = codes4_codebook(w, a, mp);
-            if (q == 0) as[j] = a;
+        for (int i = 0; i < 4; ++i) {
+            lo = fminf(lo, fminf(fminf(wv[i].x, wv[i].y), fminf(wv[i].z, wv[i].w)));
+            hi = fmaxf(hi, fmaxf(fmaxf(wv[i].x, wv[i].y), fmaxf(wv[i].z, wv[i].w)));
         }
-        *reinterpret_cast<uint16_t*>(&cs[row][4 * j + 2 * c4]) = (uint16_t)packed;
+        lo = quad_min(lo);
+        hi = quad_max(hi);
+        float al = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) c[i] = codes4_minmax(wv[i], lo, hi, al);
+        if (q == 0) { as[j] = al; bs[j] = lo; }
+    } else {
+        float a = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            a = fmaxf(a, fmaxf(fmaxf(fabsf(wv[i].x), fabsf(wv[i].y)), fmaxf(fabsf(wv[i].z), fabsf(wv[i].w))));
+        a = quad_max(a);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) c[i] = codes4_codebook(wv[i], a, mp);
+        if (q == 0) as[j] = a;
     }
+    *reinterpret_cast<uint32_t*>(&cs[2 * q][4 * j]) = c[0] | (c[1] << 16);
+    *reinterpret_cast<uint32_t*>(&cs[2 * q + 1][4 * j]) = c[2] | (c[3] << 16);
     __syncthreads();
     const int bpr64 = d_in / kBlock;
     if (t < 128) {
