@@ -24,6 +24,10 @@ struct Carver {
 };
 
 bool has_adapter(const qblora_adapter* ad) { return ad && ad->A && ad->B && ad->R > 0; }
+// Whether the narrow GEMM over `width` features takes the unexpanded adapter operand (pool / repeat factor 2)
+bool pooled_pair_operand(int64_t T, int R, int width, int lam) {
+    return lam == 2 && skinny_dup_applies(T, R, width, width / 2);
+}
 int scale_op_of(const qblora_adapter* ad) { return has_adapter(ad) ? ad->scale_op : QBLORA_OP_AVGPOOL_REPEAT; }
 // index map of an expanded operand for the compress / expand operator `op`
 int op_map(int op) { return op == QBLORA_OP_TRUNCATE_PAD0 ? MAP_FRONT : op == QBLORA_OP_SAMPLE_ZEROFILL ? MAP_STRIDE : MAP_DIV; }
@@ -295,8 +299,11 @@ int linear_fwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
     if (g.block_rows == 8) { sct.out = nullptr; g.scales = qw->scales; g.scales_tiled = nullptr; }   // read in place
     const int op = scale_op_of(ad);
     const bool prep_adapter = adapted && op == QBLORA_OP_AVGPOOL_REPEAT;
-    if ((rc = launch_adapter_prep(prep_adapter ? ad->A : nullptr, prep_adapter ? ad->B : nullptr, qw->d_in, qw->d_out,
-                                  adapted ? ad->R : 0, adapted ? ad->lambda1 : 1, adapted ? ad->lambda2 : 1,
+    // lambda1 = 2: A^T stays unexpanded and the narrow GEMM uses each of its columns for two adjacent k
+    const bool dup_a = prep_adapter && pooled_pair_operand(T, ad->R, qw->d_in, ad->lambda1);
+    if ((rc = launch_adapter_prep(prep_adapter ? ad->A : nullptr, prep_adapter ? ad->B : nullptr,
+                                  dup_a ? qw->d_in / 2 : qw->d_in, qw->d_out,
+                                  adapted ? ad->R : 0, adapted ? (dup_a ? 1 : ad->lambda1) : 1, adapted ? ad->lambda2 : 1,
                                   ws.At_x, ws.Bt, nullptr, st, &sct)))
         return rc;
     if (adapted && op != QBLORA_OP_AVGPOOL_REPEAT) {
@@ -312,6 +319,7 @@ int linear_fwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
         GemmDesc u{};
         u.qmode = 0;
         u.X2 = X; u.ldx2 = qw->d_in; u.W2 = ws.At_x; u.ldw2 = qw->d_in; u.K2 = qw->d_in; u.div2 = 1;
+        if (dup_a) { u.ldw2 = qw->d_in / 2; u.dup2 = 2; }
         qblora_bf16* su = saved ? saved : ws.U;               // kept for the backward: high part, then residual
         u.C = su; u.C_lo = saved ? saved + T * ad->R : nullptr;
         u.ldc = ad->R; u.out_scale = op ? ad->s : ad->s / (float)ad->lambda1; u.M = T; u.N = ad->R;
@@ -361,9 +369,14 @@ int linear_bwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
         const int R = ad->R;
         const int op = scale_op_of(ad);
         const int na = qw->d_in / ad->lambda1, nb = qw->d_out / ad->lambda2;
+        // lambda = 2: the narrow GEMMs read B (and A^T) unexpanded, each column serving two adjacent features
+        const bool dup_b = op == QBLORA_OP_AVGPOOL_REPEAT && pooled_pair_operand(T, R, qw->d_out, ad->lambda2) &&
+                           (reinterpret_cast<uintptr_t>(ad->B) & 15) == 0;      // B is copied in 16-byte chunks
+        const bool dup_a = op == QBLORA_OP_AVGPOOL_REPEAT && pooled_pair_operand(T, R, qw->d_in, ad->lambda1);
         if (op == QBLORA_OP_AVGPOOL_REPEAT) {
-            if ((rc = launch_adapter_prep(ad->A, ad->B, qw->d_in, qw->d_out, R, ad->lambda1, ad->lambda2,
-                                          (want_grads && !saved) ? ws.At_x : nullptr, nullptr, ws.Bx, st)))
+            if ((rc = launch_adapter_prep(ad->A, ad->B, dup_a ? qw->d_in / 2 : qw->d_in, qw->d_out, R,
+                                          dup_a ? 1 : ad->lambda1, ad->lambda2,
+                                          (want_grads && !saved) ? ws.At_x : nullptr, nullptr, dup_b ? nullptr : ws.Bx, st)))
                 return rc;
         } else {
             // Bx[j][n] = B[j][E-map(n)], A_op[k][j] = A[C-map(k)][j] (and At_x as in the forward), zeros elsewhere
@@ -379,6 +392,7 @@ int linear_bwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
         GemmDesc du{};
         du.qmode = 0;
         du.X2 = dY; du.ldx2 = qw->d_out; du.W2 = ws.Bx; du.ldw2 = qw->d_out; du.K2 = qw->d_out; du.div2 = 1;
+        if (dup_b) { du.W2 = ad->B; du.ldw2 = nb; du.dup2 = 2; }
         du.C = ws.dU; du.ldc = R; du.out_scale = ad->s; du.C2 = ws.dUs; du.c2_scale = op ? 1.0f : 1.0f / (float)ad->lambda1;
         du.C_lo = want_grads ? ws.dU_lo : nullptr;
         du.M = T; du.N = R;
@@ -389,6 +403,7 @@ int linear_bwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
                 GemmDesc u{};
                 u.qmode = 0;
                 u.X2 = X; u.ldx2 = qw->d_in; u.W2 = ws.At_x; u.ldw2 = qw->d_in; u.K2 = qw->d_in; u.div2 = 1;
+                if (dup_a) { u.ldw2 = qw->d_in / 2; u.dup2 = 2; }
                 u.C = ws.U; u.ldc = R; u.out_scale = op ? ad->s : ad->s / (float)ad->lambda1; u.M = T; u.N = R; u.C_lo = ws.U_lo;
                 if ((rc = launch_gemm(u, st))) return rc;
                 su = ws.U; su_lo = ws.U_lo;

@@ -100,12 +100,14 @@ struct GemmDesc {
     float out_scale;
     int64_t M; int N;
     int block_rows;            // rows of a quantization block: 0/1 = 64 inputs of one row, 8 = 8 rows x 8 inputs
+    int dup2;                  // qmode 0, narrow form only: 2 = W2 has K2/2 columns, column m serves k = 2m, 2m+1
 };
 int launch_gemm(const GemmDesc& d, hipStream_t st);
 // the quantized segments (qmode 1, 2) with an 8-wave 256x256 tile; called by launch_gemm
 int launch_qlinear(const GemmDesc& d, hipStream_t st);
 // narrow-output plain bf16 GEMM (qmode 0, N = inner rank); called by launch_gemm when it applies
 bool skinny_applies(const GemmDesc& d);
+bool skinny_dup_applies(int64_t M, int N, int K, int64_t ldw);
 int launch_skinny(const GemmDesc& d, hipStream_t st);
 
 // Token-contraction GEMM with split-T partials:  part[z][i][j] = sum_{t in slice z} L[t,i] * S[t,j]

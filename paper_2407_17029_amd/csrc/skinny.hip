@@ -41,12 +41,21 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
     return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
 }
 
-template <int BM, int BN, int kStages, int kSub, bool kSplitK>
+// kDup = 2: W is stored with K/2 columns and column m serves k = 2m and 2m+1 (the adapter operand
+// before its expansion along k: the pool over pairs of features is then folded into the fragment,
+// which halves the W stream from L2 and its LDS tile).  Only in the k-split form with two k-steps per
+// stage: the W columns of both k-steps are 128 contiguous bytes per row and form one tile per stage,
+// behind the stage's two X sub-tiles.
+template <int BM, int BN, int kStages, int kSub, bool kSplitK, int kDup = 1>
 __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
     static_assert(!kSplitK || (BM == 64 && BN == 64), "the k-split form is written for 64 x 64 tiles");
+    static_assert(kDup == 1 || (kDup == 2 && kSplitK && kSub == 2), "column duplication: k-split form, two k-steps per stage");
     // a stage holds kSub consecutive k-steps (sub-tiles of 64 k each): one barrier per kSub * 64 k
-    constexpr int kXBytes = BM * 128, kWBytes = BN * 128, kSubBytes = kXBytes + kWBytes, kStageBytes = kSub * kSubBytes;
-    constexpr int XC = BM / 32, WC = BN / 32;     // copies per wave and stage
+    constexpr int kXBytes = BM * 128, kWBytes = BN * 128 / kDup, kSubBytes = kXBytes + kWBytes, kStageBytes = kSub * kSubBytes;
+    constexpr int XC = BM / 32, WC = BN / 32;     // copies per wave and sub-tile (kDup = 2: W copies per stage)
+    // byte offsets of the X sub-tile u and of its W tile inside a stage
+    auto x_at = [](int u) { return kDup == 2 ? u * kXBytes : u * kSubBytes; };
+    auto w_at = [](int u) { return kDup == 2 ? kSub * kXBytes : u * kSubBytes + kXBytes; };
     constexpr int WN = BN / 32, WM = 4 / WN;      // waves along the columns / along the tokens
     constexpr int MF = BM / (32 * WM);            // 32-token blocks per wave
     static_assert(MF >= 1 && WN * WM == 4, "tile shape");
@@ -89,17 +98,18 @@ __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
     const qblora_bf16* const x_tile = X + m0 * ldx;
     const qblora_bf16* const w_tile = W + (int64_t)n0 * ldw;
     const uint32_t lds_x = __builtin_amdgcn_readfirstlane(lds_address(smem) + wave * (8 * XC) * 128);
-    const uint32_t lds_w = __builtin_amdgcn_readfirstlane(lds_address(smem) + kXBytes + wave * (8 * WC) * 128);
+    const uint32_t lds_w = __builtin_amdgcn_readfirstlane(lds_address(smem) + wave * (8 * WC) * 128);
     auto issue = [&](int step) __attribute__((always_inline)) {
         const uint32_t stage = (step % kStages) * kStageBytes;
 #pragma unroll
         for (int u = 0; u < kSub; ++u) {
             const qblora_bf16* xb = x_tile + (step * kSub + u) * kBK;
-            const qblora_bf16* wb = w_tile + (step * kSub + u) * kBK;
+            const qblora_bf16* wb = w_tile + (step * kSub + u) * (kBK / kDup);
 #pragma unroll
-            for (int i = 0; i < XC; ++i) copy16_to_lds(xb, xoff[i], lds_x + stage + u * kSubBytes + i * 8 * 128);
+            for (int i = 0; i < XC; ++i) copy16_to_lds(xb, xoff[i], lds_x + stage + x_at(u) + i * 8 * 128);
+            if (kDup == 2 && u > 0) continue;     // one W tile per stage: 64 stored columns = both k-steps
 #pragma unroll
-            for (int i = 0; i < WC; ++i) copy16_to_lds(wb, woff[i], lds_w + stage + u * kSubBytes + i * 8 * 128);
+            for (int i = 0; i < WC; ++i) copy16_to_lds(wb, woff[i], lds_w + stage + w_at(u) + i * 8 * 128);
         }
     };
 
@@ -122,12 +132,20 @@ __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
         if constexpr (kSplitK) {
 #pragma unroll
             for (int u = 0; u < kSub; ++u) {
-                const unsigned char* bx = smem + (step % kStages) * kStageBytes + u * kSubBytes;
-                const unsigned char* bw = bx + kXBytes;
+                const unsigned char* bx = smem + (step % kStages) * kStageBytes + x_at(u);
+                const unsigned char* bw = smem + (step % kStages) * kStageBytes + w_at(u);
                 bf16x8 wf[2], xf[2];
 #pragma unroll
                 for (int a = 0; a < 2; ++a) {
-                    wf[a] = *reinterpret_cast<const bf16x8*>(bw + swz(a * 32 + r, wave * 2 + hi));
+                    if constexpr (kDup == 2) {
+                        // stored columns 32*u + 8*wave + 4*hi .. +3 of row a*32 + r, each used for two k
+                        const uint2 v = *reinterpret_cast<const uint2*>(bw + swz(a * 32 + r, 4 * u + wave) + 8 * hi);
+                        const uint4 e = make_uint4(__builtin_amdgcn_perm(v.x, v.x, 0x01000100u), __builtin_amdgcn_perm(v.x, v.x, 0x03020302u),
+                                                   __builtin_amdgcn_perm(v.y, v.y, 0x01000100u), __builtin_amdgcn_perm(v.y, v.y, 0x03020302u));
+                        wf[a] = __builtin_bit_cast(bf16x8, e);
+                    } else {
+                        wf[a] = *reinterpret_cast<const bf16x8*>(bw + swz(a * 32 + r, wave * 2 + hi));
+                    }
                     xf[a] = *reinterpret_cast<const bf16x8*>(bx + swz(a * 32 + r, wave * 2 + hi));
                 }
 #pragma unroll
@@ -142,8 +160,8 @@ __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
         for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
             for (int u = 0; u < kSub; ++u) {
-                const unsigned char* bx = smem + (step % kStages) * kStageBytes + u * kSubBytes;
-                const unsigned char* bw = bx + kXBytes;
+                const unsigned char* bx = smem + (step % kStages) * kStageBytes + x_at(u);
+                const unsigned char* bw = smem + (step % kStages) * kStageBytes + w_at(u);
                 const bf16x8 wf = *reinterpret_cast<const bf16x8*>(bw + swz(wave_n * 32 + r, ks * 2 + hi));
 #pragma unroll
                 for (int b = 0; b < MF; ++b) {
@@ -159,7 +177,7 @@ __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
         if (i < nsteps) issue(i);
     int s = 0;
     for (; s + kAhead < nsteps; ++s) {
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm((kAhead - 1) * (XC + WC) * kSub));   // the younger stages may be in flight
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm((kAhead - 1) * (XC * kSub + WC * (kDup == 2 ? 1 : kSub))));   // the younger stages may be in flight
         __syncthreads();                          // stage s landed for all; everyone is done with step s-1
         issue(s + kAhead);                        // into the buffer step s-1 used
         compute(s);
@@ -233,16 +251,23 @@ __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
 }  // namespace
 
 // Whether launch_skinny can take this problem (otherwise the general tile kernel does).
+// Whether the narrow GEMM can take W with K/2 columns, each serving two adjacent k (GemmDesc::dup2 = 2): the
+// problem must be one the k-split 64 x 64 form with two k-steps per stage handles.
+bool skinny_dup_applies(int64_t M, int N, int K, int64_t ldw) {
+    const int64_t wgs = ((M + 63) / 64) * ((N + 127) / 128);
+    return wgs < 512 && N > 64 && N % 4 == 0 && N <= 512 && K % (2 * kBK) == 0 && ldw % 8 == 0;
+}
+
 bool skinny_applies(const GemmDesc& d) {
     return d.qmode == 0 && !d.out_f32 && d.div2 == 1 && d.N % 4 == 0 && d.N <= 512 && d.K2 > 0 &&
            d.K2 % kBK == 0 && d.M >= 1 && (int64_t)128 * d.ldw2 * 2 < (int64_t)1 << 31 &&
            (int64_t)64 * d.ldx2 * 2 < (int64_t)1 << 31;
 }
 
-template <int BM, int BN, int kStages, int kSub, bool kSplitK>
+template <int BM, int BN, int kStages, int kSub, bool kSplitK, int kDup = 1>
 int launch_skinny_cfg(const GemmDesc& d, hipStream_t st) {
-    constexpr size_t smem = kStages * kSub * (BM * 128 + BN * 128);
-    auto kern = k_skinny<BM, BN, kStages, kSub, kSplitK>;
+    constexpr size_t smem = kStages * kSub * (BM * 128 + BN * 128 / kDup);
+    auto kern = k_skinny<BM, BN, kStages, kSub, kSplitK, kDup>;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -260,6 +285,7 @@ int launch_skinny(const GemmDesc& d, hipStream_t st) {
     // 64 x 128 tiles once they alone fill the chip twice over; below that 64 x 64 tiles with a deep
     // ring (a narrower output has nothing to split: 32-token tiles, 128 columns)
     const int64_t wgs = ((d.M + 63) / 64) * ((d.N + 127) / 128);
+    if (d.dup2 == 2) return launch_skinny_cfg<64, 64, 5, 2, true, 2>(d, st);      // see skinny_dup_applies
     if (wgs >= 512) return launch_skinny_cfg<64, 128, 4, 1, false>(d, st);
     if (d.N > 64) {
         if (d.K2 % (2 * kBK) == 0) return launch_skinny_cfg<64, 64, 5, 2, true>(d, st);
