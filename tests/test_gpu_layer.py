@@ -45,6 +45,8 @@ CASES = [
     (77, 576, 832, 64, 4, 8, 2.0),           # lambda1 != lambda2 (the block-32 recommendation 4, 8)
     (513, 512, 1024, 128, 8, 8, 1.0),        # lambda 8, inner rank 128 (two K-extension steps)
     (130, 256, 256, 8, 1, 1, 1.0),           # lambda 1: plain LoRA, inner rank smaller than a K step
+    (333, 384, 640, 128, 2, 2, 0.5),         # lambda 2 with inner rank 128: the narrow GEMMs read A^T / B unexpanded; ragged T
+    (200, 512, 512, 96, 2, 2, 1.0),          # the same with a rank that leaves a partial column tile
 ]
 
 
