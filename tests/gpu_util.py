@@ -34,6 +34,52 @@ def qweight_from_oracle(codes, alpha, beta, codebook, block=64):
                       None if beta is None else f32_to_dev(beta))
 
 
+class OracleWeight:
+    """The quantized frozen weight as the oracle produces it from the seeded fp32 matrix: everything the
+    oracle is later fed comes from here, never from a device buffer."""
+
+    def __init__(self, oracle, W, codebook, minmax=False, grouped=False, block_rows=1):
+        self.block_rows = block_rows
+        self.sc = self.step = self.mid = None
+        if minmax:
+            self.cb = synth.codebook_int4()
+            if block_rows == 8:
+                self.codes, self.alpha, self.beta = oracle.quantize_minmax_tile(W, 8, 8)
+            else:
+                self.codes, self.alpha, self.beta = oracle.quantize_minmax(W, 64)
+        else:
+            self.cb = np.asarray(codebook, np.float32)
+            self.beta = None
+            if block_rows == 8:
+                self.codes, self.alpha = oracle.quantize_codebook_tile(W, 8, 8, codebook)
+            else:
+                self.codes, self.alpha = oracle.quantize_codebook(W, 64, codebook)
+        self.scales = self.alpha                     # what consumers read
+        if grouped:
+            self.sc, self.step, self.mid = oracle.scales_double_quantize(self.alpha.reshape(-1), 256)
+            self.scales = oracle.scales_double_dequantize(self.sc, self.step, self.mid, 256).reshape(self.alpha.shape)
+
+    def dequantize(self, oracle, mode):
+        if self.block_rows == 8:
+            return oracle.dequantize_tile(self.codes, self.scales, self.beta, self.cb, 8, 8, mode)
+        return oracle.dequantize(self.codes, self.scales, self.beta, self.cb, 64, mode)
+
+    def assert_same(self, qw):
+        """The device weight holds the oracle's bits (codes, scales, offsets, second-level scale codes)."""
+        bits = lambda a: np.ascontiguousarray(a).view(np.uint32)
+        assert np.array_equal(to_np(qw.codes), self.codes), "codes"
+        assert np.array_equal(bits(to_np(qw.scales)).reshape(-1), bits(self.alpha).reshape(-1)), "scales"
+        if self.beta is None:
+            assert qw.beta is None
+        else:
+            assert np.array_equal(bits(to_np(qw.beta)).reshape(-1), bits(self.beta).reshape(-1)), "offsets"
+        if self.sc is not None:
+            assert np.array_equal(to_np(qw.scale_codes), self.sc), "scale codes"
+            assert np.array_equal(bits(to_np(qw.scale_step)), bits(self.step)), "scale steps"
+            assert np.array_equal(bits(to_np(qw.scale_mid)), bits(self.mid)), "scale mids"
+        return self
+
+
 REL_TOL = 1e-2            # max |gpu - oracle| / rms(oracle), the bar for bf16 outputs and gradients
 
 

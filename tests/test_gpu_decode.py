@@ -18,7 +18,7 @@ def qb():
 @pytest.mark.parametrize("base", ["codebook", "minmax", "grouped"])
 @pytest.mark.parametrize("T,d_out,d_in", [(1, 512, 512), (3, 320, 192), (8, 1000, 1088), (16, 256, 2048), (5, 40, 64)])
 def test_decode_parity(qb, oracle, codebook, T, d_out, d_in, base):
-    from gpu_util import f32_to_dev, to_np, bf16_to_dev, assert_close_bf16
+    from gpu_util import f32_to_dev, bf16_to_dev, assert_close_bf16, OracleWeight
     print(f"case decode T={T} {d_out}x{d_in} base={base}", flush=True)
     L = synth.make_layer(2000 + T, T, d_out, d_in, 8, 1, 1)
     if base == "minmax":
@@ -33,18 +33,14 @@ def test_decode_parity(qb, oracle, codebook, T, d_out, d_in, base):
     Yp = qb.qblora_linear_decode(qw, X, pack=qb.qblora_decode_pack(qw))
     torch.cuda.synchronize()
     assert torch.equal(Y.view(torch.int16), Yp.view(torch.int16))       # tile-ordered pack: same bits
-    scales = to_np(qw.scales)
-    if base == "grouped":
-        scales = oracle.scales_double_dequantize(to_np(qw.scale_codes), to_np(qw.scale_step), to_np(qw.scale_mid),
-                                                 256).reshape(scales.shape)
-    beta = None if qw.beta is None else to_np(qw.beta)
-    Wt = oracle.dequantize(to_np(qw.codes), scales, beta, cb, 64, 3)     # the inference weight: alpha*bf16(c)+beta
+    ow = OracleWeight(oracle, L.W, codebook, base == "minmax", base == "grouped").assert_same(qw)
+    Wt = ow.dequantize(oracle, 3)                                        # the inference weight: alpha*bf16(c)+beta
     assert_close_bf16(Y, oracle.forward(Wt, L.X, None, None, 1, 1, 0.0), "Y")
 
 
 def test_decode_of_the_merged_int4_model(qb, oracle, codebook):
     """Sec. 3.3 deployment path: train-time layer with aligned tiles -> beta-shift merge -> 4-bit inference."""
-    from gpu_util import f32_to_dev, to_np, bf16_to_dev, assert_close_bf16
+    from gpu_util import f32_to_dev, to_np, bf16_to_dev, assert_close_bf16, OracleWeight
     T, d_out, d_in, lam1, lam2, s = 4, 512, 1024, 64, 8, 0.75
     L = synth.make_layer(2100, T, d_out, d_in, 8, lam1, lam2)
     Hb = synth.f32_to_bf16_bits((np.random.default_rng(2101).standard_normal((d_in // lam1, d_out // lam2)) * 0.05)
@@ -59,12 +55,14 @@ def test_decode_of_the_merged_int4_model(qb, oracle, codebook):
     from helpers import bf16_exact
     from gpu_util import bf16_to_f64
     cb = synth.codebook_int4()
-    beta2 = oracle.merge_beta_shift(to_np(qw.beta), bf16_exact(Hb).astype(np.float32), d_out, d_in, 64, lam1, lam2, s)
+    ow = OracleWeight(oracle, L.W, None, minmax=True).assert_same(qw)
+    beta2 = oracle.merge_beta_shift(ow.beta, bf16_exact(Hb).astype(np.float32), d_out, d_in, 64, lam1, lam2, s)
     assert np.array_equal(to_np(merged.beta).view(np.uint32), beta2.view(np.uint32))
-    Wm = oracle.dequantize(to_np(qw.codes), to_np(qw.scales), beta2, cb, 64, 3)
+    assert np.array_equal(to_np(merged.codes), ow.codes)
+    Wm = oracle.dequantize(ow.codes, ow.scales, beta2, cb, 64, 3)
     assert_close_bf16(Y, oracle.forward(Wm, L.X, None, None, 1, 1, 0.0), "Y (merged INT4, decode)")
     # ... and the train-time layer it replaces (whose base weight is rounded to bf16)
-    Wt = oracle.dequantize(to_np(qw.codes), to_np(qw.scales), to_np(qw.beta), cb, 64, 2)
+    Wt = ow.dequantize(oracle, 2)
     ref = oracle.qa_forward(Wt, L.X, Hb, lam1, lam2, s)
     err = bf16_to_f64(Y) - ref
     rms = np.sqrt(np.mean(ref ** 2))

@@ -38,10 +38,12 @@ def _run_layer(qb, oracle, codebook, seed, T, d_out, d_in, rank, lam, s, grouped
     Y = qb.qblora_linear_fwd(qw, ad, X, saved=saved)                 # as bench.py calls them
     dX, dA, dB = qb.qblora_linear_bwd(qw, ad, X, dY, saved=saved)
     H = qb.qblora_tile_product(ad, d_in, d_out)
-    merged = qb.qablora_merge_quantize(qw, H, lam, lam, s, qb.MERGE_REQUANT_MINMAX)
+    merged = qb.qablora_merge_quantize(qw, H, lam, lam, s, qb.MERGE_REQUANT_MINMAX)      # the chain bench.py times
+    Ho = oracle.tile_product(L.A, L.B).astype(np.float32)
+    merged_o = qb.qablora_merge_quantize(qw, f32_to_dev(Ho), lam, lam, s, qb.MERGE_REQUANT_MINMAX)
     torch.cuda.synchronize()
 
-    # integer paths, in full
+    # integer paths, in full (everything the oracle is fed below is the oracle's own or the seeded input)
     codes, absmax = oracle.quantize_codebook(L.W, 64, codebook)
     assert np.array_equal(to_np(qw.codes), codes)
     assert np.array_equal(to_np(qw.scales).view(np.uint32), absmax.view(np.uint32))
@@ -52,12 +54,15 @@ def _run_layer(qb, oracle, codebook, seed, T, d_out, d_in, rank, lam, s, grouped
         assert np.array_equal(to_np(qw.scale_step).view(np.uint32), stp.view(np.uint32))
         assert np.array_equal(to_np(qw.scale_mid).view(np.uint32), mid.view(np.uint32))
         scales = oracle.scales_double_dequantize(sc, stp, mid, 256).reshape(absmax.shape)
-    Hh = to_np(H)
-    co, ao, bo = oracle.merge_requant(codes, scales, None, codebook, Hh, 64, lam, lam, s)
-    assert np.array_equal(to_np(merged.codes), co)
-    assert np.array_equal(to_np(merged.scales).view(np.uint32), ao.view(np.uint32))
-    assert np.array_equal(to_np(merged.beta).view(np.uint32), bo.view(np.uint32))
+    # the merge, bit for bit, on the oracle's tile matrix; the device's own tile matrix differs from it in the
+    # last fp32 bits (summation order), so the chained result is compared by how many codes may move
+    co, ao, bo = oracle.merge_requant(codes, scales, None, codebook, Ho, 64, lam, lam, s)
+    assert np.array_equal(to_np(merged_o.codes), co)
+    assert np.array_equal(to_np(merged_o.scales).view(np.uint32), ao.view(np.uint32))
+    assert np.array_equal(to_np(merged_o.beta).view(np.uint32), bo.view(np.uint32))
     assert_close_f32(H, oracle.tile_product(L.A, L.B), "H")
+    assert np.mean(to_np(merged.codes) != co) < 1e-3
+    assert np.allclose(to_np(merged.scales), ao, rtol=1e-5, atol=0) and np.allclose(to_np(merged.beta), bo, rtol=1e-4, atol=1e-7)
 
     # forward / backward-dX on sampled token rows
     Wt = oracle.dequantize(codes, scales, None, codebook, 64, 2)
@@ -116,7 +121,8 @@ def test_single_matrix_adapter_benchmark_shape(qb, oracle, codebook):
     Y = qb.qablora_linear_fwd(qw, H, lam1, lam2, s, X)
     dX, dH = qb.qablora_linear_bwd(qw, H, lam1, lam2, s, X, dY)
     torch.cuda.synchronize()
-    Wt = oracle.dequantize(to_np(qw.codes), to_np(qw.scales), None, codebook, 64, 2)
+    from gpu_util import OracleWeight
+    Wt = OracleWeight(oracle, L.W, codebook).assert_same(qw).dequantize(oracle, 2)
     rows = synth.sample_rows(T, 128, wl.seed + 22)
     Xs, dYs = np.ascontiguousarray(L.X[rows]), np.ascontiguousarray(L.dY[rows])
     ridx = torch.from_numpy(rows).to(Y.device)
@@ -145,7 +151,8 @@ def test_scale_operators_benchmark_shape(qb, oracle, codebook, op):
     Y = qb.qblora_linear_fwd(qw, ad, X, saved=saved)
     dX, dA, dB = qb.qblora_linear_bwd(qw, ad, X, dY, saved=saved)
     torch.cuda.synchronize()
-    Wt = oracle.dequantize(to_np(qw.codes), to_np(qw.scales), None, codebook, 64, 2)
+    from gpu_util import OracleWeight
+    Wt = OracleWeight(oracle, L.W, codebook).assert_same(qw).dequantize(oracle, 2)
     rows = synth.sample_rows(T, 128, wl.seed + 40 + op)
     Xs, dYs = np.ascontiguousarray(L.X[rows]), np.ascontiguousarray(L.dY[rows])
     ridx = torch.from_numpy(rows).to(Y.device)

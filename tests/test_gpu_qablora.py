@@ -21,23 +21,15 @@ def _h_bits(seed, rows, cols, std=0.02):
 
 
 def _setup(qb, oracle, codebook, seed, T, d_out, d_in, lam1, lam2, minmax=False, grouped=False):
-    from gpu_util import f32_to_dev, to_np, bf16_to_dev
+    from gpu_util import f32_to_dev, bf16_to_dev, OracleWeight
     L = synth.make_layer(seed, T, d_out, d_in, 8, lam1, lam2)
     if minmax:
         qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 64, qb.QUANT_MINMAX_INT4)
-        cb = synth.codebook_int4()
     else:
         qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 64, qb.QUANT_ABSMAX_CODEBOOK, codebook,
                                           qb.SCALES_E4M3_GROUPED if grouped else qb.SCALES_FP32)
-        cb = codebook
     torch.cuda.synchronize()
-    if grouped:
-        scales = oracle.scales_double_dequantize(to_np(qw.scale_codes), to_np(qw.scale_step), to_np(qw.scale_mid),
-                                                 256).reshape(d_out, d_in // 64)
-    else:
-        scales = to_np(qw.scales)
-    beta = None if qw.beta is None else to_np(qw.beta)
-    Wt = oracle.dequantize(to_np(qw.codes), scales, beta, cb, 64, 2)      # the bf16 compute weight
+    Wt = OracleWeight(oracle, L.W, codebook, minmax, grouped).assert_same(qw).dequantize(oracle, 2)   # bf16 compute weight
     Hb = _h_bits(seed + 1, d_in // lam1, d_out // lam2)
     return L, qw, Wt, Hb, bf16_to_dev(Hb), bf16_to_dev(L.X), bf16_to_dev(L.dY)
 

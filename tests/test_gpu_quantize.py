@@ -65,17 +65,17 @@ def test_double_quantized_scales_bit_exact(qb, oracle, codebook, d_out, d_in):
 
 
 def test_dequantize_bf16_bit_exact(qb, oracle, codebook):
-    from gpu_util import f32_to_dev, to_np, bf16_to_f64
+    from gpu_util import f32_to_dev, bf16_to_f64, OracleWeight
     W = synth.base_weight(400, 0, 192, 320)
     qw = qb.qblora_quantize_blockwise(f32_to_dev(W), 64, qb.QUANT_ABSMAX_CODEBOOK, codebook)
     Wt = qb.qblora_dequantize_bf16(qw)
     torch.cuda.synchronize()
-    want = oracle.dequantize(to_np(qw.codes), to_np(qw.scales), None, codebook, 64, 2)
+    want = OracleWeight(oracle, W, codebook).assert_same(qw).dequantize(oracle, 2)
     assert np.array_equal(bf16_to_f64(Wt), want)
     qm = qb.qblora_quantize_blockwise(f32_to_dev(W), 64, qb.QUANT_MINMAX_INT4)
     Wm = qb.qblora_dequantize_bf16(qm)
     torch.cuda.synchronize()
-    want = oracle.dequantize(to_np(qm.codes), to_np(qm.scales), to_np(qm.beta), synth.codebook_int4(), 64, 2)
+    want = OracleWeight(oracle, W, None, minmax=True).assert_same(qm).dequantize(oracle, 2)
     assert np.array_equal(bf16_to_f64(Wm), want)
 
 

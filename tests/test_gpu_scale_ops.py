@@ -17,11 +17,11 @@ def qb():
 
 
 def _setup(qb, oracle, codebook, seed, T, d_out, d_in, R, lam1, lam2, s, op):
-    from gpu_util import f32_to_dev, to_np, bf16_to_dev
+    from gpu_util import f32_to_dev, bf16_to_dev, OracleWeight
     L = synth.make_layer(seed, T, d_out, d_in, R, lam1, lam2)
     qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 64, qb.QUANT_ABSMAX_CODEBOOK, codebook)
     torch.cuda.synchronize()
-    Wt = oracle.dequantize(to_np(qw.codes), to_np(qw.scales), None, codebook, 64, 2)
+    Wt = OracleWeight(oracle, L.W, codebook).assert_same(qw).dequantize(oracle, 2)
     ad = qb.Adapter(bf16_to_dev(L.A), bf16_to_dev(L.B), lam1, lam2, s, scale_op=op)
     return L, qw, Wt, ad, bf16_to_dev(L.X), bf16_to_dev(L.dY)
 

@@ -41,11 +41,11 @@ def test_quantizers_bit_exact(qb, oracle, codebook, d_out, d_in):
     t1, t2 = to_np(qw.codes_tiled), to_np(ref.codes_tiled)
     full = (d_out // 256) * 256 * (d_in // 64) * 32          # whole row tiles (rows past d_out are unspecified)
     assert np.array_equal(t1[:full], t2[:full])
-    # standalone dequantize (bf16 compute weight)
-    for q, beta, cb in ((qw, None, codebook), (qm, bm, synth.codebook_int4())):
+    # standalone dequantize (bf16 compute weight), against the oracle's own triplets (equal to the device's, above)
+    for q, c_o, a_o, b_o, cb in ((qw, codes, absmax, None, codebook), (qm, cm, am, bm, synth.codebook_int4())):
         Wt = qb.qblora_dequantize_bf16(q)
         torch.cuda.synchronize()
-        want = oracle.dequantize_tile(to_np(q.codes), to_np(q.scales), beta, cb, 8, 8, 2)
+        want = oracle.dequantize_tile(c_o, a_o, b_o, cb, 8, 8, 2)
         assert np.array_equal(Wt.float().cpu().numpy().astype(np.float64), want)
 
 
@@ -60,8 +60,9 @@ def test_offset_shift_merge_bit_exact(qb, oracle, lam1, lam2):
         base = qb.qblora_quantize_blockwise(f32_to_dev(W), 64, quantizer, cb, block_rows=8)
         merged = qb.qablora_merge_quantize(base, f32_to_dev(H), lam1, lam2, s, qb.MERGE_BETA_SHIFT)
         torch.cuda.synchronize()
-        beta = None if base.beta is None else to_np(base.beta)
-        want = oracle.merge_beta_shift_tile(beta, H, d_out, d_in, 8, 8, lam1, lam2, s)
+        from gpu_util import OracleWeight
+        ow = OracleWeight(oracle, W, cb, quantizer == qb.QUANT_MINMAX_INT4, block_rows=8).assert_same(base)
+        want = oracle.merge_beta_shift_tile(ow.beta, H, d_out, d_in, 8, 8, lam1, lam2, s)
         assert np.array_equal(to_np(merged.beta).view(np.uint32), want.view(np.uint32))
         assert np.array_equal(to_np(merged.codes), to_np(base.codes))
         assert np.array_equal(to_np(merged.scales).view(np.uint32), to_np(base.scales).view(np.uint32))
@@ -84,17 +85,16 @@ def test_errors(qb, oracle, codebook):
 
 
 def _layer(qb, oracle, codebook, seed, T, d_out, d_in, R, lam1, lam2, minmax):
-    from gpu_util import f32_to_dev, to_np, bf16_to_dev
+    from gpu_util import f32_to_dev, bf16_to_dev, OracleWeight
     L = synth.make_layer(seed, T, d_out, d_in, max(R, 8), lam1, lam2)
     if minmax:
         qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 64, qb.QUANT_MINMAX_INT4, block_rows=8)
-        cb = synth.codebook_int4()
     else:
         qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 64, qb.QUANT_ABSMAX_CODEBOOK, codebook, block_rows=8)
-        cb = codebook
     torch.cuda.synchronize()
-    beta = None if qw.beta is None else to_np(qw.beta)
-    Wt = oracle.dequantize_tile(to_np(qw.codes), to_np(qw.scales), beta, cb, 8, 8, 2)      # the bf16 compute weight
+    ow = OracleWeight(oracle, L.W, codebook, minmax, block_rows=8).assert_same(qw)
+    qw.oracle_weight = ow                                   # the oracle's triplets, for the tests that go on from them
+    Wt = ow.dequantize(oracle, 2)                           # the bf16 compute weight
     return L, qw, Wt, bf16_to_dev(L.X), bf16_to_dev(L.dY)
 
 
@@ -146,11 +146,15 @@ def test_quantization_aware_loop_on_8x8_blocks(qb, oracle, T, d_out, d_in, lam1,
     merged = qb.qablora_merge_quantize(qw, H.float().contiguous(), lam1, lam2, s, qb.MERGE_BETA_SHIFT)
     Ym = qb.qblora_linear_fwd(merged, None, X)
     torch.cuda.synchronize()
-    Wm = oracle.dequantize_tile(to_np(merged.codes), to_np(merged.scales), to_np(merged.beta), synth.codebook_int4(), 8, 8, 2)
+    from helpers import bf16_exact
+    ow = qw.oracle_weight
+    beta2 = oracle.merge_beta_shift_tile(ow.beta, bf16_exact(Hb).astype(np.float32), d_out, d_in, 8, 8, lam1, lam2, s)
+    assert np.array_equal(to_np(merged.beta).view(np.uint32), beta2.view(np.uint32))
+    assert np.array_equal(to_np(merged.codes), ow.codes)
+    Wm = oracle.dequantize_tile(ow.codes, ow.scales, beta2, synth.codebook_int4(), 8, 8, 2)
     assert_close_bf16(Ym, oracle.forward(Wm, L.X, None, None, 1, 1, 0.0), "Y merged")
     # the merged layer against the adapted layer: they differ by the bf16 rounding of the merged weight only
-    ref = oracle.qa_forward(oracle.dequantize_tile(to_np(qw.codes), to_np(qw.scales), to_np(qw.beta), synth.codebook_int4(), 8, 8, 0),
-                            L.X, Hb, lam1, lam2, s)
+    ref = oracle.qa_forward(ow.dequantize(oracle, 0), L.X, Hb, lam1, lam2, s)
     err = np.abs(bf16_to_f64(Ym) - ref)
     rms = np.sqrt((ref ** 2).mean())
     assert np.sqrt((err ** 2).mean()) <= 5e-3 * rms and err.max() <= 4e-2 * rms
