@@ -58,6 +58,18 @@ __device__ __forceinline__ void copy16_to_lds(const void* uniform_base, uint32_t
                  :: "s"(lds_base), "v"(lane_offset), "s"(uniform_base) : "memory");
 }
 
+// value of lane `src` (0..3) of the caller's quad
+template <int>
+__device__ __forceinline__ float quad_broadcast(float v, int src) {
+    const int x = __float_as_int(v);
+    switch (src) {
+        case 0: return __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0x00, 0xf, 0xf, false));
+        case 1: return __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0x55, 0xf, 0xf, false));
+        case 2: return __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0xAA, 0xf, 0xf, false));
+        default: return __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0xFF, 0xf, 0xf, false));
+    }
+}
+
 __device__ __forceinline__ uint32_t lds_address(const void* p) {
     return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
 }
@@ -65,13 +77,13 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
 // codes / scales of one k-step held in registers: 32 weights per thread
 //   QMODE 1: half a stored row (16 bytes of codes), one scale -- or, with 8 x 8 quantization blocks
 //            (BR = 8), one scale per code dword (8 inputs = one block column)
-//   QMODE 2: a patch of 4 stored rows x 8 columns (one dword per row), a scale per row (with BR = 8 the
-//            patch lies in one block and the four are equal)
+//   QMODE 2: a patch of 4 stored rows x 8 columns (one dword per row); one scale per thread: the
+//            patch's own with BR = 8, else that of row (lane & 3) of the patch, shared inside the quad
 template <int QMODE, int BR>
 struct Staged {
     uint32_t cw[4];
-    float sc[(QMODE == 2 || BR == 8) ? 4 : 1];
-    float be[(QMODE == 2 || BR == 8) ? 4 : 1];
+    float sc[(QMODE == 1 && BR == 8) ? 4 : 1];
+    float be[(QMODE == 1 && BR == 8) ? 4 : 1];
 };
 
 template <int QMODE, bool BETA, int BR>
@@ -224,10 +236,14 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
             for (int i = 0; i < 4; ++i) {
                 const int64_t n = nb + i;
                 s.cw[i] = *reinterpret_cast<const uint32_t*>(codes + n * (d_in / 2) + qcol / 2);
-                const int64_t blk = BR == 8 ? (n >> 3) * (d_in >> 3) + (qcol >> 3) : n * bpr + qcol / kBlock;
-                s.sc[i] = scales[blk];
-                if constexpr (BETA) s.be[i] = beta[blk];
             }
+            // One scale load per thread: with 8 x 8 blocks the patch lies in one block; with row-segment
+            // blocks the four lanes of a quad (32 consecutive columns, inside one 64-block) each fetch
+            // the scale of one of the four rows and the multiply reads it through a quad broadcast.
+            const int64_t blk = BR == 8 ? (int64_t)(nb >> 3) * (d_in >> 3) + (qcol >> 3)
+                                        : (int64_t)(nb + (t & 3)) * bpr + qcol / kBlock;
+            s.sc[0] = scales[blk];
+            if constexpr (BETA) s.be[0] = beta[blk];
         }
     };
 
@@ -255,9 +271,17 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
         float lo[8], hi[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int si = QMODE == 2 ? (i & 3) : (BR == 8 ? 2 * p + (i >> 2) : 0);
-            lo[i] = BETA ? __fmaf_rn(lv[i].x, s.sc[si], s.be[si]) : __fmul_rn(lv[i].x, s.sc[si]);
-            hi[i] = BETA ? __fmaf_rn(lv[i].y, s.sc[si], s.be[si]) : __fmul_rn(lv[i].y, s.sc[si]);
+            float sc, be = 0.0f;
+            if constexpr (QMODE == 2 && BR == 1) {           // row i & 3 of the patch: lane i & 3 of the quad holds it
+                sc = quad_broadcast<0>(s.sc[0], i & 3);
+                if constexpr (BETA) be = quad_broadcast<0>(s.be[0], i & 3);
+            } else {
+                const int si = QMODE == 2 ? 0 : (BR == 8 ? 2 * p + (i >> 2) : 0);
+                sc = s.sc[si];
+                if constexpr (BETA) be = s.be[si];
+            }
+            lo[i] = BETA ? __fmaf_rn(lv[i].x, sc, be) : __fmul_rn(lv[i].x, sc);
+            hi[i] = BETA ? __fmaf_rn(lv[i].y, sc, be) : __fmul_rn(lv[i].y, sc);
         }
         if constexpr (QMODE == 1) {
             // byte i holds elements 2i, 2i+1 of the 16: adjacent k, packed as they come
