@@ -163,3 +163,73 @@ def test_scale_operators_benchmark_shape(qb, oracle, codebook, op):
     _, rA, rB = oracle.backward_op(None, L.X, L.dY, L.A, L.B, lam, lam, s, op, compute_dx=False, d_out=d_out, d_in=d_in)
     assert_close_f32(dA, rA, "dA")
     assert_close_f32(dB, rB, "dB")
+
+
+def test_small_batch_inference_at_the_measured_shape(qb, oracle):
+    """The decode kernel on the 65B up-projection shape kernel_bench times (22016 x 8192, INT4 with offsets, tile-
+    ordered pack), T = 1 and 16: sampled output features against the oracle (a feature needs its own weight row only)."""
+    from gpu_util import f32_to_dev, bf16_to_dev, bf16_to_f64
+    d_out, d_in = 22016, 8192
+    rng = np.random.default_rng(4242)
+    W = (rng.standard_normal((d_out, d_in), dtype=np.float32) * np.float32(0.02))
+    rows = np.sort(rng.choice(d_out, 192, replace=False))
+    cb = synth.codebook_int4()
+    for block_rows in (1, 8):
+        print(f"full-size decode case {d_out}x{d_in} block_rows={block_rows}", flush=True)
+        qw = qb.qblora_quantize_blockwise(f32_to_dev(W), 64, qb.QUANT_MINMAX_INT4, tiled=False, block_rows=block_rows)
+        pack = qb.qblora_decode_pack(qw)
+        # the oracle's weight for the sampled rows: whole 8-row groups so that 8 x 8 blocks stay whole
+        grp = np.unique(rows // 8)
+        sel = (grp[:, None] * 8 + np.arange(8)[None, :]).reshape(-1)
+        Wsel = np.ascontiguousarray(W[sel])
+        if block_rows == 8:
+            c, a, b = oracle.quantize_minmax_tile(Wsel, 8, 8)
+            Wt = oracle.dequantize_tile(c, a, b, cb, 8, 8, 2)             # bf16 compute weight (8 x 8 inference arithmetic)
+        else:
+            c, a, b = oracle.quantize_minmax(Wsel, 64)
+            Wt = oracle.dequantize(c, a, b, cb, 64, 3)                    # alpha * bf16(c) + beta
+        sel_t = torch.from_numpy(sel).to(qw.codes.device)
+        assert np.array_equal(qw.codes[sel_t].cpu().numpy(), c)          # the device weight holds the oracle's bits there
+        for T in (1, 16):
+            Xb = synth.f32_to_bf16_bits(rng.standard_normal((T, d_in), dtype=np.float32))
+            Y = qb.qblora_linear_decode(qw, bf16_to_dev(Xb), pack=pack)
+            torch.cuda.synchronize()
+            ref = oracle.forward(Wt, Xb, None, None, 1, 1, 0.0)           # [T, len(sel)]
+            got = bf16_to_f64(Y[:, sel_t])
+            rms = np.sqrt(np.mean(ref ** 2))
+            excess = np.abs(got - ref) - np.abs(ref) * 2.0 ** -8
+            assert excess.max() <= 1e-2 * rms, (block_rows, T, excess.max() / rms)
+        del qw, pack
+
+
+def test_8x8_blocks_mlp_shapes_reduced_tokens(qb, oracle, codebook):
+    """The layer on 8 x 8 quantization blocks at the 7B MLP shapes (non-power-of-two widths), single-matrix adapter
+    with lambda = (8, 8), forward / backward on sampled rows, dH in full, and the exact merge."""
+    from gpu_util import f32_to_dev, to_np, bf16_to_dev, assert_close_bf16, assert_close_f32, OracleWeight
+    from helpers import bf16_exact
+    wl = synth.WORKLOADS["llama7b_mlp"]
+    for i, p in enumerate((wl.projections[0], wl.projections[2])):
+        T, d_out, d_in, lam1, lam2, s = 512, p.d_out, p.d_in, 8, 8, 1.0
+        print(f"full-size 8x8 case T={T} {d_out}x{d_in}", flush=True)
+        L = synth.make_layer(wl.seed + 50 + i, T, d_out, d_in, 8, lam1, lam2)
+        Hb = synth.f32_to_bf16_bits((np.random.default_rng(wl.seed + 60 + i).standard_normal((d_in // lam1, d_out // lam2)) * 0.02)
+                                    .astype(np.float32))
+        qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 64, qb.QUANT_MINMAX_INT4, block_rows=8)
+        H, X, dY = bf16_to_dev(Hb), bf16_to_dev(L.X), bf16_to_dev(L.dY)
+        Y = qb.qablora_linear_fwd(qw, H, lam1, lam2, s, X)
+        dX, dH = qb.qablora_linear_bwd(qw, H, lam1, lam2, s, X, dY)
+        merged = qb.qablora_merge_quantize(qw, H.float().contiguous(), lam1, lam2, s, qb.MERGE_BETA_SHIFT)
+        torch.cuda.synchronize()
+        ow = OracleWeight(oracle, L.W, None, minmax=True, block_rows=8).assert_same(qw)
+        Wt = ow.dequantize(oracle, 2)
+        rows = synth.sample_rows(T, 64, wl.seed + 70 + i)
+        Xs, dYs = np.ascontiguousarray(L.X[rows]), np.ascontiguousarray(L.dY[rows])
+        ridx = torch.from_numpy(rows).to(Y.device)
+        assert_close_bf16(Y[ridx], oracle.qa_forward(Wt, Xs, Hb, lam1, lam2, s), "Y (sampled rows)")
+        rX, _ = oracle.qa_backward(Wt, Xs, dYs, Hb, lam1, lam2, s, compute_dh=False)
+        assert_close_bf16(dX[ridx], rX, "dX (sampled rows)")
+        del Wt
+        _, rH = oracle.qa_backward(None, L.X, L.dY, Hb, lam1, lam2, s, compute_dx=False, d_out=d_out, d_in=d_in)
+        assert_close_f32(dH, rH, "dH")
+        want = oracle.merge_beta_shift_tile(ow.beta, bf16_exact(Hb).astype(np.float32), d_out, d_in, 8, 8, lam1, lam2, s)
+        assert np.array_equal(to_np(merged.beta).view(np.uint32), want.view(np.uint32))
