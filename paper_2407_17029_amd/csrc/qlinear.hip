@@ -58,8 +58,7 @@ __device__ __forceinline__ void copy16_to_lds(const void* uniform_base, uint32_t
                  :: "s"(lds_base), "v"(lane_offset), "s"(uniform_base) : "memory");
 }
 
-// value of lane `src` (0..3) of the caller's quad
-template <int>
+// value of lane `src` (0..3, a constant after unrolling) of the caller's quad
 __device__ __forceinline__ float quad_broadcast(float v, int src) {
     const int x = __float_as_int(v);
     switch (src) {
@@ -273,8 +272,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
         for (int i = 0; i < 8; ++i) {
             float sc, be = 0.0f;
             if constexpr (QMODE == 2 && BR == 1) {           // row i & 3 of the patch: lane i & 3 of the quad holds it
-                sc = quad_broadcast<0>(s.sc[0], i & 3);
-                if constexpr (BETA) be = quad_broadcast<0>(s.be[0], i & 3);
+                sc = quad_broadcast(s.sc[0], i & 3);
+                if constexpr (BETA) be = quad_broadcast(s.be[0], i & 3);
             } else {
                 const int si = QMODE == 2 ? 0 : (BR == 8 ? 2 * p + (i >> 2) : 0);
                 sc = s.sc[si];
