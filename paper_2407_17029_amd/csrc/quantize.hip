@@ -127,11 +127,13 @@ __global__ __launch_bounds__(256) void k_quantize_codebook(const float4* __restr
     const QuantTile q = quant_tile(bpr);
     const int t = threadIdx.x, u = t >> 6, lane = t & 63, j = lane >> 2;
     const int row = q.row0 + u;
+    // Lanes outside the matrix read the first block instead: their results are never stored, and the four
+    // lanes of a block are inside or outside together.
     const bool ok = row < d_out && q.blk0 + j < bpr;
-    const float4* src = W + ((int64_t)row * bpr + q.blk0) * 16 + lane * 4;
+    const float4* src = W + (ok ? ((int64_t)row * bpr + q.blk0) * 16 + lane * 4 : (lane & 3) * 4);
     float4 wv[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) wv[i] = ok ? src[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i = 0; i < 4; ++i) wv[i] = src[i];
     float a = 0.0f;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -160,11 +162,11 @@ __global__ __launch_bounds__(256) void k_quantize_minmax(const float4* __restric
     const QuantTile q = quant_tile(bpr);
     const int t = threadIdx.x, u = t >> 6, lane = t & 63, j = lane >> 2;
     const int row = q.row0 + u;
-    const bool ok = row < d_out && q.blk0 + j < bpr;
-    const float4* src = W + ((int64_t)row * bpr + q.blk0) * 16 + lane * 4;
+    const bool ok = row < d_out && q.blk0 + j < bpr;         // lanes outside the matrix read the first block
+    const float4* src = W + (ok ? ((int64_t)row * bpr + q.blk0) * 16 + lane * 4 : (lane & 3) * 4);
     float4 wv[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) wv[i] = ok ? src[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i = 0; i < 4; ++i) wv[i] = src[i];
     float lo = wv[0].x, hi = wv[0].x;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -205,11 +207,13 @@ __global__ __launch_bounds__(256) void k_quantize_tile8(const float4* __restrict
     const int jt = blockIdx.x % ntj, row0 = (blockIdx.x / ntj) * 8, col0 = jt * 512;
     const int t = threadIdx.x, j = t >> 2, q = t & 3;              // block of the workgroup, lane of its quad
     const int col = col0 + 8 * j;
-    const bool ok = col < d_in && row0 < d_out;                    // d_out % 8 == 0: whole blocks are in or out
+    // d_out % 8 == 0: whole blocks are in or out; a block outside the matrix reads block (0, 0) instead and
+    // its results are never stored
+    const bool ok = col < d_in && row0 < d_out;
+    const int rbase = ok ? row0 : 0, cbase = ok ? col : 0;
     float4 wv[4];                                                  // [2*rr + c]: row 2q+rr, inputs 4c .. 4c+3
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-        wv[i] = ok ? W[((int64_t)(row0 + 2 * q + (i >> 1)) * d_in + col + 4 * (i & 1)) >> 2] : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i = 0; i < 4; ++i) wv[i] = W[((int64_t)(rbase + 2 * q + (i >> 1)) * d_in + cbase + 4 * (i & 1)) >> 2];
     uint32_t c[4];
     if constexpr (MINMAX) {
         float lo = wv[0].x, hi = wv[0].x;
