@@ -67,7 +67,18 @@ __global__ __launch_bounds__(kMergeThreads) void k_merge_requant(MergeDesc d) {
     __shared__ float lut[16];
     extern __shared__ __align__(16) float dl[];          // deltas, [hcols][stride]
     const int t = threadIdx.x;
-    const int k0 = blockIdx.x * KT, n0 = blockIdx.y * NT;
+    // Workgroup -> tile.  Eight neighbouring k-tiles of a row tile touch the same 128-byte lines of the
+    // scale arrays (4 blocks = 16 bytes per tile and row), in and out; workgroup id mod 8 is the XCD, so the
+    // eight are given ids with equal id mod 8 (and consecutive id / 8): one L2 then sees whole lines instead
+    // of eight L2s each fetching the line and writing back an eighth of it.  Ids past the ragged end of a
+    // group of eight, or past the last group, have no tile.
+    const int ktiles = (d.d_in + KT - 1) / KT, ntiles = (d.d_out + NT - 1) / NT;
+    const int kgroups = (ktiles + 7) >> 3;
+    const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+    const int group = (seq >> 3) * 8 + xcd;
+    const int kt = (group % kgroups) * 8 + (seq & 7), nt = group / kgroups;
+    if (kt >= ktiles || nt >= ntiles) return;
+    const int k0 = kt * KT, n0 = nt * NT;
     const int row = t >> 3, bk = (t >> 1) & 3, sub = t & 1;
     const int n = n0 + row, k = k0 + kBlock * bk + 32 * sub;
     const bool live = n < d.d_out && k < d.d_in;         // the same for the two lanes of a block
@@ -215,7 +226,10 @@ template <int L1, bool OUT16>
 int launch_requant_l1(const MergeDesc& d, hipStream_t st) {
     const int hcols = NT / d.lam2 + 2;
     const size_t smem = sizeof(float) * (size_t)delta_stride<L1>(d.lam1) * hcols;
-    dim3 grid((d.d_in + KT - 1) / KT, (d.d_out + NT - 1) / NT);
+    // one id per (group of eight k-tiles, member), groups dealt round-robin to the eight XCDs
+    const int64_t groups = (int64_t)(((d.d_in + KT - 1) / KT + 7) / 8) * ((d.d_out + NT - 1) / NT);
+    if (groups > (int64_t)1 << 24) return QBLORA_ERR_UNSUPPORTED;
+    dim3 grid((unsigned)(((groups + 7) / 8) * 64));
     auto launch = [&](auto kern) -> int {
         if (smem > 48 * 1024 &&
             hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
