@@ -56,7 +56,12 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
     __shared__ float red[4][4][64];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int nl = lane & 15, kg = lane >> 4;
-    const int n0 = blockIdx.x * 16;
+    // Row groups 2i and 2i+1 share the 128-byte lines of the tile-ordered scales and offsets (16 rows = 64
+    // bytes per block): they are given workgroup ids x and x + 8 of a run of 16 ids, which are dispatched to
+    // the same XCD, so that one L2 fetches each line.  The grid is a multiple of 16; ids past the end leave.
+    const int rg = (blockIdx.x & ~15) | ((blockIdx.x & 7) << 1) | ((blockIdx.x >> 3) & 1);
+    if (rg * 16 >= d.d_out) return;
+    const int n0 = rg * 16;
     const int n = min(n0 + nl, d.d_out - 1);                  // rows past the end are computed, not stored
     const int bpr = d.d_in / kBlock;
     const int groups = (bpr + 3) / 4;
@@ -203,7 +208,7 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
 int launch_w4_decode(const uint8_t* codes, const float* scales, const float* beta, const Codebook& cb, int tiled,
                      int d_out, int d_in, const qblora_bf16* X, int T, qblora_bf16* Y, hipStream_t st, int block_rows) {
     DecodeDesc d{codes, scales, beta, cb, tiled, block_rows, d_out, d_in, X, T, Y};
-    const dim3 grid((unsigned)((d_out + 15) / 16));
+    const dim3 grid((unsigned)(((d_out + 15) / 16 + 15) / 16 * 16));
     if (block_rows == 8) {
         if (beta) hipLaunchKernelGGL((k_w4_decode<true, 8>), grid, dim3(256), 0, st, d);
         else hipLaunchKernelGGL((k_w4_decode<false, 8>), grid, dim3(256), 0, st, d);
