@@ -367,7 +367,7 @@ __global__ __launch_bounds__(256) void k_grad_reduce(GradDesc d) {
         for (int z0 = 0; z0 < d.splits; z0 += 8) {
             float v[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = (z0 + u < d.splits) ? src[(int64_t)(z0 + u) * plane] : 0.0f;
+            for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)min(z0 + u, d.splits - 1) * plane];   // unconditional, in bounds
 #pragma unroll
             for (int u = 0; u < 8; ++u)
                 if (z0 + u < d.splits) sum += v[u];
@@ -376,6 +376,47 @@ __global__ __launch_bounds__(256) void k_grad_reduce(GradDesc d) {
     sum *= d.out_scale;
     if (d.transpose_out) d.out[(int64_t)j * Ip + ip] = sum;
     else d.out[(int64_t)ip * d.J + j] = sum;
+}
+
+// The same sums (same order, same bits) for J % 4 == 0, Ip % 4 == 0 and 16-byte aligned buffers; used for
+// the transposed output.  A workgroup owns 32 pooled rows x 32 columns, a thread one pooled row and 4
+// consecutive columns, so every load instruction of a wave reads eight whole 128-byte lines and all
+// pool * splits loads of a thread are issued together; the transposed output goes through LDS so that its
+// stores are whole lines too (one thread per output element wrote 4 bytes into each of 64 lines).
+__global__ __launch_bounds__(256) void k_grad_reduce_tile(GradDesc d) {
+    __shared__ float tr[32][33];
+    const int Ip = d.I / d.pool;
+    const int tiles_j = (d.J + 31) / 32;
+    const int j0 = (blockIdx.x % tiles_j) * 32, ip0 = (blockIdx.x / tiles_j) * 32;
+    const int t = threadIdx.x, r = t >> 3, c4 = (t & 7) * 4;
+    const int ip = min(ip0 + r, Ip - 1), j = min(j0 + c4, d.J - 4);      // clamped lanes compute, never store
+    const int64_t plane = (int64_t)d.I * d.J;
+    const float* src = d.part + (int64_t)ip * d.pool * d.J + j;
+    float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int n = d.pool * d.splits;
+    for (int q0 = 0; q0 < n; q0 += 16) {                                 // q = p * splits + z: ascending (p, z)
+        float4 v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int q = min(q0 + u, n - 1), pp = q / d.splits, z = q - pp * d.splits;
+            v[u] = *reinterpret_cast<const float4*>(src + (int64_t)pp * d.J + (int64_t)z * plane);
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u)
+            if (q0 + u < n) { sum.x += v[u].x; sum.y += v[u].y; sum.z += v[u].z; sum.w += v[u].w; }
+    }
+    sum.x *= d.out_scale; sum.y *= d.out_scale; sum.z *= d.out_scale; sum.w *= d.out_scale;
+    const bool live = ip0 + r < Ip && j0 + c4 < d.J;
+    if (!d.transpose_out) {
+        if (live) *reinterpret_cast<float4*>(d.out + (int64_t)ip * d.J + j) = sum;
+        return;
+    }
+    tr[c4][r] = sum.x; tr[c4 + 1][r] = sum.y; tr[c4 + 2][r] = sum.z; tr[c4 + 3][r] = sum.w;
+    __syncthreads();
+    const int jj = t >> 3, iq = (t & 7) * 4;                             // output row j0 + jj, pooled rows ip0 + iq .. +3
+    if (j0 + jj < d.J && ip0 + iq < Ip)
+        *reinterpret_cast<float4*>(d.out + (int64_t)(j0 + jj) * Ip + ip0 + iq) =
+            make_float4(tr[jj][iq], tr[jj][iq + 1], tr[jj][iq + 2], tr[jj][iq + 3]);
 }
 
 }  // namespace
@@ -434,7 +475,16 @@ int launch_grad(const GradDesc& d, hipStream_t st) {
         if ((rc = set_lds_once(k_grad_partial, smem, set_general))) return rc;
         hipLaunchKernelGGL(k_grad_partial, grid, dim3(kThreads), smem, st, d, slice_len);
     }
-    int64_t total = (int64_t)(d.I / d.pool) * d.J;
+    const int Ip = d.I / d.pool;
+    auto aligned16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
+    // measured: the plain kernel is the faster one when the output is not transposed (5.1 vs 5.5 us), the
+    // tiled one when it is (5.8 vs 7.5 us)
+    if (d.transpose_out && d.J % 4 == 0 && Ip % 4 == 0 && aligned16(d.part) && aligned16(d.out)) {
+        const int64_t tiles = (int64_t)((d.J + 31) / 32) * ((Ip + 31) / 32);
+        hipLaunchKernelGGL(k_grad_reduce_tile, dim3((unsigned)tiles), dim3(256), 0, st, d);
+        return launch_status();
+    }
+    int64_t total = (int64_t)Ip * d.J;
     hipLaunchKernelGGL(k_grad_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, d);
     return launch_status();
 }
