@@ -316,6 +316,12 @@ int qblora_linear_decode(const qblora_qweight* qw, const void* pack, const qblor
  * 256; the values of one block for the rows of a tile are adjacent), so that a wave's load of one block
  * for 16 rows touches 5 cache lines instead of 32.  qblora_linear_decode with pack = NULL reads the
  * row-major arrays of `qw` (same result, about half the speed); with a pack it needs no workspace.
+ * A pack belongs to the description it was made from: pass the same `qw` (codebook, offsets, block shape)
+ * to qblora_linear_decode.  For an INT4 model -- codebook exactly 0, 1, ..., 15 with offsets, 64-blocks, the
+ * output of the min-max quantizer and of qablora_merge_quantize -- the pack also regroups the nibbles of
+ * every code dword and the kernel contracts the codes as the bf16 values 128 + c, taking the 128 off through
+ * the block's activation sum (alpha*sum x(128+c) + (beta - 128 alpha)*sum x): the same sums in another
+ * rounding order, equal to the unpacked result to about 1e-5 of the output scale, not bit for bit.
  */
 size_t qblora_decode_pack_bytes(const qblora_qweight* qw);
 int qblora_decode_pack(const qblora_qweight* qw, void* pack, void* stream);

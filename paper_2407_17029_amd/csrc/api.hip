@@ -701,6 +701,16 @@ int qblora_merge_bf16(const qblora_qweight* base, const float* H, int32_t lambda
 namespace {
 
 struct DecodePack { uint8_t* codes; float* scales; float* beta; size_t bytes; };
+
+// An INT4 model in 64-blocks (codebook exactly 0, 1, ..., 15 and offsets present): its pack holds the codes
+// with the nibbles of every dword regrouped for the table-free decode kernel.  Pack and decode both decide
+// from the weight's description, which a pack belongs to.
+bool decode_regrouped(const qblora_qweight* qw) {
+    if (!qw->beta || block_rows_of(qw) != 1) return false;
+    for (int j = 0; j < 16; ++j)
+        if (qw->codebook[j] != (float)j) return false;
+    return true;
+}
 DecodePack carve_pack(const qblora_qweight* qw, void* base) {
     Carver c(base);
     DecodePack p{};
@@ -729,7 +739,7 @@ int qblora_decode_pack(const qblora_qweight* qw, void* pack, void* stream) {
     if (!pack) return QBLORA_ERR_NULL;
     hipStream_t st = as_stream(stream);
     DecodePack p = carve_pack(qw, pack);
-    if ((rc = launch_prepack_codes(qw->codes, qw->d_out, qw->d_in, p.codes, st))) return rc;
+    if ((rc = launch_prepack_codes(qw->codes, qw->d_out, qw->d_in, p.codes, st, decode_regrouped(qw)))) return rc;
     if (block_rows_of(qw) == 8) return QBLORA_OK;
     ScaleTiling sct{};
     const bool grouped = qw->scale_mode == QBLORA_SCALES_E4M3_GROUPED;
@@ -766,7 +776,7 @@ int qblora_linear_decode(const qblora_qweight* qw, const void* pack, const qblor
     if (pack) {
         DecodePack p = carve_pack(qw, const_cast<void*>(pack));
         return launch_w4_decode(p.codes, p.scales, p.beta, codebook_of(qw), 1, qw->d_out, qw->d_in, X, T, Y, st,
-                                block_rows_of(qw));
+                                block_rows_of(qw), decode_regrouped(qw));
     }
     const float* scales = nullptr;
     const size_t need = qblora_linear_decode_workspace_bytes(qw);

@@ -54,7 +54,7 @@ int launch_quantize_codebook(const float* W, int d_out, int d_in, const Codebook
                              uint8_t* tiled, float* absmax, hipStream_t st, int block_rows = 1);
 int launch_quantize_minmax(const float* W, int d_out, int d_in, uint8_t* codes, uint8_t* tiled, float* alpha,
                            float* beta, hipStream_t st, int block_rows = 1);
-int launch_prepack_codes(const uint8_t* codes, int d_out, int d_in, uint8_t* tiled, hipStream_t st);
+int launch_prepack_codes(const uint8_t* codes, int d_out, int d_in, uint8_t* tiled, hipStream_t st, int regroup = 0);
 
 // byte offset of the 32-byte run of (row n, 64-block b) in the tiled code copy
 __host__ __device__ inline int64_t tiled_run_offset(int64_t n, int64_t b, int64_t blocks_per_row) {
@@ -147,7 +147,7 @@ struct MergeDesc {
 int launch_merge_requant(const MergeDesc& d, hipStream_t st);
 int launch_merge_bf16(const MergeDesc& d, hipStream_t st);
 int launch_w4_decode(const uint8_t* codes, const float* scales, const float* beta, const Codebook& cb, int tiled,
-                     int d_out, int d_in, const qblora_bf16* X, int T, qblora_bf16* Y, hipStream_t st, int block_rows = 1);
+                     int d_out, int d_in, const qblora_bf16* X, int T, qblora_bf16* Y, hipStream_t st, int block_rows = 1, int regrouped = 0);
 int launch_merge_beta_shift(const MergeDesc& d, hipStream_t st);
 
 }  // namespace qblora

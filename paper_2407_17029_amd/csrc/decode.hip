@@ -22,6 +22,12 @@
 // MFMA, so it cannot act on partial sums: there the lane builds the bf16 compute weight
 // bf16(fma(c, alpha, beta)) of its 16 inputs (two block columns; the byte table then holds fp32 pairs) and
 // the MFMAs accumulate directly -- the arithmetic of the training forward.
+//
+// INT4 models (codebook exactly 0..15, offsets present, packed arrays: DIRECT) need no table: the bf16 with
+// bits 0x4300 | c is 128 + c, so two shift/and-or instructions turn a code dword into an operand dword
+// (the pack regroups the nibbles of every dword for that), and the 128 comes off through the block's
+// sum of activations, which the offset term computes anyway:
+// alpha * sum x (128 + c) + (beta - 128 alpha) * sum x.
 #include "common.h"
 
 namespace qblora {
@@ -49,10 +55,11 @@ struct DecodeRegs {                         // one group = 4 consecutive blocks 
     uint4 x[4][2];                          // activations of the lane's token, 8 per MFMA
 };
 
-template <bool BETA, int BR>
+template <bool BETA, int BR, bool DIRECT = false>
 __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
+    static_assert(!DIRECT || (BETA && BR == 1), "the table-free form needs offsets and 64-blocks");
     // entry e of replica q at e*kReplicas + q: bf16 pairs (4 bytes), or fp32 pairs (8 bytes) for BR = 8
-    __shared__ __align__(8) uint32_t pair[256 * kReplicas * (BR == 8 ? 2 : 1)];
+    __shared__ __align__(8) uint32_t pair[DIRECT ? 2 : 256 * kReplicas * (BR == 8 ? 2 : 1)];
     __shared__ float red[4][4][64];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int nl = lane & 15, kg = lane >> 4;
@@ -65,7 +72,9 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
     const int n = min(n0 + nl, d.d_out - 1);                  // rows past the end are computed, not stored
     const int bpr = d.d_in / kBlock;
     const int groups = (bpr + 3) / 4;
-    if constexpr (BR == 8) {
+    if constexpr (DIRECT) {
+        // no table
+    } else if constexpr (BR == 8) {
         const float2 e = make_float2(d.cb.c[t & 15], d.cb.c[t >> 4]);
 #pragma unroll
         for (int q = 0; q < kReplicas; ++q) reinterpret_cast<float2*>(pair)[t * kReplicas + q] = e;
@@ -115,6 +124,7 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
                 if constexpr (BETA) {
                     const float bt = brow[(int64_t)bc * bstep];
                     r.b[q] = in ? bt : 0.0f;
+                    if constexpr (DIRECT) r.b[q] = __builtin_fmaf(-128.0f, r.a[q], r.b[q]);
                 } else {
                     r.b[q] = 0.0f;
                 }
@@ -129,6 +139,11 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
     const uint4 ones4 = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
     const bf16x8 ones = __builtin_bit_cast(bf16x8, ones4);
     auto operand = [&](uint32_t w) __attribute__((always_inline)) {
+        if constexpr (DIRECT) {
+            const uint4 v = make_uint4((w & 0x000F000Fu) | 0x43004300u, ((w >> 4) & 0x000F000Fu) | 0x43004300u,
+                                       ((w >> 8) & 0x000F000Fu) | 0x43004300u, ((w >> 12) & 0x000F000Fu) | 0x43004300u);
+            return __builtin_bit_cast(bf16x8, v);
+        }
         const uint4 v = make_uint4(my_pair[(w & 0xffu) * kReplicas], my_pair[((w >> 8) & 0xffu) * kReplicas],
                                    my_pair[((w >> 16) & 0xffu) * kReplicas], my_pair[(w >> 24) * kReplicas]);
         return __builtin_bit_cast(bf16x8, v);
@@ -206,12 +221,18 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
 }  // namespace
 
 int launch_w4_decode(const uint8_t* codes, const float* scales, const float* beta, const Codebook& cb, int tiled,
-                     int d_out, int d_in, const qblora_bf16* X, int T, qblora_bf16* Y, hipStream_t st, int block_rows) {
+                     int d_out, int d_in, const qblora_bf16* X, int T, qblora_bf16* Y, hipStream_t st, int block_rows,
+                     int regrouped) {
     DecodeDesc d{codes, scales, beta, cb, tiled, block_rows, d_out, d_in, X, T, Y};
     const dim3 grid((unsigned)(((d_out + 15) / 16 + 15) / 16 * 16));
     if (block_rows == 8) {
         if (beta) hipLaunchKernelGGL((k_w4_decode<true, 8>), grid, dim3(256), 0, st, d);
         else hipLaunchKernelGGL((k_w4_decode<false, 8>), grid, dim3(256), 0, st, d);
+        return launch_status();
+    }
+    if (regrouped) {                        // codes regrouped by the pack: INT4 model with offsets, table-free
+        if (!beta || !tiled) return QBLORA_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL((k_w4_decode<true, 1, true>), grid, dim3(256), 0, st, d);
         return launch_status();
     }
     if (beta) hipLaunchKernelGGL((k_w4_decode<true, 1>), grid, dim3(256), 0, st, d);

@@ -354,10 +354,20 @@ __global__ __launch_bounds__(256) void k_dequantize_bf16(const uint32_t* __restr
     out[i] = o;
 }
 
+// Nibbles of a code dword regrouped for the table-free decode: position p of the result holds input k(p),
+// k = 0, 2, 4, 6, 1, 3, 5, 7 -- the even inputs in the low half, the odd ones in the high half, so that
+// (w >> 4i) & 0x000F000F is the pair (input 2i, input 2i+1) in the low bits of two 16-bit lanes.
+__device__ __forceinline__ uint32_t regroup_nibbles(uint32_t w) {
+    uint32_t e = w & 0x0F0F0F0Fu, o = (w >> 4) & 0x0F0F0F0Fu;
+    e = (e | (e >> 4)) & 0x00FF00FFu; e = (e | (e >> 8)) & 0x0000FFFFu;
+    o = (o | (o >> 4)) & 0x00FF00FFu; o = (o | (o >> 8)) & 0x0000FFFFu;
+    return e | (o << 16);
+}
+
 // Tile-ordered copy of the codes: one thread moves one 16-byte half of a (row, 64-block) run; rows past
-// d_out inside the last tile are written as zeros.
+// d_out inside the last tile are written as zeros.  `regroup`: the decode pack of an INT4 model (above).
 __global__ __launch_bounds__(256) void k_prepack_codes(const uint8_t* __restrict__ codes, int d_out, int bpr,
-                                                       int64_t n_halves, uint8_t* __restrict__ tiled) {
+                                                       int64_t n_halves, uint8_t* __restrict__ tiled, int regroup) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;        // index of a 16-byte piece of the tiled copy
     if (i >= n_halves) return;
     const int half = (int)(i & 1);
@@ -368,16 +378,17 @@ __global__ __launch_bounds__(256) void k_prepack_codes(const uint8_t* __restrict
     const int64_t n = tile * 256 + r;
     uint4 v = make_uint4(0, 0, 0, 0);
     if (n < d_out) v = *reinterpret_cast<const uint4*>(codes + (n * bpr + b) * 32 + half * 16);
+    if (regroup) v = make_uint4(regroup_nibbles(v.x), regroup_nibbles(v.y), regroup_nibbles(v.z), regroup_nibbles(v.w));
     *reinterpret_cast<uint4*>(tiled + i * 16) = v;
 }
 
 }  // namespace
 
-int launch_prepack_codes(const uint8_t* codes, int d_out, int d_in, uint8_t* tiled, hipStream_t st) {
+int launch_prepack_codes(const uint8_t* codes, int d_out, int d_in, uint8_t* tiled, hipStream_t st, int regroup) {
     const int bpr = d_in / kBlock;
     const int64_t n_halves = (int64_t)((d_out + 255) / 256) * 256 * bpr * 2;
     hipLaunchKernelGGL(k_prepack_codes, dim3((unsigned)((n_halves + 255) / 256)), dim3(256), 0, st, codes, d_out, bpr,
-                       n_halves, tiled);
+                       n_halves, tiled, regroup);
     return launch_status();
 }
 

@@ -32,10 +32,15 @@ def test_decode_parity(qb, oracle, codebook, T, d_out, d_in, base):
     Y = qb.qblora_linear_decode(qw, X)
     Yp = qb.qblora_linear_decode(qw, X, pack=qb.qblora_decode_pack(qw))
     torch.cuda.synchronize()
-    assert torch.equal(Y.view(torch.int16), Yp.view(torch.int16))       # tile-ordered pack: same bits
+    if base != "minmax":
+        assert torch.equal(Y.view(torch.int16), Yp.view(torch.int16))   # tile-ordered pack: same sums, same bits
     ow = OracleWeight(oracle, L.W, codebook, base == "minmax", base == "grouped").assert_same(qw)
     Wt = ow.dequantize(oracle, 3)                                        # the inference weight: alpha*bf16(c)+beta
-    assert_close_bf16(Y, oracle.forward(Wt, L.X, None, None, 1, 1, 0.0), "Y")
+    ref = oracle.forward(Wt, L.X, None, None, 1, 1, 0.0)
+    assert_close_bf16(Y, ref, "Y")
+    # the pack of an INT4 model with offsets is contracted without the code table (operand 128 + c, the 128
+    # taken off through the block's activation sum): other roundings, same result within the bar
+    assert_close_bf16(Yp, ref, "Y (packed)")
 
 
 def test_decode_of_the_merged_int4_model(qb, oracle, codebook):
