@@ -624,8 +624,11 @@ int qblora_tile_product(const qblora_adapter* ad, int32_t d_in, int32_t d_out, f
     size_t need = qblora_tile_product_workspace_bytes(ad, d_in, d_out);
     if (!workspace || workspace_bytes < need) return QBLORA_ERR_WORKSPACE;
     hipStream_t st = as_stream(stream);
+    // whole tiles: one kernel that transposes B on the fly; otherwise a transposed copy and the general GEMM
+    int rc = launch_tile_product(ad->A, ad->B, rows, cols, ad->R, H, st);
+    if (rc != QBLORA_ERR_UNSUPPORTED) return rc;
     qblora_bf16* Bt = static_cast<qblora_bf16*>(workspace);
-    int rc = launch_adapter_prep(ad->A, ad->B, d_in, d_out, ad->R, ad->lambda1, ad->lambda2, nullptr, Bt, nullptr, st);
+    rc = launch_adapter_prep(ad->A, ad->B, d_in, d_out, ad->R, ad->lambda1, ad->lambda2, nullptr, Bt, nullptr, st);
     if (rc) return rc;
     GemmDesc g{};
     g.qmode = 0;

@@ -146,6 +146,8 @@ struct MergeDesc {
 };
 int launch_merge_requant(const MergeDesc& d, hipStream_t st);
 int launch_merge_bf16(const MergeDesc& d, hipStream_t st);
+// H = A * B (fp32) for whole 64 x 128 tiles and R % 16 == 0; QBLORA_ERR_UNSUPPORTED otherwise (nothing launched)
+int launch_tile_product(const qblora_bf16* A, const qblora_bf16* B, int rows, int cols, int R, float* H, hipStream_t st);
 int launch_w4_decode(const uint8_t* codes, const float* scales, const float* beta, const Codebook& cb, int tiled,
                      int d_out, int d_in, const qblora_bf16* X, int T, qblora_bf16* Y, hipStream_t st, int block_rows = 1, int regrouped = 0);
 int launch_merge_beta_shift(const MergeDesc& d, hipStream_t st);

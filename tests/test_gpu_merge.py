@@ -19,7 +19,8 @@ def _bits(a):
     return a.view(np.uint32)
 
 
-@pytest.mark.parametrize("d_out,d_in,R,lam1,lam2", [(512, 512, 32, 2, 2), (320, 192, 16, 4, 8), (256, 1024, 64, 1, 1)])
+@pytest.mark.parametrize("d_out,d_in,R,lam1,lam2", [(512, 512, 32, 2, 2), (320, 192, 16, 4, 8), (256, 1024, 64, 1, 1),
+                                                    (1024, 512, 256, 2, 2), (512, 256, 144, 4, 2), (768, 384, 128, 2, 3)])
 def test_tile_product(qb, oracle, d_out, d_in, R, lam1, lam2):
     from gpu_util import adapter_to_dev, assert_close_f32
     L = synth.make_layer(800, 1, d_out, d_in, R, lam1, lam2)
