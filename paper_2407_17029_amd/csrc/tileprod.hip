@@ -6,7 +6,7 @@
 // row); B is stored with k down the columns, so every thread fetches one 8 x 8 block of it (eight 16-byte
 // loads), transposes it in registers with byte permutes and writes eight 16-byte rows -- the [column][k]
 // tile the MFMA operand wants, without a transposed copy of B in HBM and without a second launch.  Rows of
-// both tiles are 256 bytes with the 16-byte chunks XOR-swizzled by (row & 15), which makes the fragment
+// both tiles are 256 bytes with the 16-byte chunks XOR-swizzled by (row ^ row >> 3) & 15, which makes the fragment
 // reads and the tile writes conflict-free.  The B tile is the MFMA A operand and the A tile the B operand,
 // so a lane ends up with 4 consecutive columns of one row of H; the wave lays its 32 x 64 part out in LDS
 // and stores whole 256-byte row segments.
@@ -19,7 +19,9 @@ namespace {
 constexpr int kTpRows = 64, kTpCols = 128, kTpK = 128;
 constexpr int kTpPitch = 64 * 4 + 16;                      // bytes per staged output row of a wave
 
-__device__ __forceinline__ int tp_swz(int row, int chunk) { return row * 256 + ((chunk ^ (row & 15)) << 4); }
+// 16 consecutive rows (fragment reads) and 16 rows 8 apart (the transposed writes of one k block) both land
+// on 16 different chunks
+__device__ __forceinline__ int tp_swz(int row, int chunk) { return row * 256 + ((chunk ^ ((row ^ (row >> 3)) & 15)) << 4); }
 
 __global__ __launch_bounds__(256) void k_tile_product(const qblora_bf16* __restrict__ A, const qblora_bf16* __restrict__ B,
                                                       int rows, int cols, int R, float* __restrict__ H) {
