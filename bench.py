@@ -40,6 +40,8 @@ def main() -> int:
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-next-rows", action="store_true", help="skip the untimed side measurement of the single-matrix adapter")
+    ap.add_argument("--plain-events", action="store_true",
+                    help="time the kernels with ordinary HIP events (system-scope fence at every record)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device copy of 256 MiB before the timed steps, so that a counter "
                          "profile of this command holds a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
@@ -113,7 +115,11 @@ def main() -> int:
     kinds = {"fwd_gemm": qb.PROFILE_FWD_GEMM, "bwd_gemm": qb.PROFILE_BWD_GEMM, "merge": qb.PROFILE_MERGE,
              "quantize": qb.PROFILE_QUANTIZE}
     side_steps = min(args.steps, 10)
-    events = {k: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+    # The events only measure time (hipEventDisableSystemFence): an ordinary event record also writes back and
+    # invalidates the caches at system scope, which costs stream time and slows the kernel behind it.
+    # --plain-events uses torch's ordinary timing events instead.
+    new_event = (lambda: torch.cuda.Event(enable_timing=True)) if args.plain_events else qb.TimingEvent
+    events = {k: [(new_event(), new_event())
                   for _ in range(args.steps if k == "fwd_gemm" else side_steps)] for k in kinds}
     for pairs in events.values():
         for a, b in pairs:
@@ -142,7 +148,10 @@ def main() -> int:
         qb.qblora_profile_events(which, None, None)
 
     raw_kernel_ms = {k: float(np.mean([a.elapsed_time(b) for a, b in pairs])) for k, pairs in events.items()}
-    kernel_ms = {k: max(v - empty_pair_ms, 1e-6) for k, v in raw_kernel_ms.items()}
+    # The empty-pair time is taken off the two GEMMs only, where the result agrees with the kernel trace of the
+    # same launches to 1 %; for kernels of 10-20 us the overlap of the second record with the kernel's tail is
+    # not that regular (trace: -10 % .. +8 %), so their elapsed times are reported as measured (an upper bound).
+    kernel_ms = {k: (max(v - empty_pair_ms, 1e-6) if k in ("fwd_gemm", "bwd_gemm") else v) for k, v in raw_kernel_ms.items()}
     ms_per_step = elapsed * 1e3 / args.steps
     flops_step = 4.0 * T * d_in * d_out + 6.0 * T * r * (d_in + d_out)
     value = flops_step / (ms_per_step * 1e-3) / 1e12
@@ -174,10 +183,10 @@ def main() -> int:
                          "achieved": round(bwd_kernel_flops / (kernel_ms["bwd_gemm"] * 1e-3) / 1e12, 2),
                          "unit": "TFLOP/s",
                          "frac": round(bwd_kernel_flops / (kernel_ms["bwd_gemm"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)},
-            "merge_requant": {"bound": "hbm", "avg_kernel_ms": round(kernel_ms["merge"], 4),
+            "merge_requant": {"bound": "hbm", "event_overhead_included": True, "avg_kernel_ms": round(kernel_ms["merge"], 4),
                               "achieved": round(merge_bytes / (kernel_ms["merge"] * 1e-3) / 1e9, 1), "unit": "GB/s",
                               "frac": round(merge_bytes / (kernel_ms["merge"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
-            "quantize": {"bound": "hbm", "avg_kernel_ms": round(kernel_ms["quantize"], 4),
+            "quantize": {"bound": "hbm", "event_overhead_included": True, "avg_kernel_ms": round(kernel_ms["quantize"], 4),
                          "achieved": round(quant_bytes / (kernel_ms["quantize"] * 1e-3) / 1e9, 1), "unit": "GB/s",
                          "frac": round(quant_bytes / (kernel_ms["quantize"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         },

@@ -112,11 +112,55 @@ def lib():
     return _lib
 
 
-def qblora_profile_events(which: int, start: "torch.cuda.Event" = None, stop: "torch.cuda.Event" = None) -> None:
+_hip = None
+
+
+def _hip_runtime():
+    """The HIP runtime the process already uses (torch has loaded it)."""
+    global _hip
+    if _hip is None:
+        _hip = C.CDLL("libamdhip64.so")
+        _hip.hipEventCreateWithFlags.argtypes = [C.POINTER(C.c_void_p), C.c_uint]
+        _hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        _hip.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        _hip.hipEventDestroy.argtypes = [C.c_void_p]
+    return _hip
+
+
+class TimingEvent:
+    """A HIP event that only measures time: created with hipEventDisableSystemFence, i.e. without the
+    system-scope cache write-back and invalidation an ordinary event record performs (which costs stream time
+    and slows the kernel behind it).  Read it only after the stream has been synchronized by other means."""
+    DISABLE_SYSTEM_FENCE = 0x20000000
+
+    def __init__(self):
+        h = C.c_void_p()
+        if _hip_runtime().hipEventCreateWithFlags(C.byref(h), self.DISABLE_SYSTEM_FENCE) != 0:
+            raise QBLoRAError("hipEventCreateWithFlags failed")
+        self.cuda_event = h.value
+
+    def record(self, stream=None):
+        if _hip_runtime().hipEventRecord(self.cuda_event, _stream() if stream is None else stream) != 0:
+            raise QBLoRAError("hipEventRecord failed")
+
+    def elapsed_time(self, stop: "TimingEvent") -> float:
+        ms = C.c_float()
+        if _hip_runtime().hipEventElapsedTime(C.byref(ms), self.cuda_event, stop.cuda_event) != 0:
+            raise QBLoRAError("hipEventElapsedTime failed")
+        return float(ms.value)
+
+    def __del__(self):
+        try:
+            _hip_runtime().hipEventDestroy(self.cuda_event)
+        except Exception:
+            pass
+
+
+def qblora_profile_events(which: int, start=None, stop=None) -> None:
     """Register (or with None, unregister) a pair of timing events recorded around one kernel.
 
-    The events must have been created with enable_timing=True and recorded once already so that
-    their native handles exist.
+    `start` / `stop`: TimingEvent, or torch.cuda.Event created with enable_timing=True and recorded once
+    already so that its native handle exists.
     """
     a = None if start is None else C.c_void_p(start.cuda_event)
     b = None if stop is None else C.c_void_p(stop.cuda_event)
