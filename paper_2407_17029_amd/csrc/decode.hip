@@ -52,15 +52,26 @@ struct DecodeRegs {                         // one group = 4 consecutive blocks 
     uint2 c[4];                             // the lane's quarter of each block's codes: 16 codes
     float a[4], b[4];                       // scale and offset of each block
     float2 a2[4], b2[4];                    // BR = 8: scales and offsets of the lane's two block columns
-    uint4 x[4][2];                          // activations of the lane's token, 8 per MFMA
+    uint4 x[4][2];                          // activations of the lane's token, 8 per MFMA (fetched in operand order)
+    uint4 xg[8];                            // XLDS: as fetched, token 2p + (lane >> 5), chunk lane & 31 of the group
 };
 
-template <bool BETA, int BR, bool DIRECT = false>
+// XLDS (used above 8 tokens): the activations go through LDS.  In operand order a load instruction touches
+// 16 token rows, 64 bytes of each; with more than a few tokens these loads, not the codes, fill the address
+// path (T = 16: 55 us against 29 at T = 1).  Fetched as whole 512-byte row segments and re-read from LDS in
+// operand order they cost half the cache-line accesses (44 us); for few tokens the extra LDS round trip is the
+// slower way (T = 1: 35 us; the two meet at 8 tokens), hence the switch.
+template <bool BETA, int BR, bool DIRECT = false, bool XLDS = false>
 __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
     static_assert(!DIRECT || (BETA && BR == 1), "the table-free form needs offsets and 64-blocks");
     // entry e of replica q at e*kReplicas + q: bf16 pairs (4 bytes), or fp32 pairs (8 bytes) for BR = 8
     __shared__ __align__(8) uint32_t pair[DIRECT ? 2 : 256 * kReplicas * (BR == 8 ? 2 : 1)];
     __shared__ float red[4][4][64];
+    // Activations of one group of 4 blocks (16 tokens x 512 bytes), one region per wave: fetched as whole
+    // 512-byte row segments (two token rows per load instruction) and read back in operand order.  A row is
+    // 528 bytes so that the 16 tokens of an operand read start 16 bytes apart modulo 256.
+    constexpr int kXPitch = 528;
+    __shared__ __align__(16) unsigned char xs_all[XLDS ? 4 : 1][XLDS ? 16 * kXPitch : 16];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int nl = lane & 15, kg = lane >> 4;
     // Row groups 2i and 2i+1 share the 128-byte lines of the tile-ordered scales and offsets (16 rows = 64
@@ -98,6 +109,8 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
     // BR = 8: block row n/8, block columns 8*b + 2*kg, +1 of 64-input step b
     const int64_t run8 = (int64_t)(n >> 3) * (d.d_in >> 3) + 2 * kg;
     const int cstep = bstep * 32;
+    unsigned char* xs = xs_all[XLDS ? wave : 0];
+    const int xtok = lane >> 5, xchunk = lane & 31;
     const qblora_bf16* xrow = d.X + (int64_t)min(nl, d.T - 1) * d.d_in + 16 * kg;
 
     // Every load is unconditional: a block past the end of the row is redirected to the last block and
@@ -129,8 +142,22 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
                     r.b[q] = 0.0f;
                 }
             }
+            if constexpr (!XLDS) {
 #pragma unroll
-            for (int m = 0; m < 2; ++m) r.x[q][m] = *reinterpret_cast<const uint4*>(xrow + bc * kBlock + 8 * m);
+                for (int m = 0; m < 2; ++m) r.x[q][m] = *reinterpret_cast<const uint4*>(xrow + bc * kBlock + 8 * m);
+            }
+        }
+        if constexpr (!XLDS) return;
+        // Token rows that do not exist are not fetched (their LDS rows keep old contents and feed output rows
+        // that are never stored); chunks of blocks past the end of the row are redirected to the last block,
+        // whose scale and offset are zero there.
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            if (2 * p < d.T) {
+                const int tk = min(2 * p + xtok, d.T - 1);
+                const int bc = min(4 * j + (xchunk >> 3), bpr - 1);
+                r.xg[p] = *reinterpret_cast<const uint4*>(d.X + (int64_t)tk * d.d_in + bc * kBlock + 8 * (xchunk & 7));
+            }
         }
     };
 
@@ -159,9 +186,20 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
         return __builtin_bit_cast(bf16x8, make_uint4(o[0], o[1], o[2], o[3]));
     };
     auto compute = [&](const DecodeRegs& r) __attribute__((always_inline)) {
+        if constexpr (XLDS) {
+#pragma unroll
+            for (int p = 0; p < 8; ++p)
+                if (2 * p < d.T) *reinterpret_cast<uint4*>(xs + (2 * p + xtok) * kXPitch + xchunk * 16) = r.xg[p];
+        }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const bf16x8 x0 = __builtin_bit_cast(bf16x8, r.x[q][0]), x1 = __builtin_bit_cast(bf16x8, r.x[q][1]);
+            bf16x8 x0, x1;
+            if constexpr (XLDS) {
+                const unsigned char* xq = xs + nl * kXPitch + 128 * q + 32 * kg;    // k = 64q + 16kg .. +15 of token nl
+                x0 = *reinterpret_cast<const bf16x8*>(xq); x1 = *reinterpret_cast<const bf16x8*>(xq + 16);
+            } else {
+                x0 = __builtin_bit_cast(bf16x8, r.x[q][0]); x1 = __builtin_bit_cast(bf16x8, r.x[q][1]);
+            }
             if constexpr (BR == 8) {
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x0, weights8(r.c[q].x, r.a2[q].x, r.b2[q].x), acc, 0, 0, 0);
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x1, weights8(r.c[q].y, r.a2[q].y, r.b2[q].y), acc, 0, 0, 0);
@@ -225,19 +263,22 @@ int launch_w4_decode(const uint8_t* codes, const float* scales, const float* bet
                      int regrouped) {
     DecodeDesc d{codes, scales, beta, cb, tiled, block_rows, d_out, d_in, X, T, Y};
     const dim3 grid((unsigned)(((d_out + 15) / 16 + 15) / 16 * 16));
-    if (block_rows == 8) {
-        if (beta) hipLaunchKernelGGL((k_w4_decode<true, 8>), grid, dim3(256), 0, st, d);
-        else hipLaunchKernelGGL((k_w4_decode<false, 8>), grid, dim3(256), 0, st, d);
+    const bool xlds = T > 8;                    // activations through LDS: measured equal at 8 tokens, see the kernel's comment
+    auto go = [&](auto plain, auto staged) -> int {
+        if (xlds) hipLaunchKernelGGL(staged, grid, dim3(256), 0, st, d);
+        else hipLaunchKernelGGL(plain, grid, dim3(256), 0, st, d);
         return launch_status();
+    };
+    if (block_rows == 8) {
+        if (beta) return go(k_w4_decode<true, 8, false, false>, k_w4_decode<true, 8, false, true>);
+        return go(k_w4_decode<false, 8, false, false>, k_w4_decode<false, 8, false, true>);
     }
     if (regrouped) {                        // codes regrouped by the pack: INT4 model with offsets, table-free
         if (!beta || !tiled) return QBLORA_ERR_UNSUPPORTED;
-        hipLaunchKernelGGL((k_w4_decode<true, 1, true>), grid, dim3(256), 0, st, d);
-        return launch_status();
+        return go(k_w4_decode<true, 1, true, false>, k_w4_decode<true, 1, true, true>);
     }
-    if (beta) hipLaunchKernelGGL((k_w4_decode<true, 1>), grid, dim3(256), 0, st, d);
-    else hipLaunchKernelGGL((k_w4_decode<false, 1>), grid, dim3(256), 0, st, d);
-    return launch_status();
+    if (beta) return go(k_w4_decode<true, 1, false, false>, k_w4_decode<true, 1, false, true>);
+    return go(k_w4_decode<false, 1, false, false>, k_w4_decode<false, 1, false, true>);
 }
 
 }  // namespace qblora
