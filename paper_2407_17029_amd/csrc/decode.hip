@@ -269,9 +269,10 @@ int launch_w4_decode(const uint8_t* codes, const float* scales, const float* bet
         else hipLaunchKernelGGL(plain, grid, dim3(256), 0, st, d);
         return launch_status();
     };
-    if (block_rows == 8) {
-        if (beta) return go(k_w4_decode<true, 8, false, false>, k_w4_decode<true, 8, false, true>);
-        return go(k_w4_decode<false, 8, false, false>, k_w4_decode<false, 8, false, true>);
+    if (block_rows == 8) {                  // its fp32 pair table and the activation rows together leave two
+                                            // workgroups per CU: measured slower (68 vs 64 us at T = 16), not used
+        if (beta) return go(k_w4_decode<true, 8, false, false>, k_w4_decode<true, 8, false, false>);
+        return go(k_w4_decode<false, 8, false, false>, k_w4_decode<false, 8, false, false>);
     }
     if (regrouped) {                        // codes regrouped by the pack: INT4 model with offsets, table-free
         if (!beta || !tiled) return QBLORA_ERR_UNSUPPORTED;
