@@ -4,9 +4,12 @@ shapes (where launch overhead no longer dominates) and the rows built next to th
 
     python -m paper_2407_17029_amd.kernel_bench [merge] [quantize] [decode] [qablora] [tile8]
 
-Each measurement is one JSON line: back-to-back launches between two HIP events on the current stream
-(warm caches; the 256 MB last-level cache holds the smaller shapes), algorithmic bytes or flops as defined
-in the design notes, and the fraction of the MI355X peak (HBM 8000 GB/s, bf16 MFMA 2500 TFLOP/s).  The
+Each measurement is one JSON line: 10 warm-up launches, then 50 back-to-back launches between two HIP events on
+the current stream, algorithmic bytes or flops as defined in the design notes, and the fraction of the MI355X
+peak (HBM 8000 GB/s, bf16 MFMA 2500 TFLOP/s).  `us` is with warm caches (the 256 MB last-level cache holds the
+operands of the smaller shapes between launches); `cold_us` (streaming kernels) rotates the launches over
+enough operand sets to exceed that cache, so every launch reads from HBM.  The one-off re-layouts
+(`prepack`, `decode_pack`) are lines of their own.  The
 short kernels are launched through the C ABI with arguments marshalled once, so that the host keeps ahead
 of the GPU (the Python wrappers cost ~25 us a call).
 """
@@ -27,7 +30,7 @@ SHAPES = [(4096, 4096), (11008, 4096), (22016, 8192)]          # 7B attention, 7
 DEV = "cuda:0"
 
 
-def timed(fn, iters=20, warm=3):
+def timed(fn, iters=50, warm=10):
     for _ in range(warm):
         fn()
     torch.cuda.synchronize()
@@ -38,6 +41,26 @@ def timed(fn, iters=20, warm=3):
     b.record()
     torch.cuda.synchronize()
     return a.elapsed_time(b) / iters * 1e-3                      # seconds per launch
+
+
+def timed_rotating(fns, iters=50, warm=10):
+    """Like timed(), the launches cycling through `fns` (one per operand set)."""
+    n = len(fns)
+    for i in range(warm):
+        fns[i % n]()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for i in range(iters):
+        fns[i % n]()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / iters * 1e-3
+
+
+def n_sets(bytes_per_set, cache_bytes=256 * 2**20):
+    """Operand sets needed so that a set has left the last-level cache when its turn comes again."""
+    return max(2, int(np.ceil(2 * cache_bytes / max(bytes_per_set, 1))) + 1)
 
 
 def emit(**kw):
@@ -54,9 +77,17 @@ def bench_quantize():
                 C.byref(q), qb._stream())
         s = timed(lambda: qb.lib().qblora_quantize_blockwise(*args))
         nbytes = d_out * d_in * (4 + 0.5 + 4 / 64)
+        # cold: every launch reads another copy of W
+        Ws = [W] + [W.clone() for _ in range(n_sets(4 * d_out * d_in) - 1)]
+        fns = []
+        for Wi in Ws:
+            ai = (qb._ptr(Wi),) + args[1:]
+            fns.append(lambda ai=ai: qb.lib().qblora_quantize_blockwise(*ai))
+        sc = timed_rotating(fns)
         emit(kernel="quantize_codebook", shape=[d_out, d_in], us=round(s * 1e6, 1), GBps=round(nbytes / s / 1e9, 1),
-             frac_hbm=round(nbytes / s / 1e9 / HBM_GBS, 3))
-        del W, qw
+             frac_hbm=round(nbytes / s / 1e9 / HBM_GBS, 3), cold_us=round(sc * 1e6, 1), cold_sets=len(Ws),
+             cold_frac_hbm=round(nbytes / sc / 1e9 / HBM_GBS, 3))
+        del W, qw, Ws, fns
 
 
 def bench_merge():
@@ -71,9 +102,22 @@ def bench_merge():
             args = (C.byref(b), qb._ptr(H), lam, lam, C.c_float(1.0), qb.MERGE_REQUANT_MINMAX, C.byref(o), qb._stream())
             s = timed(lambda: qb.lib().qablora_merge_quantize(*args))
             nbytes = d_out * d_in * (0.5 + 4 / 64 + 4.0 / (lam * lam) + 0.5 + 8 / 64)
+            # cold: every launch works on another copy of the weight, of H and of the output
+            keep, fns = [], []
+            for _ in range(n_sets(nbytes) - 1):
+                qi = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_ABSMAX_CODEBOOK, cb, tiled=False)
+                Hi = H.clone()
+                oi = qb.qablora_merge_quantize(qi, Hi, lam, lam, 1.0, qb.MERGE_REQUANT_MINMAX)
+                bi, ooi = qi.c_struct(), oi.c_struct()
+                ai = (C.byref(bi), qb._ptr(Hi), lam, lam, C.c_float(1.0), qb.MERGE_REQUANT_MINMAX, C.byref(ooi), qb._stream())
+                keep.append((qi, Hi, oi, bi, ooi))
+                fns.append(lambda ai=ai: qb.lib().qablora_merge_quantize(*ai))
+            fns.append(lambda: qb.lib().qablora_merge_quantize(*args))
+            sc = timed_rotating(fns)
             emit(kernel="merge_requant", shape=[d_out, d_in], lam=lam, us=round(s * 1e6, 1),
-                 GBps=round(nbytes / s / 1e9, 1), frac_hbm=round(nbytes / s / 1e9 / HBM_GBS, 3))
-            del W, qw, H, out
+                 GBps=round(nbytes / s / 1e9, 1), frac_hbm=round(nbytes / s / 1e9 / HBM_GBS, 3),
+                 cold_us=round(sc * 1e6, 1), cold_sets=len(fns), cold_frac_hbm=round(nbytes / sc / 1e9 / HBM_GBS, 3))
+            del W, qw, H, out, keep, fns
 
 
 def bench_decode():
@@ -81,6 +125,9 @@ def bench_decode():
         W = torch.randn(d_out, d_in, device=DEV) * 0.02
         qw = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_MINMAX_INT4, tiled=False)
         pack = qb.qblora_decode_pack(qw)
+        qp = qw.c_struct()
+        sp = timed(lambda: qb.lib().qblora_decode_pack(C.byref(qp), qb._ptr(pack), qb._stream()), iters=10, warm=2)
+        emit(kernel="decode_pack (one-off)", shape=[d_out, d_in], us=round(sp * 1e6, 1))
         for T in (1, 4, 16):
             X = torch.randn(T, d_in, device=DEV).to(torch.bfloat16)
             Y = torch.empty(T, d_out, dtype=torch.bfloat16, device=DEV)
