@@ -233,3 +233,45 @@ def test_8x8_blocks_mlp_shapes_reduced_tokens(qb, oracle, codebook):
         assert_close_f32(dH, rH, "dH")
         want = oracle.merge_beta_shift_tile(ow.beta, bf16_exact(Hb).astype(np.float32), d_out, d_in, 8, 8, lam1, lam2, s)
         assert np.array_equal(to_np(merged.beta).view(np.uint32), want.view(np.uint32))
+
+
+def test_token_count_beyond_2_31_elements(qb, oracle, codebook):
+    """Maximum sizes: T * d exceeds 2^31 elements, so every row offset in the kernels must be 64-bit.
+
+    The activations are a seeded block of 1024 token rows repeated down the token axis (513 times, ragged by 44
+    rows): forward / backward-dX are checked on rows on both sides of element offset 2^31 and at the end, the
+    parameter gradients in full -- the sum over tokens of a periodic input is the block's gradient times the
+    number of repetitions plus the gradient of the ragged rest, both from the oracle.
+    """
+    from gpu_util import f32_to_dev, bf16_to_dev, adapter_to_dev, assert_close_bf16, assert_close_f32
+    d_out, d_in, rank, lam, s, P = 4096, 4096, 16, 2, 0.5, 1024
+    T = (2**31) // d_in + 300                                        # 524588 rows: 2.149e9 elements per tensor
+    q, rem = divmod(T, P)
+    print(f"large case T={T} {d_out}x{d_in} (period {P}, {q} repetitions + {rem})", flush=True)
+    R = lam * rank
+    L = synth.make_layer(4100, P, d_out, d_in, R, lam, lam)
+    qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 64, qb.QUANT_ABSMAX_CODEBOOK, codebook)
+    ad = adapter_to_dev(L, lam, lam, s)
+    Xb, dYb = bf16_to_dev(L.X), bf16_to_dev(L.dY)
+    X = torch.cat([Xb.repeat(q, 1), Xb[:rem]]).contiguous()
+    dY = torch.cat([dYb.repeat(q, 1), dYb[:rem]]).contiguous()
+    assert X.numel() > 2**31 and X.shape[0] == T
+    Y = qb.qblora_linear_fwd(qw, ad, X)
+    dX, dA, dB = qb.qblora_linear_bwd(qw, ad, X, dY)
+    torch.cuda.synchronize()
+
+    codes, absmax = oracle.quantize_codebook(L.W, 64, codebook)
+    Wt = oracle.dequantize(codes, absmax, None, codebook, 64, 2)
+    edge = (2**31) // d_in                                            # first row whose elements lie beyond 2^31
+    rows = np.array([0, 1, P - 1, P, edge - 2, edge - 1, edge, edge + 1, edge + 255, T - 2, T - 1], dtype=np.int64)
+    Xs, dYs = np.ascontiguousarray(L.X[rows % P]), np.ascontiguousarray(L.dY[rows % P])
+    ridx = torch.from_numpy(rows).to(Y.device)
+    assert_close_bf16(Y[ridx], oracle.forward(Wt, Xs, L.A, L.B, lam, lam, s), "Y (rows around 2^31)")
+    rX, _, _ = oracle.backward(Wt, Xs, dYs, L.A, L.B, lam, lam, s, compute_dx=True, compute_dab=False)
+    assert_close_bf16(dX[ridx], rX, "dX (rows around 2^31)")
+    _, rA, rB = oracle.backward(None, L.X, L.dY, L.A, L.B, lam, lam, s, compute_dx=False, compute_dab=True,
+                                d_out=d_out, d_in=d_in)
+    _, rA2, rB2 = oracle.backward(None, np.ascontiguousarray(L.X[:rem]), np.ascontiguousarray(L.dY[:rem]), L.A, L.B,
+                                  lam, lam, s, compute_dx=False, compute_dab=True, d_out=d_out, d_in=d_in)
+    assert_close_f32(dA, q * rA + rA2, "dA")
+    assert_close_f32(dB, q * rB + rB2, "dB")
