@@ -275,3 +275,51 @@ def test_token_count_beyond_2_31_elements(qb, oracle, codebook):
                                   lam, lam, s, compute_dx=False, compute_dab=True, d_out=d_out, d_in=d_in)
     assert_close_f32(dA, q * rA + rA2, "dA")
     assert_close_f32(dB, q * rB + rB2, "dB")
+
+
+def test_weight_beyond_2_31_elements(qb, oracle, codebook):
+    """Maximum sizes on the weight side: d_out * d_in exceeds 2^31 elements (quantizers, tile-ordered copy,
+    standalone dequantize, offset-shift merge).  The weight is a seeded block of 256 rows repeated down the row
+    axis, so the oracle's result for the block is the expected value of every repetition; rows on both sides of
+    element offset 2^31 and the last rows are compared bit for bit."""
+    from gpu_util import f32_to_dev, to_np
+    d_in, P = 32768, 256
+    d_out = (2**31) // d_in + 2 * P                                  # 66048 rows: 2.164e9 elements
+    Wb = synth.base_weight(4200, 0, P, d_in)
+    print(f"large weight {d_out}x{d_in} (period {P})", flush=True)
+    W = f32_to_dev(Wb).repeat(d_out // P, 1).contiguous()
+    assert W.numel() > 2**31 and W.shape[0] == d_out
+    edge = (2**31) // d_in
+    spans = [(0, P), (edge - P, edge + P), (d_out - P, d_out)]        # whole periods: row r holds block row r % P
+
+    codes_b, absmax_b = oracle.quantize_codebook(Wb, 64, codebook)
+    qw = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_ABSMAX_CODEBOOK, codebook)
+    qm = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_MINMAX_INT4, tiled=False)
+    cm_b, am_b, bm_b = oracle.quantize_minmax(Wb, 64)
+    Wd = qb.qblora_dequantize_bf16(qm)
+    # offset-shift merge with lambda = (64, 8): one element of H per block, H periodic with the weight rows
+    lam1, lam2, s = 64, 8, 0.75
+    Hb = (np.random.default_rng(4201).standard_normal((d_in // lam1, P // lam2)) * 0.05).astype(np.float32)
+    H = f32_to_dev(Hb).repeat(1, d_out // P).contiguous()
+    merged = qb.qablora_merge_quantize(qm, H, lam1, lam2, s, qb.MERGE_BETA_SHIFT)
+    torch.cuda.synchronize()
+    beta_b = oracle.merge_beta_shift(bm_b, Hb, P, d_in, 64, lam1, lam2, s)
+    Wd_b = oracle.dequantize(cm_b, am_b, bm_b, synth.codebook_int4(), 64, 2)
+    from gpu_util import bf16_to_f64
+    for lo, hi in spans:
+        reps = (hi - lo) // P
+        tile = lambda a: np.tile(a, (reps, 1))
+        assert np.array_equal(to_np(qw.codes[lo:hi]), tile(codes_b))
+        assert np.array_equal(to_np(qw.scales[lo:hi]).view(np.uint32), tile(absmax_b).view(np.uint32))
+        assert np.array_equal(to_np(qm.codes[lo:hi]), tile(cm_b))
+        assert np.array_equal(to_np(qm.scales[lo:hi]).view(np.uint32), tile(am_b).view(np.uint32))
+        assert np.array_equal(to_np(qm.beta[lo:hi]).view(np.uint32), tile(bm_b).view(np.uint32))
+        assert np.array_equal(to_np(merged.beta[lo:hi]).view(np.uint32), tile(beta_b).view(np.uint32))
+        assert np.array_equal(bf16_to_f64(Wd[lo:hi]), tile(Wd_b))
+    # the tile-ordered copy of the codes is the canonical one, re-ordered (both written by the quantizer)
+    tiled_again = torch.empty_like(qw.codes_tiled)
+    keep = qw.codes_tiled
+    qw.codes_tiled = tiled_again
+    qb.qblora_prepack_codes(qw)
+    torch.cuda.synchronize()
+    assert torch.equal(keep, tiled_again)
