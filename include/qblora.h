@@ -315,7 +315,7 @@ int qblora_linear_decode(const qblora_qweight* qw, const void* pack, const qblor
  * fp32 block scales (grouped scales are reconstructed) and the offsets in tile order (rows in tiles of
  * 256; the values of one block for the rows of a tile are adjacent), so that a wave's load of one block
  * for 16 rows touches 5 cache lines instead of 32.  qblora_linear_decode with pack = NULL reads the
- * row-major arrays of `qw` (same result, about half the speed); with a pack it needs no workspace.
+ * row-major arrays of `qw` (the same sums, 2-3 times slower on large layers); with a pack it needs no workspace.
  * A pack belongs to the description it was made from: pass the same `qw` (codebook, offsets, block shape)
  * to qblora_linear_decode.  For an INT4 model -- codebook exactly 0, 1, ..., 15 with offsets, 64-blocks, the
  * output of the min-max quantizer and of qablora_merge_quantize -- the pack also regroups the nibbles of
