@@ -108,7 +108,7 @@ FwdSpace carve_fwd(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T
 }
 
 struct BwdSpace {
-    float* scales; qblora_bf16 *At_x, *Bx, *U, *U_lo, *dU, *dU_lo, *dUs, *A_op, *Xs, *dYs; float* part;
+    float* scales; qblora_bf16 *At_x, *Bx, *U, *U_lo, *dU, *dU_lo, *dUs, *A_op, *Xs, *dYs; float *part, *part_b;
     int splits_a, splits_b;
     size_t bytes;
 };
@@ -127,7 +127,8 @@ BwdSpace carve_bwd(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T
         s.splits_a = grad_splits(T, qw->d_in);
         s.splits_b = grad_splits(T, qw->d_out);
         size_t pa = (size_t)s.splits_a * qw->d_in * ad->R, pb = (size_t)s.splits_b * qw->d_out * ad->R;
-        s.part = c.take<float>(pa > pb ? pa : pb);
+        s.part = c.take<float>(pa);             // dA and dB are computed in one launch: a buffer each
+        s.part_b = c.take<float>(pb);
         if (scale_op_of(ad)) s.A_op = c.take<qblora_bf16>((size_t)qw->d_in * ad->R);
         if (scale_op_of(ad) == QBLORA_OP_SAMPLE_ZEROFILL) {
             s.Xs = c.take<qblora_bf16>((size_t)T * (qw->d_in / ad->lambda1));
@@ -414,7 +415,7 @@ int linear_bwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
             ga.out_scale = 1.0f / (float)ad->lambda1; ga.transpose_out = 0;
             GradDesc gb{};
             gb.L = dY; gb.ldl = qw->d_out; gb.I = qw->d_out; gb.S = su; gb.S_lo = su_lo; gb.lds = R; gb.J = R; gb.T = T;
-            gb.part = ws.part; gb.splits = ws.splits_b; gb.out = dB; gb.pool = ad->lambda2;
+            gb.part = ws.part_b; gb.splits = ws.splits_b; gb.out = dB; gb.pool = ad->lambda2;
             gb.out_scale = 1.0f; gb.transpose_out = 1;
             if (op != QBLORA_OP_AVGPOOL_REPEAT) {
                 // dA = C(X)^T dU and dB = (sU)^T E^T(dY): the kept features are the first ones of each
@@ -427,8 +428,7 @@ int linear_bwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
                     ga.L = ws.Xs; ga.ldl = na; gb.L = ws.dYs; gb.ldl = nb;
                 }
             }
-            if ((rc = launch_grad(ga, st))) return rc;
-            if ((rc = launch_grad(gb, st))) return rc;
+            if ((rc = launch_grad_pair(ga, gb, st))) return rc;
         }
         g.X2 = ws.dUs; g.ldx2 = R; g.K2 = R;
         if (op == QBLORA_OP_AVGPOOL_REPEAT) { g.W2 = ad->A; g.ldw2 = R; g.div2 = ad->lambda1; }

@@ -125,6 +125,8 @@ int grad_splits(int64_t T, int I, int J = 1);    // slices of the token range fo
 int launch_pool_rows(const qblora_bf16* in, int64_t T, int d, int lam, float scale, qblora_bf16* out,
                      qblora_bf16* out_lo, hipStream_t st);
 int launch_grad(const GradDesc& d, hipStream_t st);
+// two independent gradients whose partial buffers do not overlap: one launch for both where the shapes allow
+int launch_grad_pair(const GradDesc& a, const GradDesc& b, hipStream_t st);
 // out[t, c] = in[t, lam*c] for c < d/lam (every lam-th feature of each row), bf16
 int launch_sample_rows(const qblora_bf16* in, int64_t T, int d, int lam, qblora_bf16* out, hipStream_t st);
 

@@ -148,7 +148,7 @@ __global__ __launch_bounds__(kThreads) void k_grad_partial(GradDesc d, int64_t s
 // reads (rows +0..3 and +4..7) give a lane the 8 consecutive tokens of one feature that
 // v_mfma_f32_32x32x16_bf16 wants: lane groups 0/1 serve features 0-15 / 16-31 of a 32-feature block
 // for tokens 0-7 of a 16-token slice, groups 2/3 the same features for tokens 8-15.
-constexpr int kTrBT = 32, kTrStages = 6;
+constexpr int kTrBT = 32, kTrStages = 3;         // 72 KB: two workgroups fit a CU (6 stages measured the same)
 constexpr int kTrTile = kTrBT * 256, kTrStage = 3 * kTrTile;
 constexpr int kTrThreads = 512;
 
@@ -175,15 +175,28 @@ __device__ __forceinline__ bf16x8 tr_fragment(const unsigned char* p) {
     return __builtin_bit_cast(bf16x8, v);
 }
 
+// Two gradients in one launch (dA and dB of a layer are independent): the first n_a workgroups work on `a`,
+// the others on `b`.  With one workgroup per CU each, the dispatcher puts one of either on every CU, and one's
+// MFMAs run under the other's waits for its copies.
+struct GradPair {
+    GradDesc a, b;
+    int n_a;
+    int64_t slice_a, slice_b;
+};
+
 template <bool HAS_LO>
-__global__ __launch_bounds__(kTrThreads) void k_grad_tr(GradDesc d, int64_t slice_len) {
+__global__ __launch_bounds__(kTrThreads) void k_grad_tr(GradPair p) {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int kPer = HAS_LO ? 3 : 2;             // copy instructions per wave and stage
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const bool second = (int)blockIdx.x >= p.n_a;
+    const GradDesc& d = second ? p.b : p.a;
+    const int64_t slice_len = second ? p.slice_b : p.slice_a;
+    const int bid = (int)blockIdx.x - (second ? p.n_a : 0);
     // Consecutive workgroups go to different XCDs; the token slice varies fastest so that (with 8
     // slices) all workgroups that stream one slice of S share one XCD's L2.
     const int tiles_i = (d.I + BI - 1) / BI;
-    const int z = blockIdx.x % d.splits, rest = blockIdx.x / d.splits;
+    const int z = bid % d.splits, rest = bid / d.splits;
     const int i0 = (rest % tiles_i) * BI, j0 = (rest / tiles_i) * BJ;
     const int64_t t_begin = (int64_t)z * slice_len;
     int64_t t_end = t_begin + slice_len;
@@ -452,29 +465,47 @@ int set_lds_once(K kernel, size_t smem, bool& done) {
 
 }  // namespace
 
-int launch_grad(const GradDesc& d, hipStream_t st) {
-    if (d.T <= 0) return QBLORA_ERR_SHAPE;      // the entry point handles the empty batch itself
+namespace {
+
+int64_t slice_of(const GradDesc& d) {
     int64_t slice_len = (d.T + d.splits - 1) / d.splits;
-    slice_len = (slice_len + BT - 1) / BT * BT;
-    dim3 grid((d.I + BI - 1) / BI, (d.J + BJ - 1) / BJ, d.splits);
+    return (slice_len + BT - 1) / BT * BT;
+}
+
+unsigned tr_blocks(const GradDesc& d) {
+    return (unsigned)(((d.I + BI - 1) / BI) * ((d.J + BJ - 1) / BJ) * d.splits);
+}
+
+// partial sums of one or two gradients on the copy path (both with or both without a low-order part)
+int launch_tr(const GradDesc& a, const GradDesc* b, hipStream_t st) {
+    constexpr size_t smem = (size_t)kTrStages * kTrStage;
+    GradPair p{};
+    p.a = a; p.slice_a = slice_of(a); p.n_a = (int)tr_blocks(a);
+    unsigned blocks = tr_blocks(a);
+    if (b) { p.b = *b; p.slice_b = slice_of(*b); blocks += tr_blocks(*b); }
+    static bool set_lo = false, set_nolo = false;
     int rc;
-    if (tr_applies(d)) {
-        constexpr size_t smem = (size_t)kTrStages * kTrStage;
-        const dim3 flat(grid.x * grid.y * grid.z);
-        static bool set_lo = false, set_nolo = false;
-        if (d.S_lo) {
-            if ((rc = set_lds_once(k_grad_tr<true>, smem, set_lo))) return rc;
-            hipLaunchKernelGGL(k_grad_tr<true>, flat, dim3(kTrThreads), smem, st, d, slice_len);
-        } else {
-            if ((rc = set_lds_once(k_grad_tr<false>, smem, set_nolo))) return rc;
-            hipLaunchKernelGGL(k_grad_tr<false>, flat, dim3(kTrThreads), smem, st, d, slice_len);
-        }
+    if (a.S_lo) {
+        if ((rc = set_lds_once(k_grad_tr<true>, smem, set_lo))) return rc;
+        hipLaunchKernelGGL(k_grad_tr<true>, dim3(blocks), dim3(kTrThreads), smem, st, p);
     } else {
-        constexpr size_t smem = 2 * BI * 128 + 4 * BJ * 128;
-        static bool set_general = false;
-        if ((rc = set_lds_once(k_grad_partial, smem, set_general))) return rc;
-        hipLaunchKernelGGL(k_grad_partial, grid, dim3(kThreads), smem, st, d, slice_len);
+        if ((rc = set_lds_once(k_grad_tr<false>, smem, set_nolo))) return rc;
+        hipLaunchKernelGGL(k_grad_tr<false>, dim3(blocks), dim3(kTrThreads), smem, st, p);
     }
+    return launch_status();
+}
+
+int launch_partial(const GradDesc& d, hipStream_t st) {
+    constexpr size_t smem = 2 * BI * 128 + 4 * BJ * 128;
+    static bool set_general = false;
+    int rc;
+    if ((rc = set_lds_once(k_grad_partial, smem, set_general))) return rc;
+    dim3 grid((d.I + BI - 1) / BI, (d.J + BJ - 1) / BJ, d.splits);
+    hipLaunchKernelGGL(k_grad_partial, grid, dim3(kThreads), smem, st, d, slice_of(d));
+    return launch_status();
+}
+
+int launch_reduce(const GradDesc& d, hipStream_t st) {
     const int Ip = d.I / d.pool;
     auto aligned16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
     // measured: the plain kernel is the faster one when the output is not transposed (5.1 vs 5.5 us), the
@@ -487,6 +518,29 @@ int launch_grad(const GradDesc& d, hipStream_t st) {
     int64_t total = (int64_t)Ip * d.J;
     hipLaunchKernelGGL(k_grad_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, d);
     return launch_status();
+}
+
+}  // namespace
+
+int launch_grad(const GradDesc& d, hipStream_t st) {
+    if (d.T <= 0) return QBLORA_ERR_SHAPE;      // the entry point handles the empty batch itself
+    int rc = tr_applies(d) ? launch_tr(d, nullptr, st) : launch_partial(d, st);
+    if (rc) return rc;
+    return launch_reduce(d, st);
+}
+
+// Two independent gradients with partial buffers of their own: one launch of the copy path for both when
+// both qualify, else one after the other.
+int launch_grad_pair(const GradDesc& a, const GradDesc& b, hipStream_t st) {
+    if (a.T <= 0 || b.T <= 0) return QBLORA_ERR_SHAPE;
+    if (a.part == b.part || !tr_applies(a) || !tr_applies(b) || (a.S_lo == nullptr) != (b.S_lo == nullptr)) {
+        int rc = launch_grad(a, st);
+        return rc ? rc : launch_grad(b, st);
+    }
+    int rc = launch_tr(a, &b, st);
+    if (rc) return rc;
+    if ((rc = launch_reduce(a, st))) return rc;
+    return launch_reduce(b, st);
 }
 
 }  // namespace qblora
