@@ -364,10 +364,10 @@ __global__ __launch_bounds__(kTrThreads) void k_grad_tr(GradPair p) {
 
 // out[i', j] (or out[j, i'] when transposed) = out_scale * sum_{p < pool} sum_z part[z][i'*pool+p][j],
 // summed in ascending (p, z) order.
-__global__ __launch_bounds__(256) void k_grad_reduce(GradDesc d) {
+__device__ __forceinline__ void grad_reduce_plain(const GradDesc& d, const unsigned bid) {
     const int Ip = d.I / d.pool;
     const int64_t total = (int64_t)Ip * d.J;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t idx = (int64_t)bid * 256 + threadIdx.x;
     if (idx >= total) return;
     const int j = (int)(idx % d.J);
     const int ip = (int)(idx / d.J);
@@ -396,11 +396,10 @@ __global__ __launch_bounds__(256) void k_grad_reduce(GradDesc d) {
 // consecutive columns, so every load instruction of a wave reads eight whole 128-byte lines and all
 // pool * splits loads of a thread are issued together; the transposed output goes through LDS so that its
 // stores are whole lines too (one thread per output element wrote 4 bytes into each of 64 lines).
-__global__ __launch_bounds__(256) void k_grad_reduce_tile(GradDesc d) {
-    __shared__ float tr[32][33];
+__device__ __forceinline__ void grad_reduce_tile(const GradDesc& d, const unsigned bid, float (&tr)[32][33]) {
     const int Ip = d.I / d.pool;
     const int tiles_j = (d.J + 31) / 32;
-    const int j0 = (blockIdx.x % tiles_j) * 32, ip0 = (blockIdx.x / tiles_j) * 32;
+    const int j0 = (bid % tiles_j) * 32, ip0 = (bid / tiles_j) * 32;
     const int t = threadIdx.x, r = t >> 3, c4 = (t & 7) * 4;
     const int ip = min(ip0 + r, Ip - 1), j = min(j0 + c4, d.J - 4);      // clamped lanes compute, never store
     const int64_t plane = (int64_t)d.I * d.J;
@@ -430,6 +429,21 @@ __global__ __launch_bounds__(256) void k_grad_reduce_tile(GradDesc d) {
     if (j0 + jj < d.J && ip0 + iq < Ip)
         *reinterpret_cast<float4*>(d.out + (int64_t)(j0 + jj) * Ip + ip0 + iq) =
             make_float4(tr[jj][iq], tr[jj][iq + 1], tr[jj][iq + 2], tr[jj][iq + 3]);
+}
+
+__global__ __launch_bounds__(256) void k_grad_reduce(GradDesc d) { grad_reduce_plain(d, blockIdx.x); }
+
+__global__ __launch_bounds__(256) void k_grad_reduce_tile(GradDesc d) {
+    __shared__ float tr[32][33];
+    grad_reduce_tile(d, blockIdx.x, tr);
+}
+
+// Both second stages of a layer's gradients in one launch: blocks below n_a reduce `a` element-wise, the
+// others reduce `b` by tiles (transposed output).
+__global__ __launch_bounds__(256) void k_grad_reduce_pair(GradPair p) {
+    __shared__ float tr[32][33];
+    if ((int)blockIdx.x < p.n_a) grad_reduce_plain(p.a, blockIdx.x);
+    else grad_reduce_tile(p.b, blockIdx.x - p.n_a, tr);
 }
 
 }  // namespace
@@ -505,18 +519,22 @@ int launch_partial(const GradDesc& d, hipStream_t st) {
     return launch_status();
 }
 
-int launch_reduce(const GradDesc& d, hipStream_t st) {
+// measured: the plain kernel is the faster one when the output is not transposed (5.1 vs 5.5 us), the tiled
+// one when it is (5.8 vs 7.5 us)
+bool reduce_by_tiles(const GradDesc& d) {
     const int Ip = d.I / d.pool;
     auto aligned16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
-    // measured: the plain kernel is the faster one when the output is not transposed (5.1 vs 5.5 us), the
-    // tiled one when it is (5.8 vs 7.5 us)
-    if (d.transpose_out && d.J % 4 == 0 && Ip % 4 == 0 && aligned16(d.part) && aligned16(d.out)) {
-        const int64_t tiles = (int64_t)((d.J + 31) / 32) * ((Ip + 31) / 32);
-        hipLaunchKernelGGL(k_grad_reduce_tile, dim3((unsigned)tiles), dim3(256), 0, st, d);
-        return launch_status();
-    }
-    int64_t total = (int64_t)Ip * d.J;
-    hipLaunchKernelGGL(k_grad_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, d);
+    return d.transpose_out && d.J % 4 == 0 && Ip % 4 == 0 && aligned16(d.part) && aligned16(d.out);
+}
+unsigned reduce_blocks(const GradDesc& d) {
+    const int Ip = d.I / d.pool;
+    if (reduce_by_tiles(d)) return (unsigned)(((d.J + 31) / 32) * ((Ip + 31) / 32));
+    return (unsigned)(((int64_t)Ip * d.J + 255) / 256);
+}
+
+int launch_reduce(const GradDesc& d, hipStream_t st) {
+    if (reduce_by_tiles(d)) hipLaunchKernelGGL(k_grad_reduce_tile, dim3(reduce_blocks(d)), dim3(256), 0, st, d);
+    else hipLaunchKernelGGL(k_grad_reduce, dim3(reduce_blocks(d)), dim3(256), 0, st, d);
     return launch_status();
 }
 
@@ -539,6 +557,12 @@ int launch_grad_pair(const GradDesc& a, const GradDesc& b, hipStream_t st) {
     }
     int rc = launch_tr(a, &b, st);
     if (rc) return rc;
+    if (!reduce_by_tiles(a) && reduce_by_tiles(b)) {         // the usual case (dA plain, dB transposed): one launch
+        GradPair p{};
+        p.a = a; p.b = b; p.n_a = (int)reduce_blocks(a);
+        hipLaunchKernelGGL(k_grad_reduce_pair, dim3(reduce_blocks(a) + reduce_blocks(b)), dim3(256), 0, st, p);
+        return launch_status();
+    }
     if ((rc = launch_reduce(a, st))) return rc;
     return launch_reduce(b, st);
 }
