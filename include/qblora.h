@@ -66,8 +66,8 @@ enum { QBLORA_MERGE_BETA_SHIFT = 0, QBLORA_MERGE_REQUANT_MINMAX = 1 };
  *              the codes were chosen against) and may be NULL for consumers.
  *   scale_codes [d_out*d_in/block] bytes, OCP E4M3 bit patterns.
  *   scale_step, scale_mid  fp32 [ceil(nblocks/scale_group)].
- *   block_rows 8 selects two-dimensional quantization blocks (Sec. 3.3: pre-trained models "use block
- *              quantization with sizes of 4 x 8 or 8 x 8"; Sec. 4.3: block 64 goes with lambda1 = lambda2 = 8):
+ *   block_rows 8 selects two-dimensional 8 x 8 quantization blocks (Sec. 3.3; Sec. 4.3 pairs block size 64
+ *              with lambda1 = lambda2 = 8):
  *              block (i, j) covers output rows [8i, 8i+8) and inputs [8j, 8j+8), its scale / offset has
  *              index i*(d_in/8) + j; `codes` keeps the [d_out, d_in/2] packing.  Then every block lies in
  *              one (lambda1 x lambda2) adapter tile when 8 | lambda1 and 8 | lambda2, and the offset-shift
@@ -334,8 +334,9 @@ int qblora_decode_pack(const qblora_qweight* qw, void* pack, void* stream);
  *   QBLORA_PROFILE_BWD_GEMM   the transposed dequantize-and-contract kernel of qblora_linear_bwd
  *   QBLORA_PROFILE_MERGE      the requantizing (or beta-shift) kernel of qablora_merge_quantize
  *   QBLORA_PROFILE_QUANTIZE   the code-selection kernel of qblora_quantize_blockwise
- * Passing NULL for both events unregisters the slot.  Process-wide state, not thread safe; has no
- * effect on results.
+ * Passing NULL for both events unregisters the slot.  The registration is per host thread: it applies to
+ * calls made by the thread that registered it, so concurrent callers do not see each other's events.  Has
+ * no effect on results.
  */
 enum { QBLORA_PROFILE_FWD_GEMM = 0, QBLORA_PROFILE_BWD_GEMM = 1, QBLORA_PROFILE_MERGE = 2,
        QBLORA_PROFILE_QUANTIZE = 3 };

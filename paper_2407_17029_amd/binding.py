@@ -136,17 +136,17 @@ class TimingEvent:
     def __init__(self):
         h = C.c_void_p()
         if _hip_runtime().hipEventCreateWithFlags(C.byref(h), self.DISABLE_SYSTEM_FENCE) != 0:
-            raise QBLoRAError("hipEventCreateWithFlags failed")
+            raise RuntimeError("hipEventCreateWithFlags failed")
         self.cuda_event = h.value
 
     def record(self, stream=None):
         if _hip_runtime().hipEventRecord(self.cuda_event, _stream() if stream is None else stream) != 0:
-            raise QBLoRAError("hipEventRecord failed")
+            raise RuntimeError("hipEventRecord failed")
 
     def elapsed_time(self, stop: "TimingEvent") -> float:
         ms = C.c_float()
         if _hip_runtime().hipEventElapsedTime(C.byref(ms), self.cuda_event, stop.cuda_event) != 0:
-            raise QBLoRAError("hipEventElapsedTime failed")
+            raise RuntimeError("hipEventElapsedTime failed")
         return float(ms.value)
 
     def __del__(self):

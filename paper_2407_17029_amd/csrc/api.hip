@@ -139,7 +139,8 @@ BwdSpace carve_bwd(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T
     return s;
 }
 
-hipEvent_t g_events[4][2] = {};
+// measurement hook (qblora_profile_events): the registration belongs to the calling host thread
+thread_local hipEvent_t g_events[4][2] = {};
 
 struct ScopedEvents {
     int which; hipStream_t st;
@@ -646,6 +647,11 @@ int qablora_merge_quantize(const qblora_qweight* base, const float* H, int32_t l
     if (base->d_in % lambda1 || base->d_out % lambda2) return QBLORA_ERR_SHAPE;
     if (mode != QBLORA_MERGE_BETA_SHIFT && mode != QBLORA_MERGE_REQUANT_MINMAX) return QBLORA_ERR_UNSUPPORTED;
     if (!out->codes || !out->scales || !out->beta) return QBLORA_ERR_NULL;
+    // every check comes before `out` is touched: a rejected call leaves the caller's struct as it was
+    // (it may alias `base`)
+    if (mode == QBLORA_MERGE_BETA_SHIFT &&
+        (block_rows_of(base) == 8 ? (lambda1 % 8 != 0 || lambda2 % 8 != 0) : (lambda1 % base->block != 0)))
+        return QBLORA_ERR_ALIGNMENT;
     hipStream_t st = as_stream(stream);
     const bool grouped = base->scale_mode == QBLORA_SCALES_E4M3_GROUPED;
     MergeDesc d{};
@@ -662,8 +668,6 @@ int qablora_merge_quantize(const qblora_qweight* base, const float* H, int32_t l
     out->scale_mode = QBLORA_SCALES_FP32; out->scale_group = 0;
     out->scale_codes = nullptr; out->scale_step = nullptr; out->scale_mid = nullptr; out->codes_tiled = nullptr;
     if (mode == QBLORA_MERGE_BETA_SHIFT) {
-        if (d.block_rows == 8 ? (lambda1 % 8 != 0 || lambda2 % 8 != 0) : (lambda1 % base->block != 0))
-            return QBLORA_ERR_ALIGNMENT;
         std::memcpy(out->codebook, base->codebook, sizeof(out->codebook));
         if (out->codes != base->codes &&
             hipMemcpyAsync(out->codes, base->codes, (size_t)base->d_out * base->d_in / 2, hipMemcpyDeviceToDevice,

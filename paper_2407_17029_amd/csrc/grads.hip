@@ -467,14 +467,11 @@ bool tr_applies(const GradDesc& d) {
            (d.S_lo == nullptr || aligned16(d.S_lo));
 }
 
+// raises a kernel's dynamic LDS limit; callers keep the result in a function-local static (set once, thread safe)
 template <typename K>
-int set_lds_once(K kernel, size_t smem, bool& done) {
-    if (done) return QBLORA_OK;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)smem) != hipSuccess)
-        return QBLORA_ERR_LAUNCH;
-    done = true;
-    return QBLORA_OK;
+bool set_lds(K kernel, size_t smem) {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)smem) == hipSuccess;
 }
 
 }  // namespace
@@ -497,13 +494,13 @@ int launch_tr(const GradDesc& a, const GradDesc* b, hipStream_t st) {
     p.a = a; p.slice_a = slice_of(a); p.n_a = (int)tr_blocks(a);
     unsigned blocks = tr_blocks(a);
     if (b) { p.b = *b; p.slice_b = slice_of(*b); blocks += tr_blocks(*b); }
-    static bool set_lo = false, set_nolo = false;
-    int rc;
     if (a.S_lo) {
-        if ((rc = set_lds_once(k_grad_tr<true>, smem, set_lo))) return rc;
+        static const bool ok = set_lds(k_grad_tr<true>, smem);
+        if (!ok) return QBLORA_ERR_LAUNCH;
         hipLaunchKernelGGL(k_grad_tr<true>, dim3(blocks), dim3(kTrThreads), smem, st, p);
     } else {
-        if ((rc = set_lds_once(k_grad_tr<false>, smem, set_nolo))) return rc;
+        static const bool ok = set_lds(k_grad_tr<false>, smem);
+        if (!ok) return QBLORA_ERR_LAUNCH;
         hipLaunchKernelGGL(k_grad_tr<false>, dim3(blocks), dim3(kTrThreads), smem, st, p);
     }
     return launch_status();
@@ -511,9 +508,8 @@ int launch_tr(const GradDesc& a, const GradDesc* b, hipStream_t st) {
 
 int launch_partial(const GradDesc& d, hipStream_t st) {
     constexpr size_t smem = 2 * BI * 128 + 4 * BJ * 128;
-    static bool set_general = false;
-    int rc;
-    if ((rc = set_lds_once(k_grad_partial, smem, set_general))) return rc;
+    static const bool ok = set_lds(k_grad_partial, smem);
+    if (!ok) return QBLORA_ERR_LAUNCH;
     dim3 grid((d.I + BI - 1) / BI, (d.J + BJ - 1) / BJ, d.splits);
     hipLaunchKernelGGL(k_grad_partial, grid, dim3(kThreads), smem, st, d, slice_of(d));
     return launch_status();

@@ -288,13 +288,10 @@ template <int BM, int BN, int WM, int WN, int QMODE>
 int launch_cfg(const GemmDesc& d, hipStream_t st) {
     constexpr size_t smem = 2 * (BM + BN) * 128 + 64;
     auto kern = k_qgemm<BM, BN, WM, WN, QMODE>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)smem) != hipSuccess)
-            return QBLORA_ERR_LAUNCH;
-        attr_set = true;
-    }
+    // set once per instantiation; the initialisation of a function-local static is thread safe
+    static const bool attr_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess;
+    if (!attr_ok) return QBLORA_ERR_LAUNCH;
     int64_t tiles = ((d.M + BM - 1) / BM) * ((d.N + BN - 1) / BN);
     hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(kThreads), smem, st, d);
     return launch_status();

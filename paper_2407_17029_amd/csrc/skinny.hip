@@ -268,13 +268,10 @@ template <int BM, int BN, int kStages, int kSub, bool kSplitK, int kDup = 1>
 int launch_skinny_cfg(const GemmDesc& d, hipStream_t st) {
     constexpr size_t smem = kStages * kSub * (BM * 128 + BN * 128 / kDup);
     auto kern = k_skinny<BM, BN, kStages, kSub, kSplitK, kDup>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)smem) != hipSuccess)
-            return QBLORA_ERR_LAUNCH;
-        attr_set = true;
-    }
+    // set once per instantiation; the initialisation of a function-local static is thread safe
+    static const bool attr_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess;
+    if (!attr_ok) return QBLORA_ERR_LAUNCH;
     const int64_t tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
     dim3 grid((unsigned)((tiles_m + 7) / 8 * 8 * tiles_n));
     hipLaunchKernelGGL(kern, grid, dim3(kThreads), smem, st, d);
