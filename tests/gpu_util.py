@@ -82,29 +82,53 @@ class OracleWeight:
 
 REL_TOL = 1e-2            # max |gpu - oracle| / rms(oracle), the bar for bf16 outputs and gradients
 
+REPORT = []               # one dict per comparison made in this process (tests print / write them out)
+
+
+def bf16_half_ulp(ref: np.ndarray) -> np.ndarray:
+    """Half the spacing of bf16 numbers at |ref| (8 significant bits): 2^(floor(log2|ref|) - 8); 0 at 0."""
+    a = np.abs(ref)
+    e = np.floor(np.log2(np.where(a > 0, a, 1.0)))
+    return np.where(a > 0, np.exp2(e - 8.0), 0.0)
+
+
+RMS_TOL = 4e-3            # rms |gpu - oracle| / rms(oracle): storing in bf16 alone costs 1.7e-3 of it
+
 
 def assert_close_bf16(got_bf16: torch.Tensor, ref: np.ndarray, what: str):
-    """bf16 output vs fp64 oracle.
+    """bf16 output vs fp64 oracle; returns the measured figures (all relative to rms(oracle)).
 
-    A bf16 value carries 8 significant bits, so even the correctly rounded oracle value sits up to
-    2^-9 * |ref| (half an ulp, at most 2^-8 relative to the power of two below it) away from the
-    oracle; that representation term is allowed on top of the 1e-2 * rms bar and reported apart.
+    The bar is max |gpu - oracle| <= 1e-2 * rms(oracle).  A value stored in bf16 cannot be closer to the
+    oracle than half a bf16 spacing, 2^-9 .. 2^-8 of its magnitude, which for an output of 4 * rms is already
+    above the bar (the correctly rounded oracle value itself would fail, and every output tensor of more than
+    a few thousand elements has such entries).  So the bar is applied to what the kernel adds: the error
+    beyond exactly that half spacing at the oracle's value -- nothing proportional, nothing else -- must stay
+    within 1e-2 * rms on every element, and the rms error over all elements within 4e-3 * rms.  The raw
+    maximum over all outputs and over the outputs with |oracle| <= 2 * rms are returned, recorded in REPORT
+    and printed in every failure message, never hidden.
     """
     got = bf16_to_f64(got_bf16)
-    rms = float(np.sqrt(np.mean(ref * ref)))
+    rms = max(float(np.sqrt(np.mean(ref * ref))), 1e-300)
     err = np.abs(got - ref)
-    excess = err - np.abs(ref) * 2.0 ** -8
-    worst = float(excess.max()) / max(rms, 1e-300)
-    raw = float(err.max()) / max(rms, 1e-300)
-    rms_err = float(np.sqrt(np.mean(err * err))) / max(rms, 1e-300)
-    assert worst <= REL_TOL, f"{what}: max excess err/rms {worst:.3e} (raw {raw:.3e}, rms err {rms_err:.3e})"
-    assert rms_err <= REL_TOL, f"{what}: rms err/rms {rms_err:.3e}"
-    return raw, rms_err
+    raw = float(err.max()) / rms
+    core = np.abs(ref) <= 2.0 * rms
+    core_raw = float(err[core].max()) / rms if core.any() else 0.0
+    excess = float((err - bf16_half_ulp(ref)).max()) / rms
+    rms_err = float(np.sqrt(np.mean(err * err))) / rms
+    fig = {"what": what, "raw_max": raw, "core_raw_max": core_raw, "excess_max": excess, "rms_err": rms_err,
+           "max_abs_ref_over_rms": float(np.abs(ref).max()) / rms}
+    REPORT.append(fig)
+    msg = (f"{what}: raw max err/rms {raw:.3e}, on |ref| <= 2 rms {core_raw:.3e}, beyond the bf16 half spacing "
+           f"{excess:.3e}, rms err/rms {rms_err:.3e}")
+    assert excess <= REL_TOL, msg
+    assert rms_err <= RMS_TOL, msg
+    return fig
 
 
 def assert_close_f32(got: torch.Tensor, ref: np.ndarray, what: str):
     g = to_np(got).astype(np.float64)
-    rms = float(np.sqrt(np.mean(ref * ref)))
-    worst = float(np.abs(g - ref).max()) / max(rms, 1e-300)
+    rms = max(float(np.sqrt(np.mean(ref * ref))), 1e-300)
+    worst = float(np.abs(g - ref).max()) / rms
+    REPORT.append({"what": what, "raw_max": worst})
     assert worst <= REL_TOL, f"{what}: max err/rms {worst:.3e}"
     return worst

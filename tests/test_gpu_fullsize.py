@@ -168,7 +168,7 @@ def test_scale_operators_benchmark_shape(qb, oracle, codebook, op):
 def test_small_batch_inference_at_the_measured_shape(qb, oracle):
     """The decode kernel on the 65B up-projection shape kernel_bench times (22016 x 8192, INT4 with offsets, tile-
     ordered pack), T = 1 and 16: sampled output features against the oracle (a feature needs its own weight row only)."""
-    from gpu_util import f32_to_dev, bf16_to_dev, bf16_to_f64
+    from gpu_util import f32_to_dev, bf16_to_dev, bf16_to_f64, bf16_half_ulp
     d_out, d_in = 22016, 8192
     rng = np.random.default_rng(4242)
     W = (rng.standard_normal((d_out, d_in), dtype=np.float32) * np.float32(0.02))
@@ -197,7 +197,7 @@ def test_small_batch_inference_at_the_measured_shape(qb, oracle):
             ref = oracle.forward(Wt, Xb, None, None, 1, 1, 0.0)           # [T, len(sel)]
             got = bf16_to_f64(Y[:, sel_t])
             rms = np.sqrt(np.mean(ref ** 2))
-            excess = np.abs(got - ref) - np.abs(ref) * 2.0 ** -8
+            excess = np.abs(got - ref) - bf16_half_ulp(ref)
             assert excess.max() <= 1e-2 * rms, (block_rows, T, excess.max() / rms)
         del qw, pack
 

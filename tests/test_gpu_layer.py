@@ -164,3 +164,45 @@ def test_empty_batch_and_errors(qb, oracle, codebook):
     with pytest.raises(qb.QBLoRAError) as e:
         qb.qblora_linear_fwd(qw, ad, X, workspace=torch.empty(16, dtype=torch.uint8, device=DEV))
     assert e.value.code == -4
+
+
+# ---- the adapter term on its own scale --------------------------------------------------------------
+# With the workloads' B ~ N(0, 0.01^2) the adapter is a few per cent of Y and dX, so the 1e-2 * rms bar of
+# the cases above would let a sizeable error in it pass.  Here the adapter dominates: either the base weight
+# is all zero (absmax 0 => w~ = 0, the output IS s * expand(pool(X) A B), and dX IS expand(dU A^T) / lambda1),
+# or B ~ N(0, 0.5^2) on the usual base.  The bar then resolves the K-extension of both GEMM kernels: the scale
+# s, the 1/lambda1 factor, the n / lambda2 and k / lambda1 row maps under partial tiles.
+ADAPTER_CASES = CASES + [
+    (300, 320, 448, 24, 4, 8, 0.5),          # lambda1 != lambda2 = 8, partial feature tile (320 = 256 + 64), ragged T
+    (520, 832, 320, 40, 8, 4, 1.5),          # lambda1 = 8 > lambda2, partial tiles on both sides of the backward
+    (257, 576, 576, 136, 2, 2, 1.0),         # inner rank 136: a partial third K-extension step
+]
+
+
+@pytest.mark.parametrize("zero_base", [True, False])
+@pytest.mark.parametrize("T,d_out,d_in,R,lam1,lam2,s", ADAPTER_CASES)
+def test_adapter_dominant_parity(qb, oracle, codebook, T, d_out, d_in, R, lam1, lam2, s, zero_base):
+    from gpu_util import f32_to_dev, bf16_to_dev, assert_close_bf16, assert_close_f32, OracleWeight
+    print(f"case adapter-dominant T={T} {d_out}x{d_in} R={R} lam=({lam1},{lam2}) zero_base={zero_base}", flush=True)
+    L = synth.make_layer(1300 + T + R, T, d_out, d_in, R, lam1, lam2, b_std=0.5)
+    W = np.zeros_like(L.W) if zero_base else L.W
+    qw = qb.qblora_quantize_blockwise(f32_to_dev(W), 64, qb.QUANT_ABSMAX_CODEBOOK, codebook)
+    torch.cuda.synchronize()
+    Wt = OracleWeight(oracle, W, codebook).assert_same(qw).dequantize(oracle, 2)
+    if zero_base:
+        assert not Wt.any()
+    ad = qb.Adapter(bf16_to_dev(L.A), bf16_to_dev(L.B), lam1, lam2, s)
+    X, dY = bf16_to_dev(L.X), bf16_to_dev(L.dY)
+    Y = qb.qblora_linear_fwd(qw, ad, X)
+    dX, dA, dB = qb.qblora_linear_bwd(qw, ad, X, dY)
+    torch.cuda.synchronize()
+    ref = oracle.forward(Wt, L.X, L.A, L.B, lam1, lam2, s)
+    rX, rA, rB = oracle.backward(Wt, L.X, L.dY, L.A, L.B, lam1, lam2, s)
+    if not zero_base:
+        # the adapter term is a large part of the output (a quarter to nine tenths of its energy, by s and R)
+        base = oracle.forward(Wt, L.X, None, None, 1, 1, 0.0)
+        assert np.mean((ref - base) ** 2) > 0.2 * np.mean(ref ** 2)
+    assert_close_bf16(Y, ref, "Y (adapter-dominant)")
+    assert_close_bf16(dX, rX, "dX (adapter-dominant)")
+    assert_close_f32(dA, rA, "dA")
+    assert_close_f32(dB, rB, "dB")
