@@ -227,6 +227,22 @@ int qblora_linear_bwd_saved(const qblora_qweight* qw, const qblora_adapter* ad, 
                             float* dA, float* dB, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * qblora_linear_fwd for callers that cannot allocate device memory or hold a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks and results (bit
+ * for bit) as qblora_linear_fwd, but the scratch is an array of QBLORA_NOALLOC_SCRATCH_BYTES bytes inside the
+ * library's device image (each GPU the library runs on holds it until the process ends) instead of a caller
+ * workspace; the call allocates nothing.  A problem whose qblora_linear_fwd_workspace_bytes() exceeds
+ * qblora_noalloc_scratch_bytes() is rejected with QBLORA_ERR_WORKSPACE and nothing is enqueued (the LLaMA-7B
+ * attention projection at T = 8192, rank 64 needs 4.5 MiB).  All calls on one GPU share that GPU's array:
+ * calls that overlap on one GPU (two streams, two host threads) race; calls on one stream do not.  The first
+ * call on a device looks the array's address up (hipGetSymbolAddress); make it outside graph capture.
+ */
+#define QBLORA_NOALLOC_SCRATCH_BYTES ((size_t)16 << 20)
+size_t qblora_noalloc_scratch_bytes(void);
+int qblora_linear_fwd_noalloc(const qblora_qweight* qw, const qblora_adapter* ad, const qblora_bf16* X, int64_t T,
+                              qblora_bf16* Y, void* stream);
+
+/*
  * Single-matrix adapter (QA-BLoRA, Sec. 3.3, Alg. 2 qablora_forward with the scaling on the adapter
  * term only): the trainable adapter is one matrix H, bf16 [d_in/lambda1, d_out/lambda2] row-major,
  * device memory, whose tiles can later be folded into the block offsets (qablora_merge_quantize).

@@ -30,7 +30,8 @@ EXPORTS = ["qblora_quantize_blockwise", "qblora_dequantize_bf16", "qblora_linear
            "qablora_linear_fwd_workspace_bytes", "qablora_linear_bwd_workspace_bytes", "qablora_linear_fwd",
            "qablora_linear_bwd", "qblora_merge_bf16",
            "qblora_linear_decode_workspace_bytes", "qblora_linear_decode",
-           "qblora_decode_pack_bytes", "qblora_decode_pack"]
+           "qblora_decode_pack_bytes", "qblora_decode_pack",
+           "qblora_noalloc_scratch_bytes", "qblora_linear_fwd_noalloc"]
 
 PROFILE_FWD_GEMM, PROFILE_BWD_GEMM, PROFILE_MERGE, PROFILE_QUANTIZE = 0, 1, 2, 3
 
@@ -108,6 +109,9 @@ def lib():
                                              C.c_void_p, C.c_size_t, C.c_void_p]
         L.qblora_linear_bwd_saved.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
                                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.qblora_noalloc_scratch_bytes.restype = C.c_size_t
+        L.qblora_noalloc_scratch_bytes.argtypes = []
+        L.qblora_linear_fwd_noalloc.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -347,6 +351,21 @@ def qblora_linear_fwd(qw: QWeight, ad, X: torch.Tensor, Y: torch.Tensor = None, 
         rc = lib().qblora_linear_fwd_save(C.byref(s), aref, _ptr(X), T, _ptr(Y), _ptr(saved), _ptr(ws), ws.numel(),
                                           _stream())
         _check(rc, "qblora_linear_fwd_save")
+    return Y
+
+
+def qblora_noalloc_scratch_bytes() -> int:
+    return int(lib().qblora_noalloc_scratch_bytes())
+
+
+def qblora_linear_fwd_noalloc(qw: QWeight, ad, X: torch.Tensor, Y: torch.Tensor):
+    """qblora_linear_fwd on the library's own scratch array: the caller passes inputs and the output only."""
+    assert X.is_cuda and X.dtype == torch.bfloat16 and X.is_contiguous() and X.shape[1] == qw.d_in
+    assert Y.is_cuda and Y.dtype == torch.bfloat16 and Y.is_contiguous() and tuple(Y.shape) == (X.shape[0], qw.d_out)
+    s = qw.c_struct()
+    a, aref = _adapter_ref(ad)
+    _check(lib().qblora_linear_fwd_noalloc(C.byref(s), aref, _ptr(X), X.shape[0], _ptr(Y), _stream()),
+           "qblora_linear_fwd_noalloc")
     return Y
 
 

@@ -1,6 +1,7 @@
 // C-ABI entry points (include/qblora.h): host-side validation, workspace layout and kernel
 // sequencing.  Every step of the method runs in the kernels; nothing here touches tensor data.
 #include <cstring>
+#include <mutex>
 
 #include "common.h"
 
@@ -471,6 +472,52 @@ int qblora_linear_bwd_saved(const qblora_qweight* qw, const qblora_adapter* ad, 
     if (has_adapter(ad) && T > 0 && (dA || dB) && !saved) return QBLORA_ERR_NULL;
     return linear_bwd_impl(qw, ad, X, dY, T, has_adapter(ad) ? saved : nullptr, dX, dA, dB, workspace,
                            workspace_bytes, stream);
+}
+
+// ---- forward on a scratch array of the library's own -----------------------------------------------
+
+namespace {
+
+constexpr size_t kStaticScratchBytes = QBLORA_NOALLOC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+
+// Scratch of qblora_linear_fwd_noalloc.  Every GPU the library runs on holds its own copy of the array at
+// its own address; in host code the name is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on the current device, looked up once per device.
+int static_scratch(void** out) {
+    static std::mutex mu;
+    static void* ptrs[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return QBLORA_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return QBLORA_ERR_LAUNCH;
+        ptrs[dev] = p;
+    }
+    *out = ptrs[dev];
+    return QBLORA_OK;
+}
+
+}  // namespace
+
+size_t qblora_noalloc_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int qblora_linear_fwd_noalloc(const qblora_qweight* qw, const qblora_adapter* ad, const qblora_bf16* X, int64_t T,
+                              qblora_bf16* Y, void* stream) {
+    int rc = check_layer(qw, ad);
+    if (rc) return rc;
+    if (T < 0) return QBLORA_ERR_SHAPE;
+    if (T == 0) return QBLORA_OK;
+    if (!X || !Y) return QBLORA_ERR_NULL;
+    if (carve_fwd(qw, ad, T, nullptr).bytes > kStaticScratchBytes) return QBLORA_ERR_WORKSPACE;
+    void* ptr = nullptr;
+    if ((rc = static_scratch(&ptr))) return rc;
+    // every part of the forward's scratch is written by this call's own kernels before it is read, so
+    // nothing has to be cleared between calls
+    return linear_fwd_impl(qw, ad, X, T, Y, nullptr, ptr, kStaticScratchBytes, stream);
 }
 
 // ---- single-matrix adapter (QA-BLoRA) ------------------------------------------------------------
