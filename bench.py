@@ -1,21 +1,30 @@
 #!/usr/bin/env python3
 """Benchmark of the adapted quantized linear layer hot path on one MI355X.
 
-One step = one pass of the whole path over one synthetic batch of the LLaMA-7B attention
-projection workload (T = 8192 tokens, W 4096x4096, 4-bit block 64, adapter rank 64, lambda 2):
-block-wise quantize -> adapted forward -> backward (dX, dA, dB) -> tile product -> INT4 merge.
-All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+One step = one pass of the whole path over one synthetic batch of a LLaMA-shaped layer stack: for every
+projection of the workload, in sequence on one shared workspace,
+    block-wise quantize -> adapted forward (s*U kept) -> backward (dX, dA, dB),
+then the tile product H = A B and the requantizing INT4 merge of ALL projections back to back (the batch the
+merge is meant to be timed on).  Default workload: the LLaMA-65B-shaped layer (seven projections, T = 8192,
+double-quantized block scales, rank 128), the largest single-GPU configuration.  All inputs are resident in HBM
+before the timed region.  Prints ONE JSON line.
 
-value      = algorithmic fwd+bwd flops (4*T*D_in*D_out + 6*T*r*(D_in+D_out)) / wall time of the
-             whole step, in TFLOP/s.
-roofline   = the forward dequantize-and-contract kernel alone, timed with HIP events recorded by
-             the library around that one launch, against the dense bf16 MFMA peak.
-cpu_baseline = the fp64 CPU oracle timed on a bounded token sample of the same workload.
+value        algorithmic fwd+bwd flops of all projections (4*T*d_in*d_out + 6*T*r*(d_in+d_out) each) over the
+             wall time of the whole step, TFLOP/s.
+roofline     the forward dequantize-and-contract kernel on the workload's largest projection, timed with HIP
+             events that the library records on the launch stream around that one launch, against the dense
+             bf16 MFMA peak; frac is computed from that shape's own flops.
+kernels      the other kernels of the same projection (backward GEMM, narrow adapter GEMMs, token contractions,
+             quantize) from an untimed pass with one event pair per kernel, and the seven-matrix merge batch.
+configs      the same measurement on the other workloads (7B attention projection, 7B MLP, 13B stack with its
+             rank sweep), fewer steps each.
+cpu_baseline the fp64 CPU oracle on a bounded sample (a few token rows of each distinct projection shape),
+             extrapolated linearly in tokens and projection count, labelled as such.
 """
 from __future__ import annotations
 
 import argparse
-import ctypes as C
+import concurrent.futures as cf
 import json
 import os
 import sys
@@ -26,20 +35,343 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the forward GEMM from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see the
-# profiles/ summaries); None until measured for the workload.
-MEASURED_TRAFFIC_BYTES = {"llama7b_attn": int((209.3 + 65.0) * 2**20)}   # profiles/bench_llama7b_attn.md
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+
+
+def measured_traffic(workload: str, kernel: str):
+    """HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs, as recorded by the profile step in
+    profiles/hbm_traffic.txt (lines `workload kernel bytes`); None when that pair has not been profiled."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            f = line.split()
+            if len(f) >= 3 and not line.startswith("#") and f[0] == workload and f[1] == kernel:
+                return int(float(f[2]))
+    except OSError:
+        pass
+    return None
+
+
+class Stack:
+    """Device state of one workload: per-projection weights, adapters, outputs; shared activations and scratch."""
+
+    def __init__(self, wl, rank, dev):
+        import numpy as np
+        import torch
+        from paper_2407_17029_amd import binding as qb
+        from paper_2407_17029_amd import synth
+        self.wl, self.lam, self.dev, self.qb = wl, wl.lam, dev, qb
+        self.T = T = wl.tokens
+        self.cb = synth.codebook_nf4_style()
+        self.scale_mode = qb.SCALES_E4M3_GROUPED if wl.scale_mode else qb.SCALES_FP32
+        widths_in = sorted({p.d_in for p in wl.projections})
+        widths_out = sorted({p.d_out for p in wl.projections})
+
+        # seeded host tensors, drawn concurrently (the generators release the interpreter lock); the streams
+        # and distributions are those of synth.make_layer, one seed per projection / activation width
+        def job_w(i, p):
+            return ("W", i), synth.base_weight(wl.seed + 1 + i, 0, p.d_out, p.d_in)
+
+        def job_x(d):
+            return ("X", d), synth.f32_to_bf16_bits(synth.normal_f32(wl.seed + 50, d, (T, d)))
+
+        def job_dy(d):
+            return ("dY", d), synth.f32_to_bf16_bits(synth.normal_f32(wl.seed + 60, d, (T, d)))
+
+        jobs = [(job_w, (i, p)) for i, p in enumerate(wl.projections)]
+        jobs += [(job_x, (d,)) for d in widths_in] + [(job_dy, (d,)) for d in widths_out]
+        with cf.ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as pool:
+            host = dict(f.result() for f in [pool.submit(fn, *a) for fn, a in jobs])
+        self.host = host
+        self.X = {d: self._bf16_dev(host[("X", d)]) for d in widths_in}
+        self.dY = {d: self._bf16_dev(host[("dY", d)]) for d in widths_out}
+        self.Y = {d: torch.empty((T, d), dtype=torch.bfloat16, device=dev) for d in widths_out}
+        self.dX = {d: torch.empty((T, d), dtype=torch.bfloat16, device=dev) for d in widths_in}
+        self.proj = []
+        for i, p in enumerate(wl.projections):
+            W = torch.from_numpy(host[("W", i)]).to(dev)
+            qw = qb.qblora_quantize_blockwise(W, wl.block, qb.QUANT_ABSMAX_CODEBOOK, self.cb, self.scale_mode)
+            self.proj.append(dict(p=p, W=W, qw=qw, merged=None,
+                                  H=torch.empty((p.d_in // wl.lam, p.d_out // wl.lam), dtype=torch.float32, device=dev)))
+        self.set_rank(rank)
+
+    def _bf16_dev(self, bits):
+        import numpy as np
+        import torch
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(self.dev)
+
+    def set_rank(self, rank):
+        """(Re)builds what depends on the adapter rank: A, B, gradient buffers, workspace, saved activation."""
+        import numpy as np
+        import torch
+        from paper_2407_17029_amd import synth
+        qb, wl, lam, T, dev = self.qb, self.wl, self.lam, self.T, self.dev
+        self.rank, self.R = rank, wl.lam * rank
+        R = self.R
+        self.ws = self.saved = None
+        need = saved = 0
+        for i, st in enumerate(self.proj):
+            p = st["p"]
+            A = synth.uniform_f32(wl.seed + 1 + i + 100 * rank, 3, (p.d_in // lam, R), 1.0 / np.sqrt(p.d_in / lam))
+            B = synth.normal_f32(wl.seed + 1 + i + 100 * rank, 4, (R, p.d_out // lam), 0.01)
+            self.host[("AB", i)] = (synth.f32_to_bf16_bits(A), synth.f32_to_bf16_bits(B))
+            st["ad"] = ad = qb.Adapter(self._bf16_dev(self.host[("AB", i)][0]), self._bf16_dev(self.host[("AB", i)][1]),
+                                       lam, lam, wl.s)
+            st["dA"] = torch.empty((p.d_in // lam, R), dtype=torch.float32, device=dev)
+            st["dB"] = torch.empty((R, p.d_out // lam), dtype=torch.float32, device=dev)
+            need = max(need, qb.qblora_linear_fwd_workspace_bytes(st["qw"], ad, T),
+                       qb.qblora_linear_bwd_workspace_bytes(st["qw"], ad, T))
+            saved = max(saved, qb.qblora_saved_bytes(ad, T))
+        self.ws = torch.empty(need + 256, dtype=torch.uint8, device=dev)
+        self.saved = torch.empty(saved, dtype=torch.uint8, device=dev)
+        for st in self.proj:
+            p = st["p"]
+            st["merged"] = qb.qablora_merge_quantize(st["qw"], qb.qblora_tile_product(st["ad"], p.d_in, p.d_out, st["H"], self.ws),
+                                                     lam, lam, wl.s, qb.MERGE_REQUANT_MINMAX, out=st["merged"])
+
+    def layer_pass(self, st):
+        qb, wl, p = self.qb, self.wl, st["p"]
+        qb.qblora_quantize_blockwise(st["W"], wl.block, qb.QUANT_ABSMAX_CODEBOOK, self.cb, self.scale_mode, out=st["qw"])
+        qb.qblora_linear_fwd(st["qw"], st["ad"], self.X[p.d_in], self.Y[p.d_out], self.ws, saved=self.saved)
+        qb.qblora_linear_bwd(st["qw"], st["ad"], self.X[p.d_in], self.dY[p.d_out], True, True, self.dX[p.d_in],
+                             st["dA"], st["dB"], self.ws, saved=self.saved)
+
+    def merge_batch(self):
+        qb, wl = self.qb, self.wl
+        for st in self.proj:
+            qb.qblora_tile_product(st["ad"], st["p"].d_in, st["p"].d_out, st["H"], self.ws)
+        for st in self.proj:
+            qb.qablora_merge_quantize(st["qw"], st["H"], self.lam, self.lam, wl.s, qb.MERGE_REQUANT_MINMAX, out=st["merged"])
+
+    def step(self):
+        for st in self.proj:
+            self.layer_pass(st)
+        self.merge_batch()
+
+    # ---- counted work -------------------------------------------------------------------------------------
+    def flops_step(self):
+        T, r = self.T, self.rank
+        return sum(4.0 * T * st["p"].d_in * st["p"].d_out + 6.0 * T * r * (st["p"].d_in + st["p"].d_out) for st in self.proj)
+
+    def merge_bytes(self, p):
+        lam = self.lam
+        scale_in = (1 / 64 + 8 / (64 * 256)) if self.wl.scale_mode else 4 / 64
+        return p.d_in * p.d_out * (0.5 + scale_in + 4.0 / (lam * lam) + 0.5 + 8 / 64)
+
+    def describe(self):
+        wl = self.wl
+        shapes = {}
+        for st in self.proj:
+            k = f"{st['p'].d_out}x{st['p'].d_in}"
+            shapes[k] = shapes.get(k, 0) + 1
+        return (f"{wl.name}: T={self.T} tokens, projections " + " + ".join(f"{n} x [{k}]" for k, n in shapes.items()) +
+                f", 4-bit block {wl.block}" + (" with double-quantized (E4M3, groups of 256) block scales" if wl.scale_mode else "") +
+                f", adapter rank {self.rank}, lambda {self.lam} (inner rank {self.R}), s={wl.s}")
+
+
+def stats(ms):
+    import numpy as np
+    a = np.asarray(ms, dtype=np.float64)
+    return {"mean": round(float(a.mean()), 4), "median": round(float(np.median(a)), 4), "min": round(float(a.min()), 4)}
+
+
+def measure(S, steps, warmup, side_steps, plain_events=False, calibration_copy=False):
+    """Times `steps` steps of the workload held by `S` at its current rank; returns the result dict."""
+    import numpy as np
+    import torch
+    from paper_2407_17029_amd import binding as qb
+
+    wl, dev = S.wl, S.dev
+    T, lam, R, r = S.T, S.lam, S.R, S.rank
+    # the projection whose kernels are bracketed: the one with the most weights (first of equals)
+    big = max(range(len(S.proj)), key=lambda i: (S.proj[i]["p"].d_in * S.proj[i]["p"].d_out, -i))
+    bp = S.proj[big]["p"]
+
+    if calibration_copy:
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # reads 256 MiB, writes 256 MiB: a kernel of known traffic for counter runs
+        torch.cuda.synchronize()
+        del src, dst
+
+    for _ in range(warmup):
+        S.step()
+    torch.cuda.synchronize()
+
+    new_event = (lambda: torch.cuda.Event(enable_timing=True)) if plain_events else qb.TimingEvent
+    slots = {"fwd_gemm": qb.PROFILE_FWD_GEMM, "bwd_gemm": qb.PROFILE_BWD_GEMM, "quantize": qb.PROFILE_QUANTIZE,
+             "adapter_fwd": qb.PROFILE_ADAPTER_FWD, "adapter_bwd": qb.PROFILE_ADAPTER_BWD,
+             "adapter_grads": qb.PROFILE_ADAPTER_GRADS, "grad_reduce": qb.PROFILE_GRAD_REDUCE,
+             "prep": qb.PROFILE_PREP, "tile_product": qb.PROFILE_TILE_PRODUCT, "merge": qb.PROFILE_MERGE}
+    events = {k: [(new_event(), new_event()) for _ in range(steps if k == "fwd_gemm" else side_steps)] for k in slots}
+    marks = [new_event() for _ in range(steps + 1)]
+    for pairs in events.values():
+        for a, b in pairs:
+            a.record(); b.record()          # creates the native handles
+    for m in marks:
+        m.record()
+    torch.cuda.synchronize()
+    # What an event pair measures with nothing in between (the stream's cost of processing the second record);
+    # taken off the bracketed GEMMs' elapsed times, which then agree with the kernel trace.
+    empty_pair_ms = float(np.median([a.elapsed_time(b) for pairs in events.values() for a, b in pairs]))
+
+    def bracketed_step(i, which):
+        """One step with the event pairs of `which` registered around projection `big`'s calls only."""
+        for j, st in enumerate(S.proj):
+            if j == big:
+                for k in which:
+                    if k not in ("merge", "tile_product"):
+                        qb.qblora_profile_events(slots[k], *events[k][i])
+            S.layer_pass(st)
+            if j == big:
+                for k in which:
+                    qb.qblora_profile_events(slots[k], None, None)
+        # the merge batch: one pair around all tile products, one around all merges
+        if "merge" in which:
+            for st in S.proj:
+                qb.qblora_tile_product(st["ad"], st["p"].d_in, st["p"].d_out, st["H"], S.ws)
+            events["merge"][i][0].record()
+            for st in S.proj:
+                qb.qablora_merge_quantize(st["qw"], st["H"], lam, lam, wl.s, qb.MERGE_REQUANT_MINMAX, out=st["merged"])
+            events["merge"][i][1].record()
+        else:
+            S.merge_batch()
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        marks[i].record()
+        bracketed_step(i, ("fwd_gemm",))
+    marks[steps].record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    side = [k for k in slots if k != "fwd_gemm"]
+    for i in range(side_steps):             # untimed: one event pair per kernel of the bracketed projection
+        bracketed_step(i, side)
+    torch.cuda.synchronize()
+
+    raw = {k: [a.elapsed_time(b) for a, b in pairs] for k, pairs in events.items()}
+    step_ms = [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
+    ms_per_step = elapsed * 1e3 / steps
+    flops_step = S.flops_step()
+    value = flops_step / (ms_per_step * 1e-3) / 1e12
+
+    def gemm_ms(k):
+        return max(float(np.mean(raw[k])) - empty_pair_ms, 1e-6)
+
+    fwd_flops = 2.0 * T * bp.d_in * bp.d_out + 2.0 * T * R * bp.d_out / lam
+    bwd_flops = 2.0 * T * bp.d_in * bp.d_out + 2.0 * T * R * bp.d_in / lam
+    n_w = bp.d_in * bp.d_out
+    quant_bytes = n_w * (4 + 0.5 + 4 / 64)
+    merge_batch_bytes = sum(S.merge_bytes(st["p"]) for st in S.proj)
+    achieved = fwd_flops / (gemm_ms("fwd_gemm") * 1e-3) / 1e12
+
+    def hbm(k, nbytes, note=None):
+        ms = float(np.mean(raw[k]))
+        d = {"bound": "hbm", "event_overhead_included": True, "ms": stats(raw[k]),
+             "achieved": round(nbytes / (ms * 1e-3) / 1e9, 1), "unit": "GB/s",
+             "frac": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "algorithmic_bytes": int(nbytes)}
+        if note:
+            d["note"] = note
+        return d
+
+    proj_name = f"{bp.name} [{bp.d_out}x{bp.d_in}]"
+    kname = "k_qlinear<1> (forward dequantize-and-contract)"
+    out = {
+        "value": round(value, 2), "unit": "TFLOP/s", "steps": steps, "warmup": warmup,
+        "ms_per_step": round(ms_per_step, 4), "step_ms": stats(step_ms),
+        "tokens_per_s": round(T / (ms_per_step * 1e-3), 1),
+        "pct_of_bf16_mfma_peak": round(100.0 * value / MFMA_BF16_PEAK_TFLOPS, 2),
+        "workload": S.describe(), "counted_flops_per_step": flops_step,
+        "roofline": {"kernel": kname, "projection": proj_name, "bound": "mfma",
+                     "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "traffic": measured_traffic(wl.name, "fwd_gemm"),
+                     "avg_kernel_ms": round(gemm_ms("fwd_gemm"), 4), "kernel_ms": stats(raw["fwd_gemm"]),
+                     "empty_event_pair_ms": round(empty_pair_ms, 4), "algorithmic_flops": fwd_flops},
+        "kernels": {
+            "projection": proj_name,
+            "bwd_gemm": {"bound": "mfma", "avg_kernel_ms": round(gemm_ms("bwd_gemm"), 4), "kernel_ms": stats(raw["bwd_gemm"]),
+                         "achieved": round(bwd_flops / (gemm_ms("bwd_gemm") * 1e-3) / 1e12, 2), "unit": "TFLOP/s",
+                         "frac": round(bwd_flops / (gemm_ms("bwd_gemm") * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)},
+            "quantize": hbm("quantize", quant_bytes),
+            "adapter_fwd_skinny": hbm("adapter_fwd", 2.0 * T * bp.d_in + 2.0 * T * R * 2, "s*U = (s/lambda) X A_x^T; reads X once"),
+            "adapter_bwd_skinny": hbm("adapter_bwd", 2.0 * T * bp.d_out + 2.0 * T * R * 3, "dU = s dY B_x^T; reads dY once"),
+            "adapter_grads": hbm("adapter_grads", 2.0 * T * (bp.d_in + bp.d_out) + 8.0 * T * R,
+                                 "token contractions behind dA and dB, one launch; partial-sum writes not counted"),
+            "grad_reduce": {"ms": stats(raw["grad_reduce"])},
+            "prep": {"ms": stats(raw["prep"])},
+            "merge_requant_batch": hbm("merge", merge_batch_bytes,
+                                       f"{len(S.proj)} requantizing merges back to back (all projections of the layer)"),
+        },
+    }
+    for k in ("quantize", "adapter_fwd", "adapter_bwd", "adapter_grads", "merge"):
+        t = measured_traffic(wl.name, k)
+        key = {"adapter_fwd": "adapter_fwd_skinny", "adapter_bwd": "adapter_bwd_skinny", "merge": "merge_requant_batch"}.get(k, k)
+        out["kernels"][key]["traffic"] = t
+    adapter_ms = sum(float(np.mean(raw[k])) for k in ("adapter_fwd", "adapter_bwd", "adapter_grads", "grad_reduce", "prep"))
+    proj_ms = adapter_ms + gemm_ms("fwd_gemm") + gemm_ms("bwd_gemm") + float(np.mean(raw["quantize"]))
+    out["kernels"]["adapter_side_share_of_projection"] = round(adapter_ms / proj_ms, 4)
+    return out
+
+
+def cpu_baseline(S, sample_rows):
+    """The fp64 oracle as it stands, on a bounded sample: for each distinct projection shape the one-off parts
+    (quantize, dequantize, tile product, merge) in full and forward + backward on `sample_rows` token rows;
+    extrapolated linearly in tokens and multiplied by how many projections have that shape."""
+    import numpy as np
+    import oracle
+    from paper_2407_17029_amd import synth
+    wl, T, lam, cb = S.wl, S.T, S.lam, S.cb
+    ts = min(sample_rows, T)
+    rows = synth.sample_rows(T, ts, wl.seed)
+    seen = {}
+    for i, st in enumerate(S.proj):
+        p = st["p"]
+        key = (p.d_out, p.d_in)
+        if key in seen:
+            seen[key]["count"] += 1
+            continue
+        W = S.host[("W", i)]
+        A, B = S.host[("AB", i)]
+        Xs = np.ascontiguousarray(S.host[("X", p.d_in)][rows])
+        dYs = np.ascontiguousarray(S.host[("dY", p.d_out)][rows])
+        c0 = time.perf_counter()
+        codes, absmax = oracle.quantize_codebook(W, wl.block, cb)
+        scales = absmax
+        if wl.scale_mode:
+            sc, stp, mid = oracle.scales_double_quantize(absmax.reshape(-1), 256)
+            scales = oracle.scales_double_dequantize(sc, stp, mid, 256).reshape(absmax.shape)
+        Wt = oracle.dequantize(codes, scales, None, cb, wl.block, 2)
+        c1 = time.perf_counter()
+        oracle.forward(Wt, Xs, A, B, lam, lam, wl.s)
+        oracle.backward(Wt, Xs, dYs, A, B, lam, lam, wl.s)
+        c2 = time.perf_counter()
+        del Wt
+        Ho = oracle.tile_product(A, B).astype(np.float32)
+        oracle.merge_requant(codes, scales, None, cb, Ho, wl.block, lam, lam, wl.s)
+        c3 = time.perf_counter()
+        seen[key] = {"count": 1, "one_off": (c1 - c0) + (c3 - c2), "token_part": c2 - c1}
+    measured = sum(v["one_off"] + v["token_part"] for v in seen.values())
+    est_full = sum(v["count"] * (v["one_off"] + v["token_part"] * (T / ts)) for v in seen.values())
+    return {"value": round(S.flops_step() / est_full / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.get_threads(),
+            "kind": "oracle", "extrapolated": True,
+            "sample": f"fp64 oracle, {measured:.1f} s measured: for each of the {len(seen)} distinct projection shapes the "
+                      f"quantize + dequantize + tile product + merge in full and forward + backward (dX, dA, dB) on {ts} of {T} "
+                      f"token rows; EXTRAPOLATED linearly in tokens (x{T / ts:.0f}) and by the number of projections of each "
+                      f"shape to the full step: {est_full:.0f} s"}
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="llama7b_attn")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
+    ap.add_argument("--workload", default="llama65b_layer")
+    ap.add_argument("--rank", type=int, default=0, help="adapter rank D_rank (0 = the workload's own)")
+    ap.add_argument("--cpu-sample-rows", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-next-rows", action="store_true", help="skip the untimed side measurement of the single-matrix adapter")
+    ap.add_argument("--no-configs", action="store_true", help="skip the other workloads (the `configs` object)")
     ap.add_argument("--plain-events", action="store_true",
                     help="time the kernels with ordinary HIP events (system-scope fence at every record)")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -51,230 +383,63 @@ def main() -> int:
               file=sys.stderr)
         return 2
 
-    import numpy as np
     import torch
     from paper_2407_17029_amd import binding as qb
     from paper_2407_17029_amd import synth
 
-    wl = synth.WORKLOADS[args.workload]
-    if len(wl.projections) != 1:
-        print("bench.py: the timed workload is a single projection", file=sys.stderr)
-        return 2
-    proj = wl.projections[0]
-    T, d_out, d_in, lam, r = wl.tokens, proj.d_out, proj.d_in, wl.lam, wl.rank
-    R = lam * r
     dev = "cuda:0"
     torch.cuda.set_device(0)
     qb.lib()
-
-    L = synth.make_layer(wl.seed, T, d_out, d_in, R, lam, lam)
-    cb = synth.codebook_nf4_style()
-
-    def bf16_dev(bits):
-        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
-
-    W = torch.from_numpy(L.W).to(dev)
-    X, dY = bf16_dev(L.X), bf16_dev(L.dY)
-    ad = qb.Adapter(bf16_dev(L.A), bf16_dev(L.B), lam, lam, wl.s)
-    scale_mode = qb.SCALES_E4M3_GROUPED if wl.scale_mode else qb.SCALES_FP32
-    qw = qb.qblora_quantize_blockwise(W, wl.block, qb.QUANT_ABSMAX_CODEBOOK, cb, scale_mode)
-    Y = torch.empty((T, d_out), dtype=torch.bfloat16, device=dev)
-    dX = torch.empty((T, d_in), dtype=torch.bfloat16, device=dev)
-    dA = torch.empty((d_in // lam, R), dtype=torch.float32, device=dev)
-    dB = torch.empty((R, d_out // lam), dtype=torch.float32, device=dev)
-    H = torch.empty((d_in // lam, d_out // lam), dtype=torch.float32, device=dev)
-    nbytes = max(qb.qblora_linear_fwd_workspace_bytes(qw, ad, T), qb.qblora_linear_bwd_workspace_bytes(qw, ad, T))
-    ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
-    merged = qb.qablora_merge_quantize(qw, qb.qblora_tile_product(ad, d_in, d_out, H, ws), lam, lam, wl.s,
-                                       qb.MERGE_REQUANT_MINMAX)
-
-    saved = torch.empty(qb.qblora_saved_bytes(ad, T), dtype=torch.uint8, device=dev)   # s*U kept from forward to backward
-
-    def step():
-        qb.qblora_quantize_blockwise(W, wl.block, qb.QUANT_ABSMAX_CODEBOOK, cb, scale_mode, out=qw)
-        qb.qblora_linear_fwd(qw, ad, X, Y, ws, saved=saved)
-        qb.qblora_linear_bwd(qw, ad, X, dY, True, True, dX, dA, dB, ws, saved=saved)
-        qb.qblora_tile_product(ad, d_in, d_out, H, ws)
-        qb.qablora_merge_quantize(qw, H, lam, lam, wl.s, qb.MERGE_REQUANT_MINMAX, out=merged)
-
-    if args.calibration_copy:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
-        src.zero_()
-        dst = torch.empty_like(src)
-        dst.copy_(src)                      # reads 256 MiB, writes 256 MiB
-        torch.cuda.synchronize()
-        del src, dst
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-
-    # Per-kernel HIP events, recorded by the library on the launch stream around one kernel each.  An
-    # event record costs about 5.6 us of idle stream on this machine, so only the dominant kernel is
-    # bracketed inside the timed region; the other kernels are timed in a pass of their own afterwards.
-    kinds = {"fwd_gemm": qb.PROFILE_FWD_GEMM, "bwd_gemm": qb.PROFILE_BWD_GEMM, "merge": qb.PROFILE_MERGE,
-             "quantize": qb.PROFILE_QUANTIZE}
-    side_steps = min(args.steps, 10)
-    # The events only measure time (hipEventDisableSystemFence): an ordinary event record also writes back and
-    # invalidates the caches at system scope, which costs stream time and slows the kernel behind it.
-    # --plain-events uses torch's ordinary timing events instead.
-    new_event = (lambda: torch.cuda.Event(enable_timing=True)) if args.plain_events else qb.TimingEvent
-    events = {k: [(new_event(), new_event())
-                  for _ in range(args.steps if k == "fwd_gemm" else side_steps)] for k in kinds}
-    for pairs in events.values():
-        for a, b in pairs:
-            a.record(); b.record()          # creates the native handles
-    torch.cuda.synchronize()
-    # What an event pair measures with nothing in between: the stream's cost of processing the second
-    # record.  A bracketed kernel's elapsed time contains it (plus the launch of the kernel behind the first
-    # record); it is reported and taken off the kernel durations below.
-    empty_pair_ms = float(np.median([a.elapsed_time(b) for pairs in events.values() for a, b in pairs]))
-
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        qb.qblora_profile_events(kinds["fwd_gemm"], *events["fwd_gemm"][i])
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    qb.qblora_profile_events(kinds["fwd_gemm"], None, None)
-
-    for i in range(side_steps):             # untimed: the kernels the extra "kernels" object reports
-        for k, which in kinds.items():
-            if k != "fwd_gemm":
-                qb.qblora_profile_events(which, *events[k][i])
-        step()
-    torch.cuda.synchronize()
-    for which in kinds.values():
-        qb.qblora_profile_events(which, None, None)
-
-    raw_kernel_ms = {k: float(np.mean([a.elapsed_time(b) for a, b in pairs])) for k, pairs in events.items()}
-    # The empty-pair time is taken off the two GEMMs only, where the result agrees with the kernel trace of the
-    # same launches to 1 %; for kernels of 10-20 us the overlap of the second record with the kernel's tail is
-    # not that regular (trace: -10 % .. +8 %), so their elapsed times are reported as measured (an upper bound).
-    kernel_ms = {k: (max(v - empty_pair_ms, 1e-6) if k in ("fwd_gemm", "bwd_gemm") else v) for k, v in raw_kernel_ms.items()}
-    ms_per_step = elapsed * 1e3 / args.steps
-    flops_step = 4.0 * T * d_in * d_out + 6.0 * T * r * (d_in + d_out)
-    value = flops_step / (ms_per_step * 1e-3) / 1e12
-
-    n_w = d_in * d_out
-    fwd_kernel_flops = 2.0 * T * d_in * d_out + 2.0 * T * R * d_out / lam
-    bwd_kernel_flops = 2.0 * T * d_in * d_out + 2.0 * T * R * d_in / lam
-    merge_bytes = n_w * (0.5 + (1 / 64 + 4 / (64 * 256) if wl.scale_mode else 4 / 64) + 4.0 / (lam * lam) + 0.5 + 8 / 64)
-    quant_bytes = n_w * (4 + 0.5 + 4 / 64)
-    achieved = fwd_kernel_flops / (kernel_ms["fwd_gemm"] * 1e-3) / 1e12
-    traffic = MEASURED_TRAFFIC_BYTES.get(wl.name)
+    side_steps = max(1, min(args.steps, 5))
+    wl = synth.WORKLOADS[args.workload]
+    S = Stack(wl, args.rank or wl.rank, dev)
+    res = measure(S, args.steps, args.warmup, side_steps, args.plain_events, args.calibration_copy)
     out = {
         "metric": "fused quantized-linear+BLoRA fwd+bwd TFLOP/s",
-        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": res["value"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{wl.name}: T={T} tokens, W {d_out}x{d_in} 4-bit block {wl.block}, adapter rank {r}, "
-                               f"lambda {lam} (inner rank {R}), s={wl.s}",
-                   "step": "quantize + forward + backward(dX,dA,dB) + tile product + INT4 requantizing merge"},
-        "tokens_per_s": round(T / (ms_per_step * 1e-3), 1),
-        "pct_of_bf16_mfma_peak": round(100.0 * value / MFMA_BF16_PEAK_TFLOPS, 2),
-        "roofline": {"kernel": "k_qlinear<1> (forward dequantize-and-contract)", "bound": "mfma",
-                     "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic,
-                     "avg_kernel_ms": round(kernel_ms["fwd_gemm"], 4),
-                     "event_elapsed_ms": round(raw_kernel_ms["fwd_gemm"], 4), "empty_event_pair_ms": round(empty_pair_ms, 4)},
-        "kernels": {
-            "bwd_gemm": {"bound": "mfma", "avg_kernel_ms": round(kernel_ms["bwd_gemm"], 4),
-                         "achieved": round(bwd_kernel_flops / (kernel_ms["bwd_gemm"] * 1e-3) / 1e12, 2),
-                         "unit": "TFLOP/s",
-                         "frac": round(bwd_kernel_flops / (kernel_ms["bwd_gemm"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)},
-            "merge_requant": {"bound": "hbm", "event_overhead_included": True, "avg_kernel_ms": round(kernel_ms["merge"], 4),
-                              "achieved": round(merge_bytes / (kernel_ms["merge"] * 1e-3) / 1e9, 1), "unit": "GB/s",
-                              "frac": round(merge_bytes / (kernel_ms["merge"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
-            "quantize": {"bound": "hbm", "event_overhead_included": True, "avg_kernel_ms": round(kernel_ms["quantize"], 4),
-                         "achieved": round(quant_bytes / (kernel_ms["quantize"] * 1e-3) / 1e9, 1), "unit": "GB/s",
-                         "frac": round(quant_bytes / (kernel_ms["quantize"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
-        },
+        "config": {"workload": res["workload"],
+                   "step": "per projection: quantize + forward + backward(dX,dA,dB); then tile product + INT4 requantizing "
+                           "merge of all projections"},
+        "step_ms": res["step_ms"], "tokens_per_s": res["tokens_per_s"],
+        "pct_of_bf16_mfma_peak": res["pct_of_bf16_mfma_peak"],
+        "roofline": res["roofline"], "kernels": res["kernels"],
     }
-
-    if not args.no_next_rows:
-        # Untimed side measurement of the next row of the scope: the single-matrix (QA-BLoRA) training form at
-        # the same layer shape with the block-64 recommendation lambda = (8, 8), forward + backward (dX, dH).
-        qa_l1 = qa_l2 = 8
-        Hq = (torch.randn((d_in // qa_l1, d_out // qa_l2), device=dev) * 0.02).to(torch.bfloat16)
-        dH = torch.empty((d_in // qa_l1, d_out // qa_l2), dtype=torch.float32, device=dev)
-        qa_bytes = max(qb.lib().qablora_linear_fwd_workspace_bytes(C.byref(qw.c_struct()), qa_l1, qa_l2, T),
-                       qb.lib().qablora_linear_bwd_workspace_bytes(C.byref(qw.c_struct()), qa_l1, qa_l2, T))
-        ws_qa = torch.empty(int(qa_bytes) + 256, dtype=torch.uint8, device=dev)
-
-        def qa_step():
-            qb.qablora_linear_fwd(qw, Hq, qa_l1, qa_l2, wl.s, X, Y, ws_qa)
-            qb.qablora_linear_bwd(qw, Hq, qa_l1, qa_l2, wl.s, X, dY, True, True, dX, dH, ws_qa)
-
-        for _ in range(3):
-            qa_step()
-        torch.cuda.synchronize()
-        q0 = time.perf_counter()
-        for _ in range(side_steps):
-            qa_step()
-        torch.cuda.synchronize()
-        qa_ms = (time.perf_counter() - q0) * 1e3 / side_steps
-        qa_flops = 4.0 * T * d_in * d_out + 6.0 * T * (d_in // qa_l1) * (d_out // qa_l2)
-        out["next_rows"] = {"qablora_single_matrix_fwd_bwd": {
-            "lambda": [qa_l1, qa_l2], "ms_per_step": round(qa_ms, 4), "unit": "TFLOP/s",
-            "achieved": round(qa_flops / (qa_ms * 1e-3) / 1e12, 2),
-            "frac_of_bf16_mfma_peak": round(qa_flops / (qa_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}}
-
-    if not args.no_next_rows:
-        # The ablation's alternative scale operators on the same layer: forward + backward (dX, dA, dB) with the
-        # activation kept in between, as in the timed step (no merge: their delta weight is not tile-constant).
-        op_rows = {}
-        for name, op in (("truncate_pad0", qb.OP_TRUNCATE_PAD0), ("sample_zerofill", qb.OP_SAMPLE_ZEROFILL)):
-            ad_op = qb.Adapter(ad.A, ad.B, lam, lam, wl.s, scale_op=op)
-            nb_op = max(qb.qblora_linear_fwd_workspace_bytes(qw, ad_op, T), qb.qblora_linear_bwd_workspace_bytes(qw, ad_op, T))
-            ws_op = torch.empty(int(nb_op) + 256, dtype=torch.uint8, device=dev)
-
-            def op_step():
-                qb.qblora_linear_fwd(qw, ad_op, X, Y, ws_op, saved=saved)
-                qb.qblora_linear_bwd(qw, ad_op, X, dY, True, True, dX, dA, dB, ws_op, saved=saved)
-
-            for _ in range(3):
-                op_step()
-            torch.cuda.synchronize()
-            q0 = time.perf_counter()
-            for _ in range(side_steps):
-                op_step()
-            torch.cuda.synchronize()
-            op_ms = (time.perf_counter() - q0) * 1e3 / side_steps
-            op_flops = 4.0 * T * d_in * d_out + 6.0 * T * wl.rank * (d_in + d_out)
-            op_rows[name] = {"ms_per_step": round(op_ms, 4), "unit": "TFLOP/s",
-                             "achieved": round(op_flops / (op_ms * 1e-3) / 1e12, 2),
-                             "frac_of_bf16_mfma_peak": round(op_flops / (op_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
-            del ws_op
-        out["next_rows"]["scale_operators_fwd_bwd"] = op_rows
-
     if not args.no_cpu_baseline:
-        import oracle
-        ts = min(args.cpu_sample_tokens, T)
-        rows = synth.sample_rows(T, ts, wl.seed)
-        Xs, dYs = np.ascontiguousarray(L.X[rows]), np.ascontiguousarray(L.dY[rows])
-        c0 = time.perf_counter()
-        codes, absmax = oracle.quantize_codebook(L.W, wl.block, cb)
-        scales = absmax
-        if wl.scale_mode:
-            sc, stp, mid = oracle.scales_double_quantize(absmax.reshape(-1), 256)
-            scales = oracle.scales_double_dequantize(sc, stp, mid, 256).reshape(absmax.shape)
-        Wt = oracle.dequantize(codes, scales, None, cb, wl.block, 2)
-        c1 = time.perf_counter()
-        oracle.forward(Wt, Xs, L.A, L.B, lam, lam, wl.s)
-        oracle.backward(Wt, Xs, dYs, L.A, L.B, lam, lam, wl.s)
-        c2 = time.perf_counter()
-        Ho = oracle.tile_product(L.A, L.B).astype(np.float32)
-        oracle.merge_requant(codes, scales, None, cb, Ho, wl.block, lam, lam, wl.s)
-        c3 = time.perf_counter()
-        one_off = (c1 - c0) + (c3 - c2)
-        est_full = one_off + (c2 - c1) * (T / ts)
-        out["cpu_baseline"] = {
-            "value": round(flops_step / est_full / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.get_threads(),
-            "kind": "oracle",
-            "sample": f"fp64 oracle: quantize+dequantize+tile product+merge in full ({one_off:.2f} s), forward+backward "
-                      f"on {ts} of {T} token rows ({c2 - c1:.2f} s), token-proportional part scaled by {T / ts:.0f}x "
-                      f"(extrapolated full step {est_full:.1f} s)"}
+        out["cpu_baseline"] = cpu_baseline(S, args.cpu_sample_rows)
+    del S
+    torch.cuda.empty_cache()
+
+    if not args.no_configs:
+        cfg = {}
+        others = [n for n in ("llama7b_attn", "llama7b_mlp", "llama13b_layer") if n != args.workload]
+        for name in others:
+            steps = max(3, min(args.steps, 10))
+            wl2 = synth.WORKLOADS[name]
+            S2 = Stack(wl2, wl2.rank, dev)
+            r = measure(S2, steps, 3, min(3, side_steps), args.plain_events)
+            entry = {k: r[k] for k in ("value", "unit", "steps", "ms_per_step", "step_ms", "tokens_per_s",
+                                       "pct_of_bf16_mfma_peak", "workload")}
+            entry["roofline"] = {k: r["roofline"][k] for k in ("kernel", "projection", "bound", "achieved", "peak", "unit",
+                                                               "frac", "traffic", "avg_kernel_ms")}
+            entry["kernels"] = {"bwd_gemm_frac": r["kernels"]["bwd_gemm"]["frac"],
+                                "quantize_frac": r["kernels"]["quantize"]["frac"],
+                                "merge_requant_batch_frac": r["kernels"]["merge_requant_batch"]["frac"],
+                                "adapter_side_share_of_projection": r["kernels"]["adapter_side_share_of_projection"]}
+            if name == "llama13b_layer":
+                sweep = {str(wl2.rank): {"value": r["value"], "ms_per_step": r["ms_per_step"],
+                                         "roofline_frac": r["roofline"]["frac"]}}
+                for rk in (32, 128):
+                    S2.set_rank(rk)
+                    rr = measure(S2, steps, 3, 1, args.plain_events)
+                    sweep[str(rk)] = {"value": rr["value"], "ms_per_step": rr["ms_per_step"],
+                                      "roofline_frac": rr["roofline"]["frac"]}
+                entry["rank_sweep"] = sweep
+            del S2
+            torch.cuda.empty_cache()
+            cfg[name] = entry
+        out["configs"] = cfg
     print(json.dumps(out))
     return 0
 

@@ -350,12 +350,20 @@ int qblora_decode_pack(const qblora_qweight* qw, void* pack, void* stream);
  *   QBLORA_PROFILE_BWD_GEMM   the transposed dequantize-and-contract kernel of qblora_linear_bwd
  *   QBLORA_PROFILE_MERGE      the requantizing (or beta-shift) kernel of qablora_merge_quantize
  *   QBLORA_PROFILE_QUANTIZE   the code-selection kernel of qblora_quantize_blockwise
+ *   QBLORA_PROFILE_ADAPTER_FWD    the narrow GEMM s*U = s * AvgPool(X) A of the forward
+ *   QBLORA_PROFILE_ADAPTER_BWD    the narrow GEMM dU = dV B^T of the backward
+ *   QBLORA_PROFILE_ADAPTER_GRADS  the token contractions behind dA and dB (partial sums, both in one launch)
+ *   QBLORA_PROFILE_GRAD_REDUCE    the fixed-order reduction of those partial sums into dA and dB
+ *   QBLORA_PROFILE_PREP           the per-call re-layout launch of the forward (adapter operands, block scales)
+ *   QBLORA_PROFILE_TILE_PRODUCT   the kernel of qblora_tile_product
  * Passing NULL for both events unregisters the slot.  The registration is per host thread: it applies to
  * calls made by the thread that registered it, so concurrent callers do not see each other's events.  Has
  * no effect on results.
  */
 enum { QBLORA_PROFILE_FWD_GEMM = 0, QBLORA_PROFILE_BWD_GEMM = 1, QBLORA_PROFILE_MERGE = 2,
-       QBLORA_PROFILE_QUANTIZE = 3 };
+       QBLORA_PROFILE_QUANTIZE = 3, QBLORA_PROFILE_ADAPTER_FWD = 4, QBLORA_PROFILE_ADAPTER_BWD = 5,
+       QBLORA_PROFILE_ADAPTER_GRADS = 6, QBLORA_PROFILE_GRAD_REDUCE = 7, QBLORA_PROFILE_PREP = 8,
+       QBLORA_PROFILE_TILE_PRODUCT = 9, QBLORA_PROFILE_SLOTS = 10 };
 int qblora_profile_events(int32_t which, void* start_event, void* stop_event);
 
 /* Static description of an error code. */

@@ -34,6 +34,8 @@ EXPORTS = ["qblora_quantize_blockwise", "qblora_dequantize_bf16", "qblora_linear
            "qblora_noalloc_scratch_bytes", "qblora_linear_fwd_noalloc"]
 
 PROFILE_FWD_GEMM, PROFILE_BWD_GEMM, PROFILE_MERGE, PROFILE_QUANTIZE = 0, 1, 2, 3
+PROFILE_ADAPTER_FWD, PROFILE_ADAPTER_BWD, PROFILE_ADAPTER_GRADS, PROFILE_GRAD_REDUCE = 4, 5, 6, 7
+PROFILE_PREP, PROFILE_TILE_PRODUCT = 8, 9
 
 
 class CQWeight(C.Structure):

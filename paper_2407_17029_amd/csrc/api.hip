@@ -140,18 +140,24 @@ BwdSpace carve_bwd(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T
     return s;
 }
 
-// measurement hook (qblora_profile_events): the registration belongs to the calling host thread
-thread_local hipEvent_t g_events[4][2] = {};
+}  // namespace
 
-struct ScopedEvents {
-    int which; hipStream_t st;
-    ScopedEvents(int w, hipStream_t s) : which(w), st(s) {
-        if (g_events[which][0]) (void)hipEventRecord(g_events[which][0], st);
-    }
-    ~ScopedEvents() {
-        if (g_events[which][1]) (void)hipEventRecord(g_events[which][1], st);
-    }
-};
+// measurement hook (qblora_profile_events): the registration belongs to the calling host thread
+namespace qblora {
+namespace {
+thread_local hipEvent_t g_events[QBLORA_PROFILE_SLOTS][2] = {};
+}
+ProfileScope::ProfileScope(int w, hipStream_t s) : which(w), st(s) {
+    if (g_events[which][0]) (void)hipEventRecord(g_events[which][0], st);
+}
+ProfileScope::~ProfileScope() {
+    if (g_events[which][1]) (void)hipEventRecord(g_events[which][1], st);
+}
+}  // namespace qblora
+
+namespace {
+
+using ScopedEvents = qblora::ProfileScope;
 
 __global__ void k_fill_zero(float* p, int64_t n) {
     int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -184,10 +190,10 @@ const char* qblora_strerror(int code) {
 }
 
 int qblora_profile_events(int32_t which, void* start_event, void* stop_event) {
-    if (which < 0 || which > 3) return QBLORA_ERR_SHAPE;
+    if (which < 0 || which >= QBLORA_PROFILE_SLOTS) return QBLORA_ERR_SHAPE;
     if ((start_event == nullptr) != (stop_event == nullptr)) return QBLORA_ERR_NULL;
-    g_events[which][0] = static_cast<hipEvent_t>(start_event);
-    g_events[which][1] = static_cast<hipEvent_t>(stop_event);
+    qblora::g_events[which][0] = static_cast<hipEvent_t>(start_event);
+    qblora::g_events[which][1] = static_cast<hipEvent_t>(stop_event);
     return QBLORA_OK;
 }
 
@@ -304,11 +310,14 @@ int linear_fwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
     const bool prep_adapter = adapted && op == QBLORA_OP_AVGPOOL_REPEAT;
     // lambda1 = 2: A^T stays unexpanded and the narrow GEMM uses each of its columns for two adjacent k
     const bool dup_a = prep_adapter && pooled_pair_operand(T, ad->R, qw->d_in, ad->lambda1);
-    if ((rc = launch_adapter_prep(prep_adapter ? ad->A : nullptr, prep_adapter ? ad->B : nullptr,
-                                  dup_a ? qw->d_in / 2 : qw->d_in, qw->d_out,
-                                  adapted ? ad->R : 0, adapted ? (dup_a ? 1 : ad->lambda1) : 1, adapted ? ad->lambda2 : 1,
-                                  ws.At_x, ws.Bt, nullptr, st, &sct)))
-        return rc;
+    {
+        ScopedEvents ev(QBLORA_PROFILE_PREP, st);
+        rc = launch_adapter_prep(prep_adapter ? ad->A : nullptr, prep_adapter ? ad->B : nullptr,
+                                 dup_a ? qw->d_in / 2 : qw->d_in, qw->d_out,
+                                 adapted ? ad->R : 0, adapted ? (dup_a ? 1 : ad->lambda1) : 1, adapted ? ad->lambda2 : 1,
+                                 ws.At_x, ws.Bt, nullptr, st, &sct);
+    }
+    if (rc) return rc;
     if (adapted && op != QBLORA_OP_AVGPOOL_REPEAT) {
         // At_x[j][k] = A[C-map(k)][j] and Bt[n][j] = B[j][E-map(n)], zero where the operator drops the index
         const int na = qw->d_in / ad->lambda1, nb = qw->d_out / ad->lambda2;
@@ -326,7 +335,11 @@ int linear_fwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
         qblora_bf16* su = saved ? saved : ws.U;               // kept for the backward: high part, then residual
         u.C = su; u.C_lo = saved ? saved + T * ad->R : nullptr;
         u.ldc = ad->R; u.out_scale = op ? ad->s : ad->s / (float)ad->lambda1; u.M = T; u.N = ad->R;
-        if ((rc = launch_gemm(u, st))) return rc;
+        {
+            ScopedEvents ev(QBLORA_PROFILE_ADAPTER_FWD, st);
+            rc = launch_gemm(u, st);
+        }
+        if (rc) return rc;
         g.X2 = su; g.ldx2 = ad->R; g.W2 = ws.Bt; g.ldw2 = ad->R; g.K2 = ad->R; g.div2 = op ? 1 : ad->lambda2;
     } else {
         g.K2 = 0; g.div2 = 1;
@@ -399,7 +412,11 @@ int linear_bwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
         du.C = ws.dU; du.ldc = R; du.out_scale = ad->s; du.C2 = ws.dUs; du.c2_scale = op ? 1.0f : 1.0f / (float)ad->lambda1;
         du.C_lo = want_grads ? ws.dU_lo : nullptr;
         du.M = T; du.N = R;
-        if ((rc = launch_gemm(du, st))) return rc;
+        {
+            ScopedEvents ev(QBLORA_PROFILE_ADAPTER_BWD, st);
+            rc = launch_gemm(du, st);
+        }
+        if (rc) return rc;
         if (want_grads) {
             const qblora_bf16* su = saved; const qblora_bf16* su_lo = saved ? saved + T * R : nullptr;
             if (!saved) {                                     // s*U again from X, as the forward computed it
@@ -673,6 +690,7 @@ int qblora_tile_product(const qblora_adapter* ad, int32_t d_in, int32_t d_out, f
     if (!workspace || workspace_bytes < need) return QBLORA_ERR_WORKSPACE;
     hipStream_t st = as_stream(stream);
     // whole tiles: one kernel that transposes B on the fly; otherwise a transposed copy and the general GEMM
+    ScopedEvents ev(QBLORA_PROFILE_TILE_PRODUCT, st);
     int rc = launch_tile_product(ad->A, ad->B, rows, cols, ad->R, H, st);
     if (rc != QBLORA_ERR_UNSUPPORTED) return rc;
     qblora_bf16* Bt = static_cast<qblora_bf16*>(workspace);

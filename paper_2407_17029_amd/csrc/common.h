@@ -47,6 +47,16 @@ inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s);
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? QBLORA_OK : QBLORA_ERR_LAUNCH; }
 
+// Records the caller's registered event pair of slot `which` (qblora_profile_events; none by default) on the
+// stream around the launches made while the object lives.
+struct ProfileScope {
+    int which; hipStream_t st;
+    ProfileScope(int which, hipStream_t st);
+    ~ProfileScope();
+    ProfileScope(const ProfileScope&) = delete;
+    ProfileScope& operator=(const ProfileScope&) = delete;
+};
+
 // ---- kernels' host launchers (defined in the .hip files) -------------------------------------
 
 // `tiled` (may be NULL) receives the second, tile-ordered copy of the codes described in qblora.h

@@ -551,8 +551,13 @@ int launch_grad_pair(const GradDesc& a, const GradDesc& b, hipStream_t st) {
         int rc = launch_grad(a, st);
         return rc ? rc : launch_grad(b, st);
     }
-    int rc = launch_tr(a, &b, st);
+    int rc;
+    {
+        ProfileScope ev(QBLORA_PROFILE_ADAPTER_GRADS, st);
+        rc = launch_tr(a, &b, st);
+    }
     if (rc) return rc;
+    ProfileScope ev(QBLORA_PROFILE_GRAD_REDUCE, st);
     if (!reduce_by_tiles(a) && reduce_by_tiles(b)) {         // the usual case (dA plain, dB transposed): one launch
         GradPair p{};
         p.a = a; p.b = b; p.n_a = (int)reduce_blocks(a);
