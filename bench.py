@@ -128,12 +128,21 @@ class Stack:
             st["merged"] = qb.qablora_merge_quantize(st["qw"], qb.qblora_tile_product(st["ad"], p.d_in, p.d_out, st["H"], self.ws),
                                                      lam, lam, wl.s, qb.MERGE_REQUANT_MINMAX, out=st["merged"])
 
-    def layer_pass(self, st):
+    def layer_pass(self, st, before_phase=None):
+        """quantize -> forward -> backward of one projection; `before_phase(name)` (benchmark hook) runs in front of each."""
         qb, wl, p = self.qb, self.wl, st["p"]
+        if before_phase:
+            before_phase("quantize")
         qb.qblora_quantize_blockwise(st["W"], wl.block, qb.QUANT_ABSMAX_CODEBOOK, self.cb, self.scale_mode, out=st["qw"])
+        if before_phase:
+            before_phase("fwd")
         qb.qblora_linear_fwd(st["qw"], st["ad"], self.X[p.d_in], self.Y[p.d_out], self.ws, saved=self.saved)
+        if before_phase:
+            before_phase("bwd")
         qb.qblora_linear_bwd(st["qw"], st["ad"], self.X[p.d_in], self.dY[p.d_out], True, True, self.dX[p.d_in],
                              st["dA"], st["dB"], self.ws, saved=self.saved)
+        if before_phase:
+            before_phase("done")
 
     def merge_batch(self):
         qb, wl = self.qb, self.wl
@@ -198,10 +207,15 @@ def measure(S, steps, warmup, side_steps, plain_events=False, calibration_copy=F
     torch.cuda.synchronize()
 
     new_event = (lambda: torch.cuda.Event(enable_timing=True)) if plain_events else qb.TimingEvent
-    slots = {"fwd_gemm": qb.PROFILE_FWD_GEMM, "bwd_gemm": qb.PROFILE_BWD_GEMM, "quantize": qb.PROFILE_QUANTIZE,
-             "adapter_fwd": qb.PROFILE_ADAPTER_FWD, "adapter_bwd": qb.PROFILE_ADAPTER_BWD,
-             "adapter_grads": qb.PROFILE_ADAPTER_GRADS, "grad_reduce": qb.PROFILE_GRAD_REDUCE,
-             "prep": qb.PROFILE_PREP, "tile_product": qb.PROFILE_TILE_PRODUCT, "merge": qb.PROFILE_MERGE}
+    # bench key -> (library slot, phase of the layer pass in which the pair is registered)
+    slots = {"fwd_gemm": (qb.PROFILE_FWD_GEMM, "fwd"), "bwd_gemm": (qb.PROFILE_BWD_GEMM, "bwd"),
+             "quantize": (qb.PROFILE_QUANTIZE, "quantize"),
+             "adapter_fwd": (qb.PROFILE_ADAPTER_FWD, "fwd"), "adapter_bwd": (qb.PROFILE_ADAPTER_BWD, "bwd"),
+             "adapter_grads": (qb.PROFILE_ADAPTER_GRADS, "bwd"), "grad_reduce": (qb.PROFILE_GRAD_REDUCE, "bwd"),
+             "prep": (qb.PROFILE_PREP, "fwd"), "dequant_fwd": (qb.PROFILE_DEQUANT, "fwd"),
+             "dequant_bwd": (qb.PROFILE_DEQUANT, "bwd"), "tile_product": (qb.PROFILE_TILE_PRODUCT, "merge"),
+             "merge": (qb.PROFILE_MERGE, "merge")}
+    dense = T >= qb.qblora_dense_min_tokens()           # the calls dequantize once, then contract the bf16 weight
     events = {k: [(new_event(), new_event()) for _ in range(steps if k == "fwd_gemm" else side_steps)] for k in slots}
     marks = [new_event() for _ in range(steps + 1)]
     for pairs in events.values():
@@ -216,15 +230,19 @@ def measure(S, steps, warmup, side_steps, plain_events=False, calibration_copy=F
 
     def bracketed_step(i, which):
         """One step with the event pairs of `which` registered around projection `big`'s calls only."""
+        def hook(phase):
+            for k in which:
+                slot, ph = slots[k]
+                if ph == "merge":
+                    continue
+                qb.qblora_profile_events(slot, None, None)
+            for k in which:
+                slot, ph = slots[k]
+                if ph == phase:
+                    qb.qblora_profile_events(slot, *events[k][i])
+
         for j, st in enumerate(S.proj):
-            if j == big:
-                for k in which:
-                    if k not in ("merge", "tile_product"):
-                        qb.qblora_profile_events(slots[k], *events[k][i])
-            S.layer_pass(st)
-            if j == big:
-                for k in which:
-                    qb.qblora_profile_events(slots[k], None, None)
+            S.layer_pass(st, hook if j == big else None)
         # the merge batch: one pair around all tile products, one around all merges
         if "merge" in which:
             for st in S.proj:
@@ -259,6 +277,9 @@ def measure(S, steps, warmup, side_steps, plain_events=False, calibration_copy=F
     def gemm_ms(k):
         return max(float(np.mean(raw[k])) - empty_pair_ms, 1e-6)
 
+    if not dense:                                       # no one-off dequantize pass in these calls
+        raw["dequant_fwd"] = raw["dequant_bwd"] = [0.0]
+
     fwd_flops = 2.0 * T * bp.d_in * bp.d_out + 2.0 * T * R * bp.d_out / lam
     bwd_flops = 2.0 * T * bp.d_in * bp.d_out + 2.0 * T * R * bp.d_in / lam
     n_w = bp.d_in * bp.d_out
@@ -276,7 +297,8 @@ def measure(S, steps, warmup, side_steps, plain_events=False, calibration_copy=F
         return d
 
     proj_name = f"{bp.name} [{bp.d_out}x{bp.d_in}]"
-    kname = "k_qlinear<1> (forward dequantize-and-contract)"
+    kname = ("k_qlinear<0> (forward contraction on the weight dequantized once per call)" if dense
+             else "k_qlinear<1> (forward dequantize-and-contract)")
     out = {
         "value": round(value, 2), "unit": "TFLOP/s", "steps": steps, "warmup": warmup,
         "ms_per_step": round(ms_per_step, 4), "step_ms": stats(step_ms),
@@ -295,6 +317,10 @@ def measure(S, steps, warmup, side_steps, plain_events=False, calibration_copy=F
                          "achieved": round(bwd_flops / (gemm_ms("bwd_gemm") * 1e-3) / 1e12, 2), "unit": "TFLOP/s",
                          "frac": round(bwd_flops / (gemm_ms("bwd_gemm") * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)},
             "quantize": hbm("quantize", quant_bytes),
+            "dequantize_once_fwd": (hbm("dequant_fwd", n_w * (0.5 + 4 / 64 + 2), "codes + scales -> bf16 weight in the workspace")
+                                    if dense else None),
+            "dequantize_once_bwd": (hbm("dequant_bwd", n_w * (0.5 + 4 / 64 + 2), "the same, transposed, for the backward contraction")
+                                    if dense else None),
             "adapter_fwd_skinny": hbm("adapter_fwd", 2.0 * T * bp.d_in + 2.0 * T * R * 2, "s*U = (s/lambda) X A_x^T; reads X once"),
             "adapter_bwd_skinny": hbm("adapter_bwd", 2.0 * T * bp.d_out + 2.0 * T * R * 3, "dU = s dY B_x^T; reads dY once"),
             "adapter_grads": hbm("adapter_grads", 2.0 * T * (bp.d_in + bp.d_out) + 8.0 * T * R,
@@ -310,7 +336,14 @@ def measure(S, steps, warmup, side_steps, plain_events=False, calibration_copy=F
         key = {"adapter_fwd": "adapter_fwd_skinny", "adapter_bwd": "adapter_bwd_skinny", "merge": "merge_requant_batch"}.get(k, k)
         out["kernels"][key]["traffic"] = t
     adapter_ms = sum(float(np.mean(raw[k])) for k in ("adapter_fwd", "adapter_bwd", "adapter_grads", "grad_reduce", "prep"))
-    proj_ms = adapter_ms + gemm_ms("fwd_gemm") + gemm_ms("bwd_gemm") + float(np.mean(raw["quantize"]))
+    dq_ms = float(np.mean(raw["dequant_fwd"])) + float(np.mean(raw["dequant_bwd"]))
+    proj_ms = adapter_ms + gemm_ms("fwd_gemm") + gemm_ms("bwd_gemm") + float(np.mean(raw["quantize"])) + dq_ms
+    # the contraction with its share of the one-off dequantize pass, as one figure per direction
+    for key, gk, dk, fl in (("fwd_gemm_with_dequantize", "fwd_gemm", "dequant_fwd", fwd_flops),
+                            ("bwd_gemm_with_dequantize", "bwd_gemm", "dequant_bwd", bwd_flops)):
+        ms = gemm_ms(gk) + float(np.mean(raw[dk]))
+        out["kernels"][key] = {"ms": round(ms, 4), "achieved": round(fl / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s",
+                               "frac": round(fl / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
     out["kernels"]["adapter_side_share_of_projection"] = round(adapter_ms / proj_ms, 4)
     return out
 
@@ -362,6 +395,214 @@ def cpu_baseline(S, sample_rows):
                       f"shape to the full step: {est_full:.0f} s"}
 
 
+
+# ---- side measurements: streaming kernels on the large layer shapes, and the rows next to the hot path -------
+# Each entry: 10 warm-up launches, then 50 back-to-back launches between two HIP events on the current stream;
+# `us` is with warm caches (the 256 MB last-level cache holds the operands of the smaller shapes between
+# launches), `cold_us` rotates the launches over enough operand sets to exceed that cache, so that every launch
+# reads from HBM.  The short kernels are launched through the C ABI with arguments marshalled once, so that the
+# host keeps ahead of the GPU.
+SHAPES = [(4096, 4096), (11008, 4096), (22016, 8192)]          # 7B attention, 7B MLP up, 65B MLP up
+DEV = "cuda:0"
+
+
+def timed(fn, iters=50, warm=10):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(iters):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / iters * 1e-3                      # seconds per launch
+
+
+def timed_rotating(fns, iters=50, warm=10):
+    """Like timed(), the launches cycling through `fns` (one per operand set)."""
+    n = len(fns)
+    for i in range(warm):
+        fns[i % n]()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for i in range(iters):
+        fns[i % n]()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / iters * 1e-3
+
+
+def n_sets(bytes_per_set, cache_bytes=256 * 2**20):
+    """Operand sets needed so that a set has left the last-level cache when its turn comes again."""
+    return max(2, int(np.ceil(2 * cache_bytes / max(bytes_per_set, 1))) + 1)
+
+
+_SIDE = []
+
+
+def emit(**kw):
+    _SIDE.append(kw)
+
+
+def bench_quantize():
+    cb = synth.codebook_nf4_style()
+    for d_out, d_in in SHAPES:
+        W = torch.randn(d_out, d_in, device=DEV) * 0.02
+        qw = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_ABSMAX_CODEBOOK, cb, tiled=False)
+        q, cbp = qw.c_struct(), np.ascontiguousarray(cb, np.float32)
+        args = (qb._ptr(W), d_out, d_in, 64, qb.QUANT_ABSMAX_CODEBOOK, cbp.ctypes.data_as(C.c_void_p), qb.SCALES_FP32,
+                C.byref(q), qb._stream())
+        s = timed(lambda: qb.lib().qblora_quantize_blockwise(*args))
+        nbytes = d_out * d_in * (4 + 0.5 + 4 / 64)
+        # cold: every launch reads another copy of W
+        Ws = [W] + [W.clone() for _ in range(n_sets(4 * d_out * d_in) - 1)]
+        fns = []
+        for Wi in Ws:
+            ai = (qb._ptr(Wi),) + args[1:]
+            fns.append(lambda ai=ai: qb.lib().qblora_quantize_blockwise(*ai))
+        sc = timed_rotating(fns)
+        emit(kernel="quantize_codebook", shape=[d_out, d_in], us=round(s * 1e6, 1), GBps=round(nbytes / s / 1e9, 1),
+             frac_hbm=round(nbytes / s / 1e9 / HBM_PEAK_GBS, 3), cold_us=round(sc * 1e6, 1), cold_sets=len(Ws),
+             cold_frac_hbm=round(nbytes / sc / 1e9 / HBM_PEAK_GBS, 3))
+        del W, qw, Ws, fns
+
+
+def bench_merge():
+    cb = synth.codebook_nf4_style()
+    for d_out, d_in in SHAPES:
+        for lam in (2, 8):
+            W = torch.randn(d_out, d_in, device=DEV) * 0.02
+            qw = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_ABSMAX_CODEBOOK, cb, tiled=False)
+            H = torch.randn(d_in // lam, d_out // lam, device=DEV) * 0.01
+            out = qb.qablora_merge_quantize(qw, H, lam, lam, 1.0, qb.MERGE_REQUANT_MINMAX)
+            b, o = qw.c_struct(), out.c_struct()
+            args = (C.byref(b), qb._ptr(H), lam, lam, C.c_float(1.0), qb.MERGE_REQUANT_MINMAX, C.byref(o), qb._stream())
+            s = timed(lambda: qb.lib().qablora_merge_quantize(*args))
+            nbytes = d_out * d_in * (0.5 + 4 / 64 + 4.0 / (lam * lam) + 0.5 + 8 / 64)
+            # cold: every launch works on another copy of the weight, of H and of the output
+            keep, fns = [], []
+            for _ in range(n_sets(nbytes) - 1):
+                qi = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_ABSMAX_CODEBOOK, cb, tiled=False)
+                Hi = H.clone()
+                oi = qb.qablora_merge_quantize(qi, Hi, lam, lam, 1.0, qb.MERGE_REQUANT_MINMAX)
+                bi, ooi = qi.c_struct(), oi.c_struct()
+                ai = (C.byref(bi), qb._ptr(Hi), lam, lam, C.c_float(1.0), qb.MERGE_REQUANT_MINMAX, C.byref(ooi), qb._stream())
+                keep.append((qi, Hi, oi, bi, ooi))
+                fns.append(lambda ai=ai: qb.lib().qablora_merge_quantize(*ai))
+            fns.append(lambda: qb.lib().qablora_merge_quantize(*args))
+            sc = timed_rotating(fns)
+            emit(kernel="merge_requant", shape=[d_out, d_in], lam=lam, us=round(s * 1e6, 1),
+                 GBps=round(nbytes / s / 1e9, 1), frac_hbm=round(nbytes / s / 1e9 / HBM_PEAK_GBS, 3),
+                 cold_us=round(sc * 1e6, 1), cold_sets=len(fns), cold_frac_hbm=round(nbytes / sc / 1e9 / HBM_PEAK_GBS, 3))
+            del W, qw, H, out, keep, fns
+
+
+def bench_decode():
+    for d_out, d_in in SHAPES:
+        W = torch.randn(d_out, d_in, device=DEV) * 0.02
+        qw = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_MINMAX_INT4, tiled=False)
+        pack = qb.qblora_decode_pack(qw)
+        qp = qw.c_struct()
+        sp = timed(lambda: qb.lib().qblora_decode_pack(C.byref(qp), qb._ptr(pack), qb._stream()), iters=10, warm=2)
+        emit(kernel="decode_pack (one-off)", shape=[d_out, d_in], us=round(sp * 1e6, 1))
+        for T in (1, 4, 16):
+            X = torch.randn(T, d_in, device=DEV).to(torch.bfloat16)
+            Y = torch.empty(T, d_out, dtype=torch.bfloat16, device=DEV)
+            q = qw.c_struct()
+            for name, pk in (("packed", pack), ("row-major", None)):
+                args = (C.byref(q), qb._ptr(pk), qb._ptr(X), T, qb._ptr(Y), None, 0, qb._stream())
+                s = timed(lambda: qb.lib().qblora_linear_decode(*args), iters=50)
+                nbytes = d_out * d_in * (0.5 + 8 / 64) + 2 * T * (d_in + d_out)
+                emit(kernel="w4_decode", layout=name, shape=[d_out, d_in], T=T, us=round(s * 1e6, 1),
+                     GBps=round(nbytes / s / 1e9, 1), frac_hbm=round(nbytes / s / 1e9 / HBM_PEAK_GBS, 3))
+        del W, qw, pack
+
+
+def bench_qablora():
+    cb = synth.codebook_nf4_style()
+    T, d_out, d_in = 8192, 4096, 4096
+    W = torch.randn(d_out, d_in, device=DEV) * 0.02
+    qw = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_ABSMAX_CODEBOOK, cb)
+    X = torch.randn(T, d_in, device=DEV).to(torch.bfloat16)
+    dY = torch.randn(T, d_out, device=DEV).to(torch.bfloat16)
+    Y = torch.empty_like(dY)
+    dX = torch.empty_like(X)
+    for l1, l2 in ((8, 8), (4, 8), (2, 2)):
+        H = (torch.randn(d_in // l1, d_out // l2, device=DEV) * 0.02).to(torch.bfloat16)
+        dH = torch.empty(d_in // l1, d_out // l2, device=DEV)
+        f = timed(lambda: qb.qablora_linear_fwd(qw, H, l1, l2, 1.0, X, Y), iters=10)
+        b = timed(lambda: qb.qablora_linear_bwd(qw, H, l1, l2, 1.0, X, dY, True, True, dX, dH), iters=10)
+        flops = 4.0 * T * d_in * d_out + 6.0 * T * (d_in // l1) * (d_out // l2)
+        emit(kernel="qablora_fwd+bwd", shape=[d_out, d_in], T=T, lam=[l1, l2], fwd_us=round(f * 1e6, 1),
+             bwd_us=round(b * 1e6, 1), TFLOPs=round(flops / (f + b) / 1e12, 1),
+             frac_mfma=round(flops / (f + b) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 3))
+
+
+def bench_tile8():
+    """The quantization-aware loop on 8 x 8 quantization blocks (block 64 with lambda1 = lambda2 = 8): min-max INT4
+    quantizer, single-matrix forward / backward, the exact offset-shift merge, small-batch inference."""
+    T, d_out, d_in, l1, l2 = 8192, 4096, 4096, 8, 8
+    W = torch.randn(d_out, d_in, device=DEV) * 0.02
+    qw = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_MINMAX_INT4, block_rows=8, tiled=True)
+    q = qw.c_struct()
+    args = (qb._ptr(W), d_out, d_in, 64, qb.QUANT_MINMAX_INT4, None, qb.SCALES_FP32, C.byref(q), qb._stream())
+    s = timed(lambda: qb.lib().qblora_quantize_blockwise(*args))
+    nbytes = d_out * d_in * (4 + 0.5 + 8 / 64)
+    emit(kernel="quantize_minmax 8x8 blocks (+ tile-ordered code copy)", shape=[d_out, d_in], us=round(s * 1e6, 1),
+         GBps=round(nbytes / s / 1e9, 1), frac_hbm=round(nbytes / s / 1e9 / HBM_PEAK_GBS, 3))
+    X = torch.randn(T, d_in, device=DEV).to(torch.bfloat16)
+    dY = torch.randn(T, d_out, device=DEV).to(torch.bfloat16)
+    Y = torch.empty_like(dY)
+    dX = torch.empty_like(X)
+    H = (torch.randn(d_in // l1, d_out // l2, device=DEV) * 0.02).to(torch.bfloat16)
+    dH = torch.empty(d_in // l1, d_out // l2, device=DEV)
+    f = timed(lambda: qb.qablora_linear_fwd(qw, H, l1, l2, 1.0, X, Y), iters=10)
+    b = timed(lambda: qb.qablora_linear_bwd(qw, H, l1, l2, 1.0, X, dY, True, True, dX, dH), iters=10)
+    flops = 4.0 * T * d_in * d_out + 6.0 * T * (d_in // l1) * (d_out // l2)
+    emit(kernel="qablora_fwd+bwd 8x8 blocks", shape=[d_out, d_in], T=T, lam=[l1, l2], fwd_us=round(f * 1e6, 1),
+         bwd_us=round(b * 1e6, 1), TFLOPs=round(flops / (f + b) / 1e12, 1),
+         frac_mfma=round(flops / (f + b) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 3))
+    Hf = H.float().contiguous()
+    merged = qb.qablora_merge_quantize(qw, Hf, l1, l2, 1.0, qb.MERGE_BETA_SHIFT)
+    bq, o = qw.c_struct(), merged.c_struct()
+    margs = (C.byref(bq), qb._ptr(Hf), l1, l2, C.c_float(1.0), qb.MERGE_BETA_SHIFT, C.byref(o), qb._stream())
+    s = timed(lambda: qb.lib().qablora_merge_quantize(*margs))
+    nb = d_out * d_in // 64
+    nbytes = d_out * d_in * 0.5 * 2 + nb * 4 * 4 + Hf.numel() * 4           # codes and alpha copied, beta shifted
+    emit(kernel="merge_beta_shift 8x8 blocks (codes + alpha copied)", shape=[d_out, d_in], us=round(s * 1e6, 1),
+         GBps=round(nbytes / s / 1e9, 1), frac_hbm=round(nbytes / s / 1e9 / HBM_PEAK_GBS, 3))
+    for d_out2, d_in2 in ((4096, 4096), (22016, 8192)):
+        W2 = torch.randn(d_out2, d_in2, device=DEV) * 0.02
+        q2 = qb.qblora_quantize_blockwise(W2, 64, qb.QUANT_MINMAX_INT4, block_rows=8, tiled=False)
+        pack = qb.qblora_decode_pack(q2)
+        for Tn in (1, 16):
+            Xs = torch.randn(Tn, d_in2, device=DEV).to(torch.bfloat16)
+            Ys = torch.empty(Tn, d_out2, dtype=torch.bfloat16, device=DEV)
+            qs = q2.c_struct()
+            dargs = (C.byref(qs), qb._ptr(pack), qb._ptr(Xs), Tn, qb._ptr(Ys), None, 0, qb._stream())
+            s = timed(lambda: qb.lib().qblora_linear_decode(*dargs), iters=50)
+            nbytes = d_out2 * d_in2 * (0.5 + 8 / 64) + 2 * Tn * (d_in2 + d_out2)
+            emit(kernel="w4_decode 8x8 blocks", layout="packed", shape=[d_out2, d_in2], T=Tn, us=round(s * 1e6, 1),
+                 GBps=round(nbytes / s / 1e9, 1), frac_hbm=round(nbytes / s / 1e9 / HBM_PEAK_GBS, 3))
+        del W2, q2, pack
+
+
+def side_measurements(which):
+    import ctypes, numpy, torch
+    from paper_2407_17029_amd import binding, synth as synth_mod
+    g = globals()
+    g.update(C=ctypes, np=numpy, torch=torch, qb=binding, synth=synth_mod)
+    del _SIDE[:]
+    table = {"quantize": bench_quantize, "merge": bench_merge, "decode": bench_decode, "qablora": bench_qablora,
+             "tile8": bench_tile8}
+    for w in which:
+        table[w]()
+        torch.cuda.empty_cache()
+    return list(_SIDE)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -372,6 +613,9 @@ def main() -> int:
     ap.add_argument("--cpu-sample-rows", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the other workloads (the `configs` object)")
+    ap.add_argument("--side", default="quantize,merge,decode,qablora,tile8",
+                    help="comma-separated side measurements reported under `side` (streaming kernels on the large shapes, "
+                         "small-batch inference, single-matrix adapter, 8 x 8 blocks); empty string = none")
     ap.add_argument("--plain-events", action="store_true",
                     help="time the kernels with ordinary HIP events (system-scope fence at every record)")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -440,6 +684,9 @@ def main() -> int:
             torch.cuda.empty_cache()
             cfg[name] = entry
         out["configs"] = cfg
+    side = [w for w in args.side.split(",") if w]
+    if side:
+        out["side"] = side_measurements(side)
     print(json.dumps(out))
     return 0
 

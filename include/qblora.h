@@ -178,6 +178,18 @@ int qblora_prepack_codes(const qblora_qweight* qw, void* stream);
  */
 int qblora_dequantize_bf16(const qblora_qweight* qw, qblora_bf16* Wt, void* stream);
 
+/*
+ * How qblora_linear_fwd / _bwd build the 16-bit compute weight of Eq. 1 (Alg. 1: W_tilde = dequantize(...), then
+ * x @ W_tilde).  Below qblora_dense_min_tokens() tokens every 256-token tile of the contraction kernel rebuilds
+ * the weight tiles it needs from codes and scales in LDS; from that many tokens on, the call first dequantizes
+ * the whole weight once into a bf16 buffer inside its workspace (d_out*d_in*2 bytes; transposed for the
+ * backward) and the contraction kernel copies weight tiles from there, because rebuilding a tile for each of
+ * T/256 token tiles costs more than one sweep over the weight.  The values are the same bf16 numbers either
+ * way (qblora_dequantize_bf16's), and so are the results bit for bit.  The buffer is scratch: nothing is kept
+ * between calls, and the *_workspace_bytes() queries include it.
+ */
+int64_t qblora_dense_min_tokens(void);
+
 /* Bytes of workspace the forward / backward calls need for T tokens (0 is possible). */
 size_t qblora_linear_fwd_workspace_bytes(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T);
 size_t qblora_linear_bwd_workspace_bytes(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T);
@@ -231,9 +243,10 @@ int qblora_linear_bwd_saved(const qblora_qweight* qw, const qblora_adapter* ad, 
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks and results (bit
  * for bit) as qblora_linear_fwd, but the scratch is an array of QBLORA_NOALLOC_SCRATCH_BYTES bytes inside the
  * library's device image (each GPU the library runs on holds it until the process ends) instead of a caller
- * workspace; the call allocates nothing.  A problem whose qblora_linear_fwd_workspace_bytes() exceeds
- * qblora_noalloc_scratch_bytes() is rejected with QBLORA_ERR_WORKSPACE and nothing is enqueued (the LLaMA-7B
- * attention projection at T = 8192, rank 64 needs 4.5 MiB).  All calls on one GPU share that GPU's array:
+ * workspace; the call allocates nothing.  It always takes the form that rebuilds weight tiles in LDS (whose
+ * scratch is the adapter operands, s*U and the re-ordered block scales: 4.5 MiB for the LLaMA-7B attention
+ * projection at T = 8192, rank 64); a problem whose scratch in that form exceeds qblora_noalloc_scratch_bytes()
+ * is rejected with QBLORA_ERR_WORKSPACE and nothing is enqueued.  All calls on one GPU share that GPU's array:
  * calls that overlap on one GPU (two streams, two host threads) race; calls on one stream do not.  The first
  * call on a device looks the array's address up (hipGetSymbolAddress); make it outside graph capture.
  */
@@ -356,6 +369,7 @@ int qblora_decode_pack(const qblora_qweight* qw, void* pack, void* stream);
  *   QBLORA_PROFILE_GRAD_REDUCE    the fixed-order reduction of those partial sums into dA and dB
  *   QBLORA_PROFILE_PREP           the per-call re-layout launch of the forward (adapter operands, block scales)
  *   QBLORA_PROFILE_TILE_PRODUCT   the kernel of qblora_tile_product
+ *   QBLORA_PROFILE_DEQUANT        the one-off dequantize pass of a forward / backward call on many tokens
  * Passing NULL for both events unregisters the slot.  The registration is per host thread: it applies to
  * calls made by the thread that registered it, so concurrent callers do not see each other's events.  Has
  * no effect on results.
@@ -363,7 +377,7 @@ int qblora_decode_pack(const qblora_qweight* qw, void* pack, void* stream);
 enum { QBLORA_PROFILE_FWD_GEMM = 0, QBLORA_PROFILE_BWD_GEMM = 1, QBLORA_PROFILE_MERGE = 2,
        QBLORA_PROFILE_QUANTIZE = 3, QBLORA_PROFILE_ADAPTER_FWD = 4, QBLORA_PROFILE_ADAPTER_BWD = 5,
        QBLORA_PROFILE_ADAPTER_GRADS = 6, QBLORA_PROFILE_GRAD_REDUCE = 7, QBLORA_PROFILE_PREP = 8,
-       QBLORA_PROFILE_TILE_PRODUCT = 9, QBLORA_PROFILE_SLOTS = 10 };
+       QBLORA_PROFILE_TILE_PRODUCT = 9, QBLORA_PROFILE_DEQUANT = 10, QBLORA_PROFILE_SLOTS = 11 };
 int qblora_profile_events(int32_t which, void* start_event, void* stop_event);
 
 /* Static description of an error code. */

@@ -31,11 +31,11 @@ EXPORTS = ["qblora_quantize_blockwise", "qblora_dequantize_bf16", "qblora_linear
            "qablora_linear_bwd", "qblora_merge_bf16",
            "qblora_linear_decode_workspace_bytes", "qblora_linear_decode",
            "qblora_decode_pack_bytes", "qblora_decode_pack",
-           "qblora_noalloc_scratch_bytes", "qblora_linear_fwd_noalloc"]
+           "qblora_noalloc_scratch_bytes", "qblora_linear_fwd_noalloc", "qblora_dense_min_tokens"]
 
 PROFILE_FWD_GEMM, PROFILE_BWD_GEMM, PROFILE_MERGE, PROFILE_QUANTIZE = 0, 1, 2, 3
 PROFILE_ADAPTER_FWD, PROFILE_ADAPTER_BWD, PROFILE_ADAPTER_GRADS, PROFILE_GRAD_REDUCE = 4, 5, 6, 7
-PROFILE_PREP, PROFILE_TILE_PRODUCT = 8, 9
+PROFILE_PREP, PROFILE_TILE_PRODUCT, PROFILE_DEQUANT = 8, 9, 10
 
 
 class CQWeight(C.Structure):
@@ -111,6 +111,8 @@ def lib():
                                              C.c_void_p, C.c_size_t, C.c_void_p]
         L.qblora_linear_bwd_saved.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
                                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.qblora_dense_min_tokens.restype = C.c_int64
+        L.qblora_dense_min_tokens.argtypes = []
         L.qblora_noalloc_scratch_bytes.restype = C.c_size_t
         L.qblora_noalloc_scratch_bytes.argtypes = []
         L.qblora_linear_fwd_noalloc.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
@@ -354,6 +356,10 @@ def qblora_linear_fwd(qw: QWeight, ad, X: torch.Tensor, Y: torch.Tensor = None, 
                                           _stream())
         _check(rc, "qblora_linear_fwd_save")
     return Y
+
+
+def qblora_dense_min_tokens() -> int:
+    return int(lib().qblora_dense_min_tokens())
 
 
 def qblora_noalloc_scratch_bytes() -> int:

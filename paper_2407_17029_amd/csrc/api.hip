@@ -89,14 +89,29 @@ Codebook codebook_of(const qblora_qweight* qw) {
 
 int64_t n_blocks(const qblora_qweight* qw) { return (int64_t)qw->d_out * (qw->d_in / qw->block); }
 
+// From this many tokens on, a call dequantizes the weight ONCE into a bf16 buffer in its workspace and contracts
+// that (direct copies of both operand tiles); below it, every 256-token tile rebuilds its weight tiles in LDS.
+// Rebuilding costs about a quarter of the contraction kernel's time for every token tile; the one-off pass
+// costs one sweep over the weight (0.56 B read + 2 B written per element), which 2048 tokens amortize.
+constexpr int64_t kDenseMinTokens = 2048;
+// (the contraction kernel addresses the dequantized weight with 32-bit byte offsets)
+bool use_dense(const qblora_qweight* qw, int64_t T) {
+    return T >= kDenseMinTokens && (int64_t)qw->d_out * qw->d_in * 2 < ((int64_t)1 << 32);
+}
+
 struct FwdSpace {
-    float* scales; qblora_bf16 *At_x, *Bt, *U;
+    float* scales; qblora_bf16 *At_x, *Bt, *U, *W16;
     size_t bytes;
 };
-FwdSpace carve_fwd(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T, void* ws) {
+FwdSpace carve_fwd(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T, void* ws, bool dense) {
     Carver c(ws);
     FwdSpace s{};
-    s.scales = c.take<float>((size_t)((qw->d_out + 255) / 256) * 256 * (qw->d_in / qw->block));   // tile-ordered
+    if (dense) {
+        s.W16 = c.take<qblora_bf16>((size_t)qw->d_out * qw->d_in);
+        if (qw->scale_mode == QBLORA_SCALES_E4M3_GROUPED) s.scales = c.take<float>(n_blocks(qw));   // reconstructed
+    } else {
+        s.scales = c.take<float>((size_t)((qw->d_out + 255) / 256) * 256 * (qw->d_in / qw->block));   // tile-ordered
+    }
     if (has_adapter(ad)) {
         s.At_x = c.take<qblora_bf16>((size_t)ad->R * qw->d_in);
         // the alternative scale operators use a full [d_out, R] expansion (zero rows included)
@@ -109,14 +124,15 @@ FwdSpace carve_fwd(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T
 }
 
 struct BwdSpace {
-    float* scales; qblora_bf16 *At_x, *Bx, *U, *U_lo, *dU, *dU_lo, *dUs, *A_op, *Xs, *dYs; float *part, *part_b;
+    float* scales; qblora_bf16 *At_x, *Bx, *U, *U_lo, *dU, *dU_lo, *dUs, *A_op, *Xs, *dYs, *W16t; float *part, *part_b;
     int splits_a, splits_b;
     size_t bytes;
 };
-BwdSpace carve_bwd(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T, void* ws) {
+BwdSpace carve_bwd(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T, void* ws, bool dense) {
     Carver c(ws);
     BwdSpace s{};
     if (qw->scale_mode == QBLORA_SCALES_E4M3_GROUPED) s.scales = c.take<float>(n_blocks(qw));
+    if (dense) s.W16t = c.take<qblora_bf16>((size_t)qw->d_out * qw->d_in);
     if (has_adapter(ad)) {
         s.At_x = c.take<qblora_bf16>((size_t)ad->R * qw->d_in);
         s.Bx = c.take<qblora_bf16>((size_t)ad->R * qw->d_out);
@@ -267,13 +283,15 @@ int qblora_dequantize_bf16(const qblora_qweight* qw, qblora_bf16* Wt, void* stre
 
 size_t qblora_linear_fwd_workspace_bytes(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T) {
     if (check_layer(qw, ad) || T < 0) return 0;
-    return carve_fwd(qw, ad, T, nullptr).bytes;
+    return carve_fwd(qw, ad, T, nullptr, use_dense(qw, T)).bytes;
 }
 
 size_t qblora_linear_bwd_workspace_bytes(const qblora_qweight* qw, const qblora_adapter* ad, int64_t T) {
     if (check_layer(qw, ad) || T < 0) return 0;
-    return carve_bwd(qw, ad, T, nullptr).bytes;
+    return carve_bwd(qw, ad, T, nullptr, use_dense(qw, T)).bytes;
 }
+
+int64_t qblora_dense_min_tokens(void) { return kDenseMinTokens; }
 
 size_t qblora_saved_bytes(const qblora_adapter* ad, int64_t T) {
     if (!has_adapter(ad) || T <= 0) return 0;
@@ -283,19 +301,21 @@ size_t qblora_saved_bytes(const qblora_adapter* ad, int64_t T) {
 namespace {
 
 int linear_fwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qblora_bf16* X, int64_t T,
-                    qblora_bf16* Y, qblora_bf16* saved, void* workspace, size_t workspace_bytes, void* stream) {
+                    qblora_bf16* Y, qblora_bf16* saved, void* workspace, size_t workspace_bytes, void* stream,
+                    bool allow_dense = true) {
     int rc = check_layer(qw, ad);
     if (rc) return rc;
     if (T < 0) return QBLORA_ERR_SHAPE;
     if (T == 0) return QBLORA_OK;
     if (!X || !Y) return QBLORA_ERR_NULL;
-    FwdSpace ws = carve_fwd(qw, ad, T, workspace);
+    const bool dense = allow_dense && use_dense(qw, T);
+    FwdSpace ws = carve_fwd(qw, ad, T, workspace, dense);
     if (ws.bytes > 0 && (!workspace || workspace_bytes < ws.bytes)) return QBLORA_ERR_WORKSPACE;
     hipStream_t st = as_stream(stream);
     const bool adapted = has_adapter(ad);
 
     GemmDesc g{};
-    g.qmode = 1;
+    g.qmode = dense ? 3 : 1;
     // one launch re-orders the block scales for the forward kernel (reconstructing grouped ones) and,
     // with an adapter, builds its K-contiguous operands
     ScaleTiling sct{};
@@ -306,6 +326,18 @@ int linear_fwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
     g.scales = nullptr; g.scales_tiled = ws.scales;
     g.block_rows = block_rows_of(qw);
     if (g.block_rows == 8) { sct.out = nullptr; g.scales = qw->scales; g.scales_tiled = nullptr; }   // read in place
+    if (dense) {
+        // the weight once, as the bf16 compute weight of Eq. 1, for all token tiles of this call
+        sct.out = nullptr;
+        const float* plain = nullptr;
+        if ((rc = resolve_scales(qw, ws.scales, st, &plain))) return rc;
+        {
+            ScopedEvents ev(QBLORA_PROFILE_DEQUANT, st);
+            rc = launch_dequantize_operand(*qw, plain, 0, ws.W16, st);
+        }
+        if (rc) return rc;
+        g.W1 = ws.W16; g.K1 = qw->d_in;
+    }
     const int op = scale_op_of(ad);
     const bool prep_adapter = adapted && op == QBLORA_OP_AVGPOOL_REPEAT;
     // lambda1 = 2: A^T stays unexpanded and the narrow GEMM uses each of its columns for two adjacent k
@@ -315,7 +347,7 @@ int linear_fwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
         rc = launch_adapter_prep(prep_adapter ? ad->A : nullptr, prep_adapter ? ad->B : nullptr,
                                  dup_a ? qw->d_in / 2 : qw->d_in, qw->d_out,
                                  adapted ? ad->R : 0, adapted ? (dup_a ? 1 : ad->lambda1) : 1, adapted ? ad->lambda2 : 1,
-                                 ws.At_x, ws.Bt, nullptr, st, &sct);
+                                 ws.At_x, ws.Bt, nullptr, st, sct.out ? &sct : nullptr);
     }
     if (rc) return rc;
     if (adapted && op != QBLORA_OP_AVGPOOL_REPEAT) {
@@ -374,13 +406,23 @@ int linear_bwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
         return QBLORA_OK;
     }
     if (!dY || (adapted && !X)) return QBLORA_ERR_NULL;
-    BwdSpace ws = carve_bwd(qw, ad, T, workspace);
+    const bool dense = use_dense(qw, T) && dX;
+    BwdSpace ws = carve_bwd(qw, ad, T, workspace, use_dense(qw, T));
     if (ws.bytes > 0 && (!workspace || workspace_bytes < ws.bytes)) return QBLORA_ERR_WORKSPACE;
 
     GemmDesc g{};
-    g.qmode = 2;
+    g.qmode = dense ? 3 : 2;
     g.block_rows = block_rows_of(qw);
     if (dX && (rc = resolve_scales(qw, ws.scales, st, &g.scales))) return rc;
+    if (dense) {
+        // the transposed bf16 compute weight once, for all token tiles of this call
+        {
+            ScopedEvents ev(QBLORA_PROFILE_DEQUANT, st);
+            rc = launch_dequantize_operand(*qw, g.scales, 1, ws.W16t, st);
+        }
+        if (rc) return rc;
+        g.W1 = ws.W16t; g.K1 = qw->d_out;
+    }
     if (adapted) {
         const int R = ad->R;
         const int op = scale_op_of(ad);
@@ -529,12 +571,13 @@ int qblora_linear_fwd_noalloc(const qblora_qweight* qw, const qblora_adapter* ad
     if (T < 0) return QBLORA_ERR_SHAPE;
     if (T == 0) return QBLORA_OK;
     if (!X || !Y) return QBLORA_ERR_NULL;
-    if (carve_fwd(qw, ad, T, nullptr).bytes > kStaticScratchBytes) return QBLORA_ERR_WORKSPACE;
+    // always the form that rebuilds weight tiles in LDS: its scratch does not grow with the weight
+    if (carve_fwd(qw, ad, T, nullptr, false).bytes > kStaticScratchBytes) return QBLORA_ERR_WORKSPACE;
     void* ptr = nullptr;
     if ((rc = static_scratch(&ptr))) return rc;
     // every part of the forward's scratch is written by this call's own kernels before it is read, so
     // nothing has to be cleared between calls
-    return linear_fwd_impl(qw, ad, X, T, Y, nullptr, ptr, kStaticScratchBytes, stream);
+    return linear_fwd_impl(qw, ad, X, T, Y, nullptr, ptr, kStaticScratchBytes, stream, false);
 }
 
 // ---- single-matrix adapter (QA-BLoRA) ------------------------------------------------------------

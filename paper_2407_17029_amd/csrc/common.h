@@ -75,6 +75,12 @@ int launch_scales_double_quantize(const float* scales, int64_t n, int group, uin
 int launch_scales_reconstruct(const uint8_t* scale_codes, const float* step, const float* mid, int64_t n,
                               int group, float* scales, hipStream_t st);
 int launch_dequantize_bf16(const qblora_qweight& qw, const float* scales, qblora_bf16* Wt, hipStream_t st);
+// The bf16 compute weight in the order the contraction kernel's waves load it (qmode 3): for the operand
+// matrix Wop[N, K] -- the weight itself, N = d_out, K = d_in (transposed = 0), or its transpose, N = d_in,
+// K = d_out -- the 16 bytes Wop[32i + (l & 31)][16j + 8(l >> 5) .. + 7] sit at ((i*(K/16) + j)*64 + l)*16.
+// d_out*d_in*2 bytes, 16-byte aligned; d_in % 64 == 0, d_out % 64 == 0.
+int launch_dequantize_operand(const qblora_qweight& qw, const float* scales, int transposed, qblora_bf16* Wop,
+                              hipStream_t st);
 
 // Builds K-contiguous bf16 copies of the adapter matrices for the GEMM kernels:
 //   At_x [R, d_in]        At_x[j,k] = A[k/lam1, j]     (transpose, expand along k)
@@ -96,8 +102,10 @@ int launch_adapter_prep(const qblora_bf16* A, const qblora_bf16* B, int d_in, in
 // "token" operands X1/X2 are bf16 row-major; the quantized segment is optional (qmode 0).
 struct GemmDesc {
     int qmode;                 // 0: no quantized segment; 1: forward (N = d_out, K1 = d_in);
-                               // 2: transposed use (N = d_in, K1 = d_out)
+                               // 2: transposed use (N = d_in, K1 = d_out);
+                               // 3: first segment on a bf16 weight dequantized beforehand, in operand order
     const qblora_bf16* X1; int64_t ldx1;
+    const qblora_bf16* W1; int K1;                     // qmode 3 only: see launch_dequantize_operand
     const uint8_t* codes; const float* scales; const float* beta; int d_out, d_in;
     const uint8_t* codes_tiled;            // optional tile-ordered copy (forward only)
     const float* scales_tiled;             // optional tile-ordered scales (forward only)

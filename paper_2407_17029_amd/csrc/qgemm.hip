@@ -301,7 +301,7 @@ int launch_cfg(const GemmDesc& d, hipStream_t st) {
 
 int launch_gemm(const GemmDesc& d, hipStream_t st) {
     if (d.M <= 0 || d.N <= 0) return QBLORA_OK;
-    if (d.qmode == 1 || d.qmode == 2) return launch_qlinear(d, st);
+    if (d.qmode == 1 || d.qmode == 2 || d.qmode == 3) return launch_qlinear(d, st);
     if (skinny_applies(d)) return launch_skinny(d, st);
     // plain bf16 GEMMs of the adapter path that are not narrow (the tile product): 128 x 128 tiles unless
     // 256 x 256 tiles alone give every CU at least two workgroups

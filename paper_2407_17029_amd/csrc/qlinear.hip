@@ -13,7 +13,12 @@
 // and not to the accumulator.  Segment 2 is a plain bf16 K-extension: the adapter's rank-R product
 // rides in the same accumulators as R extra contraction steps (forward: X2 = s*U, W2 = B^T with
 // output row n using row n/lambda2, i.e. repeat_interleave; backward: X2 = dU/lambda1, W2 = A with
-// row k/lambda1).
+// row k/lambda1).  QMODE 0 is the same contraction on a weight that has already been dequantized once (the
+// layer does that when the batch is large, so that a weight is not rebuilt by every token tile) into a bf16
+// buffer in MFMA operand order: the 16 bytes lane l needs for rows 32i..32i+31 and the 16-wide k slice j sit at
+// ((i*(K1/16) + j)*64 + l)*16.  A wave then loads its weight fragments straight from global memory into
+// registers, one step ahead, 1 KB contiguous per instruction, and only the token tile goes through LDS: filling
+// LDS is the slow side of this CU (direct copies 64 B/clk, ds_write_b128 85 B/clk against 200 B/clk reads).
 //
 // Shape of the computation on a CU: one workgroup of 512 threads (8 wave64, two per SIMD) owns a
 // 256 x 256 output tile; a wave owns 128 tokens x 64 features = 8 MFMA accumulators of 32 x 32
@@ -56,6 +61,20 @@ __device__ __forceinline__ void copy16_to_lds(const void* src, uint32_t lds_base
 __device__ __forceinline__ void copy16_to_lds(const void* uniform_base, uint32_t lane_offset, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(lds_base), "v"(lane_offset), "s"(uniform_base) : "memory");
+}
+
+// 16 bytes per lane from uniform_base + lane_offset + IMM into registers.  The data arrive asynchronously: the
+// value may only be used behind a wait_vm that names it (vmcnt counts every copy and load of this kernel's
+// loop, which are all issued by statements like these, in program order).
+template <int IMM>
+__device__ __forceinline__ void load_operand16(bf16x8& v, uint32_t lane_offset, const void* uniform_base) {
+    asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3"
+                 : "=&v"(v) : "v"(lane_offset), "s"(uniform_base), "n"(IMM) : "memory");
+}
+// waits until at most N of this wave's copies / loads are outstanding; a and b are usable afterwards
+template <int N>
+__device__ __forceinline__ void wait_vm(bf16x8& a, bf16x8& b) {
+    asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
 }
 
 // value of lane `src` (0..3, a constant after unrolling) of the caller's quad
@@ -126,9 +145,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     // (c[lo], c[hi]) -- one LDS read dequantizes two weights.  The 256 entries are replicated 16 times,
     // entry b of replica q at b*128 + q*8, and lane l reads replica l & 15, so that lanes of one
     // 16-lane group never collide whatever their bytes are.
-    if (t < 16) reinterpret_cast<float*>(sT)[t] = d.cb.c[t];
-    __syncthreads();
-    {
+    if constexpr (QMODE != 0) {
+        if (t < 16) reinterpret_cast<float*>(sT)[t] = d.cb.c[t];
+        __syncthreads();
         const int b = t & 255;
         const float c_lo = reinterpret_cast<const float*>(sT)[b & 15], c_hi = reinterpret_cast<const float*>(sT)[b >> 4];
         __syncthreads();
@@ -137,7 +156,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
         for (int q = 0; q < 4; ++q) *reinterpret_cast<float4*>(sT + b * 128 + (t >> 8) * 64 + q * 16) = e;
     }
 
-    const int K1 = QMODE == 1 ? d_in : d_out;
+    const int K1 = QMODE == 0 ? d.K1 : QMODE == 1 ? d_in : d_out;
     const int steps1 = K1 / kBK, steps2 = (K2 + kBK - 1) / kBK;
     const int nsteps = steps1 + steps2;
     const int bpr = d_in / kBlock;                // blocks per stored weight row
@@ -186,6 +205,18 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
         for (int i = 0; i < 4; ++i) copy16_to_lds(base, xoff[i], lds0 + buf * kTileBytes + i * 8 * 128);
     };
+    // QMODE 0: per-lane byte offsets of this wave's two 32-row blocks in the operand-ordered weight
+    uint32_t wvoff[2] = {0u, 0u};
+    const unsigned char* const wop = reinterpret_cast<const unsigned char*>(d.W1);
+    if constexpr (QMODE == 0) {
+        const int blocks32 = (N + 31) / 32;
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+            int nb = (n0 + wn0) / 32 + a;
+            nb = nb > blocks32 - 1 ? blocks32 - 1 : nb;      // rows past N: any valid block, results never stored
+            wvoff[a] = (uint32_t)nb * (uint32_t)(d.K1 / 16) * 1024u + (uint32_t)lane * 16u;
+        }
+    }
     auto issue_copies = [&](int step, int buf) __attribute__((always_inline)) {
         if (step < steps1) {
             issue_x1(step, buf);
@@ -207,7 +238,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
         else fwd_codes = codes + (int64_t)qrow * (d_in / 2) + (t & 1) * 16;
         if (d.scales_tiled) { fwd_scales = d.scales_tiled + tiled_run_offset(n0 + (t >> 1), 0, bpr) / 32; fwd_scale_stride = 256; }
         else fwd_scales = scales + (int64_t)qrow * bpr;
-    } else {
+    } else if constexpr (QMODE == 2) {
         qcol = n0 + 8 * (t & 31);                    // this thread's 8 stored columns (k of the layer)
         if (qcol > N - 8) qcol = N - 8;
     }
@@ -246,36 +277,37 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
         }
     };
 
-    // ---- dequantization of a staged k-step: 2 pieces of 16 weights (8 table reads) per thread -------
-    //   QMODE 1: piece p = dwords 2p, 2p+1 of this thread's half row -> chunks 4*half+2p, +1 of LDS row t>>1;
-    //   QMODE 2: piece p = bytes 2p, 2p+1 (columns 4p..4p+3) of each of the 4 stored rows of the patch
-    //            -> 8-byte halves of LDS rows 8*kg+4p .. +3 (packing down the columns transposes).
+    // ---- dequantization of a staged k-step: 4 pieces of 8 weights (4 table reads each) per thread ----------
+    //   QMODE 1: piece p = code dword p of this thread's half row -> chunk 4*half+p of LDS row t>>1;
+    //   QMODE 2: piece p = byte p (columns 2p, 2p+1) of each of the 4 stored rows of the patch -> 8-byte halves
+    //            of LDS rows 8*kg+2p and 8*kg+2p+1 (packing down the columns transposes).
+    constexpr int kPieces = 4, kReads = 4;
     const uint32_t table_lane = lds_address(sT) - lds_address(smem) + ((lane & 15) << 3);
-    auto table_offsets = [&](const Staged<QMODE, BR>& s, int p, uint32_t (&li)[8]) __attribute__((always_inline)) {
+    auto table_offsets = [&](const Staged<QMODE, BR>& s, int p, uint32_t (&li)[kReads]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            // QMODE 1: i = 4*(dword in piece) + byte;  QMODE 2: i = 4*(byte in piece) + row
-            const uint32_t w = QMODE == 1 ? s.cw[2 * p + (i >> 2)] : s.cw[i & 3];
-            const int byte = QMODE == 1 ? (i & 3) : (2 * p + (i >> 2));
+        for (int i = 0; i < kReads; ++i) {
+            // QMODE 1: i = byte of dword p;  QMODE 2: i = stored row, byte p of its dword
+            const uint32_t w = QMODE == 1 ? s.cw[p] : s.cw[i];
+            const int byte = QMODE == 1 ? i : p;
             const uint32_t sh = byte == 0 ? (w << 7) : (w >> (8 * byte - 7));
             li[i] = (sh & 0x7f80u) | table_lane;
         }
     };
-    auto table_reads = [&](const uint32_t (&li)[8], float2 (&lv)[8]) __attribute__((always_inline)) {
+    auto table_reads = [&](const uint32_t (&li)[kReads], float2 (&lv)[kReads]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) lv[i] = *reinterpret_cast<const float2*>(smem + li[i]);
+        for (int i = 0; i < kReads; ++i) lv[i] = *reinterpret_cast<const float2*>(smem + li[i]);
     };
-    auto finish_piece = [&](const Staged<QMODE, BR>& s, int p, const float2 (&lv)[8], unsigned char* tile)
+    auto finish_piece = [&](const Staged<QMODE, BR>& s, int p, const float2 (&lv)[kReads], unsigned char* tile)
         __attribute__((always_inline)) {
-        float lo[8], hi[8];
+        float lo[kReads], hi[kReads];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < kReads; ++i) {
             float sc, be = 0.0f;
-            if constexpr (QMODE == 2 && BR == 1) {           // row i & 3 of the patch: lane i & 3 of the quad holds it
-                sc = quad_broadcast(s.sc[0], i & 3);
-                if constexpr (BETA) be = quad_broadcast(s.be[0], i & 3);
+            if constexpr (QMODE == 2 && BR == 1) {           // row i of the patch: lane i of the quad holds its scale
+                sc = quad_broadcast(s.sc[0], i);
+                if constexpr (BETA) be = quad_broadcast(s.be[0], i);
             } else {
-                const int si = QMODE == 2 ? 0 : (BR == 8 ? 2 * p + (i >> 2) : 0);
+                const int si = QMODE == 2 ? 0 : (BR == 8 ? p : 0);
                 sc = s.sc[si];
                 if constexpr (BETA) be = s.be[si];
             }
@@ -283,34 +315,27 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
             hi[i] = BETA ? __fmaf_rn(lv[i].y, sc, be) : __fmul_rn(lv[i].y, sc);
         }
         if constexpr (QMODE == 1) {
-            // byte i holds elements 2i, 2i+1 of the 16: adjacent k, packed as they come
-            uint4 o0, o1;
+            // byte i holds elements 2i, 2i+1 of the 8: adjacent k, packed as they come
+            uint4 o0;
             o0.x = pack_bf16(lo[0], hi[0]); o0.y = pack_bf16(lo[1], hi[1]);
             o0.z = pack_bf16(lo[2], hi[2]); o0.w = pack_bf16(lo[3], hi[3]);
-            o1.x = pack_bf16(lo[4], hi[4]); o1.y = pack_bf16(lo[5], hi[5]);
-            o1.z = pack_bf16(lo[6], hi[6]); o1.w = pack_bf16(lo[7], hi[7]);
-            const int chunk = 4 * (t & 1) + 2 * p;
-            *reinterpret_cast<uint4*>(tile + swz(t >> 1, chunk)) = o0;
-            *reinterpret_cast<uint4*>(tile + swz(t >> 1, chunk + 1)) = o1;
+            *reinterpret_cast<uint4*>(tile + swz(t >> 1, 4 * (t & 1) + p)) = o0;
         } else {
-            // lv[4*j + i] is (column 4p+2j, column 4p+2j+1) of stored row i: pack down each column
+            // lv[i] is (column 2p, column 2p+1) of stored row i: pack down each column
             const int kg = t & 31, ng = t >> 5;
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                uint2 c0, c1;
-                c0.x = pack_bf16(lo[4 * j + 0], lo[4 * j + 1]); c0.y = pack_bf16(lo[4 * j + 2], lo[4 * j + 3]);
-                c1.x = pack_bf16(hi[4 * j + 0], hi[4 * j + 1]); c1.y = pack_bf16(hi[4 * j + 2], hi[4 * j + 3]);
-                const int row = 8 * kg + 4 * p + 2 * j;
-                *reinterpret_cast<uint2*>(tile + swz(row, ng >> 1) + 8 * (ng & 1)) = c0;
-                *reinterpret_cast<uint2*>(tile + swz(row + 1, ng >> 1) + 8 * (ng & 1)) = c1;
-            }
+            uint2 c0, c1;
+            c0.x = pack_bf16(lo[0], lo[1]); c0.y = pack_bf16(lo[2], lo[3]);
+            c1.x = pack_bf16(hi[0], hi[1]); c1.y = pack_bf16(hi[2], hi[3]);
+            const int row = 8 * kg + 2 * p;
+            *reinterpret_cast<uint2*>(tile + swz(row, ng >> 1) + 8 * (ng & 1)) = c0;
+            *reinterpret_cast<uint2*>(tile + swz(row + 1, ng >> 1) + 8 * (ng & 1)) = c1;
         }
     };
     auto dequant_store = [&](const Staged<QMODE, BR>& s, unsigned char* tile) __attribute__((always_inline)) {
 #pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            uint32_t li[8];
-            float2 lv[8];
+        for (int p = 0; p < kPieces; ++p) {
+            uint32_t li[kReads];
+            float2 lv[kReads];
             table_offsets(s, p, li);
             table_reads(li, lv);
             finish_piece(s, p, lv, tile);
@@ -335,27 +360,32 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
         const uint32_t wo = (uint32_t)(bw - sW), xo = (uint32_t)(bx - sX);
 #pragma unroll
         for (int a = 0; a < 2; ++a)
-            fw[a] = *reinterpret_cast<const bf16x8*>(smem + (((frag_w + wo) ^ (uint32_t)(((2 * ks) ^ (4 * (a & 1))) << 4)) + a * 4096));
+            fw[a] = *reinterpret_cast<const bf16x8*>(smem + ((frag_w ^ (uint32_t)(((2 * ks) ^ (4 * (a & 1))) << 4)) + (wo + a * 4096)));
 #pragma unroll
         for (int b = 0; b < 4; ++b)
-            fx[b] = *reinterpret_cast<const bf16x8*>(smem + (((frag_x + xo) ^ (uint32_t)(((2 * ks) ^ (4 * (b & 1))) << 4)) + b * 4096));
+            fx[b] = *reinterpret_cast<const bf16x8*>(smem + ((frag_x ^ (uint32_t)(((2 * ks) ^ (4 * (b & 1))) << 4)) + (xo + b * 4096)));
     };
     // dq: dequantize `sdq` into bw_next during this step; has_next: a step follows (its tiles are in
-    // bx_next / bw_next once the barrier is passed).  Both are literal `true` in the steady state.
+    // bx_next / bw_next once the barrier is passed); dq_next: the following step dequantizes `sdq_next`, whose
+    // first piece is looked up behind this step's barrier (lv0 carries the values across the step boundary).
+    // All flags are literal `true` in the steady state.
+    float2 lv0[kReads];
     auto run_step = [&](const unsigned char* bx, const unsigned char* bw, const unsigned char* bx_next,
                         unsigned char* bw_next, const bool dq, const Staged<QMODE, BR>& sdq, const bool has_next,
-                        const bool refill, const int step2, const int buf2) __attribute__((always_inline)) {
-        float2 lv[2][8];
-        uint32_t li[8];
+                        const bool refill, const int step2, const int buf2, const bool dq_next,
+                        const Staged<QMODE, BR>& sdq_next) __attribute__((always_inline)) {
+        float2 lv[2][kReads];
+        uint32_t li[kReads];
         asm volatile("" : "+v"(frag_w), "+v"(frag_x));
         if (dq) {
-            table_offsets(sdq, 0, li);
-            table_reads(li, lv[0]);
-            table_offsets(sdq, 1, li);
+#pragma unroll
+            for (int i = 0; i < kReads; ++i) lv[0][i] = lv0[i];
         }
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             const int cur = ks & 1, nxt = cur ^ 1;
+            // the last piece is stored in front of the barrier that publishes the tile
+            if (ks == 3 && dq) finish_piece(sdq, 3, lv[1], bw_next);
             if (ks == 3 && has_next) {
                 __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): direct copies and staged codes
                 __syncthreads();                           // next tiles published; this step's tiles free
@@ -363,16 +393,152 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
                 if (refill) issue_x1(step2, buf2);         // this step's token buffer is free: refill it
             }
             if (ks < 3) read_frags(bx, bw, ks + 1, wf[nxt], xf[nxt]);
-            if (dq) {
-                if (ks == 0) table_reads(li, lv[1]);
-                if (ks == 1) finish_piece(sdq, 0, lv[0], bw_next);
-                if (ks == 2) finish_piece(sdq, 1, lv[1], bw_next);
+            if (dq && ks < 3) {
+                // piece ks+1 is looked up while piece ks is scaled and stored
+                table_offsets(sdq, ks + 1, li);
+                table_reads(li, lv[nxt]);
             }
+            if (ks == 3 && dq_next) {                      // the staged codes of the next step's tile have arrived
+                // (the empty statement pins the address arithmetic behind the barrier: hoisted to the top of
+                // the step it would wait for the code loads issued there)
+                Staged<QMODE, BR> nx = sdq_next;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) asm volatile("" : "+v"(nx.cw[i]));
+                table_offsets(nx, 0, li);
+                table_reads(li, lv0);
+            }
+            __builtin_amdgcn_sched_barrier(0);             // LDS reads of the next quarter go out before this quarter's MFMAs
+            if (dq && ks < 3) finish_piece(sdq, ks, lv[cur], bw_next);
 #pragma unroll
             for (int a = 0; a < 2; ++a)
 #pragma unroll
                 for (int b = 0; b < 4; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][a], xf[cur][b], acc[a][b], 0, 0, 0);
+            // the scaling arithmetic of the piece goes into the shadow of the MFMAs, two vector instructions each
+#pragma unroll
+            for (int i = 0; i < 7; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // ---- QMODE 0: steps on the operand-ordered weight ---------------------------------------------------
+    // wreg[ks][a] holds the weight fragment of quarter ks, feature block a.  In the steady state a step loads
+    // the next step's fragment of a quarter right behind that quarter's MFMAs (into the registers they have
+    // just read), so a load has a whole step to arrive.  Every copy and load of the loop is issued by an asm
+    // statement in program order, per step: W(s+1,0) x2, W(s+1,1) x2, W(s+1,2) x2, X copies of step s+2 x4,
+    // W(s+1,3) x2.  The fragment of quarter q < 3 was issued one step earlier and 10 operations have been
+    // issued since, hence vmcnt(10); in front of the barrier of the last quarter the token copies of step s+1
+    // and W(s,3) have the 6 loads of this step behind them, hence vmcnt(6).
+    bf16x8 wreg[4][2];
+    auto read_x = [&](const unsigned char* bx, int ks, bf16x8 (&fx)[4]) __attribute__((always_inline)) {
+        const uint32_t xo = (uint32_t)(bx - sX);
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+            fx[b] = *reinterpret_cast<const bf16x8*>(smem + ((frag_x ^ (uint32_t)(((2 * ks) ^ (4 * (b & 1))) << 4)) + (xo + b * 4096)));
+    };
+    auto mfma_quarter = [&](const int ks, const int cur) __attribute__((always_inline)) {
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wreg[ks][a], xf[cur][b], acc[a][b], 0, 0, 0);
+    };
+    auto load_w_quarter = [&](const int ks, const void* base) __attribute__((always_inline)) {
+        if (ks == 0) { load_operand16<0>(wreg[0][0], wvoff[0], base); load_operand16<0>(wreg[0][1], wvoff[1], base); }
+        if (ks == 1) { load_operand16<1024>(wreg[1][0], wvoff[0], base); load_operand16<1024>(wreg[1][1], wvoff[1], base); }
+        if (ks == 2) { load_operand16<2048>(wreg[2][0], wvoff[0], base); load_operand16<2048>(wreg[2][1], wvoff[1], base); }
+        if (ks == 3) { load_operand16<3072>(wreg[3][0], wvoff[0], base); load_operand16<3072>(wreg[3][1], wvoff[1], base); }
+    };
+    // a step that is followed by another step on the operand-ordered weight (step + 1 < steps1)
+    auto dense_step = [&](const unsigned char* bx, const unsigned char* bx_next, const bool refill, const int step,
+                          const int buf2) __attribute__((always_inline)) {
+        const void* const next_w = wop + (int64_t)(step + 1) * 4096;          // 4 slices of 1 KB per step
+        asm volatile("" : "+v"(frag_x));
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks < 3) {
+                read_x(bx, ks + 1, xf[nxt]);
+                wait_vm<10>(wreg[ks][0], wreg[ks][1]);
+            } else {
+                wait_vm<6>(wreg[3][0], wreg[3][1]);        // also: this wave's token copies of the next step
+                __syncthreads();                           // next token tile published; this step's tile free
+                read_x(bx_next, 0, xf[0]);
+                if (refill) issue_x1(step + 2, buf2);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_quarter(ks, cur);
+            __builtin_amdgcn_sched_barrier(0);
+            load_w_quarter(ks, next_w);
+        }
+    };
+    // the last step on the operand-ordered weight: nothing more is loaded; if a K-extension step follows, its
+    // tiles (8 copies, issued just before) are the youngest operations
+    auto dense_last = [&](const unsigned char* bx, const unsigned char* bx_next, const unsigned char* bw_next,
+                          const bool has_next) __attribute__((always_inline)) {
+        asm volatile("" : "+v"(frag_w), "+v"(frag_x));
+        if (has_next) wait_vm<8>(wreg[0][0], wreg[0][1]); else wait_vm<0>(wreg[0][0], wreg[0][1]);
+#pragma unroll
+        for (int ks = 1; ks < 4; ++ks) asm volatile("" : "+v"(wreg[ks][0]), "+v"(wreg[ks][1]));
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks < 3) read_x(bx, ks + 1, xf[nxt]);
+            if (ks == 3 && has_next) {
+                __builtin_amdgcn_s_waitcnt(0x0F70);
+                __syncthreads();
+                read_frags(bx_next, bw_next, 0, wf[0], xf[0]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_quarter(ks, cur);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    auto dense_loop = [&]() __attribute__((always_inline)) {
+        if (nsteps <= 0) return;
+        Staged<QMODE, BR> none{};
+        int s = 0, issued = 0;
+        if (steps1 > 0) {
+            issue_x1(0, 0);
+            if (steps1 > 1) { issue_x1(1, 1); issued = 1; }
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) load_w_quarter(ks, wop);
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+            read_x(sX, 0, xf[0]);
+            for (; s + 2 < steps1; s += 2) {
+                dense_step(sX, sX + kTileBytes, true, s, 0);
+                const bool more = s + 3 < steps1;
+                dense_step(sX + kTileBytes, sX, more, s + 1, 1);
+                issued = more ? s + 3 : s + 2;
+            }
+            if (s + 1 < steps1) {
+                dense_step(sX, sX + kTileBytes, false, s, 0);
+                ++s;
+            }
+            const int buf = s & 1;
+            const bool has_next = s + 1 < nsteps;
+            if (has_next) { issue_copies(s + 1, buf ^ 1); issued = s + 1; }
+            dense_last(sX + buf * kTileBytes, sX + (buf ^ 1) * kTileBytes, sW + (buf ^ 1) * kTileBytes, has_next);
+            ++s;
+        } else {
+            issue_copies(0, 0);
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+            read_frags(sX, sW, 0, wf[0], xf[0]);
+        }
+        // K-extension steps: both tiles through LDS
+        for (; s < nsteps; ++s) {
+            const int buf = s & 1;
+            const bool has_next = s + 1 < nsteps;
+            if (has_next && issued < s + 1) { issue_copies(s + 1, buf ^ 1); issued = s + 1; }
+            run_step(sX + buf * kTileBytes, sW + buf * kTileBytes, sX + (buf ^ 1) * kTileBytes,
+                     sW + (buf ^ 1) * kTileBytes, false, none, has_next, false, 0, 0, false, none);
         }
     };
 
@@ -380,17 +546,27 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     // Invariant at the top of step s: tile buffers s&1 hold step s and fragment set 0 holds its first
     // quarter; st[(s+1)&1] holds the codes of step s+1 (if that is a quantized step).
     Staged<QMODE, BR> st[2];
-    if (nsteps > 0) {
+    if constexpr (QMODE == 0) {
+        dense_loop();
+    } else if (nsteps > 0) {
         issue_copies(0, 0);
         int issued = 0;                                    // copies are in flight or done for steps <= issued
         if (steps1 > 1) { issue_copies(1, 1); issued = 1; }
-        if (steps1 > 0) load_staged(st[0], 0);
-        if (steps1 > 1) load_staged(st[1], 1);
-        __syncthreads();                                   // pair table visible
-        if (steps1 > 0) dequant_store(st[0], sW);
+        constexpr bool kDq = QMODE != 0;                   // segment 1 is dequantized in the kernel
+        if constexpr (kDq) {
+            if (steps1 > 0) load_staged(st[0], 0);
+            if (steps1 > 1) load_staged(st[1], 1);
+            __syncthreads();                               // pair table visible
+            if (steps1 > 0) dequant_store(st[0], sW);
+        }
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
         read_frags(sX, sW, 0, wf[0], xf[0]);
+        if (kDq && steps1 > 1) {                           // first piece of the tile the first step dequantizes
+            uint32_t li[kReads];
+            table_offsets(st[1], 0, li);
+            table_reads(li, lv0);
+        }
         int s = 0;
         // Quantized steps whose successor is quantized too (the successor's tile is dequantized during
         // the step), unrolled by two so that the staging registers and the tile buffers have fixed
@@ -400,15 +576,16 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
         // barrier, under its last 8 MFMAs.
         const int last_q = steps1 - 1;
         for (; s + 2 < steps1; s += 2) {
-            load_staged(st[0], min(s + 2, last_q));
-            run_step(sX, sW, sX + kTileBytes, sW + kTileBytes, true, st[1], true, true, s + 2, 0);
-            load_staged(st[1], min(s + 3, last_q));
+            if constexpr (kDq) load_staged(st[0], min(s + 2, last_q));
+            run_step(sX, sW, sX + kTileBytes, sW + kTileBytes, kDq, st[1], true, true, s + 2, 0, kDq, st[0]);
+            if constexpr (kDq) load_staged(st[1], min(s + 3, last_q));
             const bool more = s + 3 < steps1;
-            run_step(sX + kTileBytes, sW + kTileBytes, sX, sW, true, st[0], true, more, s + 3, 1);
+            // (past the last dequantizing step the looked-up piece is simply not used)
+            run_step(sX + kTileBytes, sW + kTileBytes, sX, sW, kDq, st[0], true, more, s + 3, 1, kDq, st[1]);
             issued = more ? s + 3 : s + 2;
         }
         if (s + 1 < steps1) {
-            run_step(sX, sW, sX + kTileBytes, sW + kTileBytes, true, st[1], true, false, 0, 0);
+            run_step(sX, sW, sX + kTileBytes, sW + kTileBytes, kDq, st[1], true, false, 0, 0, false, st[0]);
             ++s;
         }
         // the last quantized step and the K-extension steps: nothing to dequantize; copies of the next
@@ -418,7 +595,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
             const bool has_next = s + 1 < nsteps;
             if (has_next && issued < s + 1) { issue_copies(s + 1, buf ^ 1); issued = s + 1; }
             run_step(sX + buf * kTileBytes, sW + buf * kTileBytes, sX + (buf ^ 1) * kTileBytes,
-                     sW + (buf ^ 1) * kTileBytes, false, st[0], has_next, false, 0, 0);
+                     sW + (buf ^ 1) * kTileBytes, false, st[0], has_next, false, 0, 0, false, st[0]);
         }
     }
 
@@ -475,7 +652,7 @@ int launch_cfg(const GemmDesc& d, hipStream_t st) {
 int launch_qlinear(const GemmDesc& d, hipStream_t st) {
     if (d.M <= 0 || d.N <= 0) return QBLORA_OK;
     if (d.out_f32 || d.C2 || d.C_lo) return QBLORA_ERR_UNSUPPORTED;
-    if (d.block_rows == 8) {
+    if (d.block_rows == 8 && d.qmode != 3) {
         // scales / offsets are read as 16-byte groups of 4 block columns; tile-ordered scales do not exist
         if (d.scales_tiled || !d.scales || d.d_out % 8 != 0 || (reinterpret_cast<uintptr_t>(d.scales) & 15) ||
             (reinterpret_cast<uintptr_t>(d.beta) & 15))
@@ -483,6 +660,14 @@ int launch_qlinear(const GemmDesc& d, hipStream_t st) {
         if (d.qmode == 1) return d.beta ? launch_cfg<1, true, 8>(d, st) : launch_cfg<1, false, 8>(d, st);
         if (d.qmode == 2) return d.beta ? launch_cfg<2, true, 8>(d, st) : launch_cfg<2, false, 8>(d, st);
         return QBLORA_ERR_UNSUPPORTED;
+    }
+    if (d.qmode == 3) {
+        // dense first segment: whole 64-wide steps of 16-byte chunks
+        // whole 64-wide steps, whole 32-row blocks, 32-bit byte offsets into the operand-ordered weight
+        if (!d.W1 || d.K1 <= 0 || d.K1 % kBK != 0 || d.N % 32 != 0 || (reinterpret_cast<uintptr_t>(d.W1) & 15) ||
+            (int64_t)d.N * d.K1 * 2 >= ((int64_t)1 << 32))
+            return QBLORA_ERR_UNSUPPORTED;
+        return launch_cfg<0, false, 1>(d, st);
     }
     if (d.qmode == 1) return d.beta ? launch_cfg<1, true, 1>(d, st) : launch_cfg<1, false, 1>(d, st);
     if (d.qmode == 2) return d.beta ? launch_cfg<2, true, 1>(d, st) : launch_cfg<2, false, 1>(d, st);

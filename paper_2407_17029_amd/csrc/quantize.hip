@@ -354,6 +354,97 @@ __global__ __launch_bounds__(256) void k_dequantize_bf16(const uint32_t* __restr
     out[i] = o;
 }
 
+// The bf16 compute weight in MFMA operand order (see launch_dequantize_operand): the weight itself.
+// A wave owns 32 stored rows x one 64-block: lane l = r + 32*hi reads the 32 code bytes of row r's block and
+// writes, for each of the block's four 16-wide k slices q, the 8 weights k = 16q + 8hi .. + 7 as 16 bytes at
+// lane l of that slice's 1 KB piece -- 4 KB contiguous per wave, 16 KB per workgroup (four consecutive blocks).
+__global__ __launch_bounds__(256) void k_dequantize_operand(const uint8_t* __restrict__ codes,
+                                                            const float* __restrict__ scales,
+                                                            const float* __restrict__ beta, Codebook cb,
+                                                            int d_out, int d_in, int block_rows,
+                                                            uint4* __restrict__ out) {
+    __shared__ float lut[16];
+    const int t = threadIdx.x, lane = t & 63;
+    if (t < 16) lut[t] = cb.c[t];
+    __syncthreads();
+    const int bpr = d_in / kBlock, groups = (bpr + 3) / 4;
+    const int nb = blockIdx.x / groups;                         // 32-row block
+    const int b = (blockIdx.x % groups) * 4 + (t >> 6);        // 64-block of this wave
+    if (b >= bpr) return;
+    const int r = lane & 31, hi = lane >> 5;
+    const int64_t n = (int64_t)nb * 32 + r;                     // d_out is a multiple of 32 here
+    const uint4* run = reinterpret_cast<const uint4*>(codes + n * (d_in / 2) + b * 32);
+    const uint4 c0 = run[0], c1 = run[1];
+    const uint32_t cw[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+    float a = 0.0f, be = 0.0f;
+    if (block_rows != 8) {
+        a = scales[n * bpr + b];
+        if (beta) be = beta[n * bpr + b];
+    }
+    const int64_t kb_count = d_in / 16;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t w = cw[2 * q + hi];
+        if (block_rows == 8) {                                  // one 8 x 8 block per code dword
+            const int64_t blk = (n >> 3) * (int64_t)(d_in / 8) + (8 * b + 2 * q + hi);
+            a = scales[blk];
+            if (beta) be = beta[blk];
+        }
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float c = lut[(w >> (4 * j)) & 15];
+            v[j] = beta ? __fmaf_rn(c, a, be) : __fmul_rn(c, a);
+        }
+        uint4 o;
+        o.x = pack_bf16(v[0], v[1]); o.y = pack_bf16(v[2], v[3]);
+        o.z = pack_bf16(v[4], v[5]); o.w = pack_bf16(v[6], v[7]);
+        out[((int64_t)nb * kb_count + 4 * b + q) * 64 + lane] = o;
+    }
+}
+
+// The same for the transposed weight (operand rows = inputs k, contraction = stored rows n), which the
+// backward contraction reads.  A workgroup owns 32 inputs x 64 stored rows: a thread dequantizes 8 inputs of
+// one stored row into an LDS tile laid out [k][n], then the four 16-row slices leave as 1 KB pieces (lane l =
+// r + 32*hi holds k = r, n = 16q + 8hi .. + 7) -- 4 KB contiguous per workgroup.
+__global__ __launch_bounds__(256) void k_dequantize_operand_t(const uint8_t* __restrict__ codes,
+                                                              const float* __restrict__ scales,
+                                                              const float* __restrict__ beta, Codebook cb,
+                                                              int d_out, int d_in, int block_rows,
+                                                              uint4* __restrict__ out) {
+    __shared__ float lut[16];
+    __shared__ __align__(16) uint16_t tile[32][72];             // [k][n], pitch 144 bytes
+    const int t = threadIdx.x;
+    if (t < 16) lut[t] = cb.c[t];
+    __syncthreads();
+    const int n_tiles = d_out / 64;                             // d_out is a multiple of 64 here
+    const int kb32 = blockIdx.x / n_tiles;                      // block of 32 inputs
+    const int nt = blockIdx.x % n_tiles;                        // 64 stored rows
+    {
+        const int row = t >> 2, wd = t & 3;                     // stored row in tile, code dword (8 inputs)
+        const int64_t n = (int64_t)nt * 64 + row;
+        const int k0 = kb32 * 32 + wd * 8;
+        const uint32_t w = *reinterpret_cast<const uint32_t*>(codes + n * (d_in / 2) + k0 / 2);
+        const int64_t blk = block_rows == 8 ? (n >> 3) * (int64_t)(d_in / 8) + k0 / 8
+                                            : n * (int64_t)(d_in / kBlock) + k0 / kBlock;
+        const float a = scales[blk];
+        const float be = beta ? beta[blk] : 0.0f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float c = lut[(w >> (4 * j)) & 15];
+            const float v = beta ? __fmaf_rn(c, a, be) : __fmul_rn(c, a);
+            tile[wd * 8 + j][row] = (uint16_t)(pack_bf16(v, 0.0f) & 0xffffu);
+        }
+    }
+    __syncthreads();
+    {
+        const int q = t >> 6, lane = t & 63, r = lane & 31, hi = lane >> 5;
+        const uint4 o = *reinterpret_cast<const uint4*>(&tile[r][16 * q + 8 * hi]);
+        const int64_t kb_count = d_out / 16;                    // slices of the contraction (stored rows)
+        out[((int64_t)kb32 * kb_count + (int64_t)nt * 4 + q) * 64 + lane] = o;
+    }
+}
+
 // Nibbles of a code dword regrouped for the table-free decode: position p of the result holds input k(p),
 // k = 0, 2, 4, 6, 1, 3, 5, 7 -- the even inputs in the low half, the odd ones in the high half, so that
 // (w >> 4i) & 0x000F000F is the pair (input 2i, input 2i+1) in the low bits of two 16-bit lanes.
@@ -452,6 +543,28 @@ int launch_dequantize_bf16(const qblora_qweight& qw, const float* scales, qblora
     hipLaunchKernelGGL(k_dequantize_bf16, dim3(grid), dim3(256), 0, st,
                        reinterpret_cast<const uint32_t*>(qw.codes), scales, qw.beta, cb, n_words,
                        qw.block_rows == 8 ? qw.d_in / 8 : 0, reinterpret_cast<uint4*>(Wt));
+    return launch_status();
+}
+
+int launch_dequantize_operand(const qblora_qweight& qw, const float* scales, int transposed, qblora_bf16* Wop,
+                              hipStream_t st) {
+    if (qw.d_in % 64 != 0 || qw.d_out % 64 != 0 || (reinterpret_cast<uintptr_t>(Wop) & 15) ||
+        (reinterpret_cast<uintptr_t>(qw.codes) & 15))
+        return QBLORA_ERR_UNSUPPORTED;
+    Codebook cb;
+    for (int j = 0; j < 16; ++j) cb.c[j] = qw.codebook[j];
+    const int br = qw.block_rows == 8 ? 8 : 1;
+    if (!transposed) {
+        const int64_t blocks = (int64_t)(qw.d_out / 32) * ((qw.d_in / kBlock + 3) / 4);
+        if (blocks > 0x7fffffff) return QBLORA_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(k_dequantize_operand, dim3((unsigned)blocks), dim3(256), 0, st, qw.codes, scales, qw.beta, cb,
+                           qw.d_out, qw.d_in, br, reinterpret_cast<uint4*>(Wop));
+    } else {
+        const int64_t blocks = (int64_t)(qw.d_in / 32) * (qw.d_out / 64);
+        if (blocks > 0x7fffffff) return QBLORA_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(k_dequantize_operand_t, dim3((unsigned)blocks), dim3(256), 0, st, qw.codes, scales, qw.beta,
+                           cb, qw.d_out, qw.d_in, br, reinterpret_cast<uint4*>(Wop));
+    }
     return launch_status();
 }
 

@@ -120,11 +120,23 @@ def test_workspace_sizes(qb):
     qw = qb.CQWeight()
     qw.d_out, qw.d_in, qw.block = 4096, 4096, 64
     qw.codes = qw.scales = 0x1000
+    few = L.qblora_dense_min_tokens() - 1                               # weight tiles rebuilt in LDS per token tile
+    many = L.qblora_dense_min_tokens()                                  # weight dequantized once into the workspace
+    assert few >= 256
     scales_t = 4 * 4096 * 64                                            # tile-ordered fp32 block scales
-    assert L.qblora_linear_fwd_workspace_bytes(C.byref(qw), None, 8192) == scales_t
+    assert L.qblora_linear_fwd_workspace_bytes(C.byref(qw), None, few) == scales_t
     ad = qb.CAdapter()
     ad.lambda1, ad.lambda2, ad.R, ad.s, ad.A, ad.B = 2, 2, 128, 1.0, 0x1000, 0x1000
-    fwd = L.qblora_linear_fwd_workspace_bytes(C.byref(qw), C.byref(ad), 8192)
-    assert fwd == scales_t + 2 * (128 * 4096 + 2048 * 128 + 8192 * 128)   # + At_x, Bt, U in bf16
-    bwd = L.qblora_linear_bwd_workspace_bytes(C.byref(qw), C.byref(ad), 8192)
+    fwd = L.qblora_linear_fwd_workspace_bytes(C.byref(qw), C.byref(ad), few)
+    assert fwd == scales_t + 2 * (128 * 4096 + 2048 * 128 + few * 128) + (256 - 2 * few * 128 % 256) % 256   # + At_x, Bt, U in bf16
+    bwd = L.qblora_linear_bwd_workspace_bytes(C.byref(qw), C.byref(ad), few)
     assert bwd > fwd and bwd % 256 == 0
+    dense_w = 2 * 4096 * 4096                                           # the bf16 weight
+    assert L.qblora_linear_fwd_workspace_bytes(C.byref(qw), None, many) == dense_w
+    fwd_many = L.qblora_linear_fwd_workspace_bytes(C.byref(qw), C.byref(ad), many)
+    assert fwd_many == dense_w + 2 * (128 * 4096 + 2048 * 128 + many * 128)
+    assert L.qblora_linear_bwd_workspace_bytes(C.byref(qw), C.byref(ad), many) > dense_w
+    # double-quantized scales: the one-off pass reads reconstructed fp32 scales from the workspace
+    qw.scale_mode, qw.scale_group = 1, 256
+    qw.scale_codes = qw.scale_step = qw.scale_mid = 0x1000
+    assert L.qblora_linear_fwd_workspace_bytes(C.byref(qw), None, many) == dense_w + 4 * 4096 * 64

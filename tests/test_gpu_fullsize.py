@@ -166,7 +166,7 @@ def test_scale_operators_benchmark_shape(qb, oracle, codebook, op):
 
 
 def test_small_batch_inference_at_the_measured_shape(qb, oracle):
-    """The decode kernel on the 65B up-projection shape kernel_bench times (22016 x 8192, INT4 with offsets, tile-
+    """The decode kernel on the 65B up-projection shape bench.py times among its side measurements (22016 x 8192, INT4 with offsets, tile-
     ordered pack), T = 1 and 16: sampled output features against the oracle (a feature needs its own weight row only)."""
     from gpu_util import f32_to_dev, bf16_to_dev, bf16_to_f64, bf16_half_ulp
     d_out, d_in = 22016, 8192

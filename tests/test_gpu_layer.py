@@ -206,3 +206,54 @@ def test_adapter_dominant_parity(qb, oracle, codebook, T, d_out, d_in, R, lam1, 
     assert_close_bf16(dX, rX, "dX (adapter-dominant)")
     assert_close_f32(dA, rA, "dA")
     assert_close_f32(dB, rB, "dB")
+
+
+# ---- many tokens: the weight is dequantized once per call ---------------------------------------------
+# From qblora_dense_min_tokens() tokens on, the forward / backward calls first write the bf16 compute weight
+# (transposed for the backward) into their workspace and contract that.  Small widths with ragged token counts
+# keep the oracle fast while the path sees partial tiles, every block geometry and scale format.
+DENSE_CASES = [
+    # extra tokens, d_out, d_in, R, lam1, lam2, s, minmax, grouped, block_rows
+    (52, 320, 192, 16, 2, 2, 0.25, False, False, 1),       # ragged tokens, partial tiles in every dimension
+    (256, 576, 832, 64, 4, 8, 2.0, False, True, 1),        # lambda1 != lambda2, double-quantized scales
+    (1, 256, 384, 40, 2, 2, 1.0, True, False, 1),          # min-max base with offsets, one token beyond a tile
+    (130, 320, 448, 24, 8, 8, 0.5, True, False, 8),        # 8 x 8 blocks with offsets
+    (77, 512, 256, 0, 1, 1, 1.0, False, False, 8),         # 8 x 8 blocks, codebook base, no adapter
+]
+
+
+@pytest.mark.parametrize("extra,d_out,d_in,R,lam1,lam2,s,minmax,grouped,block_rows", DENSE_CASES)
+def test_many_token_calls_dequantize_once(qb, oracle, codebook, extra, d_out, d_in, R, lam1, lam2, s, minmax, grouped,
+                                          block_rows):
+    from gpu_util import f32_to_dev, bf16_to_dev, assert_close_bf16, assert_close_f32, OracleWeight
+    T = qb.qblora_dense_min_tokens() + extra
+    print(f"case many tokens T={T} {d_out}x{d_in} R={R} lam=({lam1},{lam2}) minmax={minmax} grouped={grouped} "
+          f"block_rows={block_rows}", flush=True)
+    L = synth.make_layer(1500 + extra + d_out, T, d_out, d_in, max(R, 8), lam1, lam2, b_std=0.2)
+    Wd = f32_to_dev(L.W)
+    if minmax:
+        qw = qb.qblora_quantize_blockwise(Wd, 64, qb.QUANT_MINMAX_INT4, block_rows=block_rows)
+    else:
+        qw = qb.qblora_quantize_blockwise(Wd, 64, qb.QUANT_ABSMAX_CODEBOOK, codebook,
+                                          qb.SCALES_E4M3_GROUPED if grouped else qb.SCALES_FP32, block_rows=block_rows)
+    torch.cuda.synchronize()
+    Wt = OracleWeight(oracle, L.W, codebook, minmax, grouped, block_rows).assert_same(qw).dequantize(oracle, 2)
+    ad = qb.Adapter(bf16_to_dev(L.A), bf16_to_dev(L.B), lam1, lam2, s) if R > 0 else None
+    A, B = (L.A, L.B) if R > 0 else (None, None)
+    X, dY = bf16_to_dev(L.X), bf16_to_dev(L.dY)
+    assert qb.qblora_linear_fwd_workspace_bytes(qw, ad, T) >= 2 * d_out * d_in
+    Y = qb.qblora_linear_fwd(qw, ad, X)
+    dX, dA, dB = qb.qblora_linear_bwd(qw, ad, X, dY, need_grads=R > 0)
+    torch.cuda.synchronize()
+    assert_close_bf16(Y, oracle.forward(Wt, L.X, A, B, lam1, lam2, s if R > 0 else 0.0), "Y")
+    rX, rA, rB = oracle.backward(Wt, L.X, L.dY, A, B, lam1, lam2, s if R > 0 else 0.0)
+    assert_close_bf16(dX, rX, "dX")
+    if R > 0:
+        assert_close_f32(dA, rA, "dA")
+        assert_close_f32(dB, rB, "dB")
+    # the same bf16 weight either way: the form that rebuilds tiles in LDS (which the no-allocation entry point
+    # always takes) gives the same bits
+    Y2 = torch.empty_like(Y)
+    qb.qblora_linear_fwd_noalloc(qw, ad, X, Y2)
+    torch.cuda.synchronize()
+    assert torch.equal(Y.view(torch.int16), Y2.view(torch.int16))
