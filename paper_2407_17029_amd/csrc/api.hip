@@ -595,23 +595,29 @@ int check_qa(const qblora_qweight* qw, const qblora_bf16* H, int32_t lam1, int32
     return QBLORA_OK;
 }
 
-struct QaFwdSpace { float* scales; qblora_bf16 *Ht, *P; size_t bytes; };
+struct QaFwdSpace { float* scales; qblora_bf16 *Ht, *P, *W16; size_t bytes; };
 QaFwdSpace carve_qa_fwd(const qblora_qweight* qw, int lam1, int lam2, int64_t T, void* ws) {
     Carver c(ws);
     QaFwdSpace s{};
-    s.scales = c.take<float>((size_t)((qw->d_out + 255) / 256) * 256 * (qw->d_in / qw->block));
+    if (use_dense(qw, T)) {
+        s.W16 = c.take<qblora_bf16>((size_t)qw->d_out * qw->d_in);
+        if (qw->scale_mode == QBLORA_SCALES_E4M3_GROUPED) s.scales = c.take<float>(n_blocks(qw));
+    } else {
+        s.scales = c.take<float>((size_t)((qw->d_out + 255) / 256) * 256 * (qw->d_in / qw->block));
+    }
     s.Ht = c.take<qblora_bf16>((size_t)(qw->d_out / lam2) * (qw->d_in / lam1));
     s.P = c.take<qblora_bf16>((size_t)T * (qw->d_in / lam1));
     s.bytes = c.off;
     return s;
 }
 
-struct QaBwdSpace { float* scales; qblora_bf16 *P, *dVs, *dVs_lo; float* part; int splits; size_t bytes; };
+struct QaBwdSpace { float* scales; qblora_bf16 *P, *dVs, *dVs_lo, *W16t; float* part; int splits; size_t bytes; };
 QaBwdSpace carve_qa_bwd(const qblora_qweight* qw, int lam1, int lam2, int64_t T, void* ws) {
     Carver c(ws);
     QaBwdSpace s{};
     const int I = qw->d_in / lam1, J = qw->d_out / lam2;
     if (qw->scale_mode == QBLORA_SCALES_E4M3_GROUPED) s.scales = c.take<float>(n_blocks(qw));
+    if (use_dense(qw, T)) s.W16t = c.take<qblora_bf16>((size_t)qw->d_out * qw->d_in);
     s.P = c.take<qblora_bf16>((size_t)T * I);
     s.dVs = c.take<qblora_bf16>((size_t)T * J);
     s.dVs_lo = c.take<qblora_bf16>((size_t)T * J);
@@ -653,8 +659,14 @@ int qablora_linear_fwd(const qblora_qweight* qw, const qblora_bf16* H, int32_t l
     if (grouped) { sct.scale_codes = qw->scale_codes; sct.scale_step = qw->scale_step; sct.scale_mid = qw->scale_mid; }
     sct.scale_group = qw->scale_group; sct.d_out = qw->d_out; sct.d_in = qw->d_in; sct.out = ws.scales;
     const bool tile8 = block_rows_of(qw) == 8;               // 8 x 8 blocks: scales are read in place
-    if (tile8) sct.out = nullptr;
-    if ((rc = launch_adapter_prep(H, H, I, J, J, 1, 1, ws.Ht, nullptr, nullptr, st, &sct))) return rc;
+    const bool dense = use_dense(qw, T);                     // many tokens: the weight is dequantized once
+    if (tile8 || dense) sct.out = nullptr;
+    if ((rc = launch_adapter_prep(H, H, I, J, J, 1, 1, ws.Ht, nullptr, nullptr, st, sct.out ? &sct : nullptr))) return rc;
+    if (dense) {
+        const float* plain = nullptr;
+        if ((rc = resolve_scales(qw, ws.scales, st, &plain))) return rc;
+        if ((rc = launch_dequantize_operand(*qw, plain, 0, ws.W16, st))) return rc;
+    }
     // s * AvgPool_lambda1(X)
     if ((rc = launch_pool_rows(X, T, qw->d_in, lambda1, s / (float)lambda1, ws.P, nullptr, st))) return rc;
 
@@ -662,6 +674,7 @@ int qablora_linear_fwd(const qblora_qweight* qw, const qblora_bf16* H, int32_t l
     g.qmode = 1;
     g.scales = nullptr; g.scales_tiled = ws.scales;
     if (tile8) { g.scales = qw->scales; g.scales_tiled = nullptr; g.block_rows = 8; }
+    if (dense) { g.qmode = 3; g.W1 = ws.W16; g.K1 = qw->d_in; }
     g.X2 = ws.P; g.ldx2 = I; g.W2 = ws.Ht; g.ldw2 = I; g.K2 = I; g.div2 = lambda2;
     g.X1 = X; g.ldx1 = qw->d_in;
     g.codes = qw->codes; g.beta = qw->beta; g.d_out = qw->d_out; g.d_in = qw->d_in; g.cb = codebook_of(qw);
@@ -708,6 +721,10 @@ int qablora_linear_bwd(const qblora_qweight* qw, const qblora_bf16* H, int32_t l
     g.qmode = 2;
     g.block_rows = block_rows_of(qw);
     if ((rc = resolve_scales(qw, ws.scales, st, &g.scales))) return rc;
+    if (use_dense(qw, T)) {
+        if ((rc = launch_dequantize_operand(*qw, g.scales, 1, ws.W16t, st))) return rc;
+        g.qmode = 3; g.W1 = ws.W16t; g.K1 = qw->d_out;
+    }
     g.X2 = ws.dVs; g.ldx2 = J; g.W2 = H; g.ldw2 = J; g.K2 = J; g.div2 = lambda1;
     g.X1 = dY; g.ldx1 = qw->d_out;
     g.codes = qw->codes; g.beta = qw->beta; g.d_out = qw->d_out; g.d_in = qw->d_in; g.cb = codebook_of(qw);
