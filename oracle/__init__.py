@@ -15,7 +15,10 @@ import numpy as np
 
 _DIR = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_DIR, "qblora_oracle.cpp")
-_LIB = os.path.join(_DIR, "libqblora_oracle.so")
+# ORACLE_SANITIZE=1 selects a build of its own under AddressSanitizer + UndefinedBehaviorSanitizer (host code
+# only; run the CPU tests with the sanitizer runtimes preloaded, see README)
+_SANITIZE = os.environ.get("ORACLE_SANITIZE", "") not in ("", "0")
+_LIB = os.path.join(_DIR, "libqblora_oracle_san.so" if _SANITIZE else "libqblora_oracle.so")
 _lib = None
 
 
@@ -24,6 +27,8 @@ def build(force: bool = True) -> str:
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-pthread", "-ffp-contract=off",
                "-fno-fast-math", "-o", _LIB, _SRC]
+        if _SANITIZE:
+            cmd[1:2] = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-omit-frame-pointer"]
         subprocess.run(cmd, check=True)
     return _LIB
 
