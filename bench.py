@@ -520,6 +520,37 @@ def bench_decode():
         del W, qw, pack
 
 
+def bench_midbatch():
+    """16 < T <= 256 on the merged INT4 model (packed) and on a codebook base (row-major): time against the two
+    floors of the regime, the weight stream from HBM and the bf16 MFMA work."""
+    cb = synth.codebook_nf4_style()
+    for d_out, d_in in SHAPES:
+        W = torch.randn(d_out, d_in, device=DEV) * 0.02
+        for base in ("int4 packed", "codebook row-major"):
+            if base == "int4 packed":
+                qw = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_MINMAX_INT4, tiled=False)
+                pack = qb.qblora_decode_pack(qw)
+            else:
+                qw = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_ABSMAX_CODEBOOK, cb, tiled=False)
+                pack = None
+            q = qw.c_struct()
+            for T in (32, 64, 128, 256):
+                X = torch.randn(T, d_in, device=DEV).to(torch.bfloat16)
+                Y = torch.empty(T, d_out, dtype=torch.bfloat16, device=DEV)
+                need = int(qb.lib().qblora_linear_decode_tokens_workspace_bytes(C.byref(q), T))
+                ws = torch.empty(max(need, 256), dtype=torch.uint8, device=DEV)
+                args = (C.byref(q), qb._ptr(pack), qb._ptr(X), T, qb._ptr(Y), qb._ptr(ws), ws.numel(), qb._stream())
+                s = timed(lambda: qb.lib().qblora_linear_decode(*args), iters=30)
+                nbytes = d_out * d_in * (0.5 + (8 if qw.beta is not None else 4) / 64) + 2 * T * (d_in + d_out)
+                flops = 2.0 * T * d_in * d_out
+                emit(kernel="w4_mid", base=base, shape=[d_out, d_in], T=T, us=round(s * 1e6, 1),
+                     GBps=round(nbytes / s / 1e9, 1), frac_hbm=round(nbytes / s / 1e9 / HBM_PEAK_GBS, 3),
+                     TFLOPs=round(flops / s / 1e12, 1), frac_mfma=round(flops / s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 3),
+                     partial_bytes=need)
+            del qw, pack
+        del W
+
+
 def bench_qablora():
     cb = synth.codebook_nf4_style()
     T, d_out, d_in = 8192, 4096, 4096
@@ -595,7 +626,8 @@ def side_measurements(which):
     g = globals()
     g.update(C=ctypes, np=numpy, torch=torch, qb=binding, synth=synth_mod)
     del _SIDE[:]
-    table = {"quantize": bench_quantize, "merge": bench_merge, "decode": bench_decode, "qablora": bench_qablora,
+    table = {"quantize": bench_quantize, "merge": bench_merge, "decode": bench_decode, "midbatch": bench_midbatch,
+             "qablora": bench_qablora,
              "tile8": bench_tile8}
     for w in which:
         table[w]()
@@ -613,7 +645,7 @@ def main() -> int:
     ap.add_argument("--cpu-sample-rows", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the other workloads (the `configs` object)")
-    ap.add_argument("--side", default="quantize,merge,decode,qablora,tile8",
+    ap.add_argument("--side", default="quantize,merge,decode,midbatch,qablora,tile8",
                     help="comma-separated side measurements reported under `side` (streaming kernels on the large shapes, "
                          "small-batch inference, single-matrix adapter, 8 x 8 blocks); empty string = none")
     ap.add_argument("--plain-events", action="store_true",

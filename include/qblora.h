@@ -324,17 +324,26 @@ int qblora_merge_bf16(const qblora_qweight* base, const float* H, int32_t lambda
 /*
  * Small-batch forward of a quantized layer without adapter -- inference on the INT4 model that
  * qablora_merge_quantize produces (Sec. 3.3: the fine-tuned model is deployed in 4 bits), or on any
- * other qblora_qweight, for 1 <= T <= 16 tokens (decode batches):
+ * other qblora_qweight, for 1 <= T <= 256 tokens.
+ * 1 <= T <= 16 (decode batches), bound by the weight stream from HBM:
  *   Y[t,n] = sum_b ( alpha[n,b] * sum_{k in block b} X[t,k] * bf16(c[code[n,k]]) + beta[n,b] * sum_{k in b} X[t,k] ),
  * fp32 accumulation.  Scale and offset act on the block sums, so the weight itself is never rounded to
  * 16 bits; for the integer codebook of INT4 models bf16(c) = c and the result is Eq. 1 contracted in
  * fp32.  It differs from qblora_linear_fwd without adapter (which contracts the bf16-rounded weight)
  * by that rounding only.
+ * 16 < T <= 256 (mid batch: prefill chunks, batched decode), in chunks of at most 128 tokens:
+ *   Y[t,n] = sum_k X[t,k] * bf16( c[code[n,k]] * alpha (+ beta) ),
+ * the arithmetic of qblora_linear_fwd without adapter (Eq. 1 rounded once to the bf16 compute weight, fp32
+ * accumulation), on token tiles of 32 / 64 / 128 with the input dimension split over workgroups; the fp32
+ * partial tiles of the splits are added in a fixed order (reproducible bit for bit).
  *   X bf16 [T, d_in], 16-byte aligned; Y bf16 [T, d_out], fully overwritten.
- *   workspace: qblora_linear_decode_workspace_bytes() bytes (non-zero only for grouped scales).
- * T = 0 is a no-op; T > 16 is QBLORA_ERR_SHAPE (use qblora_linear_fwd).
+ *   workspace: T <= 16: qblora_linear_decode_workspace_bytes() bytes (non-zero only for grouped scales, and
+ *   not needed with a pack); T > 16: qblora_linear_decode_tokens_workspace_bytes(qw, T) bytes, 16-byte aligned
+ *   (the former plus the partial tiles).
+ * T = 0 is a no-op; T > 256 is QBLORA_ERR_SHAPE (use qblora_linear_fwd).
  */
 size_t qblora_linear_decode_workspace_bytes(const qblora_qweight* qw);
+size_t qblora_linear_decode_tokens_workspace_bytes(const qblora_qweight* qw, int32_t T);
 int qblora_linear_decode(const qblora_qweight* qw, const void* pack, const qblora_bf16* X, int32_t T, qblora_bf16* Y,
                          void* workspace, size_t workspace_bytes, void* stream);
 
@@ -344,7 +353,8 @@ int qblora_linear_decode(const qblora_qweight* qw, const void* pack, const qblor
  * fp32 block scales (grouped scales are reconstructed) and the offsets in tile order (rows in tiles of
  * 256; the values of one block for the rows of a tile are adjacent), so that a wave's load of one block
  * for 16 rows touches 5 cache lines instead of 32.  qblora_linear_decode with pack = NULL reads the
- * row-major arrays of `qw` (the same sums, 2-3 times slower on large layers); with a pack it needs no workspace.
+ * row-major arrays of `qw` (the same sums, 2-3 times slower on large layers); with a pack a call of at most
+ * 16 tokens needs no workspace.
  * A pack belongs to the description it was made from: pass the same `qw` (codebook, offsets, block shape)
  * to qblora_linear_decode.  For an INT4 model -- codebook exactly 0, 1, ..., 15 with offsets, 64-blocks, the
  * output of the min-max quantizer and of qablora_merge_quantize -- the pack also regroups the nibbles of

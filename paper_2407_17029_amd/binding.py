@@ -29,7 +29,7 @@ EXPORTS = ["qblora_quantize_blockwise", "qblora_dequantize_bf16", "qblora_linear
            "qblora_saved_bytes", "qblora_linear_fwd_save", "qblora_linear_bwd_saved",
            "qablora_linear_fwd_workspace_bytes", "qablora_linear_bwd_workspace_bytes", "qablora_linear_fwd",
            "qablora_linear_bwd", "qblora_merge_bf16",
-           "qblora_linear_decode_workspace_bytes", "qblora_linear_decode",
+           "qblora_linear_decode_workspace_bytes", "qblora_linear_decode_tokens_workspace_bytes", "qblora_linear_decode",
            "qblora_decode_pack_bytes", "qblora_decode_pack",
            "qblora_noalloc_scratch_bytes", "qblora_linear_fwd_noalloc", "qblora_dense_min_tokens"]
 
@@ -100,6 +100,8 @@ def lib():
         L.qblora_merge_bf16.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p]
         L.qblora_linear_decode_workspace_bytes.restype = C.c_size_t
         L.qblora_linear_decode_workspace_bytes.argtypes = [C.c_void_p]
+        L.qblora_linear_decode_tokens_workspace_bytes.restype = C.c_size_t
+        L.qblora_linear_decode_tokens_workspace_bytes.argtypes = [C.c_void_p, C.c_int32]
         L.qblora_linear_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
                                            C.c_void_p]
         L.qblora_decode_pack_bytes.restype = C.c_size_t
@@ -498,13 +500,13 @@ def qblora_decode_pack(qw: QWeight) -> torch.Tensor:
 
 def qblora_linear_decode(qw: QWeight, X: torch.Tensor, Y: torch.Tensor = None, workspace: torch.Tensor = None,
                          pack: torch.Tensor = None):
-    """Small-batch (T <= 16) forward of a quantized layer without adapter."""
+    """Small- and mid-batch (T <= 256) forward of a quantized layer without adapter."""
     assert X.is_cuda and X.dtype == torch.bfloat16 and X.is_contiguous() and X.shape[1] == qw.d_in
     T = X.shape[0]
     if Y is None:
         Y = torch.empty((T, qw.d_out), dtype=torch.bfloat16, device=X.device)
     q = qw.c_struct()
-    ws = _workspace(int(lib().qblora_linear_decode_workspace_bytes(C.byref(q))), X.device, workspace)
+    ws = _workspace(int(lib().qblora_linear_decode_tokens_workspace_bytes(C.byref(q), T)), X.device, workspace)
     rc = lib().qblora_linear_decode(C.byref(q), _ptr(pack), _ptr(X), T, _ptr(Y), _ptr(ws), ws.numel(), _stream())
     _check(rc, "qblora_linear_decode")
     return Y

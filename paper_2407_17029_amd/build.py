@@ -8,7 +8,7 @@ import subprocess
 _DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_DIR, "csrc")
 LIB = os.path.join(_DIR, "libqblora.so")
-SOURCES = ["api.hip", "quantize.hip", "prep.hip", "qgemm.hip", "qlinear.hip", "skinny.hip", "grads.hip", "merge.hip", "pool.hip", "decode.hip", "tileprod.hip"]
+SOURCES = ["api.hip", "quantize.hip", "prep.hip", "qgemm.hip", "qlinear.hip", "skinny.hip", "grads.hip", "merge.hip", "pool.hip", "decode.hip", "w4mid.hip", "tileprod.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

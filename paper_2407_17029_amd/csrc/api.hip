@@ -1,5 +1,6 @@
 // C-ABI entry points (include/qblora.h): host-side validation, workspace layout and kernel
 // sequencing.  Every step of the method runs in the kernels; nothing here touches tensor data.
+#include <algorithm>
 #include <cstring>
 #include <mutex>
 
@@ -833,6 +834,9 @@ int qblora_merge_bf16(const qblora_qweight* base, const float* H, int32_t lambda
 namespace {
 
 struct DecodePack { uint8_t* codes; float* scales; float* beta; size_t bytes; };
+constexpr int32_t kDecodeMaxTokens = 16;     // up to here: the streaming kernel that scales block sums
+constexpr int32_t kMidChunk = 128;           // above: the bf16 compute weight, at most this many tokens per launch
+constexpr int32_t kMidMaxTokens = 256;
 
 // An INT4 model in 64-blocks (codebook exactly 0, 1, ..., 15 and offsets present): its pack holds the codes
 // with the nibbles of every dword regrouped for the table-free decode kernel.  Pack and decode both decide
@@ -893,29 +897,56 @@ size_t qblora_linear_decode_workspace_bytes(const qblora_qweight* qw) {
     if (check_qweight(qw, false, true)) return 0;
     return qw->scale_mode == QBLORA_SCALES_E4M3_GROUPED ? align_up(sizeof(float) * (size_t)n_blocks(qw)) : 0;
 }
-
+size_t qblora_linear_decode_tokens_workspace_bytes(const qblora_qweight* qw, int32_t T) {
+    if (check_qweight(qw, false, true)) return 0;
+    size_t part = 0;
+    for (int32_t t0 = kDecodeMaxTokens < T ? 0 : T; t0 < T; t0 += kMidChunk)        // chunks of the mid-batch form
+        part = std::max(part, w4_mid_part_bytes(qw->d_out, qw->d_in, std::min(kMidChunk, T - t0)));
+    return qblora_linear_decode_workspace_bytes(qw) + align_up(part);
+}
 int qblora_linear_decode(const qblora_qweight* qw, const void* pack, const qblora_bf16* X, int32_t T, qblora_bf16* Y,
                          void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_qweight(qw, true, true);
     if (rc) return rc;
-    if (T < 0 || T > 16) return QBLORA_ERR_SHAPE;
+    if (T < 0 || T > kMidMaxTokens) return QBLORA_ERR_SHAPE;
     if (T == 0) return QBLORA_OK;
     if (!X || !Y) return QBLORA_ERR_NULL;
     if (qw->d_in % 8 != 0 || (reinterpret_cast<uintptr_t>(X) & 15) || (reinterpret_cast<uintptr_t>(qw->codes) & 15) ||
         (reinterpret_cast<uintptr_t>(pack) & 255))
         return QBLORA_ERR_SHAPE;
     hipStream_t st = as_stream(stream);
+    const bool mid = T > kDecodeMaxTokens;
+    const size_t scale_bytes = qblora_linear_decode_workspace_bytes(qw);
+    const size_t need = mid ? qblora_linear_decode_tokens_workspace_bytes(qw, T) : (pack ? 0 : scale_bytes);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return QBLORA_ERR_WORKSPACE;
+    if (mid && need > scale_bytes && (reinterpret_cast<uintptr_t>(workspace) & 15)) return QBLORA_ERR_WORKSPACE;
+    // the mid-batch kernel stores 8-byte words and, with 8 x 8 blocks, loads four block parameters at a time
+    if (mid && ((reinterpret_cast<uintptr_t>(Y) & 7) || qw->d_in % kBlock != 0 ||
+                (block_rows_of(qw) == 8 && ((reinterpret_cast<uintptr_t>(qw->scales) & 15) ||
+                                            (reinterpret_cast<uintptr_t>(qw->beta) & 15)))))
+        return QBLORA_ERR_SHAPE;
+    const uint8_t* codes = qw->codes;
+    const float* scales = nullptr;
+    const float* beta = qw->beta;
+    const int regrouped = pack ? decode_regrouped(qw) : 0;
     if (pack) {
         DecodePack p = carve_pack(qw, const_cast<void*>(pack));
-        return launch_w4_decode(p.codes, p.scales, p.beta, codebook_of(qw), 1, qw->d_out, qw->d_in, X, T, Y, st,
-                                block_rows_of(qw), decode_regrouped(qw));
+        codes = p.codes; scales = p.scales; beta = p.beta;
+    } else if ((rc = resolve_scales(qw, static_cast<float*>(workspace), st, &scales))) {
+        return rc;
     }
-    const float* scales = nullptr;
-    const size_t need = qblora_linear_decode_workspace_bytes(qw);
-    if (need > 0 && (!workspace || workspace_bytes < need)) return QBLORA_ERR_WORKSPACE;
-    if ((rc = resolve_scales(qw, static_cast<float*>(workspace), st, &scales))) return rc;
-    return launch_w4_decode(qw->codes, scales, qw->beta, codebook_of(qw), 0, qw->d_out, qw->d_in, X, T, Y, st,
-                            block_rows_of(qw));
+    if (!mid)
+        return launch_w4_decode(codes, scales, beta, codebook_of(qw), pack ? 1 : 0, qw->d_out, qw->d_in, X, T, Y, st,
+                                block_rows_of(qw), regrouped);
+    float* part = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + scale_bytes);
+    for (int32_t t0 = 0; t0 < T; t0 += kMidChunk) {
+        const int32_t tc = std::min(kMidChunk, T - t0);
+        if ((rc = launch_w4_mid(codes, scales, beta, codebook_of(qw), pack ? 1 : 0, qw->d_out, qw->d_in,
+                                X + (int64_t)t0 * qw->d_in, tc, Y + (int64_t)t0 * qw->d_out,
+                                w4_mid_part_bytes(qw->d_out, qw->d_in, tc) ? part : nullptr, st, block_rows_of(qw), regrouped)))
+            return rc;
+    }
+    return QBLORA_OK;
 }
 
 }  // extern "C"

@@ -170,6 +170,13 @@ int launch_merge_bf16(const MergeDesc& d, hipStream_t st);
 int launch_tile_product(const qblora_bf16* A, const qblora_bf16* B, int rows, int cols, int R, float* H, hipStream_t st);
 int launch_w4_decode(const uint8_t* codes, const float* scales, const float* beta, const Codebook& cb, int tiled,
                      int d_out, int d_in, const qblora_bf16* X, int T, qblora_bf16* Y, hipStream_t st, int block_rows = 1, int regrouped = 0);
+// The same layer for 1 <= T <= 128 tokens on the bf16 compute weight (w4mid.hip); `part` holds
+// w4_mid_part_bytes() bytes of split-K partial tiles (may be NULL when that is 0)
+int w4_mid_splits(int d_out, int d_in, int T);
+size_t w4_mid_part_bytes(int d_out, int d_in, int T);
+int launch_w4_mid(const uint8_t* codes, const float* scales, const float* beta, const Codebook& cb, int tiled, int d_out,
+                  int d_in, const qblora_bf16* X, int T, qblora_bf16* Y, float* part, hipStream_t st, int block_rows = 1,
+                  int regrouped = 0);
 int launch_merge_beta_shift(const MergeDesc& d, hipStream_t st);
 
 }  // namespace qblora

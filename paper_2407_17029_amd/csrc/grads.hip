@@ -193,11 +193,16 @@ __global__ __launch_bounds__(kTrThreads) void k_grad_tr(GradPair p) {
     const GradDesc& d = second ? p.b : p.a;
     const int64_t slice_len = second ? p.slice_b : p.slice_a;
     const int bid = (int)blockIdx.x - (second ? p.n_a : 0);
-    // Consecutive workgroups go to different XCDs; the token slice varies fastest so that (with 8
-    // slices) all workgroups that stream one slice of S share one XCD's L2.
-    const int tiles_i = (d.I + BI - 1) / BI;
-    const int z = bid % d.splits, rest = bid / d.splits;
-    const int i0 = (rest % tiles_i) * BI, j0 = (rest / tiles_i) * BJ;
+    // Consecutive workgroup ids go to different XCDs (id % 8).  The column tiles of one (row tile, token
+    // slice) read the same stream of L, the wide operand: they get ids 8 apart inside a run of 8 * tiles_j
+    // ids, so they start together on one XCD and its L2 fetches L once for all of them.  The grid is
+    // rounded up to whole runs; ids past the last (row tile, slice) leave.
+    const int tiles_i = (d.I + BI - 1) / BI, tiles_j = (d.J + BJ - 1) / BJ;
+    const int run = bid / (8 * tiles_j), within = bid % (8 * tiles_j);
+    const int unit = run * 8 + (within & 7);
+    if (unit >= tiles_i * d.splits) return;
+    const int z = unit % d.splits;
+    const int i0 = (unit / d.splits) * BI, j0 = (within >> 3) * BJ;
     const int64_t t_begin = (int64_t)z * slice_len;
     int64_t t_end = t_begin + slice_len;
     if (t_end > d.T) t_end = d.T;
@@ -483,8 +488,9 @@ int64_t slice_of(const GradDesc& d) {
     return (slice_len + BT - 1) / BT * BT;
 }
 
-unsigned tr_blocks(const GradDesc& d) {
-    return (unsigned)(((d.I + BI - 1) / BI) * ((d.J + BJ - 1) / BJ) * d.splits);
+unsigned tr_blocks(const GradDesc& d) {              // whole runs of 8 (row tile, slice) units x column tiles
+    const unsigned units = (unsigned)(((d.I + BI - 1) / BI) * d.splits);
+    return (units + 7) / 8 * 8 * (unsigned)((d.J + BJ - 1) / BJ);
 }
 
 // partial sums of one or two gradients on the copy path (both with or both without a low-order part)

@@ -95,7 +95,14 @@ def test_host_validation_of_the_later_entry_points(qb):
     assert L.qblora_merge_bf16(C.byref(qw), dummy, 2, 2, f, None, None) == -1
     assert L.qblora_merge_bf16(C.byref(qw), dummy, 5, 2, f, dummy, None) == -2
     # small-batch inference
-    assert L.qblora_linear_decode(C.byref(qw), None, dummy, 17, dummy, None, 0, None) == -2               # T > 16
+    assert L.qblora_linear_decode(C.byref(qw), None, dummy, 257, dummy, None, 0, None) == -2              # T > 256
+    assert L.qblora_linear_decode_tokens_workspace_bytes(C.byref(qw), 16) == L.qblora_linear_decode_workspace_bytes(C.byref(qw))
+    big_qw = qb.CQWeight()
+    big_qw.d_out, big_qw.d_in, big_qw.block = 4096, 4096, 64
+    big_qw.codes = big_qw.scales = 0x1000
+    need = L.qblora_linear_decode_tokens_workspace_bytes(C.byref(big_qw), 64)                            # split partial tiles
+    assert need >= 2 * 64 * 4096 * 4 and need % 256 == 0
+    assert L.qblora_linear_decode(C.byref(big_qw), None, dummy, 64, dummy, dummy, need - 1, None) == -4
     assert L.qblora_linear_decode(C.byref(qw), None, None, 4, dummy, None, 0, None) == -1
     assert L.qblora_linear_decode(C.byref(qw), None, dummy, 0, dummy, None, 0, None) == 0
     assert L.qblora_linear_decode(C.byref(qw), C.c_void_p(0x1010), dummy, 4, dummy, None, 0, None) == -2   # pack alignment

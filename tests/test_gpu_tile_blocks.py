@@ -160,7 +160,7 @@ def test_quantization_aware_loop_on_8x8_blocks(qb, oracle, T, d_out, d_in, lam1,
     assert np.sqrt((err ** 2).mean()) <= 5e-3 * rms and err.max() <= 4e-2 * rms
 
 
-@pytest.mark.parametrize("T", [1, 5, 16])
+@pytest.mark.parametrize("T", [1, 5, 16, 40, 130])       # above 16: the mid-batch form of the same call
 @pytest.mark.parametrize("d_out,d_in,minmax", [(512, 1024, True), (328, 832, True), (256, 512, False)])
 def test_small_batch_inference_on_8x8_blocks(qb, oracle, codebook, T, d_out, d_in, minmax):
     """Merged-model inference (Sec. 3.3) on 8 x 8 blocks: the small-batch kernel contracts the bf16 compute
