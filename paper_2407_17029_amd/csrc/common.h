@@ -163,6 +163,7 @@ struct MergeDesc {
     uint8_t* codes_out; float* alpha_out; float* beta_out;
     qblora_bf16* w16_out;                  // 16-bit merge only
     int block_rows;                        // 1 or 8 (offset-shift merge only)
+    uint32_t kgroups_magic;                // set by the launcher: reciprocal for the tile index arithmetic
 };
 int launch_merge_requant(const MergeDesc& d, hipStream_t st);
 int launch_merge_bf16(const MergeDesc& d, hipStream_t st);

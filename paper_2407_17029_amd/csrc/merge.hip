@@ -7,7 +7,12 @@
 //
 // Requantize tiling: a workgroup of 512 threads owns 64 output rows x 256 input columns and every
 // thread owns half (32 elements) of one 64-block; the block minimum and maximum are combined over
-// the two lanes with DPP.  The kernel is bound by vector instructions as much as by HBM: one thread
+// the two lanes with DPP.  Measured on a 22016 x 8192 weight, lambda 2 (95 us): without the arithmetic 93 us,
+// without the fetches of H 55, without the stores 51, with neither H nor arithmetic 48 -- the fetches of H (128
+// byte pieces 44 KB apart) and the stores (128 byte pieces 4 KB apart, block parameters 16 bytes per row) each
+// cost as much as everything else together; a variant that walks eight tiles per workgroup with the next
+// tile's loads in flight and stores whole lines of block parameters was slower (fewer waves).  With lambda 8
+// (H a sixteenth of the bytes) the vector ALU is the limit: one thread
 // per block (64 elements) keeps the per-thread overhead (addresses, the two divisions of a block)
 // lowest but gives only 4 waves per SIMD over a 4096 x 4096 weight, all resident at once and moving
 // through load, compute and store phases in lockstep; a quarter block per thread overlaps those
@@ -30,11 +35,19 @@ struct TileGeom {
     int hrow0, hrows, hcol0, hcols;
 };
 
-__device__ __forceinline__ TileGeom tile_geom(const MergeDesc& d, int n0, int k0) {
+// x / lam with the division spelled out only where it is one: lam a power of two (shift >= 0) shifts.  Integer
+// division has no instruction on this chip; even for a workgroup-uniform value it expands to some fifteen
+// vector instructions, and the tile arithmetic below had seven of them -- a fifth of the kernel's issue slots.
+__device__ __forceinline__ int div_by(int x, int lam, int shift) { return shift >= 0 ? x >> shift : x / lam; }
+__device__ __forceinline__ int shift_of(int lam) { return (lam & (lam - 1)) == 0 ? 31 - __builtin_clz(lam) : -1; }
+
+template <int L1>
+__device__ __forceinline__ TileGeom tile_geom(const MergeDesc& d, int n0, int k0, int sh2) {
     TileGeom g;
     int k1 = min(k0 + KT, d.d_in) - 1, n1 = min(n0 + NT, d.d_out) - 1;
-    g.hrow0 = k0 / d.lam1; g.hrows = k1 / d.lam1 - g.hrow0 + 1;
-    g.hcol0 = n0 / d.lam2; g.hcols = n1 / d.lam2 - g.hcol0 + 1;
+    if constexpr (L1 > 0) { g.hrow0 = k0 / L1; g.hrows = k1 / L1 - g.hrow0 + 1; }
+    else { g.hrow0 = k0 / d.lam1; g.hrows = k1 / d.lam1 - g.hrow0 + 1; }
+    g.hcol0 = div_by(n0, d.lam2, sh2); g.hcols = div_by(n1, d.lam2, sh2) - g.hcol0 + 1;
     return g;
 }
 
@@ -76,7 +89,9 @@ __global__ __launch_bounds__(kMergeThreads) void k_merge_requant(MergeDesc d) {
     const int kgroups = (ktiles + 7) >> 3;
     const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
     const int group = (seq >> 3) * 8 + xcd;
-    const int kt = (group % kgroups) * 8 + (seq & 7), nt = group / kgroups;
+    // group / kgroups by the host's reciprocal (exact for group < 2^24, kgroups < 2^8: the launcher checks)
+    const int nt = kgroups == 1 ? group : (int)__umulhi((uint32_t)group, d.kgroups_magic);
+    const int kt = (group - nt * kgroups) * 8 + (seq & 7);
     if (kt >= ktiles || nt >= ntiles) return;
     const int k0 = kt * KT, n0 = nt * NT;
     const int row = t >> 3, bk = (t >> 1) & 3, sub = t & 1;
@@ -91,16 +106,22 @@ __global__ __launch_bounds__(kMergeThreads) void k_merge_requant(MergeDesc d) {
     if (live) {
         blk = (int64_t)n * bpr + k / kBlock;
         cq = *reinterpret_cast<const uint4*>(d.codes + ((int64_t)n * d.d_in + k) / 2);
-        if constexpr (GROUPED) a = grouped_scale(d.scale_codes, d.scale_step, d.scale_mid, blk, d.scale_group);
-        else a = d.scales[blk];
+        if constexpr (GROUPED) {
+            const int gs = shift_of(d.scale_group);
+            const int64_t grp = gs >= 0 ? blk >> gs : blk / d.scale_group;
+            a = __fmaf_rn(e4m3_to_float(d.scale_codes[blk]), d.scale_step[grp], d.scale_mid[grp]);   // = grouped_scale()
+        } else {
+            a = d.scales[blk];
+        }
         if constexpr (BETA) b = d.beta[blk];
     }
 
     // stage the deltas of the tile: delta = (s*H)/lambda1, a division unless lambda1 is one of the
     // powers of two with a code path of their own, where multiplying by the (exact) reciprocal gives
     // the same bits
-    const TileGeom g = tile_geom(d, n0, k0);
-    const int ldH = d.d_out / d.lam2, stride = delta_stride<L1>(d.lam1);
+    const int sh2 = shift_of(d.lam2);
+    const TileGeom g = tile_geom<L1>(d, n0, k0, sh2);
+    const int ldH = div_by(d.d_out, d.lam2, sh2), stride = delta_stride<L1>(d.lam1);
     if (t < 16) lut[t] = d.cb.c[t];
     const float lam1f = (float)d.lam1;
     auto delta_of = [&](float h) __attribute__((always_inline)) {
@@ -133,7 +154,7 @@ __global__ __launch_bounds__(kMergeThreads) void k_merge_requant(MergeDesc d) {
     // w' = w~ + delta for the 32 elements of the half
     float w[32];
     const uint32_t cw[4] = {cq.x, cq.y, cq.z, cq.w};
-    const int c = n / d.lam2 - g.hcol0;
+    const int c = div_by(n, d.lam2, sh2) - g.hcol0;
     auto element = [&](int j, float de) __attribute__((always_inline)) {
         const float cv = lut[(cw[j >> 3] >> (4 * (j & 7))) & 15];
         const float wt = BETA ? __fmaf_rn(cv, a, b) : __fmul_rn(cv, a);
@@ -228,14 +249,17 @@ int launch_requant_l1(const MergeDesc& d, hipStream_t st) {
     const size_t smem = sizeof(float) * (size_t)delta_stride<L1>(d.lam1) * hcols;
     // one id per (group of eight k-tiles, member), groups dealt round-robin to the eight XCDs
     const int64_t groups = (int64_t)(((d.d_in + KT - 1) / KT + 7) / 8) * ((d.d_out + NT - 1) / NT);
-    if (groups > (int64_t)1 << 24) return QBLORA_ERR_UNSUPPORTED;
+    const int64_t kgroups = ((d.d_in + KT - 1) / KT + 7) / 8;
+    if (groups > (int64_t)1 << 24 || kgroups >= 256) return QBLORA_ERR_UNSUPPORTED;
+    MergeDesc dd = d;
+    dd.kgroups_magic = kgroups > 1 ? (uint32_t)((((uint64_t)1 << 32) / (uint64_t)kgroups) + 1) : 0u;
     dim3 grid((unsigned)(((groups + 7) / 8) * 64));
     auto launch = [&](auto kern) -> int {
         if (smem > 48 * 1024 &&
             hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)smem) != hipSuccess)
             return QBLORA_ERR_LAUNCH;
-        hipLaunchKernelGGL(kern, grid, dim3(kMergeThreads), smem, st, d);
+        hipLaunchKernelGGL(kern, grid, dim3(kMergeThreads), smem, st, dd);
         return launch_status();
     };
     if (d.scale_codes)

@@ -56,6 +56,50 @@ __device__ __forceinline__ uint32_t codes4_codebook(const float4& w, float a, co
     return c0 | (c1 << 4) | (c2 << 8) | (c3 << 12);
 }
 
+// The same bisection with the thresholds of the lower three levels in LDS instead of registers: choosing a
+// register by the earlier outcomes takes 1 + 3 + 7 select instructions per weight, and with the compares
+// and the assembly of the code the register form spends 24 vector instructions per weight, which makes the
+// kernel issue-bound, not HBM-bound.  Here a level is: one LDS read at (base + 4 * path), one compare, one
+// add-with-carry that appends the outcome to the path (path = 2 * path + (x > t)); after four levels the path
+// is the code.  Level l of a block's tree is an array of 2^(l-1) thresholds, [t3, t11], [t1, t5, t9, t13],
+// [t0, t2, ..., t14]; the root t7 stays in a register.
+// Level arrays of the 16 blocks of a wave side by side: [block][position], so that the 16 quads of a wave read
+// different banks on levels 2 and 3 (32 and 64 words) and each half-wave does on level 4 (128 words).
+struct WaveTrees {
+    float2 l2[16]; float4 l3[16]; float4 l4[16][2];
+};
+__device__ __forceinline__ void append_gt(uint32_t& path, float x, float t) {
+    asm("v_cmp_gt_f32_e32 vcc, %1, %2\n\tv_addc_co_u32_e32 %0, vcc, %0, %0, vcc" : "+v"(path) : "v"(x), "v"(t) : "vcc");
+}
+struct BlockTree {                       // the three level arrays of one block
+    const float* l2; const float* l3; const float* l4;
+};
+__device__ __forceinline__ uint32_t code_by_tree(float x, float t7, const BlockTree& tree) {
+    uint32_t path = x > t7 ? 1u : 0u;
+    append_gt(path, x, tree.l2[path]);
+    append_gt(path, x, tree.l3[path]);
+    append_gt(path, x, tree.l4[path]);
+    return path;
+}
+// thresholds t_j = m_j * a of block j into the wave's trees (every lane of the block writes the same values);
+// returns t7
+__device__ __forceinline__ float build_tree(WaveTrees& w, int j, float a, const Midpoints& mp, BlockTree& tree) {
+    auto t = [&](int i) { return __fmul_rn(mp.m[i], a); };
+    w.l2[j] = make_float2(t(3), t(11));
+    w.l3[j] = make_float4(t(1), t(5), t(9), t(13));
+    w.l4[j][0] = make_float4(t(0), t(2), t(4), t(6));
+    w.l4[j][1] = make_float4(t(8), t(10), t(12), t(14));
+    tree.l2 = reinterpret_cast<const float*>(&w.l2[j]);
+    tree.l3 = reinterpret_cast<const float*>(&w.l3[j]);
+    tree.l4 = reinterpret_cast<const float*>(&w.l4[j][0]);
+    return t(7);
+}
+__device__ __forceinline__ uint32_t codes4_by_tree(const float4& w, float t7, const BlockTree& tree) {
+    const uint32_t c0 = code_by_tree(w.x, t7, tree), c1 = code_by_tree(w.y, t7, tree), c2 = code_by_tree(w.z, t7, tree),
+                   c3 = code_by_tree(w.w, t7, tree);
+    return c0 | (c1 << 4) | (c2 << 8) | (c3 << 12);
+}
+
 // Four min-max codes of one float4 given the block's extremes; also returns alpha = (hi-lo)/15.
 __device__ __forceinline__ uint32_t codes4_minmax(const float4& w, float lo, float hi, float& al) {
     const float range = __fsub_rn(hi, lo);
@@ -88,13 +132,20 @@ struct QuantTile {
     int row0, blk0, jt;
 };
 
-__device__ __forceinline__ QuantTile quant_tile(int bpr) {
-    const int ntj = (bpr + kQBlocks - 1) / kQBlocks;
+// grid: x = tile along the row (fastest, as consecutive workgroups should read consecutive memory), y and z = row
+// tile (two dimensions only because one is limited to 65535) -- no division by a run-time count in the kernel
+constexpr int kQGridY = 32768;
+__device__ __forceinline__ QuantTile quant_tile() {
     QuantTile q;
-    q.jt = blockIdx.x % ntj;
-    q.row0 = (blockIdx.x / ntj) * kQRows;
+    q.jt = blockIdx.x;
+    q.row0 = ((int)blockIdx.z * kQGridY + (int)blockIdx.y) * kQRows;     // rows past the end are handled by the callers
     q.blk0 = q.jt * kQBlocks;
     return q;
+}
+inline dim3 quant_grid(int d_out, int bpr) {
+    const int row_tiles = (d_out + kQRows - 1) / kQRows;
+    return dim3((unsigned)((bpr + kQBlocks - 1) / kQBlocks), (unsigned)(row_tiles < kQGridY ? row_tiles : kQGridY),
+                (unsigned)((row_tiles + kQGridY - 1) / kQGridY));
 }
 
 // codes of the tile from LDS (cs[u][g] = 4 codes of float4 group g of row u) to both global layouts
@@ -124,7 +175,8 @@ __global__ __launch_bounds__(256) void k_quantize_codebook(const float4* __restr
                                                            uint8_t* __restrict__ tiled, float* __restrict__ absmax) {
     __shared__ __align__(16) uint16_t cs[kQRows][256];
     __shared__ float as[kQRows][kQBlocks];
-    const QuantTile q = quant_tile(bpr);
+    __shared__ __align__(16) WaveTrees trees[kQRows];
+    const QuantTile q = quant_tile();
     const int t = threadIdx.x, u = t >> 6, lane = t & 63, j = lane >> 2;
     const int row = q.row0 + u;
     // Lanes outside the matrix read the first block instead: their results are never stored, and the four
@@ -139,9 +191,13 @@ __global__ __launch_bounds__(256) void k_quantize_codebook(const float4* __restr
     for (int i = 0; i < 4; ++i)
         a = fmaxf(a, fmaxf(fmaxf(fabsf(wv[i].x), fabsf(wv[i].y)), fmaxf(fabsf(wv[i].z), fabsf(wv[i].w))));
     a = quad_max(a);
+    // the block's tree is written and read by the lanes of its own quad only: DS operations of a wave execute in
+    // order, so no barrier stands between the build and the look-ups
+    BlockTree tree;
+    const float t7 = build_tree(trees[u], j, a, mp, tree);
     uint32_t c[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) c[i] = codes4_codebook(wv[i], a, mp);
+    for (int i = 0; i < 4; ++i) c[i] = codes4_by_tree(wv[i], t7, tree);
     *reinterpret_cast<uint2*>(&cs[u][lane * 4]) = make_uint2(c[0] | (c[1] << 16), c[2] | (c[3] << 16));
     if ((lane & 3) == 0) as[u][j] = a;
     __syncthreads();
@@ -159,7 +215,7 @@ __global__ __launch_bounds__(256) void k_quantize_minmax(const float4* __restric
                                                          float* __restrict__ alpha, float* __restrict__ beta) {
     __shared__ __align__(16) uint16_t cs[kQRows][256];
     __shared__ float as[kQRows][kQBlocks], bs[kQRows][kQBlocks];
-    const QuantTile q = quant_tile(bpr);
+    const QuantTile q = quant_tile();
     const int t = threadIdx.x, u = t >> 6, lane = t & 63, j = lane >> 2;
     const int row = q.row0 + u;
     const bool ok = row < d_out && q.blk0 + j < bpr;         // lanes outside the matrix read the first block
@@ -498,8 +554,7 @@ int launch_quantize_codebook(const float* W, int d_out, int d_in, const Codebook
         return launch_status();
     }
     const int bpr = d_in / kBlock;
-    const unsigned grid = (unsigned)(((bpr + kQBlocks - 1) / kQBlocks) * ((d_out + kQRows - 1) / kQRows));
-    hipLaunchKernelGGL(k_quantize_codebook, dim3(grid), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
+    hipLaunchKernelGGL(k_quantize_codebook, quant_grid(d_out, bpr), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
                        d_out, bpr, mp, codes, tiled, absmax);
     return launch_status();
 }
@@ -513,8 +568,7 @@ int launch_quantize_minmax(const float* W, int d_out, int d_in, uint8_t* codes, 
         return launch_status();
     }
     const int bpr = d_in / kBlock;
-    const unsigned grid = (unsigned)(((bpr + kQBlocks - 1) / kQBlocks) * ((d_out + kQRows - 1) / kQRows));
-    hipLaunchKernelGGL(k_quantize_minmax, dim3(grid), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
+    hipLaunchKernelGGL(k_quantize_minmax, quant_grid(d_out, bpr), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
                        d_out, bpr, codes, tiled, alpha, beta);
     return launch_status();
 }

@@ -19,9 +19,9 @@
 // tile never crosses LDS.  The token tile does ([token][64 inputs] bf16, 16-byte chunks XOR-swizzled by
 // (row ^ row>>3) & 7): it is shared by the four waves, arrives by direct global -> LDS copies into a ring of
 // four stages, and is read as the B operand (lane l: token l & 31, the same 8 inputs).  All vector-memory
-// operations of the loop are issued from assembly statements three steps ahead and counted by hand (the
-// compiler would tie every LDS access to them): step s waits until only the operations of steps s+1 and s+2
-// are outstanding.
+// operations of the loop are issued from assembly statements three steps ahead (codes: four) and counted by
+// hand (the compiler would tie every LDS access to them): a step waits until only the two youngest batches are
+// outstanding.  The operands of step s+1 are built between the MFMAs of step s.
 //
 // A lane ends up with 4 consecutive output rows of one token per accumulator quad and stores them as one
 // 8-byte word (bf16) or one 16-byte word (fp32 partials).
@@ -143,10 +143,11 @@ __global__ __launch_bounds__(kMidThreads) void k_w4_mid(MidDesc d) {
     const unsigned char* const bbase = reinterpret_cast<const unsigned char*>(d.beta);
     const unsigned char* const xbase = reinterpret_cast<const unsigned char*>(d.X);
 
-    // everything step `s` needs, into register slot `sl` and ring stage `stage`; steps past the slice are
-    // redirected to its last step (fetched, never used), so that every step issues the same kOps operations
-    auto issue = [&](Slot<BR>& sl, int s, int stage) __attribute__((always_inline)) {
-        const int64_t sc = min(s, s_end - 1);
+    // One batch of operations per step, the same count (kOps) whatever the step: the codes and block parameters of
+    // step `sc` into register slot `sl`, and the token tile of step `sx` into ring stage `stage`.  Steps past the
+    // slice are redirected to its last step (fetched, never used).
+    auto issue_codes = [&](Slot<BR>& sl, int step) __attribute__((always_inline)) {
+        const int64_t sc = min(step, s_end - 1);
         load16(sl.cw, c_off, cbase + sc * c_step);
         if constexpr (BR == 8) {
             load16f(sl.sc4, s_off, sbase + sc * s_step);
@@ -155,8 +156,11 @@ __global__ __launch_bounds__(kMidThreads) void k_w4_mid(MidDesc d) {
             load4(sl.sc, s_off, sbase + sc * s_step);
             if constexpr (BETA) load4(sl.be, s_off, bbase + sc * s_step);
         }
+    };
+    auto issue_x = [&](int step, int stage) __attribute__((always_inline)) {
+        const int64_t sx = min(step, s_end - 1);
 #pragma unroll
-        for (int i = 0; i < TB; ++i) copy16_to_lds(xbase + sc * 128, x_off[i], lds_x + stage * kStageBytes + i * 1024);
+        for (int i = 0; i < TB; ++i) copy16_to_lds(xbase + sx * 128, x_off[i], lds_x + stage * kStageBytes + i * 1024);
     };
 
     // fragment addresses of the token tile: token 32*tb + r, logical chunk 4h + j
@@ -176,39 +180,78 @@ __global__ __launch_bounds__(kMidThreads) void k_w4_mid(MidDesc d) {
     auto weight = [&](float c, float a, float b) __attribute__((always_inline)) {
         return BETA ? __fmaf_rn(c, a, b) : __fmul_rn(c, a);
     };
-    // the 8 weights of code dword w as bf16, inputs in ascending order
-    auto operand = [&](uint32_t w, float a, float b) __attribute__((always_inline)) {
-        uint32_t o[4];
-        if constexpr (REGROUPED) {
-            // nibble p of w holds input 0, 2, 4, 6, 1, 3, 5, 7: bytes of t0 are inputs 0, 4, 1, 5, of t1 2, 6, 3, 7
-            const uint32_t t0 = w & 0x0F0F0F0Fu, t1 = (w >> 4) & 0x0F0F0F0Fu;
-            o[0] = pack_bf16(weight((float)(t0 & 0xffu), a, b), weight((float)((t0 >> 16) & 0xffu), a, b));
-            o[1] = pack_bf16(weight((float)(t1 & 0xffu), a, b), weight((float)((t1 >> 16) & 0xffu), a, b));
-            o[2] = pack_bf16(weight((float)((t0 >> 8) & 0xffu), a, b), weight((float)(t0 >> 24), a, b));
-            o[3] = pack_bf16(weight((float)((t1 >> 8) & 0xffu), a, b), weight((float)(t1 >> 24), a, b));
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float2 c = my_table[((w >> (8 * i)) & 0xffu) * kTableReplicas];
-                o[i] = pack_bf16(weight(c.x, a, b), weight(c.y, a, b));
-            }
-        }
-        return __builtin_bit_cast(bf16x8, make_uint4(o[0], o[1], o[2], o[3]));
-    };
-    auto compute = [&](const Slot<BR>& sl, int stage) __attribute__((always_inline)) {
-        const uint32_t cw[4] = {sl.cw.x, sl.cw.y, sl.cw.z, sl.cw.w};
-        const float a4[4] = {sl.sc4.x, sl.sc4.y, sl.sc4.z, sl.sc4.w};
-        const float b4[4] = {sl.be4.x, sl.be4.y, sl.be4.z, sl.be4.w};
-        const unsigned char* xs = sX + stage * kStageBytes;
+    // Dequantization in 16 units per step: unit k = 4j + i makes dword i (two weights, inputs 2i and 2i+1 of the
+    // 8) of the j-th A operand (code dword j).  Table form: unit_a fetches the byte's (c[lo], c[hi]) pair from LDS,
+    // unit_b scales, offsets and rounds; an INT4 model's regrouped dword holds input 0, 2, 4, 6, 1, 3, 5, 7 in its
+    // nibbles, so the bytes of (w & 0x0F0F0F0F) are inputs 0, 4, 1, 5 and those of ((w >> 4) & 0x0F0F0F0F) 2, 6, 3, 7.
+    struct Params { uint32_t cw[4]; float a[4], b[4]; };
+    auto params = [&](const Slot<BR>& sl) __attribute__((always_inline)) {
+        Params p;
+        p.cw[0] = sl.cw.x; p.cw[1] = sl.cw.y; p.cw[2] = sl.cw.z; p.cw[3] = sl.cw.w;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const bf16x8 wf = (BR == 8) ? operand(cw[j], a4[j], BETA ? b4[j] : 0.0f) : operand(cw[j], sl.sc, BETA ? sl.be : 0.0f);
-#pragma unroll
-            for (int tb = 0; tb < TB; ++tb) {
-                const bf16x8 xf = *reinterpret_cast<const bf16x8*>(xs + (f_off[tb] ^ (j << 4)));
-                acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[tb], 0, 0, 0);
-            }
+            p.a[j] = BR == 8 ? sl.sc4[j] : sl.sc;
+            p.b[j] = !BETA ? 0.0f : BR == 8 ? sl.be4[j] : sl.be;
         }
+        return p;
+    };
+    auto unit_a = [&](const Params& p, int k, float2& tv) __attribute__((always_inline)) {
+        if constexpr (!REGROUPED) tv = my_table[((p.cw[k >> 2] >> (8 * (k & 3))) & 0xffu) * kTableReplicas];
+    };
+    auto unit_b = [&](const Params& p, int k, const float2& tv) __attribute__((always_inline)) {
+        const int j = k >> 2, i = k & 3;
+        float lo, hi;
+        if constexpr (REGROUPED) {
+            const uint32_t t = (p.cw[j] >> (4 * (i & 1))) & 0x0F0F0F0Fu;       // i odd: inputs 2, 6, 3, 7
+            lo = (float)((t >> (8 * (i >> 1))) & 0xffu);                          // i < 2: bytes 0 and 2, else 1 and 3
+            hi = (float)((t >> (16 + 8 * (i >> 1))) & 0xffu);
+        } else {
+            lo = tv.x; hi = tv.y;
+        }
+        return pack_bf16(weight(lo, p.a[j], p.b[j]), weight(hi, p.a[j], p.b[j]));
+    };
+    // all four operands at once (before the loop)
+    auto dequantize = [&](const Slot<BR>& sl, bf16x8 (&wf)[4]) __attribute__((always_inline)) {
+        const Params p = params(sl);
+        uint32_t o[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) { float2 tv = make_float2(0.f, 0.f); unit_a(p, k, tv); o[k] = unit_b(p, k, tv); }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) wf[j] = __builtin_bit_cast(bf16x8, make_uint4(o[4 * j], o[4 * j + 1], o[4 * j + 2], o[4 * j + 3]));
+    };
+    // One step: the 4 * TB MFMAs on this step's operands `wf`, and between them the units that build the next
+    // step's operands `wn` from slot `sl` -- written in issue order and fenced after every MFMA: a wave issues in
+    // order, so vector work has to sit between the MFMAs to run in their shadow.  LDS reads are issued one MFMA
+    // (token fragment) or one unit (table pair) ahead of their use.
+    auto step = [&](const bf16x8 (&wf)[4], int stage, const Slot<BR>& sl, bf16x8 (&wn)[4]) __attribute__((always_inline)) {
+        constexpr int M = 4 * TB, U = 16 / M;
+        const unsigned char* xs = sX + stage * kStageBytes;
+        const Params p = params(sl);
+        uint32_t o[16];
+        float2 tv[2] = {make_float2(0.f, 0.f), make_float2(0.f, 0.f)};
+        bf16x8 xf[2];
+        auto read_x = [&](int m) __attribute__((always_inline)) {
+            return *reinterpret_cast<const bf16x8*>(xs + (f_off[m % TB] ^ ((m / TB) << 4)));
+        };
+        unit_a(p, 0, tv[0]);
+        xf[0] = read_x(0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            if (m + 1 < M) xf[(m + 1) & 1] = read_x(m + 1);
+            acc[m % TB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[m / TB], xf[m & 1], acc[m % TB], 0, 0, 0);
+#pragma unroll
+            for (int q = 0; q < U; ++q) {
+                const int k = m * U + q;
+                if (k + 1 < 16) unit_a(p, k + 1, tv[(k + 1) & 1]);
+                o[k] = unit_b(p, k, tv[k & 1]);
+                asm volatile("" : "+v"(o[k]));                  // computed here
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            wn[j] = __builtin_bit_cast(bf16x8, make_uint4(o[4 * j], o[4 * j + 1], o[4 * j + 2], o[4 * j + 3]));
     };
 
     Slot<BR> slot[kStages];
@@ -217,18 +260,25 @@ __global__ __launch_bounds__(kMidThreads) void k_w4_mid(MidDesc d) {
         slot[u].sc = 0.0f; slot[u].be = 0.0f;
         slot[u].sc4 = f32x4{0.f, 0.f, 0.f, 0.f}; slot[u].be4 = f32x4{0.f, 0.f, 0.f, 0.f};
     }
+    bf16x8 wf[2][4];                                            // operands of this step and of the next
     __syncthreads();                                            // the table is complete
+    // The weights of step s+1 are dequantized while the MFMAs of step s issue, so the codes run one step ahead of
+    // the token tiles: batch b carries the codes of step b+4 and the tile of step b+3.
+    issue_codes(slot[0], s_begin);
 #pragma unroll
-    for (int u = 0; u < kStages - 1; ++u) issue(slot[u], s_begin + u, u);
+    for (int u = 0; u < kStages - 1; ++u) { issue_codes(slot[u + 1], s_begin + u + 1); issue_x(s_begin + u, u); }
+    wait_slot<(kStages - 1) * kOps, BR, BETA>(slot[0]);
+    dequantize(slot[0], wf[0]);
     for (int s = s_begin; s < s_end; s += kStages) {
 #pragma unroll
         for (int u = 0; u < kStages; ++u) {
-            // this step's operations are done when at most those of the next two steps are outstanding
-            wait_slot<(kStages - 2) * kOps, BR, BETA>(slot[u]);
+            // the batch issued three steps ago is in when at most the two after it are outstanding
+            wait_slot<(kStages - 2) * kOps, BR, BETA>(slot[(u + 1) % kStages]);
             __syncthreads();                                    // every wave's part of the tile is in; all waves are past
                                                                 // the step before, whose stage is refilled now
-            issue(slot[(u + kStages - 1) % kStages], s + u + kStages - 1, (u + kStages - 1) % kStages);
-            if (s + u < s_end) compute(slot[u], u);
+            issue_codes(slot[u], s + u + kStages);              // slot u was turned into operands a step ago
+            issue_x(s + u + kStages - 1, (u + kStages - 1) % kStages);
+            if (s + u < s_end) step(wf[u & 1], u, slot[(u + 1) % kStages], wf[(u + 1) & 1]);
         }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");            // the redirected look-ahead operations
