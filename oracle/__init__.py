@@ -338,3 +338,29 @@ def merge_bf16(codes, alpha, beta, codebook, H, block, lam1, lam2, s):
     lib().oracle_merge_bf16(_p(codes), _p(alpha), _p(beta), _p(cb), _p(H), i64(d_out), i64(d_in), C.c_int(block),
                             C.c_int(lam1), C.c_int(lam2), C.c_float(s), _p(W16))
     return W16
+
+
+def merge_requant_tile(codes, alpha, beta, codebook, H, br, bc, lam1, lam2, s):
+    """Requantizing merge on br x bc blocks: alpha / beta are [d_out/br, d_in/bc]."""
+    codes = _c(codes, np.uint8); alpha = _c(alpha, np.float32); cb = _c(codebook, np.float32)
+    beta = None if beta is None else _c(beta, np.float32)
+    H = _c(H, np.float32)
+    d_out, d_in = codes.shape[0], codes.shape[1] * 2
+    assert H.shape == (d_in // lam1, d_out // lam2) and alpha.size == (d_out // br) * (d_in // bc)
+    co = np.zeros_like(codes); ao = np.zeros_like(alpha); bo = np.zeros_like(alpha)
+    lib().oracle_merge_requant_tile(_p(codes), _p(alpha), _p(beta), _p(cb), _p(H), i64(d_out), i64(d_in), C.c_int(br),
+                                    C.c_int(bc), C.c_int(lam1), C.c_int(lam2), C.c_float(s), _p(co), _p(ao), _p(bo))
+    return co, ao, bo
+
+
+def merge_bf16_tile(codes, alpha, beta, codebook, H, br, bc, lam1, lam2, s):
+    """16-bit merge on br x bc blocks: bf16 bit patterns [d_out, d_in]."""
+    codes = _c(codes, np.uint8); alpha = _c(alpha, np.float32); cb = _c(codebook, np.float32)
+    beta = None if beta is None else _c(beta, np.float32)
+    H = _c(H, np.float32)
+    d_out, d_in = codes.shape[0], codes.shape[1] * 2
+    assert H.shape == (d_in // lam1, d_out // lam2) and alpha.size == (d_out // br) * (d_in // bc)
+    W16 = np.zeros((d_out, d_in), np.uint16)
+    lib().oracle_merge_bf16_tile(_p(codes), _p(alpha), _p(beta), _p(cb), _p(H), i64(d_out), i64(d_in), C.c_int(br),
+                                 C.c_int(bc), C.c_int(lam1), C.c_int(lam2), C.c_float(s), _p(W16))
+    return W16

@@ -820,6 +820,37 @@ void oracle_merge_requant(const uint8_t* codes, const float* alpha, const float*
     });
 }
 
+// The same requantizing merge on two-dimensional blocks of br output rows x bc inputs (Sec. 3.3 names 4 x 8
+// and 8 x 8; block (i, j) has index i*(d_in/bc) + j): per block, w' = w~ + delta element by element in fp32,
+// then the min-max quantizer of Eq. 1 over the block's br*bc values.
+void oracle_merge_requant_tile(const uint8_t* codes, const float* alpha, const float* beta,
+                               const float* codebook, const float* H, int64_t d_out, int64_t d_in,
+                               int br, int bc, int lam1, int lam2, float s,
+                               uint8_t* codes_out, float* alpha_out, float* beta_out) {
+    const int64_t nbr = d_out / br, nbc = d_in / bc, cols = d_out / lam2;
+    std::memset(codes_out, 0, (size_t)(d_out * d_in / 2));
+    parallel_rows(nbr, [&](int64_t r0, int64_t r1) {
+        std::vector<float> w(br * bc);
+        std::vector<int> c(br * bc);
+        for (int64_t rb = r0; rb < r1; ++rb)
+            for (int64_t cbk = 0; cbk < nbc; ++cbk) {
+                const int64_t blk = rb * nbc + cbk;
+                for (int i = 0; i < br; ++i)
+                    for (int j = 0; j < bc; ++j) {
+                        const int64_t n = rb * br + i, k = cbk * bc + j;
+                        float cv = codebook[get_code(codes, n * d_in + k)];
+                        float wt = beta ? std::fmaf(cv, alpha[blk], beta[blk]) : f32_mul(cv, alpha[blk]);
+                        float delta = f32_div(f32_mul(s, H[(k / lam1) * cols + n / lam2]), (float)lam1);
+                        w[i * bc + j] = f32_add(wt, delta);
+                    }
+                minmax_encode_block(w.data(), br * bc, c.data(), &alpha_out[blk], &beta_out[blk]);
+                for (int i = 0; i < br; ++i)
+                    for (int j = 0; j < bc; ++j)
+                        put_code(codes_out, (rb * br + i) * d_in + cbk * bc + j, c[i * bc + j]);
+            }
+    });
+}
+
 // ---------------------------------------------------------------------------
 // Merge into a 16-bit weight (Sec. 3.2 "Merging Q-BLoRA", Alg. 1 get_delta_weight): W'[n,k] = w~[n,k] +
 // delta(n,k), delta = (s*H[k/lam1, n/lam2]) / lam1, with w~ and the sum in fp32 exactly as in the
@@ -840,6 +871,26 @@ void oracle_merge_bf16(const uint8_t* codes, const float* alpha, const float* be
                 float w = f32_add(wt, delta);
                 uint32_t bits;
                 float r = round_to_bf16(w);
+                std::memcpy(&bits, &r, 4);
+                W16[n * d_in + k] = (uint16_t)(bits >> 16);
+            }
+    });
+}
+
+// ... and on br x bc blocks (scale and offset of block (n/br, k/bc)).
+void oracle_merge_bf16_tile(const uint8_t* codes, const float* alpha, const float* beta, const float* codebook,
+                            const float* H, int64_t d_out, int64_t d_in, int br, int bc, int lam1, int lam2, float s,
+                            uint16_t* W16) {
+    const int64_t nbc = d_in / bc, cols = d_out / lam2;
+    parallel_rows(d_out, [&](int64_t n0, int64_t n1) {
+        for (int64_t n = n0; n < n1; ++n)
+            for (int64_t k = 0; k < d_in; ++k) {
+                const int64_t blk = (n / br) * nbc + k / bc;
+                float cv = codebook[get_code(codes, n * d_in + k)];
+                float wt = beta ? std::fmaf(cv, alpha[blk], beta[blk]) : f32_mul(cv, alpha[blk]);
+                float delta = f32_div(f32_mul(s, H[(k / lam1) * cols + n / lam2]), (float)lam1);
+                float r = round_to_bf16(f32_add(wt, delta));
+                uint32_t bits;
                 std::memcpy(&bits, &r, 4);
                 W16[n * d_in + k] = (uint16_t)(bits >> 16);
             }

@@ -101,3 +101,66 @@ def test_offset_shift_merge_rejects_straddling_blocks_and_handles_missing_beta(o
     H = np.full((d_in // 8, d_out // 8), 0.5, np.float32)
     out = oracle.merge_beta_shift_tile(None, H, d_out, d_in, 8, 8, 8, 8, 2.0)
     assert np.array_equal(out, np.full((2, 4), 0.125, np.float32))              # (2 * 0.5) / 8
+
+
+def test_tile_merges_with_one_row_blocks_are_the_row_segment_merges(oracle, codebook):
+    """br = 1, bc = 64 is the block of Sec. 3.1: both merges must reproduce the row-segment functions bit for bit."""
+    d_out, d_in, lam1, lam2, s = 16, 128, 2, 4, 0.5
+    L = synth.make_layer(81, 2, d_out, d_in, 8, lam1, lam2)
+    H = (np.random.default_rng(81).standard_normal((d_in // lam1, d_out // lam2)) * 0.05).astype(np.float32)
+    for minmax in (False, True):
+        if minmax:
+            codes, alpha, beta = oracle.quantize_minmax(L.W, 64); cb = synth.codebook_int4()
+        else:
+            (codes, alpha), beta, cb = oracle.quantize_codebook(L.W, 64, codebook), None, codebook
+        a = oracle.merge_requant(codes, alpha, beta, cb, H, 64, lam1, lam2, s)
+        b = oracle.merge_requant_tile(codes, alpha, beta, cb, H, 1, 64, lam1, lam2, s)
+        for x, y in zip(a, b):
+            assert np.array_equal(x.view(np.uint8), y.view(np.uint8))
+        assert np.array_equal(oracle.merge_bf16(codes, alpha, beta, cb, H, 64, lam1, lam2, s),
+                              oracle.merge_bf16_tile(codes, alpha, beta, cb, H, 1, 64, lam1, lam2, s))
+
+
+@pytest.mark.parametrize("br,bc", [(8, 8), (4, 8)])
+@pytest.mark.parametrize("lam1,lam2", [(2, 2), (4, 2), (8, 8), (3, 5)])
+def test_tile_merges_against_numpy_on_gathered_blocks(oracle, br, bc, lam1, lam2):
+    """The merged weight written out: w' = fl(fl(fma(c, alpha, beta)) + fl(fl(s h) / lambda1)) per element, then per
+    block alpha' = (max - min) / 15, beta' = min, codes rint((w' - min) * (15 / (max - min))); the 16-bit merge
+    rounds w' once.  Built with numpy float32 operations on blocks gathered by reshapes."""
+    d_out, d_in, s = 120, 120, np.float32(0.75)          # divisible by 8, 4 and the lambdas 2, 3, 4, 5, 8
+    L = synth.make_layer(82 + lam1, 2, d_out, d_in, 8, 1, 1)
+    codes, alpha, beta = oracle.quantize_minmax_tile(L.W, br, bc)
+    cb = synth.codebook_int4()
+    H = (np.random.default_rng(83).standard_normal((d_in // lam1, d_out // lam2)) * 0.05).astype(np.float32)
+    c = unpack_codes(codes).astype(np.float32)                                   # [d_out, d_in] code values 0..15
+    A = np.repeat(np.repeat(alpha, br, 0), bc, 1); Bt = np.repeat(np.repeat(beta, br, 0), bc, 1)
+    wt = (c.astype(np.float64) * A.astype(np.float64) + Bt.astype(np.float64)).astype(np.float32)   # one rounding = fma
+    delta = ((s * np.repeat(np.repeat(H, lam1, 0), lam2, 1).T).astype(np.float32) / np.float32(lam1)).astype(np.float32)
+    w = (wt + delta).astype(np.float32)
+    # 16-bit merge
+    W16 = oracle.merge_bf16_tile(codes, alpha, beta, cb, H, br, bc, lam1, lam2, float(s))
+    assert np.array_equal(W16, synth.f32_to_bf16_bits(w))
+    # requantizing merge
+    co, ao, bo = oracle.merge_requant_tile(codes, alpha, beta, cb, H, br, bc, lam1, lam2, float(s))
+    wb = _blocks(w, br, bc)
+    lo, hi = wb.min(-1), wb.max(-1)
+    rng_ = (hi - lo).astype(np.float32)
+    assert np.array_equal(bo, lo) and np.array_equal(ao, (rng_ / np.float32(15)).astype(np.float32))
+    inv = (np.float32(15) / rng_).astype(np.float32)
+    q = np.rint(((wb - lo[..., None]).astype(np.float32) * inv[..., None]).astype(np.float32)).astype(np.uint8)
+    assert np.array_equal(_blocks(unpack_codes(co), br, bc), q)
+    # and the merged INT4 model is the shifted weight to within half a quantization step
+    Wm = oracle.dequantize_tile(co, ao, bo, cb, br, bc, 0)
+    step = np.repeat(np.repeat(ao, br, 0), bc, 1).astype(np.float64)
+    assert np.all(np.abs(Wm - w.astype(np.float64)) <= 0.5 * step * (1 + 1e-5) + 1e-9)
+
+
+def test_tile_16bit_merge_without_shift_is_the_compute_weight(oracle, codebook):
+    """H = 0: the 16-bit merge is the bf16 compute weight of the forward pass (dequantize mode 2)."""
+    d_out, d_in = 24, 64
+    W = synth.make_layer(84, 2, d_out, d_in, 8, 1, 1).W
+    codes, absmax = oracle.quantize_codebook_tile(W, 8, 8, codebook)
+    H = np.zeros((d_in // 2, d_out // 2), np.float32)
+    W16 = oracle.merge_bf16_tile(codes, absmax, None, codebook, H, 8, 8, 2, 2, 1.0)
+    ref = oracle.dequantize_tile(codes, absmax, None, codebook, 8, 8, 2)
+    assert np.array_equal(bf16_exact(W16), ref)
