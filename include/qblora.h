@@ -74,9 +74,10 @@ enum { QBLORA_MERGE_BETA_SHIFT = 0, QBLORA_MERGE_REQUANT_MINMAX = 1 };
  *              merge (Alg. 2 get_new_beta) is exact.  Needs d_out % 8 == 0 and fp32 scales.  The caller sets
  *              the field before qblora_quantize_blockwise.  Taken by the quantizers, qblora_prepack_codes,
  *              qblora_dequantize_bf16, the forward / backward calls of both adapter forms, the
- *              QBLORA_MERGE_BETA_SHIFT merge (alignment rule 8 | lambda1 and 8 | lambda2) and the small-batch
- *              inference calls (which then contract bf16(fma(c, alpha, beta)) like the training forward);
- *              the requantizing merge and qblora_merge_bf16 return QBLORA_ERR_UNSUPPORTED for them.
+ *              merges (QBLORA_MERGE_BETA_SHIFT with the alignment rule 8 | lambda1 and 8 | lambda2; the
+ *              requantizing merge and qblora_merge_bf16 for any lambdas, the former writing 8 x 8 blocks again)
+ *              and the small-batch inference calls (which then contract bf16(fma(c, alpha, beta)) like the
+ *              training forward).
  *   codes_tiled optional second copy of the codes (NULL = absent) in the order the forward kernel
  *              streams them, qblora_codes_tiled_bytes() bytes: output rows in tiles of 256, and for
  *              tile i and 64-wide input step j one contiguous 8 KiB block at ((i*(d_in/64) + j)*256 + r)*32

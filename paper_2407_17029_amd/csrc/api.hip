@@ -766,7 +766,7 @@ int qblora_tile_product(const qblora_adapter* ad, int32_t d_in, int32_t d_out, f
 
 int qablora_merge_quantize(const qblora_qweight* base, const float* H, int32_t lambda1, int32_t lambda2, float s,
                            int32_t mode, qblora_qweight* out, void* stream) {
-    int rc = check_qweight(base, true, mode == QBLORA_MERGE_BETA_SHIFT);     // 8 x 8 blocks: offset shift only
+    int rc = check_qweight(base, true, true);
     if (rc) return rc;
     if (!H || !out) return QBLORA_ERR_NULL;
     if (lambda1 <= 0 || lambda2 <= 0) return QBLORA_ERR_SHAPE;
@@ -813,7 +813,7 @@ int qablora_merge_quantize(const qblora_qweight* base, const float* H, int32_t l
 
 int qblora_merge_bf16(const qblora_qweight* base, const float* H, int32_t lambda1, int32_t lambda2, float s,
                       qblora_bf16* W16, void* stream) {
-    int rc = check_qweight(base, true);
+    int rc = check_qweight(base, true, true);
     if (rc) return rc;
     if (!H || !W16) return QBLORA_ERR_NULL;
     if (lambda1 <= 0 || lambda2 <= 0) return QBLORA_ERR_SHAPE;
@@ -828,6 +828,7 @@ int qblora_merge_bf16(const qblora_qweight* base, const float* H, int32_t lambda
     d.cb = codebook_of(base); d.d_out = base->d_out; d.d_in = base->d_in;
     d.H = H; d.lam1 = lambda1; d.lam2 = lambda2; d.s = s;
     d.w16_out = W16;
+    d.block_rows = block_rows_of(base);
     return launch_merge_bf16(d, as_stream(stream));
 }
 

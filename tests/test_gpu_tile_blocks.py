@@ -76,8 +76,7 @@ def test_errors(qb, oracle, codebook):
     H = torch.zeros((128 // 4, 64 // 8), dtype=torch.float32, device=W.device)
     with pytest.raises(qb.QBLoRAError):                      # lambda1 = 4 splits an 8-wide block
         qb.qablora_merge_quantize(base, H, 4, 8, 1.0, qb.MERGE_BETA_SHIFT)
-    with pytest.raises(qb.QBLoRAError):                      # the requantizing merge is for row-segment blocks
-        qb.qablora_merge_quantize(base, H, 4, 8, 1.0, qb.MERGE_REQUANT_MINMAX)
+    qb.qablora_merge_quantize(base, H, 4, 8, 1.0, qb.MERGE_REQUANT_MINMAX)      # ... which the requantizing merge takes
     with pytest.raises(qb.QBLoRAError):                      # d_out must be a multiple of 8
         qb.qblora_quantize_blockwise(W[:60].contiguous(), 64, qb.QUANT_MINMAX_INT4, block_rows=8)
     with pytest.raises(qb.QBLoRAError):
@@ -175,3 +174,33 @@ def test_small_batch_inference_on_8x8_blocks(qb, oracle, codebook, T, d_out, d_i
     ref = oracle.forward(Wt, L.X, None, None, 1, 1, 0.0)
     assert_close_bf16(Y, ref, "Y")
     assert torch.equal(Y, Yp)
+
+
+@pytest.mark.parametrize("minmax", [True, False])
+@pytest.mark.parametrize("d_out,d_in,lam1,lam2,s", [(512, 512, 2, 2, 1.0), (328, 832, 4, 2, 0.5), (96, 192, 3, 2, 1.5),
+                                                     (256, 1024, 8, 8, 0.75), (64, 64, 1, 1, 1.0)])
+def test_requantizing_and_16bit_merge_on_8x8_blocks(qb, oracle, codebook, d_out, d_in, lam1, lam2, s, minmax):
+    """Sec. 3.3 with lambdas that do not cover whole 8 x 8 blocks: the merge requantizes every block (or writes the
+    16-bit weight); codes, scales, offsets and bf16 bits against the oracle, bit for bit."""
+    from gpu_util import f32_to_dev, to_np, bf16_to_f64
+    print(f"case 8x8 merge {d_out}x{d_in} lam=({lam1},{lam2}) minmax={minmax}", flush=True)
+    L, qw, Wt, X, dY = _layer(qb, oracle, codebook, 1800 + d_out + lam1, 4, d_out, d_in, 8, 1, 1, minmax)
+    ow = qw.oracle_weight
+    H = synth.normal_f32(1801, 1, (d_in // lam1, d_out // lam2), 0.01)
+    out = qb.qablora_merge_quantize(qw, f32_to_dev(H), lam1, lam2, s, qb.MERGE_REQUANT_MINMAX)
+    W16 = qb.qblora_merge_bf16(qw, f32_to_dev(H), lam1, lam2, s)
+    torch.cuda.synchronize()
+    co, ao, bo = oracle.merge_requant_tile(ow.codes, ow.scales, ow.beta, ow.cb, H, 8, 8, lam1, lam2, s)
+    bits = lambda a: np.ascontiguousarray(a).view(np.uint32).reshape(-1)
+    assert out.block_rows == 8
+    assert np.array_equal(to_np(out.codes), co)
+    assert np.array_equal(bits(to_np(out.scales)), bits(ao)) and np.array_equal(bits(to_np(out.beta)), bits(bo))
+    assert np.array_equal(out.codebook, np.arange(16, dtype=np.float32))
+    ref16 = oracle.merge_bf16_tile(ow.codes, ow.scales, ow.beta, ow.cb, H, 8, 8, lam1, lam2, s)
+    assert np.array_equal(to_np(W16.view(torch.int16)).view(np.uint16), ref16)
+    # the merged INT4 model runs through the small-batch call like any other 8 x 8 weight
+    Ym = qb.qblora_linear_decode(out, X)
+    torch.cuda.synchronize()
+    from gpu_util import assert_close_bf16
+    Wm = oracle.dequantize_tile(co, ao, bo, synth.codebook_int4(), 8, 8, 2)
+    assert_close_bf16(Ym, oracle.forward(Wm, L.X, None, None, 1, 1, 0.0), "Y (merged, 8x8)")
