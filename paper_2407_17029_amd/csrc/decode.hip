@@ -52,6 +52,7 @@ struct DecodeRegs {                         // one group = 4 consecutive blocks 
     uint2 c[4];                             // the lane's quarter of each block's codes: 16 codes
     float a[4], b[4];                       // scale and offset of each block
     float2 a2[4], b2[4];                    // BR = 8: scales and offsets of the lane's two block columns
+    int xb[4];                              // XALL: the (redirected) block whose activations go with c[q]
     uint4 x[4][2];                          // activations of the lane's token, 8 per MFMA (fetched in operand order)
     uint4 xg[8];                            // XLDS: as fetched, token 2p + (lane >> 5), chunk lane & 31 of the group
 };
@@ -61,9 +62,29 @@ struct DecodeRegs {                         // one group = 4 consecutive blocks 
 // path (T = 16: 55 us against 29 at T = 1).  Fetched as whole 512-byte row segments and re-read from LDS in
 // operand order they cost half the cache-line accesses (44 us); for few tokens the extra LDS round trip is the
 // slower way (T = 1: 35 us; the two meet at 8 tokens), hence the switch.
-template <bool BETA, int BR, bool DIRECT = false, bool XLDS = false>
-__global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
+// XMODE 2 (few tokens, rows short enough: at most kXAllBytes of activations): the workgroup copies all of X into
+// LDS once, and the loop has no activation loads at all.  With one token the operand-order loads above move 16 x
+// the bytes of the codes through the vector memory path (every lane fetches its own copy of the 16 activations
+// it shares with 15 others), and that path, not HBM, set the time.
+constexpr int kXAllBytes = 40 * 1024;
+template <bool BETA, int BR, bool DIRECT, int XMODE>
+__device__ __forceinline__ void w4_decode(const DecodeDesc& d);
+
+template <bool BETA, int BR, bool DIRECT = false, int XMODE = 0>
+__global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) { w4_decode<BETA, BR, DIRECT, XMODE>(d); }
+
+// (limiting this form to 84 registers for six waves per SIMD, so that the 1376 workgroups of a 22016-row layer
+// are resident at once, spills 24 of them and nearly doubles the time: 45.8 against 25.6 us)
+template <bool BETA, bool DIRECT>
+__global__ __launch_bounds__(256) void k_w4_decode_xall(DecodeDesc d) {
+    w4_decode<BETA, 1, DIRECT, 2>(d);
+}
+
+template <bool BETA, int BR, bool DIRECT, int XMODE>
+__device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
+    constexpr bool XLDS = XMODE == 1, XALL = XMODE == 2;
     static_assert(!DIRECT || (BETA && BR == 1), "the table-free form needs offsets and 64-blocks");
+    extern __shared__ __align__(16) unsigned char x_all[];       // XALL: [T][d_in * 2 + 16] bytes
     // entry e of replica q at e*kReplicas + q: bf16 pairs (4 bytes), or fp32 pairs (8 bytes) for BR = 8
     __shared__ __align__(8) uint32_t pair[DIRECT ? 2 : 256 * kReplicas * (BR == 8 ? 2 : 1)];
     __shared__ float red[4][4][64];
@@ -112,6 +133,8 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
     unsigned char* xs = xs_all[XLDS ? wave : 0];
     const int xtok = lane >> 5, xchunk = lane & 31;
     const qblora_bf16* xrow = d.X + (int64_t)min(nl, d.T - 1) * d.d_in + 16 * kg;
+    const int x_pitch = d.d_in * 2 + 16;                      // token rows start 16 bytes apart modulo the banks
+    const unsigned char* x_mine = x_all + min(nl, d.T - 1) * x_pitch + 32 * kg;      // XALL: inputs 16 kg .. of block 0
 
     // Every load is unconditional: a block past the end of the row is redirected to the last block and
     // given scale = offset = 0; lanes whose token does not exist read the last token's row and produce
@@ -142,7 +165,9 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
                     r.b[q] = 0.0f;
                 }
             }
-            if constexpr (!XLDS) {
+            if constexpr (XALL) {
+                r.xb[q] = bc;
+            } else if constexpr (!XLDS) {
 #pragma unroll
                 for (int m = 0; m < 2; ++m) r.x[q][m] = *reinterpret_cast<const uint4*>(xrow + bc * kBlock + 8 * m);
             }
@@ -197,6 +222,9 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
             if constexpr (XLDS) {
                 const unsigned char* xq = xs + nl * kXPitch + 128 * q + 32 * kg;    // k = 64q + 16kg .. +15 of token nl
                 x0 = *reinterpret_cast<const bf16x8*>(xq); x1 = *reinterpret_cast<const bf16x8*>(xq + 16);
+            } else if constexpr (XALL) {
+                const unsigned char* xq = x_mine + r.xb[q] * (kBlock * 2);
+                x0 = *reinterpret_cast<const bf16x8*>(xq); x1 = *reinterpret_cast<const bf16x8*>(xq + 16);
             } else {
                 x0 = __builtin_bit_cast(bf16x8, r.x[q][0]); x1 = __builtin_bit_cast(bf16x8, r.x[q][1]);
             }
@@ -222,6 +250,26 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) {
     DecodeRegs r0, r1;
     int j = wave;
     if (j < groups) load(r0, j);
+    if constexpr (XALL) {                                     // behind the first loads of codes: both are in flight together
+        const int chunks = d.d_in / 8;                        // 16-byte pieces per token row
+        for (int i0 = t; i0 < d.T * chunks; i0 += 4 * 256) {
+            uint4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = min(i0 + u * 256, d.T * chunks - 1);
+                const int tk = i / chunks, c = i - tk * chunks;
+                v[u] = *reinterpret_cast<const uint4*>(d.X + (int64_t)tk * d.d_in + c * 8);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = i0 + u * 256;
+                if (i >= d.T * chunks) break;
+                const int tk = i / chunks, c = i - tk * chunks;
+                *reinterpret_cast<uint4*>(x_all + tk * x_pitch + c * 16) = v[u];
+            }
+        }
+        __syncthreads();
+    }
     for (; j < groups; j += 8) {
         if (j + 4 < groups) load(r1, j + 4);
         compute(r0);
@@ -269,17 +317,29 @@ int launch_w4_decode(const uint8_t* codes, const float* scales, const float* bet
         else hipLaunchKernelGGL(plain, grid, dim3(256), 0, st, d);
         return launch_status();
     };
+    const size_t x_all_bytes = (size_t)T * ((size_t)d_in * 2 + 16);
+    if (block_rows != 8 && x_all_bytes <= (size_t)kXAllBytes && d_in % 8 == 0) {       // all of X in LDS
+        auto all = [&](auto kern) -> int {
+            hipLaunchKernelGGL(kern, grid, dim3(256), x_all_bytes, st, d);
+            return launch_status();
+        };
+        if (regrouped) {
+            if (!beta || !tiled) return QBLORA_ERR_UNSUPPORTED;
+            return all(k_w4_decode_xall<true, true>);
+        }
+        return beta ? all(k_w4_decode_xall<true, false>) : all(k_w4_decode_xall<false, false>);
+    }
     if (block_rows == 8) {                  // its fp32 pair table and the activation rows together leave two
                                             // workgroups per CU: measured slower (68 vs 64 us at T = 16), not used
-        if (beta) return go(k_w4_decode<true, 8, false, false>, k_w4_decode<true, 8, false, false>);
-        return go(k_w4_decode<false, 8, false, false>, k_w4_decode<false, 8, false, false>);
+        if (beta) return go(k_w4_decode<true, 8, false, 0>, k_w4_decode<true, 8, false, 0>);
+        return go(k_w4_decode<false, 8, false, 0>, k_w4_decode<false, 8, false, 0>);
     }
     if (regrouped) {                        // codes regrouped by the pack: INT4 model with offsets, table-free
         if (!beta || !tiled) return QBLORA_ERR_UNSUPPORTED;
-        return go(k_w4_decode<true, 1, true, false>, k_w4_decode<true, 1, true, true>);
+        return go(k_w4_decode<true, 1, true, 0>, k_w4_decode<true, 1, true, 1>);
     }
-    if (beta) return go(k_w4_decode<true, 1, false, false>, k_w4_decode<true, 1, false, true>);
-    return go(k_w4_decode<false, 1, false, false>, k_w4_decode<false, 1, false, true>);
+    if (beta) return go(k_w4_decode<true, 1, false, 0>, k_w4_decode<true, 1, false, 1>);
+    return go(k_w4_decode<false, 1, false, 0>, k_w4_decode<false, 1, false, 1>);
 }
 
 }  // namespace qblora
