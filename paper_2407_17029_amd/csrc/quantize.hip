@@ -460,44 +460,85 @@ __global__ __launch_bounds__(256) void k_dequantize_operand(const uint8_t* __res
 }
 
 // The same for the transposed weight (operand rows = inputs k, contraction = stored rows n), which the
-// backward contraction reads.  A workgroup owns 32 inputs x 64 stored rows: a thread dequantizes 8 inputs of
-// one stored row into an LDS tile laid out [k][n], then the four 16-row slices leave as 1 KB pieces (lane l =
-// r + 32*hi holds k = r, n = 16q + 8hi .. + 7) -- 4 KB contiguous per workgroup.
+// backward contraction reads.  A workgroup owns 64 stored rows x 128 inputs.  A thread dequantizes 32 inputs of
+// one stored row (16 bytes of codes; four lanes read 64 contiguous bytes of a row) and writes them as four
+// 16-byte chunks into an LDS tile in the stored orientation, [n][128 k] with 256-byte rows; the transposition is
+// left to the transposing LDS read ds_read_b64_tr_b16 (a group of 16 lanes that points at 4 rows x 16 columns
+// gets, lane i, column i of the four rows): two of them give a lane the 8 consecutive n of its k that the
+// operand order wants.  Logical chunk c of row n sits at chunk position c ^ ((n & 3) << 2), so that the four
+// rows of a transposing read lie in different banks.  Each wave then stores 1 KB pieces (lane l = r + 32*hi
+// holds k = r, n = 16q + 8hi .. + 7).  (The first form read 4 bytes of codes per thread and wrote 2-byte elements
+// into a [k][n] tile: 57 % of its LDS cycles were bank conflicts and it streamed at 0.49 of the HBM peak.)
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 __global__ __launch_bounds__(256) void k_dequantize_operand_t(const uint8_t* __restrict__ codes,
                                                               const float* __restrict__ scales,
                                                               const float* __restrict__ beta, Codebook cb,
                                                               int d_out, int d_in, int block_rows,
                                                               uint4* __restrict__ out) {
     __shared__ float lut[16];
-    __shared__ __align__(16) uint16_t tile[32][72];             // [k][n], pitch 144 bytes
+    __shared__ __align__(16) unsigned char tile[64 * 256];      // [n][128 k] bf16, chunks swizzled
     const int t = threadIdx.x;
     if (t < 16) lut[t] = cb.c[t];
     __syncthreads();
     const int n_tiles = d_out / 64;                             // d_out is a multiple of 64 here
-    const int kb32 = blockIdx.x / n_tiles;                      // block of 32 inputs
+    const int kt = blockIdx.x / n_tiles;                        // 128 inputs
     const int nt = blockIdx.x % n_tiles;                        // 64 stored rows
     {
-        const int row = t >> 2, wd = t & 3;                     // stored row in tile, code dword (8 inputs)
+        const int row = t >> 2, piece = t & 3;                  // stored row in tile, 32 inputs
         const int64_t n = (int64_t)nt * 64 + row;
-        const int k0 = kb32 * 32 + wd * 8;
-        const uint32_t w = *reinterpret_cast<const uint32_t*>(codes + n * (d_in / 2) + k0 / 2);
-        const int64_t blk = block_rows == 8 ? (n >> 3) * (int64_t)(d_in / 8) + k0 / 8
-                                            : n * (int64_t)(d_in / kBlock) + k0 / kBlock;
-        const float a = scales[blk];
-        const float be = beta ? beta[blk] : 0.0f;
+        const int k0 = kt * 128 + piece * 32;
+        uint4 cq = make_uint4(0, 0, 0, 0);
+        float a1 = 0.0f, b1 = 0.0f;
+        float4 a4 = make_float4(0.f, 0.f, 0.f, 0.f), b4 = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (k0 < d_in) {                                        // d_in % 64 == 0: the last tile may be half
+            cq = *reinterpret_cast<const uint4*>(codes + n * (d_in / 2) + k0 / 2);
+            if (block_rows == 8) {                              // four block columns of 8 inputs
+                const int64_t blk = (n >> 3) * (int64_t)(d_in / 8) + k0 / 8;
+                a4 = *reinterpret_cast<const float4*>(scales + blk);
+                if (beta) b4 = *reinterpret_cast<const float4*>(beta + blk);
+            } else {
+                const int64_t blk = n * (int64_t)(d_in / kBlock) + k0 / kBlock;
+                a1 = scales[blk];
+                if (beta) b1 = beta[blk];
+            }
+        }
+        const uint32_t cw[4] = {cq.x, cq.y, cq.z, cq.w};
+        const float as[4] = {a4.x, a4.y, a4.z, a4.w}, bs[4] = {b4.x, b4.y, b4.z, b4.w};
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const float c = lut[(w >> (4 * j)) & 15];
-            const float v = beta ? __fmaf_rn(c, a, be) : __fmul_rn(c, a);
-            tile[wd * 8 + j][row] = (uint16_t)(pack_bf16(v, 0.0f) & 0xffffu);
+        for (int c = 0; c < 4; ++c) {                           // chunk 4*piece + c: 8 inputs
+            const float a = block_rows == 8 ? as[c] : a1, be = block_rows == 8 ? bs[c] : b1;
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float cv = lut[(cw[c] >> (4 * j)) & 15];
+                v[j] = beta ? __fmaf_rn(cv, a, be) : __fmul_rn(cv, a);
+            }
+            const int pos = (4 * piece + c) ^ ((row & 3) << 2);
+            *reinterpret_cast<uint4*>(tile + row * 256 + pos * 16) =
+                make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]));
         }
     }
     __syncthreads();
     {
-        const int q = t >> 6, lane = t & 63, r = lane & 31, hi = lane >> 5;
-        const uint4 o = *reinterpret_cast<const uint4*>(&tile[r][16 * q + 8 * hi]);
+        const int q = t >> 6, lane = t & 63;                    // wave q: stored rows 16q .. 16q+15 of the tile
+        const int g = lane >> 4, sl = lane & 15;
+        const int frow = 8 * (g >> 1) + (sl >> 2);              // row inside the 16-row slice this lane points at
         const int64_t kb_count = d_out / 16;                    // slices of the contraction (stored rows)
-        out[((int64_t)kb32 * kb_count + (int64_t)nt * 4 + q) * 64 + lane] = o;
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb) {                        // 32 inputs each
+            const int col = 32 * kb + 16 * (g & 1) + 4 * (sl & 3);
+            const unsigned char* p = tile + (16 * q + frow) * 256 + ((((col >> 3) ^ ((frow & 3) << 2)) & 15) << 4) +
+                                     ((col >> 2) & 1) * 8;
+            const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(p));
+            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(p + 4 * 256));
+            const int64_t kb32 = (int64_t)kt * 4 + kb;
+            if (kb32 * 32 < d_in) {
+                uint4 o;
+                o.x = __builtin_bit_cast(uint2, lo).x; o.y = __builtin_bit_cast(uint2, lo).y;
+                o.z = __builtin_bit_cast(uint2, hi).x; o.w = __builtin_bit_cast(uint2, hi).y;
+                out[(kb32 * kb_count + (int64_t)nt * 4 + q) * 64 + lane] = o;
+            }
+        }
     }
 }
 
@@ -605,6 +646,9 @@ int launch_dequantize_operand(const qblora_qweight& qw, const float* scales, int
     if (qw.d_in % 64 != 0 || qw.d_out % 64 != 0 || (reinterpret_cast<uintptr_t>(Wop) & 15) ||
         (reinterpret_cast<uintptr_t>(qw.codes) & 15))
         return QBLORA_ERR_UNSUPPORTED;
+    if (qw.block_rows == 8 && transposed &&               // four block parameters per 16-byte load
+        ((reinterpret_cast<uintptr_t>(scales) & 15) || (reinterpret_cast<uintptr_t>(qw.beta) & 15)))
+        return QBLORA_ERR_UNSUPPORTED;
     Codebook cb;
     for (int j = 0; j < 16; ++j) cb.c[j] = qw.codebook[j];
     const int br = qw.block_rows == 8 ? 8 : 1;
@@ -614,7 +658,7 @@ int launch_dequantize_operand(const qblora_qweight& qw, const float* scales, int
         hipLaunchKernelGGL(k_dequantize_operand, dim3((unsigned)blocks), dim3(256), 0, st, qw.codes, scales, qw.beta, cb,
                            qw.d_out, qw.d_in, br, reinterpret_cast<uint4*>(Wop));
     } else {
-        const int64_t blocks = (int64_t)(qw.d_in / 32) * (qw.d_out / 64);
+        const int64_t blocks = (int64_t)((qw.d_in + 127) / 128) * (qw.d_out / 64);
         if (blocks > 0x7fffffff) return QBLORA_ERR_UNSUPPORTED;
         hipLaunchKernelGGL(k_dequantize_operand_t, dim3((unsigned)blocks), dim3(256), 0, st, qw.codes, scales, qw.beta,
                            cb, qw.d_out, qw.d_in, br, reinterpret_cast<uint4*>(Wop));
