@@ -363,13 +363,17 @@ int launch_tb(const MidDesc& d, unsigned blocks, hipStream_t st, int block_rows,
 
 int w4_mid_token_blocks(int T) { return T <= 32 ? 1 : T <= 64 ? 2 : 4; }
 
-// Slices of the input dimension for T <= 128 tokens: enough workgroups for two (token tile of 128) to four per CU,
-// at least 8 steps per slice, at most 8 slices (their partial tiles are extra traffic), no empty slice.
+// Slices of the input dimension for T <= 128 tokens.  Measured over 2 / 3 / 4 waves per workgroup and 1 .. 8 slices on
+// 4096 x 4096, 11008 x 4096 and 22016 x 8192: what counts is the number of workgroups -- about 700 up to 64 tokens
+// (the weight stream wants loads in flight), about 400 at 128 (two resident per CU; more slices only add partial
+// tiles) -- while 64- or 96-row workgroups differ from 128-row ones by a few percent at most; one slice per row tile,
+// which the balance of matrix work alone would choose at 128 tokens, is 20 % slower than two.  At least 4 steps per
+// slice, at most 8 slices, no empty slice.
 int w4_mid_splits(int d_out, int d_in, int T) {
     const int tiles_n = (d_out + kMidRows - 1) / kMidRows, steps = d_in / kBlock;
-    const int per_cu = w4_mid_token_blocks(T) == 4 ? 2 : w4_mid_token_blocks(T) == 2 ? 3 : 4;
-    int want = (256 * per_cu) / tiles_n;
-    if (want > steps / 8) want = steps / 8;
+    const int target = w4_mid_token_blocks(T) == 4 ? 400 : 700;
+    int want = (target + tiles_n / 2) / tiles_n;
+    if (want > steps / 4) want = steps / 4;
     if (want > 8) want = 8;
     if (want < 1) want = 1;
     const int per = (steps + want - 1) / want;
