@@ -148,8 +148,9 @@ class Stack:
         qb, wl = self.qb, self.wl
         for st in self.proj:
             qb.qblora_tile_product(st["ad"], st["p"].d_in, st["p"].d_out, st["H"], self.ws)
-        for st in self.proj:
-            qb.qablora_merge_quantize(st["qw"], st["H"], self.lam, self.lam, wl.s, qb.MERGE_REQUANT_MINMAX, out=st["merged"])
+        # all projections of the layer in one call (one launch where the kernels allow it)
+        qb.qablora_merge_quantize_batch([st["qw"] for st in self.proj], [st["H"] for st in self.proj], self.lam, self.lam,
+                                        wl.s, qb.MERGE_REQUANT_MINMAX, outs=[st["merged"] for st in self.proj])
 
     def step(self):
         for st in self.proj:

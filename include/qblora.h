@@ -312,6 +312,18 @@ int qablora_merge_quantize(const qblora_qweight* base, const float* H, int32_t l
                            float s, int32_t mode, qblora_qweight* out, void* stream);
 
 /*
+ * The same merge for `count` weights with common lambdas, scale and mode -- the projections of a layer (Sec. 3.3 merges
+ * every adapted matrix of the model).  bases / H / outs are host arrays of `count` pointers, entry m as the arguments
+ * of qablora_merge_quantize.  Requantizing merges of row-segment weights that share the scale format and the presence
+ * of offsets go out as one launch per 8 weights (no idle tail and no launch gap between them); anything else is
+ * merged one weight after the other.  Same outputs, bit for bit, as `count` single calls.  All weights are validated
+ * before anything is written or launched; count = 0 is a no-op.
+ */
+int qablora_merge_quantize_batch(int32_t count, const qblora_qweight* const* bases, const float* const* H,
+                                 int32_t lambda1, int32_t lambda2, float s, int32_t mode, qblora_qweight* const* outs,
+                                 void* stream);
+
+/*
  * Merge into a 16-bit weight (Sec. 3.2 "Merging Q-BLoRA", Alg. 1 get_delta_weight):
  *   W16[n,k] = bf16( w~[n,k] + (s * H[k/lambda1, n/lambda2]) / lambda1 ),
  * w~ = c*alpha or fma(c, alpha, beta) and the sum in fp32 (the arithmetic of the requantizing merge), one

@@ -25,6 +25,7 @@ OP_AVGPOOL_REPEAT, OP_TRUNCATE_PAD0, OP_SAMPLE_ZEROFILL = 0, 1, 2
 EXPORTS = ["qblora_quantize_blockwise", "qblora_dequantize_bf16", "qblora_linear_fwd_workspace_bytes",
            "qblora_linear_bwd_workspace_bytes", "qblora_linear_fwd", "qblora_linear_bwd",
            "qblora_tile_product_workspace_bytes", "qblora_tile_product", "qablora_merge_quantize",
+           "qablora_merge_quantize_batch",
            "qblora_strerror", "qblora_profile_events", "qblora_codes_tiled_bytes", "qblora_prepack_codes",
            "qblora_saved_bytes", "qblora_linear_fwd_save", "qblora_linear_bwd_saved",
            "qablora_linear_fwd_workspace_bytes", "qablora_linear_bwd_workspace_bytes", "qablora_linear_fwd",
@@ -86,6 +87,8 @@ def lib():
                                           C.c_void_p]
         L.qablora_merge_quantize.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_int32,
                                              C.c_void_p, C.c_void_p]
+        L.qablora_merge_quantize_batch.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float,
+                                                   C.c_int32, C.c_void_p, C.c_void_p]
         L.qblora_profile_events.argtypes = [C.c_int32, C.c_void_p, C.c_void_p]
         L.qblora_codes_tiled_bytes.restype = C.c_size_t
         L.qblora_codes_tiled_bytes.argtypes = [C.c_int32, C.c_int32]
@@ -476,6 +479,32 @@ def qablora_merge_quantize(base: QWeight, H: torch.Tensor, lambda1: int, lambda2
     out.scale_codes = out.scale_step = out.scale_mid = None
     out.codes_tiled = None
     return out
+
+
+def qablora_merge_quantize_batch(bases, Hs, lambda1: int, lambda2: int, s: float, mode: int, outs=None):
+    """qablora_merge_quantize for a list of weights (one launch per 8 where the kernels allow it)."""
+    n = len(bases)
+    assert len(Hs) == n and all(H.is_cuda and H.dtype == torch.float32 and H.is_contiguous() for H in Hs)
+    if outs is None:
+        outs = [QWeight(b.d_out, b.d_in, b.block, b.codebook, torch.empty_like(b.codes),
+                        torch.empty(tuple(b.scales.shape), dtype=torch.float32, device=b.codes.device),
+                        torch.empty(tuple(b.scales.shape), dtype=torch.float32, device=b.codes.device),
+                        block_rows=b.block_rows) for b in bases]
+    bs = [b.c_struct() for b in bases]
+    os_ = [o.c_struct() for o in outs]
+    Pq = C.POINTER(CQWeight)
+    barr = (Pq * n)(*[C.pointer(x) for x in bs])
+    oarr = (Pq * n)(*[C.pointer(x) for x in os_])
+    harr = (C.c_void_p * n)(*[_ptr(H) for H in Hs])
+    rc = lib().qablora_merge_quantize_batch(n, barr, harr, lambda1, lambda2, C.c_float(s), mode, oarr, _stream())
+    _check(rc, "qablora_merge_quantize_batch")
+    for o, oc in zip(outs, os_):
+        beta_keep = o.beta
+        o.absorb(oc)
+        o.beta = beta_keep
+        o.scale_codes = o.scale_step = o.scale_mid = None
+        o.codes_tiled = None
+    return outs
 
 
 def qblora_merge_bf16(base: QWeight, H: torch.Tensor, lambda1: int, lambda2: int, s: float,

@@ -189,6 +189,62 @@ int resolve_scales(const qblora_qweight* qw, float* scratch, hipStream_t st, con
                                      qw->scale_group, scratch, st);
 }
 
+// ---- QA-BLoRA merge: validation (touches nothing), description + output header, offset-shift launch ------------
+
+int merge_check(const qblora_qweight* base, const float* H, int32_t lambda1, int32_t lambda2, int32_t mode,
+                const qblora_qweight* out) {
+    int rc = check_qweight(base, true, true);
+    if (rc) return rc;
+    if (!H || !out) return QBLORA_ERR_NULL;
+    if (lambda1 <= 0 || lambda2 <= 0) return QBLORA_ERR_SHAPE;
+    if (base->d_in % lambda1 || base->d_out % lambda2) return QBLORA_ERR_SHAPE;
+    if (mode != QBLORA_MERGE_BETA_SHIFT && mode != QBLORA_MERGE_REQUANT_MINMAX) return QBLORA_ERR_UNSUPPORTED;
+    if (!out->codes || !out->scales || !out->beta) return QBLORA_ERR_NULL;
+    if (mode == QBLORA_MERGE_BETA_SHIFT &&
+        (block_rows_of(base) == 8 ? (lambda1 % 8 != 0 || lambda2 % 8 != 0) : (lambda1 % base->block != 0)))
+        return QBLORA_ERR_ALIGNMENT;
+    return QBLORA_OK;
+}
+
+// after merge_check: the kernels' description, and the header of `out` (which may alias `base`)
+MergeDesc merge_fill(const qblora_qweight* base, const float* H, int32_t lambda1, int32_t lambda2, float s, int32_t mode,
+                     qblora_qweight* out) {
+    const bool grouped = base->scale_mode == QBLORA_SCALES_E4M3_GROUPED;
+    MergeDesc d{};
+    d.codes = base->codes; d.scales = base->scales; d.beta = base->beta;
+    if (grouped) {
+        d.scale_codes = base->scale_codes; d.scale_step = base->scale_step; d.scale_mid = base->scale_mid;
+        d.scale_group = base->scale_group;
+    }
+    d.cb = codebook_of(base); d.d_out = base->d_out; d.d_in = base->d_in;
+    d.H = H; d.lam1 = lambda1; d.lam2 = lambda2; d.s = s;
+    d.codes_out = out->codes; d.alpha_out = out->scales; d.beta_out = out->beta;
+    d.block_rows = block_rows_of(base);
+    float cbk[16];
+    std::memcpy(cbk, base->codebook, sizeof(cbk));
+    out->d_out = base->d_out; out->d_in = base->d_in; out->block = base->block; out->block_rows = base->block_rows;
+    out->scale_mode = QBLORA_SCALES_FP32; out->scale_group = 0;
+    out->scale_codes = nullptr; out->scale_step = nullptr; out->scale_mid = nullptr; out->codes_tiled = nullptr;
+    if (mode == QBLORA_MERGE_BETA_SHIFT) std::memcpy(out->codebook, cbk, sizeof(cbk));
+    else for (int j = 0; j < 16; ++j) out->codebook[j] = (float)j;
+    return d;
+}
+
+// offset-shift merge: codes and alpha are copied when the output is a separate weight, beta is shifted
+int merge_shift(const qblora_qweight* base, const MergeDesc& d, const qblora_qweight* out, hipStream_t st) {
+    const bool grouped = d.scale_codes != nullptr;
+    if (d.codes_out != d.codes &&
+        hipMemcpyAsync(d.codes_out, d.codes, (size_t)d.d_out * d.d_in / 2, hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return QBLORA_ERR_LAUNCH;
+    if (!grouped && d.alpha_out != d.scales &&
+        hipMemcpyAsync(d.alpha_out, d.scales, sizeof(float) * (size_t)n_blocks(base), hipMemcpyDeviceToDevice, st) !=
+            hipSuccess)
+        return QBLORA_ERR_LAUNCH;
+    (void)out;
+    ScopedEvents ev(QBLORA_PROFILE_MERGE, st);
+    return launch_merge_beta_shift(d, st);
+}
+
 }  // namespace
 
 extern "C" {
@@ -766,49 +822,48 @@ int qblora_tile_product(const qblora_adapter* ad, int32_t d_in, int32_t d_out, f
 
 int qablora_merge_quantize(const qblora_qweight* base, const float* H, int32_t lambda1, int32_t lambda2, float s,
                            int32_t mode, qblora_qweight* out, void* stream) {
-    int rc = check_qweight(base, true, true);
+    int rc = merge_check(base, H, lambda1, lambda2, mode, out);
     if (rc) return rc;
-    if (!H || !out) return QBLORA_ERR_NULL;
-    if (lambda1 <= 0 || lambda2 <= 0) return QBLORA_ERR_SHAPE;
-    if (base->d_in % lambda1 || base->d_out % lambda2) return QBLORA_ERR_SHAPE;
-    if (mode != QBLORA_MERGE_BETA_SHIFT && mode != QBLORA_MERGE_REQUANT_MINMAX) return QBLORA_ERR_UNSUPPORTED;
-    if (!out->codes || !out->scales || !out->beta) return QBLORA_ERR_NULL;
-    // every check comes before `out` is touched: a rejected call leaves the caller's struct as it was
-    // (it may alias `base`)
-    if (mode == QBLORA_MERGE_BETA_SHIFT &&
-        (block_rows_of(base) == 8 ? (lambda1 % 8 != 0 || lambda2 % 8 != 0) : (lambda1 % base->block != 0)))
-        return QBLORA_ERR_ALIGNMENT;
     hipStream_t st = as_stream(stream);
-    const bool grouped = base->scale_mode == QBLORA_SCALES_E4M3_GROUPED;
-    MergeDesc d{};
-    d.codes = base->codes; d.scales = base->scales; d.beta = base->beta;
-    if (grouped) {
-        d.scale_codes = base->scale_codes; d.scale_step = base->scale_step; d.scale_mid = base->scale_mid;
-        d.scale_group = base->scale_group;
-    }
-    d.cb = codebook_of(base); d.d_out = base->d_out; d.d_in = base->d_in;
-    d.H = H; d.lam1 = lambda1; d.lam2 = lambda2; d.s = s;
-    d.codes_out = out->codes; d.alpha_out = out->scales; d.beta_out = out->beta;
-    out->d_out = base->d_out; out->d_in = base->d_in; out->block = base->block; out->block_rows = base->block_rows;
-    d.block_rows = block_rows_of(base);
-    out->scale_mode = QBLORA_SCALES_FP32; out->scale_group = 0;
-    out->scale_codes = nullptr; out->scale_step = nullptr; out->scale_mid = nullptr; out->codes_tiled = nullptr;
-    if (mode == QBLORA_MERGE_BETA_SHIFT) {
-        std::memcpy(out->codebook, base->codebook, sizeof(out->codebook));
-        if (out->codes != base->codes &&
-            hipMemcpyAsync(out->codes, base->codes, (size_t)base->d_out * base->d_in / 2, hipMemcpyDeviceToDevice,
-                           st) != hipSuccess)
-            return QBLORA_ERR_LAUNCH;
-        if (!grouped && out->scales != base->scales &&
-            hipMemcpyAsync(out->scales, base->scales, sizeof(float) * (size_t)n_blocks(base),
-                           hipMemcpyDeviceToDevice, st) != hipSuccess)
-            return QBLORA_ERR_LAUNCH;
-        ScopedEvents ev(QBLORA_PROFILE_MERGE, st);
-        return launch_merge_beta_shift(d, st);
-    }
-    for (int j = 0; j < 16; ++j) out->codebook[j] = (float)j;
+    const MergeDesc d = merge_fill(base, H, lambda1, lambda2, s, mode, out);
+    if (mode == QBLORA_MERGE_BETA_SHIFT) return merge_shift(base, d, out, st);
     ScopedEvents ev(QBLORA_PROFILE_MERGE, st);
     return launch_merge_requant(d, st);
+}
+
+int qablora_merge_quantize_batch(int32_t count, const qblora_qweight* const* bases, const float* const* H,
+                                 int32_t lambda1, int32_t lambda2, float s, int32_t mode, qblora_qweight* const* outs,
+                                 void* stream) {
+    if (count < 0) return QBLORA_ERR_SHAPE;
+    if (count == 0) return QBLORA_OK;
+    if (!bases || !H || !outs) return QBLORA_ERR_NULL;
+    for (int32_t m = 0; m < count; ++m) {                   // every check of every weight before any `out` is touched
+        if (!bases[m] || !outs[m]) return QBLORA_ERR_NULL;
+        const int rc = merge_check(bases[m], H[m], lambda1, lambda2, mode, outs[m]);
+        if (rc) return rc;
+    }
+    hipStream_t st = as_stream(stream);
+    constexpr int32_t kChunk = 8;                           // weights per launch
+    for (int32_t m0 = 0; m0 < count; m0 += kChunk) {
+        const int32_t n = std::min(kChunk, count - m0);
+        MergeDesc ds[kChunk];
+        for (int32_t m = 0; m < n; ++m) ds[m] = merge_fill(bases[m0 + m], H[m0 + m], lambda1, lambda2, s, mode, outs[m0 + m]);
+        int rc = QBLORA_ERR_UNSUPPORTED;
+        if (mode == QBLORA_MERGE_REQUANT_MINMAX) {
+            ScopedEvents ev(QBLORA_PROFILE_MERGE, st);
+            rc = launch_merge_requant_batch(ds, n, st);
+        }
+        if (rc == QBLORA_ERR_UNSUPPORTED) {                 // one by one (nothing was launched)
+            for (int32_t m = 0; m < n; ++m) {
+                if (mode == QBLORA_MERGE_BETA_SHIFT) rc = merge_shift(bases[m0 + m], ds[m], outs[m0 + m], st);
+                else rc = launch_merge_requant(ds[m], st);
+                if (rc) return rc;
+            }
+        } else if (rc) {
+            return rc;
+        }
+    }
+    return QBLORA_OK;
 }
 
 int qblora_merge_bf16(const qblora_qweight* base, const float* H, int32_t lambda1, int32_t lambda2, float s,

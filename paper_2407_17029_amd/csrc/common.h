@@ -166,6 +166,8 @@ struct MergeDesc {
     uint32_t kgroups_magic;                // set by the launcher: reciprocal for the tile index arithmetic
 };
 int launch_merge_requant(const MergeDesc& d, hipStream_t st);
+// several weights in one launch; QBLORA_ERR_UNSUPPORTED (nothing launched) when they cannot share one
+int launch_merge_requant_batch(const MergeDesc* ds, int count, hipStream_t st);
 int launch_merge_bf16(const MergeDesc& d, hipStream_t st);
 // H = A * B (fp32) for whole 64 x 128 tiles and R % 16 == 0; QBLORA_ERR_UNSUPPORTED otherwise (nothing launched)
 int launch_tile_product(const qblora_bf16* A, const qblora_bf16* B, int rows, int cols, int R, float* H, hipStream_t st);

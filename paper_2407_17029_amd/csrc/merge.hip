@@ -76,7 +76,7 @@ __device__ __forceinline__ float pair_max(float v) {
 
 // OUT16: write the shifted weights themselves as bf16 (the 16-bit merge) instead of requantizing them.
 template <bool GROUPED, bool BETA, int L1, bool OUT16>
-__global__ __launch_bounds__(kMergeThreads) void k_merge_requant(MergeDesc d) {
+__device__ __forceinline__ void merge_requant_tile(const MergeDesc& d, const unsigned wg) {
     __shared__ float lut[16];
     extern __shared__ __align__(16) float dl[];          // deltas, [hcols][stride]
     const int t = threadIdx.x;
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(kMergeThreads) void k_merge_requant(MergeDesc d) {
     // group of eight, or past the last group, have no tile.
     const int ktiles = (d.d_in + KT - 1) / KT, ntiles = (d.d_out + NT - 1) / NT;
     const int kgroups = (ktiles + 7) >> 3;
-    const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+    const int xcd = wg & 7, seq = wg >> 3;
     const int group = (seq >> 3) * 8 + xcd;
     // group / kgroups by the host's reciprocal (exact for group < 2^24, kgroups < 2^8: the launcher checks)
     const int nt = kgroups == 1 ? group : (int)__umulhi((uint32_t)group, d.kgroups_magic);
@@ -212,6 +212,29 @@ __global__ __launch_bounds__(kMergeThreads) void k_merge_requant(MergeDesc d) {
     }
 }
 
+template <bool GROUPED, bool BETA, int L1, bool OUT16>
+__global__ __launch_bounds__(kMergeThreads) void k_merge_requant(MergeDesc d) {
+    merge_requant_tile<GROUPED, BETA, L1, OUT16>(d, blockIdx.x);
+}
+
+// Several weights in one launch (the projections of a layer): the workgroup ids of weight m start at first[m], a
+// multiple of 64, so the id -> XCD pattern of the single launch is kept; between the weights there is no idle
+// tail and no launch gap.
+constexpr int kMergeBatchMax = 8;
+struct MergeBatch {
+    MergeDesc d[kMergeBatchMax];
+    unsigned first[kMergeBatchMax + 1];
+    int count;
+};
+template <bool GROUPED, bool BETA, int L1>
+__global__ __launch_bounds__(kMergeThreads) void k_merge_requant_batch(MergeBatch b) {
+    int m = 0;
+#pragma unroll
+    for (int i = 1; i < kMergeBatchMax; ++i)
+        if (i < b.count && blockIdx.x >= b.first[i]) m = i;
+    merge_requant_tile<GROUPED, BETA, L1, false>(b.d[m], blockIdx.x - b.first[m]);
+}
+
 // beta'[n,b] = beta[n,b] + delta(n, k = b*64); also emits fp32 alpha when the base scales are grouped.
 template <bool GROUPED>
 __global__ __launch_bounds__(256) void k_merge_beta_shift(MergeDesc d) {
@@ -329,6 +352,61 @@ int launch_requant_l1(const MergeDesc& d, hipStream_t st) {
     if (d.scale_codes)
         return d.beta ? launch(k_merge_requant<true, true, L1, OUT16>) : launch(k_merge_requant<true, false, L1, OUT16>);
     return d.beta ? launch(k_merge_requant<false, true, L1, OUT16>) : launch(k_merge_requant<false, false, L1, OUT16>);
+}
+
+// workgroups of the requantizing launch for one weight (a multiple of 64) and its reciprocal; 0 when the shape
+// is beyond the index arithmetic
+unsigned requant_grid(const MergeDesc& d, uint32_t* magic) {
+    const int64_t kgroups = ((d.d_in + KT - 1) / KT + 7) / 8;
+    const int64_t groups = kgroups * ((d.d_out + NT - 1) / NT);
+    if (groups > (int64_t)1 << 24 || kgroups >= 256) return 0;
+    *magic = kgroups > 1 ? (uint32_t)((((uint64_t)1 << 32) / (uint64_t)kgroups) + 1) : 0u;
+    return (unsigned)(((groups + 7) / 8) * 64);
+}
+
+template <int L1>
+int launch_requant_batch_l1(const MergeDesc* ds, int count, hipStream_t st) {
+    MergeBatch b{};
+    b.count = count;
+    unsigned total = 0;
+    size_t smem = 0;
+    for (int m = 0; m < count; ++m) {
+        b.d[m] = ds[m];
+        const unsigned g = requant_grid(ds[m], &b.d[m].kgroups_magic);
+        if (g == 0) return QBLORA_ERR_UNSUPPORTED;
+        b.first[m] = total;
+        total += g;
+        smem = sizeof(float) * (size_t)delta_stride<L1>(ds[m].lam1) * (NT / ds[m].lam2 + 2);
+    }
+    b.first[count] = total;
+    auto launch = [&](auto kern) -> int {
+        if (smem > 48 * 1024 &&
+            hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)smem) != hipSuccess)
+            return QBLORA_ERR_LAUNCH;
+        hipLaunchKernelGGL(kern, dim3(total), dim3(kMergeThreads), smem, st, b);
+        return launch_status();
+    };
+    if (ds[0].scale_codes)
+        return ds[0].beta ? launch(k_merge_requant_batch<true, true, L1>) : launch(k_merge_requant_batch<true, false, L1>);
+    return ds[0].beta ? launch(k_merge_requant_batch<false, true, L1>) : launch(k_merge_requant_batch<false, false, L1>);
+}
+
+// One launch for `count` (2 .. 8) row-segment weights that share lambdas, scale format and the presence of offsets;
+// QBLORA_ERR_UNSUPPORTED (nothing launched) when they do not -- the caller then merges them one by one.
+int launch_merge_requant_batch(const MergeDesc* ds, int count, hipStream_t st) {
+    if (count < 2 || count > kMergeBatchMax) return QBLORA_ERR_UNSUPPORTED;
+    for (int m = 0; m < count; ++m)
+        if (ds[m].block_rows == 8 || ds[m].lam1 != ds[0].lam1 || ds[m].lam2 != ds[0].lam2 ||
+            (ds[m].scale_codes == nullptr) != (ds[0].scale_codes == nullptr) || (ds[m].beta == nullptr) != (ds[0].beta == nullptr))
+            return QBLORA_ERR_UNSUPPORTED;
+    switch (ds[0].lam1) {
+        case 1: return launch_requant_batch_l1<1>(ds, count, st);
+        case 2: return launch_requant_batch_l1<2>(ds, count, st);
+        case 4: return launch_requant_batch_l1<4>(ds, count, st);
+        case 8: return launch_requant_batch_l1<8>(ds, count, st);
+        default: return launch_requant_batch_l1<0>(ds, count, st);
+    }
 }
 
 template <bool OUT16>

@@ -69,6 +69,12 @@ def test_host_validation_rejects_bad_arguments(qb):
     assert L.qablora_merge_quantize(C.byref(qw), dummy, 2, 2, C.c_float(1.0), 0, C.byref(out), None) == -5
     assert L.qablora_merge_quantize(C.byref(qw), dummy, 3, 2, C.c_float(1.0), 1, C.byref(out), None) == -2
     assert L.qablora_merge_quantize(C.byref(qw), None, 2, 2, C.c_float(1.0), 1, C.byref(out), None) == -1
+    Pq = C.POINTER(qb.CQWeight)
+    barr, oarr, harr = (Pq * 2)(C.pointer(qw), C.pointer(qw)), (Pq * 2)(C.pointer(out), C.pointer(out)), (C.c_void_p * 2)(0x1000, 0)
+    assert L.qablora_merge_quantize_batch(0, None, None, 2, 2, C.c_float(1.0), 1, None, None) == 0       # empty batch
+    assert L.qablora_merge_quantize_batch(2, None, harr, 2, 2, C.c_float(1.0), 1, oarr, None) == -1
+    assert L.qablora_merge_quantize_batch(2, barr, harr, 2, 2, C.c_float(1.0), 1, oarr, None) == -1      # second H missing
+    assert L.qablora_merge_quantize_batch(-1, barr, harr, 2, 2, C.c_float(1.0), 1, oarr, None) == -2
 
 
 def test_host_validation_of_the_later_entry_points(qb):

@@ -148,3 +148,50 @@ def test_merged_bf16_layer_reproduces_the_adapted_layer(qb, oracle, codebook):
     err = bf16_to_f64(Y16) - ref
     rms = np.sqrt(np.mean(ref ** 2))
     assert np.sqrt(np.mean(err ** 2)) <= 5e-3 * rms and np.abs(err).max() <= 4e-2 * rms
+
+
+@pytest.mark.parametrize("grouped", [False, True])
+def test_batched_merge_equals_single_merges(qb, oracle, codebook, grouped):
+    """The projections of a layer merged in one call: same bits as one call per weight (and so as the oracle);
+    mixed shapes, more weights than one launch takes, and a mode that goes one by one."""
+    from gpu_util import f32_to_dev, to_np
+    shapes = [(128, 256), (192, 512), (64, 1024), (128, 256), (256, 192), (64, 64), (320, 256), (128, 128), (64, 320)]
+    lam1, lam2, s = 2, 2, 0.75
+    bases, Hs = [], []
+    for i, (d_out, d_in) in enumerate(shapes):
+        W = synth.base_weight(860 + i, 0, d_out, d_in)
+        bases.append(qb.qblora_quantize_blockwise(f32_to_dev(W), 64, qb.QUANT_ABSMAX_CODEBOOK, codebook,
+                                                  qb.SCALES_E4M3_GROUPED if grouped else qb.SCALES_FP32))
+        Hs.append(f32_to_dev(synth.normal_f32(870 + i, 1, (d_in // lam1, d_out // lam2), 0.01)))
+    outs = qb.qablora_merge_quantize_batch(bases, Hs, lam1, lam2, s, qb.MERGE_REQUANT_MINMAX)
+    torch.cuda.synchronize()
+    for b, H, o in zip(bases, Hs, outs):
+        single = qb.qablora_merge_quantize(b, H, lam1, lam2, s, qb.MERGE_REQUANT_MINMAX)
+        torch.cuda.synchronize()
+        assert torch.equal(o.codes, single.codes)
+        assert torch.equal(o.scales.view(torch.int32), single.scales.view(torch.int32))
+        assert torch.equal(o.beta.view(torch.int32), single.beta.view(torch.int32))
+        assert np.array_equal(o.codebook, np.arange(16, dtype=np.float32)) and o.scale_mode == qb.SCALES_FP32
+    # against the oracle directly, for one of them
+    from gpu_util import OracleWeight
+    W3 = synth.base_weight(863, 0, *shapes[3])
+    ow = OracleWeight(oracle, W3, codebook, grouped=grouped).assert_same(bases[3])
+    co, ao, bo = oracle.merge_requant(ow.codes, ow.scales, None, codebook, to_np(Hs[3]), 64, lam1, lam2, s)
+    assert np.array_equal(to_np(outs[3].codes), co) and np.array_equal(_bits(to_np(outs[3].scales)), _bits(ao))
+
+
+def test_batched_merge_offset_shift_and_errors(qb, oracle, codebook):
+    from gpu_util import f32_to_dev
+    lam1, lam2, s = 64, 2, 0.5
+    bases = [qb.qblora_quantize_blockwise(f32_to_dev(synth.base_weight(880 + i, 0, 128, 256)), 64, qb.QUANT_MINMAX_INT4)
+             for i in range(3)]
+    Hs = [f32_to_dev(synth.normal_f32(885 + i, 1, (256 // lam1, 128 // lam2), 0.01)) for i in range(3)]
+    outs = qb.qablora_merge_quantize_batch(bases, Hs, lam1, lam2, s, qb.MERGE_BETA_SHIFT)
+    torch.cuda.synchronize()
+    for b, H, o in zip(bases, Hs, outs):
+        single = qb.qablora_merge_quantize(b, H, lam1, lam2, s, qb.MERGE_BETA_SHIFT)
+        torch.cuda.synchronize()
+        assert torch.equal(o.codes, single.codes) and torch.equal(o.beta.view(torch.int32), single.beta.view(torch.int32))
+    assert qb.qablora_merge_quantize_batch([], [], 2, 2, 1.0, qb.MERGE_REQUANT_MINMAX) == []
+    with pytest.raises(qb.QBLoRAError):                      # one misaligned weight rejects the whole call
+        qb.qablora_merge_quantize_batch(bases, Hs, 2, 2, s, qb.MERGE_BETA_SHIFT)
