@@ -411,51 +411,76 @@ __global__ __launch_bounds__(256) void k_dequantize_bf16(const uint32_t* __restr
 }
 
 // The bf16 compute weight in MFMA operand order (see launch_dequantize_operand): the weight itself.
-// A wave owns 32 stored rows x one 64-block: lane l = r + 32*hi reads the 32 code bytes of row r's block and
-// writes, for each of the block's four 16-wide k slices q, the 8 weights k = 16q + 8hi .. + 7 as 16 bytes at
-// lane l of that slice's 1 KB piece -- 4 KB contiguous per wave, 16 KB per workgroup (four consecutive blocks).
+// A workgroup owns 64 stored rows x 128 inputs.  A thread dequantizes 32 inputs of one stored row (16 bytes of
+// codes; four lanes read 64 contiguous bytes of a row) into four 16-byte chunks of an LDS tile [n][16 chunks], chunk
+// c of row n at position c ^ (n & 15); operand order only regroups whole chunks -- lane l = r + 32*hi of the k slice
+// j takes chunk 2j + hi of row r -- so each wave reads its pieces back with 16-byte LDS loads (16 consecutive rows of
+// one chunk lie in 16 different positions) and stores 1 KB per instruction, 4 KB contiguous per wave.  (The first form
+// let a lane load the 32 code bytes of its row's block, twice per row: both lanes of a row need every other dword;
+// it streamed at 0.60 of the HBM peak.)
 __global__ __launch_bounds__(256) void k_dequantize_operand(const uint8_t* __restrict__ codes,
                                                             const float* __restrict__ scales,
                                                             const float* __restrict__ beta, Codebook cb,
                                                             int d_out, int d_in, int block_rows,
                                                             uint4* __restrict__ out) {
     __shared__ float lut[16];
-    const int t = threadIdx.x, lane = t & 63;
+    __shared__ __align__(16) uint4 tile[64][16];                // [n][chunk of 8 k], positions swizzled
+    const int t = threadIdx.x;
     if (t < 16) lut[t] = cb.c[t];
     __syncthreads();
-    const int bpr = d_in / kBlock, groups = (bpr + 3) / 4;
-    const int nb = blockIdx.x / groups;                         // 32-row block
-    const int b = (blockIdx.x % groups) * 4 + (t >> 6);        // 64-block of this wave
-    if (b >= bpr) return;
-    const int r = lane & 31, hi = lane >> 5;
-    const int64_t n = (int64_t)nb * 32 + r;                     // d_out is a multiple of 32 here
-    const uint4* run = reinterpret_cast<const uint4*>(codes + n * (d_in / 2) + b * 32);
-    const uint4 c0 = run[0], c1 = run[1];
-    const uint32_t cw[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
-    float a = 0.0f, be = 0.0f;
-    if (block_rows != 8) {
-        a = scales[n * bpr + b];
-        if (beta) be = beta[n * bpr + b];
+    const int n_tiles = (d_out + 63) / 64;                      // d_out is a multiple of 32 here
+    const int kt = blockIdx.x / n_tiles;                        // 128 inputs
+    const int nt = blockIdx.x % n_tiles;                        // 64 stored rows
+    {
+        const int row = t >> 2, piece = t & 3;                  // stored row in tile, 32 inputs
+        const int64_t n = min((int64_t)nt * 64 + row, (int64_t)d_out - 1);    // rows past the end: computed, never stored
+        const int k0 = kt * 128 + piece * 32;
+        uint4 cq = make_uint4(0, 0, 0, 0);
+        float a1 = 0.0f, b1 = 0.0f;
+        float4 a4 = make_float4(0.f, 0.f, 0.f, 0.f), b4 = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (k0 < d_in) {                                        // d_in % 64 == 0: the last tile may be half
+            cq = *reinterpret_cast<const uint4*>(codes + n * (d_in / 2) + k0 / 2);
+            if (block_rows == 8) {                              // four block columns of 8 inputs
+                const int64_t blk = (n >> 3) * (int64_t)(d_in / 8) + k0 / 8;
+                a4 = *reinterpret_cast<const float4*>(scales + blk);
+                if (beta) b4 = *reinterpret_cast<const float4*>(beta + blk);
+            } else {
+                const int64_t blk = n * (int64_t)(d_in / kBlock) + k0 / kBlock;
+                a1 = scales[blk];
+                if (beta) b1 = beta[blk];
+            }
+        }
+        const uint32_t cw[4] = {cq.x, cq.y, cq.z, cq.w};
+        const float as[4] = {a4.x, a4.y, a4.z, a4.w}, bs[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {                           // chunk 4*piece + c: 8 inputs
+            const float a = block_rows == 8 ? as[c] : a1, be = block_rows == 8 ? bs[c] : b1;
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float cv = lut[(cw[c] >> (4 * j)) & 15];
+                v[j] = beta ? __fmaf_rn(cv, a, be) : __fmul_rn(cv, a);
+            }
+            tile[row][(4 * piece + c) ^ (row & 15)] =
+                make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]));
+        }
     }
-    const int64_t kb_count = d_in / 16;
+    __syncthreads();
+    {
+        const int w = t >> 6, lane = t & 63, r = lane & 31, hi = lane >> 5;
+        const int rb = w >> 1;                                  // 32-row block of the tile
+        const int64_t nb = (int64_t)nt * 2 + rb;                // 32-row block of the weight
+        if (nb * 32 < d_out) {
+            const int64_t kb_count = d_in / 16;                 // 16-wide k slices of a row block
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const uint32_t w = cw[2 * q + hi];
-        if (block_rows == 8) {                                  // one 8 x 8 block per code dword
-            const int64_t blk = (n >> 3) * (int64_t)(d_in / 8) + (8 * b + 2 * q + hi);
-            a = scales[blk];
-            if (beta) be = beta[blk];
+            for (int q = 0; q < 4; ++q) {
+                const int j = (w & 1) * 4 + q;                  // slice inside the tile
+                const int64_t js = (int64_t)kt * 8 + j;
+                const int row = rb * 32 + r;
+                const uint4 o = tile[row][(2 * j + hi) ^ (row & 15)];
+                if (js < kb_count) out[(nb * kb_count + js) * 64 + lane] = o;
+            }
         }
-        float v[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const float c = lut[(w >> (4 * j)) & 15];
-            v[j] = beta ? __fmaf_rn(c, a, be) : __fmul_rn(c, a);
-        }
-        uint4 o;
-        o.x = pack_bf16(v[0], v[1]); o.y = pack_bf16(v[2], v[3]);
-        o.z = pack_bf16(v[4], v[5]); o.w = pack_bf16(v[6], v[7]);
-        out[((int64_t)nb * kb_count + 4 * b + q) * 64 + lane] = o;
     }
 }
 
@@ -646,14 +671,14 @@ int launch_dequantize_operand(const qblora_qweight& qw, const float* scales, int
     if (qw.d_in % 64 != 0 || qw.d_out % 64 != 0 || (reinterpret_cast<uintptr_t>(Wop) & 15) ||
         (reinterpret_cast<uintptr_t>(qw.codes) & 15))
         return QBLORA_ERR_UNSUPPORTED;
-    if (qw.block_rows == 8 && transposed &&               // four block parameters per 16-byte load
+    if (qw.block_rows == 8 &&                             // four block parameters per 16-byte load
         ((reinterpret_cast<uintptr_t>(scales) & 15) || (reinterpret_cast<uintptr_t>(qw.beta) & 15)))
         return QBLORA_ERR_UNSUPPORTED;
     Codebook cb;
     for (int j = 0; j < 16; ++j) cb.c[j] = qw.codebook[j];
     const int br = qw.block_rows == 8 ? 8 : 1;
     if (!transposed) {
-        const int64_t blocks = (int64_t)(qw.d_out / 32) * ((qw.d_in / kBlock + 3) / 4);
+        const int64_t blocks = (int64_t)((qw.d_out + 63) / 64) * ((qw.d_in + 127) / 128);
         if (blocks > 0x7fffffff) return QBLORA_ERR_UNSUPPORTED;
         hipLaunchKernelGGL(k_dequantize_operand, dim3((unsigned)blocks), dim3(256), 0, st, qw.codes, scales, qw.beta, cb,
                            qw.d_out, qw.d_in, br, reinterpret_cast<uint4*>(Wop));
