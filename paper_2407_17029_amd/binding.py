@@ -286,8 +286,8 @@ def qblora_quantize_blockwise(W: torch.Tensor, block: int = 64, quantizer: int =
         return out
     nblk = d_out * (d_in // max(block, 1))
     codes = torch.empty((d_out, d_in // 2), dtype=torch.uint8, device=dev)
-    if block_rows == 8:
-        scales = torch.empty((d_out // 8, d_in // 8), dtype=torch.float32, device=dev)
+    if block_rows == 8:                      # blocks of 8 rows x (block / 8) inputs: 8 x 8, or 8 x 4 with block = 32
+        scales = torch.empty((d_out // 8, d_in // (block // 8)), dtype=torch.float32, device=dev)
     else:
         scales = torch.empty((d_out, d_in // max(block, 1)), dtype=torch.float32, device=dev)
     beta = torch.empty_like(scales) if quantizer == QUANT_MINMAX_INT4 else None

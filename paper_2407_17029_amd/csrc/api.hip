@@ -36,12 +36,18 @@ int op_map(int op) { return op == QBLORA_OP_TRUNCATE_PAD0 ? MAP_FRONT : op == QB
 
 // rows of a quantization block: 1 (row segments of 64 inputs) or 8 (8 x 8 blocks)
 int block_rows_of(const qblora_qweight* qw) { return qw->block_rows == 8 ? 8 : 1; }
+// inputs per block: 64 (row segments), or with 8-row blocks 8 (block size 64) or 4 (block size 32)
+int block_cols_of(const qblora_qweight* qw) { return qw->block_rows == 8 ? qw->block / 8 : qw->block; }
+// Blocks of 8 rows x 4 inputs: the kernels that rebuild weights inside a contraction (training calls on few tokens,
+// the inference kernels) do not know this shape; every training call takes the dequantize-once form instead.
+bool half_blocks(const qblora_qweight* qw) { return qw->block_rows == 8 && qw->block == 32; }
 
 int check_qweight(const qblora_qweight* qw, bool need_codes, bool allow_tile8 = false) {
     if (!qw) return QBLORA_ERR_NULL;
     if (qw->d_out <= 0 || qw->d_in <= 0) return QBLORA_ERR_SHAPE;
-    if (qw->block != kBlock) return qw->block > 0 ? QBLORA_ERR_UNSUPPORTED : QBLORA_ERR_SHAPE;
-    if (qw->d_in % qw->block != 0 || qw->d_in % 2 != 0) return QBLORA_ERR_SHAPE;
+    if (qw->block != kBlock && !(qw->block == 32 && qw->block_rows == 8 && allow_tile8))
+        return qw->block > 0 ? QBLORA_ERR_UNSUPPORTED : QBLORA_ERR_SHAPE;
+    if (qw->d_in % kBlock != 0) return QBLORA_ERR_SHAPE;
     if (qw->block_rows != 0 && qw->block_rows != 1 && qw->block_rows != 8) return QBLORA_ERR_UNSUPPORTED;
     if (qw->block_rows == 8) {
         if (!allow_tile8 || qw->scale_mode != QBLORA_SCALES_FP32) return QBLORA_ERR_UNSUPPORTED;
@@ -97,7 +103,7 @@ int64_t n_blocks(const qblora_qweight* qw) { return (int64_t)qw->d_out * (qw->d_
 constexpr int64_t kDenseMinTokens = 2048;
 // (the contraction kernel addresses the dequantized weight with 32-bit byte offsets)
 bool use_dense(const qblora_qweight* qw, int64_t T) {
-    return T >= kDenseMinTokens && (int64_t)qw->d_out * qw->d_in * 2 < ((int64_t)1 << 32);
+    return (T >= kDenseMinTokens || half_blocks(qw)) && (int64_t)qw->d_out * qw->d_in * 2 < ((int64_t)1 << 32);
 }
 
 struct FwdSpace {
@@ -201,7 +207,7 @@ int merge_check(const qblora_qweight* base, const float* H, int32_t lambda1, int
     if (mode != QBLORA_MERGE_BETA_SHIFT && mode != QBLORA_MERGE_REQUANT_MINMAX) return QBLORA_ERR_UNSUPPORTED;
     if (!out->codes || !out->scales || !out->beta) return QBLORA_ERR_NULL;
     if (mode == QBLORA_MERGE_BETA_SHIFT &&
-        (block_rows_of(base) == 8 ? (lambda1 % 8 != 0 || lambda2 % 8 != 0) : (lambda1 % base->block != 0)))
+        (block_rows_of(base) == 8 ? (lambda1 % block_cols_of(base) != 0 || lambda2 % 8 != 0) : (lambda1 % base->block != 0)))
         return QBLORA_ERR_ALIGNMENT;
     return QBLORA_OK;
 }
@@ -219,7 +225,7 @@ MergeDesc merge_fill(const qblora_qweight* base, const float* H, int32_t lambda1
     d.cb = codebook_of(base); d.d_out = base->d_out; d.d_in = base->d_in;
     d.H = H; d.lam1 = lambda1; d.lam2 = lambda2; d.s = s;
     d.codes_out = out->codes; d.alpha_out = out->scales; d.beta_out = out->beta;
-    d.block_rows = block_rows_of(base);
+    d.block_rows = block_rows_of(base); d.block_cols = block_cols_of(base);
     float cbk[16];
     std::memcpy(cbk, base->codebook, sizeof(cbk));
     out->d_out = base->d_out; out->d_in = base->d_in; out->block = base->block; out->block_rows = base->block_rows;
@@ -274,8 +280,8 @@ int qblora_quantize_blockwise(const float* W, int32_t d_out, int32_t d_in, int32
                               const float* codebook, int32_t scale_mode, qblora_qweight* out, void* stream) {
     if (!W || !out) return QBLORA_ERR_NULL;
     if (d_out <= 0 || d_in <= 0 || block <= 0) return QBLORA_ERR_SHAPE;
-    if (block != kBlock) return QBLORA_ERR_UNSUPPORTED;
-    if (d_in % block != 0) return QBLORA_ERR_SHAPE;
+    if (block != kBlock && !(block == 32 && out->block_rows == 8)) return QBLORA_ERR_UNSUPPORTED;
+    if (d_in % kBlock != 0) return QBLORA_ERR_SHAPE;
     if (quantizer != QBLORA_QUANT_ABSMAX_CODEBOOK && quantizer != QBLORA_QUANT_MINMAX_INT4)
         return QBLORA_ERR_UNSUPPORTED;
     if (scale_mode != QBLORA_SCALES_FP32 && scale_mode != QBLORA_SCALES_E4M3_GROUPED) return QBLORA_ERR_UNSUPPORTED;
@@ -301,7 +307,8 @@ int qblora_quantize_blockwise(const float* W, int32_t d_out, int32_t d_in, int32
     if (quantizer == QBLORA_QUANT_MINMAX_INT4) {
         for (int j = 0; j < 16; ++j) out->codebook[j] = (float)j;
         ScopedEvents ev(QBLORA_PROFILE_QUANTIZE, st);
-        return launch_quantize_minmax(W, d_out, d_in, out->codes, out->codes_tiled, out->scales, out->beta, st, block_rows);
+        return launch_quantize_minmax(W, d_out, d_in, out->codes, out->codes_tiled, out->scales, out->beta, st, block_rows,
+                                      block_rows == 8 ? block / 8 : 8);
     }
     Codebook cb;
     for (int j = 0; j < 16; ++j) { cb.c[j] = codebook[j]; out->codebook[j] = codebook[j]; }
@@ -309,7 +316,8 @@ int qblora_quantize_blockwise(const float* W, int32_t d_out, int32_t d_in, int32
     int rc;
     {
         ScopedEvents ev(QBLORA_PROFILE_QUANTIZE, st);
-        rc = launch_quantize_codebook(W, d_out, d_in, cb, out->codes, out->codes_tiled, out->scales, st, block_rows);
+        rc = launch_quantize_codebook(W, d_out, d_in, cb, out->codes, out->codes_tiled, out->scales, st, block_rows,
+                                      block_rows == 8 ? block / 8 : 8);
     }
     if (rc) return rc;
     if (scale_mode == QBLORA_SCALES_E4M3_GROUPED)
@@ -366,6 +374,7 @@ int linear_fwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
     if (T == 0) return QBLORA_OK;
     if (!X || !Y) return QBLORA_ERR_NULL;
     const bool dense = allow_dense && use_dense(qw, T);
+    if (half_blocks(qw) && !dense) return QBLORA_ERR_UNSUPPORTED;
     FwdSpace ws = carve_fwd(qw, ad, T, workspace, dense);
     if (ws.bytes > 0 && (!workspace || workspace_bytes < ws.bytes)) return QBLORA_ERR_WORKSPACE;
     hipStream_t st = as_stream(stream);
@@ -464,6 +473,7 @@ int linear_bwd_impl(const qblora_qweight* qw, const qblora_adapter* ad, const qb
     }
     if (!dY || (adapted && !X)) return QBLORA_ERR_NULL;
     const bool dense = use_dense(qw, T) && dX;
+    if (half_blocks(qw) && dX && !dense) return QBLORA_ERR_UNSUPPORTED;
     BwdSpace ws = carve_bwd(qw, ad, T, workspace, use_dense(qw, T));
     if (ws.bytes > 0 && (!workspace || workspace_bytes < ws.bytes)) return QBLORA_ERR_WORKSPACE;
 
@@ -717,6 +727,7 @@ int qablora_linear_fwd(const qblora_qweight* qw, const qblora_bf16* H, int32_t l
     sct.scale_group = qw->scale_group; sct.d_out = qw->d_out; sct.d_in = qw->d_in; sct.out = ws.scales;
     const bool tile8 = block_rows_of(qw) == 8;               // 8 x 8 blocks: scales are read in place
     const bool dense = use_dense(qw, T);                     // many tokens: the weight is dequantized once
+    if (half_blocks(qw) && !dense) return QBLORA_ERR_UNSUPPORTED;
     if (tile8 || dense) sct.out = nullptr;
     if ((rc = launch_adapter_prep(H, H, I, J, J, 1, 1, ws.Ht, nullptr, nullptr, st, sct.out ? &sct : nullptr))) return rc;
     if (dense) {
@@ -781,6 +792,8 @@ int qablora_linear_bwd(const qblora_qweight* qw, const qblora_bf16* H, int32_t l
     if (use_dense(qw, T)) {
         if ((rc = launch_dequantize_operand(*qw, g.scales, 1, ws.W16t, st))) return rc;
         g.qmode = 3; g.W1 = ws.W16t; g.K1 = qw->d_out;
+    } else if (half_blocks(qw)) {
+        return QBLORA_ERR_UNSUPPORTED;
     }
     g.X2 = ws.dVs; g.ldx2 = J; g.W2 = H; g.ldw2 = J; g.K2 = J; g.div2 = lambda1;
     g.X1 = dY; g.ldx1 = qw->d_out;
@@ -883,7 +896,7 @@ int qblora_merge_bf16(const qblora_qweight* base, const float* H, int32_t lambda
     d.cb = codebook_of(base); d.d_out = base->d_out; d.d_in = base->d_in;
     d.H = H; d.lam1 = lambda1; d.lam2 = lambda2; d.s = s;
     d.w16_out = W16;
-    d.block_rows = block_rows_of(base);
+    d.block_rows = block_rows_of(base); d.block_cols = block_cols_of(base);
     return launch_merge_bf16(d, as_stream(stream));
 }
 
@@ -928,6 +941,7 @@ size_t qblora_decode_pack_bytes(const qblora_qweight* qw) {
 int qblora_decode_pack(const qblora_qweight* qw, void* pack, void* stream) {
     int rc = check_qweight(qw, true, true);
     if (rc) return rc;
+    if (half_blocks(qw)) return QBLORA_ERR_UNSUPPORTED;
     if (!pack) return QBLORA_ERR_NULL;
     hipStream_t st = as_stream(stream);
     DecodePack p = carve_pack(qw, pack);
@@ -964,6 +978,7 @@ int qblora_linear_decode(const qblora_qweight* qw, const void* pack, const qblor
                          void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_qweight(qw, true, true);
     if (rc) return rc;
+    if (half_blocks(qw)) return QBLORA_ERR_UNSUPPORTED;      // the inference kernels know 64-blocks and 8 x 8 blocks
     if (T < 0 || T > kMidMaxTokens) return QBLORA_ERR_SHAPE;
     if (T == 0) return QBLORA_OK;
     if (!X || !Y) return QBLORA_ERR_NULL;

@@ -61,9 +61,9 @@ struct ProfileScope {
 
 // `tiled` (may be NULL) receives the second, tile-ordered copy of the codes described in qblora.h
 int launch_quantize_codebook(const float* W, int d_out, int d_in, const Codebook& cb, uint8_t* codes,
-                             uint8_t* tiled, float* absmax, hipStream_t st, int block_rows = 1);
+                             uint8_t* tiled, float* absmax, hipStream_t st, int block_rows = 1, int block_cols = 8);
 int launch_quantize_minmax(const float* W, int d_out, int d_in, uint8_t* codes, uint8_t* tiled, float* alpha,
-                           float* beta, hipStream_t st, int block_rows = 1);
+                           float* beta, hipStream_t st, int block_rows = 1, int block_cols = 8);
 int launch_prepack_codes(const uint8_t* codes, int d_out, int d_in, uint8_t* tiled, hipStream_t st, int regroup = 0);
 
 // byte offset of the 32-byte run of (row n, 64-block b) in the tiled code copy
@@ -162,7 +162,8 @@ struct MergeDesc {
     const float* H; int lam1, lam2; float s;
     uint8_t* codes_out; float* alpha_out; float* beta_out;
     qblora_bf16* w16_out;                  // 16-bit merge only
-    int block_rows;                        // 1 or 8 (offset-shift merge only)
+    int block_rows;                        // 1 or 8
+    int block_cols;                        // with block_rows 8: inputs per block, 8 or 4
     uint32_t kgroups_magic;                // set by the launcher: reciprocal for the tile index arithmetic
 };
 int launch_merge_requant(const MergeDesc& d, hipStream_t st);

@@ -254,12 +254,12 @@ __global__ __launch_bounds__(256) void k_merge_beta_shift(MergeDesc d) {
 // The same shift on 8 x 8 blocks (block (i, j): rows 8i.., inputs 8j.., index i*(d_in/8) + j); with 8 | lambda1
 // and 8 | lambda2 the whole block sees one element of H, so the merged weight is exact (Alg. 2 get_new_beta).
 __global__ __launch_bounds__(256) void k_merge_beta_shift_tile8(MergeDesc d) {
-    const int nbc = d.d_in / 8;
+    const int bc = d.block_cols, nbc = d.d_in / bc;               // blocks of 8 rows x bc inputs
     const int64_t total = (int64_t)(d.d_out / 8) * nbc;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
     const int i = (int)(idx / nbc), j = (int)(idx - (int64_t)i * nbc);
-    const float h = d.H[(int64_t)((8 * j) / d.lam1) * (d.d_out / d.lam2) + (8 * i) / d.lam2];
+    const float h = d.H[(int64_t)((bc * j) / d.lam1) * (d.d_out / d.lam2) + (8 * i) / d.lam2];
     const float delta = __fdiv_rn(__fmul_rn(d.s, h), (float)d.lam1);
     d.beta_out[idx] = d.beta ? __fadd_rn(d.beta[idx], delta) : delta;
 }
@@ -270,27 +270,29 @@ __global__ __launch_bounds__(256) void k_merge_beta_shift_tile8(MergeDesc d) {
 // element (n, k) is read from H where it is (the 64 elements see at most (8/lambda1 + 1)(8/lambda2 + 1) entries,
 // served by the cache).  Same arithmetic as on 64-blocks: fp32 w~ = fma(c, alpha, beta) or c * alpha, + delta,
 // then the min-max quantizer of Eq. 1 over the block, or one rounding to bf16.
-template <bool BETA, bool OUT16>
+// BC = 4: blocks of 8 rows x 4 inputs (two code bytes per row).
+template <bool BETA, bool OUT16, int BC>
 __global__ __launch_bounds__(256) void k_merge_tile8(MergeDesc d) {
     __shared__ float lut[16];
     if (threadIdx.x < 16) lut[threadIdx.x] = d.cb.c[threadIdx.x];
     __syncthreads();
-    const int nbc = d.d_in / 8;
+    const int nbc = d.d_in / BC;
     const int64_t total = (int64_t)(d.d_out / 8) * nbc;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
     const int bi = (int)(idx / nbc), bj = (int)(idx - (int64_t)bi * nbc);
-    const int n0 = 8 * bi, k0 = 8 * bj;
+    const int n0 = 8 * bi, k0 = BC * bj;
     const float a = d.scales[idx], b = BETA ? d.beta[idx] : 0.0f;
     const int ldH = d.d_out / d.lam2;
     const float lam1f = (float)d.lam1;
-    float w[8][8];
+    float w[8][BC];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const uint32_t cw = *reinterpret_cast<const uint32_t*>(d.codes + ((int64_t)(n0 + i) * d.d_in + k0) / 2);
+        const uint8_t* cp = d.codes + ((int64_t)(n0 + i) * d.d_in + k0) / 2;
+        const uint32_t cw = BC == 8 ? *reinterpret_cast<const uint32_t*>(cp) : (uint32_t)*reinterpret_cast<const uint16_t*>(cp);
         const float* hrow = d.H + (n0 + i) / d.lam2;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < BC; ++j) {
             const float cv = lut[(cw >> (4 * j)) & 15];
             const float wt = BETA ? __fmaf_rn(cv, a, b) : __fmul_rn(cv, a);
             const float delta = __fdiv_rn(__fmul_rn(d.s, hrow[(int64_t)((k0 + j) / d.lam1) * ldH]), lam1f);
@@ -299,17 +301,21 @@ __global__ __launch_bounds__(256) void k_merge_tile8(MergeDesc d) {
     }
     if constexpr (OUT16) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            *reinterpret_cast<uint4*>(d.w16_out + (int64_t)(n0 + i) * d.d_in + k0) =
-                make_uint4(pack_bf16(w[i][0], w[i][1]), pack_bf16(w[i][2], w[i][3]), pack_bf16(w[i][4], w[i][5]),
-                           pack_bf16(w[i][6], w[i][7]));
+        for (int i = 0; i < 8; ++i) {
+            qblora_bf16* wp = d.w16_out + (int64_t)(n0 + i) * d.d_in + k0;
+            if constexpr (BC == 8)
+                *reinterpret_cast<uint4*>(wp) = make_uint4(pack_bf16(w[i][0], w[i][1]), pack_bf16(w[i][2], w[i][3]),
+                                                           pack_bf16(w[i][4], w[i][5]), pack_bf16(w[i][6], w[i][7]));
+            else
+                *reinterpret_cast<uint2*>(wp) = make_uint2(pack_bf16(w[i][0], w[i][1]), pack_bf16(w[i][2], w[i][3]));
+        }
         return;
     }
     float lo = w[0][0], hi = w[0][0];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) { lo = fminf(lo, w[i][j]); hi = fmaxf(hi, w[i][j]); }
+        for (int j = 0; j < BC; ++j) { lo = fminf(lo, w[i][j]); hi = fmaxf(hi, w[i][j]); }
     const float range = __fsub_rn(hi, lo);
     const float al = __fdiv_rn(range, 15.0f);
     const float inv = al != 0.0f ? __fdiv_rn(15.0f, range) : 0.0f;     // a flat block gets codes 0
@@ -317,12 +323,14 @@ __global__ __launch_bounds__(256) void k_merge_tile8(MergeDesc d) {
     for (int i = 0; i < 8; ++i) {
         uint32_t p = 0;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < BC; ++j) {
             // (w-lo)*inv lies in [0, 15*(1+2^-23)]: rint() of it is already a code
             const float q = rintf(__fmul_rn(__fsub_rn(w[i][j], lo), inv));
             p |= (uint32_t)q << (4 * j);
         }
-        *reinterpret_cast<uint32_t*>(d.codes_out + ((int64_t)(n0 + i) * d.d_in + k0) / 2) = p;
+        uint8_t* op = d.codes_out + ((int64_t)(n0 + i) * d.d_in + k0) / 2;
+        if constexpr (BC == 8) *reinterpret_cast<uint32_t*>(op) = p;
+        else *reinterpret_cast<uint16_t*>(op) = (uint16_t)p;
     }
     d.alpha_out[idx] = al;
     d.beta_out[idx] = lo;
@@ -412,11 +420,17 @@ int launch_merge_requant_batch(const MergeDesc* ds, int count, hipStream_t st) {
 template <bool OUT16>
 int launch_merge_elementwise(const MergeDesc& d, hipStream_t st) {
     if (d.block_rows == 8) {
-        if (d.scale_codes || d.d_out % 8 != 0 || d.d_in % 8 != 0) return QBLORA_ERR_UNSUPPORTED;
-        const int64_t total = (int64_t)(d.d_out / 8) * (d.d_in / 8);
+        if (d.scale_codes || d.d_out % 8 != 0 || d.d_in % 8 != 0 || (d.block_cols != 8 && d.block_cols != 4))
+            return QBLORA_ERR_UNSUPPORTED;
+        const int64_t total = (int64_t)(d.d_out / 8) * (d.d_in / d.block_cols);
         const dim3 grid((unsigned)((total + 255) / 256));
-        if (d.beta) hipLaunchKernelGGL((k_merge_tile8<true, OUT16>), grid, dim3(256), 0, st, d);
-        else hipLaunchKernelGGL((k_merge_tile8<false, OUT16>), grid, dim3(256), 0, st, d);
+        if (d.block_cols == 4) {
+            if (d.beta) hipLaunchKernelGGL((k_merge_tile8<true, OUT16, 4>), grid, dim3(256), 0, st, d);
+            else hipLaunchKernelGGL((k_merge_tile8<false, OUT16, 4>), grid, dim3(256), 0, st, d);
+        } else {
+            if (d.beta) hipLaunchKernelGGL((k_merge_tile8<true, OUT16, 8>), grid, dim3(256), 0, st, d);
+            else hipLaunchKernelGGL((k_merge_tile8<false, OUT16, 8>), grid, dim3(256), 0, st, d);
+        }
         return launch_status();
     }
     switch (d.lam1) {
@@ -432,7 +446,7 @@ int launch_merge_requant(const MergeDesc& d, hipStream_t st) { return launch_mer
 int launch_merge_bf16(const MergeDesc& d, hipStream_t st) { return launch_merge_elementwise<true>(d, st); }
 
 int launch_merge_beta_shift(const MergeDesc& d, hipStream_t st) {
-    int64_t total = (int64_t)d.d_out * (d.d_in / kBlock);
+    int64_t total = d.block_rows == 8 ? (int64_t)(d.d_out / 8) * (d.d_in / d.block_cols) : (int64_t)d.d_out * (d.d_in / kBlock);
     unsigned grid = (unsigned)((total + 255) / 256);
     if (d.block_rows == 8) {
         hipLaunchKernelGGL(k_merge_beta_shift_tile8, dim3(grid), dim3(256), 0, st, d);

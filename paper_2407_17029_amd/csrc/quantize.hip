@@ -253,12 +253,16 @@ __global__ __launch_bounds__(256) void k_quantize_minmax(const float4* __restric
 // four lanes of a quad hold block t/4, lane q of the quad its rows 2q and 2q+1 (two 16-byte loads each), so
 // a wave reads 512 contiguous bytes of each of the 8 rows and the block reduction is two quad swaps.
 // Codes go through LDS as [row][256 bytes] and leave 16 bytes per thread in both layouts.
-template <bool MINMAX>
+// BC: inputs per block, 8 (8 x 8) or 4 (blocks of 8 rows x 4 inputs, block size 32: the other shape Sec. 3.3
+// names).  With BC = 4 a lane's eight inputs of a row are two blocks: wv[0], wv[2] (inputs 0..3 of its two rows) belong
+// to the left one, wv[1], wv[3] to the right one, each reduced over the quad on its own.
+template <bool MINMAX, int BC>
 __global__ __launch_bounds__(256) void k_quantize_tile8(const float4* __restrict__ W, int d_out, int d_in, Midpoints mp,
                                                         uint8_t* __restrict__ codes, uint8_t* __restrict__ tiled,
                                                         float* __restrict__ alpha, float* __restrict__ beta) {
+    constexpr int NB = 8 / BC;                                     // blocks per lane and row: 1 or 2
     __shared__ __align__(16) uint8_t cs[8][256];
-    __shared__ float as[64], bs[64];
+    __shared__ float as[64 * NB], bs[64 * NB];
     const int ntj = (d_in + 511) / 512;
     const int jt = blockIdx.x % ntj, row0 = (blockIdx.x / ntj) * 8, col0 = jt * 512;
     const int t = threadIdx.x, j = t >> 2, q = t & 3;              // block of the workgroup, lane of its quad
@@ -271,28 +275,36 @@ __global__ __launch_bounds__(256) void k_quantize_tile8(const float4* __restrict
 #pragma unroll
     for (int i = 0; i < 4; ++i) wv[i] = W[((int64_t)(rbase + 2 * q + (i >> 1)) * d_in + cbase + 4 * (i & 1)) >> 2];
     uint32_t c[4];
-    if constexpr (MINMAX) {
-        float lo = wv[0].x, hi = wv[0].x;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            lo = fminf(lo, fminf(fminf(wv[i].x, wv[i].y), fminf(wv[i].z, wv[i].w)));
-            hi = fmaxf(hi, fmaxf(fmaxf(wv[i].x, wv[i].y), fmaxf(wv[i].z, wv[i].w)));
+    for (int h = 0; h < NB; ++h) {                                 // h: the lane's block (BC = 4: left, right)
+        if constexpr (MINMAX) {
+            float lo = wv[h].x, hi = wv[h].x;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (NB == 2 && (i & 1) != h) continue;
+                lo = fminf(lo, fminf(fminf(wv[i].x, wv[i].y), fminf(wv[i].z, wv[i].w)));
+                hi = fmaxf(hi, fmaxf(fmaxf(wv[i].x, wv[i].y), fmaxf(wv[i].z, wv[i].w)));
+            }
+            lo = quad_min(lo);
+            hi = quad_max(hi);
+            float al = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (NB == 1 || (i & 1) == h) c[i] = codes4_minmax(wv[i], lo, hi, al);
+            if (q == 0) { as[NB * j + h] = al; bs[NB * j + h] = lo; }
+        } else {
+            float a = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (NB == 2 && (i & 1) != h) continue;
+                a = fmaxf(a, fmaxf(fmaxf(fabsf(wv[i].x), fabsf(wv[i].y)), fmaxf(fabsf(wv[i].z), fabsf(wv[i].w))));
+            }
+            a = quad_max(a);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (NB == 1 || (i & 1) == h) c[i] = codes4_codebook(wv[i], a, mp);
+            if (q == 0) as[NB * j + h] = a;
         }
-        lo = quad_min(lo);
-        hi = quad_max(hi);
-        float al = 0.0f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) c[i] = codes4_minmax(wv[i], lo, hi, al);
-        if (q == 0) { as[j] = al; bs[j] = lo; }
-    } else {
-        float a = 0.0f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            a = fmaxf(a, fmaxf(fmaxf(fabsf(wv[i].x), fabsf(wv[i].y)), fmaxf(fabsf(wv[i].z), fabsf(wv[i].w))));
-        a = quad_max(a);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) c[i] = codes4_codebook(wv[i], a, mp);
-        if (q == 0) as[j] = a;
     }
     *reinterpret_cast<uint32_t*>(&cs[2 * q][4 * j]) = c[0] | (c[1] << 16);
     *reinterpret_cast<uint32_t*>(&cs[2 * q + 1][4 * j]) = c[2] | (c[3] << 16);
@@ -309,8 +321,8 @@ __global__ __launch_bounds__(256) void k_quantize_tile8(const float4* __restrict
             *reinterpret_cast<uint4*>(tiled + tiled_run_offset(row0 + r, col0 / 64 + ks, bpr64) + half * 16) =
                 *reinterpret_cast<const uint4*>(&cs[r][32 * ks + 16 * half]);
     }
-    if (t < 64 && col0 + 8 * t < d_in && row0 < d_out) {
-        const int64_t blk = (int64_t)(row0 / 8) * (d_in / 8) + col0 / 8 + t;
+    if (t < 64 * NB && col0 + BC * t < d_in && row0 < d_out) {
+        const int64_t blk = (int64_t)(row0 / 8) * (d_in / BC) + col0 / BC + t;
         alpha[blk] = as[t];
         if constexpr (MINMAX) beta[blk] = bs[t];
     }
@@ -381,7 +393,7 @@ __global__ __launch_bounds__(256) void k_scales_reconstruct(const uint8_t* __res
 __global__ __launch_bounds__(256) void k_dequantize_bf16(const uint32_t* __restrict__ codes32,
                                                          const float* __restrict__ scales,
                                                          const float* __restrict__ beta, Codebook cb,
-                                                         int64_t n_words, int words_per_row,
+                                                         int64_t n_words, int words_per_row, int block_cols,
                                                          uint4* __restrict__ out) {
     __shared__ float lut[16];
     if (threadIdx.x < 16) lut[threadIdx.x] = cb.c[threadIdx.x];
@@ -389,20 +401,21 @@ __global__ __launch_bounds__(256) void k_dequantize_bf16(const uint32_t* __restr
     int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n_words) return;
     uint32_t w = codes32[i];
-    int64_t blk = i >> 3;    // 8 words of 8 codes per 64-block
-    if (words_per_row > 0) { // 8 x 8 blocks: a word is one row of block (n/8, word in row)
-        const int64_t n = i / words_per_row;
-        blk = (n >> 3) * words_per_row + (i - n * words_per_row);
+    int64_t blk = i >> 3, blk2 = blk;    // 8 words of 8 codes per 64-block
+    if (words_per_row > 0) { // blocks of 8 rows: a word is one row of block (n/8, word in row), or of two blocks of 4 inputs
+        const int64_t n = i / words_per_row, wd = i - n * words_per_row;
+        blk = blk2 = (n >> 3) * words_per_row + wd;
+        if (block_cols == 4) { blk = (n >> 3) * (2 * (int64_t)words_per_row) + 2 * wd; blk2 = blk + 1; }
     }
-    float a = scales[blk];
+    const float a = scales[blk], a2 = scales[blk2];
     float v[8];
     if (beta) {
-        float b = beta[blk];
+        const float b = beta[blk], b2 = beta[blk2];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = __fmaf_rn(lut[(w >> (4 * j)) & 15], a, b);
+        for (int j = 0; j < 8; ++j) v[j] = __fmaf_rn(lut[(w >> (4 * j)) & 15], j < 4 ? a : a2, j < 4 ? b : b2);
     } else {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = __fmul_rn(lut[(w >> (4 * j)) & 15], a);
+        for (int j = 0; j < 8; ++j) v[j] = __fmul_rn(lut[(w >> (4 * j)) & 15], j < 4 ? a : a2);
     }
     uint4 o;
     o.x = pack_bf16(v[0], v[1]); o.y = pack_bf16(v[2], v[3]);
@@ -421,7 +434,7 @@ __global__ __launch_bounds__(256) void k_dequantize_bf16(const uint32_t* __restr
 __global__ __launch_bounds__(256) void k_dequantize_operand(const uint8_t* __restrict__ codes,
                                                             const float* __restrict__ scales,
                                                             const float* __restrict__ beta, Codebook cb,
-                                                            int d_out, int d_in, int block_rows,
+                                                            int d_out, int d_in, int block_rows, int block_cols,
                                                             uint4* __restrict__ out) {
     __shared__ float lut[16];
     __shared__ __align__(16) uint4 tile[64][16];                // [n][chunk of 8 k], positions swizzled
@@ -437,10 +450,15 @@ __global__ __launch_bounds__(256) void k_dequantize_operand(const uint8_t* __res
         const int k0 = kt * 128 + piece * 32;
         uint4 cq = make_uint4(0, 0, 0, 0);
         float a1 = 0.0f, b1 = 0.0f;
-        float4 a4 = make_float4(0.f, 0.f, 0.f, 0.f), b4 = make_float4(0.f, 0.f, 0.f, 0.f);
+        float4 a4 = make_float4(0.f, 0.f, 0.f, 0.f), b4 = make_float4(0.f, 0.f, 0.f, 0.f), a4b = a4, b4b = b4;
         if (k0 < d_in) {                                        // d_in % 64 == 0: the last tile may be half
             cq = *reinterpret_cast<const uint4*>(codes + n * (d_in / 2) + k0 / 2);
-            if (block_rows == 8) {                              // four block columns of 8 inputs
+            if (block_rows == 8 && block_cols == 4) {           // eight block columns of 4 inputs
+                const int64_t blk = (n >> 3) * (int64_t)(d_in / 4) + k0 / 4;
+                a4 = *reinterpret_cast<const float4*>(scales + blk);
+                a4b = *reinterpret_cast<const float4*>(scales + blk + 4);
+                if (beta) { b4 = *reinterpret_cast<const float4*>(beta + blk); b4b = *reinterpret_cast<const float4*>(beta + blk + 4); }
+            } else if (block_rows == 8) {                       // four block columns of 8 inputs
                 const int64_t blk = (n >> 3) * (int64_t)(d_in / 8) + k0 / 8;
                 a4 = *reinterpret_cast<const float4*>(scales + blk);
                 if (beta) b4 = *reinterpret_cast<const float4*>(beta + blk);
@@ -451,15 +469,18 @@ __global__ __launch_bounds__(256) void k_dequantize_operand(const uint8_t* __res
             }
         }
         const uint32_t cw[4] = {cq.x, cq.y, cq.z, cq.w};
-        const float as[4] = {a4.x, a4.y, a4.z, a4.w}, bs[4] = {b4.x, b4.y, b4.z, b4.w};
+        const float as[8] = {a4.x, a4.y, a4.z, a4.w, a4b.x, a4b.y, a4b.z, a4b.w};
+        const float bs[8] = {b4.x, b4.y, b4.z, b4.w, b4b.x, b4b.y, b4b.z, b4b.w};
+        const bool half = block_rows == 8 && block_cols == 4;   // two blocks per chunk of 8 inputs
 #pragma unroll
         for (int c = 0; c < 4; ++c) {                           // chunk 4*piece + c: 8 inputs
-            const float a = block_rows == 8 ? as[c] : a1, be = block_rows == 8 ? bs[c] : b1;
+            const float a = half ? as[2 * c] : block_rows == 8 ? as[c] : a1, be = half ? bs[2 * c] : block_rows == 8 ? bs[c] : b1;
+            const float a_hi = half ? as[2 * c + 1] : a, be_hi = half ? bs[2 * c + 1] : be;    // inputs 4 .. 7 of the chunk
             float v[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const float cv = lut[(cw[c] >> (4 * j)) & 15];
-                v[j] = beta ? __fmaf_rn(cv, a, be) : __fmul_rn(cv, a);
+                v[j] = beta ? __fmaf_rn(cv, j < 4 ? a : a_hi, j < 4 ? be : be_hi) : __fmul_rn(cv, j < 4 ? a : a_hi);
             }
             tile[row][(4 * piece + c) ^ (row & 15)] =
                 make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]));
@@ -498,7 +519,7 @@ typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 __global__ __launch_bounds__(256) void k_dequantize_operand_t(const uint8_t* __restrict__ codes,
                                                               const float* __restrict__ scales,
                                                               const float* __restrict__ beta, Codebook cb,
-                                                              int d_out, int d_in, int block_rows,
+                                                              int d_out, int d_in, int block_rows, int block_cols,
                                                               uint4* __restrict__ out) {
     __shared__ float lut[16];
     __shared__ __align__(16) unsigned char tile[64 * 256];      // [n][128 k] bf16, chunks swizzled
@@ -514,10 +535,15 @@ __global__ __launch_bounds__(256) void k_dequantize_operand_t(const uint8_t* __r
         const int k0 = kt * 128 + piece * 32;
         uint4 cq = make_uint4(0, 0, 0, 0);
         float a1 = 0.0f, b1 = 0.0f;
-        float4 a4 = make_float4(0.f, 0.f, 0.f, 0.f), b4 = make_float4(0.f, 0.f, 0.f, 0.f);
+        float4 a4 = make_float4(0.f, 0.f, 0.f, 0.f), b4 = make_float4(0.f, 0.f, 0.f, 0.f), a4b = a4, b4b = b4;
         if (k0 < d_in) {                                        // d_in % 64 == 0: the last tile may be half
             cq = *reinterpret_cast<const uint4*>(codes + n * (d_in / 2) + k0 / 2);
-            if (block_rows == 8) {                              // four block columns of 8 inputs
+            if (block_rows == 8 && block_cols == 4) {           // eight block columns of 4 inputs
+                const int64_t blk = (n >> 3) * (int64_t)(d_in / 4) + k0 / 4;
+                a4 = *reinterpret_cast<const float4*>(scales + blk);
+                a4b = *reinterpret_cast<const float4*>(scales + blk + 4);
+                if (beta) { b4 = *reinterpret_cast<const float4*>(beta + blk); b4b = *reinterpret_cast<const float4*>(beta + blk + 4); }
+            } else if (block_rows == 8) {                       // four block columns of 8 inputs
                 const int64_t blk = (n >> 3) * (int64_t)(d_in / 8) + k0 / 8;
                 a4 = *reinterpret_cast<const float4*>(scales + blk);
                 if (beta) b4 = *reinterpret_cast<const float4*>(beta + blk);
@@ -528,15 +554,18 @@ __global__ __launch_bounds__(256) void k_dequantize_operand_t(const uint8_t* __r
             }
         }
         const uint32_t cw[4] = {cq.x, cq.y, cq.z, cq.w};
-        const float as[4] = {a4.x, a4.y, a4.z, a4.w}, bs[4] = {b4.x, b4.y, b4.z, b4.w};
+        const float as[8] = {a4.x, a4.y, a4.z, a4.w, a4b.x, a4b.y, a4b.z, a4b.w};
+        const float bs[8] = {b4.x, b4.y, b4.z, b4.w, b4b.x, b4b.y, b4b.z, b4b.w};
+        const bool half = block_rows == 8 && block_cols == 4;   // two blocks per chunk of 8 inputs
 #pragma unroll
         for (int c = 0; c < 4; ++c) {                           // chunk 4*piece + c: 8 inputs
-            const float a = block_rows == 8 ? as[c] : a1, be = block_rows == 8 ? bs[c] : b1;
+            const float a = half ? as[2 * c] : block_rows == 8 ? as[c] : a1, be = half ? bs[2 * c] : block_rows == 8 ? bs[c] : b1;
+            const float a_hi = half ? as[2 * c + 1] : a, be_hi = half ? bs[2 * c + 1] : be;    // inputs 4 .. 7 of the chunk
             float v[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const float cv = lut[(cw[c] >> (4 * j)) & 15];
-                v[j] = beta ? __fmaf_rn(cv, a, be) : __fmul_rn(cv, a);
+                v[j] = beta ? __fmaf_rn(cv, j < 4 ? a : a_hi, j < 4 ? be : be_hi) : __fmul_rn(cv, j < 4 ? a : a_hi);
             }
             const int pos = (4 * piece + c) ^ ((row & 3) << 2);
             *reinterpret_cast<uint4*>(tile + row * 256 + pos * 16) =
@@ -606,7 +635,7 @@ int launch_prepack_codes(const uint8_t* codes, int d_out, int d_in, uint8_t* til
 }
 
 int launch_quantize_codebook(const float* W, int d_out, int d_in, const Codebook& cb, uint8_t* codes,
-                             uint8_t* tiled, float* absmax, hipStream_t st, int block_rows) {
+                             uint8_t* tiled, float* absmax, hipStream_t st, int block_rows, int block_cols) {
     Midpoints mp;
     for (int j = 0; j < 15; ++j) {
         volatile float sum = cb.c[j] + cb.c[j + 1];   // two separate fp32 roundings
@@ -615,8 +644,12 @@ int launch_quantize_codebook(const float* W, int d_out, int d_in, const Codebook
     }
     if (block_rows == 8) {
         const unsigned grid8 = (unsigned)(((d_in + 511) / 512) * (d_out / 8));
-        hipLaunchKernelGGL(k_quantize_tile8<false>, dim3(grid8), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
-                           d_out, d_in, mp, codes, tiled, absmax, static_cast<float*>(nullptr));
+        if (block_cols == 4)
+            hipLaunchKernelGGL((k_quantize_tile8<false, 4>), dim3(grid8), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
+                               d_out, d_in, mp, codes, tiled, absmax, static_cast<float*>(nullptr));
+        else
+            hipLaunchKernelGGL((k_quantize_tile8<false, 8>), dim3(grid8), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
+                               d_out, d_in, mp, codes, tiled, absmax, static_cast<float*>(nullptr));
         return launch_status();
     }
     const int bpr = d_in / kBlock;
@@ -626,11 +659,15 @@ int launch_quantize_codebook(const float* W, int d_out, int d_in, const Codebook
 }
 
 int launch_quantize_minmax(const float* W, int d_out, int d_in, uint8_t* codes, uint8_t* tiled, float* alpha,
-                           float* beta, hipStream_t st, int block_rows) {
+                           float* beta, hipStream_t st, int block_rows, int block_cols) {
     if (block_rows == 8) {
         const unsigned grid8 = (unsigned)(((d_in + 511) / 512) * (d_out / 8));
-        hipLaunchKernelGGL(k_quantize_tile8<true>, dim3(grid8), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
-                           d_out, d_in, Midpoints{}, codes, tiled, alpha, beta);
+        if (block_cols == 4)
+            hipLaunchKernelGGL((k_quantize_tile8<true, 4>), dim3(grid8), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
+                               d_out, d_in, Midpoints{}, codes, tiled, alpha, beta);
+        else
+            hipLaunchKernelGGL((k_quantize_tile8<true, 8>), dim3(grid8), dim3(256), 0, st, reinterpret_cast<const float4*>(W),
+                               d_out, d_in, Midpoints{}, codes, tiled, alpha, beta);
         return launch_status();
     }
     const int bpr = d_in / kBlock;
@@ -662,7 +699,8 @@ int launch_dequantize_bf16(const qblora_qweight& qw, const float* scales, qblora
     unsigned grid = (unsigned)((n_words + 255) / 256);
     hipLaunchKernelGGL(k_dequantize_bf16, dim3(grid), dim3(256), 0, st,
                        reinterpret_cast<const uint32_t*>(qw.codes), scales, qw.beta, cb, n_words,
-                       qw.block_rows == 8 ? qw.d_in / 8 : 0, reinterpret_cast<uint4*>(Wt));
+                       qw.block_rows == 8 ? qw.d_in / 8 : 0, qw.block_rows == 8 ? qw.block / 8 : 8,
+                       reinterpret_cast<uint4*>(Wt));
     return launch_status();
 }
 
@@ -676,17 +714,17 @@ int launch_dequantize_operand(const qblora_qweight& qw, const float* scales, int
         return QBLORA_ERR_UNSUPPORTED;
     Codebook cb;
     for (int j = 0; j < 16; ++j) cb.c[j] = qw.codebook[j];
-    const int br = qw.block_rows == 8 ? 8 : 1;
+    const int br = qw.block_rows == 8 ? 8 : 1, bc = br == 8 ? qw.block / 8 : qw.block;
     if (!transposed) {
         const int64_t blocks = (int64_t)((qw.d_out + 63) / 64) * ((qw.d_in + 127) / 128);
         if (blocks > 0x7fffffff) return QBLORA_ERR_UNSUPPORTED;
         hipLaunchKernelGGL(k_dequantize_operand, dim3((unsigned)blocks), dim3(256), 0, st, qw.codes, scales, qw.beta, cb,
-                           qw.d_out, qw.d_in, br, reinterpret_cast<uint4*>(Wop));
+                           qw.d_out, qw.d_in, br, bc, reinterpret_cast<uint4*>(Wop));
     } else {
         const int64_t blocks = (int64_t)((qw.d_in + 127) / 128) * (qw.d_out / 64);
         if (blocks > 0x7fffffff) return QBLORA_ERR_UNSUPPORTED;
         hipLaunchKernelGGL(k_dequantize_operand_t, dim3((unsigned)blocks), dim3(256), 0, st, qw.codes, scales, qw.beta,
-                           cb, qw.d_out, qw.d_in, br, reinterpret_cast<uint4*>(Wop));
+                           cb, qw.d_out, qw.d_in, br, bc, reinterpret_cast<uint4*>(Wop));
     }
     return launch_status();
 }

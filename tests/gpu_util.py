@@ -38,20 +38,21 @@ class OracleWeight:
     """The quantized frozen weight as the oracle produces it from the seeded fp32 matrix: everything the
     oracle is later fed comes from here, never from a device buffer."""
 
-    def __init__(self, oracle, W, codebook, minmax=False, grouped=False, block_rows=1):
+    def __init__(self, oracle, W, codebook, minmax=False, grouped=False, block_rows=1, block_cols=8):
         self.block_rows = block_rows
+        self.block_cols = block_cols                 # with block_rows = 8: inputs per block, 8 or 4
         self.sc = self.step = self.mid = None
         if minmax:
             self.cb = synth.codebook_int4()
             if block_rows == 8:
-                self.codes, self.alpha, self.beta = oracle.quantize_minmax_tile(W, 8, 8)
+                self.codes, self.alpha, self.beta = oracle.quantize_minmax_tile(W, 8, block_cols)
             else:
                 self.codes, self.alpha, self.beta = oracle.quantize_minmax(W, 64)
         else:
             self.cb = np.asarray(codebook, np.float32)
             self.beta = None
             if block_rows == 8:
-                self.codes, self.alpha = oracle.quantize_codebook_tile(W, 8, 8, codebook)
+                self.codes, self.alpha = oracle.quantize_codebook_tile(W, 8, block_cols, codebook)
             else:
                 self.codes, self.alpha = oracle.quantize_codebook(W, 64, codebook)
         self.scales = self.alpha                     # what consumers read
@@ -61,7 +62,7 @@ class OracleWeight:
 
     def dequantize(self, oracle, mode):
         if self.block_rows == 8:
-            return oracle.dequantize_tile(self.codes, self.scales, self.beta, self.cb, 8, 8, mode)
+            return oracle.dequantize_tile(self.codes, self.scales, self.beta, self.cb, 8, self.block_cols, mode)
         return oracle.dequantize(self.codes, self.scales, self.beta, self.cb, 64, mode)
 
     def assert_same(self, qw):

@@ -204,3 +204,88 @@ def test_requantizing_and_16bit_merge_on_8x8_blocks(qb, oracle, codebook, d_out,
     from gpu_util import assert_close_bf16
     Wm = oracle.dequantize_tile(co, ao, bo, synth.codebook_int4(), 8, 8, 2)
     assert_close_bf16(Ym, oracle.forward(Wm, L.X, None, None, 1, 1, 0.0), "Y (merged, 8x8)")
+
+
+# ---- blocks of 8 output rows x 4 inputs (block size 32; Sec. 3.3: blocks "of 4 x 8 or 8 x 8") ------------------------
+
+def _layer84(qb, oracle, codebook, seed, T, d_out, d_in, R, lam1, lam2, minmax):
+    from gpu_util import f32_to_dev, bf16_to_dev, OracleWeight
+    L = synth.make_layer(seed, T, d_out, d_in, max(R, 8), lam1, lam2)
+    if minmax:
+        qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 32, qb.QUANT_MINMAX_INT4, block_rows=8)
+    else:
+        qw = qb.qblora_quantize_blockwise(f32_to_dev(L.W), 32, qb.QUANT_ABSMAX_CODEBOOK, codebook, block_rows=8)
+    torch.cuda.synchronize()
+    ow = OracleWeight(oracle, L.W, codebook, minmax, block_rows=8, block_cols=4).assert_same(qw)    # quantizers: bit for bit
+    qw.oracle_weight = ow
+    return L, qw, ow.dequantize(oracle, 2), bf16_to_dev(L.X), bf16_to_dev(L.dY)
+
+
+@pytest.mark.parametrize("minmax", [True, False])
+@pytest.mark.parametrize("d_out,d_in", [(64, 64), (328, 832), (512, 1088)])
+def test_quantize_and_dequantize_on_8x4_blocks(qb, oracle, codebook, d_out, d_in, minmax):
+    from gpu_util import to_np
+    print(f"case 8x4 quantize {d_out}x{d_in} minmax={minmax}", flush=True)
+    L, qw, Wt, X, dY = _layer84(qb, oracle, codebook, 1900 + d_out, 4, d_out, d_in, 8, 1, 1, minmax)
+    assert qw.block == 32 and tuple(qw.scales.shape) == (d_out // 8, d_in // 4)
+    W16 = qb.qblora_dequantize_bf16(qw)
+    torch.cuda.synchronize()
+    from helpers import bf16_exact
+    assert np.array_equal(bf16_exact(to_np(W16.view(torch.int16)).view(np.uint16)), Wt)      # Eq. 1, one rounding
+
+
+@pytest.mark.parametrize("T,d_out,d_in,R,lam1,lam2,s,minmax", [(77, 320, 192, 16, 2, 2, 0.25, True),
+                                                            (300, 576, 832, 64, 4, 8, 2.0, False),
+                                                            (2100, 512, 1024, 32, 4, 8, 1.0, True)])
+def test_two_matrix_layer_on_8x4_blocks(qb, oracle, codebook, T, d_out, d_in, R, lam1, lam2, s, minmax):
+    """Forward and backward: at any token count the call dequantizes the weight once (there is no in-kernel form for
+    this block shape) and contracts that."""
+    from gpu_util import assert_close_bf16, assert_close_f32, adapter_to_dev
+    print(f"case 8x4 layer T={T} {d_out}x{d_in} R={R} lam=({lam1},{lam2}) minmax={minmax}", flush=True)
+    L, qw, Wt, X, dY = _layer84(qb, oracle, codebook, 1950 + T, T, d_out, d_in, R, lam1, lam2, minmax)
+    ad = adapter_to_dev(L, lam1, lam2, s)
+    Y = qb.qblora_linear_fwd(qw, ad, X)
+    dX, dA, dB = qb.qblora_linear_bwd(qw, ad, X, dY)
+    torch.cuda.synchronize()
+    assert_close_bf16(Y, oracle.forward(Wt, L.X, L.A, L.B, lam1, lam2, s), "Y")
+    rX, rA, rB = oracle.backward(Wt, L.X, L.dY, L.A, L.B, lam1, lam2, s)
+    assert_close_bf16(dX, rX, "dX"); assert_close_f32(dA, rA, "dA"); assert_close_f32(dB, rB, "dB")
+
+
+def test_quantization_aware_loop_on_8x4_blocks(qb, oracle, codebook):
+    """Sec. 3.3 at (lambda1, lambda2) = (4, 8): single-matrix training calls, then the offset-shift merge, exact because
+    every 8 x 4 block lies in one adapter tile; the requantizing and 16-bit merges for lambdas that split blocks."""
+    from gpu_util import f32_to_dev, to_np, bf16_to_dev, assert_close_bf16, assert_close_f32
+    from helpers import bf16_exact
+    T, d_out, d_in, lam1, lam2, s = 200, 256, 512, 4, 8, 0.75
+    L, qw, Wt, X, dY = _layer84(qb, oracle, codebook, 1990, T, d_out, d_in, 8, lam1, lam2, True)
+    ow = qw.oracle_weight
+    Hb = synth.f32_to_bf16_bits((np.random.default_rng(1991).standard_normal((d_in // lam1, d_out // lam2)) * 0.05)
+                                .astype(np.float32))
+    H = bf16_to_dev(Hb)
+    Y = qb.qablora_linear_fwd(qw, H, lam1, lam2, s, X)
+    dX, dH = qb.qablora_linear_bwd(qw, H, lam1, lam2, s, X, dY)
+    torch.cuda.synchronize()
+    assert_close_bf16(Y, oracle.qa_forward(Wt, L.X, Hb, lam1, lam2, s), "Y")
+    rX, rH = oracle.qa_backward(Wt, L.X, L.dY, Hb, lam1, lam2, s)
+    assert_close_bf16(dX, rX, "dX"); assert_close_f32(dH, rH, "dH")
+    Hf = bf16_exact(Hb).astype(np.float32)
+    merged = qb.qablora_merge_quantize(qw, f32_to_dev(Hf), lam1, lam2, s, qb.MERGE_BETA_SHIFT)
+    torch.cuda.synchronize()
+    want = oracle.merge_beta_shift_tile(ow.beta, Hf, d_out, d_in, 8, 4, lam1, lam2, s)
+    assert np.array_equal(to_np(merged.beta).view(np.uint32), want.view(np.uint32))
+    assert np.array_equal(to_np(merged.codes), ow.codes) and merged.block == 32 and merged.block_rows == 8
+    with pytest.raises(qb.QBLoRAError):                      # lambda1 = 2 splits a 4-wide block
+        qb.qablora_merge_quantize(qw, torch.zeros((d_in // 2, d_out // 8), device=X.device), 2, 8, s, qb.MERGE_BETA_SHIFT)
+    H2 = synth.normal_f32(1992, 1, (d_in // 2, d_out // 2), 0.01)
+    out = qb.qablora_merge_quantize(qw, f32_to_dev(H2), 2, 2, s, qb.MERGE_REQUANT_MINMAX)
+    W16 = qb.qblora_merge_bf16(qw, f32_to_dev(H2), 2, 2, s)
+    torch.cuda.synchronize()
+    co, ao, bo = oracle.merge_requant_tile(ow.codes, ow.scales, ow.beta, ow.cb, H2, 8, 4, 2, 2, s)
+    bits = lambda a: np.ascontiguousarray(a).view(np.uint32).reshape(-1)
+    assert np.array_equal(to_np(out.codes), co)
+    assert np.array_equal(bits(to_np(out.scales)), bits(ao)) and np.array_equal(bits(to_np(out.beta)), bits(bo))
+    assert np.array_equal(to_np(W16.view(torch.int16)).view(np.uint16),
+                          oracle.merge_bf16_tile(ow.codes, ow.scales, ow.beta, ow.cb, H2, 8, 4, 2, 2, s))
+    with pytest.raises(qb.QBLoRAError):                      # the inference kernels do not take this block shape
+        qb.qblora_linear_decode(qw, X[:4].contiguous())
