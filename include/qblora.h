@@ -82,9 +82,10 @@ enum { QBLORA_MERGE_BETA_SHIFT = 0, QBLORA_MERGE_REQUANT_MINMAX = 1 };
  *              Sec. 3.3 names ("4 x 8": lambda1 = 4 inputs by lambda2 = 8 outputs); scale / offset index
  *              i*(d_in/4) + j.  Taken by the quantizers, qblora_dequantize_bf16, the forward / backward calls of both
  *              adapter forms at any token count (they dequantize the weight once per call into the workspace, as
- *              calls on many tokens do -- the workspace sizes say so), and the three merges (offset shift: 4 | lambda1
- *              and 8 | lambda2).  qblora_linear_fwd_noalloc, qblora_linear_decode and qblora_decode_pack return
- *              QBLORA_ERR_UNSUPPORTED for them.
+ *              calls on many tokens do -- the workspace sizes say so), the three merges (offset shift: 4 | lambda1
+ *              and 8 | lambda2) and qblora_linear_decode (at every token count the kernel of the mid-batch form,
+ *              i.e. bf16(fma(c, alpha, beta)) contracted; workspace from qblora_linear_decode_tokens_workspace_bytes).
+ *              qblora_linear_fwd_noalloc returns QBLORA_ERR_UNSUPPORTED for them.
  *   codes_tiled optional second copy of the codes (NULL = absent) in the order the forward kernel
  *              streams them, qblora_codes_tiled_bytes() bytes: output rows in tiles of 256, and for
  *              tile i and 64-wide input step j one contiguous 8 KiB block at ((i*(d_in/64) + j)*256 + r)*32

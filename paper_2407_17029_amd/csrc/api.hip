@@ -919,7 +919,7 @@ bool decode_regrouped(const qblora_qweight* qw) {
 DecodePack carve_pack(const qblora_qweight* qw, void* base) {
     Carver c(base);
     DecodePack p{};
-    const size_t rows = (size_t)((qw->d_out + 255) / 256) * 256, bpr = (size_t)(qw->d_in / qw->block);
+    const size_t rows = (size_t)((qw->d_out + 255) / 256) * 256, bpr = (size_t)(qw->d_in / kBlock);   // 64-input runs of codes
     p.codes = c.take<uint8_t>(rows * bpr * 32);
     if (block_rows_of(qw) == 8) {            // scales and offsets of 8 x 8 blocks are read where they are
         p.scales = qw->scales; p.beta = qw->beta;
@@ -941,7 +941,6 @@ size_t qblora_decode_pack_bytes(const qblora_qweight* qw) {
 int qblora_decode_pack(const qblora_qweight* qw, void* pack, void* stream) {
     int rc = check_qweight(qw, true, true);
     if (rc) return rc;
-    if (half_blocks(qw)) return QBLORA_ERR_UNSUPPORTED;
     if (!pack) return QBLORA_ERR_NULL;
     hipStream_t st = as_stream(stream);
     DecodePack p = carve_pack(qw, pack);
@@ -970,7 +969,7 @@ size_t qblora_linear_decode_workspace_bytes(const qblora_qweight* qw) {
 size_t qblora_linear_decode_tokens_workspace_bytes(const qblora_qweight* qw, int32_t T) {
     if (check_qweight(qw, false, true)) return 0;
     size_t part = 0;
-    for (int32_t t0 = kDecodeMaxTokens < T ? 0 : T; t0 < T; t0 += kMidChunk)        // chunks of the mid-batch form
+    for (int32_t t0 = (kDecodeMaxTokens < T || half_blocks(qw)) ? 0 : T; t0 < T; t0 += kMidChunk)   // chunks of the mid-batch form
         part = std::max(part, w4_mid_part_bytes(qw->d_out, qw->d_in, std::min(kMidChunk, T - t0)));
     return qblora_linear_decode_workspace_bytes(qw) + align_up(part);
 }
@@ -978,7 +977,6 @@ int qblora_linear_decode(const qblora_qweight* qw, const void* pack, const qblor
                          void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_qweight(qw, true, true);
     if (rc) return rc;
-    if (half_blocks(qw)) return QBLORA_ERR_UNSUPPORTED;      // the inference kernels know 64-blocks and 8 x 8 blocks
     if (T < 0 || T > kMidMaxTokens) return QBLORA_ERR_SHAPE;
     if (T == 0) return QBLORA_OK;
     if (!X || !Y) return QBLORA_ERR_NULL;
@@ -986,7 +984,7 @@ int qblora_linear_decode(const qblora_qweight* qw, const void* pack, const qblor
         (reinterpret_cast<uintptr_t>(pack) & 255))
         return QBLORA_ERR_SHAPE;
     hipStream_t st = as_stream(stream);
-    const bool mid = T > kDecodeMaxTokens;
+    const bool mid = T > kDecodeMaxTokens || half_blocks(qw);   // 8 x 4 blocks: the mid-batch kernel at every token count
     const size_t scale_bytes = qblora_linear_decode_workspace_bytes(qw);
     const size_t need = mid ? qblora_linear_decode_tokens_workspace_bytes(qw, T) : (pack ? 0 : scale_bytes);
     if (need > 0 && (!workspace || workspace_bytes < need)) return QBLORA_ERR_WORKSPACE;
@@ -1014,7 +1012,8 @@ int qblora_linear_decode(const qblora_qweight* qw, const void* pack, const qblor
         const int32_t tc = std::min(kMidChunk, T - t0);
         if ((rc = launch_w4_mid(codes, scales, beta, codebook_of(qw), pack ? 1 : 0, qw->d_out, qw->d_in,
                                 X + (int64_t)t0 * qw->d_in, tc, Y + (int64_t)t0 * qw->d_out,
-                                w4_mid_part_bytes(qw->d_out, qw->d_in, tc) ? part : nullptr, st, block_rows_of(qw), regrouped)))
+                                w4_mid_part_bytes(qw->d_out, qw->d_in, tc) ? part : nullptr, st, block_rows_of(qw), regrouped,
+                                block_rows_of(qw) == 8 ? block_cols_of(qw) : 8)))
             return rc;
     }
     return QBLORA_OK;

@@ -180,7 +180,7 @@ int w4_mid_splits(int d_out, int d_in, int T);
 size_t w4_mid_part_bytes(int d_out, int d_in, int T);
 int launch_w4_mid(const uint8_t* codes, const float* scales, const float* beta, const Codebook& cb, int tiled, int d_out,
                   int d_in, const qblora_bf16* X, int T, qblora_bf16* Y, float* part, hipStream_t st, int block_rows = 1,
-                  int regrouped = 0);
+                  int regrouped = 0, int block_cols = 8);
 int launch_merge_beta_shift(const MergeDesc& d, hipStream_t st);
 
 }  // namespace qblora

@@ -72,11 +72,16 @@ struct Slot {
     u32x4 cw;
     float sc, be;              // 64-blocks: the row's scale and offset of this step
     f32x4 sc4, be4;            // 8 x 8 blocks: those of the lane's four block columns
+    f32x4 sc4b, be4b;          // blocks of 8 rows x 4 inputs (BR = 84): the lane has eight block columns, these are 4 .. 7
 };
 
 template <int N, int BR, bool BETA>
 __device__ __forceinline__ void wait_slot(Slot<BR>& s) {
-    if constexpr (BR == 8) {
+    if constexpr (BR == 84) {
+        if constexpr (BETA)
+            asm volatile("s_waitcnt vmcnt(%5)" : "+v"(s.cw), "+v"(s.sc4), "+v"(s.sc4b), "+v"(s.be4), "+v"(s.be4b) : "n"(N) : "memory");
+        else asm volatile("s_waitcnt vmcnt(%3)" : "+v"(s.cw), "+v"(s.sc4), "+v"(s.sc4b) : "n"(N) : "memory");
+    } else if constexpr (BR == 8) {
         if constexpr (BETA) asm volatile("s_waitcnt vmcnt(%3)" : "+v"(s.cw), "+v"(s.sc4), "+v"(s.be4) : "n"(N) : "memory");
         else asm volatile("s_waitcnt vmcnt(%2)" : "+v"(s.cw), "+v"(s.sc4) : "n"(N) : "memory");
     } else {
@@ -85,13 +90,15 @@ __device__ __forceinline__ void wait_slot(Slot<BR>& s) {
     }
 }
 
-// TB: 32-token blocks; BETA: offsets present; BR: 1 (64 inputs of one row) or 8 (8 rows x 8 inputs);
+// TB: 32-token blocks; BETA: offsets present; BR: 1 (64 inputs of one row), 8 (8 rows x 8 inputs) or 84 (8 rows x 4 inputs);
 // REGROUPED: INT4 model whose code dwords were regrouped by the decode pack (codebook 0..15, offsets present)
 template <int TB, bool BETA, int BR, bool REGROUPED>
 __global__ __launch_bounds__(kMidThreads) void k_w4_mid(MidDesc d) {
     static_assert(!REGROUPED || (BETA && BR == 1), "regrouped codes belong to INT4 models in 64-blocks");
     constexpr int kStageBytes = TB * 32 * 128;
-    constexpr int kOps = TB + 2 + (BETA ? 1 : 0);              // vector-memory operations per wave and step
+    static_assert(BR == 1 || BR == 8 || BR == 84, "block shape");
+    constexpr int kParamLoads = BR == 84 ? 2 : 1;              // 16-byte (or 4-byte) loads of scales per step; as many of offsets
+    constexpr int kOps = TB + 1 + kParamLoads * (BETA ? 2 : 1);   // vector-memory operations per wave and step
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* const sX = smem;                                              // kStages token tiles
     float2* const sT = reinterpret_cast<float2*>(smem + kStages * kStageBytes);  // byte -> (c[lo], c[hi]), replicated
@@ -121,7 +128,10 @@ __global__ __launch_bounds__(kMidThreads) void k_w4_mid(MidDesc d) {
     const uint32_t c_off = (uint32_t)(run * 32 + 16 * h);
     uint32_t s_off;
     int64_t s_step;                                            // bytes per step in the scale / offset arrays
-    if constexpr (BR == 8) {
+    if constexpr (BR == 84) {                                  // 16 block columns per step, the lane's half: 8
+        s_off = (uint32_t)((((int64_t)(n >> 3) * (d_in >> 2)) + 8 * h) * 4);
+        s_step = 64;
+    } else if constexpr (BR == 8) {
         s_off = (uint32_t)((((int64_t)(n >> 3) * (d_in >> 3)) + 4 * h) * 4);
         s_step = 32;
     } else {
@@ -149,7 +159,11 @@ __global__ __launch_bounds__(kMidThreads) void k_w4_mid(MidDesc d) {
     auto issue_codes = [&](Slot<BR>& sl, int step) __attribute__((always_inline)) {
         const int64_t sc = min(step, s_end - 1);
         load16(sl.cw, c_off, cbase + sc * c_step);
-        if constexpr (BR == 8) {
+        if constexpr (BR == 84) {
+            load16f(sl.sc4, s_off, sbase + sc * s_step);
+            load16f(sl.sc4b, s_off + 16, sbase + sc * s_step);
+            if constexpr (BETA) { load16f(sl.be4, s_off, bbase + sc * s_step); load16f(sl.be4b, s_off + 16, bbase + sc * s_step); }
+        } else if constexpr (BR == 8) {
             load16f(sl.sc4, s_off, sbase + sc * s_step);
             if constexpr (BETA) load16f(sl.be4, s_off, bbase + sc * s_step);
         } else {
@@ -184,14 +198,20 @@ __global__ __launch_bounds__(kMidThreads) void k_w4_mid(MidDesc d) {
     // 8) of the j-th A operand (code dword j).  Table form: unit_a fetches the byte's (c[lo], c[hi]) pair from LDS,
     // unit_b scales, offsets and rounds; an INT4 model's regrouped dword holds input 0, 2, 4, 6, 1, 3, 5, 7 in its
     // nibbles, so the bytes of (w & 0x0F0F0F0F) are inputs 0, 4, 1, 5 and those of ((w >> 4) & 0x0F0F0F0F) 2, 6, 3, 7.
-    struct Params { uint32_t cw[4]; float a[4], b[4]; };
+    struct Params { uint32_t cw[4]; float a[8], b[8]; };       // scale / offset of inputs 0..3 and 4..7 of each code dword
     auto params = [&](const Slot<BR>& sl) __attribute__((always_inline)) {
         Params p;
         p.cw[0] = sl.cw.x; p.cw[1] = sl.cw.y; p.cw[2] = sl.cw.z; p.cw[3] = sl.cw.w;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            p.a[j] = BR == 8 ? sl.sc4[j] : sl.sc;
-            p.b[j] = !BETA ? 0.0f : BR == 8 ? sl.be4[j] : sl.be;
+        for (int e = 0; e < 8; ++e) {
+            const int j = e >> 1;
+            if constexpr (BR == 84) {
+                p.a[e] = e < 4 ? sl.sc4[e] : sl.sc4b[e - 4];
+                p.b[e] = !BETA ? 0.0f : e < 4 ? sl.be4[e] : sl.be4b[e - 4];
+            } else {
+                p.a[e] = BR == 8 ? sl.sc4[j] : sl.sc;
+                p.b[e] = !BETA ? 0.0f : BR == 8 ? sl.be4[j] : sl.be;
+            }
         }
         return p;
     };
@@ -208,7 +228,8 @@ __global__ __launch_bounds__(kMidThreads) void k_w4_mid(MidDesc d) {
         } else {
             lo = tv.x; hi = tv.y;
         }
-        return pack_bf16(weight(lo, p.a[j], p.b[j]), weight(hi, p.a[j], p.b[j]));
+        const int e = 2 * j + (i >> 1);                        // byte i of the dword: inputs 2i, 2i+1
+        return pack_bf16(weight(lo, p.a[e], p.b[e]), weight(hi, p.a[e], p.b[e]));
     };
     // all four operands at once (before the loop)
     auto dequantize = [&](const Slot<BR>& sl, bf16x8 (&wf)[4]) __attribute__((always_inline)) {
@@ -259,6 +280,7 @@ __global__ __launch_bounds__(kMidThreads) void k_w4_mid(MidDesc d) {
     for (int u = 0; u < kStages; ++u) {                         // defined values for the fields a variant never loads
         slot[u].sc = 0.0f; slot[u].be = 0.0f;
         slot[u].sc4 = f32x4{0.f, 0.f, 0.f, 0.f}; slot[u].be4 = f32x4{0.f, 0.f, 0.f, 0.f};
+        slot[u].sc4b = f32x4{0.f, 0.f, 0.f, 0.f}; slot[u].be4b = f32x4{0.f, 0.f, 0.f, 0.f};
     }
     bf16x8 wf[2][4];                                            // operands of this step and of the next
     __syncthreads();                                            // the table is complete
@@ -352,7 +374,9 @@ int launch_one(const MidDesc& d, unsigned blocks, hipStream_t st) {
 }
 
 template <int TB>
-int launch_tb(const MidDesc& d, unsigned blocks, hipStream_t st, int block_rows, int regrouped) {
+int launch_tb(const MidDesc& d, unsigned blocks, hipStream_t st, int block_rows, int regrouped, int block_cols) {
+    if (block_rows == 8 && block_cols == 4)
+        return d.beta ? launch_one<TB, true, 84, false>(d, blocks, st) : launch_one<TB, false, 84, false>(d, blocks, st);
     if (block_rows == 8)
         return d.beta ? launch_one<TB, true, 8, false>(d, blocks, st) : launch_one<TB, false, 8, false>(d, blocks, st);
     if (regrouped) return d.beta ? launch_one<TB, true, 1, true>(d, blocks, st) : QBLORA_ERR_UNSUPPORTED;
@@ -387,7 +411,7 @@ size_t w4_mid_part_bytes(int d_out, int d_in, int T) {
 
 int launch_w4_mid(const uint8_t* codes, const float* scales, const float* beta, const Codebook& cb, int tiled, int d_out,
                   int d_in, const qblora_bf16* X, int T, qblora_bf16* Y, float* part, hipStream_t st, int block_rows,
-                  int regrouped) {
+                  int regrouped, int block_cols) {
     if (T < 1 || T > 128 || d_in % kBlock != 0 || d_out < 1) return QBLORA_ERR_SHAPE;
     // 32-bit lane offsets: the arrays of one weight and the token rows must stay below 4 GiB
     if ((int64_t)((d_out + 255) / 256) * 256 * (d_in / 2) >= ((int64_t)1 << 32) || (int64_t)T * d_in * 2 >= ((int64_t)1 << 32))
@@ -399,9 +423,9 @@ int launch_w4_mid(const uint8_t* codes, const float* scales, const float* beta, 
     const unsigned blocks = (unsigned)(((d_out + kMidRows - 1) / kMidRows) * splits);
     int rc;
     switch (w4_mid_token_blocks(T)) {
-        case 1: rc = launch_tb<1>(d, blocks, st, block_rows, regrouped); break;
-        case 2: rc = launch_tb<2>(d, blocks, st, block_rows, regrouped); break;
-        default: rc = launch_tb<4>(d, blocks, st, block_rows, regrouped); break;
+        case 1: rc = launch_tb<1>(d, blocks, st, block_rows, regrouped, block_cols); break;
+        case 2: rc = launch_tb<2>(d, blocks, st, block_rows, regrouped, block_cols); break;
+        default: rc = launch_tb<4>(d, blocks, st, block_rows, regrouped, block_cols); break;
     }
     if (rc || splits == 1) return rc;
     const int64_t count = (int64_t)T * d_out;

@@ -287,5 +287,16 @@ def test_quantization_aware_loop_on_8x4_blocks(qb, oracle, codebook):
     assert np.array_equal(bits(to_np(out.scales)), bits(ao)) and np.array_equal(bits(to_np(out.beta)), bits(bo))
     assert np.array_equal(to_np(W16.view(torch.int16)).view(np.uint16),
                           oracle.merge_bf16_tile(ow.codes, ow.scales, ow.beta, ow.cb, H2, 8, 4, 2, 2, s))
-    with pytest.raises(qb.QBLoRAError):                      # the inference kernels do not take this block shape
-        qb.qblora_linear_decode(qw, X[:4].contiguous())
+    # inference on the merged model (and on the base): the mid-batch kernel at every token count, with and without
+    # the tile-ordered code copy
+    for weight, codes_o, a_o, b_o in ((merged, ow.codes, ow.scales, want), (out, co, ao, bo)):
+        Wm = oracle.dequantize_tile(codes_o, a_o, b_o, synth.codebook_int4(), 8, 4, 2)
+        pack = qb.qblora_decode_pack(weight)
+        for Tn in (1, 16, 40, 200):
+            Yd = qb.qblora_linear_decode(weight, X[:Tn].contiguous())
+            Yp = qb.qblora_linear_decode(weight, X[:Tn].contiguous(), pack=pack)
+            torch.cuda.synchronize()
+            assert_close_bf16(Yd, oracle.forward(Wm, L.X[:Tn], None, None, 1, 1, 0.0), f"Y (8x4 inference, T={Tn})")
+            assert torch.equal(Yd, Yp)
+    with pytest.raises(qb.QBLoRAError):                      # the forward on the library's own scratch does not take the shape
+        qb.qblora_linear_fwd_noalloc(qw, None, X, torch.empty((T, d_out), dtype=torch.bfloat16, device=X.device))
