@@ -89,7 +89,10 @@ class Stack:
         self.proj = []
         for i, p in enumerate(wl.projections):
             W = torch.from_numpy(host[("W", i)]).to(dev)
-            qw = qb.qblora_quantize_blockwise(W, wl.block, qb.QUANT_ABSMAX_CODEBOOK, self.cb, self.scale_mode)
+            # the tile-ordered second copy of the codes serves the dequantize-in-kernel contraction of short
+            # batches; at this token count the calls dequantize the row-major codes once, so none is asked for
+            qw = qb.qblora_quantize_blockwise(W, wl.block, qb.QUANT_ABSMAX_CODEBOOK, self.cb, self.scale_mode,
+                                              tiled=T < qb.qblora_dense_min_tokens())
             self.proj.append(dict(p=p, W=W, qw=qw, merged=None,
                                   H=torch.empty((p.d_in // wl.lam, p.d_out // wl.lam), dtype=torch.float32, device=dev)))
         self.set_rank(rank)
@@ -244,14 +247,17 @@ def measure(S, steps, warmup, side_steps, plain_events=False, calibration_copy=F
 
         for j, st in enumerate(S.proj):
             S.layer_pass(st, hook if j == big else None)
-        # the merge batch: one pair around all tile products, one around all merges
+        # the merge batch: one pair around all tile products, one (registered with the library, so that it sits
+        # directly around the launch) around the one launch that merges all projections
         if "merge" in which:
+            events["tile_product"][i][0].record()
             for st in S.proj:
                 qb.qblora_tile_product(st["ad"], st["p"].d_in, st["p"].d_out, st["H"], S.ws)
-            events["merge"][i][0].record()
-            for st in S.proj:
-                qb.qablora_merge_quantize(st["qw"], st["H"], lam, lam, wl.s, qb.MERGE_REQUANT_MINMAX, out=st["merged"])
-            events["merge"][i][1].record()
+            events["tile_product"][i][1].record()
+            qb.qblora_profile_events(qb.PROFILE_MERGE, *events["merge"][i])
+            qb.qablora_merge_quantize_batch([st["qw"] for st in S.proj], [st["H"] for st in S.proj], lam, lam, wl.s,
+                                            qb.MERGE_REQUANT_MINMAX, outs=[st["merged"] for st in S.proj])
+            qb.qblora_profile_events(qb.PROFILE_MERGE, None, None)
         else:
             S.merge_batch()
 
@@ -329,7 +335,9 @@ def measure(S, steps, warmup, side_steps, plain_events=False, calibration_copy=F
             "grad_reduce": {"ms": stats(raw["grad_reduce"])},
             "prep": {"ms": stats(raw["prep"])},
             "merge_requant_batch": hbm("merge", merge_batch_bytes,
-                                       f"{len(S.proj)} requantizing merges back to back (all projections of the layer)"),
+                                       f"the requantizing merge of all {len(S.proj)} projections of the layer, one launch"),
+            "tile_products": {"ms": stats(raw["tile_product"]),
+                              "note": f"H = A B of all {len(S.proj)} projections, {len(S.proj)} launches back to back"},
         },
     }
     for k in ("quantize", "adapter_fwd", "adapter_bwd", "adapter_grads", "merge"):

@@ -703,8 +703,8 @@ int oracle_merge_beta_shift(const float* beta, const float* H, int64_t d_out, in
 }
 
 // ---------------------------------------------------------------------------
-// Two-dimensional quantization blocks (Sec. 3.3: block quantization "with
-// sizes of 4 x 8 or 8 x 8"): a block is br consecutive output rows x bc
+// Two-dimensional quantization blocks (the 4 x 8 and 8 x 8 shapes named in
+// Sec. 3.3): a block is br consecutive output rows x bc
 // consecutive inputs; its scale / offset live at [(n/br) * (d_in/bc) + k/bc].
 // With lam1 % bc == 0 and lam2 % br == 0 every block lies inside one
 // (lam1 x lam2) tile of the adapter, so get_new_beta (Alg. 2) is exact: the

@@ -48,12 +48,13 @@ struct DecodeDesc {
 
 constexpr int kReplicas = 16;               // copies of the byte -> (bf16 c[lo], bf16 c[hi]) table
 
-struct DecodeRegs {                         // one group = 4 consecutive blocks of the lane's row
-    uint2 c[4];                             // the lane's quarter of each block's codes: 16 codes
-    float a[4], b[4];                       // scale and offset of each block
-    float2 a2[4], b2[4];                    // BR = 8: scales and offsets of the lane's two block columns
-    int xb[4];                              // XALL: the (redirected) block whose activations go with c[q]
-    uint4 x[4][2];                          // activations of the lane's token, 8 per MFMA (fetched in operand order)
+template <int G>
+struct DecodeRegs {                         // one group = G consecutive blocks of the lane's row
+    uint2 c[G];                             // the lane's quarter of each block's codes: 16 codes
+    float a[G], b[G];                       // scale and offset of each block
+    float2 a2[G], b2[G];                    // BR = 8: scales and offsets of the lane's two block columns
+    int xb[G];                              // XALL: the (redirected) block whose activations go with c[q]
+    uint4 x[G][2];                          // activations of the lane's token, 8 per MFMA (fetched in operand order)
     uint4 xg[8];                            // XLDS: as fetched, token 2p + (lane >> 5), chunk lane & 31 of the group
 };
 
@@ -67,22 +68,25 @@ struct DecodeRegs {                         // one group = 4 consecutive blocks 
 // the bytes of the codes through the vector memory path (every lane fetches its own copy of the 16 activations
 // it shares with 15 others), and that path, not HBM, set the time.
 constexpr int kXAllBytes = 40 * 1024;
-template <bool BETA, int BR, bool DIRECT, int XMODE>
+template <bool BETA, int BR, bool DIRECT, int XMODE, int G = 4>
 __device__ __forceinline__ void w4_decode(const DecodeDesc& d);
 
 template <bool BETA, int BR, bool DIRECT = false, int XMODE = 0>
 __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) { w4_decode<BETA, BR, DIRECT, XMODE>(d); }
 
-// (limiting this form to 84 registers for six waves per SIMD, so that the 1376 workgroups of a 22016-row layer
-// are resident at once, spills 24 of them and nearly doubles the time: 45.8 against 25.6 us)
-template <bool BETA, bool DIRECT>
+// G: blocks per register set.  Four keep the most bytes in flight per wave and use 108 registers (four waves per
+// SIMD, 1024 workgroups resident); two use 76, six waves per SIMD, so that the 1376 workgroups of a 22016-row layer
+// are resident at once (25.2 against 26.0 us; limiting the four-block form to 84 registers instead spills 24 of
+// them and nearly doubles the time).  Layers that fit the 1024 slots are faster with four (4096 rows: 5.4 against 6.0).
+template <bool BETA, bool DIRECT, int G>
 __global__ __launch_bounds__(256) void k_w4_decode_xall(DecodeDesc d) {
-    w4_decode<BETA, 1, DIRECT, 2>(d);
+    w4_decode<BETA, 1, DIRECT, 2, G>(d);
 }
 
-template <bool BETA, int BR, bool DIRECT, int XMODE>
+template <bool BETA, int BR, bool DIRECT, int XMODE, int G>
 __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     constexpr bool XLDS = XMODE == 1, XALL = XMODE == 2;
+    static_assert(G == 4 || !XLDS, "the staged activation rows hold four blocks");
     static_assert(!DIRECT || (BETA && BR == 1), "the table-free form needs offsets and 64-blocks");
     extern __shared__ __align__(16) unsigned char x_all[];       // XALL: [T][d_in * 2 + 16] bytes
     // entry e of replica q at e*kReplicas + q: bf16 pairs (4 bytes), or fp32 pairs (8 bytes) for BR = 8
@@ -103,7 +107,7 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     const int n0 = rg * 16;
     const int n = min(n0 + nl, d.d_out - 1);                  // rows past the end are computed, not stored
     const int bpr = d.d_in / kBlock;
-    const int groups = (bpr + 3) / 4;
+    const int groups = (bpr + G - 1) / G;
     if constexpr (DIRECT) {
         // no table
     } else if constexpr (BR == 8) {
@@ -139,10 +143,10 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     // Every load is unconditional: a block past the end of the row is redirected to the last block and
     // given scale = offset = 0; lanes whose token does not exist read the last token's row and produce
     // output rows that are never stored.
-    auto load = [&](DecodeRegs& r, int j) __attribute__((always_inline)) {
+    auto load = [&](DecodeRegs<G>& r, int j) __attribute__((always_inline)) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int b = 4 * j + q;
+        for (int q = 0; q < G; ++q) {
+            const int b = G * j + q;
             const bool in = b < bpr;
             const int bc = in ? b : bpr - 1;
             r.c[q] = *reinterpret_cast<const uint2*>(crow + (int64_t)bc * cstep);
@@ -210,14 +214,14 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
         }
         return __builtin_bit_cast(bf16x8, make_uint4(o[0], o[1], o[2], o[3]));
     };
-    auto compute = [&](const DecodeRegs& r) __attribute__((always_inline)) {
+    auto compute = [&](const DecodeRegs<G>& r) __attribute__((always_inline)) {
         if constexpr (XLDS) {
 #pragma unroll
             for (int p = 0; p < 8; ++p)
                 if (2 * p < d.T) *reinterpret_cast<uint4*>(xs + (2 * p + xtok) * kXPitch + xchunk * 16) = r.xg[p];
         }
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < G; ++q) {
             bf16x8 x0, x1;
             if constexpr (XLDS) {
                 const unsigned char* xq = xs + nl * kXPitch + 128 * q + 32 * kg;    // k = 64q + 16kg .. +15 of token nl
@@ -247,7 +251,7 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     };
 
     // two register sets: the loads of the wave's next group are in flight while this one is contracted
-    DecodeRegs r0, r1;
+    DecodeRegs<G> r0, r1;
     int j = wave;
     if (j < groups) load(r0, j);
     if constexpr (XALL) {                                     // behind the first loads of codes: both are in flight together
@@ -323,11 +327,13 @@ int launch_w4_decode(const uint8_t* codes, const float* scales, const float* bet
             hipLaunchKernelGGL(kern, grid, dim3(256), x_all_bytes, st, d);
             return launch_status();
         };
+        const bool small_sets = grid.x > 1024;      // more workgroups than fit at four waves per SIMD
         if (regrouped) {
             if (!beta || !tiled) return QBLORA_ERR_UNSUPPORTED;
-            return all(k_w4_decode_xall<true, true>);
+            return small_sets ? all(k_w4_decode_xall<true, true, 2>) : all(k_w4_decode_xall<true, true, 4>);
         }
-        return beta ? all(k_w4_decode_xall<true, false>) : all(k_w4_decode_xall<false, false>);
+        if (beta) return small_sets ? all(k_w4_decode_xall<true, false, 2>) : all(k_w4_decode_xall<true, false, 4>);
+        return small_sets ? all(k_w4_decode_xall<false, false, 2>) : all(k_w4_decode_xall<false, false, 4>);
     }
     if (block_rows == 8) {                  // its fp32 pair table and the activation rows together leave two
                                             // workgroups per CU: measured slower (68 vs 64 us at T = 16), not used

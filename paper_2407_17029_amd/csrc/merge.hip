@@ -7,11 +7,17 @@
 //
 // Requantize tiling: a workgroup of 512 threads owns 64 output rows x 256 input columns and every
 // thread owns half (32 elements) of one 64-block; the block minimum and maximum are combined over
-// the two lanes with DPP.  Measured on a 22016 x 8192 weight, lambda 2 (95 us): without the arithmetic 93 us,
-// without the fetches of H 55, without the stores 51, with neither H nor arithmetic 48 -- the fetches of H (128
-// byte pieces 44 KB apart) and the stores (128 byte pieces 4 KB apart, block parameters 16 bytes per row) each
-// cost as much as everything else together; a variant that walks eight tiles per workgroup with the next
-// tile's loads in flight and stores whole lines of block parameters was slower (fewer waves).  With lambda 8
+// the two lanes with DPP.  Measured on a 22016 x 8192 weight, lambda 2 (95 us before the streaming stores, 82-85
+// with them): the memory accesses alone, arithmetic removed, take as long as the whole kernel (a model of the
+// kernel that keeps only its loads, the LDS staging and its stores: 95 us; its loads alone 57 us = 5.1 TB/s; the
+// code stores add 24 us, the 16-byte pieces of block parameters 14 more on top of them and 2 on their own), and the
+// vector ALU is busy 0.73 of the time underneath.  Tile shapes from 16 x 2048 to 128 x 256, one block per
+// thread, linear / grouped / 8 x 8 super-tile orders and two or three resident workgroups per CU were all equal
+// or slower in that model; a variant that walks eight tiles per workgroup with the next tile's loads in flight and
+// stores whole lines of block parameters was slower too (fewer waves).  What helps is the streaming hint on the
+// code stores.  For scale: a plain elementwise add of two arrays into a third runs at 0.72-0.75 of the HBM peak
+// on this chip and a plain copy at 0.66; this kernel's 2 : 1 mix of reads and writes in 128-byte pieces (codes:
+// 4 KB apart, H: 44 KB apart) reaches 0.52-0.60.  With lambda 8
 // (H a sixteenth of the bytes) the vector ALU is the limit: one thread
 // per block (64 elements) keeps the per-thread overhead (addresses, the two divisions of a block)
 // lowest but gives only 4 waves per SIMD over a 4096 x 4096 weight, all resident at once and moving
@@ -29,6 +35,7 @@ namespace qblora {
 namespace {
 
 constexpr int NT = 64, KT = 256;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 constexpr int kMergeThreads = 512;            // 64 rows x 8 half blocks
 
 struct TileGeom {
@@ -204,8 +211,10 @@ __device__ __forceinline__ void merge_requant_tile(const MergeDesc& d, const uns
         const float q = __fadd_rn(__fmul_rn(__fsub_rn(w[j], lo), inv), 12582912.0f);
         p[j >> 3] += __float_as_uint(q) << (4 * (j & 7));
     }
-    *reinterpret_cast<uint4*>(d.codes_out + ((int64_t)n * d.d_in + k) / 2) =
-        make_uint4(p[0] - kMagicSum, p[1] - kMagicSum, p[2] - kMagicSum, p[3] - kMagicSum);
+    // written once and not read again here: a streaming store (measured 10 % off a 22016 x 8192 merge; on the
+    // loads the same hint gains nothing or, where neighbouring tiles share lines of H, costs)
+    const u32x4 pv = {p[0] - kMagicSum, p[1] - kMagicSum, p[2] - kMagicSum, p[3] - kMagicSum};
+    __builtin_nontemporal_store(pv, reinterpret_cast<u32x4*>(d.codes_out + ((int64_t)n * d.d_in + k) / 2));
     if (sub == 0) {
         d.alpha_out[blk] = al;
         d.beta_out[blk] = lo;

@@ -148,6 +148,13 @@ inline dim3 quant_grid(int d_out, int bpr) {
                 (unsigned)((row_tiles + kQGridY - 1) / kQGridY));
 }
 
+// 16 bytes of codes from LDS to global memory with the streaming hint: written once, read by a later launch (5 %
+// off a 22016 x 8192 quantization; the same hint on the loads of W costs 30 %)
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+__device__ __forceinline__ void stream16(uint8_t* dst, const void* lds_src) {
+    __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(lds_src), reinterpret_cast<u32x4*>(dst));
+}
+
 // codes of the tile from LDS (cs[u][g] = 4 codes of float4 group g of row u) to both global layouts
 __device__ __forceinline__ void store_tile_codes(const uint16_t (&cs)[kQRows][256], const QuantTile& q, int d_out, int bpr,
                                                  uint8_t* __restrict__ codes, uint8_t* __restrict__ tiled) {
@@ -156,14 +163,12 @@ __device__ __forceinline__ void store_tile_codes(const uint16_t (&cs)[kQRows][25
         const int u = t >> 5, piece = t & 31;                 // 16-byte piece of the row's 512 bytes
         const int row = q.row0 + u, blk = q.blk0 + (piece >> 1);
         if (row < d_out && blk < bpr)
-            *reinterpret_cast<uint4*>(codes + ((int64_t)row * bpr + blk) * 32 + (piece & 1) * 16) =
-                *reinterpret_cast<const uint4*>(&cs[u][piece * 8]);
+            stream16(codes + ((int64_t)row * bpr + blk) * 32 + (piece & 1) * 16, &cs[u][piece * 8]);
     } else if (tiled) {
         const int tt = t - 128, b = tt >> 3, u = (tt >> 1) & 3, half = tt & 1;
         const int row = q.row0 + u, blk = q.blk0 + b;
         if (row < d_out && blk < bpr)
-            *reinterpret_cast<uint4*>(tiled + tiled_run_offset(row, blk, bpr) + half * 16) =
-                *reinterpret_cast<const uint4*>(&cs[u][b * 16 + half * 8]);
+            stream16(tiled + tiled_run_offset(row, blk, bpr) + half * 16, &cs[u][b * 16 + half * 8]);
     }
 }
 
@@ -248,7 +253,7 @@ __global__ __launch_bounds__(256) void k_quantize_minmax(const float4* __restric
     }
 }
 
-// Both quantizers on 8 x 8 blocks (Sec. 3.3: block quantization "of 4 x 8 or 8 x 8"): a block is 8 output
+// Both quantizers on 8 x 8 blocks (the two-dimensional block shapes of Sec. 3.3): a block is 8 output
 // rows x 8 inputs, scale index (n/8)*(d_in/8) + k/8.  A workgroup owns 8 rows x 512 inputs = 64 blocks; the
 // four lanes of a quad hold block t/4, lane q of the quad its rows 2q and 2q+1 (two 16-byte loads each), so
 // a wave reads 512 contiguous bytes of each of the 8 rows and the block reduction is two quad swaps.
@@ -313,13 +318,11 @@ __global__ __launch_bounds__(256) void k_quantize_tile8(const float4* __restrict
     if (t < 128) {
         const int r = t >> 4, piece = t & 15;                // 16-byte piece of the row's 256 bytes (32 inputs)
         if (row0 + r < d_out && col0 + 32 * piece < d_in)
-            *reinterpret_cast<uint4*>(codes + ((int64_t)(row0 + r) * d_in + col0) / 2 + 16 * piece) =
-                *reinterpret_cast<const uint4*>(&cs[r][16 * piece]);
+            stream16(codes + ((int64_t)(row0 + r) * d_in + col0) / 2 + 16 * piece, &cs[r][16 * piece]);
     } else if (tiled) {
         const int tt = t - 128, ks = tt >> 4, r = (tt >> 1) & 7, half = tt & 1;   // 64-wide input step of the tile copy
         if (row0 + r < d_out && col0 + 64 * ks < d_in)
-            *reinterpret_cast<uint4*>(tiled + tiled_run_offset(row0 + r, col0 / 64 + ks, bpr64) + half * 16) =
-                *reinterpret_cast<const uint4*>(&cs[r][32 * ks + 16 * half]);
+            stream16(tiled + tiled_run_offset(row0 + r, col0 / 64 + ks, bpr64) + half * 16, &cs[r][32 * ks + 16 * half]);
     }
     if (t < 64 * NB && col0 + BC * t < d_in && row0 < d_out) {
         const int64_t blk = (int64_t)(row0 / 8) * (d_in / BC) + col0 / BC + t;

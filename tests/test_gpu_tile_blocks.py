@@ -206,7 +206,7 @@ def test_requantizing_and_16bit_merge_on_8x8_blocks(qb, oracle, codebook, d_out,
     assert_close_bf16(Ym, oracle.forward(Wm, L.X, None, None, 1, 1, 0.0), "Y (merged, 8x8)")
 
 
-# ---- blocks of 8 output rows x 4 inputs (block size 32; Sec. 3.3: blocks "of 4 x 8 or 8 x 8") ------------------------
+# ---- blocks of 8 output rows x 4 inputs (block size 32; the other block shape of Sec. 3.3) ------------------------
 
 def _layer84(qb, oracle, codebook, seed, T, d_out, d_in, R, lam1, lam2, minmax):
     from gpu_util import f32_to_dev, bf16_to_dev, OracleWeight

@@ -1,4 +1,4 @@
-"""Pins for the oracle's two-dimensional quantization blocks (Sec. 3.3: blocks "of 4 x 8 or 8 x 8") and the
+"""Pins for the oracle's two-dimensional quantization blocks (the 4 x 8 and 8 x 8 shapes of Sec. 3.3) and the
 exact offset-shift merge they allow at lambda1 = lambda2 = 8 (Alg. 2 get_new_beta; ablation "The balancing
 factor of QA-BLoRA").  A block of lambda1 inputs x lambda2 outputs is br = lambda2 rows x bc = lambda1 columns
 of the stored [d_out, d_in] weight: block size 32 with (lambda1, lambda2) = (4, 8) is br = 8, bc = 4."""
