@@ -628,7 +628,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
             const int row = i * 8 + erow;
             const uint4 v = *reinterpret_cast<const uint4*>(eb + row * kPitch + echunk * 16);
             const int64_t m = m0 + wm0 + row;
-            if (m < M && n < N) *reinterpret_cast<uint4*>(C + m * ldc + n) = v;
+            if (m < M && n < N) {
+                typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+                const u32x4 vv = {v.x, v.y, v.z, v.w};
+                __builtin_nontemporal_store(vv, reinterpret_cast<u32x4*>(C + m * ldc + n));
+            }
         }
     }
 }

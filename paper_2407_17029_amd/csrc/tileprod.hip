@@ -100,8 +100,9 @@ __global__ __launch_bounds__(256) void k_tile_product(const qblora_bf16* __restr
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int row = 4 * i + rr;
-        const float4 v = *reinterpret_cast<const float4*>(eb + row * kTpPitch + cc * 16);
-        *reinterpret_cast<float4*>(out + (int64_t)row * cols) = v;
+        // H is far larger than the caches and read by a later launch: a streaming store
+        __builtin_nontemporal_store(*reinterpret_cast<const f32x4*>(eb + row * kTpPitch + cc * 16),
+                                    reinterpret_cast<f32x4*>(out + (int64_t)row * cols));
     }
 }
 
