@@ -308,6 +308,14 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     }
 }
 
+// the form with all of X in LDS (at most kXAllBytes of it: inside the default limit of dynamic LDS; a limit of 66 KB
+// measured slower wherever it applied -- 22016 x 8192 at four tokens 48 against 33 us, two workgroups per CU)
+template <bool BETA, bool DIRECT, int G>
+int launch_xall(const DecodeDesc& d, dim3 grid, size_t x_all_bytes, hipStream_t st) {
+    hipLaunchKernelGGL((k_w4_decode_xall<BETA, DIRECT, G>), grid, dim3(256), x_all_bytes, st, d);
+    return launch_status();
+}
+
 }  // namespace
 
 int launch_w4_decode(const uint8_t* codes, const float* scales, const float* beta, const Codebook& cb, int tiled,
@@ -322,18 +330,18 @@ int launch_w4_decode(const uint8_t* codes, const float* scales, const float* bet
         return launch_status();
     };
     const size_t x_all_bytes = (size_t)T * ((size_t)d_in * 2 + 16);
-    if (block_rows != 8 && x_all_bytes <= (size_t)kXAllBytes && d_in % 8 == 0) {       // all of X in LDS
-        auto all = [&](auto kern) -> int {
-            hipLaunchKernelGGL(kern, grid, dim3(256), x_all_bytes, st, d);
-            return launch_status();
-        };
+    // all of X in LDS: when it is small enough, and when the workgroups of the launch still fit the CUs together with
+    // their copies (160 KB of LDS per CU; 22016 x 8192 at two tokens: 31.3 us with six 36 KB workgroups wanted per CU,
+    // 29.9 without the copy)
+    const size_t per_cu = (grid.x + 255) / 256;
+    if (block_rows != 8 && x_all_bytes <= (size_t)kXAllBytes && per_cu * (x_all_bytes + 5 * 1024) <= 150 * 1024 && d_in % 8 == 0) {
         const bool small_sets = grid.x > 1024;      // more workgroups than fit at four waves per SIMD
         if (regrouped) {
             if (!beta || !tiled) return QBLORA_ERR_UNSUPPORTED;
-            return small_sets ? all(k_w4_decode_xall<true, true, 2>) : all(k_w4_decode_xall<true, true, 4>);
+            return small_sets ? launch_xall<true, true, 2>(d, grid, x_all_bytes, st) : launch_xall<true, true, 4>(d, grid, x_all_bytes, st);
         }
-        if (beta) return small_sets ? all(k_w4_decode_xall<true, false, 2>) : all(k_w4_decode_xall<true, false, 4>);
-        return small_sets ? all(k_w4_decode_xall<false, false, 2>) : all(k_w4_decode_xall<false, false, 4>);
+        if (beta) return small_sets ? launch_xall<true, false, 2>(d, grid, x_all_bytes, st) : launch_xall<true, false, 4>(d, grid, x_all_bytes, st);
+        return small_sets ? launch_xall<false, false, 2>(d, grid, x_all_bytes, st) : launch_xall<false, false, 4>(d, grid, x_all_bytes, st);
     }
     if (block_rows == 8) {                  // its fp32 pair table and the activation rows together leave two
                                             // workgroups per CU: measured slower (68 vs 64 us at T = 16), not used
