@@ -301,6 +301,8 @@ def measure(S, steps, warmup, side_steps, plain_events=False, calibration_copy=F
              "frac": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "algorithmic_bytes": int(nbytes)}
         if note:
             d["note"] = note
+        if nbytes <= 256e6:                 # the launch's operands can stay in the 256 MB last-level cache from one
+            d["fits_last_level_cache"] = True   # step to the next: then this is not a rate HBM delivered
         return d
 
     proj_name = f"{bp.name} [{bp.d_out}x{bp.d_in}]"
@@ -711,6 +713,8 @@ def main() -> int:
             entry["kernels"] = {"bwd_gemm_frac": r["kernels"]["bwd_gemm"]["frac"],
                                 "quantize_frac": r["kernels"]["quantize"]["frac"],
                                 "merge_requant_batch_frac": r["kernels"]["merge_requant_batch"]["frac"],
+                                "merge_requant_batch_fits_last_level_cache":
+                                    r["kernels"]["merge_requant_batch"].get("fits_last_level_cache", False),
                                 "adapter_side_share_of_projection": r["kernels"]["adapter_side_share_of_projection"]}
             if name == "llama13b_layer":
                 sweep = {str(wl2.rank): {"value": r["value"], "ms_per_step": r["ms_per_step"],

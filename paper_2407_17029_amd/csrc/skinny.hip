@@ -48,7 +48,7 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
 // behind the stage's two X sub-tiles.
 template <int BM, int BN, int kStages, int kSub, bool kSplitK, int kDup = 1>
 __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
-    static_assert(!kSplitK || (BM == 64 && BN == 64), "the k-split form is written for 64 x 64 tiles");
+    static_assert(!kSplitK || (BM == 64 && (BN == 64 || BN == 128)), "the k-split form is written for 64 x 64 and 64 x 128 tiles");
     static_assert(kDup == 1 || (kDup == 2 && kSplitK && kSub == 2), "column duplication: k-split form, two k-steps per stage");
     // a stage holds kSub consecutive k-steps (sub-tiles of 64 k each): one barrier per kSub * 64 k
     constexpr int kXBytes = BM * 128, kWBytes = BN * 128 / kDup, kSubBytes = kXBytes + kWBytes, kStageBytes = kSub * kSubBytes;
@@ -114,11 +114,12 @@ __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
     };
 
     // Plain form: a wave owns 32 columns x MF token blocks and keeps one accumulator chain per
-    // sub-tile (added at the end).  k-split form (64 x 64 tiles): a 32 x 32 wave tile would read two
-    // fragments per MFMA, which is all the LDS can deliver; instead every wave computes the whole
-    // 64 x 64 tile (acc[column block][token block]) for one quarter of each sub-tile's k (slice ks ==
-    // wave), one fragment read per MFMA, and the four partial tiles are added through LDS at the end.
-    constexpr int NA = kSplitK ? 2 : kSub, NB = kSplitK ? 2 : MF;
+    // sub-tile (added at the end).  k-split form (64 tokens x 64 or 128 columns): a 32 x 32 wave tile would
+    // read two fragments per MFMA, which is all the LDS can deliver; instead every wave computes the whole
+    // tile (acc[column block][token block]) for one quarter of each sub-tile's k (slice ks == wave), one
+    // fragment read per MFMA (three per four with 128 columns), and the four partial tiles are added through
+    // LDS at the end, 64 columns at a time.
+    constexpr int NA = kSplitK ? BN / 32 : kSub, NB = kSplitK ? 2 : MF;
     f32x16 acc[NA][NB];
 #pragma unroll
     for (int u = 0; u < NA; ++u)
@@ -134,9 +135,11 @@ __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
             for (int u = 0; u < kSub; ++u) {
                 const unsigned char* bx = smem + (step % kStages) * kStageBytes + x_at(u);
                 const unsigned char* bw = smem + (step % kStages) * kStageBytes + w_at(u);
-                bf16x8 wf[2], xf[2];
+                bf16x8 wf[NA], xf[2];
 #pragma unroll
-                for (int a = 0; a < 2; ++a) {
+                for (int a = 0; a < 2; ++a) xf[a] = *reinterpret_cast<const bf16x8*>(bx + swz(a * 32 + r, wave * 2 + hi));
+#pragma unroll
+                for (int a = 0; a < NA; ++a) {
                     if constexpr (kDup == 2) {
                         // stored columns 32*u + 8*wave + 4*hi .. +3 of row a*32 + r, each used for two k
                         const uint2 v = *reinterpret_cast<const uint2*>(bw + swz(a * 32 + r, 4 * u + wave) + 8 * hi);
@@ -146,10 +149,9 @@ __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
                     } else {
                         wf[a] = *reinterpret_cast<const bf16x8*>(bw + swz(a * 32 + r, wave * 2 + hi));
                     }
-                    xf[a] = *reinterpret_cast<const bf16x8*>(bx + swz(a * 32 + r, wave * 2 + hi));
                 }
 #pragma unroll
-                for (int a = 0; a < 2; ++a)
+                for (int a = 0; a < NA; ++a)
 #pragma unroll
                     for (int b = 0; b < 2; ++b)
                         acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[a], xf[b], acc[a][b], 0, 0, 0);
@@ -188,47 +190,16 @@ __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
         compute(s);
     }
 
-    int out_n = wave_n * 32, out_m = wave_m * MF * 32;      // first column / token of this wave's output
-    if constexpr (kSplitK) {
-        // partial tiles -> LDS (the ring is idle: the last step's data has been read by everyone after
-        // this barrier), register i of block (a, b) of wave w at float [((w*4 + a*2+b)*16 + i)*64 + lane];
-        // wave w then adds the four partials of block (a, b) = (w >> 1, w & 1) in wave order.
-        __syncthreads();
-        float* red = reinterpret_cast<float*>(smem);
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) red[((wave * 4 + a * 2 + b) * 16 + i) * 64 + lane] = acc[a][b][i];
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            float v = red[((0 * 4 + wave) * 16 + i) * 64 + lane];
-#pragma unroll
-            for (int w = 1; w < 4; ++w) v += red[((w * 4 + wave) * 16 + i) * 64 + lane];
-            acc[0][0][i] = v;
-        }
-        out_n = (wave >> 1) * 32; out_m = (wave & 1) * 32;
-    } else {
-#pragma unroll
-        for (int u = 1; u < kSub; ++u)
-#pragma unroll
-            for (int b = 0; b < MF; ++b)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[0][b][i] += acc[u][b][i];
-    }
-    // lane holds columns n..n+3 of one token per accumulator quad
-#pragma unroll
-    for (int b = 0; b < (kSplitK ? 1 : MF); ++b) {
-        const int64_t m = m0 + out_m + b * 32 + r;
-        if (m >= M) continue;
+    // lane holds columns n..n+3 of one token per accumulator quad of a 32 x 32 block
+    auto emit = [&](const f32x16& v, const int out_n, const int out_m) __attribute__((always_inline)) {
+        const int64_t m = m0 + out_m + r;
+        if (m >= M) return;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int n = n0 + out_n + q * 8 + hi * 4;
             if (n >= N) continue;
-            const float v0 = acc[0][b][q * 4 + 0] * out_scale, v1 = acc[0][b][q * 4 + 1] * out_scale;
-            const float v2 = acc[0][b][q * 4 + 2] * out_scale, v3 = acc[0][b][q * 4 + 3] * out_scale;
+            const float v0 = v[q * 4 + 0] * out_scale, v1 = v[q * 4 + 1] * out_scale;
+            const float v2 = v[q * 4 + 2] * out_scale, v3 = v[q * 4 + 3] * out_scale;
             uint2 h;
             h.x = pack_bf16(v0, v1); h.y = pack_bf16(v2, v3);
             *reinterpret_cast<uint2*>(C + m * ldc + n) = h;
@@ -245,6 +216,41 @@ __global__ __launch_bounds__(kThreads) void k_skinny(GemmDesc d) {
                 *reinterpret_cast<uint2*>(C2 + m * ldc + n) = o;
             }
         }
+    };
+    if constexpr (kSplitK) {
+        // partial tiles -> LDS, 64 columns (two column blocks) per pass: register i of block (a, b) of wave w at
+        // float [((w*4 + a*2+b)*16 + i)*64 + lane]; wave w then adds the four partials of block (a, b) =
+        // (w >> 1, w & 1) in wave order.  The first barrier also ends the last step's reads of the ring.
+        float* red = reinterpret_cast<float*>(smem);
+#pragma unroll
+        for (int p = 0; p < NA / 2; ++p) {
+            __syncthreads();
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) red[((wave * 4 + a * 2 + b) * 16 + i) * 64 + lane] = acc[2 * p + a][b][i];
+            __syncthreads();
+            f32x16 sum;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                float v = red[((0 * 4 + wave) * 16 + i) * 64 + lane];
+#pragma unroll
+                for (int w = 1; w < 4; ++w) v += red[((w * 4 + wave) * 16 + i) * 64 + lane];
+                sum[i] = v;
+            }
+            emit(sum, p * 64 + (wave >> 1) * 32, (wave & 1) * 32);
+        }
+    } else {
+#pragma unroll
+        for (int u = 1; u < kSub; ++u)
+#pragma unroll
+            for (int b = 0; b < MF; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[0][b][i] += acc[u][b][i];
+#pragma unroll
+        for (int b = 0; b < MF; ++b) emit(acc[0][b], wave_n * 32, (wave_m * MF + b) * 32);
     }
 }
 
@@ -282,7 +288,13 @@ int launch_skinny(const GemmDesc& d, hipStream_t st) {
     // 64 x 128 tiles once they alone fill the chip twice over; below that 64 x 64 tiles with a deep
     // ring (a narrower output has nothing to split: 32-token tiles, 128 columns)
     const int64_t wgs = ((d.M + 63) / 64) * ((d.N + 127) / 128);
-    if (d.dup2 == 2) return launch_skinny_cfg<64, 64, 5, 2, true, 2>(d, st);      // see skinny_dup_applies
+    if (d.dup2 == 2) {                                                             // see skinny_dup_applies
+        // 128 columns per workgroup once that still puts a workgroup on every CU: the token tile is then fetched by
+        // two workgroups instead of four (65B gate projection, inner rank 256: 2.16 -> 1.44 GB through the CUs,
+        // backward 200 -> 157 us, forward 77 -> 62 us; three or four stages measure the same, two are slower)
+        if (d.N > 64 && wgs >= 256) return launch_skinny_cfg<64, 128, 3, 2, true, 2>(d, st);
+        return launch_skinny_cfg<64, 64, 5, 2, true, 2>(d, st);
+    }
     if (wgs >= 512) return launch_skinny_cfg<64, 128, 4, 1, false>(d, st);
     if (d.N > 64) {
         if (d.K2 % (2 * kBK) == 0) return launch_skinny_cfg<64, 64, 5, 2, true>(d, st);
