@@ -40,6 +40,7 @@ CASES = [
     (130, 256, 256, 8, 1, 1, 1.0),           # lambda 1: plain LoRA, inner rank smaller than a K step
     (333, 384, 640, 128, 2, 2, 0.5),         # lambda 2 with inner rank 128: the narrow GEMMs read A^T / B unexpanded; ragged T
     (200, 512, 512, 96, 2, 2, 1.0),          # the same with a rank that leaves a partial column tile
+    (8200, 256, 384, 224, 2, 2, 0.75),       # enough token tiles for the narrow GEMMs' 128-column form: ragged T, partial second column tile
 ]
 
 
