@@ -51,6 +51,23 @@ def measured_traffic(workload: str, kernel: str):
     return None
 
 
+VALU_FILE = os.path.join(ROOT, "profiles", "valu_counters.txt")
+
+
+def measured_valu(workload: str, kernel: str):
+    """Vector-ALU figures of a streaming kernel from the rocprofv3 SQ counter runs, as recorded by the profile step
+    in profiles/valu_counters.txt (lines `workload kernel lane-instructions-per-weight-element busy-share`): a kernel
+    whose vector ALU is busy most of the time is bound by that, not by the HBM rate it is priced against."""
+    try:
+        for line in open(VALU_FILE):
+            f = line.split()
+            if len(f) >= 4 and not line.startswith("#") and f[0] == workload and f[1] == kernel:
+                return {"valu_lane_insts_per_element": float(f[2]), "valu_busy": float(f[3])}
+    except OSError:
+        pass
+    return None
+
+
 class Stack:
     """Device state of one workload: per-projection weights, adapters, outputs; shared activations and scratch."""
 
@@ -346,6 +363,11 @@ def measure(S, steps, warmup, side_steps, plain_events=False, calibration_copy=F
         t = measured_traffic(wl.name, k)
         key = {"adapter_fwd": "adapter_fwd_skinny", "adapter_bwd": "adapter_bwd_skinny", "merge": "merge_requant_batch"}.get(k, k)
         out["kernels"][key]["traffic"] = t
+    for k, key in (("quantize", "quantize"), ("merge", "merge_requant_batch"), ("dequant_fwd", "dequantize_once_fwd"),
+                   ("dequant_bwd", "dequantize_once_bwd")):
+        v = measured_valu(wl.name, k)
+        if v and out["kernels"].get(key):
+            out["kernels"][key].update(v)
     adapter_ms = sum(float(np.mean(raw[k])) for k in ("adapter_fwd", "adapter_bwd", "adapter_grads", "grad_reduce", "prep"))
     dq_ms = float(np.mean(raw["dequant_fwd"])) + float(np.mean(raw["dequant_bwd"]))
     proj_ms = adapter_ms + gemm_ms("fwd_gemm") + gemm_ms("bwd_gemm") + float(np.mean(raw["quantize"])) + dq_ms
