@@ -36,6 +36,17 @@ namespace {
 
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
+// byte N of v as a float (v_cvt_f32_ubyteN)
+template <int N>
+__device__ __forceinline__ float ubyte_to_float(uint32_t v) {
+    float r;
+    if constexpr (N == 0) asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(r) : "v"(v));
+    else if constexpr (N == 1) asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(r) : "v"(v));
+    else if constexpr (N == 2) asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(r) : "v"(v));
+    else asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(r) : "v"(v));
+    return r;
+}
+
 struct DecodeDesc {
     const uint8_t* codes; const float* scales; const float* beta; Codebook cb;
     int tiled;                 // the three arrays are in tile order (256-row tiles, rows of a block adjacent);
@@ -78,16 +89,16 @@ __global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) { w4_decode<BET
 // SIMD, 1024 workgroups resident); two use 76, six waves per SIMD, so that the 1376 workgroups of a 22016-row layer
 // are resident at once (25.2 against 26.0 us; limiting the four-block form to 84 registers instead spills 24 of
 // them and nearly doubles the time).  Layers that fit the 1024 slots are faster with four (4096 rows: 5.4 against 6.0).
-template <bool BETA, bool DIRECT, int G>
+template <bool BETA, bool DIRECT, int G, int BR = 1>
 __global__ __launch_bounds__(256) void k_w4_decode_xall(DecodeDesc d) {
-    w4_decode<BETA, 1, DIRECT, 2, G>(d);
+    w4_decode<BETA, BR, DIRECT, 2, G>(d);
 }
 
 template <bool BETA, int BR, bool DIRECT, int XMODE, int G>
 __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     constexpr bool XLDS = XMODE == 1, XALL = XMODE == 2;
     static_assert(G == 4 || !XLDS, "the staged activation rows hold four blocks");
-    static_assert(!DIRECT || (BETA && BR == 1), "the table-free form needs offsets and 64-blocks");
+    static_assert(!DIRECT || BR == 8 || BETA, "the table-free form of 64-blocks needs offsets");
     extern __shared__ __align__(16) unsigned char x_all[];       // XALL: [T][d_in * 2 + 16] bytes
     // entry e of replica q at e*kReplicas + q: bf16 pairs (4 bytes), or fp32 pairs (8 bytes) for BR = 8
     __shared__ __align__(8) uint32_t pair[DIRECT ? 2 : 256 * kReplicas * (BR == 8 ? 2 : 1)];
@@ -214,7 +225,50 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
         }
         return __builtin_bit_cast(bf16x8, make_uint4(o[0], o[1], o[2], o[3]));
     };
+    // BR = 8: the four table entries of an operand (one code dword) are read one operand ahead of their use, so that
+    // a wave has LDS reads in flight under the scaling arithmetic of the previous operand instead of waiting for
+    // each operand's reads in turn (the compiler's order: eight exposed LDS round trips per group of blocks)
+    // (DIRECT with BR = 8: the codebook is exactly 0 .. 15, so a code is its own value and the byte-to-float
+    // conversions replace the table; its reads, two-way bank conflicts included, otherwise cost as much LDS time as the
+    // codes cost HBM time)
+    auto fetch8 = [&](uint32_t w, float2 (&cv)[4]) __attribute__((always_inline)) {
+        if constexpr (DIRECT) {
+            // one byte-to-float conversion per code on the two masked dwords (written as the instruction: from shifts
+            // and masks the compiler makes a bit-field extract and a conversion per code)
+            const uint32_t lo = w & 0x0F0F0F0Fu, hi = (w >> 4) & 0x0F0F0F0Fu;
+            cv[0] = make_float2(ubyte_to_float<0>(lo), ubyte_to_float<0>(hi));
+            cv[1] = make_float2(ubyte_to_float<1>(lo), ubyte_to_float<1>(hi));
+            cv[2] = make_float2(ubyte_to_float<2>(lo), ubyte_to_float<2>(hi));
+            cv[3] = make_float2(ubyte_to_float<3>(lo), ubyte_to_float<3>(hi));
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) cv[i] = my_pairf[((w >> (8 * i)) & 0xffu) * kReplicas];
+        }
+    };
+    auto build8 = [&](const float2 (&cv)[4], float a, float b) __attribute__((always_inline)) {
+        uint32_t o[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            o[i] = BETA ? pack_bf16(__fmaf_rn(cv[i].x, a, b), __fmaf_rn(cv[i].y, a, b)) : pack_bf16(__fmul_rn(cv[i].x, a), __fmul_rn(cv[i].y, a));
+        return __builtin_bit_cast(bf16x8, make_uint4(o[0], o[1], o[2], o[3]));
+    };
+    auto compute8 = [&](const DecodeRegs<G>& r) __attribute__((always_inline)) {
+        float2 cv[2][4];
+        fetch8(r.c[0].x, cv[0]);
+#pragma unroll
+        for (int u = 0; u < 2 * G; ++u) {                     // operand u: block u / 2, code dword u % 2
+            const int q = u >> 1;
+            if (u + 1 < 2 * G) fetch8((u & 1) ? r.c[q + 1 < G ? q + 1 : q].x : r.c[q].y, cv[(u + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            bf16x8 x;
+            if constexpr (XALL) x = *reinterpret_cast<const bf16x8*>(x_mine + r.xb[q] * (kBlock * 2) + 16 * (u & 1));
+            else x = __builtin_bit_cast(bf16x8, r.x[q][u & 1]);
+            const bf16x8 wv = build8(cv[u & 1], (u & 1) ? r.a2[q].y : r.a2[q].x, (u & 1) ? r.b2[q].y : r.b2[q].x);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, wv, acc, 0, 0, 0);
+        }
+    };
     auto compute = [&](const DecodeRegs<G>& r) __attribute__((always_inline)) {
+        if constexpr (BR == 8 && !XLDS) { compute8(r); return; }
         if constexpr (XLDS) {
 #pragma unroll
             for (int p = 0; p < 8; ++p)
@@ -310,9 +364,9 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
 
 // the form with all of X in LDS (at most kXAllBytes of it: inside the default limit of dynamic LDS; a limit of 66 KB
 // measured slower wherever it applied -- 22016 x 8192 at four tokens 48 against 33 us, two workgroups per CU)
-template <bool BETA, bool DIRECT, int G>
+template <bool BETA, bool DIRECT, int G, int BR = 1>
 int launch_xall(const DecodeDesc& d, dim3 grid, size_t x_all_bytes, hipStream_t st) {
-    hipLaunchKernelGGL((k_w4_decode_xall<BETA, DIRECT, G>), grid, dim3(256), x_all_bytes, st, d);
+    hipLaunchKernelGGL((k_w4_decode_xall<BETA, DIRECT, G, BR>), grid, dim3(256), x_all_bytes, st, d);
     return launch_status();
 }
 
@@ -334,6 +388,15 @@ int launch_w4_decode(const uint8_t* codes, const float* scales, const float* bet
     // their copies (160 KB of LDS per CU; 22016 x 8192 at two tokens: 31.3 us with six 36 KB workgroups wanted per CU,
     // 29.9 without the copy)
     const size_t per_cu = (grid.x + 255) / 256;
+    bool int4 = true;                       // codes are their own values: no table
+    for (int j = 0; j < 16; ++j) int4 = int4 && cb.c[j] == (float)j;
+    // 8 x 8 blocks of an INT4 model, few tokens: no table, all of X in LDS (22016 x 8192 at one token: 35.8 -> 28.2 us;
+    // with at most two workgroups per CU the copy costs more than it saves: 4096 rows 6.3 against 5.9 us)
+    if (block_rows == 8 && int4 && grid.x > 512 && x_all_bytes <= (size_t)kXAllBytes &&
+        per_cu * (x_all_bytes + 5 * 1024) <= 150 * 1024 && d_in % 8 == 0) {
+        if (grid.x > 1024) return beta ? launch_xall<true, true, 2, 8>(d, grid, x_all_bytes, st) : launch_xall<false, true, 2, 8>(d, grid, x_all_bytes, st);
+        return beta ? launch_xall<true, true, 4, 8>(d, grid, x_all_bytes, st) : launch_xall<false, true, 4, 8>(d, grid, x_all_bytes, st);
+    }
     if (block_rows != 8 && x_all_bytes <= (size_t)kXAllBytes && per_cu * (x_all_bytes + 5 * 1024) <= 150 * 1024 && d_in % 8 == 0) {
         const bool small_sets = grid.x > 1024;      // more workgroups than fit at four waves per SIMD
         if (regrouped) {
@@ -345,6 +408,10 @@ int launch_w4_decode(const uint8_t* codes, const float* scales, const float* bet
     }
     if (block_rows == 8) {                  // its fp32 pair table and the activation rows together leave two
                                             // workgroups per CU: measured slower (68 vs 64 us at T = 16), not used
+        if (int4) {                         // (two-block register sets measured slower here: 38.3 against 35.8 us)
+            if (beta) return go(k_w4_decode<true, 8, true, 0>, k_w4_decode<true, 8, true, 0>);
+            return go(k_w4_decode<false, 8, true, 0>, k_w4_decode<false, 8, true, 0>);
+        }
         if (beta) return go(k_w4_decode<true, 8, false, 0>, k_w4_decode<true, 8, false, 0>);
         return go(k_w4_decode<false, 8, false, 0>, k_w4_decode<false, 8, false, 0>);
     }
