@@ -21,7 +21,10 @@
 // With 8 x 8 quantization blocks (BR = 8) the scale changes every 8 inputs, inside the contraction of one
 // MFMA, so it cannot act on partial sums: there the lane builds the bf16 compute weight
 // bf16(fma(c, alpha, beta)) of its 16 inputs (two block columns; the byte table then holds fp32 pairs) and
-// the MFMAs accumulate directly -- the arithmetic of the training forward.
+// the MFMAs accumulate directly -- the arithmetic of the training forward.  The table entries of an operand are read
+// one operand ahead of their use; for an INT4 model (codebook exactly 0..15) a code is its own value, so there is no
+// table at all: two masks per code dword and one byte-to-float conversion per code.  That form is bound by its vector
+// arithmetic (some 4 instructions per weight: conversion, scale-and-shift, half a packing, loop overhead), not by HBM.
 //
 // INT4 models (codebook exactly 0..15, offsets present, packed arrays: DIRECT) need no table: the bf16 with
 // bits 0x4300 | c is 128 + c, so two shift/and-or instructions turn a code dword into an operand dword
