@@ -264,19 +264,20 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
             if (u + 1 < 2 * G) fetch8((u & 1) ? r.c[q + 1 < G ? q + 1 : q].x : r.c[q].y, cv[(u + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
             bf16x8 x;
-            if constexpr (XALL) x = *reinterpret_cast<const bf16x8*>(x_mine + r.xb[q] * (kBlock * 2) + 16 * (u & 1));
+            if constexpr (XLDS) x = *reinterpret_cast<const bf16x8*>(xs + nl * kXPitch + 128 * q + 32 * kg + 16 * (u & 1));
+            else if constexpr (XALL) x = *reinterpret_cast<const bf16x8*>(x_mine + r.xb[q] * (kBlock * 2) + 16 * (u & 1));
             else x = __builtin_bit_cast(bf16x8, r.x[q][u & 1]);
             const bf16x8 wv = build8(cv[u & 1], (u & 1) ? r.a2[q].y : r.a2[q].x, (u & 1) ? r.b2[q].y : r.b2[q].x);
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, wv, acc, 0, 0, 0);
         }
     };
     auto compute = [&](const DecodeRegs<G>& r) __attribute__((always_inline)) {
-        if constexpr (BR == 8 && !XLDS) { compute8(r); return; }
         if constexpr (XLDS) {
 #pragma unroll
             for (int p = 0; p < 8; ++p)
                 if (2 * p < d.T) *reinterpret_cast<uint4*>(xs + (2 * p + xtok) * kXPitch + xchunk * 16) = r.xg[p];
         }
+        if constexpr (BR == 8) { compute8(r); return; }
 #pragma unroll
         for (int q = 0; q < G; ++q) {
             bf16x8 x0, x1;
@@ -412,6 +413,18 @@ int launch_w4_decode(const uint8_t* codes, const float* scales, const float* bet
     if (block_rows == 8) {                  // its fp32 pair table and the activation rows together leave two
                                             // workgroups per CU: measured slower (68 vs 64 us at T = 16), not used
         if (int4) {                         // (two-block register sets measured slower here: 38.3 against 35.8 us)
+            // above 6 tokens the activations go through LDS as for 64-blocks (22016 x 8192 at 16 tokens: 61.6 -> 47.3 us),
+            // unless the layer has at most one workgroup per CU (4096 rows: 7.8 against 9.0 us)
+            if (grid.x > 256) {
+                const bool staged = T > 6;  // measured: level at 6 tokens, 45.3 -> 41.1 us at 8 (22016 x 8192)
+                auto go2 = [&](auto plain, auto st2) -> int {
+                    if (staged) hipLaunchKernelGGL(st2, grid, dim3(256), 0, st, d);
+                    else hipLaunchKernelGGL(plain, grid, dim3(256), 0, st, d);
+                    return launch_status();
+                };
+                if (beta) return go2(k_w4_decode<true, 8, true, 0>, k_w4_decode<true, 8, true, 1>);
+                return go2(k_w4_decode<false, 8, true, 0>, k_w4_decode<false, 8, true, 1>);
+            }
             if (beta) return go(k_w4_decode<true, 8, true, 0>, k_w4_decode<true, 8, true, 0>);
             return go(k_w4_decode<false, 8, true, 0>, k_w4_decode<false, 8, true, 0>);
         }
