@@ -62,11 +62,11 @@ struct DecodeDesc {
 
 constexpr int kReplicas = 16;               // copies of the byte -> (bf16 c[lo], bf16 c[hi]) table
 
-template <int G>
-struct DecodeRegs {                         // one group = G consecutive blocks of the lane's row
-    uint2 c[G];                             // the lane's quarter of each block's codes: 16 codes
-    float a[G], b[G];                       // scale and offset of each block
-    float2 a2[G], b2[G];                    // BR = 8: scales and offsets of the lane's two block columns
+template <int G, int R>
+struct DecodeRegs {                         // one group = G consecutive blocks of the lane's R rows (16 rows apart)
+    uint2 c[G][R];                          // the lane's quarter of each block's codes: 16 codes
+    float a[G][R], b[G][R];                 // scale and offset of each block
+    float2 a2[G][R], b2[G][R];              // BR = 8: scales and offsets of the lane's two block columns
     int xb[G];                              // XALL: the (redirected) block whose activations go with c[q]
     uint4 x[G][2];                          // activations of the lane's token, 8 per MFMA (fetched in operand order)
     uint4 xg[8];                            // XLDS: as fetched, token 2p + (lane >> 5), chunk lane & 31 of the group
@@ -82,22 +82,24 @@ struct DecodeRegs {                         // one group = G consecutive blocks 
 // the bytes of the codes through the vector memory path (every lane fetches its own copy of the 16 activations
 // it shares with 15 others), and that path, not HBM, set the time.
 constexpr int kXAllBytes = 40 * 1024;
-template <bool BETA, int BR, bool DIRECT, int XMODE, int G = 4>
+template <bool BETA, int BR, bool DIRECT, int XMODE, int G = 4, int R = 1>
 __device__ __forceinline__ void w4_decode(const DecodeDesc& d);
 
-template <bool BETA, int BR, bool DIRECT = false, int XMODE = 0, int G = 4>
-__global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) { w4_decode<BETA, BR, DIRECT, XMODE, G>(d); }
+template <bool BETA, int BR, bool DIRECT = false, int XMODE = 0, int G = 4, int R = 1>
+__global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) { w4_decode<BETA, BR, DIRECT, XMODE, G, R>(d); }
 
 // G: blocks per register set.  Four keep the most bytes in flight per wave and use 108 registers (four waves per
 // SIMD, 1024 workgroups resident); two use 76, six waves per SIMD, so that the 1376 workgroups of a 22016-row layer
 // are resident at once (25.2 against 26.0 us; limiting the four-block form to 84 registers instead spills 24 of
 // them and nearly doubles the time).  Layers that fit the 1024 slots are faster with four (4096 rows: 5.4 against 6.0).
-template <bool BETA, bool DIRECT, int G, int BR = 1>
+template <bool BETA, bool DIRECT, int G, int BR = 1, int R = 1>
 __global__ __launch_bounds__(256) void k_w4_decode_xall(DecodeDesc d) {
-    w4_decode<BETA, BR, DIRECT, 2, G>(d);
+    w4_decode<BETA, BR, DIRECT, 2, G, R>(d);
 }
 
-template <bool BETA, int BR, bool DIRECT, int XMODE, int G>
+// R: row groups of 16 per workgroup.  With two, the activation operands (which every workgroup fetches for its own
+// rows: at 16 tokens four times the bytes of the codes) serve 32 rows, and so do the block sums of the activations.
+template <bool BETA, int BR, bool DIRECT, int XMODE, int G, int R>
 __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     constexpr bool XLDS = XMODE == 1, XALL = XMODE == 2;
     static_assert(G == 4 || !XLDS, "the staged activation rows hold four blocks");
@@ -116,10 +118,13 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     // Row groups 2i and 2i+1 share the 128-byte lines of the tile-ordered scales and offsets (16 rows = 64
     // bytes per block): they are given workgroup ids x and x + 8 of a run of 16 ids, which are dispatched to
     // the same XCD, so that one L2 fetches each line.  The grid is a multiple of 16; ids past the end leave.
-    const int rg = (blockIdx.x & ~15) | ((blockIdx.x & 7) << 1) | ((blockIdx.x >> 3) & 1);
-    if (rg * 16 >= d.d_out) return;
-    const int n0 = rg * 16;
-    const int n = min(n0 + nl, d.d_out - 1);                  // rows past the end are computed, not stored
+    // (With two row groups per workgroup the pair is in one workgroup anyway.)
+    const int rg = R == 1 ? (int)((blockIdx.x & ~15) | ((blockIdx.x & 7) << 1) | ((blockIdx.x >> 3) & 1)) : (int)blockIdx.x;
+    if (rg * 16 * R >= d.d_out) return;
+    const int n0 = rg * 16 * R;
+    int n[R];
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) n[rr] = min(n0 + 16 * rr + nl, d.d_out - 1);    // rows past the end are computed, not stored
     const int bpr = d.d_in / kBlock;
     const int groups = (bpr + G - 1) / G;
     if constexpr (DIRECT) {
@@ -140,13 +145,17 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     // Row-major arrays: a wave's load of one block touches 16 rows, i.e. 16 cache lines.  In tile order
     // (the layout of the forward kernel's code copy) the 16 rows of a block are adjacent: 4 lines of codes
     // and one of scales per load, which is what keeps the address path from being the bottleneck.
-    const int64_t run = d.tiled ? ((int64_t)(n >> 8) * bpr * 256 + (n & 255)) : (int64_t)n * bpr;   // block 0 of row n
     const int bstep = d.tiled ? 256 : 1;                                                            // next block
-    const uint8_t* crow = d.codes + run * 32 + 8 * kg;
-    const float* srow = d.scales + run;
-    const float* brow = BETA ? d.beta + run : nullptr;
-    // BR = 8: block row n/8, block columns 8*b + 2*kg, +1 of 64-input step b
-    const int64_t run8 = (int64_t)(n >> 3) * (d.d_in >> 3) + 2 * kg;
+    const uint8_t* crow[R]; const float* srow[R]; const float* brow[R];
+    int64_t run8[R];                        // BR = 8: block row n/8, block columns 8*b + 2*kg, +1 of 64-input step b
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) {
+        const int64_t run = d.tiled ? ((int64_t)(n[rr] >> 8) * bpr * 256 + (n[rr] & 255)) : (int64_t)n[rr] * bpr;   // block 0 of the row
+        crow[rr] = d.codes + run * 32 + 8 * kg;
+        srow[rr] = d.scales + run;
+        brow[rr] = BETA ? d.beta + run : nullptr;
+        run8[rr] = (int64_t)(n[rr] >> 3) * (d.d_in >> 3) + 2 * kg;
+    }
     const int cstep = bstep * 32;
     unsigned char* xs = xs_all[XLDS ? wave : 0];
     const int xtok = lane >> 5, xchunk = lane & 31;
@@ -157,30 +166,33 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     // Every load is unconditional: a block past the end of the row is redirected to the last block and
     // given scale = offset = 0; lanes whose token does not exist read the last token's row and produce
     // output rows that are never stored.
-    auto load = [&](DecodeRegs<G>& r, int j) __attribute__((always_inline)) {
+    auto load = [&](DecodeRegs<G, R>& r, int j) __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < G; ++q) {
             const int b = G * j + q;
             const bool in = b < bpr;
             const int bc = in ? b : bpr - 1;
-            r.c[q] = *reinterpret_cast<const uint2*>(crow + (int64_t)bc * cstep);
-            if constexpr (BR == 8) {
-                const float2 a = *reinterpret_cast<const float2*>(d.scales + run8 + 8 * bc);
-                r.a2[q] = in ? a : make_float2(0.0f, 0.0f);
-                r.b2[q] = make_float2(0.0f, 0.0f);
-                if constexpr (BETA) {
-                    const float2 bt = *reinterpret_cast<const float2*>(d.beta + run8 + 8 * bc);
-                    if (in) r.b2[q] = bt;
-                }
-            } else {
-                const float a = srow[(int64_t)bc * bstep];
-                r.a[q] = in ? a : 0.0f;
-                if constexpr (BETA) {
-                    const float bt = brow[(int64_t)bc * bstep];
-                    r.b[q] = in ? bt : 0.0f;
-                    if constexpr (DIRECT) r.b[q] = __builtin_fmaf(-128.0f, r.a[q], r.b[q]);
+#pragma unroll
+            for (int rr = 0; rr < R; ++rr) {
+                r.c[q][rr] = *reinterpret_cast<const uint2*>(crow[rr] + (int64_t)bc * cstep);
+                if constexpr (BR == 8) {
+                    const float2 a = *reinterpret_cast<const float2*>(d.scales + run8[rr] + 8 * bc);
+                    r.a2[q][rr] = in ? a : make_float2(0.0f, 0.0f);
+                    r.b2[q][rr] = make_float2(0.0f, 0.0f);
+                    if constexpr (BETA) {
+                        const float2 bt = *reinterpret_cast<const float2*>(d.beta + run8[rr] + 8 * bc);
+                        if (in) r.b2[q][rr] = bt;
+                    }
                 } else {
-                    r.b[q] = 0.0f;
+                    const float a = srow[rr][(int64_t)bc * bstep];
+                    r.a[q][rr] = in ? a : 0.0f;
+                    if constexpr (BETA) {
+                        const float bt = brow[rr][(int64_t)bc * bstep];
+                        r.b[q][rr] = in ? bt : 0.0f;
+                        if constexpr (DIRECT) r.b[q][rr] = __builtin_fmaf(-128.0f, r.a[q][rr], r.b[q][rr]);
+                    } else {
+                        r.b[q][rr] = 0.0f;
+                    }
                 }
             }
             if constexpr (XALL) {
@@ -204,8 +216,10 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
         }
     };
 
-    f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
     const f32x4_t zero = {0.0f, 0.0f, 0.0f, 0.0f};
+    f32x4_t acc[R];
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) acc[rr] = zero;
     const uint4 ones4 = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
     const bf16x8 ones = __builtin_bit_cast(bf16x8, ones4);
     auto operand = [&](uint32_t w) __attribute__((always_inline)) {
@@ -217,16 +231,6 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
         const uint4 v = make_uint4(my_pair[(w & 0xffu) * kReplicas], my_pair[((w >> 8) & 0xffu) * kReplicas],
                                    my_pair[((w >> 16) & 0xffu) * kReplicas], my_pair[(w >> 24) * kReplicas]);
         return __builtin_bit_cast(bf16x8, v);
-    };
-    // BR = 8: the 8 weights of one code dword (one block column) as bf16(fma(c, alpha, beta))
-    auto weights8 = [&](uint32_t w, float a, float b) __attribute__((always_inline)) {
-        uint32_t o[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float2 c = my_pairf[((w >> (8 * i)) & 0xffu) * kReplicas];
-            o[i] = BETA ? pack_bf16(__fmaf_rn(c.x, a, b), __fmaf_rn(c.y, a, b)) : pack_bf16(__fmul_rn(c.x, a), __fmul_rn(c.y, a));
-        }
-        return __builtin_bit_cast(bf16x8, make_uint4(o[0], o[1], o[2], o[3]));
     };
     // BR = 8: the four table entries of an operand (one code dword) are read one operand ahead of their use, so that
     // a wave has LDS reads in flight under the scaling arithmetic of the previous operand instead of waiting for
@@ -255,23 +259,29 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
             o[i] = BETA ? pack_bf16(__fmaf_rn(cv[i].x, a, b), __fmaf_rn(cv[i].y, a, b)) : pack_bf16(__fmul_rn(cv[i].x, a), __fmul_rn(cv[i].y, a));
         return __builtin_bit_cast(bf16x8, make_uint4(o[0], o[1], o[2], o[3]));
     };
-    auto compute8 = [&](const DecodeRegs<G>& r) __attribute__((always_inline)) {
+    auto compute8 = [&](const DecodeRegs<G, R>& r) __attribute__((always_inline)) {
         float2 cv[2][4];
-        fetch8(r.c[0].x, cv[0]);
+        auto dword = [&](int v) __attribute__((always_inline)) {      // operand v = (block, code dword, row group)
+            const int u = v / R, rr = v % R;
+            return (u & 1) ? r.c[u >> 1][rr].y : r.c[u >> 1][rr].x;
+        };
+        fetch8(dword(0), cv[0]);
+        bf16x8 x;
 #pragma unroll
-        for (int u = 0; u < 2 * G; ++u) {                     // operand u: block u / 2, code dword u % 2
-            const int q = u >> 1;
-            if (u + 1 < 2 * G) fetch8((u & 1) ? r.c[q + 1 < G ? q + 1 : q].x : r.c[q].y, cv[(u + 1) & 1]);
+        for (int v = 0; v < 2 * G * R; ++v) {
+            const int u = v / R, rr = v % R, q = u >> 1;
+            if (v + 1 < 2 * G * R) fetch8(dword(v + 1 < 2 * G * R ? v + 1 : v), cv[(v + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
-            bf16x8 x;
-            if constexpr (XLDS) x = *reinterpret_cast<const bf16x8*>(xs + nl * kXPitch + 128 * q + 32 * kg + 16 * (u & 1));
-            else if constexpr (XALL) x = *reinterpret_cast<const bf16x8*>(x_mine + r.xb[q] * (kBlock * 2) + 16 * (u & 1));
-            else x = __builtin_bit_cast(bf16x8, r.x[q][u & 1]);
-            const bf16x8 wv = build8(cv[u & 1], (u & 1) ? r.a2[q].y : r.a2[q].x, (u & 1) ? r.b2[q].y : r.b2[q].x);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, wv, acc, 0, 0, 0);
+            if (rr == 0) {
+                if constexpr (XLDS) x = *reinterpret_cast<const bf16x8*>(xs + nl * kXPitch + 128 * q + 32 * kg + 16 * (u & 1));
+                else if constexpr (XALL) x = *reinterpret_cast<const bf16x8*>(x_mine + r.xb[q] * (kBlock * 2) + 16 * (u & 1));
+                else x = __builtin_bit_cast(bf16x8, r.x[q][u & 1]);
+            }
+            const bf16x8 wv = build8(cv[v & 1], (u & 1) ? r.a2[q][rr].y : r.a2[q][rr].x, (u & 1) ? r.b2[q][rr].y : r.b2[q][rr].x);
+            acc[rr] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, wv, acc[rr], 0, 0, 0);
         }
     };
-    auto compute = [&](const DecodeRegs<G>& r) __attribute__((always_inline)) {
+    auto compute = [&](const DecodeRegs<G, R>& r) __attribute__((always_inline)) {
         if constexpr (XLDS) {
 #pragma unroll
             for (int p = 0; p < 8; ++p)
@@ -290,26 +300,27 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
             } else {
                 x0 = __builtin_bit_cast(bf16x8, r.x[q][0]); x1 = __builtin_bit_cast(bf16x8, r.x[q][1]);
             }
-            if constexpr (BR == 8) {
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x0, weights8(r.c[q].x, r.a2[q].x, r.b2[q].x), acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x1, weights8(r.c[q].y, r.a2[q].y, r.b2[q].y), acc, 0, 0, 0);
-                continue;
-            }
-            f32x4_t blk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x0, operand(r.c[q].x), zero, 0, 0, 0);
-            blk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x1, operand(r.c[q].y), blk, 0, 0, 0);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(r.a[q], blk[e], acc[e]);
+            f32x4_t sx = zero;
             if constexpr (BETA) {
-                f32x4_t sx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x0, ones, zero, 0, 0, 0);
+                sx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x0, ones, zero, 0, 0, 0);
                 sx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x1, ones, sx, 0, 0, 0);
+            }
 #pragma unroll
-                for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(r.b[q], sx[e], acc[e]);
+            for (int rr = 0; rr < R; ++rr) {
+                f32x4_t blk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x0, operand(r.c[q][rr].x), zero, 0, 0, 0);
+                blk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x1, operand(r.c[q][rr].y), blk, 0, 0, 0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[rr][e] = __builtin_fmaf(r.a[q][rr], blk[e], acc[rr][e]);
+                if constexpr (BETA) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[rr][e] = __builtin_fmaf(r.b[q][rr], sx[e], acc[rr][e]);
+                }
             }
         }
     };
 
     // two register sets: the loads of the wave's next group are in flight while this one is contracted
-    DecodeRegs<G> r0, r1;
+    DecodeRegs<G, R> r0, r1;
     int j = wave;
     if (j < groups) load(r0, j);
     if constexpr (XALL) {                                     // behind the first loads of codes: both are in flight together
@@ -343,34 +354,38 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
 
     // The lane holds row nl, tokens 4*kg .. 4*kg+3.  Partial tiles of the four waves -> LDS; wave 0 adds
     // them in wave order, lane l taking token l >> 2 and rows 4*(l & 3) .. +3 so that stores run along n.
-#pragma unroll
-    for (int e = 0; e < 4; ++e) red[wave][e][lane] = acc[e];
-    __syncthreads();
     const int tok = lane >> 2, nq = 4 * (lane & 3);
-    if (wave == 0 && tok < d.T) {
-        float v[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int src = (nq + i) + 16 * (tok >> 2), e = tok & 3;
-            v[i] = ((red[0][e][src] + red[1][e][src]) + red[2][e][src]) + red[3][e][src];
-        }
-        const int nb = n0 + nq;
-        qblora_bf16* yp = d.Y + (int64_t)tok * d.d_out + nb;
-        if (nb + 3 < d.d_out && (d.d_out & 3) == 0) {
-            *reinterpret_cast<uint2*>(yp) = make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]));
-        } else {
+    for (int rr = 0; rr < R; ++rr) {
+        if (rr) __syncthreads();                               // wave 0 has read the previous row group's partial tiles
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (nb + i < d.d_out) reinterpret_cast<uint16_t*>(yp)[i] = (uint16_t)(pack_bf16(v[i], 0.0f) & 0xffffu);
+        for (int e = 0; e < 4; ++e) red[wave][e][lane] = acc[rr][e];
+        __syncthreads();
+        if (wave == 0 && tok < d.T) {
+            float v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int src = (nq + i) + 16 * (tok >> 2), e = tok & 3;
+                v[i] = ((red[0][e][src] + red[1][e][src]) + red[2][e][src]) + red[3][e][src];
+            }
+            const int nb = n0 + 16 * rr + nq;
+            qblora_bf16* yp = d.Y + (int64_t)tok * d.d_out + nb;
+            if (nb + 3 < d.d_out && (d.d_out & 3) == 0) {
+                *reinterpret_cast<uint2*>(yp) = make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]));
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (nb + i < d.d_out) reinterpret_cast<uint16_t*>(yp)[i] = (uint16_t)(pack_bf16(v[i], 0.0f) & 0xffffu);
+            }
         }
     }
 }
 
 // the form with all of X in LDS (at most kXAllBytes of it: inside the default limit of dynamic LDS; a limit of 66 KB
 // measured slower wherever it applied -- 22016 x 8192 at four tokens 48 against 33 us, two workgroups per CU)
-template <bool BETA, bool DIRECT, int G, int BR = 1>
+template <bool BETA, bool DIRECT, int G, int BR = 1, int R = 1>
 int launch_xall(const DecodeDesc& d, dim3 grid, size_t x_all_bytes, hipStream_t st) {
-    hipLaunchKernelGGL((k_w4_decode_xall<BETA, DIRECT, G, BR>), grid, dim3(256), x_all_bytes, st, d);
+    hipLaunchKernelGGL((k_w4_decode_xall<BETA, DIRECT, G, BR, R>), grid, dim3(256), x_all_bytes, st, d);
     return launch_status();
 }
 
@@ -401,6 +416,19 @@ int launch_w4_decode(const uint8_t* codes, const float* scales, const float* bet
         if (grid.x > 1024) return beta ? launch_xall<true, true, 2, 8>(d, grid, x_all_bytes, st) : launch_xall<false, true, 2, 8>(d, grid, x_all_bytes, st);
         return beta ? launch_xall<true, true, 4, 8>(d, grid, x_all_bytes, st) : launch_xall<false, true, 4, 8>(d, grid, x_all_bytes, st);
     }
+    // Two row groups per workgroup in that form, for tall layers of packed INT4 models (more than 512 workgroups
+    // of 32 rows): half as many copies of X, and the workgroups fit the CUs with the copy at two tokens as well
+    // (22016 x 8192: one token 25.8 -> 23.6 us = 0.60 of the HBM peak, two tokens 29.3 -> 25.5 us).  Without the
+    // copy, and with the activations staged per wave, two row groups measured slower (three tokens 34.2 against 30.4
+    // us, sixteen 46.5 against 43.8); on shorter or wider layers too (11008 rows 9.1 against 7.8 us).
+    const dim3 grid2((unsigned)(((d_out + 31) / 32 + 15) / 16 * 16));
+    const size_t per_cu2 = (grid2.x + 255) / 256;
+    const bool two_groups = grid2.x > 512 && x_all_bytes <= (size_t)kXAllBytes && per_cu2 * (x_all_bytes + 5 * 1024) <= 150 * 1024 &&
+                            d_in % 8 == 0;
+    // (8 x 8 blocks of an INT4 model: level at one token, 35.6 -> 29.8 us at two)
+    if (block_rows == 8 && int4 && two_groups)
+        return beta ? launch_xall<true, true, 2, 8, 2>(d, grid2, x_all_bytes, st) : launch_xall<false, true, 2, 8, 2>(d, grid2, x_all_bytes, st);
+    if (block_rows != 8 && regrouped && beta && tiled && two_groups) return launch_xall<true, true, 2, 1, 2>(d, grid2, x_all_bytes, st);
     if (block_rows != 8 && x_all_bytes <= (size_t)kXAllBytes && per_cu * (x_all_bytes + 5 * 1024) <= 150 * 1024 && d_in % 8 == 0) {
         const bool small_sets = grid.x > 1024;      // more workgroups than fit at four waves per SIMD
         if (regrouped) {

@@ -161,7 +161,8 @@ def test_quantization_aware_loop_on_8x8_blocks(qb, oracle, T, d_out, d_in, lam1,
 
 @pytest.mark.parametrize("T", [1, 5, 16, 40, 130])       # above 16: the mid-batch form of the same call
 # (the tall case: more than 512 row groups, where few tokens of an INT4 model take the form with all of X in LDS)
-@pytest.mark.parametrize("d_out,d_in,minmax", [(512, 1024, True), (328, 832, True), (256, 512, False), (8264, 192, True)])
+@pytest.mark.parametrize("d_out,d_in,minmax", [(512, 1024, True), (328, 832, True), (256, 512, False), (8264, 192, True),
+                                               (16456, 128, True)])
 def test_small_batch_inference_on_8x8_blocks(qb, oracle, codebook, T, d_out, d_in, minmax):
     """Merged-model inference (Sec. 3.3) on 8 x 8 blocks: the small-batch kernel contracts the bf16 compute
     weight bf16(fma(c, alpha, beta)), like the training forward; with and without the tile-ordered code copy."""
