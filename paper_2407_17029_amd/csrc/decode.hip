@@ -429,6 +429,20 @@ int launch_w4_decode(const uint8_t* codes, const float* scales, const float* bet
     if (block_rows == 8 && int4 && two_groups)
         return beta ? launch_xall<true, true, 2, 8, 2>(d, grid2, x_all_bytes, st) : launch_xall<false, true, 2, 8, 2>(d, grid2, x_all_bytes, st);
     if (block_rows != 8 && regrouped && beta && tiled && two_groups) return launch_xall<true, true, 2, 1, 2>(d, grid2, x_all_bytes, st);
+    // Four row groups (64 rows, a copy of up to 66 KB, two workgroups per CU) where the copy would not fit otherwise:
+    // 22016 x 8192 at three / four tokens 30.4 -> 28.4 / 32.0 -> 29.6 us.  The kernel's limit of dynamic LDS is raised
+    // once (the initialisation of a function-local static is thread safe).
+    if (block_rows != 8 && regrouped && beta && tiled && d_in % 8 == 0 && x_all_bytes <= 66 * 1024) {
+        const dim3 grid4((unsigned)(((d_out + 63) / 64 + 15) / 16 * 16));
+        const size_t per_cu4 = (grid4.x + 255) / 256;
+        if (grid4.x > 256 && per_cu4 * (x_all_bytes + 5 * 1024) <= 150 * 1024) {
+            auto kern = k_w4_decode_xall<true, true, 2, 1, 4>;
+            static const hipError_t raised = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 66 * 1024);
+            if (raised != hipSuccess) return QBLORA_ERR_LAUNCH;
+            hipLaunchKernelGGL(kern, grid4, dim3(256), x_all_bytes, st, d);
+            return launch_status();
+        }
+    }
     if (block_rows != 8 && x_all_bytes <= (size_t)kXAllBytes && per_cu * (x_all_bytes + 5 * 1024) <= 150 * 1024 && d_in % 8 == 0) {
         const bool small_sets = grid.x > 1024;      // more workgroups than fit at four waves per SIMD
         if (regrouped) {

@@ -167,7 +167,7 @@ def test_scale_operators_benchmark_shape(qb, oracle, codebook, op):
 
 def test_small_batch_inference_at_the_measured_shape(qb, oracle):
     """The decode kernel on the 65B up-projection shape bench.py times among its side measurements (22016 x 8192, INT4 with offsets, tile-
-    ordered pack), T = 1 and 16, and the mid-batch form at 32, 128 and 200 tokens: sampled output features against the oracle (a feature needs its own weight row only)."""
+    ordered pack), T = 1, 2, 3, 7 and 16, and the mid-batch form at 32, 128 and 200 tokens: sampled output features against the oracle (a feature needs its own weight row only)."""
     from gpu_util import f32_to_dev, bf16_to_dev, bf16_to_f64, bf16_half_ulp
     d_out, d_in = 22016, 8192
     rng = np.random.default_rng(4242)
@@ -191,7 +191,7 @@ def test_small_batch_inference_at_the_measured_shape(qb, oracle):
             Wt_mid = oracle.dequantize(c, a, b, cb, 64, 2)                # above 16 tokens: the bf16 compute weight
         sel_t = torch.from_numpy(sel).to(qw.codes.device)
         assert np.array_equal(qw.codes[sel_t].cpu().numpy(), c)          # the device weight holds the oracle's bits there
-        for T in (1, 16, 32, 128, 200):                                  # 32 ...: the mid-batch form, split over the inputs
+        for T in (1, 2, 3, 7, 16, 32, 128, 200):                         # 1 .. 3: the forms with X in LDS; 32 ...: the mid-batch form, split over the inputs
             Xb = synth.f32_to_bf16_bits(rng.standard_normal((T, d_in), dtype=np.float32))
             Y = qb.qblora_linear_decode(qw, bf16_to_dev(Xb), pack=pack)
             torch.cuda.synchronize()
