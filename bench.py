@@ -540,7 +540,7 @@ def bench_decode():
         qp = qw.c_struct()
         sp = timed(lambda: qb.lib().qblora_decode_pack(C.byref(qp), qb._ptr(pack), qb._stream()), iters=10, warm=2)
         emit(kernel="decode_pack (one-off)", shape=[d_out, d_in], us=round(sp * 1e6, 1))
-        for T in (1, 4, 16):
+        for T in (1, 2, 4, 16):
             X = torch.randn(T, d_in, device=DEV).to(torch.bfloat16)
             Y = torch.empty(T, d_out, dtype=torch.bfloat16, device=DEV)
             q = qw.c_struct()
