@@ -35,6 +35,17 @@ __device__ __forceinline__ float e4m3_to_float(uint32_t c) {
     return (c & 0x80) ? -v : v;
 }
 
+// Byte `idx` (0 .. 3, a constant after unrolling) of v as a float: one v_cvt_f32_ubyteN.  Written as the instruction:
+// from a shift and a mask the compiler makes a bit-field extract and a conversion.
+__device__ __forceinline__ float byte_to_float(uint32_t v, int idx) {
+    float r;
+    if (idx == 0) asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(r) : "v"(v));
+    else if (idx == 1) asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(r) : "v"(v));
+    else if (idx == 2) asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(r) : "v"(v));
+    else asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(r) : "v"(v));
+    return r;
+}
+
 // Reconstructed block scale under the grouped E4M3 second-level quantization.
 __device__ __forceinline__ float grouped_scale(const uint8_t* __restrict__ scale_codes,
                                                const float* __restrict__ step,

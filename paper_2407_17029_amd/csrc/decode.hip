@@ -39,17 +39,6 @@ namespace {
 
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
-// byte N of v as a float (v_cvt_f32_ubyteN)
-template <int N>
-__device__ __forceinline__ float ubyte_to_float(uint32_t v) {
-    float r;
-    if constexpr (N == 0) asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(r) : "v"(v));
-    else if constexpr (N == 1) asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(r) : "v"(v));
-    else if constexpr (N == 2) asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(r) : "v"(v));
-    else asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(r) : "v"(v));
-    return r;
-}
-
 struct DecodeDesc {
     const uint8_t* codes; const float* scales; const float* beta; Codebook cb;
     int tiled;                 // the three arrays are in tile order (256-row tiles, rows of a block adjacent);
@@ -243,10 +232,10 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
             // one byte-to-float conversion per code on the two masked dwords (written as the instruction: from shifts
             // and masks the compiler makes a bit-field extract and a conversion per code)
             const uint32_t lo = w & 0x0F0F0F0Fu, hi = (w >> 4) & 0x0F0F0F0Fu;
-            cv[0] = make_float2(ubyte_to_float<0>(lo), ubyte_to_float<0>(hi));
-            cv[1] = make_float2(ubyte_to_float<1>(lo), ubyte_to_float<1>(hi));
-            cv[2] = make_float2(ubyte_to_float<2>(lo), ubyte_to_float<2>(hi));
-            cv[3] = make_float2(ubyte_to_float<3>(lo), ubyte_to_float<3>(hi));
+            cv[0] = make_float2(byte_to_float(lo, 0), byte_to_float(hi, 0));
+            cv[1] = make_float2(byte_to_float(lo, 1), byte_to_float(hi, 1));
+            cv[2] = make_float2(byte_to_float(lo, 2), byte_to_float(hi, 2));
+            cv[3] = make_float2(byte_to_float(lo, 3), byte_to_float(hi, 3));
         } else {
 #pragma unroll
             for (int i = 0; i < 4; ++i) cv[i] = my_pairf[((w >> (8 * i)) & 0xffu) * kReplicas];
