@@ -434,11 +434,16 @@ __global__ __launch_bounds__(256) void k_dequantize_bf16(const uint32_t* __restr
 // one chunk lie in 16 different positions) and stores 1 KB per instruction, 4 KB contiguous per wave.  (The first form
 // let a lane load the 32 code bytes of its row's block, twice per row: both lanes of a row need every other dword;
 // it streamed at 0.60 of the HBM peak.)
+// BETA: offsets present; GEOM: 0 = 64-blocks, 1 = 8 x 8 blocks, 2 = blocks of 8 rows x 4 inputs -- compile-time, so that
+// a launch carries neither the other geometries' loads nor both of multiply and multiply-add with a select per weight
+// (380 -> 230 vector instructions per thread).
+template <bool BETA, int GEOM>
 __global__ __launch_bounds__(256) void k_dequantize_operand(const uint8_t* __restrict__ codes,
                                                             const float* __restrict__ scales,
                                                             const float* __restrict__ beta, Codebook cb,
-                                                            int d_out, int d_in, int block_rows, int block_cols,
+                                                            int d_out, int d_in,
                                                             uint4* __restrict__ out) {
+    constexpr int block_rows = GEOM == 0 ? 1 : 8, block_cols = GEOM == 2 ? 4 : 8;
     __shared__ float lut[16];
     __shared__ __align__(16) uint4 tile[64][16];                // [n][chunk of 8 k], positions swizzled
     const int t = threadIdx.x;
@@ -456,25 +461,25 @@ __global__ __launch_bounds__(256) void k_dequantize_operand(const uint8_t* __res
         float4 a4 = make_float4(0.f, 0.f, 0.f, 0.f), b4 = make_float4(0.f, 0.f, 0.f, 0.f), a4b = a4, b4b = b4;
         if (k0 < d_in) {                                        // d_in % 64 == 0: the last tile may be half
             cq = *reinterpret_cast<const uint4*>(codes + n * (d_in / 2) + k0 / 2);
-            if (block_rows == 8 && block_cols == 4) {           // eight block columns of 4 inputs
+            if constexpr (block_rows == 8 && block_cols == 4) {  // eight block columns of 4 inputs
                 const int64_t blk = (n >> 3) * (int64_t)(d_in / 4) + k0 / 4;
                 a4 = *reinterpret_cast<const float4*>(scales + blk);
                 a4b = *reinterpret_cast<const float4*>(scales + blk + 4);
-                if (beta) { b4 = *reinterpret_cast<const float4*>(beta + blk); b4b = *reinterpret_cast<const float4*>(beta + blk + 4); }
-            } else if (block_rows == 8) {                       // four block columns of 8 inputs
+                if constexpr (BETA) { b4 = *reinterpret_cast<const float4*>(beta + blk); b4b = *reinterpret_cast<const float4*>(beta + blk + 4); }
+            } else if constexpr (block_rows == 8) {              // four block columns of 8 inputs
                 const int64_t blk = (n >> 3) * (int64_t)(d_in / 8) + k0 / 8;
                 a4 = *reinterpret_cast<const float4*>(scales + blk);
-                if (beta) b4 = *reinterpret_cast<const float4*>(beta + blk);
+                if constexpr (BETA) b4 = *reinterpret_cast<const float4*>(beta + blk);
             } else {
                 const int64_t blk = n * (int64_t)(d_in / kBlock) + k0 / kBlock;
                 a1 = scales[blk];
-                if (beta) b1 = beta[blk];
+                if constexpr (BETA) b1 = beta[blk];
             }
         }
         const uint32_t cw[4] = {cq.x, cq.y, cq.z, cq.w};
         const float as[8] = {a4.x, a4.y, a4.z, a4.w, a4b.x, a4b.y, a4b.z, a4b.w};
         const float bs[8] = {b4.x, b4.y, b4.z, b4.w, b4b.x, b4b.y, b4b.z, b4b.w};
-        const bool half = block_rows == 8 && block_cols == 4;   // two blocks per chunk of 8 inputs
+        constexpr bool half = block_rows == 8 && block_cols == 4;   // two blocks per chunk of 8 inputs
 #pragma unroll
         for (int c = 0; c < 4; ++c) {                           // chunk 4*piece + c: 8 inputs
             const float a = half ? as[2 * c] : block_rows == 8 ? as[c] : a1, be = half ? bs[2 * c] : block_rows == 8 ? bs[c] : b1;
@@ -483,7 +488,7 @@ __global__ __launch_bounds__(256) void k_dequantize_operand(const uint8_t* __res
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const float cv = lut[(cw[c] >> (4 * j)) & 15];
-                v[j] = beta ? __fmaf_rn(cv, j < 4 ? a : a_hi, j < 4 ? be : be_hi) : __fmul_rn(cv, j < 4 ? a : a_hi);
+                v[j] = BETA ? __fmaf_rn(cv, j < 4 ? a : a_hi, j < 4 ? be : be_hi) : __fmul_rn(cv, j < 4 ? a : a_hi);
             }
             tile[row][(4 * piece + c) ^ (row & 15)] =
                 make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]));
@@ -519,11 +524,13 @@ __global__ __launch_bounds__(256) void k_dequantize_operand(const uint8_t* __res
 // holds k = r, n = 16q + 8hi .. + 7).  (The first form read 4 bytes of codes per thread and wrote 2-byte elements
 // into a [k][n] tile: 57 % of its LDS cycles were bank conflicts and it streamed at 0.49 of the HBM peak.)
 typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+template <bool BETA, int GEOM>
 __global__ __launch_bounds__(256) void k_dequantize_operand_t(const uint8_t* __restrict__ codes,
                                                               const float* __restrict__ scales,
                                                               const float* __restrict__ beta, Codebook cb,
-                                                              int d_out, int d_in, int block_rows, int block_cols,
+                                                              int d_out, int d_in,
                                                               uint4* __restrict__ out) {
+    constexpr int block_rows = GEOM == 0 ? 1 : 8, block_cols = GEOM == 2 ? 4 : 8;
     __shared__ float lut[16];
     __shared__ __align__(16) unsigned char tile[64 * 256];      // [n][128 k] bf16, chunks swizzled
     const int t = threadIdx.x;
@@ -541,25 +548,25 @@ __global__ __launch_bounds__(256) void k_dequantize_operand_t(const uint8_t* __r
         float4 a4 = make_float4(0.f, 0.f, 0.f, 0.f), b4 = make_float4(0.f, 0.f, 0.f, 0.f), a4b = a4, b4b = b4;
         if (k0 < d_in) {                                        // d_in % 64 == 0: the last tile may be half
             cq = *reinterpret_cast<const uint4*>(codes + n * (d_in / 2) + k0 / 2);
-            if (block_rows == 8 && block_cols == 4) {           // eight block columns of 4 inputs
+            if constexpr (block_rows == 8 && block_cols == 4) {  // eight block columns of 4 inputs
                 const int64_t blk = (n >> 3) * (int64_t)(d_in / 4) + k0 / 4;
                 a4 = *reinterpret_cast<const float4*>(scales + blk);
                 a4b = *reinterpret_cast<const float4*>(scales + blk + 4);
-                if (beta) { b4 = *reinterpret_cast<const float4*>(beta + blk); b4b = *reinterpret_cast<const float4*>(beta + blk + 4); }
-            } else if (block_rows == 8) {                       // four block columns of 8 inputs
+                if constexpr (BETA) { b4 = *reinterpret_cast<const float4*>(beta + blk); b4b = *reinterpret_cast<const float4*>(beta + blk + 4); }
+            } else if constexpr (block_rows == 8) {              // four block columns of 8 inputs
                 const int64_t blk = (n >> 3) * (int64_t)(d_in / 8) + k0 / 8;
                 a4 = *reinterpret_cast<const float4*>(scales + blk);
-                if (beta) b4 = *reinterpret_cast<const float4*>(beta + blk);
+                if constexpr (BETA) b4 = *reinterpret_cast<const float4*>(beta + blk);
             } else {
                 const int64_t blk = n * (int64_t)(d_in / kBlock) + k0 / kBlock;
                 a1 = scales[blk];
-                if (beta) b1 = beta[blk];
+                if constexpr (BETA) b1 = beta[blk];
             }
         }
         const uint32_t cw[4] = {cq.x, cq.y, cq.z, cq.w};
         const float as[8] = {a4.x, a4.y, a4.z, a4.w, a4b.x, a4b.y, a4b.z, a4b.w};
         const float bs[8] = {b4.x, b4.y, b4.z, b4.w, b4b.x, b4b.y, b4b.z, b4b.w};
-        const bool half = block_rows == 8 && block_cols == 4;   // two blocks per chunk of 8 inputs
+        constexpr bool half = block_rows == 8 && block_cols == 4;   // two blocks per chunk of 8 inputs
 #pragma unroll
         for (int c = 0; c < 4; ++c) {                           // chunk 4*piece + c: 8 inputs
             const float a = half ? as[2 * c] : block_rows == 8 ? as[c] : a1, be = half ? bs[2 * c] : block_rows == 8 ? bs[c] : b1;
@@ -568,7 +575,7 @@ __global__ __launch_bounds__(256) void k_dequantize_operand_t(const uint8_t* __r
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const float cv = lut[(cw[c] >> (4 * j)) & 15];
-                v[j] = beta ? __fmaf_rn(cv, j < 4 ? a : a_hi, j < 4 ? be : be_hi) : __fmul_rn(cv, j < 4 ? a : a_hi);
+                v[j] = BETA ? __fmaf_rn(cv, j < 4 ? a : a_hi, j < 4 ? be : be_hi) : __fmul_rn(cv, j < 4 ? a : a_hi);
             }
             const int pos = (4 * piece + c) ^ ((row & 3) << 2);
             *reinterpret_cast<uint4*>(tile + row * 256 + pos * 16) =
@@ -718,16 +725,26 @@ int launch_dequantize_operand(const qblora_qweight& qw, const float* scales, int
     Codebook cb;
     for (int j = 0; j < 16; ++j) cb.c[j] = qw.codebook[j];
     const int br = qw.block_rows == 8 ? 8 : 1, bc = br == 8 ? qw.block / 8 : qw.block;
-    if (!transposed) {
-        const int64_t blocks = (int64_t)((qw.d_out + 63) / 64) * ((qw.d_in + 127) / 128);
-        if (blocks > 0x7fffffff) return QBLORA_ERR_UNSUPPORTED;
-        hipLaunchKernelGGL(k_dequantize_operand, dim3((unsigned)blocks), dim3(256), 0, st, qw.codes, scales, qw.beta, cb,
-                           qw.d_out, qw.d_in, br, bc, reinterpret_cast<uint4*>(Wop));
+    const int64_t blocks = transposed ? (int64_t)((qw.d_in + 127) / 128) * (qw.d_out / 64)
+                                      : (int64_t)((qw.d_out + 63) / 64) * ((qw.d_in + 127) / 128);
+    if (blocks > 0x7fffffff) return QBLORA_ERR_UNSUPPORTED;
+    auto go = [&](auto plain, auto trans) {
+        if (transposed)
+            hipLaunchKernelGGL(trans, dim3((unsigned)blocks), dim3(256), 0, st, qw.codes, scales, qw.beta, cb, qw.d_out, qw.d_in,
+                               reinterpret_cast<uint4*>(Wop));
+        else
+            hipLaunchKernelGGL(plain, dim3((unsigned)blocks), dim3(256), 0, st, qw.codes, scales, qw.beta, cb, qw.d_out, qw.d_in,
+                               reinterpret_cast<uint4*>(Wop));
+    };
+    const int geom = br == 1 ? 0 : bc == 8 ? 1 : 2;
+    if (qw.beta) {
+        if (geom == 0) go(k_dequantize_operand<true, 0>, k_dequantize_operand_t<true, 0>);
+        else if (geom == 1) go(k_dequantize_operand<true, 1>, k_dequantize_operand_t<true, 1>);
+        else go(k_dequantize_operand<true, 2>, k_dequantize_operand_t<true, 2>);
     } else {
-        const int64_t blocks = (int64_t)((qw.d_in + 127) / 128) * (qw.d_out / 64);
-        if (blocks > 0x7fffffff) return QBLORA_ERR_UNSUPPORTED;
-        hipLaunchKernelGGL(k_dequantize_operand_t, dim3((unsigned)blocks), dim3(256), 0, st, qw.codes, scales, qw.beta,
-                           cb, qw.d_out, qw.d_in, br, bc, reinterpret_cast<uint4*>(Wop));
+        if (geom == 0) go(k_dequantize_operand<false, 0>, k_dequantize_operand_t<false, 0>);
+        else if (geom == 1) go(k_dequantize_operand<false, 1>, k_dequantize_operand_t<false, 1>);
+        else go(k_dequantize_operand<false, 2>, k_dequantize_operand_t<false, 2>);
     }
     return launch_status();
 }
