@@ -58,7 +58,7 @@ struct DecodeRegs {                         // one group = G consecutive blocks 
     float2 a2[G][R], b2[G][R];              // BR = 8: scales and offsets of the lane's two block columns
     int xb[G];                              // XALL: the (redirected) block whose activations go with c[q]
     uint4 x[G][2];                          // activations of the lane's token, 8 per MFMA (fetched in operand order)
-    uint4 xg[8];                            // XLDS: as fetched, token 2p + (lane >> 5), chunk lane & 31 of the group
+    uint4 xg[8];                            // XLDS: as fetched, 64 / (8 G) token rows per load, 16-byte chunk lane % (8 G) of the group
 };
 
 // XLDS (used above 8 tokens): the activations go through LDS.  In operand order a load instruction touches
@@ -71,6 +71,8 @@ struct DecodeRegs {                         // one group = G consecutive blocks 
 // the bytes of the codes through the vector memory path (every lane fetches its own copy of the 16 activations
 // it shares with 15 others), and that path, not HBM, set the time.
 constexpr int kXAllBytes = 40 * 1024;
+constexpr int kStagedPairMinTokens = 4;    // see launch_w4_decode
+constexpr int kStagedPairMinTokens8 = 2;   // the same for 8 x 8 blocks
 template <bool BETA, int BR, bool DIRECT, int XMODE, int G = 4, int R = 1>
 __device__ __forceinline__ void w4_decode(const DecodeDesc& d);
 
@@ -91,7 +93,6 @@ __global__ __launch_bounds__(256) void k_w4_decode_xall(DecodeDesc d) {
 template <bool BETA, int BR, bool DIRECT, int XMODE, int G, int R>
 __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     constexpr bool XLDS = XMODE == 1, XALL = XMODE == 2;
-    static_assert(G == 4 || !XLDS, "the staged activation rows hold four blocks");
     static_assert(!DIRECT || BR == 8 || BETA, "the table-free form of 64-blocks needs offsets");
     extern __shared__ __align__(16) unsigned char x_all[];       // XALL: [T][d_in * 2 + 16] bytes
     // entry e of replica q at e*kReplicas + q: bf16 pairs (4 bytes), or fp32 pairs (8 bytes) for BR = 8
@@ -100,7 +101,8 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     // Activations of one group of 4 blocks (16 tokens x 512 bytes), one region per wave: fetched as whole
     // 512-byte row segments (two token rows per load instruction) and read back in operand order.  A row is
     // 528 bytes so that the 16 tokens of an operand read start 16 bytes apart modulo 256.
-    constexpr int kXPitch = 528;
+    constexpr int kXPitch = G * 128 + 16;
+    constexpr int kLPR = 8 * G, kTPL = 64 / kLPR, kNX = 16 / kTPL;    // lanes per staged token row, token rows per load, loads
     __shared__ __align__(16) unsigned char xs_all[XLDS ? 4 : 1][XLDS ? 16 * kXPitch : 16];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int nl = lane & 15, kg = lane >> 4;
@@ -147,7 +149,7 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     }
     const int cstep = bstep * 32;
     unsigned char* xs = xs_all[XLDS ? wave : 0];
-    const int xtok = lane >> 5, xchunk = lane & 31;
+    const int xtok = lane / kLPR, xchunk = lane % kLPR;
     const qblora_bf16* xrow = d.X + (int64_t)min(nl, d.T - 1) * d.d_in + 16 * kg;
     const int x_pitch = d.d_in * 2 + 16;                      // token rows start 16 bytes apart modulo the banks
     const unsigned char* x_mine = x_all + min(nl, d.T - 1) * x_pitch + 32 * kg;      // XALL: inputs 16 kg .. of block 0
@@ -196,10 +198,10 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
         // that are never stored); chunks of blocks past the end of the row are redirected to the last block,
         // whose scale and offset are zero there.
 #pragma unroll
-        for (int p = 0; p < 8; ++p) {
-            if (2 * p < d.T) {
-                const int tk = min(2 * p + xtok, d.T - 1);
-                const int bc = min(4 * j + (xchunk >> 3), bpr - 1);
+        for (int p = 0; p < kNX; ++p) {
+            if (kTPL * p < d.T) {
+                const int tk = min(kTPL * p + xtok, d.T - 1);
+                const int bc = min(G * j + (xchunk >> 3), bpr - 1);
                 r.xg[p] = *reinterpret_cast<const uint4*>(d.X + (int64_t)tk * d.d_in + bc * kBlock + 8 * (xchunk & 7));
             }
         }
@@ -273,8 +275,8 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     auto compute = [&](const DecodeRegs<G, R>& r) __attribute__((always_inline)) {
         if constexpr (XLDS) {
 #pragma unroll
-            for (int p = 0; p < 8; ++p)
-                if (2 * p < d.T) *reinterpret_cast<uint4*>(xs + (2 * p + xtok) * kXPitch + xchunk * 16) = r.xg[p];
+            for (int p = 0; p < kNX; ++p)
+                if (kTPL * p < d.T) *reinterpret_cast<uint4*>(xs + (kTPL * p + xtok) * kXPitch + xchunk * 16) = r.xg[p];
         }
         if constexpr (BR == 8) { compute8(r); return; }
 #pragma unroll
@@ -408,8 +410,9 @@ int launch_w4_decode(const uint8_t* codes, const float* scales, const float* bet
     // Two row groups per workgroup in that form, for tall layers of packed INT4 models (more than 512 workgroups
     // of 32 rows): half as many copies of X, and the workgroups fit the CUs with the copy at two tokens as well
     // (22016 x 8192: one token 25.8 -> 23.6 us = 0.60 of the HBM peak, two tokens 29.3 -> 25.5 us).  Without the
-    // copy, and with the activations staged per wave, two row groups measured slower (three tokens 34.2 against 30.4
-    // us, sixteen 46.5 against 43.8); on shorter or wider layers too (11008 rows 9.1 against 7.8 us).
+    // copy two row groups measured slower with four-block register sets (three tokens 34.2 against 30.4 us, sixteen,
+    // staged per wave, 46.5 against 43.8; the staged form with two-block sets is the faster one, see below); on
+    // shorter or wider layers too (11008 rows 9.1 against 7.8 us).
     const dim3 grid2((unsigned)(((d_out + 31) / 32 + 15) / 16 * 16));
     const size_t per_cu2 = (grid2.x + 255) / 256;
     const bool two_groups = grid2.x > 512 && x_all_bytes <= (size_t)kXAllBytes && per_cu2 * (x_all_bytes + 5 * 1024) <= 150 * 1024 &&
@@ -444,6 +447,13 @@ int launch_w4_decode(const uint8_t* codes, const float* scales, const float* bet
     if (block_rows == 8) {                  // its fp32 pair table and the activation rows together leave two
                                             // workgroups per CU: measured slower (68 vs 64 us at T = 16), not used
         if (int4) {                         // (two-block register sets measured slower here: 38.3 against 35.8 us)
+            // tall layers: two row groups with staged two-block activation groups, as for the packed form below
+            // (22016 x 8192 at 3 / 4 / 8 / 16 tokens: 36 -> 34.8 / 38 -> 35.4 / 41.3 -> 37.4 / 46.3 -> 39.7 us)
+            if (grid2.x > 512 && T > kStagedPairMinTokens8) {
+                if (beta) hipLaunchKernelGGL((k_w4_decode<true, 8, true, 1, 2, 2>), grid2, dim3(256), 0, st, d);
+                else hipLaunchKernelGGL((k_w4_decode<false, 8, true, 1, 2, 2>), grid2, dim3(256), 0, st, d);
+                return launch_status();
+            }
             // above 6 tokens the activations go through LDS as for 64-blocks (22016 x 8192 at 16 tokens: 61.6 -> 47.3 us),
             // unless the layer has at most one workgroup per CU (4096 rows: 7.8 against 9.0 us)
             if (grid.x > 256) {
@@ -464,6 +474,14 @@ int launch_w4_decode(const uint8_t* codes, const float* scales, const float* bet
     }
     if (regrouped) {                        // codes regrouped by the pack: INT4 model with offsets, table-free
         if (!beta || !tiled) return QBLORA_ERR_UNSUPPORTED;
+        // Tall layers (more than 512 workgroups of 32 rows), beyond the forms with the LDS copy: two row groups per
+        // workgroup with the activations staged per wave in two-block groups (136 registers).  22016 x 8192 at 12 / 16
+        // tokens 40.5 -> 32.6 / 43.6 -> 34.2 us, at 6 / 8 tokens 33.7 -> 31.7 / 38 -> 31.6 us; on shorter or wider layers
+        // slower (11008 rows 14.5 against 12.3 us), and so are four row groups (164 registers: 35.7 to 37.4 us).
+        if (grid2.x > 512 && T > kStagedPairMinTokens) {
+            hipLaunchKernelGGL((k_w4_decode<true, 1, true, 1, 2, 2>), grid2, dim3(256), 0, st, d);
+            return launch_status();
+        }
         // more workgroups than fit at three waves per SIMD (156 registers): two-block register sets (92 registers, five
         // waves; 22016 x 8192 at two tokens 29.9 -> 28.1 us)
         if (!xlds && grid.x > 768) return go(k_w4_decode<true, 1, true, 0, 2>, k_w4_decode<true, 1, true, 1>);

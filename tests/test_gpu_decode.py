@@ -18,7 +18,7 @@ def qb():
 @pytest.mark.parametrize("base", ["codebook", "minmax", "grouped"])
 # (the last two: long rows, where the activations of a few tokens no longer fit the workgroup's LDS copy)
 @pytest.mark.parametrize("T,d_out,d_in", [(1, 512, 512), (3, 320, 192), (8, 1000, 1088), (16, 256, 2048), (5, 40, 64),
-                                         (8, 96, 4096), (4, 80, 8192), (2, 16448, 128)])   # (the last: a tall layer, two row groups per workgroup)
+                                         (8, 96, 4096), (4, 80, 8192), (2, 16448, 128), (7, 16440, 192), (12, 16448, 128)])   # (the last three: tall layers, two row groups per workgroup)
 def test_decode_parity(qb, oracle, codebook, T, d_out, d_in, base):
     from gpu_util import f32_to_dev, bf16_to_dev, assert_close_bf16, OracleWeight
     print(f"case decode T={T} {d_out}x{d_in} base={base}", flush=True)
