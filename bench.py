@@ -532,56 +532,89 @@ def bench_merge():
             del W, qw, H, out, keep, fns
 
 
-def bench_decode():
-    for d_out, d_in in SHAPES:
+def _decode_sets(d_out, d_in, **quant_kw):
+    """Enough quantized copies (weight, pack, C struct) of one layer for the cold measurement."""
+    wbytes = d_out * d_in * (0.5 + 8 / 64)
+    sets = []
+    for _ in range(n_sets(wbytes)):
         W = torch.randn(d_out, d_in, device=DEV) * 0.02
-        qw = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_MINMAX_INT4, tiled=False)
-        pack = qb.qblora_decode_pack(qw)
-        qp = qw.c_struct()
+        qw = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_MINMAX_INT4, tiled=False, **quant_kw)
+        sets.append((qw, qb.qblora_decode_pack(qw), qw.c_struct()))
+        del W
+    return sets
+
+
+DECODE_SHAPES = SHAPES + [(8192, 8192), (8192, 22016)]            # + 65B attention and MLP down
+
+
+def bench_decode():
+    """`us`: one weight set, which the 256 MB last-level cache holds between launches (every shape here is smaller);
+    `cold_us`: the launches rotate over enough sets that each reads its weights from HBM, as inference over the
+    layers of a model does.  frac_hbm / cold_frac_hbm = the weight stream's bytes over those times."""
+    for d_out, d_in in DECODE_SHAPES:
+        sets = _decode_sets(d_out, d_in)
+        qw, pack, qp = sets[0]
         sp = timed(lambda: qb.lib().qblora_decode_pack(C.byref(qp), qb._ptr(pack), qb._stream()), iters=10, warm=2)
         emit(kernel="decode_pack (one-off)", shape=[d_out, d_in], us=round(sp * 1e6, 1))
-        for T in (1, 2, 4, 16):
+        for T in (1, 2, 4, 8, 16):
             X = torch.randn(T, d_in, device=DEV).to(torch.bfloat16)
             Y = torch.empty(T, d_out, dtype=torch.bfloat16, device=DEV)
-            q = qw.c_struct()
-            for name, pk in (("packed", pack), ("row-major", None)):
-                args = (C.byref(q), qb._ptr(pk), qb._ptr(X), T, qb._ptr(Y), None, 0, qb._stream())
-                s = timed(lambda: qb.lib().qblora_linear_decode(*args), iters=50)
+            for name in ("packed", "row-major"):
+                if name == "row-major" and (T not in (1, 16) or (d_out, d_in) not in SHAPES):
+                    continue
+                fns = []
+                for qi, pk, ci in sets:
+                    ai = (C.byref(ci), qb._ptr(pk if name == "packed" else None), qb._ptr(X), T, qb._ptr(Y), None, 0,
+                          qb._stream())
+                    fns.append(lambda ai=ai: qb.lib().qblora_linear_decode(*ai))
+                s = timed(fns[0], iters=50)
+                sc = timed_rotating(fns, iters=60, warm=12)
                 nbytes = d_out * d_in * (0.5 + 8 / 64) + 2 * T * (d_in + d_out)
                 emit(kernel="w4_decode", layout=name, shape=[d_out, d_in], T=T, us=round(s * 1e6, 1),
-                     GBps=round(nbytes / s / 1e9, 1), frac_hbm=round(nbytes / s / 1e9 / HBM_PEAK_GBS, 3))
-        del W, qw, pack
+                     GBps=round(nbytes / s / 1e9, 1), frac_hbm=round(nbytes / s / 1e9 / HBM_PEAK_GBS, 3),
+                     cold_us=round(sc * 1e6, 1), cold_sets=len(fns),
+                     cold_frac_hbm=round(nbytes / sc / 1e9 / HBM_PEAK_GBS, 3))
+        del sets, qw, pack
 
 
 def bench_midbatch():
     """16 < T <= 256 on the merged INT4 model (packed) and on a codebook base (row-major): time against the two
-    floors of the regime, the weight stream from HBM and the bf16 MFMA work."""
+    floors of the regime, the weight stream from HBM and the bf16 MFMA work.  `us` with one weight set (held by the
+    last-level cache between launches), `cold_us` rotating over sets so that the weights come from HBM."""
     cb = synth.codebook_nf4_style()
     for d_out, d_in in SHAPES:
-        W = torch.randn(d_out, d_in, device=DEV) * 0.02
         for base in ("int4 packed", "codebook row-major"):
-            if base == "int4 packed":
-                qw = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_MINMAX_INT4, tiled=False)
-                pack = qb.qblora_decode_pack(qw)
-            else:
-                qw = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_ABSMAX_CODEBOOK, cb, tiled=False)
-                pack = None
-            q = qw.c_struct()
+            sets = []
+            for _ in range(n_sets(d_out * d_in * 0.625)):
+                W = torch.randn(d_out, d_in, device=DEV) * 0.02
+                if base == "int4 packed":
+                    qw = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_MINMAX_INT4, tiled=False)
+                    sets.append((qw, qb.qblora_decode_pack(qw), qw.c_struct()))
+                else:
+                    qw = qb.qblora_quantize_blockwise(W, 64, qb.QUANT_ABSMAX_CODEBOOK, cb, tiled=False)
+                    sets.append((qw, None, qw.c_struct()))
+                del W
+            qw, q = sets[0][0], sets[0][2]
             for T in (32, 64, 128, 256):
                 X = torch.randn(T, d_in, device=DEV).to(torch.bfloat16)
                 Y = torch.empty(T, d_out, dtype=torch.bfloat16, device=DEV)
                 need = int(qb.lib().qblora_linear_decode_tokens_workspace_bytes(C.byref(q), T))
                 ws = torch.empty(max(need, 256), dtype=torch.uint8, device=DEV)
-                args = (C.byref(q), qb._ptr(pack), qb._ptr(X), T, qb._ptr(Y), qb._ptr(ws), ws.numel(), qb._stream())
-                s = timed(lambda: qb.lib().qblora_linear_decode(*args), iters=30)
+                fns = []
+                for qi, pk, ci in sets:
+                    ai = (C.byref(ci), qb._ptr(pk), qb._ptr(X), T, qb._ptr(Y), qb._ptr(ws), ws.numel(), qb._stream())
+                    fns.append(lambda ai=ai: qb.lib().qblora_linear_decode(*ai))
+                s = timed(fns[0], iters=30)
+                sc = timed_rotating(fns, iters=36, warm=len(fns))
                 nbytes = d_out * d_in * (0.5 + (8 if qw.beta is not None else 4) / 64) + 2 * T * (d_in + d_out)
                 flops = 2.0 * T * d_in * d_out
                 emit(kernel="w4_mid", base=base, shape=[d_out, d_in], T=T, us=round(s * 1e6, 1),
                      GBps=round(nbytes / s / 1e9, 1), frac_hbm=round(nbytes / s / 1e9 / HBM_PEAK_GBS, 3),
+                     cold_us=round(sc * 1e6, 1), cold_sets=len(fns),
+                     cold_frac_hbm=round(nbytes / sc / 1e9 / HBM_PEAK_GBS, 3),
                      TFLOPs=round(flops / s / 1e12, 1), frac_mfma=round(flops / s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 3),
                      partial_bytes=need)
-            del qw, pack
-        del W
+            del sets, qw
 
 
 def bench_qablora():
@@ -638,19 +671,22 @@ def bench_tile8():
     emit(kernel="merge_beta_shift 8x8 blocks (codes + alpha copied)", shape=[d_out, d_in], us=round(s * 1e6, 1),
          GBps=round(nbytes / s / 1e9, 1), frac_hbm=round(nbytes / s / 1e9 / HBM_PEAK_GBS, 3))
     for d_out2, d_in2 in ((4096, 4096), (22016, 8192)):
-        W2 = torch.randn(d_out2, d_in2, device=DEV) * 0.02
-        q2 = qb.qblora_quantize_blockwise(W2, 64, qb.QUANT_MINMAX_INT4, block_rows=8, tiled=False)
-        pack = qb.qblora_decode_pack(q2)
-        for Tn in (1, 16):
+        sets = _decode_sets(d_out2, d_in2, block_rows=8)
+        for Tn in (1, 4, 16):
             Xs = torch.randn(Tn, d_in2, device=DEV).to(torch.bfloat16)
             Ys = torch.empty(Tn, d_out2, dtype=torch.bfloat16, device=DEV)
-            qs = q2.c_struct()
-            dargs = (C.byref(qs), qb._ptr(pack), qb._ptr(Xs), Tn, qb._ptr(Ys), None, 0, qb._stream())
-            s = timed(lambda: qb.lib().qblora_linear_decode(*dargs), iters=50)
+            fns = []
+            for qi, pk, ci in sets:
+                ai = (C.byref(ci), qb._ptr(pk), qb._ptr(Xs), Tn, qb._ptr(Ys), None, 0, qb._stream())
+                fns.append(lambda ai=ai: qb.lib().qblora_linear_decode(*ai))
+            s = timed(fns[0], iters=50)
+            sc = timed_rotating(fns, iters=60, warm=12)
             nbytes = d_out2 * d_in2 * (0.5 + 8 / 64) + 2 * Tn * (d_in2 + d_out2)
             emit(kernel="w4_decode 8x8 blocks", layout="packed", shape=[d_out2, d_in2], T=Tn, us=round(s * 1e6, 1),
-                 GBps=round(nbytes / s / 1e9, 1), frac_hbm=round(nbytes / s / 1e9 / HBM_PEAK_GBS, 3))
-        del W2, q2, pack
+                 GBps=round(nbytes / s / 1e9, 1), frac_hbm=round(nbytes / s / 1e9 / HBM_PEAK_GBS, 3),
+                 cold_us=round(sc * 1e6, 1), cold_sets=len(fns),
+                 cold_frac_hbm=round(nbytes / sc / 1e9 / HBM_PEAK_GBS, 3))
+        del sets
 
 
 def side_measurements(which):

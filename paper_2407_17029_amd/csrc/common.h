@@ -35,15 +35,17 @@ __device__ __forceinline__ float e4m3_to_float(uint32_t c) {
     return (c & 0x80) ? -v : v;
 }
 
-// Byte `idx` (0 .. 3, a constant after unrolling) of v as a float: one v_cvt_f32_ubyteN.  Written as the instruction:
-// from a shift and a mask the compiler makes a bit-field extract and a conversion.
-__device__ __forceinline__ float byte_to_float(uint32_t v, int idx) {
-    float r;
-    if (idx == 0) asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(r) : "v"(v));
-    else if (idx == 1) asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(r) : "v"(v));
-    else if (idx == 2) asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(r) : "v"(v));
-    else asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(r) : "v"(v));
-    return r;
+// Byte `idx` (0 .. 3, a constant after unrolling) of v as a float: one v_cvt_f32_ubyteN, provided the compiler knows
+// nothing about v's bits (see opaque_bits): from a shift and a mask of a value whose upper nibbles it knows to be zero
+// it makes a bit-field extract and a conversion.
+__device__ __forceinline__ float byte_to_float(uint32_t v, int idx) { return (float)((v >> (8 * idx)) & 0xffu); }
+
+// The same value in a register the compiler cannot see through (no instruction).  Used instead of writing vector
+// instructions as inline assembly: the compiler's hazard handling around MFMAs does not look inside assembly
+// statements (an assembly instruction that reuses a register of an MFMA result still in flight is overwritten by it).
+__device__ __forceinline__ uint32_t opaque_bits(uint32_t v) {
+    asm volatile("" : "+v"(v));
+    return v;
 }
 
 // Reconstructed block scale under the grouped E4M3 second-level quantization.

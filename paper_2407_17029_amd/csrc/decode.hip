@@ -9,8 +9,9 @@
 // are constant inside a 64-block, so they are applied to the block's partial sums, not to the weights,
 // and a code byte becomes two bf16 operand values with one LDS read.
 //
-// A workgroup of 4 waves owns 16 output rows; the waves split the input dimension (wave w takes the
-// groups of 4 consecutive blocks j = w, w+4, ...) and add their partial tiles through LDS at the end.
+// A workgroup of 4 waves (8 on layers with few rows) owns 16 output rows (32 or 64 on tall layers); the waves split
+// the input dimension (wave w takes the groups of 4 or 2 consecutive blocks j = w, w+4, ...) and add their partial
+// tiles through LDS at the end.
 // Inside a wave, lane l works on row (l & 15): for block b it loads 8 of the block's 32 code bytes
 // (quarter l >> 4), turns them into the B operand of two v_mfma_f32_16x16x32_bf16 whose A operand is the
 // matching 8 activations of token (l & 15) (zero for tokens >= T): the two MFMAs give the lane the
@@ -32,6 +33,7 @@
 // sum of activations, which the offset term computes anyway:
 // alpha * sum x (128 + c) + (beta - 128 alpha) * sum x.
 #include "common.h"
+#include <type_traits>
 
 namespace qblora {
 
@@ -71,40 +73,50 @@ struct DecodeRegs {                         // one group = G consecutive blocks 
 // the bytes of the codes through the vector memory path (every lane fetches its own copy of the 16 activations
 // it shares with 15 others), and that path, not HBM, set the time.
 constexpr int kXAllBytes = 40 * 1024;
+constexpr int kXAllBytesFew = 59 * 1024;     // with the 4 KB of static LDS inside the 64 KB a launch may ask for without more ado
+constexpr int kBufferWord3 = 0x00020000;    // buffer descriptor, last word: untyped 32-bit data, no swizzle, no stride
 constexpr int kStagedPairMinTokens = 4;    // see launch_w4_decode
 constexpr int kStagedPairMinTokens8 = 2;   // the same for 8 x 8 blocks
-template <bool BETA, int BR, bool DIRECT, int XMODE, int G = 4, int R = 1>
+template <bool BETA, int BR, bool DIRECT, int XMODE, int G = 4, int R = 1, int NE = 4, int NW = 4>
 __device__ __forceinline__ void w4_decode(const DecodeDesc& d);
 
-template <bool BETA, int BR, bool DIRECT = false, int XMODE = 0, int G = 4, int R = 1>
-__global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) { w4_decode<BETA, BR, DIRECT, XMODE, G, R>(d); }
+template <bool BETA, int BR, bool DIRECT = false, int XMODE = 0, int G = 4, int R = 1, int NE = 4>
+__global__ __launch_bounds__(256) void k_w4_decode(DecodeDesc d) { w4_decode<BETA, BR, DIRECT, XMODE, G, R, NE>(d); }
 
 // G: blocks per register set.  Four keep the most bytes in flight per wave and use 108 registers (four waves per
 // SIMD, 1024 workgroups resident); two use 76, six waves per SIMD, so that the 1376 workgroups of a 22016-row layer
 // are resident at once (25.2 against 26.0 us; limiting the four-block form to 84 registers instead spills 24 of
 // them and nearly doubles the time).  Layers that fit the 1024 slots are faster with four (4096 rows: 5.4 against 6.0).
-template <bool BETA, bool DIRECT, int G, int BR = 1, int R = 1>
-__global__ __launch_bounds__(256) void k_w4_decode_xall(DecodeDesc d) {
-    w4_decode<BETA, BR, DIRECT, 2, G, R>(d);
+// NE: tokens per lane that are kept (a lane holds tokens 4 * (lane / 16) .. + 3 of its row): with one or two tokens
+// the scale-and-offset FMAs of the others are left out (8 -> 2 or 4 per block and row group).
+// NW: waves per workgroup.  Layers with at most two workgroups of four waves per CU (8192 rows and fewer) have too few
+// waves to keep enough loads in flight; eight waves split the input dimension finer instead.
+template <bool BETA, bool DIRECT, int G, int BR = 1, int R = 1, int NE = 4, int NW = 4>
+__global__ __launch_bounds__(NW * 64) void k_w4_decode_xall(DecodeDesc d) {
+    w4_decode<BETA, BR, DIRECT, 2, G, R, NE, NW>(d);
 }
 
 // R: row groups of 16 per workgroup.  With two, the activation operands (which every workgroup fetches for its own
 // rows: at 16 tokens four times the bytes of the codes) serve 32 rows, and so do the block sums of the activations.
-template <bool BETA, int BR, bool DIRECT, int XMODE, int G, int R>
+template <bool BETA, int BR, bool DIRECT, int XMODE, int G, int R, int NE, int NW>
 __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
+    static_assert(NW == 4 || DIRECT, "the table is filled by 256 threads");
     constexpr bool XLDS = XMODE == 1, XALL = XMODE == 2;
     static_assert(!DIRECT || BR == 8 || BETA, "the table-free form of 64-blocks needs offsets");
     extern __shared__ __align__(16) unsigned char x_all[];       // XALL: [T][d_in * 2 + 16] bytes
     // entry e of replica q at e*kReplicas + q: bf16 pairs (4 bytes), or fp32 pairs (8 bytes) for BR = 8
     __shared__ __align__(8) uint32_t pair[DIRECT ? 2 : 256 * kReplicas * (BR == 8 ? 2 : 1)];
-    __shared__ float red[4][4][64];
+    __shared__ float red[NW][4][64];
     // Activations of one group of 4 blocks (16 tokens x 512 bytes), one region per wave: fetched as whole
     // 512-byte row segments (two token rows per load instruction) and read back in operand order.  A row is
     // 528 bytes so that the 16 tokens of an operand read start 16 bytes apart modulo 256.
     constexpr int kXPitch = G * 128 + 16;
     constexpr int kLPR = 8 * G, kTPL = 64 / kLPR, kNX = 16 / kTPL;    // lanes per staged token row, token rows per load, loads
-    __shared__ __align__(16) unsigned char xs_all[XLDS ? 4 : 1][XLDS ? 16 * kXPitch : 16];
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    __shared__ __align__(16) unsigned char xs_all[XLDS ? NW : 1][XLDS ? 16 * kXPitch : 16];
+    const int t = threadIdx.x, lane = t & 63;
+    // the wave id as a scalar: block indices, the redirects of blocks past the end and the block part of every address
+    // are then scalar arithmetic, and the loads take a scalar base with a 32-bit lane offset
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int nl = lane & 15, kg = lane >> 4;
     // Row groups 2i and 2i+1 share the 128-byte lines of the tile-ordered scales and offsets (16 rows = 64
     // bytes per block): they are given workgroup ids x and x + 8 of a run of 16 ids, which are dispatched to
@@ -137,17 +149,26 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     // (the layout of the forward kernel's code copy) the 16 rows of a block are adjacent: 4 lines of codes
     // and one of scales per load, which is what keeps the address path from being the bottleneck.
     const int bstep = d.tiled ? 256 : 1;                                                            // next block
-    const uint8_t* crow[R]; const float* srow[R]; const float* brow[R];
-    int64_t run8[R];                        // BR = 8: block row n/8, block columns 8*b + 2*kg, +1 of 64-input step b
+    // the lane's part of every address, in bytes (the launcher has checked that the arrays are below 4 GB)
+    uint32_t coff[R], soff[R];
+    uint32_t off8[R];                       // BR = 8: block row n/8, block columns 8*b + 2*kg, +1 of 64-input step b
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
-        const int64_t run = d.tiled ? ((int64_t)(n[rr] >> 8) * bpr * 256 + (n[rr] & 255)) : (int64_t)n[rr] * bpr;   // block 0 of the row
-        crow[rr] = d.codes + run * 32 + 8 * kg;
-        srow[rr] = d.scales + run;
-        brow[rr] = BETA ? d.beta + run : nullptr;
-        run8[rr] = (int64_t)(n[rr] >> 3) * (d.d_in >> 3) + 2 * kg;
+        const uint32_t run = d.tiled ? ((uint32_t)(n[rr] >> 8) * bpr * 256 + (n[rr] & 255)) : (uint32_t)n[rr] * bpr;   // block 0 of the row
+        coff[rr] = run * 32 + 8 * kg;
+        soff[rr] = run * 4;
+        off8[rr] = ((uint32_t)(n[rr] >> 3) * (d.d_in >> 3) + 2 * kg) * 4;
     }
     const int cstep = bstep * 32;
+    // Codes, scales and offsets come through buffer loads: scalar base (the descriptor), scalar block offset and the
+    // lane's constant 32-bit offset, so that no load needs vector address arithmetic (as global loads every one cost
+    // a 64-bit vector add, a quarter of the loop's vector instructions).  num_records = the array's size: an offset
+    // past it would read zero instead of faulting.
+    const uint32_t rows_held = d.tiled ? (uint32_t)((d.d_out + 255) & ~255) : (uint32_t)d.d_out;
+    const uint32_t param_bytes = BR == 8 ? (uint32_t)((d.d_out + 7) >> 3) * (d.d_in >> 3) * 4 : rows_held * bpr * 4;
+    const auto rsrc_c = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(d.codes), 0, rows_held * bpr * 32, kBufferWord3);
+    const auto rsrc_s = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(d.scales), 0, param_bytes, kBufferWord3);
+    const auto rsrc_b = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(BETA ? d.beta : d.scales), 0, param_bytes, kBufferWord3);
     unsigned char* xs = xs_all[XLDS ? wave : 0];
     const int xtok = lane / kLPR, xchunk = lane % kLPR;
     const qblora_bf16* xrow = d.X + (int64_t)min(nl, d.T - 1) * d.d_in + 16 * kg;
@@ -157,28 +178,31 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     // Every load is unconditional: a block past the end of the row is redirected to the last block and
     // given scale = offset = 0; lanes whose token does not exist read the last token's row and produce
     // output rows that are never stored.
-    auto load = [&](DecodeRegs<G, R>& r, int j) __attribute__((always_inline)) {
+    // (a group that lies wholly inside the row -- every group of a layer whose input size is a multiple of 64 G --
+    // takes a copy of the code without the redirects and selects: FULL)
+    auto load_as = [&](DecodeRegs<G, R>& r, int j, auto full) __attribute__((always_inline)) {
+        constexpr bool FULL = decltype(full)::value;
 #pragma unroll
         for (int q = 0; q < G; ++q) {
             const int b = G * j + q;
-            const bool in = b < bpr;
+            const bool in = FULL || b < bpr;
             const int bc = in ? b : bpr - 1;
 #pragma unroll
             for (int rr = 0; rr < R; ++rr) {
-                r.c[q][rr] = *reinterpret_cast<const uint2*>(crow[rr] + (int64_t)bc * cstep);
+                r.c[q][rr] = __builtin_bit_cast(uint2, __builtin_amdgcn_raw_buffer_load_b64(rsrc_c, coff[rr], bc * cstep, 0));
                 if constexpr (BR == 8) {
-                    const float2 a = *reinterpret_cast<const float2*>(d.scales + run8[rr] + 8 * bc);
+                    const float2 a = __builtin_bit_cast(float2, __builtin_amdgcn_raw_buffer_load_b64(rsrc_s, off8[rr], 32 * bc, 0));
                     r.a2[q][rr] = in ? a : make_float2(0.0f, 0.0f);
                     r.b2[q][rr] = make_float2(0.0f, 0.0f);
                     if constexpr (BETA) {
-                        const float2 bt = *reinterpret_cast<const float2*>(d.beta + run8[rr] + 8 * bc);
+                        const float2 bt = __builtin_bit_cast(float2, __builtin_amdgcn_raw_buffer_load_b64(rsrc_b, off8[rr], 32 * bc, 0));
                         if (in) r.b2[q][rr] = bt;
                     }
                 } else {
-                    const float a = srow[rr][(int64_t)bc * bstep];
+                    const float a = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc_s, soff[rr], bc * bstep * 4, 0));
                     r.a[q][rr] = in ? a : 0.0f;
                     if constexpr (BETA) {
-                        const float bt = brow[rr][(int64_t)bc * bstep];
+                        const float bt = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc_b, soff[rr], bc * bstep * 4, 0));
                         r.b[q][rr] = in ? bt : 0.0f;
                         if constexpr (DIRECT) r.b[q][rr] = __builtin_fmaf(-128.0f, r.a[q][rr], r.b[q][rr]);
                     } else {
@@ -201,9 +225,17 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
         for (int p = 0; p < kNX; ++p) {
             if (kTPL * p < d.T) {
                 const int tk = min(kTPL * p + xtok, d.T - 1);
-                const int bc = min(G * j + (xchunk >> 3), bpr - 1);
+                const int bc = FULL ? G * j + (xchunk >> 3) : min(G * j + (xchunk >> 3), bpr - 1);
                 r.xg[p] = *reinterpret_cast<const uint4*>(d.X + (int64_t)tk * d.d_in + bc * kBlock + 8 * (xchunk & 7));
             }
+        }
+    };
+    auto load = [&](DecodeRegs<G, R>& r, int j) __attribute__((always_inline)) {
+        if constexpr (XLDS) {              // (two copies cost the staged form ten registers and with them a wave per SIMD)
+            load_as(r, j, std::false_type{});
+        } else {
+            if (G * j + G <= bpr) load_as(r, j, std::true_type{});
+            else load_as(r, j, std::false_type{});
         }
     };
 
@@ -213,10 +245,15 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     for (int rr = 0; rr < R; ++rr) acc[rr] = zero;
     const uint4 ones4 = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
     const bf16x8 ones = __builtin_bit_cast(bf16x8, ones4);
+    // The two constants of the table-free operand sit in registers the compiler cannot see through: with literals it
+    // emits an AND and an OR per operand dword (the three-operand AND-OR cannot encode two literals), with registers
+    // the one instruction.  (The instruction is left to the compiler rather than written as inline assembly, so that
+    // its hazard handling next to the MFMAs sees it.)
+    const uint32_t nib_mask = opaque_bits(0x000F000Fu), bf16_128 = opaque_bits(0x43004300u);
     auto operand = [&](uint32_t w) __attribute__((always_inline)) {
         if constexpr (DIRECT) {
-            const uint4 v = make_uint4((w & 0x000F000Fu) | 0x43004300u, ((w >> 4) & 0x000F000Fu) | 0x43004300u,
-                                       ((w >> 8) & 0x000F000Fu) | 0x43004300u, ((w >> 12) & 0x000F000Fu) | 0x43004300u);
+            const uint4 v = make_uint4((w & nib_mask) | bf16_128, ((w >> 4) & nib_mask) | bf16_128,
+                                       ((w >> 8) & nib_mask) | bf16_128, ((w >> 12) & nib_mask) | bf16_128);
             return __builtin_bit_cast(bf16x8, v);
         }
         const uint4 v = make_uint4(my_pair[(w & 0xffu) * kReplicas], my_pair[((w >> 8) & 0xffu) * kReplicas],
@@ -231,9 +268,9 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     // codes cost HBM time)
     auto fetch8 = [&](uint32_t w, float2 (&cv)[4]) __attribute__((always_inline)) {
         if constexpr (DIRECT) {
-            // one byte-to-float conversion per code on the two masked dwords (written as the instruction: from shifts
-            // and masks the compiler makes a bit-field extract and a conversion per code)
-            const uint32_t lo = w & 0x0F0F0F0Fu, hi = (w >> 4) & 0x0F0F0F0Fu;
+            // one byte-to-float conversion per code on the two masked dwords (whose known zero nibbles are hidden from
+            // the compiler: otherwise it makes a bit-field extract and a conversion per code)
+            const uint32_t lo = opaque_bits(w & 0x0F0F0F0Fu), hi = opaque_bits((w >> 4) & 0x0F0F0F0Fu);
             cv[0] = make_float2(byte_to_float(lo, 0), byte_to_float(hi, 0));
             cv[1] = make_float2(byte_to_float(lo, 1), byte_to_float(hi, 1));
             cv[2] = make_float2(byte_to_float(lo, 2), byte_to_float(hi, 2));
@@ -301,10 +338,10 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
                 f32x4_t blk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x0, operand(r.c[q][rr].x), zero, 0, 0, 0);
                 blk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x1, operand(r.c[q][rr].y), blk, 0, 0, 0);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) acc[rr][e] = __builtin_fmaf(r.a[q][rr], blk[e], acc[rr][e]);
+                for (int e = 0; e < NE; ++e) acc[rr][e] = __builtin_fmaf(r.a[q][rr], blk[e], acc[rr][e]);
                 if constexpr (BETA) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[rr][e] = __builtin_fmaf(r.b[q][rr], sx[e], acc[rr][e]);
+                    for (int e = 0; e < NE; ++e) acc[rr][e] = __builtin_fmaf(r.b[q][rr], sx[e], acc[rr][e]);
                 }
             }
         }
@@ -316,17 +353,17 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     if (j < groups) load(r0, j);
     if constexpr (XALL) {                                     // behind the first loads of codes: both are in flight together
         const int chunks = d.d_in / 8;                        // 16-byte pieces per token row
-        for (int i0 = t; i0 < d.T * chunks; i0 += 4 * 256) {
+        for (int i0 = t; i0 < d.T * chunks; i0 += 4 * NW * 64) {
             uint4 v[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int i = min(i0 + u * 256, d.T * chunks - 1);
+                const int i = min(i0 + u * NW * 64, d.T * chunks - 1);
                 const int tk = i / chunks, c = i - tk * chunks;
                 v[u] = *reinterpret_cast<const uint4*>(d.X + (int64_t)tk * d.d_in + c * 8);
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int i = i0 + u * 256;
+                const int i = i0 + u * NW * 64;
                 if (i >= d.T * chunks) break;
                 const int tk = i / chunks, c = i - tk * chunks;
                 *reinterpret_cast<uint4*>(x_all + tk * x_pitch + c * 16) = v[u];
@@ -334,16 +371,16 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
         }
         __syncthreads();
     }
-    for (; j < groups; j += 8) {
-        if (j + 4 < groups) load(r1, j + 4);
+    for (; j < groups; j += 2 * NW) {
+        if (j + NW < groups) load(r1, j + NW);
         compute(r0);
-        if (j + 4 < groups) {
-            if (j + 8 < groups) load(r0, j + 8);
+        if (j + NW < groups) {
+            if (j + 2 * NW < groups) load(r0, j + 2 * NW);
             compute(r1);
         }
     }
 
-    // The lane holds row nl, tokens 4*kg .. 4*kg+3.  Partial tiles of the four waves -> LDS; wave 0 adds
+    // The lane holds row nl, tokens 4*kg .. 4*kg+3.  Partial tiles of the waves -> LDS; wave 0 adds
     // them in wave order, lane l taking token l >> 2 and rows 4*(l & 3) .. +3 so that stores run along n.
     const int tok = lane >> 2, nq = 4 * (lane & 3);
 #pragma unroll
@@ -357,7 +394,10 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int src = (nq + i) + 16 * (tok >> 2), e = tok & 3;
-                v[i] = ((red[0][e][src] + red[1][e][src]) + red[2][e][src]) + red[3][e][src];
+                float sum = red[0][e][src];
+#pragma unroll
+                for (int w = 1; w < NW; ++w) sum += red[w][e][src];
+                v[i] = sum;
             }
             const int nb = n0 + 16 * rr + nq;
             qblora_bf16* yp = d.Y + (int64_t)tok * d.d_out + nb;
@@ -374,9 +414,9 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
 
 // the form with all of X in LDS (at most kXAllBytes of it: inside the default limit of dynamic LDS; a limit of 66 KB
 // measured slower wherever it applied -- 22016 x 8192 at four tokens 48 against 33 us, two workgroups per CU)
-template <bool BETA, bool DIRECT, int G, int BR = 1, int R = 1>
+template <bool BETA, bool DIRECT, int G, int BR = 1, int R = 1, int NE = 4, int NW = 4>
 int launch_xall(const DecodeDesc& d, dim3 grid, size_t x_all_bytes, hipStream_t st) {
-    hipLaunchKernelGGL((k_w4_decode_xall<BETA, DIRECT, G, BR, R>), grid, dim3(256), x_all_bytes, st, d);
+    hipLaunchKernelGGL((k_w4_decode_xall<BETA, DIRECT, G, BR, R, NE, NW>), grid, dim3(NW * 64), x_all_bytes, st, d);
     return launch_status();
 }
 
@@ -386,6 +426,8 @@ int launch_w4_decode(const uint8_t* codes, const float* scales, const float* bet
                      int d_out, int d_in, const qblora_bf16* X, int T, qblora_bf16* Y, hipStream_t st, int block_rows,
                      int regrouped) {
     DecodeDesc d{codes, scales, beta, cb, tiled, block_rows, d_out, d_in, X, T, Y};
+    // the kernels address codes, scales and offsets with 32-bit byte offsets
+    if (((int64_t)d_out + 255) / 256 * 256 * (int64_t)d_in / 2 >= (int64_t)1 << 31) return QBLORA_ERR_UNSUPPORTED;
     const dim3 grid((unsigned)(((d_out + 15) / 16 + 15) / 16 * 16));
     const bool xlds = T > 8;                    // activations through LDS: measured equal at 8 tokens, see the kernel's comment
     auto go = [&](auto plain, auto staged) -> int {
@@ -420,7 +462,11 @@ int launch_w4_decode(const uint8_t* codes, const float* scales, const float* bet
     // (8 x 8 blocks of an INT4 model: level at one token, 35.6 -> 29.8 us at two)
     if (block_rows == 8 && int4 && two_groups)
         return beta ? launch_xall<true, true, 2, 8, 2>(d, grid2, x_all_bytes, st) : launch_xall<false, true, 2, 8, 2>(d, grid2, x_all_bytes, st);
-    if (block_rows != 8 && regrouped && beta && tiled && two_groups) return launch_xall<true, true, 2, 1, 2>(d, grid2, x_all_bytes, st);
+    if (block_rows != 8 && regrouped && beta && tiled && two_groups) {
+        if (T == 1) return launch_xall<true, true, 2, 1, 2, 1>(d, grid2, x_all_bytes, st);
+        if (T == 2) return launch_xall<true, true, 2, 1, 2, 2>(d, grid2, x_all_bytes, st);
+        return launch_xall<true, true, 2, 1, 2>(d, grid2, x_all_bytes, st);
+    }
     // Four row groups (64 rows, a copy of up to 66 KB, two workgroups per CU) where the copy would not fit otherwise:
     // 22016 x 8192 at three / four tokens 30.4 -> 28.4 / 32.0 -> 29.6 us.  The kernel's limit of dynamic LDS is raised
     // once (the initialisation of a function-local static is thread safe).
@@ -435,10 +481,21 @@ int launch_w4_decode(const uint8_t* codes, const float* scales, const float* bet
             return launch_status();
         }
     }
-    if (block_rows != 8 && x_all_bytes <= (size_t)kXAllBytes && per_cu * (x_all_bytes + 5 * 1024) <= 150 * 1024 && d_in % 8 == 0) {
+    // (with at most two workgroups per CU a larger copy costs no residency: 8192 x 22016 at one token, 44 KB)
+    const size_t x_all_limit = per_cu <= 2 ? (size_t)kXAllBytesFew : (size_t)kXAllBytes;
+    if (block_rows != 8 && x_all_bytes <= x_all_limit && per_cu * (x_all_bytes + 5 * 1024) <= 150 * 1024 && d_in % 8 == 0) {
         const bool small_sets = grid.x > 1024;      // more workgroups than fit at four waves per SIMD
         if (regrouped) {
             if (!beta || !tiled) return QBLORA_ERR_UNSUPPORTED;
+            // at most two workgroups per CU: eight waves each (8192 x 8192 at one token 11.1 -> 10.0 us, from HBM 13.7 ->
+            // 11.9; 8192 x 22016: 24.2 -> 20.8 and 30.2 -> 24.7 us; with two-block sets 10.4 / 12.7 and 21.7 / 27.1)
+            if (per_cu <= 2) {
+                if (T == 1) return launch_xall<true, true, 4, 1, 1, 1, 8>(d, grid, x_all_bytes, st);
+                if (T == 2) return launch_xall<true, true, 4, 1, 1, 2, 8>(d, grid, x_all_bytes, st);
+                return launch_xall<true, true, 4, 1, 1, 4, 8>(d, grid, x_all_bytes, st);
+            }
+            if (T == 1) return small_sets ? launch_xall<true, true, 2, 1, 1, 1>(d, grid, x_all_bytes, st) : launch_xall<true, true, 4, 1, 1, 1>(d, grid, x_all_bytes, st);
+            if (T == 2) return small_sets ? launch_xall<true, true, 2, 1, 1, 2>(d, grid, x_all_bytes, st) : launch_xall<true, true, 4, 1, 1, 2>(d, grid, x_all_bytes, st);
             return small_sets ? launch_xall<true, true, 2>(d, grid, x_all_bytes, st) : launch_xall<true, true, 4>(d, grid, x_all_bytes, st);
         }
         if (beta) return small_sets ? launch_xall<true, false, 2>(d, grid, x_all_bytes, st) : launch_xall<true, false, 4>(d, grid, x_all_bytes, st);
@@ -484,7 +541,14 @@ int launch_w4_decode(const uint8_t* codes, const float* scales, const float* bet
         }
         // more workgroups than fit at three waves per SIMD (156 registers): two-block register sets (92 registers, five
         // waves; 22016 x 8192 at two tokens 29.9 -> 28.1 us)
-        if (!xlds && grid.x > 768) return go(k_w4_decode<true, 1, true, 0, 2>, k_w4_decode<true, 1, true, 1>);
+        if (!xlds && grid.x > 768) {
+            if (T == 1) return go(k_w4_decode<true, 1, true, 0, 2, 1, 1>, k_w4_decode<true, 1, true, 1>);
+            if (T == 2) return go(k_w4_decode<true, 1, true, 0, 2, 1, 2>, k_w4_decode<true, 1, true, 1>);
+            return go(k_w4_decode<true, 1, true, 0, 2>, k_w4_decode<true, 1, true, 1>);
+        }
+        // (eight waves per workgroup measured slower in these forms: 8192 x 8192 at four tokens 14.1 against 12.2 us)
+        if (T == 1) return go(k_w4_decode<true, 1, true, 0, 4, 1, 1>, k_w4_decode<true, 1, true, 1>);
+        if (T == 2) return go(k_w4_decode<true, 1, true, 0, 4, 1, 2>, k_w4_decode<true, 1, true, 1>);
         return go(k_w4_decode<true, 1, true, 0>, k_w4_decode<true, 1, true, 1>);
     }
     if (beta) return go(k_w4_decode<true, 1, false, 0>, k_w4_decode<true, 1, false, 1>);
