@@ -60,14 +60,21 @@ struct DecodeRegs {                         // one group = G consecutive blocks 
     float2 a2[G][R], b2[G][R];              // BR = 8: scales and offsets of the lane's two block columns
     int xb[G];                              // XALL: the (redirected) block whose activations go with c[q]
     uint4 x[G][2];                          // activations of the lane's token, 8 per MFMA (fetched in operand order)
-    uint4 xg[8];                            // XLDS: as fetched, 64 / (8 G) token rows per load, 16-byte chunk lane % (8 G) of the group
 };
 
-// XLDS (used above 8 tokens): the activations go through LDS.  In operand order a load instruction touches
-// 16 token rows, 64 bytes of each; with more than a few tokens these loads, not the codes, fill the address
-// path (T = 16: 55 us against 29 at T = 1).  Fetched as whole 512-byte row segments and re-read from LDS in
-// operand order they cost half the cache-line accesses (44 us); for few tokens the extra LDS round trip is the
-// slower way (T = 1: 35 us; the two meet at 8 tokens), hence the switch.
+// XLDS: the activations of a group as fetched.  (A native vector type: with HIP's uint4, a struct that is copied as
+// memory, the compiler kept these registers in scratch memory -- a store, a wait for it and a load per group.)
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+template <int N>
+struct StagedRegs { u32x4_t v[N]; };
+
+// XLDS: the activations go through LDS.  In operand order a load instruction touches 16 token rows, 64 bytes of
+// each; with more than a few tokens these loads, not the codes, fill the address path (T = 16: 55 us against 29 at
+// T = 1).  Fetched as whole row segments (512 bytes with four-block sets, 256 with two-block sets) and re-read from
+// the wave's own LDS region in operand order they cost half the cache-line accesses.  With two-block sets the region
+// holds two buffers and the staging runs one group ahead of the MFMAs (see the loop); as first written -- the group's
+// activations held in scratch memory by the compiler and written to LDS right before they were read -- this form
+// only paid above 8 tokens (T = 16: 44 us); now it is the form of the table-free kernels from two tokens on.
 // XMODE 2 (few tokens, rows short enough: at most kXAllBytes of activations): the workgroup copies all of X into
 // LDS once, and the loop has no activation loads at all.  With one token the operand-order loads above move 16 x
 // the bytes of the codes through the vector memory path (every lane fetches its own copy of the 16 activations
@@ -75,8 +82,6 @@ struct DecodeRegs {                         // one group = G consecutive blocks 
 constexpr int kXAllBytes = 40 * 1024;
 constexpr int kXAllBytesFew = 59 * 1024;     // with the 4 KB of static LDS inside the 64 KB a launch may ask for without more ado
 constexpr int kBufferWord3 = 0x00020000;    // buffer descriptor, last word: untyped 32-bit data, no swizzle, no stride
-constexpr int kStagedPairMinTokens = 4;    // see launch_w4_decode
-constexpr int kStagedPairMinTokens8 = 2;   // the same for 8 x 8 blocks
 template <bool BETA, int BR, bool DIRECT, int XMODE, int G = 4, int R = 1, int NE = 4, int NW = 4>
 __device__ __forceinline__ void w4_decode(const DecodeDesc& d);
 
@@ -112,7 +117,8 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     // 528 bytes so that the 16 tokens of an operand read start 16 bytes apart modulo 256.
     constexpr int kXPitch = G * 128 + 16;
     constexpr int kLPR = 8 * G, kTPL = 64 / kLPR, kNX = 16 / kTPL;    // lanes per staged token row, token rows per load, loads
-    __shared__ __align__(16) unsigned char xs_all[XLDS ? NW : 1][XLDS ? 16 * kXPitch : 16];
+    constexpr int kXBufs = G <= 2 ? 2 : 1;                     // LDS buffers per wave (two: 35 KB per workgroup at G = 2)
+    __shared__ __align__(16) unsigned char xs_all[XLDS ? NW : 1][XLDS ? kXBufs * 16 * kXPitch : 16];
     const int t = threadIdx.x, lane = t & 63;
     // the wave id as a scalar: block indices, the redirects of blocks past the end and the block part of every address
     // are then scalar arithmetic, and the loads take a scalar base with a 32-bit lane offset
@@ -217,18 +223,27 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
                 for (int m = 0; m < 2; ++m) r.x[q][m] = *reinterpret_cast<const uint4*>(xrow + bc * kBlock + 8 * m);
             }
         }
-        if constexpr (!XLDS) return;
-        // Token rows that do not exist are not fetched (their LDS rows keep old contents and feed output rows
-        // that are never stored); chunks of blocks past the end of the row are redirected to the last block,
-        // whose scale and offset are zero there.
+    };
+    using XRegs = StagedRegs<kNX>;
+    // XLDS: the activations of group j as fetched, 64 / (8 G) token rows per load, 16-byte chunk lane % (8 G) of the
+    // group.  Token rows that do not exist are not fetched (their LDS rows keep old contents and feed output rows
+    // that are never stored); chunks of blocks past the end of the row are redirected to the last block, whose
+    // scale and offset are zero there.
+    auto load_x = [&](XRegs& x, int j) __attribute__((always_inline)) {
 #pragma unroll
         for (int p = 0; p < kNX; ++p) {
             if (kTPL * p < d.T) {
                 const int tk = min(kTPL * p + xtok, d.T - 1);
-                const int bc = FULL ? G * j + (xchunk >> 3) : min(G * j + (xchunk >> 3), bpr - 1);
-                r.xg[p] = *reinterpret_cast<const uint4*>(d.X + (int64_t)tk * d.d_in + bc * kBlock + 8 * (xchunk & 7));
+                const int bc = min(G * j + (xchunk >> 3), bpr - 1);
+                x.v[p] = *reinterpret_cast<const u32x4_t*>(d.X + (int64_t)tk * d.d_in + bc * kBlock + 8 * (xchunk & 7));
             }
         }
+    };
+    // ... and into the wave's LDS buffer `buf`
+    auto stage = [&](const XRegs& x, int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int p = 0; p < kNX; ++p)
+            if (kTPL * p < d.T) *reinterpret_cast<u32x4_t*>(xs + buf * (16 * kXPitch) + (kTPL * p + xtok) * kXPitch + xchunk * 16) = x.v[p];
     };
     auto load = [&](DecodeRegs<G, R>& r, int j) __attribute__((always_inline)) {
         if constexpr (XLDS) {              // (two copies cost the staged form ten registers and with them a wave per SIMD)
@@ -287,7 +302,7 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
             o[i] = BETA ? pack_bf16(__fmaf_rn(cv[i].x, a, b), __fmaf_rn(cv[i].y, a, b)) : pack_bf16(__fmul_rn(cv[i].x, a), __fmul_rn(cv[i].y, a));
         return __builtin_bit_cast(bf16x8, make_uint4(o[0], o[1], o[2], o[3]));
     };
-    auto compute8 = [&](const DecodeRegs<G, R>& r) __attribute__((always_inline)) {
+    auto compute8 = [&](const DecodeRegs<G, R>& r, const unsigned char* xsb) __attribute__((always_inline)) {
         float2 cv[2][4];
         auto dword = [&](int v) __attribute__((always_inline)) {      // operand v = (block, code dword, row group)
             const int u = v / R, rr = v % R;
@@ -301,7 +316,7 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
             if (v + 1 < 2 * G * R) fetch8(dword(v + 1 < 2 * G * R ? v + 1 : v), cv[(v + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
             if (rr == 0) {
-                if constexpr (XLDS) x = *reinterpret_cast<const bf16x8*>(xs + nl * kXPitch + 128 * q + 32 * kg + 16 * (u & 1));
+                if constexpr (XLDS) x = *reinterpret_cast<const bf16x8*>(xsb + nl * kXPitch + 128 * q + 32 * kg + 16 * (u & 1));
                 else if constexpr (XALL) x = *reinterpret_cast<const bf16x8*>(x_mine + r.xb[q] * (kBlock * 2) + 16 * (u & 1));
                 else x = __builtin_bit_cast(bf16x8, r.x[q][u & 1]);
             }
@@ -309,18 +324,15 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
             acc[rr] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, wv, acc[rr], 0, 0, 0);
         }
     };
-    auto compute = [&](const DecodeRegs<G, R>& r) __attribute__((always_inline)) {
-        if constexpr (XLDS) {
-#pragma unroll
-            for (int p = 0; p < kNX; ++p)
-                if (kTPL * p < d.T) *reinterpret_cast<uint4*>(xs + (kTPL * p + xtok) * kXPitch + xchunk * 16) = r.xg[p];
-        }
-        if constexpr (BR == 8) { compute8(r); return; }
+    // (buf: the wave's LDS buffer that holds the group's activations, XLDS only)
+    auto compute = [&](const DecodeRegs<G, R>& r, int buf = 0) __attribute__((always_inline)) {
+        const unsigned char* xsb = xs + buf * (16 * kXPitch);
+        if constexpr (BR == 8) { compute8(r, xsb); return; }
 #pragma unroll
         for (int q = 0; q < G; ++q) {
             bf16x8 x0, x1;
             if constexpr (XLDS) {
-                const unsigned char* xq = xs + nl * kXPitch + 128 * q + 32 * kg;    // k = 64q + 16kg .. +15 of token nl
+                const unsigned char* xq = xsb + nl * kXPitch + 128 * q + 32 * kg;    // k = 64q + 16kg .. +15 of token nl
                 x0 = *reinterpret_cast<const bf16x8*>(xq); x1 = *reinterpret_cast<const bf16x8*>(xq + 16);
             } else if constexpr (XALL) {
                 const unsigned char* xq = x_mine + r.xb[q] * (kBlock * 2);
@@ -371,12 +383,52 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
         }
         __syncthreads();
     }
-    for (; j < groups; j += 2 * NW) {
-        if (j + NW < groups) load(r1, j + NW);
-        compute(r0);
-        if (j + NW < groups) {
-            if (j + 2 * NW < groups) load(r0, j + 2 * NW);
-            compute(r1);
+    if constexpr (XLDS && kXBufs == 2) {
+        // Two LDS buffers per wave: while group g is contracted out of one, the activations of group g + 1 (fetched
+        // during the contraction of group g - 1) are written into the other and those of group g + 2 set out -- the
+        // write -> read -> MFMA round trip of a group is then not waited for in front of its MFMAs.
+        XRegs xq;
+        if (j < groups) { load_x(xq, j); stage(xq, 0); }       // (the codes of group j are already on their way)
+        if (j + NW < groups) load_x(xq, j + NW);
+        for (; j < groups; j += 2 * NW) {
+            if (j + NW < groups) {
+                load(r1, j + NW);
+                stage(xq, 1);
+                if (j + 2 * NW < groups) load_x(xq, j + 2 * NW);
+            }
+            compute(r0, 0);
+            if (j + NW < groups) {
+                if (j + 2 * NW < groups) {
+                    load(r0, j + 2 * NW);
+                    stage(xq, 0);
+                    if (j + 3 * NW < groups) load_x(xq, j + 3 * NW);
+                }
+                compute(r1, 1);
+            }
+        }
+    } else if constexpr (XLDS) {                               // one buffer: written just before it is read
+        XRegs xq;
+        if (j < groups) load_x(xq, j);
+        for (; j < groups; j += 2 * NW) {
+            if (j + NW < groups) load(r1, j + NW);
+            stage(xq, 0);
+            if (j + NW < groups) load_x(xq, j + NW);
+            compute(r0, 0);
+            if (j + NW < groups) {
+                if (j + 2 * NW < groups) load(r0, j + 2 * NW);
+                stage(xq, 0);
+                if (j + 2 * NW < groups) load_x(xq, j + 2 * NW);
+                compute(r1, 0);
+            }
+        }
+    } else {
+        for (; j < groups; j += 2 * NW) {
+            if (j + NW < groups) load(r1, j + NW);
+            compute(r0);
+            if (j + NW < groups) {
+                if (j + 2 * NW < groups) load(r0, j + 2 * NW);
+                compute(r1);
+            }
         }
     }
 
@@ -428,131 +480,90 @@ int launch_w4_decode(const uint8_t* codes, const float* scales, const float* bet
     DecodeDesc d{codes, scales, beta, cb, tiled, block_rows, d_out, d_in, X, T, Y};
     // the kernels address codes, scales and offsets with 32-bit byte offsets
     if (((int64_t)d_out + 255) / 256 * 256 * (int64_t)d_in / 2 >= (int64_t)1 << 31) return QBLORA_ERR_UNSUPPORTED;
-    const dim3 grid((unsigned)(((d_out + 15) / 16 + 15) / 16 * 16));
-    const bool xlds = T > 8;                    // activations through LDS: measured equal at 8 tokens, see the kernel's comment
-    auto go = [&](auto plain, auto staged) -> int {
-        if (xlds) hipLaunchKernelGGL(staged, grid, dim3(256), 0, st, d);
-        else hipLaunchKernelGGL(plain, grid, dim3(256), 0, st, d);
+    if (regrouped && (!beta || !tiled || block_rows == 8)) return QBLORA_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)(((d_out + 15) / 16 + 15) / 16 * 16));       // 16 rows per workgroup
+    const dim3 grid2((unsigned)(((d_out + 31) / 32 + 15) / 16 * 16));      // 32 rows (two row groups)
+    const size_t per_cu = (grid.x + 255) / 256, per_cu2 = (grid2.x + 255) / 256;
+    const bool tall = grid2.x > 512;            // more than 16384 rows: the forms with two row groups pay
+    auto launch = [&](auto kernel, dim3 g) -> int {
+        hipLaunchKernelGGL(kernel, g, dim3(256), 0, st, d);
         return launch_status();
     };
-    const size_t x_all_bytes = (size_t)T * ((size_t)d_in * 2 + 16);
-    // all of X in LDS: when it is small enough, and when the workgroups of the launch still fit the CUs together with
+    // All of X in LDS: when it is small enough, and when the workgroups of the launch still fit the CUs together with
     // their copies (160 KB of LDS per CU; 22016 x 8192 at two tokens: 31.3 us with six 36 KB workgroups wanted per CU,
-    // 29.9 without the copy)
-    const size_t per_cu = (grid.x + 255) / 256;
-    bool int4 = true;                       // codes are their own values: no table
+    // 29.9 without the copy).  With at most two workgroups per CU a larger copy costs no residency (8192 x 22016 at
+    // one token, 44 KB).
+    const size_t x_all_bytes = (size_t)T * ((size_t)d_in * 2 + 16);
+    auto x_all_fits = [&](size_t workgroups_per_cu, size_t limit) {
+        return d_in % 8 == 0 && x_all_bytes <= limit && workgroups_per_cu * (x_all_bytes + 5 * 1024) <= 150 * 1024;
+    };
+    bool int4 = true;                           // codes are their own values: no table
     for (int j = 0; j < 16; ++j) int4 = int4 && cb.c[j] == (float)j;
-    // 8 x 8 blocks of an INT4 model, few tokens: no table, all of X in LDS (22016 x 8192 at one token: 35.8 -> 28.2 us;
-    // with at most two workgroups per CU the copy costs more than it saves: 4096 rows 6.3 against 5.9 us)
-    if (block_rows == 8 && int4 && grid.x > 512 && x_all_bytes <= (size_t)kXAllBytes &&
-        per_cu * (x_all_bytes + 5 * 1024) <= 150 * 1024 && d_in % 8 == 0) {
-        if (grid.x > 1024) return beta ? launch_xall<true, true, 2, 8>(d, grid, x_all_bytes, st) : launch_xall<false, true, 2, 8>(d, grid, x_all_bytes, st);
-        return beta ? launch_xall<true, true, 4, 8>(d, grid, x_all_bytes, st) : launch_xall<false, true, 4, 8>(d, grid, x_all_bytes, st);
-    }
-    // Two row groups per workgroup in that form, for tall layers of packed INT4 models (more than 512 workgroups
-    // of 32 rows): half as many copies of X, and the workgroups fit the CUs with the copy at two tokens as well
-    // (22016 x 8192: one token 25.8 -> 23.6 us = 0.60 of the HBM peak, two tokens 29.3 -> 25.5 us).  Without the
-    // copy two row groups measured slower with four-block register sets (three tokens 34.2 against 30.4 us, sixteen,
-    // staged per wave, 46.5 against 43.8; the staged form with two-block sets is the faster one, see below); on
-    // shorter or wider layers too (11008 rows 9.1 against 7.8 us).
-    const dim3 grid2((unsigned)(((d_out + 31) / 32 + 15) / 16 * 16));
-    const size_t per_cu2 = (grid2.x + 255) / 256;
-    const bool two_groups = grid2.x > 512 && x_all_bytes <= (size_t)kXAllBytes && per_cu2 * (x_all_bytes + 5 * 1024) <= 150 * 1024 &&
-                            d_in % 8 == 0;
-    // (8 x 8 blocks of an INT4 model: level at one token, 35.6 -> 29.8 us at two)
-    if (block_rows == 8 && int4 && two_groups)
-        return beta ? launch_xall<true, true, 2, 8, 2>(d, grid2, x_all_bytes, st) : launch_xall<false, true, 2, 8, 2>(d, grid2, x_all_bytes, st);
-    if (block_rows != 8 && regrouped && beta && tiled && two_groups) {
-        if (T == 1) return launch_xall<true, true, 2, 1, 2, 1>(d, grid2, x_all_bytes, st);
-        if (T == 2) return launch_xall<true, true, 2, 1, 2, 2>(d, grid2, x_all_bytes, st);
-        return launch_xall<true, true, 2, 1, 2>(d, grid2, x_all_bytes, st);
-    }
-    // Four row groups (64 rows, a copy of up to 66 KB, two workgroups per CU) where the copy would not fit otherwise:
-    // 22016 x 8192 at three / four tokens 30.4 -> 28.4 / 32.0 -> 29.6 us.  The kernel's limit of dynamic LDS is raised
-    // once (the initialisation of a function-local static is thread safe).
-    if (block_rows != 8 && regrouped && beta && tiled && d_in % 8 == 0 && x_all_bytes <= 66 * 1024) {
-        const dim3 grid4((unsigned)(((d_out + 63) / 64 + 15) / 16 * 16));
-        const size_t per_cu4 = (grid4.x + 255) / 256;
-        if (grid4.x > 256 && per_cu4 * (x_all_bytes + 5 * 1024) <= 150 * 1024) {
-            auto kern = k_w4_decode_xall<true, true, 2, 1, 4>;
-            static const hipError_t raised = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 66 * 1024);
-            if (raised != hipSuccess) return QBLORA_ERR_LAUNCH;
-            hipLaunchKernelGGL(kern, grid4, dim3(256), x_all_bytes, st, d);
-            return launch_status();
+
+    // ---- packed INT4 model in 64-blocks (table-free, codes regrouped by the pack) --------------------------------------
+    // Measured on 22016 x 8192 / 8192 x 22016 / 8192 x 8192 / 11008 x 4096, warm us (cold in brackets where it decides):
+    //   one token: the LDS-copy forms win (20.5 / 20.7 / 9.9 / 7.0 against 21.1 / 24.4 / 11.4 / 7.6 staged);
+    //   two and more: the staged forms (two tokens 20.9 / 24.2 / 11.2 / 7.6 against 22.0 / 25.4 / 10.9 / 7.5 -- level
+    //   warm, 1 us ahead cold; four tokens 20.8 / 25.8 / 11.8 / 7.8 against 25.3 / 28.5 / 12.9 / 8.7), except where the
+    //   eight-wave copy form applies (at most two workgroups per CU: 8192 x 8192 at two / three tokens 10.9 (12.9) /
+    //   11.9 (13.8) against 11.2 (13.9) / 11.8 (14.7)) and on layers with one workgroup per CU (4096 x 4096: 4.4 to
+    //   5.5 us against 5.3 to 5.8).
+    if (regrouped) {
+        if (per_cu <= 2 && x_all_fits(per_cu, kXAllBytesFew)) {
+            // eight waves per workgroup (8192 x 8192 at one token 11.1 -> 10.0 us, from HBM 13.7 -> 11.9; 8192 x 22016:
+            // 24.2 -> 20.8 and 30.2 -> 24.7 us; with two-block sets 10.4 / 12.7 and 21.7 / 27.1)
+            if (T == 1) return launch_xall<true, true, 4, 1, 1, 1, 8>(d, grid, x_all_bytes, st);
+            if (T == 2) return launch_xall<true, true, 4, 1, 1, 2, 8>(d, grid, x_all_bytes, st);
+            return launch_xall<true, true, 4, 1, 1, 4, 8>(d, grid, x_all_bytes, st);
         }
-    }
-    // (with at most two workgroups per CU a larger copy costs no residency: 8192 x 22016 at one token, 44 KB)
-    const size_t x_all_limit = per_cu <= 2 ? (size_t)kXAllBytesFew : (size_t)kXAllBytes;
-    if (block_rows != 8 && x_all_bytes <= x_all_limit && per_cu * (x_all_bytes + 5 * 1024) <= 150 * 1024 && d_in % 8 == 0) {
-        const bool small_sets = grid.x > 1024;      // more workgroups than fit at four waves per SIMD
-        if (regrouped) {
-            if (!beta || !tiled) return QBLORA_ERR_UNSUPPORTED;
-            // at most two workgroups per CU: eight waves each (8192 x 8192 at one token 11.1 -> 10.0 us, from HBM 13.7 ->
-            // 11.9; 8192 x 22016: 24.2 -> 20.8 and 30.2 -> 24.7 us; with two-block sets 10.4 / 12.7 and 21.7 / 27.1)
-            if (per_cu <= 2) {
-                if (T == 1) return launch_xall<true, true, 4, 1, 1, 1, 8>(d, grid, x_all_bytes, st);
-                if (T == 2) return launch_xall<true, true, 4, 1, 1, 2, 8>(d, grid, x_all_bytes, st);
-                return launch_xall<true, true, 4, 1, 1, 4, 8>(d, grid, x_all_bytes, st);
-            }
-            if (T == 1) return small_sets ? launch_xall<true, true, 2, 1, 1, 1>(d, grid, x_all_bytes, st) : launch_xall<true, true, 4, 1, 1, 1>(d, grid, x_all_bytes, st);
-            if (T == 2) return small_sets ? launch_xall<true, true, 2, 1, 1, 2>(d, grid, x_all_bytes, st) : launch_xall<true, true, 4, 1, 1, 2>(d, grid, x_all_bytes, st);
-            return small_sets ? launch_xall<true, true, 2>(d, grid, x_all_bytes, st) : launch_xall<true, true, 4>(d, grid, x_all_bytes, st);
+        if (T == 1) {
+            // tall layers: two row groups per workgroup, half as many copies of X (22016 x 8192: 25.8 -> 23.6 us before
+            // the changes to the loads, 20.5 now); otherwise two-block sets when there are more workgroups than the
+            // four-block form's 1024 slots
+            if (tall && x_all_fits(per_cu2, kXAllBytes)) return launch_xall<true, true, 2, 1, 2, 1>(d, grid2, x_all_bytes, st);
+            if (x_all_fits(per_cu, kXAllBytes))
+                return grid.x > 1024 ? launch_xall<true, true, 2, 1, 1, 1>(d, grid, x_all_bytes, st)
+                                     : launch_xall<true, true, 4, 1, 1, 1>(d, grid, x_all_bytes, st);
+            return grid.x > 768 ? launch(k_w4_decode<true, 1, true, 0, 2, 1, 1>, grid) : launch(k_w4_decode<true, 1, true, 0, 4, 1, 1>, grid);
         }
+        if (per_cu <= 1 && T <= 8) return launch(k_w4_decode<true, 1, true, 0>, grid);
+        // staged: two row groups and two-block sets on tall layers (22016 x 8192 at 8 / 16 tokens 22.8 / 24.7 us; with
+        // one row group and four-block sets 52 / 54 us before the staging was pipelined), else one and four
+        if (tall) return launch(k_w4_decode<true, 1, true, 1, 2, 2>, grid2);
+        return launch(k_w4_decode<true, 1, true, 1>, grid);
+    }
+
+    // ---- 8 x 8 blocks ----------------------------------------------------------------------------------------------
+    if (block_rows == 8) {
+        if (!int4) {                            // table of fp32 pairs: with the activation rows too it leaves two workgroups
+                                                // per CU, measured slower (68 vs 64 us at T = 16): the plain form only
+            return beta ? launch(k_w4_decode<true, 8, false, 0>, grid) : launch(k_w4_decode<false, 8, false, 0>, grid);
+        }
+        // INT4 model, one token: no table, all of X in LDS (22016 x 8192: 35.8 -> 28.2 us, with two row groups level;
+        // with at most two workgroups per CU the copy costs more than it saves: 4096 rows 6.3 against 5.9 us)
+        if (T == 1 && tall && x_all_fits(per_cu2, kXAllBytes))
+            return beta ? launch_xall<true, true, 2, 8, 2>(d, grid2, x_all_bytes, st) : launch_xall<false, true, 2, 8, 2>(d, grid2, x_all_bytes, st);
+        if (T == 1 && grid.x > 512 && x_all_fits(per_cu, kXAllBytes)) {
+            if (grid.x > 1024) return beta ? launch_xall<true, true, 2, 8>(d, grid, x_all_bytes, st) : launch_xall<false, true, 2, 8>(d, grid, x_all_bytes, st);
+            return beta ? launch_xall<true, true, 4, 8>(d, grid, x_all_bytes, st) : launch_xall<false, true, 4, 8>(d, grid, x_all_bytes, st);
+        }
+        // otherwise staged (22016 x 8192 at 2 / 4 / 8 / 16 tokens 26.4 / 26.5 / 27.9 / 30.8 us; 8192 x 8192 at one token
+        // 13.8 against 14.7 us plain), unless the layer has at most one workgroup per CU (4096 rows)
+        if (tall) return beta ? launch(k_w4_decode<true, 8, true, 1, 2, 2>, grid2) : launch(k_w4_decode<false, 8, true, 1, 2, 2>, grid2);
+        if (grid.x > 256) return beta ? launch(k_w4_decode<true, 8, true, 1>, grid) : launch(k_w4_decode<false, 8, true, 1>, grid);
+        return beta ? launch(k_w4_decode<true, 8, true, 0>, grid) : launch(k_w4_decode<false, 8, true, 0>, grid);
+    }
+
+    // ---- 64-blocks with a code table (any codebook; row-major or tile-ordered arrays) ------------------------------------
+    if (x_all_fits(per_cu, kXAllBytes)) {
+        const bool small_sets = grid.x > 1024;  // more workgroups than fit at four waves per SIMD
         if (beta) return small_sets ? launch_xall<true, false, 2>(d, grid, x_all_bytes, st) : launch_xall<true, false, 4>(d, grid, x_all_bytes, st);
         return small_sets ? launch_xall<false, false, 2>(d, grid, x_all_bytes, st) : launch_xall<false, false, 4>(d, grid, x_all_bytes, st);
     }
-    if (block_rows == 8) {                  // its fp32 pair table and the activation rows together leave two
-                                            // workgroups per CU: measured slower (68 vs 64 us at T = 16), not used
-        if (int4) {                         // (two-block register sets measured slower here: 38.3 against 35.8 us)
-            // tall layers: two row groups with staged two-block activation groups, as for the packed form below
-            // (22016 x 8192 at 3 / 4 / 8 / 16 tokens: 36 -> 34.8 / 38 -> 35.4 / 41.3 -> 37.4 / 46.3 -> 39.7 us)
-            if (grid2.x > 512 && T > kStagedPairMinTokens8) {
-                if (beta) hipLaunchKernelGGL((k_w4_decode<true, 8, true, 1, 2, 2>), grid2, dim3(256), 0, st, d);
-                else hipLaunchKernelGGL((k_w4_decode<false, 8, true, 1, 2, 2>), grid2, dim3(256), 0, st, d);
-                return launch_status();
-            }
-            // above 6 tokens the activations go through LDS as for 64-blocks (22016 x 8192 at 16 tokens: 61.6 -> 47.3 us),
-            // unless the layer has at most one workgroup per CU (4096 rows: 7.8 against 9.0 us)
-            if (grid.x > 256) {
-                const bool staged = T > 6;  // measured: level at 6 tokens, 45.3 -> 41.1 us at 8 (22016 x 8192)
-                auto go2 = [&](auto plain, auto st2) -> int {
-                    if (staged) hipLaunchKernelGGL(st2, grid, dim3(256), 0, st, d);
-                    else hipLaunchKernelGGL(plain, grid, dim3(256), 0, st, d);
-                    return launch_status();
-                };
-                if (beta) return go2(k_w4_decode<true, 8, true, 0>, k_w4_decode<true, 8, true, 1>);
-                return go2(k_w4_decode<false, 8, true, 0>, k_w4_decode<false, 8, true, 1>);
-            }
-            if (beta) return go(k_w4_decode<true, 8, true, 0>, k_w4_decode<true, 8, true, 0>);
-            return go(k_w4_decode<false, 8, true, 0>, k_w4_decode<false, 8, true, 0>);
-        }
-        if (beta) return go(k_w4_decode<true, 8, false, 0>, k_w4_decode<true, 8, false, 0>);
-        return go(k_w4_decode<false, 8, false, 0>, k_w4_decode<false, 8, false, 0>);
-    }
-    if (regrouped) {                        // codes regrouped by the pack: INT4 model with offsets, table-free
-        if (!beta || !tiled) return QBLORA_ERR_UNSUPPORTED;
-        // Tall layers (more than 512 workgroups of 32 rows), beyond the forms with the LDS copy: two row groups per
-        // workgroup with the activations staged per wave in two-block groups (136 registers).  22016 x 8192 at 12 / 16
-        // tokens 40.5 -> 32.6 / 43.6 -> 34.2 us, at 6 / 8 tokens 33.7 -> 31.7 / 38 -> 31.6 us; on shorter or wider layers
-        // slower (11008 rows 14.5 against 12.3 us), and so are four row groups (164 registers: 35.7 to 37.4 us).
-        if (grid2.x > 512 && T > kStagedPairMinTokens) {
-            hipLaunchKernelGGL((k_w4_decode<true, 1, true, 1, 2, 2>), grid2, dim3(256), 0, st, d);
-            return launch_status();
-        }
-        // more workgroups than fit at three waves per SIMD (156 registers): two-block register sets (92 registers, five
-        // waves; 22016 x 8192 at two tokens 29.9 -> 28.1 us)
-        if (!xlds && grid.x > 768) {
-            if (T == 1) return go(k_w4_decode<true, 1, true, 0, 2, 1, 1>, k_w4_decode<true, 1, true, 1>);
-            if (T == 2) return go(k_w4_decode<true, 1, true, 0, 2, 1, 2>, k_w4_decode<true, 1, true, 1>);
-            return go(k_w4_decode<true, 1, true, 0, 2>, k_w4_decode<true, 1, true, 1>);
-        }
-        // (eight waves per workgroup measured slower in these forms: 8192 x 8192 at four tokens 14.1 against 12.2 us)
-        if (T == 1) return go(k_w4_decode<true, 1, true, 0, 4, 1, 1>, k_w4_decode<true, 1, true, 1>);
-        if (T == 2) return go(k_w4_decode<true, 1, true, 0, 4, 1, 2>, k_w4_decode<true, 1, true, 1>);
-        return go(k_w4_decode<true, 1, true, 0>, k_w4_decode<true, 1, true, 1>);
-    }
-    if (beta) return go(k_w4_decode<true, 1, false, 0>, k_w4_decode<true, 1, false, 1>);
-    return go(k_w4_decode<false, 1, false, 0>, k_w4_decode<false, 1, false, 1>);
+    // above 8 tokens the activations go through LDS (with the table in LDS as well, two workgroups per CU: the staged
+    // form starts to pay later than in the table-free kernels -- 22016 x 8192 at 6 tokens 32.2 plain, 35.8 staged)
+    if (T > 8) return beta ? launch(k_w4_decode<true, 1, false, 1>, grid) : launch(k_w4_decode<false, 1, false, 1>, grid);
+    return beta ? launch(k_w4_decode<true, 1, false, 0>, grid) : launch(k_w4_decode<false, 1, false, 0>, grid);
 }
 
 }  // namespace qblora
