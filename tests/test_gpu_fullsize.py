@@ -165,12 +165,11 @@ def test_scale_operators_benchmark_shape(qb, oracle, codebook, op):
     assert_close_f32(dB, rB, "dB")
 
 
-def test_small_batch_inference_at_the_measured_shape(qb, oracle):
-    """The decode kernel on the 65B up-projection shape bench.py times among its side measurements (22016 x 8192, INT4 with offsets, tile-
-    ordered pack), T = 1, 2, 3, 7 and 16, and the mid-batch form at 32, 128 and 200 tokens: sampled output features against the oracle (a feature needs its own weight row only)."""
+def _inference_on_sampled_rows(qb, oracle, d_out, d_in, tokens, seed):
+    """Sampled output features of qblora_linear_decode on a packed INT4 model against the oracle (a feature needs its own
+    weight row only), with 64-blocks and with 8 x 8 blocks."""
     from gpu_util import f32_to_dev, bf16_to_dev, bf16_to_f64, bf16_half_ulp
-    d_out, d_in = 22016, 8192
-    rng = np.random.default_rng(4242)
+    rng = np.random.default_rng(seed)
     W = (rng.standard_normal((d_out, d_in), dtype=np.float32) * np.float32(0.02))
     rows = np.sort(rng.choice(d_out, 192, replace=False))
     cb = synth.codebook_int4()
@@ -191,7 +190,7 @@ def test_small_batch_inference_at_the_measured_shape(qb, oracle):
             Wt_mid = oracle.dequantize(c, a, b, cb, 64, 2)                # above 16 tokens: the bf16 compute weight
         sel_t = torch.from_numpy(sel).to(qw.codes.device)
         assert np.array_equal(qw.codes[sel_t].cpu().numpy(), c)          # the device weight holds the oracle's bits there
-        for T in (1, 2, 3, 7, 16, 32, 128, 200):                         # 1 .. 3: the forms with X in LDS; 32 ...: the mid-batch form, split over the inputs
+        for T in tokens:
             Xb = synth.f32_to_bf16_bits(rng.standard_normal((T, d_in), dtype=np.float32))
             Y = qb.qblora_linear_decode(qw, bf16_to_dev(Xb), pack=pack)
             torch.cuda.synchronize()
@@ -201,6 +200,20 @@ def test_small_batch_inference_at_the_measured_shape(qb, oracle):
             excess = np.abs(got - ref) - bf16_half_ulp(ref)
             assert excess.max() <= 1e-2 * rms, (block_rows, T, excess.max() / rms)
         del qw, pack
+
+
+def test_small_batch_inference_at_the_measured_shape(qb, oracle):
+    """The decode kernel on the 65B up-projection shape bench.py times among its side measurements (22016 x 8192, INT4 with
+    offsets, tile-ordered pack): one token (all of X in LDS, two row groups per workgroup), 2 .. 16 (activations staged per
+    wave, two row groups), and the mid-batch form at 32, 128 and 200 tokens."""
+    _inference_on_sampled_rows(qb, oracle, 22016, 8192, (1, 2, 3, 7, 16, 32, 128, 200), 4242)
+
+
+@pytest.mark.parametrize("d_out,d_in", [(8192, 22016), (8192, 8192)])
+def test_small_batch_inference_short_layers(qb, oracle, d_out, d_in):
+    """The 65B down and attention projections: at most two workgroups per CU, so the forms with eight waves per workgroup
+    (one token; up to three at 8192 inputs) and the staged form with one row group."""
+    _inference_on_sampled_rows(qb, oracle, d_out, d_in, (1, 2, 3, 4, 9, 16), 4243)
 
 
 def test_8x8_blocks_mlp_shapes_reduced_tokens(qb, oracle, codebook):
