@@ -9,7 +9,7 @@
 // are constant inside a 64-block, so they are applied to the block's partial sums, not to the weights,
 // and a code byte becomes two bf16 operand values with one LDS read.
 //
-// A workgroup of 4 waves (8 on layers with few rows) owns 16 output rows (32 or 64 on tall layers); the waves split
+// A workgroup of 4 waves (8 on layers with few rows) owns 16 output rows (32 on tall layers); the waves split
 // the input dimension (wave w takes the groups of 4 or 2 consecutive blocks j = w, w+4, ...) and add their partial
 // tiles through LDS at the end.
 // Inside a wave, lane l works on row (l & 15): for block b it loads 8 of the block's 32 code bytes
@@ -112,9 +112,9 @@ __device__ __forceinline__ void w4_decode(const DecodeDesc& d) {
     // entry e of replica q at e*kReplicas + q: bf16 pairs (4 bytes), or fp32 pairs (8 bytes) for BR = 8
     __shared__ __align__(8) uint32_t pair[DIRECT ? 2 : 256 * kReplicas * (BR == 8 ? 2 : 1)];
     __shared__ float red[NW][4][64];
-    // Activations of one group of 4 blocks (16 tokens x 512 bytes), one region per wave: fetched as whole
-    // 512-byte row segments (two token rows per load instruction) and read back in operand order.  A row is
-    // 528 bytes so that the 16 tokens of an operand read start 16 bytes apart modulo 256.
+    // Activations of one group of G blocks (16 tokens x 128 G bytes), one region per wave: fetched as whole
+    // row segments (two or four token rows per load instruction) and read back in operand order.  A row is
+    // 128 G + 16 bytes so that the 16 tokens of an operand read start 16 bytes apart modulo 256.
     constexpr int kXPitch = G * 128 + 16;
     constexpr int kLPR = 8 * G, kTPL = 64 / kLPR, kNX = 16 / kTPL;    // lanes per staged token row, token rows per load, loads
     constexpr int kXBufs = G <= 2 ? 2 : 1;                     // LDS buffers per wave (two: 35 KB per workgroup at G = 2)
