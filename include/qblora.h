@@ -361,7 +361,9 @@ int qblora_merge_bf16(const qblora_qweight* base, const float* H, int32_t lambda
  *   workspace: T <= 16: qblora_linear_decode_workspace_bytes() bytes (non-zero only for grouped scales, and
  *   not needed with a pack); T > 16: qblora_linear_decode_tokens_workspace_bytes(qw, T) bytes, 16-byte aligned
  *   (the former plus the partial tiles).
- * T = 0 is a no-op; T > 256 is QBLORA_ERR_SHAPE (use qblora_linear_fwd).
+ * T = 0 is a no-op; T > 256 is QBLORA_ERR_SHAPE (use qblora_linear_fwd).  With T <= 16 a weight whose codes take
+ * 2 GB or more (d_out rounded up to 256, times d_in / 2) is QBLORA_ERR_UNSUPPORTED: the kernel addresses them with
+ * 32-bit offsets.
  */
 size_t qblora_linear_decode_workspace_bytes(const qblora_qweight* qw);
 size_t qblora_linear_decode_tokens_workspace_bytes(const qblora_qweight* qw, int32_t T);
